@@ -1,0 +1,160 @@
+"""Benchmark: one "step" = one pass of the whole hot path (plan lookup, Image-halo and Filter staging, MFMA
+contraction, Out epilogue: one cacnn_conv_forward call) over one batch of synthetic input resident in HBM.
+
+Prints ONE JSON line.  metric/unit follow the benchmark definition (conv TFLOP/s on one MI355X); `roofline`
+prices the kernel against the MFMA peak of its dtype; `cpu_baseline` is the fp64 loop-nest oracle timed on the
+host in the same run; `shapes` carries the same measurements for all five benchmark shapes.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}      # MI355X published dense MFMA peaks
+HBM_PEAK_GBS = 8000.0
+LDS_BYTES = 160 * 1024
+
+
+def time_config(cc, torch, ci, np, cfg, steps, warmup, repeats=1):
+    """Average launch duration (seconds) of cacnn_conv_forward over `steps` back-to-back launches, measured with
+    events on the stream the kernel runs on (torch's current stream)."""
+    img, flt = ci.make_inputs(cfg)
+    if cfg.dtype == "bf16":
+        d_img = torch.from_numpy(ci.bf16_bits(img).view(np.int16).reshape(-1)).cuda()
+        d_flt = torch.from_numpy(ci.bf16_bits(flt).view(np.int16).reshape(-1)).cuda()
+    else:
+        d_img = torch.from_numpy(img.reshape(-1)).cuda()
+        d_flt = torch.from_numpy(flt.reshape(-1)).cuda()
+    d_out = torch.empty(int(np.prod(cfg.out_shape)), dtype=torch.float32, device="cuda:0")
+    dt = 0 if cfg.dtype == "f32" else 1
+    for _ in range(warmup):
+        cc.cacnn_conv_forward(cfg.dims, dt, d_img, d_flt, d_out)
+    torch.cuda.synchronize()
+    best = None
+    for _ in range(repeats):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            cc.cacnn_conv_forward(cfg.dims, dt, d_img, d_flt, d_out)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        ev = e0.elapsed_time(e1) * 1e-3
+        if best is None or ev < best[0]:
+            best = (ev, wall)
+    return best[0] / steps, best[1] / steps, (img, flt, d_out)
+
+
+def shape_report(cc, cfg, sec):
+    dt = 0 if cfg.dtype == "f32" else 1
+    esz = 4 if dt == 0 else 2
+    flops = 2.0 * cfg.macs
+    tflops = flops / sec / 1e12
+    plan = cc.cacnn_tile_plan(cfg.dims, dt)
+    n_img = 1
+    for x in cfg.image_shape:
+        n_img *= x
+    n_flt = cfg.K * cfg.R * cfg.S * cfg.C
+    n_out = cfg.K * cfg.H * cfg.W * cfg.B
+    compulsory = esz * (n_img + n_flt) + 4 * n_out
+    lb = cc.cacnn_lower_bound(cfg.dims, LDS_BYTES / esz)
+    lb_bytes = max(4 * lb.term[0], esz * max(lb.term[1:]))
+    return {
+        "us": sec * 1e6, "tflops": tflops, "frac_mfma_peak": tflops / MFMA_PEAK_TFLOPS[cfg.dtype],
+        "frac_hbm_roofline": compulsory / sec / 1e9 / HBM_PEAK_GBS,
+        "compulsory_bytes": compulsory, "paper_bound_bytes_at_M_lds": lb_bytes,
+        "planned_staged_bytes": esz * (plan.predicted_words - n_out) + 4 * n_out,
+        "variant": cc.cacnn_variant_name(plan.variant), "grid": plan.grid[0], "lds_bytes": plan.lds_bytes_used,
+        "b_c": plan.b_c,
+    }
+
+
+def cpu_baseline(cfg, img, flt, np):
+    """The oracle as it stands, all host threads, on the whole workload when that is a few seconds of CPU work,
+    otherwise on the first k output channels (the work per channel is identical)."""
+    from oracle import conv as oconv
+    threads = oconv.num_threads()
+    K = cfg.K
+    budget_macs = 40e9          # about 10-30 s on a few cores
+    k_use = max(1, min(K, int(K * budget_macs / cfg.macs)))
+    p = oconv.Problem(cfg.B, cfg.C, k_use, cfg.W, cfg.H, cfg.R, cfg.S, cfg.sigma_w, cfg.sigma_h)
+    sub = np.ascontiguousarray(flt[:k_use])
+    oconv.conv_fp64(oconv.Problem(cfg.B, cfg.C, 1, cfg.W, cfg.H, cfg.R, cfg.S, cfg.sigma_w, cfg.sigma_h), img,
+                    np.ascontiguousarray(flt[:1]))            # load the library, touch the inputs
+    t0 = time.perf_counter()
+    ref, ab = oconv.conv_fp64(p, img, sub)
+    dt = time.perf_counter() - t0
+    macs = cfg.macs * k_use / K
+    return {"value": 2.0 * macs / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"{cfg.name}: output channels 0..{k_use - 1} of {K} ({macs:.3g} MACs, fp64, {dt:.2f} s)"}, ref, ab, k_use
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-shapes", action="store_true", help="time only the headline workload")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards over b or k with no exchange step, "
+              "but no multi-GPU run is part of it); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import cacnn_inputs as ci
+    import paper_1802_06905_amd as cc      # raises if libcacnn.so is not built: no fallback
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    cfg = ci.CONFIGS[args.workload]
+    sec, wall, (img, flt, d_out) = time_config(cc, torch, ci, np, cfg, args.steps, args.warmup)
+    head = shape_report(cc, cfg, sec)
+
+    # parity of the timed launch against the oracle (also the cpu_baseline leg)
+    result = {
+        "metric": "conv TFLOP/s at 1 MI355X", "value": head["tflops"], "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype if cfg.dtype == "f32" else "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B} C={cfg.C} K={cfg.K} W=H={cfg.W} R=S={cfg.R} "
+                               f"sigma={cfg.sigma_w} {cfg.dtype} in, fp32 accumulate/out",
+                   "variant": head["variant"], "grid": head["grid"], "lds_bytes": head["lds_bytes"]},
+        "roofline": {"bound": "mfma", "achieved": head["tflops"], "peak": MFMA_PEAK_TFLOPS[cfg.dtype],
+                     "unit": "TFLOP/s", "frac": head["frac_mfma_peak"], "traffic": None,
+                     "wall_us_per_step": wall * 1e6},
+    }
+    if not args.no_cpu:
+        base, ref, ab, k_use = cpu_baseline(cfg, img, flt, np)
+        got = d_out.cpu().numpy().reshape(cfg.out_shape)[:k_use].astype(np.float64)
+        err = float(np.max(np.abs(got - ref) / np.maximum(ab, 1e-300)))
+        base["max_rel_err_gpu_vs_oracle"] = err
+        result["cpu_baseline"] = base
+    if not args.no_shapes:
+        shapes = {}
+        for name, c in ci.CONFIGS.items():
+            if name == cfg.name:
+                shapes[name] = head
+                continue
+            s, _, _ = time_config(cc, torch, ci, np, c, args.steps, args.warmup)
+            shapes[name] = shape_report(cc, c, s)
+        result["shapes"] = shapes
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

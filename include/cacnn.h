@@ -1,0 +1,164 @@
+/*
+ * cacnn -- communication-avoiding convolution for AMD MI355X (gfx950), C ABI.
+ *
+ * The library computes the seven-nested-loop convolution analysed in "Communication-Optimal Convolutional
+ * Neural Nets" (Demmel, Dinh; arXiv 1802.06905), evaluates the paper's lower bound on words moved, and plans
+ * the tiling it launches.  HBM plays the paper's slow memory; one compute unit's LDS (plus its register file)
+ * plays the cache of M words.
+ *
+ * Conventions shared by every entry point
+ *   - Problem parameters follow the paper's problem statement (Section 2): B images, C input channels,
+ *     K output channels, W x H OUTPUT extents, R x S filter extents (R pairs with w, S with h), strides
+ *     sigma_w, sigma_h.  F = B*C*K*W*H*R*S multiply-adds.
+ *   - Arrays are dense, row-major in the paper's index order, last index fastest:
+ *         Image  [IW][IH][C][B]   IW = sigma_w*(W-1)+R,  IH = sigma_h*(H-1)+S   (the touched extent; no padding)
+ *         Filter [K][R][S][C]
+ *         Out    [K][H][W][B]     always fp32
+ *     Note the transposition the paper itself has: Image's first axis pairs with (r, w), its second with
+ *     (s, h), while Out is indexed (k, h, w, b).
+ *   - Every function returns a cacnn_status (0 = success).  Nothing throws, aborts or prints.
+ *   - "words" are elements, as in the paper (it has a single word size).
+ */
+#ifndef CACNN_H
+#define CACNN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CACNN_OK = 0,
+    CACNN_ERR_NULL = 1,         /* a required pointer is NULL */
+    CACNN_ERR_INVALID_ARG = 2,  /* a dimension or stride < 1, M <= 1, a size that overflows the kernel's indexing */
+    CACNN_ERR_UNSUPPORTED = 3,  /* unknown dtype, unknown variant, plan that does not fit the machine */
+    CACNN_ERR_LAUNCH = 4,       /* the HIP runtime refused the launch */
+    CACNN_ERR_NO_DEVICE = 5     /* no usable GPU */
+} cacnn_status;
+
+/* Section 2 of the paper: the nine integers that define one convolution.  W and H are OUTPUT extents. */
+typedef struct {
+    int64_t B, C, K, W, H, R, S, sigma_w, sigma_h;
+} cacnn_problem;
+
+typedef enum {
+    CACNN_F32 = 0,         /* fp32 Image and Filter, fp32 multiply-accumulate (fp32 MFMA, no reduced-precision mode) */
+    CACNN_BF16_F32ACC = 1  /* bf16 Image and Filter (raw 16-bit patterns), fp32 accumulate (bf16 MFMA) */
+} cacnn_dtype;
+
+/* Theorem 1 (Section 4): the five terms, their maximum and which term it is (0-based, first of equals). */
+typedef struct {
+    double term[5];  /* BKWH, sw*sh*BCWH, CKRS, BCKWHRS/M, BCKWH*sqrt(RS*sw*sh/M) */
+    double bound;
+    int32_t argmax;
+} cacnn_bound;
+
+/* The fast memory a tile has to fit.  Passing NULL where one is accepted means the MI355X defaults
+ * (160 KiB LDS per compute unit, 512 KiB vector registers per compute unit, 256 compute units). */
+typedef struct {
+    int64_t lds_bytes;
+    int64_t vgpr_bytes_per_cu;
+    int64_t num_cu;
+} cacnn_machine;
+
+/* Result of planning.  The first block is the paper's own linear program (Section 5, the program over the
+ * logs of the nine tile sizes) solved at M = lds_bytes / input element size: it is prior art for an abstract
+ * machine and is reported for comparison.  The second block is the tiling the GPU kernel is launched with;
+ * it is re-derived for LDS capacity, the accumulator registers and MFMA fragment shapes. */
+typedef struct {
+    /* --- paper LP at M = LDS words; order b,c,k,w,h,r',r'',s',s'' (r = sigma_w*r' + r'', s likewise) --- */
+    double lp_tile[9];
+    double lp_volume;        /* G*: product of lp_tile */
+    double lp_cost_words;    /* F*M/G*  (Section 5.2) */
+    double bound_words;      /* Theorem 1 at the same M */
+    int32_t paper_case;      /* Appendix A leaf for strides 1: 11,16 = Cases 1.1,1.6; 1 = another Case-1 leaf;
+                                21, 221, 2221, 2222 = Cases 2.1 .. 2.2.2.2; 0 = strides are not both 1 */
+    /* --- tiling launched on the GPU --- */
+    int32_t variant;         /* index into the compiled kernel table, see cacnn_variant_name */
+    int32_t b_b, b_c, b_k, b_w, b_h;       /* tile of (b,c,k,w,h) held by one workgroup per contraction step */
+    int32_t b_r1, b_r2, b_s1, b_s2;        /* lifted filter tile: the kernel stages b_r = contiguous r range;
+                                              b_r2 = min(sigma_w, b_r), b_r1 = ceil(b_r / sigma_w) */
+    int32_t b_r, b_s;
+    int32_t grid[3];
+    int32_t block;           /* threads per workgroup */
+    int64_t lds_bytes_used;
+    double tile_volume;      /* b_b*b_c*b_k*b_w*b_h*b_r*b_s */
+    double predicted_words;  /* words this schedule moves between HBM/L2 and the compute units:
+                                staged Image halo tiles + staged Filter tiles + Out written once */
+} cacnn_plan;
+
+/*
+ * Theorem 1 (Section 4; also Section 1): lower bound on words moved between a slow memory and a cache of
+ * M_words words, for any execution order of the loop nest.  Host only; needs no GPU.
+ *   problem  in   host pointer
+ *   M_words  in   cache size in words, must be > 0
+ *   out      out  host pointer, caller-owned
+ * The constant hidden in the paper's Omega is taken as 1 and nothing is floored.  If a stride exceeds its
+ * filter extent (outside the paper's assumption sigma <= R) it is clamped to the extent in terms 2 and 5,
+ * since only touched Image elements count.
+ * Errors: CACNN_ERR_NULL; CACNN_ERR_INVALID_ARG for any parameter < 1 or M_words <= 0 (out untouched).
+ */
+int cacnn_lower_bound(const cacnn_problem* problem, double M_words, cacnn_bound* out);
+
+/*
+ * Section 5 (optimal tiling as a linear program) and Appendix A (case analysis), then the re-derivation for
+ * gfx950: chooses the kernel variant, the workgroup tile and the contraction tile that minimise a cost model
+ * of staged words and machine fill, subject to LDS bytes and accumulator registers.  Host only; needs no GPU.
+ *   problem  in   host pointer
+ *   dtype    in   cacnn_dtype
+ *   machine  in   host pointer or NULL for MI355X defaults
+ *   out      out  host pointer, caller-owned
+ * Several tilings reach the same optimal volume (Appendix A says so); only lp_volume / lp_cost_words are
+ * unique, lp_tile is one optimiser.
+ * Errors: CACNN_ERR_NULL, CACNN_ERR_INVALID_ARG (bad dimensions; machine->lds_bytes too small for any tile),
+ * CACNN_ERR_UNSUPPORTED (dtype).
+ */
+int cacnn_tile_plan(const cacnn_problem* problem, int dtype, const cacnn_machine* machine, cacnn_plan* out);
+
+/*
+ * Eq. (1) of the paper (Section 2): Out(k,h,w,b) = sum over c,r,s of
+ *     Image(r + sigma_w*w, s + sigma_h*h, c, b) * Filter(k,r,s,c),
+ * executed as the blocked schedule of Section 5 on the GPU: each workgroup owns one Out tile, walks the
+ * contraction (c, r, s) in tiles, stages the Image halo tile and the Filter tile in LDS and multiplies on MFMA.
+ *   problem  in   host pointer
+ *   dtype    in   cacnn_dtype
+ *   image    in   DEVICE pointer, IW*IH*C*B elements (fp32, or bf16 bit patterns), read-only
+ *   filter   in   DEVICE pointer, K*R*S*C elements, same element type as image, read-only
+ *   out      out  DEVICE pointer, K*H*W*B fp32; OVERWRITTEN with the full sum (the paper's += from zero);
+ *                 must not alias the inputs
+ *   hip_stream    hipStream_t cast to void*; NULL is the default stream
+ * The call enqueues work on the stream and returns; it never synchronises, allocates no device memory and
+ * keeps no reference to the buffers.  The caller owns all three buffers.  Pointers must be aligned to their
+ * element size; 16-byte alignment enables the vector paths.
+ * Parameters outside the paper's assumptions (sigma > R, R > sigma_w*W) are computed correctly.
+ * Errors: CACNN_ERR_NULL, CACNN_ERR_INVALID_ARG (dimension < 1, element counts beyond 2^31-1 per array),
+ * CACNN_ERR_UNSUPPORTED (dtype), CACNN_ERR_NO_DEVICE, CACNN_ERR_LAUNCH.  On error nothing is enqueued.
+ */
+int cacnn_conv_forward(const cacnn_problem* problem, int dtype, const void* image, const void* filter,
+                       void* out, void* hip_stream);
+
+/*
+ * Same computation as cacnn_conv_forward, launched with a caller-supplied plan instead of the planner's
+ * choice (Section 5: any admissible tiling computes the same sums; Appendix A: several are optimal).
+ * Only plan->variant, b_c, b_r, b_s are read; the workgroup tile is a property of the variant.  b_c is rounded
+ * up to the variant's contraction granularity.  Used by tests (every variant must agree with the oracle on
+ * every shape) and for tuning.
+ * Extra errors: CACNN_ERR_UNSUPPORTED if the variant does not exist, is for the other dtype, or the tile does
+ * not fit in LDS.
+ */
+int cacnn_conv_forward_with_plan(const cacnn_problem* problem, int dtype, const cacnn_plan* plan,
+                                 const void* image, const void* filter, void* out, void* hip_stream);
+
+/* Number of compiled kernel variants, and a static, NUL-terminated description of one
+ * ("f32 k64 b8w4h4 ..."); NULL if the index is out of range.  Host only. */
+int cacnn_variant_count(void);
+const char* cacnn_variant_name(int variant);
+
+/* Static, NUL-terminated text for a status code (never NULL). */
+const char* cacnn_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CACNN_H */

@@ -1,0 +1,157 @@
+"""ctypes binding with the same names as the C entry points declared in include/cacnn.h.
+
+The shared library must have been built in-tree (python -m paper_1802_06905_amd.build); importing this module without
+it raises: there is no CPU fallback.
+"""
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libcacnn.so")
+
+CACNN_F32 = 0
+CACNN_BF16_F32ACC = 1
+
+
+class CacnnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {cacnn_status_string(status)} (status {status})")
+
+
+class Problem(ctypes.Structure):
+    """cacnn_problem: B, C, K, W, H (output extents), R, S, sigma_w, sigma_h."""
+    _fields_ = [(n, ctypes.c_int64) for n in ("B", "C", "K", "W", "H", "R", "S", "sigma_w", "sigma_h")]
+
+    @property
+    def IW(self):
+        return self.sigma_w * (self.W - 1) + self.R
+
+    @property
+    def IH(self):
+        return self.sigma_h * (self.H - 1) + self.S
+
+
+class Bound(ctypes.Structure):
+    _fields_ = [("term", ctypes.c_double * 5), ("bound", ctypes.c_double), ("argmax", ctypes.c_int32)]
+
+
+class Machine(ctypes.Structure):
+    _fields_ = [("lds_bytes", ctypes.c_int64), ("vgpr_bytes_per_cu", ctypes.c_int64), ("num_cu", ctypes.c_int64)]
+
+
+class Plan(ctypes.Structure):
+    _fields_ = [
+        ("lp_tile", ctypes.c_double * 9), ("lp_volume", ctypes.c_double), ("lp_cost_words", ctypes.c_double),
+        ("bound_words", ctypes.c_double), ("paper_case", ctypes.c_int32),
+        ("variant", ctypes.c_int32),
+        ("b_b", ctypes.c_int32), ("b_c", ctypes.c_int32), ("b_k", ctypes.c_int32), ("b_w", ctypes.c_int32),
+        ("b_h", ctypes.c_int32),
+        ("b_r1", ctypes.c_int32), ("b_r2", ctypes.c_int32), ("b_s1", ctypes.c_int32), ("b_s2", ctypes.c_int32),
+        ("b_r", ctypes.c_int32), ("b_s", ctypes.c_int32),
+        ("grid", ctypes.c_int32 * 3), ("block", ctypes.c_int32),
+        ("lds_bytes_used", ctypes.c_int64),
+        ("tile_volume", ctypes.c_double), ("predicted_words", ctypes.c_double),
+    ]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_1802_06905_amd.build` "
+                      "(there is no CPU fallback)")
+
+_lib = ctypes.CDLL(_LIB_PATH)
+_lib.cacnn_lower_bound.restype = ctypes.c_int
+_lib.cacnn_lower_bound.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, ctypes.POINTER(Bound)]
+_lib.cacnn_tile_plan.restype = ctypes.c_int
+_lib.cacnn_tile_plan.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctypes.POINTER(Machine), ctypes.POINTER(Plan)]
+_lib.cacnn_conv_forward.restype = ctypes.c_int
+_lib.cacnn_conv_forward.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                    ctypes.c_void_p, ctypes.c_void_p]
+_lib.cacnn_conv_forward_with_plan.restype = ctypes.c_int
+_lib.cacnn_conv_forward_with_plan.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctypes.POINTER(Plan),
+                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.cacnn_variant_count.restype = ctypes.c_int
+_lib.cacnn_variant_name.restype = ctypes.c_char_p
+_lib.cacnn_variant_name.argtypes = [ctypes.c_int]
+_lib.cacnn_status_string.restype = ctypes.c_char_p
+_lib.cacnn_status_string.argtypes = [ctypes.c_int]
+
+
+def cacnn_status_string(status: int) -> str:
+    return _lib.cacnn_status_string(int(status)).decode()
+
+
+def cacnn_variant_count() -> int:
+    return int(_lib.cacnn_variant_count())
+
+
+def cacnn_variant_name(i: int) -> Optional[str]:
+    s = _lib.cacnn_variant_name(int(i))
+    return s.decode() if s is not None else None
+
+
+def _as_problem(problem) -> Problem:
+    if isinstance(problem, Problem):
+        return problem
+    return Problem(*[int(x) for x in problem])
+
+
+def cacnn_lower_bound(problem, M_words: float) -> Bound:
+    """Theorem 1's five terms and their maximum for a cache of M_words words (host only)."""
+    out = Bound()
+    rc = _lib.cacnn_lower_bound(ctypes.byref(_as_problem(problem)), float(M_words), ctypes.byref(out))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_lower_bound")
+    return out
+
+
+def cacnn_tile_plan(problem, dtype: int, machine: Optional[Machine] = None) -> Plan:
+    """The paper's tiling LP and the gfx950 tiling the kernel is launched with (host only)."""
+    out = Plan()
+    rc = _lib.cacnn_tile_plan(ctypes.byref(_as_problem(problem)), int(dtype),
+                              ctypes.byref(machine) if machine is not None else None, ctypes.byref(out))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_tile_plan")
+    return out
+
+
+def _ptr(t) -> int:
+    """Device address of a torch tensor (or a plain int address)."""
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda:
+        raise ValueError("cacnn_conv_forward takes device tensors")
+    if not t.is_contiguous():
+        raise ValueError("cacnn_conv_forward takes contiguous tensors")
+    return t.data_ptr()
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return stream
+    return int(stream.cuda_stream)
+
+
+def cacnn_conv_forward(problem, dtype: int, image, filt, out, stream=None) -> None:
+    """Enqueue Out = conv(Image, Filter) on `stream` (torch stream, raw handle, or None = torch's current stream).
+    image/filt/out are device tensors laid out Image[IW,IH,C,B], Filter[K,R,S,C], Out[K,H,W,B] (fp32)."""
+    rc = _lib.cacnn_conv_forward(ctypes.byref(_as_problem(problem)), int(dtype), _ptr(image), _ptr(filt), _ptr(out),
+                                 _stream_handle(stream))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_conv_forward")
+
+
+def cacnn_conv_forward_with_plan(problem, dtype: int, plan: Plan, image, filt, out, stream=None) -> None:
+    """Same as cacnn_conv_forward with a caller-chosen kernel variant and contraction tile."""
+    rc = _lib.cacnn_conv_forward_with_plan(ctypes.byref(_as_problem(problem)), int(dtype), ctypes.byref(plan),
+                                           _ptr(image), _ptr(filt), _ptr(out), _stream_handle(stream))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_conv_forward_with_plan")

@@ -1,0 +1,548 @@
+// Host side of the cacnn C ABI: Theorem 1's bound, the tiling linear program of Section 5, the Appendix A case
+// analysis, the gfx950 tile planner, argument validation and the launch dispatcher.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <limits>
+#include <mutex>
+#include <vector>
+
+#include "../../include/cacnn.h"
+#include "cacnn_internal.h"
+
+using namespace cacnn;
+
+namespace {
+
+const cacnn_machine kDefaultMachine = {160 * 1024, 512 * 1024, 256};
+
+bool valid_problem(const cacnn_problem* p) {
+    const int64_t v[9] = {p->B, p->C, p->K, p->W, p->H, p->R, p->S, p->sigma_w, p->sigma_h};
+    for (int64_t x : v)
+        if (x < 1) return false;
+    return true;
+}
+
+// product with overflow detection; returns false on overflow past lim
+bool mul_check(int64_t a, int64_t b, int64_t lim, int64_t* out) {
+    if (a != 0 && b > lim / a) return false;
+    *out = a * b;
+    return true;
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Section 5: the linear program over l_x = log_M(tile size of x), x in (b,c,k,w,h,r',r'',s',s'').
+// maximise sum l_x  s.t.  l >= 0, each tile within its loop bound, Out / Filter / Image footprints <= M, the Image
+// footprint (b_w + b_r')(b_h + b_s') being bounded term by term.  All right-hand sides are >= 0, so the slack basis
+// is feasible and a plain primal simplex (Bland's rule) suffices.
+struct LpSolution {
+    double l[9];
+    double log_volume;
+};
+
+LpSolution solve_tiling_lp(const cacnn_problem& p, double M) {
+    const int n = 9;
+    enum { b_, c_, k_, w_, h_, r1_, r2_, s1_, s2_ };
+    const double lnM = std::log(M);
+    auto lg = [&](double x) { return std::log(x) / lnM; };
+    const double sw = (double)std::min(p.sigma_w, p.R), sh = (double)std::min(p.sigma_h, p.S);
+
+    std::vector<std::vector<double>> A;
+    std::vector<double> rhs;
+    auto row = [&](std::initializer_list<int> vars, double r) {
+        std::vector<double> a(n, 0.0);
+        for (int v : vars) a[v] += 1.0;
+        A.push_back(a);
+        rhs.push_back(std::max(r, 0.0));
+    };
+    row({b_}, lg((double)p.B));
+    row({c_}, lg((double)p.C));
+    row({k_}, lg((double)p.K));
+    row({w_}, lg((double)p.W));
+    row({h_}, lg((double)p.H));
+    row({r2_}, lg(sw));
+    row({s2_}, lg(sh));
+    row({r1_}, lg((double)p.R) - lg(sw));
+    row({s1_}, lg((double)p.S) - lg(sh));
+    row({b_, k_, w_, h_}, 1.0);                    // Out tile
+    row({c_, k_, r1_, r2_, s1_, s2_}, 1.0);        // Filter tile
+    row({b_, c_, w_, h_, r2_, s2_}, 1.0);          // Image tile, four products
+    row({b_, c_, w_, s1_, r2_, s2_}, 1.0);
+    row({b_, c_, r1_, h_, r2_, s2_}, 1.0);
+    row({b_, c_, r1_, s1_, r2_, s2_}, 1.0);
+
+    const int m = (int)A.size();
+    // tableau: m rows x (n + m + 1) columns, objective row last; maximise sum x  <=>  reduced costs start at -1
+    const int cols = n + m + 1;
+    std::vector<std::vector<double>> T(m + 1, std::vector<double>(cols, 0.0));
+    std::vector<int> basis(m);
+    for (int i = 0; i < m; ++i) {
+        for (int jx = 0; jx < n; ++jx) T[i][jx] = A[i][jx];
+        T[i][n + i] = 1.0;
+        T[i][cols - 1] = rhs[i];
+        basis[i] = n + i;
+    }
+    for (int jx = 0; jx < n; ++jx) T[m][jx] = -1.0;
+    const double eps = 1e-12;
+    for (int iter = 0; iter < 10000; ++iter) {
+        int enter = -1;
+        for (int jx = 0; jx < n + m; ++jx)
+            if (T[m][jx] < -1e-10) {
+                enter = jx;  // Bland: lowest index
+                break;
+            }
+        if (enter < 0) break;
+        int leave = -1;
+        double best = 0.0;
+        for (int i = 0; i < m; ++i) {
+            if (T[i][enter] > eps) {
+                const double ratio = T[i][cols - 1] / T[i][enter];
+                if (leave < 0 || ratio < best - 1e-14 || (std::fabs(ratio - best) <= 1e-14 && basis[i] < basis[leave])) {
+                    leave = i;
+                    best = ratio;
+                }
+            }
+        }
+        if (leave < 0) break;  // unbounded: cannot happen, every variable is capped
+        const double piv = T[leave][enter];
+        for (int jx = 0; jx < cols; ++jx) T[leave][jx] /= piv;
+        for (int i = 0; i <= m; ++i) {
+            if (i == leave) continue;
+            const double f = T[i][enter];
+            if (f != 0.0)
+                for (int jx = 0; jx < cols; ++jx) T[i][jx] -= f * T[leave][jx];
+        }
+        basis[leave] = enter;
+    }
+    LpSolution s;
+    for (int jx = 0; jx < n; ++jx) s.l[jx] = 0.0;
+    for (int i = 0; i < m; ++i)
+        if (basis[i] < n) s.l[basis[i]] = std::max(0.0, T[i][cols - 1]);
+    s.log_volume = 0.0;
+    for (int jx = 0; jx < n; ++jx) s.log_volume += s.l[jx];
+    return s;
+}
+
+// Appendix A, Theorem 2 (strides 1): which leaf of the decision tree the shape falls in.
+int appendix_a_case(const cacnn_problem& p, double M) {
+    if (p.sigma_w != 1 || p.sigma_h != 1) return 0;
+    const double img = (double)p.C * p.H * p.W * p.B, flt = (double)p.K * p.C * p.R * p.S,
+                 out = (double)p.K * p.H * p.W * p.B;
+    if (std::min(img, std::min(flt, out)) <= M) {
+        if (img <= M && flt <= M && out <= M) return 11;
+        if (img > M && out > M && flt <= M) return 16;
+        return 1;
+    }
+    const double RS = (double)p.R * p.S, BHW = (double)p.B * p.H * p.W;
+    if (RS >= M) return 21;
+    if (M * RS >= BHW * BHW) return 221;
+    if ((double)std::min(p.C, p.K) >= std::sqrt(M / RS)) return 2221;
+    return 2222;
+}
+
+void bound_terms(const cacnn_problem& p, double M, cacnn_bound* out) {
+    const double sw = (double)std::min(p.sigma_w, p.R), sh = (double)std::min(p.sigma_h, p.S);
+    const double B = (double)p.B, C = (double)p.C, K = (double)p.K, W = (double)p.W, H = (double)p.H, R = (double)p.R,
+                 S = (double)p.S;
+    out->term[0] = B * K * W * H;
+    out->term[1] = sw * sh * B * C * W * H;
+    out->term[2] = C * K * R * S;
+    out->term[3] = B * C * K * W * H * R * S / M;
+    out->term[4] = B * C * K * W * H * std::sqrt(R * S * sw * sh / M);
+    out->argmax = 0;
+    for (int i = 1; i < 5; ++i)
+        if (out->term[i] > out->term[out->argmax]) out->argmax = i;
+    out->bound = out->term[out->argmax];
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// gfx950 tile geometry for one (variant, contraction tile)
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+struct Geometry {
+    int CT, bR, bS, XS, YS, xpitch, ypitch, fpitch, QE, img_lds_elems, zero_off;
+    int64_t lds_bytes;
+};
+
+Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int bR, int bS, bool vec_img) {
+    Geometry g;
+    g.CT = CT;
+    g.bR = bR;
+    g.bS = bS;
+    g.XS = (int)(p.sigma_w * (v.TW - 1) + bR);
+    g.YS = (int)(p.sigma_h * (v.TH - 1) + bS);
+    if (v.dtype == CACNN_F32) {
+        g.ypitch = CT * v.TB;
+        int base = g.YS * g.ypitch;
+        int pad = 0;
+        if (v.TB < 32) {
+            // spread the position groups of one MFMA column block over the 32 LDS banks: sigma_w * xpitch = TB (mod 32)
+            int best = -1;
+            for (int t = 0; t < 64; ++t) {
+                if (vec_img && ((base + t) % 4) != 0) continue;
+                if (best < 0) best = t;
+                if (((int64_t)p.sigma_w * (base + t)) % 32 == v.TB % 32) {
+                    best = t;
+                    break;
+                }
+            }
+            pad = best < 0 ? 0 : best;
+        }
+        g.xpitch = base + pad;
+        g.QE = bS * CT + ((bS * CT) & 1);
+        g.fpitch = bR * g.QE;
+        if ((g.fpitch & 1) == 0) g.fpitch += 1;  // odd pitch: the 32 rows of an A fragment hit 32 different banks
+        g.zero_off = g.XS * g.xpitch;
+        g.img_lds_elems = (int)round_up(g.zero_off + 64, 4);
+        g.lds_bytes = 4ll * (g.img_lds_elems + (int64_t)v.KT() * g.fpitch);
+    } else {
+        const int C8 = CT / 8;
+        g.ypitch = C8 * v.TB;           // 16-byte units
+        g.xpitch = g.YS * g.ypitch;
+        g.QE = 0;
+        int f8 = bR * bS * C8;          // Filter row in 16-byte units; odd count keeps 16-byte reads conflict-free
+        if ((f8 & 1) == 0) f8 += 1;
+        g.fpitch = f8 * 8;
+        g.zero_off = 0;
+        g.img_lds_elems = g.XS * g.xpitch;
+        g.lds_bytes = 16ll * g.img_lds_elems + 2ll * v.KT() * g.fpitch;
+    }
+    return g;
+}
+
+struct Choice {
+    int variant = -1;
+    Geometry g{};
+    double cost = 0.0;
+    int64_t n_wg = 0;
+    double words = 0.0;
+};
+
+// words staged from global memory by the whole grid for one variant/geometry, clipped to the arrays
+double staged_words(const VariantInfo& v, const cacnn_problem& p, const Geometry& g, double* image_words) {
+    const int64_t tiles_k = ceil_div(p.K, v.KT()), tiles_b = ceil_div(p.B, v.TB), tiles_w = ceil_div(p.W, v.TW),
+                  tiles_h = ceil_div(p.H, v.TH);
+    const int64_t IW = p.sigma_w * (p.W - 1) + p.R, IH = p.sigma_h * (p.H - 1) + p.S;
+    double sum_x = 0.0, sum_y = 0.0;
+    for (int64_t r0 = 0; r0 < p.R; r0 += g.bR)
+        for (int64_t tw = 0; tw < tiles_w; ++tw) {
+            const int64_t lo = p.sigma_w * tw * v.TW + r0;
+            sum_x += (double)std::max<int64_t>(0, std::min<int64_t>(IW, lo + g.XS) - lo);
+        }
+    for (int64_t s0 = 0; s0 < p.S; s0 += g.bS)
+        for (int64_t th = 0; th < tiles_h; ++th) {
+            const int64_t lo = p.sigma_h * th * v.TH + s0;
+            sum_y += (double)std::max<int64_t>(0, std::min<int64_t>(IH, lo + g.YS) - lo);
+        }
+    const double image = (double)tiles_k * sum_x * sum_y * (double)p.C * (double)p.B;
+    const double filter = (double)tiles_b * tiles_w * tiles_h * (double)p.K * p.R * p.S * p.C;
+    if (image_words) *image_words = image;
+    return image + filter;
+}
+
+bool vec_img_ok(const VariantInfo& v, const cacnn_problem& p) {
+    const int vi = v.dtype == CACNN_F32 ? 4 : 8;
+    return v.TB % vi == 0 && p.B % vi == 0;
+}
+
+// Cost model in CU cycles: MFMA issue time of one wavefront plus the staging time of the workgroup, times the
+// number of workgroups a compute unit has to run.  Staging overlaps MFMA only when two workgroups share a CU.
+bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice* best) {
+    const VariantInfo& v = variant(vi).info;
+    // fp32 slices in multiples of 4 channels keep the 16-byte Filter loads legal
+    const int gran = (v.dtype == CACNN_F32 && p.C % 4 == 0) ? 4 : v.cgran();
+    const int Cpad = (int)std::min<int64_t>(round_up(p.C, gran), 1 << 20);
+    // candidate contraction tiles: every even split of the (padded) channel range, and halvings of the s and r ranges
+    std::vector<int> cts;
+    for (int d = 1; d <= 64; ++d) {
+        const int ct = (int)round_up(ceil_div(Cpad, d), gran);
+        if (cts.empty() || cts.back() != ct) cts.push_back(ct);
+        if (ct == gran) break;
+    }
+    const bool vimg = vec_img_ok(v, p);
+    bool found = false;
+    const int64_t tiles_k = ceil_div(p.K, v.KT()), tiles_b = ceil_div(p.B, v.TB), tiles_w = ceil_div(p.W, v.TW),
+                  tiles_h = ceil_div(p.H, v.TH);
+    int64_t n_wg = 0, t = 0;
+    if (!mul_check(tiles_k, tiles_b, INT32_MAX, &t) || !mul_check(t, tiles_w, INT32_MAX, &t) ||
+        !mul_check(t, tiles_h, INT32_MAX, &n_wg))
+        return false;
+    const double ebytes = v.dtype == CACNN_F32 ? 4.0 : 2.0;
+    // global runs shorter than 32 bytes along b waste the rest of each 32-byte sector
+    const double run_bytes = (double)std::min<int64_t>(v.TB, p.B) * ebytes;
+    const double waste = std::max(1.0, 32.0 / run_bytes);
+    for (int bR = (int)std::min<int64_t>(p.R, 1 << 12); bR >= 1; bR = (bR + 1) / 2 == bR ? 0 : (bR + 1) / 2) {
+        for (int bS = (int)std::min<int64_t>(p.S, 1 << 12); bS >= 1; bS = (bS + 1) / 2 == bS ? 0 : (bS + 1) / 2) {
+            for (int ct : cts) {
+                const Geometry g = make_geometry(v, p, ct, bR, bS, vimg);
+                if (g.lds_bytes > mach.lds_bytes) continue;
+                double img_words = 0.0;
+                const double words = staged_words(v, p, g, &img_words);
+                const double ksteps = v.dtype == CACNN_F32 ? (double)p.R * ceil_div((int64_t)p.S * Cpad, 2)
+                                                           : (double)p.R * p.S * (Cpad / 16);
+                const double mfma_cyc = (v.dtype == CACNN_F32 ? 64.0 : 32.0) * v.MBLK * v.NBLK * ksteps;
+                const double stage_cyc =
+                    (img_words * waste + (words - img_words)) * ebytes / (double)n_wg / 32.0;  // ~32 B/clk/CU
+                const double epi_cyc = (double)v.KT() * v.NT() * 4.0 / 64.0 * waste;
+                const double n_ctiles = (double)ceil_div(p.R, bR) * ceil_div(p.S, bS) * ceil_div(Cpad, ct);
+                const double latency_cyc = 2500.0 * n_ctiles;   // exposed load latency + two barriers per tile
+                const int resident = g.lds_bytes * 2 <= mach.lds_bytes ? 2 : 1;
+                const double hide = resident >= 2 ? 0.4 : 1.0;
+                const double per_wg = mfma_cyc + hide * (stage_cyc + epi_cyc + latency_cyc) + 1500.0;
+                const double per_cu = (double)ceil_div(n_wg, mach.num_cu);
+                const double cost = per_cu * per_wg;
+                if (best->variant < 0 || cost < best->cost) {
+                    best->variant = vi;
+                    best->g = g;
+                    best->cost = cost;
+                    best->n_wg = n_wg;
+                    best->words = words;
+                }
+                found = true;
+            }
+        }
+    }
+    return found;
+}
+
+int fill_plan(const cacnn_problem& p, int dtype, const cacnn_machine& mach, const Choice& ch, cacnn_plan* out) {
+    const VariantInfo& v = variant(ch.variant).info;
+    const double esz = dtype == CACNN_F32 ? 4.0 : 2.0;
+    const double M = (double)mach.lds_bytes / esz;
+    std::memset(out, 0, sizeof(*out));
+    if (M > 1.0) {
+        const LpSolution s = solve_tiling_lp(p, M);
+        for (int i = 0; i < 9; ++i) out->lp_tile[i] = std::pow(M, s.l[i]);
+        out->lp_volume = std::pow(M, s.log_volume);
+        const double F = (double)p.B * p.C * p.K * p.W * p.H * p.R * p.S;
+        out->lp_cost_words = F * M / out->lp_volume;
+        cacnn_bound b;
+        bound_terms(p, M, &b);
+        out->bound_words = b.bound;
+        out->paper_case = appendix_a_case(p, M);
+    }
+    out->variant = ch.variant;
+    out->b_b = v.TB;
+    out->b_c = ch.g.CT;
+    out->b_k = v.KT();
+    out->b_w = v.TW;
+    out->b_h = v.TH;
+    out->b_r = ch.g.bR;
+    out->b_s = ch.g.bS;
+    out->b_r2 = (int32_t)std::min<int64_t>(p.sigma_w, ch.g.bR);
+    out->b_r1 = (int32_t)ceil_div(ch.g.bR, std::max<int64_t>(1, std::min<int64_t>(p.sigma_w, p.R)));
+    out->b_s2 = (int32_t)std::min<int64_t>(p.sigma_h, ch.g.bS);
+    out->b_s1 = (int32_t)ceil_div(ch.g.bS, std::max<int64_t>(1, std::min<int64_t>(p.sigma_h, p.S)));
+    out->grid[0] = (int32_t)ch.n_wg;
+    out->grid[1] = 1;
+    out->grid[2] = 1;
+    out->block = v.threads();
+    out->lds_bytes_used = ch.g.lds_bytes;
+    out->tile_volume = (double)v.TB * ch.g.CT * v.KT() * v.TW * v.TH * ch.g.bR * ch.g.bS;
+    out->predicted_words = ch.words + (double)p.K * p.H * p.W * p.B;
+    return CACNN_OK;
+}
+
+int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, cacnn_plan* out) {
+    if (!p || !out) return CACNN_ERR_NULL;
+    if (!valid_problem(p)) return CACNN_ERR_INVALID_ARG;
+    if (dtype != CACNN_F32 && dtype != CACNN_BF16_F32ACC) return CACNN_ERR_UNSUPPORTED;
+    cacnn_machine mach = machine ? *machine : kDefaultMachine;
+    if (mach.lds_bytes < 1024 || mach.num_cu < 1) return CACNN_ERR_INVALID_ARG;
+    mach.lds_bytes = std::min<int64_t>(mach.lds_bytes, 160 * 1024);  // the kernels cannot address more
+    // per-array element counts must fit the kernels' 31-bit tile arithmetic
+    const int64_t IW = p->sigma_w * (p->W - 1) + p->R, IH = p->sigma_h * (p->H - 1) + p->S;
+    int64_t t;
+    const int64_t lim = INT32_MAX;
+    if (p->sigma_w > lim || p->sigma_h > lim || p->W > lim || p->H > lim || p->R > lim || p->S > lim ||
+        IW > lim || IH > lim || IW < 1 || IH < 1)
+        return CACNN_ERR_INVALID_ARG;
+    if (!mul_check(IW, IH, lim, &t) || !mul_check(t, p->C, lim, &t) || !mul_check(t, p->B, lim, &t))
+        return CACNN_ERR_INVALID_ARG;
+    if (!mul_check(p->K, p->R, lim, &t) || !mul_check(t, p->S, lim, &t) || !mul_check(t, p->C, lim, &t))
+        return CACNN_ERR_INVALID_ARG;
+    if (!mul_check(p->K, p->H, lim, &t) || !mul_check(t, p->W, lim, &t) || !mul_check(t, p->B, lim, &t))
+        return CACNN_ERR_INVALID_ARG;
+    Choice best;
+    for (int vi = 0; vi < num_variants(); ++vi) {
+        if (variant(vi).info.dtype != dtype) continue;
+        evaluate(vi, *p, mach, &best);
+    }
+    if (best.variant < 0) return CACNN_ERR_INVALID_ARG;  // nothing fits the given LDS size
+    return fill_plan(*p, dtype, mach, best, out);
+}
+
+bool g_device_checked = false;
+bool g_device_ok = false;
+std::mutex g_mutex;
+
+bool have_device() {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (!g_device_checked) {
+        int n = 0;
+        const hipError_t e = hipGetDeviceCount(&n);
+        if (e != hipSuccess) (void)hipGetLastError();
+        g_device_ok = (e == hipSuccess && n > 0);
+        g_device_checked = true;
+    }
+    return g_device_ok;
+}
+
+int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int bS, const void* image,
+                const void* filter, void* out, void* stream) {
+    const Variant& var = variant(vi);
+    const VariantInfo& v = var.info;
+    const bool aligned_img = (reinterpret_cast<uintptr_t>(image) % 16) == 0;
+    const bool aligned_flt = (reinterpret_cast<uintptr_t>(filter) % 16) == 0;
+    const size_t esz = dtype == CACNN_F32 ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(image) % esz || reinterpret_cast<uintptr_t>(filter) % esz ||
+        reinterpret_cast<uintptr_t>(out) % 4)
+        return CACNN_ERR_INVALID_ARG;
+    const bool vimg = vec_img_ok(v, p) && aligned_img;
+    const Geometry g = make_geometry(v, p, CT, bR, bS, vimg);
+    if (g.lds_bytes > 160 * 1024) return CACNN_ERR_UNSUPPORTED;
+
+    KernelArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.image = image;
+    a.filter = filter;
+    a.out = (float*)out;
+    a.B = (int32_t)p.B;
+    a.C = (int32_t)p.C;
+    a.K = (int32_t)p.K;
+    a.W = (int32_t)p.W;
+    a.H = (int32_t)p.H;
+    a.R = (int32_t)p.R;
+    a.S = (int32_t)p.S;
+    a.sw = (int32_t)p.sigma_w;
+    a.sh = (int32_t)p.sigma_h;
+    a.IW = (int32_t)(p.sigma_w * (p.W - 1) + p.R);
+    a.IH = (int32_t)(p.sigma_h * (p.H - 1) + p.S);
+    a.bR = g.bR;
+    a.bS = g.bS;
+    a.CT = g.CT;
+    a.XS = g.XS;
+    a.YS = g.YS;
+    a.xpitch = g.xpitch;
+    a.ypitch = g.ypitch;
+    a.fpitch = g.fpitch;
+    a.QE = g.QE;
+    a.img_lds_elems = g.img_lds_elems;
+    a.zero_off = g.zero_off;
+    a.tiles_k = (int32_t)ceil_div(p.K, v.KT());
+    a.tiles_b = (int32_t)ceil_div(p.B, v.TB);
+    a.tiles_w = (int32_t)ceil_div(p.W, v.TW);
+    a.tiles_h = (int32_t)ceil_div(p.H, v.TH);
+    a.vec_img = vimg ? 1 : 0;
+    if (dtype == CACNN_F32)
+        a.vec_flt = (aligned_flt && p.C % 4 == 0 && g.CT % 4 == 0) ? 1 : 0;
+    else
+        a.vec_flt = (aligned_flt && p.C % 8 == 0) ? 1 : 0;
+    a.d_CT = make_fastdiv((uint32_t)g.CT);
+    a.d_YS = make_fastdiv((uint32_t)g.YS);
+    a.d_bS = make_fastdiv((uint32_t)g.bS);
+    a.d_bR = make_fastdiv((uint32_t)g.bR);
+    a.d_RS = make_fastdiv((uint32_t)(g.bR * g.bS));
+    if (dtype == CACNN_F32)
+        a.d_C8 = make_fastdiv((uint32_t)(a.vec_flt ? g.CT / 4 : g.CT));
+    else
+        a.d_C8 = make_fastdiv((uint32_t)(g.CT / 8));
+    int64_t grid = 0, t = 0;
+    if (!mul_check(a.tiles_k, a.tiles_b, INT32_MAX, &t) || !mul_check(t, a.tiles_w, INT32_MAX, &t) ||
+        !mul_check(t, a.tiles_h, INT32_MAX, &grid))
+        return CACNN_ERR_INVALID_ARG;
+    if (!have_device()) return CACNN_ERR_NO_DEVICE;
+    return var.launch(a, (int)grid, (size_t)g.lds_bytes, stream) == 0 ? CACNN_OK : CACNN_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cacnn_lower_bound(const cacnn_problem* problem, double M_words, cacnn_bound* out) {
+    if (!problem || !out) return CACNN_ERR_NULL;
+    if (!valid_problem(problem) || !(M_words > 0.0) || !std::isfinite(M_words)) return CACNN_ERR_INVALID_ARG;
+    bound_terms(*problem, M_words, out);
+    return CACNN_OK;
+}
+
+int cacnn_tile_plan(const cacnn_problem* problem, int dtype, const cacnn_machine* machine, cacnn_plan* out) {
+    return plan_impl(problem, dtype, machine, out);
+}
+
+int cacnn_conv_forward(const cacnn_problem* problem, int dtype, const void* image, const void* filter, void* out,
+                       void* hip_stream) {
+    if (!problem || !image || !filter || !out) return CACNN_ERR_NULL;
+    if (dtype != CACNN_F32 && dtype != CACNN_BF16_F32ACC) return CACNN_ERR_UNSUPPORTED;
+    // plans are cached per (problem, dtype): planning costs tens of microseconds, a launch a few
+    struct Entry {
+        cacnn_problem p;
+        int dtype;
+        cacnn_plan plan;
+    };
+    static std::vector<Entry> cache;
+    cacnn_plan plan;
+    bool hit = false;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        for (const Entry& e : cache)
+            if (e.dtype == dtype && std::memcmp(&e.p, problem, sizeof(cacnn_problem)) == 0) {
+                plan = e.plan;
+                hit = true;
+                break;
+            }
+    }
+    if (!hit) {
+        const int rc = plan_impl(problem, dtype, nullptr, &plan);
+        if (rc != CACNN_OK) return rc;
+        std::lock_guard<std::mutex> lock(g_mutex);
+        if (cache.size() >= 64) cache.erase(cache.begin());
+        cache.push_back(Entry{*problem, dtype, plan});
+    }
+    return launch_with(*problem, dtype, plan.variant, plan.b_c, plan.b_r, plan.b_s, image, filter, out, hip_stream);
+}
+
+int cacnn_conv_forward_with_plan(const cacnn_problem* problem, int dtype, const cacnn_plan* plan, const void* image,
+                                 const void* filter, void* out, void* hip_stream) {
+    if (!problem || !plan || !image || !filter || !out) return CACNN_ERR_NULL;
+    if (dtype != CACNN_F32 && dtype != CACNN_BF16_F32ACC) return CACNN_ERR_UNSUPPORTED;
+    // same dimension checks as the planner
+    cacnn_plan scratch;
+    const int rc = plan_impl(problem, dtype, nullptr, &scratch);
+    if (rc != CACNN_OK) return rc;
+    if (plan->variant < 0 || plan->variant >= num_variants()) return CACNN_ERR_UNSUPPORTED;
+    const VariantInfo& v = variant(plan->variant).info;
+    if (v.dtype != dtype) return CACNN_ERR_UNSUPPORTED;
+    if (plan->b_c < 1 || plan->b_r < 1 || plan->b_s < 1) return CACNN_ERR_INVALID_ARG;
+    const int64_t Cpad = round_up(problem->C, v.cgran());
+    const int CT = (int)std::min<int64_t>(round_up(plan->b_c, v.cgran()), Cpad);
+    const int bR = (int)std::min<int64_t>(plan->b_r, problem->R);
+    const int bS = (int)std::min<int64_t>(plan->b_s, problem->S);
+    return launch_with(*problem, dtype, plan->variant, CT, bR, bS, image, filter, out, hip_stream);
+}
+
+int cacnn_variant_count(void) { return num_variants(); }
+
+const char* cacnn_variant_name(int i) {
+    if (i < 0 || i >= num_variants()) return nullptr;
+    return variant(i).info.name;
+}
+
+const char* cacnn_status_string(int status) {
+    switch (status) {
+        case CACNN_OK: return "ok";
+        case CACNN_ERR_NULL: return "null pointer argument";
+        case CACNN_ERR_INVALID_ARG: return "invalid argument";
+        case CACNN_ERR_UNSUPPORTED: return "unsupported dtype, variant or plan";
+        case CACNN_ERR_LAUNCH: return "kernel launch failed";
+        case CACNN_ERR_NO_DEVICE: return "no usable GPU";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

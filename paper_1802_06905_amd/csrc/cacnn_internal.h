@@ -1,0 +1,67 @@
+// Internal interface between the host planner/dispatcher (cacnn_host.cpp) and the gfx950 kernels
+// (cacnn_kernels.hip).  Not part of the public ABI.
+#ifndef CACNN_INTERNAL_H
+#define CACNN_INTERNAL_H
+
+#include <stdint.h>
+
+namespace cacnn {
+
+// Division of small unsigned numbers by a run-time constant with one multiply-high.
+// Exact for n * d < 2^32 (the staged-tile indices it is used on are bounded by the LDS size).
+struct FastDiv {
+    uint32_t mul;  // floor(2^32 / d) + 1, or 0 when d == 1
+    uint32_t d;
+};
+
+inline FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f;
+    f.d = d;
+    f.mul = (d <= 1) ? 0u : (uint32_t)((0x100000000ull / d) + 1ull);
+    return f;
+}
+
+// Geometry of one compiled kernel variant: the workgroup's Out tile is KT output channels by a position tile of
+// TB images x TW output columns x TH output rows, flattened as n = (h_l*TW + w_l)*TB + b_l and cut into MFMA
+// column blocks of 32.  WM x WN wavefronts; each owns MBLK x NBLK MFMA tiles of 32x32.
+struct VariantInfo {
+    const char* name;
+    int dtype;  // cacnn_dtype
+    int WM, WN, MBLK, NBLK, TB, TW, TH;
+    int KT() const { return WM * MBLK * 32; }
+    int NT() const { return TB * TW * TH; }
+    int threads() const { return WM * WN * 64; }
+    int cgran() const { return dtype == 0 ? 1 : 16; }  // contraction granularity of the c-slice
+};
+
+// Everything a kernel needs, passed by value.
+struct KernelArgs {
+    const void* image;
+    const void* filter;
+    float* out;
+    int32_t B, C, K, W, H, R, S, sw, sh, IW, IH;
+    int32_t bR, bS, CT;       // contraction tile: r-range, s-range, c-slice (CT multiple of cgran)
+    int32_t XS, YS;           // staged Image extents: sw*(TW-1)+bR, sh*(TH-1)+bS
+    int32_t xpitch, ypitch;   // LDS pitches of the staged Image tile (fp32: floats; bf16: 16-byte units)
+    int32_t fpitch;           // LDS pitch of one Filter row (one k), in elements
+    int32_t QE;               // fp32: per-r contraction length bS*CT rounded up to even
+    int32_t img_lds_elems;    // fp32: floats before the Filter tile; bf16: 16-byte units before it
+    int32_t zero_off;         // fp32: offset (floats) of a zeroed row of 64 floats inside the Image region
+    int32_t tiles_k, tiles_b, tiles_w, tiles_h;
+    int32_t vec_img, vec_flt; // 1 = 16-byte global loads are legal for this operand
+    FastDiv d_CT, d_YS, d_bS, d_bR, d_C8, d_RS;
+};
+
+typedef int (*LaunchFn)(const KernelArgs& a, int grid, size_t lds_bytes, void* stream);
+
+struct Variant {
+    VariantInfo info;
+    LaunchFn launch;
+};
+
+// Defined in cacnn_kernels.hip.
+int num_variants();
+const Variant& variant(int i);
+
+}  // namespace cacnn
+#endif

@@ -1,0 +1,530 @@
+// gfx950 (CDNA4) kernels for the blocked convolution schedule.
+//
+// One workgroup owns one Out tile (b_k output channels x a position tile of b_b images x b_w columns x b_h rows) and
+// walks the contraction (c, r, s) in tiles, as in the blocked loop nest of Section 5 of the paper: the outer loops
+// over (c, r', s') tiles are the kernel's main loop, the inner loops are the MFMA sweep.  Per contraction tile the
+// Image halo tile (Section 5, item 3: its w-extent is sigma_w*(b_w-1)+b_r) and the Filter tile are staged from global
+// memory into LDS; the Out tile stays in accumulator registers for the whole contraction, so each Out word is
+// written exactly once and partial sums never travel (Theorem 1's first term is met with equality).
+//
+// MFMA mapping: rows (M) = output channels k, columns (N) = positions (b fastest, as in memory), contraction = (c,r,s).
+//   fp32 : v_mfma_f32_32x32x2_f32,   A[i][kk] lane = i + 32*kk,          B[kk][j] lane = j + 32*kk
+//   bf16 : v_mfma_f32_32x32x16_bf16, A[i][8g..8g+7] lane = i + 32*g,     B[8g..8g+7][j] lane = j + 32*g
+//   D    : lane = j + 32*q holds rows 8*(v/4) + 4*q + (v%4), v = 0..15, of column j
+// Every staged Image word is reused for all b_k channels and for every (r,s) shift that touches it -- the extra
+// (RS/sigma_w sigma_h)^(1/2) reuse over matmul that the small-filter bound of Section 4.3 expresses.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cacnn_internal.h"
+
+namespace cacnn {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv& f) {
+    return f.mul ? __umulhi(n, f.mul) : n;
+}
+
+struct TileCoord {
+    int k0, b0, w0, h0;
+};
+
+__device__ __forceinline__ TileCoord decode_tile(const KernelArgs& a, int KT, int TB, int TW, int TH) {
+    int t = blockIdx.x;
+    const int tk = t % a.tiles_k;
+    t /= a.tiles_k;
+    const int tb = t % a.tiles_b;
+    t /= a.tiles_b;
+    const int tw = t % a.tiles_w;
+    const int th = t / a.tiles_w;
+    TileCoord tc;
+    tc.k0 = tk * KT;
+    tc.b0 = tb * TB;
+    tc.w0 = tw * TW;
+    tc.h0 = th * TH;
+    return tc;
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// fp32
+// LDS: s_img[x*xpitch + (y*CT + c)*TB + b]  (+ a zeroed row at zero_off),  s_flt[k_l*fpitch + r*QE + s*CT + c]
+// The contraction over (s,c) for a fixed r is one contiguous run of Q = bS*CT rows in both tiles.
+
+template <int THREADS, int TB, int VI>
+__device__ __forceinline__ void stage_image_f32(const KernelArgs& a, float* s_img, int tid, int x0, int y0, int c0,
+                                                int b0) {
+    constexpr int VPR = TB / VI;
+    constexpr int U = 4;
+    const int total = a.XS * a.YS * a.CT * VPR;
+    const float* __restrict__ img = (const float*)a.image;
+    for (int base = tid; base < total; base += THREADS * U) {
+        float v[U][VI];
+        int off[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int idx = base + u * THREADS;
+            off[u] = -1;
+#pragma unroll
+            for (int e = 0; e < VI; ++e) v[u][e] = 0.f;
+            if (idx < total) {
+                const uint32_t row = (uint32_t)idx / VPR;
+                const int bv = idx % VPR;
+                const uint32_t t = fdiv(row, a.d_CT);
+                const int c = row - t * a.CT;
+                const uint32_t x = fdiv(t, a.d_YS);
+                const int y = t - x * a.YS;
+                const int gx = x0 + (int)x, gy = y0 + y, gc = c0 + c, gb = b0 + bv * VI;
+                off[u] = (int)x * a.xpitch + (y * a.CT + c) * TB + bv * VI;
+                if (gx < a.IW && gy < a.IH && gc < a.C && gb < a.B) {
+                    const int64_t g = (((int64_t)gx * a.IH + gy) * a.C + gc) * a.B + gb;
+                    if constexpr (VI == 4) {
+                        const f32x4 q = *(const f32x4*)(img + g);
+                        v[u][0] = q[0];
+                        v[u][1] = q[1];
+                        v[u][2] = q[2];
+                        v[u][3] = q[3];
+                    } else {
+                        v[u][0] = img[g];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (off[u] >= 0) {
+                if constexpr (VI == 4) {
+                    f32x4 q = {v[u][0], v[u][1], v[u][2], v[u][3]};
+                    *(f32x4*)(s_img + off[u]) = q;
+                } else {
+                    s_img[off[u]] = v[u][0];
+                }
+            }
+        }
+    }
+}
+
+template <int THREADS, int KT, int VF>
+__device__ __forceinline__ void stage_filter_f32(const KernelArgs& a, float* s_flt, int tid, int k0, int r0, int s0,
+                                                 int c0) {
+    constexpr int U = 4;
+    const int CTV = a.CT / VF;
+    const int total = KT * a.bR * a.bS * CTV;
+    const float* __restrict__ flt = (const float*)a.filter;
+    for (int base = tid; base < total; base += THREADS * U) {
+        float v[U][VF];
+        int off[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int idx = base + u * THREADS;
+            off[u] = -1;
+#pragma unroll
+            for (int e = 0; e < VF; ++e) v[u][e] = 0.f;
+            if (idx < total) {
+                uint32_t t = fdiv((uint32_t)idx, a.d_C8);
+                const int c = (idx - t * CTV) * VF;
+                uint32_t t2 = fdiv(t, a.d_bS);
+                const int s = t - t2 * a.bS;
+                const uint32_t kl = fdiv(t2, a.d_bR);
+                const int r = t2 - kl * a.bR;
+                const int gk = k0 + (int)kl, gr = r0 + r, gs = s0 + s, gc = c0 + c;
+                off[u] = (int)kl * a.fpitch + r * a.QE + s * a.CT + c;
+                if (gk < a.K && gr < a.R && gs < a.S && gc < a.C) {
+                    const int64_t g = (((int64_t)gk * a.R + gr) * a.S + gs) * a.C + gc;
+                    if constexpr (VF == 4) {
+                        const f32x4 q = *(const f32x4*)(flt + g);
+                        v[u][0] = q[0];
+                        v[u][1] = q[1];
+                        v[u][2] = q[2];
+                        v[u][3] = q[3];
+                    } else {
+                        v[u][0] = flt[g];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (off[u] >= 0) {
+#pragma unroll
+                for (int e = 0; e < VF; ++e) s_flt[off[u] + e] = v[u][e];
+            }
+        }
+    }
+}
+
+template <int WM, int WN, int MBLK, int NBLK, int TB, int TW, int TH>
+__global__ void __launch_bounds__(WM* WN * 64) conv_f32_kernel(const KernelArgs a) {
+    constexpr int THREADS = WM * WN * 64;
+    constexpr int NT = TB * TW * TH;
+    constexpr int KT = WM * MBLK * 32;
+    extern __shared__ __align__(16) float smem_f[];
+    float* s_img = smem_f;
+    float* s_flt = smem_f + a.img_lds_elems;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WM, wn = wave / WM;
+    const int j = lane & 31, kk = lane >> 5;
+    const TileCoord tc = decode_tile(a, KT, TB, TW, TH);
+
+    int posoff[NBLK];
+#pragma unroll
+    for (int n = 0; n < NBLK; ++n) {
+        int nn = (wn * NBLK + n) * 32 + j;
+        if (nn >= NT) nn = 0;
+        const int b_l = nn % TB, w_l = (nn / TB) % TW, h_l = nn / (TB * TW);
+        posoff[n] = a.sw * w_l * a.xpitch + a.sh * h_l * a.ypitch + b_l;
+    }
+
+    f32x16 acc[MBLK][NBLK];
+#pragma unroll
+    for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[m][n][v] = 0.f;
+
+    // one-time zeros: the zero row read by the odd-length tail, and the pad column of each Filter row
+    if (tid < 64) s_img[a.zero_off + tid] = 0.f;
+    const int Q = a.bS * a.CT;
+    if (Q & 1) {
+        for (int idx = tid; idx < KT * a.bR; idx += THREADS) {
+            const int kl = idx / a.bR, r = idx - kl * a.bR;
+            s_flt[kl * a.fpitch + r * a.QE + Q] = 0.f;
+        }
+    }
+
+    for (int r0 = 0; r0 < a.R; r0 += a.bR) {
+        for (int s0 = 0; s0 < a.S; s0 += a.bS) {
+            for (int c0 = 0; c0 < a.C; c0 += a.CT) {
+                __syncthreads();
+                const int x0 = a.sw * tc.w0 + r0, y0 = a.sh * tc.h0 + s0;
+                if (a.vec_img) {
+                    if constexpr (TB % 4 == 0) stage_image_f32<THREADS, TB, 4>(a, s_img, tid, x0, y0, c0, tc.b0);
+                } else {
+                    stage_image_f32<THREADS, TB, 1>(a, s_img, tid, x0, y0, c0, tc.b0);
+                }
+                if (a.vec_flt)
+                    stage_filter_f32<THREADS, KT, 4>(a, s_flt, tid, tc.k0, r0, s0, c0);
+                else
+                    stage_filter_f32<THREADS, KT, 1>(a, s_flt, tid, tc.k0, r0, s0, c0);
+                __syncthreads();
+
+                const int rmax = min(a.bR, a.R - r0);
+                for (int r = 0; r < rmax; ++r) {
+                    const float* ap = s_flt + (wm * MBLK * 32 + j) * a.fpitch + r * a.QE + kk;
+                    const float* bp = s_img + r * a.xpitch + kk * TB;
+                    const int pairs = Q >> 1;
+#pragma unroll 4
+                    for (int q2 = 0; q2 < pairs; ++q2) {
+                        float av[MBLK], bv[NBLK];
+#pragma unroll
+                        for (int m = 0; m < MBLK; ++m) av[m] = ap[m * 32 * a.fpitch + 2 * q2];
+#pragma unroll
+                        for (int n = 0; n < NBLK; ++n) bv[n] = bp[posoff[n] + 2 * q2 * TB];
+#pragma unroll
+                        for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                            for (int n = 0; n < NBLK; ++n)
+                                acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m], bv[n], acc[m][n], 0, 0, 0);
+                    }
+                    if (Q & 1) {
+                        // last contraction index pairs with a zero: the kk = 1 half reads the pad column / zero row
+                        float av[MBLK], bv[NBLK];
+#pragma unroll
+                        for (int m = 0; m < MBLK; ++m) av[m] = ap[m * 32 * a.fpitch + (Q - 1)];
+#pragma unroll
+                        for (int n = 0; n < NBLK; ++n)
+                            bv[n] = kk ? s_img[a.zero_off + j] : bp[posoff[n] + (Q - 1) * TB];
+#pragma unroll
+                        for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                            for (int n = 0; n < NBLK; ++n)
+                                acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m], bv[n], acc[m][n], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+
+    // epilogue: every Out word of the tile is written once
+#pragma unroll
+    for (int n = 0; n < NBLK; ++n) {
+        const int nn = (wn * NBLK + n) * 32 + j;
+        const int b = tc.b0 + nn % TB, w = tc.w0 + (nn / TB) % TW, h = tc.h0 + nn / (TB * TW);
+        const bool pos_ok = nn < NT && b < a.B && w < a.W && h < a.H;
+#pragma unroll
+        for (int m = 0; m < MBLK; ++m) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int k = tc.k0 + (wm * MBLK + m) * 32 + (v >> 2) * 8 + kk * 4 + (v & 3);
+                if (pos_ok && k < a.K) a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b] = acc[m][n][v];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// bf16 inputs, fp32 accumulate
+// LDS in 16-byte units (8 bf16 of consecutive c): s_img[x*xpitch + y*ypitch + c8*TB + b], so the MFMA B operand of a
+// lane (8 consecutive contraction indices of one position) is one 16-byte read.  Global memory has b fastest, so the
+// staging transposes 8x8 blocks in registers.  s_flt (bf16 elements): [k_l*fpitch + (r*bS+s)*CT + c].
+
+__device__ __forceinline__ void transpose8x8_bf16(const uint4 (&in)[8], uint4 (&out)[8]) {
+    // in[c] holds b0..b7 of row c; out[b] holds c0..c7 of column b
+    uint32_t w[8][4];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        w[c][0] = in[c].x;
+        w[c][1] = in[c].y;
+        w[c][2] = in[c].z;
+        w[c][3] = in[c].w;
+    }
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        uint32_t lo[4], hi[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t e = w[2 * q][m], o = w[2 * q + 1][m];
+            lo[q] = (e & 0xffffu) | (o << 16);
+            hi[q] = (e >> 16) | (o & 0xffff0000u);
+        }
+        out[2 * m] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+        out[2 * m + 1] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+    }
+}
+
+template <int THREADS, int TB>
+__device__ __forceinline__ void stage_image_bf16_vec(const KernelArgs& a, uint4* s_img, int tid, int x0, int y0,
+                                                     int c0, int b0) {
+    constexpr int B8 = TB / 8;
+    const int C8 = a.CT >> 3;
+    const int total = a.XS * a.YS * C8 * B8;
+    const uint16_t* __restrict__ img = (const uint16_t*)a.image;
+    for (int idx = tid; idx < total; idx += THREADS) {
+        const int b8 = idx % B8;
+        const uint32_t t = (uint32_t)idx / B8;
+        const uint32_t t2 = fdiv(t, a.d_C8);
+        const int c8 = t - t2 * C8;
+        const uint32_t x = fdiv(t2, a.d_YS);
+        const int y = t2 - x * a.YS;
+        const int gx = x0 + (int)x, gy = y0 + y, gb = b0 + b8 * 8;
+        uint4 in[8], out[8];
+        const bool ok = gx < a.IW && gy < a.IH && gb < a.B;
+        const int64_t g0 = (((int64_t)gx * a.IH + gy) * a.C) * a.B + gb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int gc = c0 + c8 * 8 + e;
+            in[e] = make_uint4(0, 0, 0, 0);
+            if (ok && gc < a.C) in[e] = *(const uint4*)(img + g0 + (int64_t)gc * a.B);
+        }
+        transpose8x8_bf16(in, out);
+        uint4* dst = s_img + (int)x * a.xpitch + y * a.ypitch + c8 * TB + b8 * 8;
+#pragma unroll
+        for (int bb = 0; bb < 8; ++bb) dst[bb] = out[bb];
+    }
+}
+
+template <int THREADS, int TB>
+__device__ __forceinline__ void stage_image_bf16_scalar(const KernelArgs& a, uint4* s_img, int tid, int x0, int y0,
+                                                        int c0, int b0) {
+    const int total = a.XS * a.YS * a.CT * TB;
+    const uint16_t* __restrict__ img = (const uint16_t*)a.image;
+    uint16_t* s16 = (uint16_t*)s_img;
+    for (int idx = tid; idx < total; idx += THREADS) {
+        const int b = idx % TB;
+        const uint32_t t = (uint32_t)idx / TB;
+        const uint32_t t2 = fdiv(t, a.d_CT);
+        const int c = t - t2 * a.CT;
+        const uint32_t x = fdiv(t2, a.d_YS);
+        const int y = t2 - x * a.YS;
+        const int gx = x0 + (int)x, gy = y0 + y, gc = c0 + c, gb = b0 + b;
+        uint16_t v = 0;
+        if (gx < a.IW && gy < a.IH && gc < a.C && gb < a.B)
+            v = img[(((int64_t)gx * a.IH + gy) * a.C + gc) * a.B + gb];
+        s16[((int)x * a.xpitch + y * a.ypitch + (c >> 3) * TB + b) * 8 + (c & 7)] = v;
+    }
+}
+
+template <int THREADS, int KT>
+__device__ __forceinline__ void stage_filter_bf16(const KernelArgs& a, uint16_t* s_flt, int tid, int k0, int r0,
+                                                  int s0, int c0) {
+    const uint16_t* __restrict__ flt = (const uint16_t*)a.filter;
+    const int RS = a.bR * a.bS;
+    if (a.vec_flt) {
+        const int C8 = a.CT >> 3;
+        const int total = KT * RS * C8;
+        for (int idx = tid; idx < total; idx += THREADS) {
+            const uint32_t t = fdiv((uint32_t)idx, a.d_C8);
+            const int c8 = idx - t * C8;
+            const uint32_t kl = fdiv(t, a.d_RS);
+            const int rs = t - kl * RS;
+            const uint32_t r = fdiv((uint32_t)rs, a.d_bS);
+            const int s = rs - r * a.bS;
+            const int gk = k0 + (int)kl, gr = r0 + (int)r, gs = s0 + s, gc = c0 + c8 * 8;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (gk < a.K && gr < a.R && gs < a.S && gc < a.C)
+                v = *(const uint4*)(flt + (((int64_t)gk * a.R + gr) * a.S + gs) * a.C + gc);
+            *(uint4*)(s_flt + (int)kl * a.fpitch + rs * a.CT + c8 * 8) = v;
+        }
+    } else {
+        const int total = KT * RS * a.CT;
+        for (int idx = tid; idx < total; idx += THREADS) {
+            const uint32_t t = fdiv((uint32_t)idx, a.d_CT);
+            const int c = idx - t * a.CT;
+            const uint32_t kl = fdiv(t, a.d_RS);
+            const int rs = t - kl * RS;
+            const uint32_t r = fdiv((uint32_t)rs, a.d_bS);
+            const int s = rs - r * a.bS;
+            const int gk = k0 + (int)kl, gr = r0 + (int)r, gs = s0 + s, gc = c0 + c;
+            uint16_t v = 0;
+            if (gk < a.K && gr < a.R && gs < a.S && gc < a.C)
+                v = flt[(((int64_t)gk * a.R + gr) * a.S + gs) * a.C + gc];
+            s_flt[(int)kl * a.fpitch + rs * a.CT + c] = v;
+        }
+    }
+}
+
+template <int WM, int WN, int MBLK, int NBLK, int TB, int TW, int TH>
+__global__ void __launch_bounds__(WM* WN * 64) conv_bf16_kernel(const KernelArgs a) {
+    constexpr int THREADS = WM * WN * 64;
+    constexpr int NT = TB * TW * TH;
+    constexpr int KT = WM * MBLK * 32;
+    extern __shared__ __align__(16) uint4 smem_u[];
+    uint4* s_img = smem_u;
+    uint4* s_fltu = smem_u + a.img_lds_elems;
+    uint16_t* s_flt = (uint16_t*)s_fltu;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WM, wn = wave / WM;
+    const int j = lane & 31, g = lane >> 5;
+    const TileCoord tc = decode_tile(a, KT, TB, TW, TH);
+
+    int posoff[NBLK];
+#pragma unroll
+    for (int n = 0; n < NBLK; ++n) {
+        int nn = (wn * NBLK + n) * 32 + j;
+        if (nn >= NT) nn = 0;
+        const int b_l = nn % TB, w_l = (nn / TB) % TW, h_l = nn / (TB * TW);
+        posoff[n] = a.sw * w_l * a.xpitch + a.sh * h_l * a.ypitch + b_l;
+    }
+
+    f32x16 acc[MBLK][NBLK];
+#pragma unroll
+    for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[m][n][v] = 0.f;
+
+    const int fp8 = a.fpitch >> 3;   // Filter row pitch in 16-byte units
+    const int ct8 = a.CT >> 3;
+    for (int r0 = 0; r0 < a.R; r0 += a.bR) {
+        for (int s0 = 0; s0 < a.S; s0 += a.bS) {
+            for (int c0 = 0; c0 < a.C; c0 += a.CT) {
+                __syncthreads();
+                const int x0 = a.sw * tc.w0 + r0, y0 = a.sh * tc.h0 + s0;
+                if (a.vec_img) {
+                    if constexpr (TB % 8 == 0) stage_image_bf16_vec<THREADS, TB>(a, s_img, tid, x0, y0, c0, tc.b0);
+                } else {
+                    stage_image_bf16_scalar<THREADS, TB>(a, s_img, tid, x0, y0, c0, tc.b0);
+                }
+                stage_filter_bf16<THREADS, KT>(a, s_flt, tid, tc.k0, r0, s0, c0);
+                __syncthreads();
+
+                const int rmax = min(a.bR, a.R - r0), smax = min(a.bS, a.S - s0);
+                for (int r = 0; r < rmax; ++r) {
+                    for (int s = 0; s < smax; ++s) {
+                        const uint4* ap = s_fltu + (wm * MBLK * 32 + j) * fp8 + (r * a.bS + s) * ct8 + g;
+                        const uint4* bp = s_img + r * a.xpitch + s * a.ypitch + g * TB;
+                        const int steps = a.CT >> 4;
+#pragma unroll 2
+                        for (int cs = 0; cs < steps; ++cs) {
+                            bf16x8 av[MBLK], bv[NBLK];
+#pragma unroll
+                            for (int m = 0; m < MBLK; ++m)
+                                av[m] = __builtin_bit_cast(bf16x8, ap[m * 32 * fp8 + 2 * cs]);
+#pragma unroll
+                            for (int n = 0; n < NBLK; ++n)
+                                bv[n] = __builtin_bit_cast(bf16x8, bp[posoff[n] + 2 * cs * TB]);
+#pragma unroll
+                            for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                                for (int n = 0; n < NBLK; ++n)
+                                    acc[m][n] =
+                                        __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[m], bv[n], acc[m][n], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+#pragma unroll
+    for (int n = 0; n < NBLK; ++n) {
+        const int nn = (wn * NBLK + n) * 32 + j;
+        const int b = tc.b0 + nn % TB, w = tc.w0 + (nn / TB) % TW, h = tc.h0 + nn / (TB * TW);
+        const bool pos_ok = nn < NT && b < a.B && w < a.W && h < a.H;
+#pragma unroll
+        for (int m = 0; m < MBLK; ++m) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int k = tc.k0 + (wm * MBLK + m) * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+                if (pos_ok && k < a.K) a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b] = acc[m][n][v];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// launch table
+
+template <typename KernelT>
+static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const KernelArgs& a, int grid, size_t lds_bytes,
+                         void* stream) {
+    if (!attr_done) {
+        // raise the dynamic-LDS ceiling of this kernel to the CU's full 160 KiB once
+        if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) !=
+            hipSuccess) {
+            (void)hipGetLastError();
+            return 1;
+        }
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), lds_bytes, (hipStream_t)stream, a);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+#define CACNN_VARIANT(DT, KERNEL, NAME, WM, WN, MBLK, NBLK, TB, TW, TH)                                  \
+    {                                                                                                    \
+        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH},                                                      \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                         \
+                static bool attr_done = false;                                                           \
+                return launch_kernel(KERNEL<WM, WN, MBLK, NBLK, TB, TW, TH>, attr_done, WM * WN * 64, a, \
+                                     grid, lds, stream);                                                 \
+            }                                                                                            \
+    }
+
+static const Variant g_variants[] = {
+    // fp32
+    CACNN_VARIANT(0, conv_f32_kernel, "f32 k32 b1w16h16 w1x4 m1n2", 1, 4, 1, 2, 1, 16, 16),
+    CACNN_VARIANT(0, conv_f32_kernel, "f32 k64 b8w4h4 w2x2 m1n2", 2, 2, 1, 2, 8, 4, 4),
+    CACNN_VARIANT(0, conv_f32_kernel, "f32 k64 b32w4h2 w2x2 m1n4", 2, 2, 1, 4, 32, 4, 2),
+    CACNN_VARIANT(0, conv_f32_kernel, "f32 k64 b32w2h2 w2x2 m1n2", 2, 2, 1, 2, 32, 2, 2),
+    CACNN_VARIANT(0, conv_f32_kernel, "f32 k64 b4w8h4 w2x2 m1n2", 2, 2, 1, 2, 4, 8, 4),
+    // bf16
+    CACNN_VARIANT(1, conv_bf16_kernel, "bf16 k128 b32w2h2 w2x2 m2n2", 2, 2, 2, 2, 32, 2, 2),
+    CACNN_VARIANT(1, conv_bf16_kernel, "bf16 k128 b32w7h1 w4x1 m1n7", 4, 1, 1, 7, 32, 7, 1),
+    CACNN_VARIANT(1, conv_bf16_kernel, "bf16 k64 b8w4h4 w2x2 m1n2", 2, 2, 1, 2, 8, 4, 4),
+    CACNN_VARIANT(1, conv_bf16_kernel, "bf16 k32 b1w16h16 w1x4 m1n2", 1, 4, 1, 2, 1, 16, 16),
+    CACNN_VARIANT(1, conv_bf16_kernel, "bf16 k64 b64w2h1 w2x2 m1n2", 2, 2, 1, 2, 64, 2, 1),
+};
+
+int num_variants() { return (int)(sizeof(g_variants) / sizeof(g_variants[0])); }
+const Variant& variant(int i) { return g_variants[i]; }
+
+}  // namespace cacnn

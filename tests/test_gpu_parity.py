@@ -1,0 +1,165 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 loop-nest oracle, element by element on the same
+seeded inputs.  Tolerance (benchmark definition): max|err| / sum|Image*Filter| <= 1e-5 for fp32, <= 1e-2 for bf16
+inputs with fp32 accumulation; integer-valued inputs must match exactly."""
+import sys
+
+import numpy as np
+import pytest
+
+import cacnn_inputs as ci
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_1802_06905_amd as cc
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return cc, torch
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
+def test_benchmark_shape_full_array(env, name):
+    """The five benchmark shapes at full size, in the launch configuration the benchmark times (planner's choice),
+    every output element against the oracle."""
+    cc, torch = env
+    cfg = ci.CONFIGS[name]
+    say(f"[parity] {name} dims={cfg.dims} dtype={cfg.dtype} entry=cacnn_conv_forward")
+    img, flt = ci.make_inputs(cfg)
+    out = gu.run_gpu(cc, torch, cfg, img, flt)
+    ref, ab = gu.oracle_full(cfg, img, flt)
+    e = gu.assert_parity(cfg, out, ref, ab, "planner")
+    say(f"[parity] {name} max rel err {e:.3e}")
+
+
+# shapes that span several tiles with ragged tails in every dimension, strides, asymmetric filters
+RAGGED = [
+    # name, B, C, K, W, H, R, S, sw, sh
+    ("tiny_b1", 1, 3, 8, 16, 16, 3, 3, 1, 1),
+    ("ragged_all", 5, 7, 37, 11, 9, 3, 2, 1, 1),
+    ("stride_2_3", 3, 5, 33, 9, 7, 5, 4, 2, 3),
+    ("stride_gt_filter", 2, 4, 9, 6, 5, 1, 2, 3, 2),
+    ("one_by_one", 9, 19, 40, 5, 6, 1, 1, 1, 1),
+    ("matmul", 70, 45, 66, 1, 1, 1, 1, 1, 1),
+    ("wide_b", 67, 6, 10, 5, 3, 3, 3, 1, 1),
+    ("b_mult8", 16, 24, 70, 9, 10, 3, 3, 1, 1),
+    ("c_one", 4, 1, 5, 7, 8, 2, 3, 1, 2),
+    ("big_filter", 2, 3, 6, 4, 3, 9, 8, 1, 1),
+    ("seven_by_seven", 40, 16, 96, 7, 7, 3, 3, 1, 1),
+]
+
+
+def variants_for(cc, dtype):
+    return [i for i in range(cc.cacnn_variant_count()) if cc.cacnn_variant_name(i).startswith(dtype + " ")]
+
+
+@pytest.mark.parametrize("shape", RAGGED, ids=[s[0] for s in RAGGED])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_every_variant_on_ragged_shapes(env, shape, dtype):
+    """Every compiled kernel variant must compute every shape (tiles overhang the arrays in all dimensions), with
+    the whole contraction in one tile and with the contraction cut in (c, r, s) tiles."""
+    cc, torch = env
+    cfg = ci.custom(shape[0], *shape[1:], dtype=dtype, dist="normal", seed=100 + len(shape[0]))
+    img, flt = ci.make_inputs(cfg)
+    ref, ab = gu.oracle_full(cfg, img, flt)
+    for vi in variants_for(cc, dtype):
+        for (bc, br, bs) in ((1 << 20, 1 << 20, 1 << 20), (16 if dtype == "bf16" else 3, 2, 1)):
+            plan = cc.Plan()
+            plan.variant, plan.b_c, plan.b_r, plan.b_s = vi, bc, br, bs
+            say(f"[parity] {shape[0]} {dtype} variant={vi} '{cc.cacnn_variant_name(vi)}' b_c={bc} b_r={br} b_s={bs}")
+            out = gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
+            gu.assert_parity(cfg, out, ref, ab, f"variant {vi} tile ({bc},{br},{bs})")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_integer_inputs_are_exact(env, dtype):
+    """Small integers: every product and partial sum is exact in bf16/fp32/fp64, so the result must be bit-exact
+    whatever the summation order."""
+    cc, torch = env
+    cfg = ci.custom("ints", 12, 20, 50, 9, 6, 3, 4, 2, 1, dtype=dtype, dist="smallint", seed=7)
+    img, flt = ci.make_inputs(cfg)
+    ref, _ = gu.oracle_full(cfg, img, flt)
+    say(f"[parity] ints {dtype} planner")
+    out = gu.run_gpu(cc, torch, cfg, img, flt)
+    assert np.array_equal(out.astype(np.float64), ref)
+    for vi in variants_for(cc, dtype):
+        plan = cc.Plan()
+        plan.variant, plan.b_c, plan.b_r, plan.b_s = vi, 16, 2, 3
+        say(f"[parity] ints {dtype} variant={vi}")
+        out = gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
+        assert np.array_equal(out.astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_unaligned_pointers_take_the_scalar_paths(env, dtype):
+    cc, torch = env
+    cfg = ci.custom("unaligned", 16, 16, 40, 6, 5, 3, 3, 1, 1, dtype=dtype, dist="normal", seed=9)
+    img, flt = ci.make_inputs(cfg)
+    ref, ab = gu.oracle_full(cfg, img, flt)
+    say(f"[parity] unaligned {dtype}")
+    out = gu.run_gpu(cc, torch, cfg, img, flt, misalign=1)
+    gu.assert_parity(cfg, out, ref, ab, "misaligned by one element")
+
+
+def test_runs_on_a_side_stream_and_overwrites_out(env):
+    cc, torch = env
+    cfg = ci.custom("stream", 8, 16, 64, 12, 12, 3, 3, 1, 1, dtype="f32", dist="normal", seed=11)
+    img, flt = ci.make_inputs(cfg)
+    ref, ab = gu.oracle_full(cfg, img, flt)
+    s = torch.cuda.Stream()
+    say("[parity] side stream")
+    out = gu.run_gpu(cc, torch, cfg, img, flt, stream=s, prefill=123.0)
+    gu.assert_parity(cfg, out, ref, ab, "side stream")
+    # same launch twice gives identical bits (no atomics, fixed summation order)
+    out2 = gu.run_gpu(cc, torch, cfg, img, flt, prefill=-1.0)
+    assert np.array_equal(out, out2)
+
+
+def test_nonfinite_inputs_stay_local(env):
+    """An Inf in the Image must reach exactly the outputs whose receptive field holds it (zero-padding inside the
+    kernel must not multiply it into other outputs)."""
+    cc, torch = env
+    for dtype in ("f32", "bf16"):
+        cfg = ci.custom("inf", 2, 3, 5, 6, 5, 3, 3, 1, 1, dtype=dtype, dist="normal", seed=13)
+        img, flt = ci.make_inputs(cfg)
+        img[4, 3, 1, 0] = np.inf
+        say(f"[parity] inf {dtype}")
+        out = gu.run_gpu(cc, torch, cfg, img, flt)
+        bad = ~np.isfinite(out)
+        want = np.zeros(cfg.out_shape, bool)
+        for w in range(cfg.W):
+            for h in range(cfg.H):
+                if 0 <= 4 - w < cfg.R and 0 <= 3 - h < cfg.S:
+                    want[:, h, w, 0] = True
+        assert np.array_equal(bad, want)
+
+
+def test_error_paths_enqueue_nothing(env):
+    cc, torch = env
+    cfg = ci.CONFIGS["c1"]
+    img, flt = ci.make_inputs(cfg)
+    d_img, d_flt = gu.upload(cfg, img, flt, torch)
+    d_out = torch.zeros(int(np.prod(cfg.out_shape)), dtype=torch.float32, device="cuda:0")
+    with pytest.raises(cc.CacnnError) as e:
+        cc.cacnn_conv_forward(cfg.dims, 0, 0, d_flt, d_out)
+    assert e.value.status == 1
+    with pytest.raises(cc.CacnnError) as e:
+        cc.cacnn_conv_forward((1, 3, 8, 16, 0, 3, 3, 1, 1), 0, d_img, d_flt, d_out)
+    assert e.value.status == 2
+    with pytest.raises(cc.CacnnError) as e:
+        cc.cacnn_conv_forward(cfg.dims, 7, d_img, d_flt, d_out)
+    assert e.value.status == 3
+    plan = cc.Plan()
+    plan.variant, plan.b_c, plan.b_r, plan.b_s = 999, 1, 1, 1
+    with pytest.raises(cc.CacnnError) as e:
+        cc.cacnn_conv_forward_with_plan(cfg.dims, 0, plan, d_img, d_flt, d_out)
+    assert e.value.status == 3
+    torch.cuda.synchronize()
+    assert not d_out.any()

@@ -1,0 +1,193 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header declares, and its host-only
+entry points (lower bound, tile planner) agree with the oracle.  No GPU compute is called here."""
+import ctypes
+import os
+import re
+import subprocess
+import tempfile
+
+import numpy as np
+import pytest
+
+import cacnn_inputs as ci
+import paper_1802_06905_amd as cc
+from oracle import lower_bound as olb
+from oracle import lp_tiling as olp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "cacnn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(cacnn_[a-z_]+)\s*\(", header))
+    assert {"cacnn_lower_bound", "cacnn_tile_plan", "cacnn_conv_forward", "cacnn_conv_forward_with_plan",
+            "cacnn_status_string", "cacnn_variant_count", "cacnn_variant_name"} <= names
+    lib = ctypes.CDLL(cc.library_path())
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_sizes_match_the_header():
+    src = r'''
+    #include <stdio.h>
+    #include "cacnn.h"
+    int main(void){ printf("%zu %zu %zu %zu\n", sizeof(cacnn_problem), sizeof(cacnn_bound), sizeof(cacnn_machine), sizeof(cacnn_plan)); return 0; }
+    '''
+    with tempfile.TemporaryDirectory() as d:
+        open(os.path.join(d, "t.c"), "w").write(src)
+        subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                        "-o", os.path.join(d, "t"), os.path.join(d, "t.c")], check=True)
+        sizes = [int(x) for x in subprocess.run([os.path.join(d, "t")], capture_output=True, text=True,
+                                                check=True).stdout.split()]
+    assert sizes == [ctypes.sizeof(cc.Problem), ctypes.sizeof(cc.Bound), ctypes.sizeof(cc.Machine),
+                     ctypes.sizeof(cc.Plan)]
+
+
+def test_fastdiv_is_exact_over_its_domain():
+    """The kernels divide staged-tile indices by run-time constants with one multiply-high; check the host-made
+    magic numbers against plain division for every divisor up to 4096 over the index range an LDS tile can have."""
+    src = r'''
+    #include <cstdio>
+    #include <cstdint>
+    #include "cacnn_internal.h"
+    int main(){
+      for (uint32_t d = 1; d <= 4096; ++d) {
+        cacnn::FastDiv f = cacnn::make_fastdiv(d);
+        for (uint32_t n = 0; n < 200000; n += (n < 70000 ? 1 : 7)) {
+          uint32_t q = f.mul ? (uint32_t)(((uint64_t)n * f.mul) >> 32) : n;
+          if (q != n / d) { printf("bad %u %u\n", n, d); return 1; }
+        }
+      }
+      printf("ok\n"); return 0; }
+    '''
+    with tempfile.TemporaryDirectory() as d:
+        open(os.path.join(d, "t.cpp"), "w").write(src)
+        subprocess.run(["g++", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "paper_1802_06905_amd", "csrc"),
+                        "-o", os.path.join(d, "t"), os.path.join(d, "t.cpp")], check=True)
+        out = subprocess.run([os.path.join(d, "t")], capture_output=True, text=True).stdout
+    assert out.strip() == "ok"
+
+
+def test_lower_bound_matches_oracle():
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        dims = [int(x) for x in rng.integers(1, 300, 7)] + [int(x) for x in rng.integers(1, 5, 2)]
+        M = float(rng.integers(1, 100000))
+        got = cc.cacnn_lower_bound(dims, M)
+        want = olb.lower_bound(*dims, M)
+        assert np.allclose(list(got.term), want.terms, rtol=1e-13)
+        assert got.bound == pytest.approx(want.bound, rel=1e-13)
+        assert got.argmax == want.argmax
+
+
+def test_lower_bound_alexnet_example():
+    dims = (1000, 3, 96, 55, 55, 11, 11, 4, 4)
+    b = cc.cacnn_lower_bound(dims, 17424.0)
+    assert b.term[4] == pytest.approx(b.term[0]) and b.term[0] == 290400000.0
+
+
+def test_lower_bound_errors():
+    with pytest.raises(cc.CacnnError) as e:
+        cc.cacnn_lower_bound((0, 1, 1, 1, 1, 1, 1, 1, 1), 10.0)
+    assert e.value.status == 2
+    with pytest.raises(cc.CacnnError) as e:
+        cc.cacnn_lower_bound((1, 1, 1, 1, 1, 1, 1, 1, 1), 0.0)
+    assert e.value.status == 2
+    assert cc.cacnn_status_string(0) == "ok" and "unknown" in cc.cacnn_status_string(99)
+
+
+@pytest.mark.parametrize("name", list(ci.CONFIGS))
+def test_plan_paper_block_matches_oracle(name):
+    cfg = ci.CONFIGS[name]
+    dtype = 0 if cfg.dtype == "f32" else 1
+    plan = cc.cacnn_tile_plan(cfg.dims, dtype)
+    M = 160 * 1024 / (4 if dtype == 0 else 2)
+    want = olp.solve_lp(*cfg.dims, M)
+    assert plan.lp_volume == pytest.approx(want.volume, rel=1e-6)
+    assert plan.lp_cost_words == pytest.approx(want.cost, rel=1e-6)
+    assert plan.bound_words == pytest.approx(olb.lower_bound(*cfg.dims, M).bound, rel=1e-12)
+    assert np.prod(list(plan.lp_tile)) == pytest.approx(plan.lp_volume, rel=1e-9)
+    if cfg.sigma_w == 1 and cfg.sigma_h == 1:
+        label = olp.appendix_a_case(*cfg.dims[:7], M)[0]
+        assert str(plan.paper_case) == label.replace(".", "")
+    else:
+        assert plan.paper_case == 0
+
+
+def test_plan_lp_volume_matches_oracle_on_random_shapes():
+    rng = np.random.default_rng(1)
+    for _ in range(150):
+        sw, sh = (int(x) for x in rng.integers(1, 4, 2))
+        R, S = int(rng.integers(1, 12)), int(rng.integers(1, 12))
+        W, H = int(rng.integers(1, 60)), int(rng.integers(1, 60))
+        B, C, K = (int(x) for x in rng.integers(1, 600, 3))
+        lds = int(2 ** rng.integers(11, 18))
+        mach = cc.Machine(lds, 512 * 1024, 256)
+        dtype = int(rng.integers(0, 2))
+        try:
+            plan = cc.cacnn_tile_plan((B, C, K, W, H, R, S, sw, sh), dtype, mach)
+        except cc.CacnnError as e:
+            assert e.status == 2          # nothing fits a tiny LDS
+            continue
+        M = lds / (4 if dtype == 0 else 2)
+        want = olp.solve_lp(B, C, K, W, H, R, S, sw, sh, M)
+        assert plan.lp_volume == pytest.approx(want.volume, rel=1e-6)
+
+
+@pytest.mark.parametrize("name", list(ci.CONFIGS))
+def test_plan_gpu_block_is_feasible(name):
+    cfg = ci.CONFIGS[name]
+    dtype = 0 if cfg.dtype == "f32" else 1
+    plan = cc.cacnn_tile_plan(cfg.dims, dtype)
+    assert 0 <= plan.variant < cc.cacnn_variant_count()
+    assert cc.cacnn_variant_name(plan.variant).startswith(cfg.dtype + " ")
+    assert 0 < plan.lds_bytes_used <= 160 * 1024
+    cdiv = lambda a, b: -(-a // b)
+    assert plan.grid[0] == cdiv(cfg.K, plan.b_k) * cdiv(cfg.B, plan.b_b) * cdiv(cfg.W, plan.b_w) * cdiv(cfg.H, plan.b_h)
+    assert plan.block in (64, 128, 256, 512)
+    assert 1 <= plan.b_r <= cfg.R and 1 <= plan.b_s <= cfg.S and plan.b_c >= 1
+    assert plan.b_r2 <= cfg.sigma_w and cfg.sigma_w * (plan.b_r1 - 1) + 1 <= plan.b_r
+    # the schedule reads at least each input once and writes Out once
+    compulsory = np.prod(cfg.image_shape) + np.prod(cfg.filter_shape) + np.prod(cfg.out_shape)
+    assert plan.predicted_words >= compulsory
+    assert plan.tile_volume == plan.b_b * plan.b_c * plan.b_k * plan.b_w * plan.b_h * plan.b_r * plan.b_s
+
+
+def test_plan_errors():
+    with pytest.raises(cc.CacnnError) as e:
+        cc.cacnn_tile_plan((1, 1, 1, 1, 1, 1, 1, 1, 0), 0)
+    assert e.value.status == 2
+    with pytest.raises(cc.CacnnError) as e:
+        cc.cacnn_tile_plan((1, 1, 1, 1, 1, 1, 1, 1, 1), 5)
+    assert e.value.status == 3
+    with pytest.raises(cc.CacnnError) as e:
+        cc.cacnn_tile_plan((2 ** 20, 2 ** 20, 4, 4, 4, 1, 1, 1, 1), 0)     # Image has more than 2^31 elements
+    assert e.value.status == 2
+    assert cc.cacnn_variant_name(-1) is None and cc.cacnn_variant_name(10 ** 6) is None
+
+
+def test_conv_forward_rejects_null_and_bad_arguments_without_a_gpu():
+    lib = ctypes.CDLL(cc.library_path())
+    lib.cacnn_conv_forward.restype = ctypes.c_int
+    lib.cacnn_conv_forward.argtypes = [ctypes.POINTER(cc.Problem), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_void_p, ctypes.c_void_p]
+    p = cc.Problem(1, 3, 8, 16, 16, 3, 3, 1, 1)
+    assert lib.cacnn_conv_forward(None, 0, 16, 16, 16, None) == 1
+    assert lib.cacnn_conv_forward(ctypes.byref(p), 0, None, 16, 16, None) == 1
+    assert lib.cacnn_conv_forward(ctypes.byref(p), 9, 16, 16, 16, None) == 3
+    bad = cc.Problem(1, 3, 8, 16, 16, 3, 3, 0, 1)
+    assert lib.cacnn_conv_forward(ctypes.byref(bad), 0, 16, 16, 16, None) == 2
+    assert lib.cacnn_conv_forward(ctypes.byref(p), 0, 18, 16, 16, None) == 2      # pointer not aligned to a float
+
+
+def test_conv_forward_without_a_gpu_reports_no_device():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    lib = ctypes.CDLL(cc.library_path())
+    lib.cacnn_conv_forward.restype = ctypes.c_int
+    lib.cacnn_conv_forward.argtypes = [ctypes.POINTER(cc.Problem), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_void_p, ctypes.c_void_p]
+    p = cc.Problem(1, 3, 8, 16, 16, 3, 3, 1, 1)
+    assert lib.cacnn_conv_forward(ctypes.byref(p), 0, 4096, 8192, 16384, None) == 5   # never dereferenced
