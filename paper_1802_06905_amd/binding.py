@@ -64,6 +64,10 @@ if not os.path.exists(_LIB_PATH):
     raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_1802_06905_amd.build` "
                       "(there is no CPU fallback)")
 
+# PyTorch owns the device memory and the streams handed to this library, so both must talk to the SAME HIP runtime:
+# import torch first, so that its copy of libamdhip64 (same SONAME) is the one the loader binds libcacnn.so to.
+import torch  # noqa: E402,F401
+
 _lib = ctypes.CDLL(_LIB_PATH)
 _lib.cacnn_lower_bound.restype = ctypes.c_int
 _lib.cacnn_lower_bound.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, ctypes.POINTER(Bound)]

@@ -74,7 +74,12 @@ def test_every_variant_on_ragged_shapes(env, shape, dtype):
             plan = cc.Plan()
             plan.variant, plan.b_c, plan.b_r, plan.b_s = vi, bc, br, bs
             say(f"[parity] {shape[0]} {dtype} variant={vi} '{cc.cacnn_variant_name(vi)}' b_c={bc} b_r={br} b_s={bs}")
-            out = gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
+            try:
+                out = gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
+            except cc.CacnnError as e:
+                # a forced whole-contraction tile may not fit in LDS: the library must say so, not launch
+                assert e.status == 3 and bc == 1 << 20, (e.status, bc)
+                continue
             gu.assert_parity(cfg, out, ref, ab, f"variant {vi} tile ({bc},{br},{bs})")
 
 
