@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <limits>
 #include <mutex>
@@ -167,15 +168,25 @@ int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 struct Geometry {
     int CT, bR, bS, XS, YS, xpitch, ypitch, fpitch, QE, img_lds_elems, zero_off;
     int64_t lds_bytes;
+    // pipelined variants
+    int img_items, flt_items, img_buf, flt_buf, flt_off, flt_resident;
+    int64_t n_slices;
+    bool legal;   // the variant can run this geometry (staging items fit, packed fields fit)
 };
 
 Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int bR, int bS, bool vec_img) {
     Geometry g;
+    std::memset(&g, 0, sizeof(g));
+    g.legal = true;
     g.CT = CT;
     g.bR = bR;
     g.bS = bS;
     g.XS = (int)(p.sigma_w * (v.TW - 1) + bR);
     g.YS = (int)(p.sigma_h * (v.TH - 1) + bS);
+    const int64_t Cpad = round_up(p.C, v.cgran());
+    g.n_slices = ceil_div(p.R, bR) * ceil_div(p.S, bS) * ceil_div(Cpad, CT);
+    g.flt_resident = (g.n_slices == 1 && ceil_div(p.K, v.KT()) == 1) ? 1 : 0;
+    const int nbuf_f = g.flt_resident ? 1 : 2;
     if (v.dtype == CACNN_F32) {
         g.ypitch = CT * v.TB;
         int base = g.YS * g.ypitch;
@@ -197,20 +208,50 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
         g.QE = bS * CT + ((bS * CT) & 1);
         g.fpitch = bR * g.QE;
         if ((g.fpitch & 1) == 0) g.fpitch += 1;  // odd pitch: the 32 rows of an A fragment hit 32 different banks
-        g.zero_off = g.XS * g.xpitch;
-        g.img_lds_elems = (int)round_up(g.zero_off + 64, 4);
-        g.lds_bytes = 4ll * (g.img_lds_elems + (int64_t)v.KT() * g.fpitch);
+        if (!v.pipelined) {
+            g.zero_off = g.XS * g.xpitch;
+            g.img_lds_elems = (int)round_up(g.zero_off + 64, 4);
+            g.lds_bytes = 4ll * (g.img_lds_elems + (int64_t)v.KT() * g.fpitch);
+        } else {
+            g.img_buf = (int)round_up((int64_t)g.XS * g.xpitch, 4);
+            g.zero_off = 2 * g.img_buf;
+            g.flt_off = g.zero_off + 64;
+            g.flt_buf = (int)round_up((int64_t)v.KT() * g.fpitch, 4);
+            g.lds_bytes = 4ll * (g.flt_off + (int64_t)nbuf_f * g.flt_buf);
+            g.img_items = g.XS * g.YS * CT * (v.TB / 4);
+            g.flt_items = v.KT() * bR * bS * (CT / 4);
+            g.legal = vec_img && v.TB % 4 == 0 && (g.flt_resident || (CT % 4 == 0 && p.C % 4 == 0));
+        }
     } else {
         const int C8 = CT / 8;
-        g.ypitch = C8 * v.TB;           // 16-byte units
-        g.xpitch = g.YS * g.ypitch;
-        g.QE = 0;
         int f8 = bR * bS * C8;          // Filter row in 16-byte units; odd count keeps 16-byte reads conflict-free
         if ((f8 & 1) == 0) f8 += 1;
         g.fpitch = f8 * 8;
-        g.zero_off = 0;
-        g.img_lds_elems = g.XS * g.xpitch;
-        g.lds_bytes = 16ll * g.img_lds_elems + 2ll * v.KT() * g.fpitch;
+        g.ypitch = C8 * v.TB;           // 16-byte units, [c/8][b][8 c]
+        g.xpitch = g.YS * g.ypitch;
+        if (!v.pipelined) {
+            g.img_lds_elems = g.XS * g.xpitch;
+            g.lds_bytes = 16ll * g.img_lds_elems + 2ll * v.KT() * g.fpitch;
+        } else {
+            g.img_buf = g.XS * g.xpitch;
+            g.flt_off = 2 * g.img_buf;
+            g.flt_buf = v.KT() * f8;
+            g.lds_bytes = 16ll * (g.flt_off + (int64_t)nbuf_f * g.flt_buf);
+            g.img_items = g.XS * g.YS * C8 * (v.TB / 8);    // 8 channels x 8 images each
+            g.flt_items = v.KT() * bR * bS * C8;
+            g.legal = vec_img && v.TB % 8 == 0 && (g.flt_resident || p.C % 8 == 0);
+        }
+    }
+    if (v.reuse_r > 0 && (bR != v.reuse_r || p.sigma_w != 1)) g.legal = false;
+    if (v.pipelined) {
+        const int64_t thr = v.threads();
+        if (g.img_items > v.MAXI * thr || (!g.flt_resident && g.flt_items > v.MAXF * thr)) g.legal = false;
+        if (g.XS > 1023 || g.YS > 1023 || CT > 1023 || bR > 127 || bS > 127 || v.KT() > 256) g.legal = false;
+        // staging items are addressed by 32-bit byte offsets from the unit's origin
+        const double esz = v.dtype == CACNN_F32 ? 4.0 : 2.0;
+        const double IHd = (double)(p.sigma_h * (p.H - 1) + p.S);
+        if ((double)(g.XS + 1) * IHd * (double)p.C * (double)p.B * esz >= 2147483648.0) g.legal = false;
+        if ((double)(v.KT() + 1) * (double)p.R * (double)p.S * (double)p.C * esz >= 2147483648.0) g.legal = false;
     }
     return g;
 }
@@ -280,7 +321,7 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
         for (int bS = (int)std::min<int64_t>(p.S, 1 << 12); bS >= 1; bS = (bS + 1) / 2 == bS ? 0 : (bS + 1) / 2) {
             for (int ct : cts) {
                 const Geometry g = make_geometry(v, p, ct, bR, bS, vimg);
-                if (g.lds_bytes > mach.lds_bytes) continue;
+                if (!g.legal || g.lds_bytes > mach.lds_bytes) continue;
                 double img_words = 0.0;
                 const double words = staged_words(v, p, g, &img_words);
                 const double ksteps = v.dtype == CACNN_F32 ? (double)p.R * ceil_div((int64_t)p.S * Cpad, 2)
@@ -289,13 +330,22 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
                 const double stage_cyc =
                     (img_words * waste + (words - img_words)) * ebytes / (double)n_wg / 32.0;  // ~32 B/clk/CU
                 const double epi_cyc = (double)v.KT() * v.NT() * 4.0 / 64.0 * waste;
-                const double n_ctiles = (double)ceil_div(p.R, bR) * ceil_div(p.S, bS) * ceil_div(Cpad, ct);
-                const double latency_cyc = 2500.0 * n_ctiles;   // exposed load latency + two barriers per tile
+                const double n_ctiles = (double)g.n_slices;
                 const int resident = g.lds_bytes * 2 <= mach.lds_bytes ? 2 : 1;
-                const double hide = resident >= 2 ? 0.4 : 1.0;
-                const double per_wg = mfma_cyc + hide * (stage_cyc + epi_cyc + latency_cyc) + 1500.0;
                 const double per_cu = (double)ceil_div(n_wg, mach.num_cu);
-                const double cost = per_cu * per_wg;
+                double cost;
+                if (!v.pipelined) {
+                    const double latency_cyc = 2500.0 * n_ctiles;   // exposed load latency + two barriers per tile
+                    const double hide = resident >= 2 ? 0.4 : 1.0;
+                    const double per_wg = mfma_cyc + hide * (stage_cyc + epi_cyc + latency_cyc) + 1500.0;
+                    cost = per_cu * per_wg;
+                } else {
+                    // loads overlap the multiply; what stays exposed per slice is the LDS write phase and one barrier
+                    const double per_slice = std::max(mfma_cyc / n_ctiles, 0.5 * stage_cyc / n_ctiles) +
+                                             0.25 * stage_cyc / n_ctiles + 300.0;
+                    const double per_tile = n_ctiles * per_slice + 0.5 * epi_cyc;
+                    cost = per_cu * per_tile + 3000.0;
+                }
                 if (best->variant < 0 || cost < best->cost) {
                     best->variant = vi;
                     best->g = g;
@@ -308,6 +358,14 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
         }
     }
     return found;
+}
+
+// workgroups launched: one per Out tile, or for the persistent kernels as many as the machine holds at once
+int64_t launch_grid(const VariantInfo& v, const Geometry& g, int64_t n_tiles, const cacnn_machine& mach) {
+    if (!v.pipelined) return n_tiles;
+    const int64_t resident =
+        std::max<int64_t>(1, std::min<int64_t>(v.occ, mach.lds_bytes / std::max<int64_t>(1, g.lds_bytes)));
+    return std::min<int64_t>(n_tiles, mach.num_cu * resident);
 }
 
 int fill_plan(const cacnn_problem& p, int dtype, const cacnn_machine& mach, const Choice& ch, cacnn_plan* out) {
@@ -338,7 +396,7 @@ int fill_plan(const cacnn_problem& p, int dtype, const cacnn_machine& mach, cons
     out->b_r1 = (int32_t)ceil_div(ch.g.bR, std::max<int64_t>(1, std::min<int64_t>(p.sigma_w, p.R)));
     out->b_s2 = (int32_t)std::min<int64_t>(p.sigma_h, ch.g.bS);
     out->b_s1 = (int32_t)ceil_div(ch.g.bS, std::max<int64_t>(1, std::min<int64_t>(p.sigma_h, p.S)));
-    out->grid[0] = (int32_t)ch.n_wg;
+    out->grid[0] = (int32_t)launch_grid(v, ch.g, ch.n_wg, mach);
     out->grid[1] = 1;
     out->grid[2] = 1;
     out->block = v.threads();
@@ -348,7 +406,8 @@ int fill_plan(const cacnn_problem& p, int dtype, const cacnn_machine& mach, cons
     return CACNN_OK;
 }
 
-int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, cacnn_plan* out) {
+int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, cacnn_plan* out,
+              bool allow_pipelined = true) {
     if (!p || !out) return CACNN_ERR_NULL;
     if (!valid_problem(p)) return CACNN_ERR_INVALID_ARG;
     if (dtype != CACNN_F32 && dtype != CACNN_BF16_F32ACC) return CACNN_ERR_UNSUPPORTED;
@@ -371,10 +430,21 @@ int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, c
     Choice best;
     for (int vi = 0; vi < num_variants(); ++vi) {
         if (variant(vi).info.dtype != dtype) continue;
+        if (variant(vi).info.pipelined && !allow_pipelined) continue;
         evaluate(vi, *p, mach, &best);
     }
     if (best.variant < 0) return CACNN_ERR_INVALID_ARG;  // nothing fits the given LDS size
     return fill_plan(*p, dtype, mach, best, out);
+}
+
+// XCD count used for the tile remapping; CACNN_XCDS=1 switches the remapping off (debugging aid)
+int xcd_count() {
+    static int n = [] {
+        const char* e = std::getenv("CACNN_XCDS");
+        const int v = e ? std::atoi(e) : 8;
+        return v >= 1 && v <= 64 ? v : 8;
+    }();
+    return n;
 }
 
 bool g_device_checked = false;
@@ -406,6 +476,7 @@ int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int b
     const bool vimg = vec_img_ok(v, p) && aligned_img;
     const Geometry g = make_geometry(v, p, CT, bR, bS, vimg);
     if (g.lds_bytes > 160 * 1024) return CACNN_ERR_UNSUPPORTED;
+    if (v.pipelined && (!g.legal || (!aligned_flt && !g.flt_resident))) return CACNN_ERR_UNSUPPORTED;
 
     KernelArgs a;
     std::memset(&a, 0, sizeof(a));
@@ -456,6 +527,15 @@ int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int b
     if (!mul_check(a.tiles_k, a.tiles_b, INT32_MAX, &t) || !mul_check(t, a.tiles_w, INT32_MAX, &t) ||
         !mul_check(t, a.tiles_h, INT32_MAX, &grid))
         return CACNN_ERR_INVALID_ARG;
+    a.n_tiles = (int32_t)grid;
+    a.n_xcd = xcd_count();
+    a.img_items = g.img_items;
+    a.flt_items = g.flt_items;
+    a.img_buf = g.img_buf;
+    a.flt_buf = g.flt_buf;
+    a.flt_off = g.flt_off;
+    a.flt_resident = g.flt_resident;
+    grid = launch_grid(v, g, grid, kDefaultMachine);
     if (!have_device()) return CACNN_ERR_NO_DEVICE;
     return var.launch(a, (int)grid, (size_t)g.lds_bytes, stream) == 0 ? CACNN_OK : CACNN_ERR_LAUNCH;
 }
@@ -485,24 +565,27 @@ int cacnn_conv_forward(const cacnn_problem* problem, int dtype, const void* imag
         int dtype;
         cacnn_plan plan;
     };
+    // the pipelined kernels need 16-byte aligned operands; a misaligned call is planned without them
+    const bool aligned = reinterpret_cast<uintptr_t>(image) % 16 == 0 && reinterpret_cast<uintptr_t>(filter) % 16 == 0;
+    const int key = dtype | (aligned ? 0 : 0x100);
     static std::vector<Entry> cache;
     cacnn_plan plan;
     bool hit = false;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
         for (const Entry& e : cache)
-            if (e.dtype == dtype && std::memcmp(&e.p, problem, sizeof(cacnn_problem)) == 0) {
+            if (e.dtype == key && std::memcmp(&e.p, problem, sizeof(cacnn_problem)) == 0) {
                 plan = e.plan;
                 hit = true;
                 break;
             }
     }
     if (!hit) {
-        const int rc = plan_impl(problem, dtype, nullptr, &plan);
+        const int rc = plan_impl(problem, dtype, nullptr, &plan, aligned);
         if (rc != CACNN_OK) return rc;
         std::lock_guard<std::mutex> lock(g_mutex);
         if (cache.size() >= 64) cache.erase(cache.begin());
-        cache.push_back(Entry{*problem, dtype, plan});
+        cache.push_back(Entry{*problem, key, plan});
     }
     return launch_with(*problem, dtype, plan.variant, plan.b_c, plan.b_r, plan.b_s, image, filter, out, hip_stream);
 }

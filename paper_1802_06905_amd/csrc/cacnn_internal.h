@@ -28,6 +28,14 @@ struct VariantInfo {
     const char* name;
     int dtype;  // cacnn_dtype
     int WM, WN, MBLK, NBLK, TB, TW, TH;
+    // 0: one workgroup per Out tile, staging and MFMA alternate (works for every shape and alignment).
+    // 1: persistent workgroups walk a list of (tile, contraction slice) units; the next unit's Image and Filter
+    //    words are fetched into registers while the current one is multiplied, LDS is double-buffered.
+    //    Needs 16-byte-legal operands and a slice that fits MAXI/MAXF staging items per thread.
+    int pipelined;
+    int MAXI, MAXF;
+    int occ;    // workgroups of this kernel one compute unit can hold at once, as far as registers go
+    int reuse_r;  // > 0: filter-row reuse path compiled for exactly this many taps per contraction tile (sigma_w = 1)
     int KT() const { return WM * MBLK * 32; }
     int NT() const { return TB * TW * TH; }
     int threads() const { return WM * WN * 64; }
@@ -50,6 +58,13 @@ struct KernelArgs {
     int32_t tiles_k, tiles_b, tiles_w, tiles_h;
     int32_t vec_img, vec_flt; // 1 = 16-byte global loads are legal for this operand
     FastDiv d_CT, d_YS, d_bS, d_bR, d_C8, d_RS;
+    // pipelined kernels only
+    int32_t n_tiles;          // Out tiles in the whole problem (all kernels)
+    int32_t n_xcd;            // XCDs the dispatcher deals workgroups to (8 on MI355X); 1 = no remapping
+    int32_t img_items, flt_items;   // 16-byte staging items per slice
+    int32_t img_buf, flt_buf; // size of one LDS buffer of each operand (fp32: floats; bf16: 16-byte units)
+    int32_t flt_off;          // where the Filter buffers start (same unit)
+    int32_t flt_resident;     // 1 = the Filter tile is the same for every unit of a workgroup: staged once
 };
 
 typedef int (*LaunchFn)(const KernelArgs& a, int grid, size_t lds_bytes, void* stream);

@@ -32,8 +32,19 @@ struct TileCoord {
     int k0, b0, w0, h0;
 };
 
+// Workgroups are dealt round-robin to the XCDs (each with its own L2), so consecutive dispatch indices land on
+// different L2s.  Give every XCD one contiguous run of the tile list instead: with the output-channel tile as the
+// fastest index, the workgroups that share an Image tile (and walk the Filter slices in step) then share an L2.
+// i -> tile is a bijection on [0, n): XCD x = i % n_xcd owns tiles [x*q + min(x,rem), ...) with n = n_xcd*q + rem.
+__device__ __forceinline__ int xcd_tile(int i, int n, int n_xcd) {
+    if (n_xcd <= 1) return i;
+    const int q = n / n_xcd, rem = n - q * n_xcd;
+    const int x = i % n_xcd, l = i / n_xcd;
+    return x * q + min(x, rem) + l;
+}
+
 __device__ __forceinline__ TileCoord decode_tile(const KernelArgs& a, int KT, int TB, int TW, int TH) {
-    int t = blockIdx.x;
+    int t = xcd_tile(blockIdx.x, a.n_tiles, a.n_xcd);
     const int tk = t % a.tiles_k;
     t /= a.tiles_k;
     const int tb = t % a.tiles_b;
@@ -481,6 +492,572 @@ __global__ void __launch_bounds__(WM* WN * 64) conv_bf16_kernel(const KernelArgs
 }
 
 // ---------------------------------------------------------------------------------------------------------------
+// Pipelined persistent kernels.
+//
+// A workgroup walks units u = (Out tile, contraction slice): tiles blockIdx.x, blockIdx.x + gridDim.x, ... and, inside a
+// tile, the slices (r0, s0, c0) of the contraction.  While unit u is multiplied out of LDS buffer u&1, the 16-byte
+// staging items of unit u+1 are already in flight from global memory into registers; they are written to the other
+// LDS buffer after the multiply, so one barrier per unit suffices: a thread can only reach the stores of unit u+1
+// after every thread has passed the barrier of unit u, i.e. has finished reading the buffer being overwritten.
+// Which item a thread fetches is fixed for the whole kernel (it depends only on the slice geometry): its byte offset
+// from the unit's origin in global memory and its LDS address are computed once, so fetching a unit costs one
+// scalar base address and one load per item.  Units whose tile or slice overhangs an array take a slower path that
+// checks every item and zero-fills.  The loops are finite and identical for all threads of a workgroup: every wave
+// reaches every barrier.
+
+struct UnitPos {
+    int t;       // position in this workgroup's tile sequence (tile list index), >= n_tiles when exhausted
+    int r0, s0, c0;
+    TileCoord tc;
+};
+
+__device__ __forceinline__ TileCoord decode_tile_index(const KernelArgs& a, int t, int KT, int TB, int TW, int TH) {
+    t = xcd_tile(t, a.n_tiles, a.n_xcd);
+    const int tk = t % a.tiles_k;
+    t /= a.tiles_k;
+    const int tb = t % a.tiles_b;
+    t /= a.tiles_b;
+    const int tw = t % a.tiles_w;
+    const int th = t / a.tiles_w;
+    TileCoord tc;
+    tc.k0 = tk * KT;
+    tc.b0 = tb * TB;
+    tc.w0 = tw * TW;
+    tc.h0 = th * TH;
+    return tc;
+}
+
+__device__ __forceinline__ void advance_unit(const KernelArgs& a, UnitPos& p, int KT, int TB, int TW, int TH) {
+    p.c0 += a.CT;
+    if (p.c0 >= a.C) {
+        p.c0 = 0;
+        p.s0 += a.bS;
+        if (p.s0 >= a.S) {
+            p.s0 = 0;
+            p.r0 += a.bR;
+            if (p.r0 >= a.R) {
+                p.r0 = 0;
+                p.t += gridDim.x;
+                if (p.t < a.n_tiles) p.tc = decode_tile_index(a, p.t, KT, TB, TW, TH);
+            }
+        }
+    }
+}
+
+// What is uniform over one unit: the origins of its Image and Filter tiles and how far the arrays extend from them.
+struct UnitBase {
+    const char* img;   // &Image(x0, y0, c0, b0)
+    const char* flt;   // &Filter(k0, r0, s0, c0)
+    int lx, ly, lc, lb, lk, lr, ls;
+    bool img_inside, flt_inside;
+};
+
+template <int ESZ>
+__device__ __forceinline__ UnitBase unit_base(const KernelArgs& a, const UnitPos& p, int KT, int TB) {
+    UnitBase u;
+    const int x0 = a.sw * p.tc.w0 + p.r0, y0 = a.sh * p.tc.h0 + p.s0;
+    u.img = (const char*)a.image + ((((int64_t)x0 * a.IH + y0) * a.C + p.c0) * a.B + p.tc.b0) * ESZ;
+    u.flt = (const char*)a.filter + ((((int64_t)p.tc.k0 * a.R + p.r0) * a.S + p.s0) * a.C + p.c0) * ESZ;
+    u.lx = a.IW - x0;
+    u.ly = a.IH - y0;
+    u.lc = a.C - p.c0;
+    u.lb = a.B - p.tc.b0;
+    u.lk = a.K - p.tc.k0;
+    u.lr = a.R - p.r0;
+    u.ls = a.S - p.s0;
+    u.img_inside = u.lx >= a.XS && u.ly >= a.YS && u.lc >= a.CT && u.lb >= TB;
+    u.flt_inside = u.lk >= KT && u.lr >= a.bR && u.ls >= a.bS && u.lc >= a.CT;
+    return u;
+}
+
+template <int WM, int WN, int MBLK, int NBLK, int TB, int TW, int TH, int MAXI, int MAXF>
+__global__ void __launch_bounds__(WM* WN * 64) conv_f32_pipe_kernel(const KernelArgs a) {
+    constexpr int THREADS = WM * WN * 64;
+    constexpr int NT = TB * TW * TH;
+    constexpr int KT = WM * MBLK * 32;
+    constexpr int VPR = TB / 4;
+    extern __shared__ __align__(16) float smem_f[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WM, wn = wave / WM;
+    const int j = lane & 31, kk = lane >> 5;
+    const int zero_off = 2 * a.img_buf;
+
+    int posoff[NBLK];
+#pragma unroll
+    for (int n = 0; n < NBLK; ++n) {
+        int nn = (wn * NBLK + n) * 32 + j;
+        if (nn >= NT) nn = 0;
+        const int b_l = nn % TB, w_l = (nn / TB) % TW, h_l = nn / (TB * TW);
+        posoff[n] = a.sw * w_l * a.xpitch + a.sh * h_l * a.ypitch + b_l;
+    }
+
+    // static staging assignment: byte offset from the unit origin, LDS offset, packed coordinates (edge checks)
+    uint32_t i_g[MAXI];
+    int i_lds[MAXI], i_pk[MAXI];
+#pragma unroll
+    for (int i = 0; i < MAXI; ++i) {
+        const int idx = tid + i * THREADS;
+        i_pk[i] = -1;
+        i_lds[i] = 0;
+        i_g[i] = 0;
+        if (idx < a.img_items) {
+            const uint32_t row = (uint32_t)idx / VPR;
+            const int bv = idx % VPR;
+            const uint32_t t = fdiv(row, a.d_CT);
+            const int c = row - t * a.CT;
+            const uint32_t x = fdiv(t, a.d_YS);
+            const int y = t - x * a.YS;
+            i_pk[i] = (int)x | (y << 10) | (c << 20);
+            i_lds[i] = (int)x * a.xpitch + (y * a.CT + c) * TB + bv * 4;
+            i_g[i] = (((x * a.IH + y) * a.C + c) * a.B + bv * 4) * 4u;
+        }
+    }
+    uint32_t f_g[MAXF], f_pk[MAXF];
+    int f_lds[MAXF];
+    const int CTV = a.CT >> 2;
+#pragma unroll
+    for (int i = 0; i < MAXF; ++i) {
+        const int idx = tid + i * THREADS;
+        f_pk[i] = 0xffffffffu;
+        f_lds[i] = 0;
+        f_g[i] = 0;
+        if (!a.flt_resident && idx < a.flt_items) {
+            const uint32_t t = fdiv((uint32_t)idx, a.d_C8);
+            const int c = (idx - t * CTV) * 4;
+            const uint32_t t2 = fdiv(t, a.d_bS);
+            const int s = t - t2 * a.bS;
+            const uint32_t kl = fdiv(t2, a.d_bR);
+            const int r = t2 - kl * a.bR;
+            f_pk[i] = kl | ((uint32_t)r << 8) | ((uint32_t)s << 15) | ((uint32_t)c << 22);
+            f_lds[i] = (int)kl * a.fpitch + r * a.QE + s * a.CT + c;
+            f_g[i] = (((kl * a.R + r) * a.S + s) * a.C + c) * 4u;
+        }
+    }
+
+    // one-time zeros: the zero row, and the pad column of every Filter row in both buffers
+    if (tid < 64) smem_f[zero_off + tid] = 0.f;
+    const int Q = a.bS * a.CT;
+    if (Q & 1) {
+        const int nbuf = a.flt_resident ? 1 : 2;
+        for (int idx = tid; idx < nbuf * KT * a.bR; idx += THREADS) {
+            const int bsel = idx / (KT * a.bR), rem = idx - bsel * KT * a.bR;
+            const int kl = rem / a.bR, r = rem - kl * a.bR;
+            smem_f[a.flt_off + bsel * a.flt_buf + kl * a.fpitch + r * a.QE + Q] = 0.f;
+        }
+    }
+
+    f32x4 ireg[MAXI], freg[MAXF];
+    auto issue_loads = [&](const UnitPos& p) {
+        const UnitBase u = unit_base<4>(a, p, KT, TB);
+        if (u.img_inside) {
+#pragma unroll
+            for (int i = 0; i < MAXI; ++i) ireg[i] = *(const f32x4*)(u.img + i_g[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < MAXI; ++i) {
+                const int pk = i_pk[i];
+                const bool ok = pk >= 0 && (pk & 1023) < u.lx && ((pk >> 10) & 1023) < u.ly && (pk >> 20) < u.lc &&
+                                ((tid + i * THREADS) % VPR) * 4 < u.lb;
+                const f32x4 v = *(const f32x4*)(u.img + (ok ? i_g[i] : 0u));
+                const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+                ireg[i] = ok ? v : z;
+            }
+        }
+        if (!a.flt_resident) {
+            if (u.flt_inside) {
+#pragma unroll
+                for (int i = 0; i < MAXF; ++i) freg[i] = *(const f32x4*)(u.flt + f_g[i]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < MAXF; ++i) {
+                    const uint32_t pk = f_pk[i];
+                    const bool ok = pk != 0xffffffffu && (int)(pk & 255) < u.lk && (int)((pk >> 8) & 127) < u.lr &&
+                                    (int)((pk >> 15) & 127) < u.ls && (int)(pk >> 22) < u.lc;
+                    const f32x4 v = *(const f32x4*)(u.flt + (ok ? f_g[i] : 0u));
+                    const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+                    freg[i] = ok ? v : z;
+                }
+            }
+        }
+    };
+    auto store_regs = [&](int buf) {
+        float* s_img = smem_f + buf * a.img_buf;
+#pragma unroll
+        for (int i = 0; i < MAXI; ++i)
+            if (i_pk[i] >= 0) *(f32x4*)(s_img + i_lds[i]) = ireg[i];
+        if (!a.flt_resident) {
+            float* s_flt = smem_f + a.flt_off + buf * a.flt_buf;
+#pragma unroll
+            for (int i = 0; i < MAXF; ++i)
+                if (f_pk[i] != 0xffffffffu) {
+                    s_flt[f_lds[i] + 0] = freg[i][0];
+                    s_flt[f_lds[i] + 1] = freg[i][1];
+                    s_flt[f_lds[i] + 2] = freg[i][2];
+                    s_flt[f_lds[i] + 3] = freg[i][3];
+                }
+        }
+    };
+
+    f32x16 acc[MBLK][NBLK];
+#pragma unroll
+    for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[m][n][v] = 0.f;
+
+    UnitPos cur;
+    cur.t = blockIdx.x;
+    cur.r0 = cur.s0 = cur.c0 = 0;
+    cur.tc = decode_tile_index(a, cur.t < a.n_tiles ? cur.t : 0, KT, TB, TW, TH);
+    UnitPos nxt = cur;
+    if (cur.t < a.n_tiles) {
+        issue_loads(cur);
+        advance_unit(a, nxt, KT, TB, TW, TH);
+    }
+    if (a.flt_resident) {
+        // one Filter tile serves every unit of this workgroup: stage it once (any alignment, any C)
+        if (a.vec_flt)
+            stage_filter_f32<THREADS, KT, 4>(a, smem_f + a.flt_off, tid, 0, 0, 0, 0);
+        else
+            stage_filter_f32<THREADS, KT, 1>(a, smem_f + a.flt_off, tid, 0, 0, 0, 0);
+    }
+    int buf = 0;
+    while (cur.t < a.n_tiles) {
+        store_regs(buf);
+        __syncthreads();
+        const bool have_next = nxt.t < a.n_tiles;
+        if (have_next) issue_loads(nxt);
+
+        const float* s_img = smem_f + buf * a.img_buf;
+        const float* s_flt = smem_f + a.flt_off + (a.flt_resident ? 0 : buf) * a.flt_buf;
+        const int rmax = min(a.bR, a.R - cur.r0);
+        for (int r = 0; r < rmax; ++r) {
+            const float* ap = s_flt + (wm * MBLK * 32 + j) * a.fpitch + r * a.QE + kk;
+            const float* bp = s_img + r * a.xpitch + kk * TB;
+            const int pairs = Q >> 1;
+#pragma unroll 4
+            for (int q2 = 0; q2 < pairs; ++q2) {
+                float av[MBLK], bv[NBLK];
+#pragma unroll
+                for (int m = 0; m < MBLK; ++m) av[m] = ap[m * 32 * a.fpitch + 2 * q2];
+#pragma unroll
+                for (int n = 0; n < NBLK; ++n) bv[n] = bp[posoff[n] + 2 * q2 * TB];
+#pragma unroll
+                for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                    for (int n = 0; n < NBLK; ++n)
+                        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m], bv[n], acc[m][n], 0, 0, 0);
+            }
+            if (Q & 1) {
+                float av[MBLK], bv[NBLK];
+#pragma unroll
+                for (int m = 0; m < MBLK; ++m) av[m] = ap[m * 32 * a.fpitch + (Q - 1)];
+#pragma unroll
+                for (int n = 0; n < NBLK; ++n) bv[n] = kk ? smem_f[zero_off + j] : bp[posoff[n] + (Q - 1) * TB];
+#pragma unroll
+                for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                    for (int n = 0; n < NBLK; ++n)
+                        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m], bv[n], acc[m][n], 0, 0, 0);
+            }
+        }
+
+        if (!have_next || nxt.t != cur.t) {
+            // the tile's contraction is complete: write it out once and start the next tile from zero
+#pragma unroll
+            for (int n = 0; n < NBLK; ++n) {
+                const int nn = (wn * NBLK + n) * 32 + j;
+                const int b = cur.tc.b0 + nn % TB, w = cur.tc.w0 + (nn / TB) % TW, h = cur.tc.h0 + nn / (TB * TW);
+                const bool pos_ok = nn < NT && b < a.B && w < a.W && h < a.H;
+#pragma unroll
+                for (int m = 0; m < MBLK; ++m) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int k = cur.tc.k0 + (wm * MBLK + m) * 32 + (v >> 2) * 8 + kk * 4 + (v & 3);
+                        if (pos_ok && k < a.K) a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b] = acc[m][n][v];
+                        acc[m][n][v] = 0.f;
+                    }
+                }
+            }
+        }
+        cur = nxt;
+        if (have_next) advance_unit(a, nxt, KT, TB, TW, TH);
+        buf ^= 1;
+    }
+}
+
+// bf16 pipelined kernel.  LDS holds the Image tile in 16-byte units of 8 consecutive channels of one position,
+// s_img[x*xpitch + y*ypitch + c8*TB + (b ^ key)], so that the MFMA B operand of a lane is ONE 16-byte read (LDS reads
+// run at full bandwidth only for 16-byte accesses).  Global memory has b fastest, so a staging item is an 8x8 block
+// (8 channels x 8 images) that is transposed in registers; the XOR key (low three bits of b, a function of the item)
+// spreads the eight 16-byte stores of neighbouring lanes over the banks and is undone, per lane, in the reads.
+//
+// BR > 0 selects the filter-row reuse path (needs sigma_w = 1, b_r = BR, TB = 32 and one wave spanning the tile's
+// width): for one filter row offset s and one 16-channel step, a wave reads the TW+BR-1 Image fragments of its row
+// once and uses each of them for up to BR filter taps r -- the register-level form of the reuse that lets the
+// small-filter bound of Section 4.3 sit below the matmul bound.  Fragments are double-buffered in registers so the
+// LDS reads of step t+1 overlap the MFMAs of step t.
+template <int TB>
+__device__ __forceinline__ int store_key(int b8, int c8) {
+    constexpr int B8 = TB / 8;
+    return B8 == 4 ? ((b8 + 4 * (c8 & 1)) & 7) : (b8 & 7);
+}
+
+template <int WM, int WN, int MBLK, int NBLK, int TB, int TW, int TH, int MAXI, int MAXF, int BR = 0>
+__global__ void __launch_bounds__(WM* WN * 64) conv_bf16_pipe_kernel(const KernelArgs a) {
+    static_assert(TB % 8 == 0, "staging items are 8 channels x 8 images");
+    static_assert(BR == 0 || (TB == 32 && NBLK == TW), "row reuse: a wave owns TW consecutive columns of 32 images");
+    constexpr int THREADS = WM * WN * 64;
+    constexpr int NT = TB * TW * TH;
+    constexpr int KT = WM * MBLK * 32;
+    constexpr int B8 = TB / 8;
+    extern __shared__ __align__(16) uint4 smem_u[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WM, wn = wave / WM;
+    const int j = lane & 31, g = lane >> 5;
+
+    // LDS unit of this lane's B fragment for column block n at (r, s, c-step) = 0; c8 = 2*cs + g has the parity of g
+    int posoff[NBLK];
+#pragma unroll
+    for (int n = 0; n < NBLK; ++n) {
+        int nn = (wn * NBLK + n) * 32 + j;
+        if (nn >= NT) nn = 0;
+        const int b_l = nn % TB, w_l = (nn / TB) % TW, h_l = nn / (TB * TW);
+        const int b_sw = (b_l & ~7) | ((b_l & 7) ^ store_key<TB>(b_l >> 3, g));
+        posoff[n] = a.sw * w_l * a.xpitch + a.sh * h_l * a.ypitch + g * TB + b_sw;
+    }
+
+    const int C8 = a.CT >> 3, RS = a.bR * a.bS;
+    const uint32_t row_bytes = (uint32_t)a.B * 2u;
+    uint32_t i_g[MAXI];
+    int i_lds[MAXI], i_pk[MAXI], i_key[MAXI];
+#pragma unroll
+    for (int i = 0; i < MAXI; ++i) {
+        const int idx = tid + i * THREADS;
+        i_pk[i] = -1;
+        i_lds[i] = 0;
+        i_g[i] = 0;
+        i_key[i] = 0;
+        if (idx < a.img_items) {
+            const int b8 = idx % B8;
+            const uint32_t t = (uint32_t)idx / B8;
+            const uint32_t t2 = fdiv(t, a.d_C8);
+            const int c8 = t - t2 * C8;
+            const uint32_t x = fdiv(t2, a.d_YS);
+            const int y = t2 - x * a.YS;
+            i_pk[i] = (int)x | (y << 10) | (c8 << 20);
+            i_lds[i] = (int)x * a.xpitch + y * a.ypitch + c8 * TB + b8 * 8;
+            i_key[i] = store_key<TB>(b8, c8);
+            i_g[i] = (((x * a.IH + y) * a.C + c8 * 8) * a.B + b8 * 8) * 2u;
+        }
+    }
+    uint32_t f_g[MAXF], f_pk[MAXF];
+    int f_lds[MAXF];
+#pragma unroll
+    for (int i = 0; i < MAXF; ++i) {
+        const int idx = tid + i * THREADS;
+        f_pk[i] = 0xffffffffu;
+        f_lds[i] = 0;
+        f_g[i] = 0;
+        if (!a.flt_resident && idx < a.flt_items) {
+            const uint32_t t = fdiv((uint32_t)idx, a.d_C8);
+            const int c8 = idx - t * C8;
+            const uint32_t kl = fdiv(t, a.d_RS);
+            const int rs = t - kl * RS;
+            const uint32_t r = fdiv((uint32_t)rs, a.d_bS);
+            const int s = rs - r * a.bS;
+            f_pk[i] = kl | (r << 8) | ((uint32_t)s << 15) | ((uint32_t)c8 << 22);
+            f_lds[i] = ((int)kl * a.fpitch + rs * a.CT) / 8 + c8;
+            f_g[i] = (((kl * a.R + r) * a.S + s) * a.C + c8 * 8) * 2u;
+        }
+    }
+
+    uint4 ireg[MAXI][8], freg[MAXF];
+    auto issue_loads = [&](const UnitPos& p) {
+        const UnitBase u = unit_base<2>(a, p, KT, TB);
+        if (u.img_inside) {
+#pragma unroll
+            for (int i = 0; i < MAXI; ++i)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ireg[i][e] = *(const uint4*)(u.img + i_g[i] + e * row_bytes);
+        } else {
+#pragma unroll
+            for (int i = 0; i < MAXI; ++i) {
+                const int pk = i_pk[i];
+                const bool ok = pk >= 0 && (pk & 1023) < u.lx && ((pk >> 10) & 1023) < u.ly &&
+                                ((tid + i * THREADS) % B8) * 8 < u.lb;
+                const int c = (pk >> 20) * 8;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool oke = ok && c + e < u.lc;
+                    const uint4 v = *(const uint4*)(u.img + (oke ? i_g[i] + e * row_bytes : 0u));
+                    ireg[i][e] = oke ? v : make_uint4(0, 0, 0, 0);
+                }
+            }
+        }
+        if (!a.flt_resident) {
+            if (u.flt_inside) {
+#pragma unroll
+                for (int i = 0; i < MAXF; ++i) freg[i] = *(const uint4*)(u.flt + f_g[i]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < MAXF; ++i) {
+                    const uint32_t pk = f_pk[i];
+                    const bool ok = pk != 0xffffffffu && (int)(pk & 255) < u.lk && (int)((pk >> 8) & 127) < u.lr &&
+                                    (int)((pk >> 15) & 127) < u.ls && (int)(pk >> 22) * 8 < u.lc;
+                    const uint4 v = *(const uint4*)(u.flt + (ok ? f_g[i] : 0u));
+                    freg[i] = ok ? v : make_uint4(0, 0, 0, 0);
+                }
+            }
+        }
+    };
+    auto store_regs = [&](int buf) {
+        uint4* s_img = smem_u + buf * a.img_buf;
+#pragma unroll
+        for (int i = 0; i < MAXI; ++i)
+            if (i_pk[i] >= 0) {
+                uint4 out[8];
+                transpose8x8_bf16(ireg[i], out);
+                uint4* dst = s_img + i_lds[i];
+#pragma unroll
+                for (int bb = 0; bb < 8; ++bb) dst[bb ^ i_key[i]] = out[bb];
+            }
+        if (!a.flt_resident) {
+            uint4* s_flt = smem_u + a.flt_off + buf * a.flt_buf;
+#pragma unroll
+            for (int i = 0; i < MAXF; ++i)
+                if (f_pk[i] != 0xffffffffu) s_flt[f_lds[i]] = freg[i];
+        }
+    };
+
+    f32x16 acc[MBLK][NBLK];
+#pragma unroll
+    for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[m][n][v] = 0.f;
+
+    UnitPos cur;
+    cur.t = blockIdx.x;
+    cur.r0 = cur.s0 = cur.c0 = 0;
+    cur.tc = decode_tile_index(a, cur.t < a.n_tiles ? cur.t : 0, KT, TB, TW, TH);
+    UnitPos nxt = cur;
+    if (cur.t < a.n_tiles) {
+        issue_loads(cur);
+        advance_unit(a, nxt, KT, TB, TW, TH);
+    }
+    if (a.flt_resident) stage_filter_bf16<THREADS, KT>(a, (uint16_t*)(smem_u + a.flt_off), tid, 0, 0, 0, 0);
+    const int fp8 = a.fpitch >> 3, ct8 = a.CT >> 3;
+    int buf = 0;
+    while (cur.t < a.n_tiles) {
+        store_regs(buf);
+        __syncthreads();
+        const bool have_next = nxt.t < a.n_tiles;
+        if (have_next) issue_loads(nxt);
+
+        const uint4* s_img = smem_u + buf * a.img_buf;
+        const uint4* s_flt = smem_u + a.flt_off + (a.flt_resident ? 0 : buf) * a.flt_buf;
+        const int rmax = min(a.bR, a.R - cur.r0), smax = min(a.bS, a.S - cur.s0);
+        const int steps = a.CT >> 4;
+        if constexpr (BR > 0) {
+            constexpr int NX = TW + BR - 1;
+            auto load_frags = [&](int s, int cs, bf16x8(&A)[MBLK][BR], bf16x8(&X)[NX]) {
+                const uint4* ap = s_flt + (wm * MBLK * 32 + j) * fp8 + s * ct8 + g + 2 * cs;
+#pragma unroll
+                for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                    for (int r = 0; r < BR; ++r)
+                        A[m][r] = __builtin_bit_cast(bf16x8, ap[m * 32 * fp8 + r * a.bS * ct8]);
+                const uint4* bp = s_img + posoff[0] + s * a.ypitch + 2 * cs * TB;
+#pragma unroll
+                for (int x = 0; x < NX; ++x) X[x] = __builtin_bit_cast(bf16x8, bp[x * a.xpitch]);
+            };
+            auto mfmas = [&](const bf16x8(&A)[MBLK][BR], const bf16x8(&X)[NX]) {
+#pragma unroll
+                for (int r = 0; r < BR; ++r)
+#pragma unroll
+                    for (int n = 0; n < TW; ++n)
+#pragma unroll
+                        for (int m = 0; m < MBLK; ++m)
+                            acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[m][r], X[n + r], acc[m][n], 0, 0, 0);
+            };
+            const int T = smax * steps;
+            int s_n = 0, cs_n = 0;
+            auto next_step = [&]() {
+                if (++cs_n == steps) {
+                    cs_n = 0;
+                    ++s_n;
+                }
+            };
+            bf16x8 A0[MBLK][BR], X0[NX], A1[MBLK][BR], X1[NX];
+            load_frags(0, 0, A0, X0);
+            next_step();
+            for (int t = 0; t < T; t += 2) {
+                if (t + 1 < T) {
+                    load_frags(s_n, cs_n, A1, X1);
+                    next_step();
+                }
+                mfmas(A0, X0);
+                if (t + 1 < T) {
+                    if (t + 2 < T) {
+                        load_frags(s_n, cs_n, A0, X0);
+                        next_step();
+                    }
+                    mfmas(A1, X1);
+                }
+            }
+        } else {
+            for (int r = 0; r < rmax; ++r) {
+                for (int s = 0; s < smax; ++s) {
+                    const uint4* ap = s_flt + (wm * MBLK * 32 + j) * fp8 + (r * a.bS + s) * ct8 + g;
+                    const uint4* bp = s_img + r * a.xpitch + s * a.ypitch;
+#pragma unroll 2
+                    for (int cs = 0; cs < steps; ++cs) {
+                        bf16x8 av[MBLK], bv[NBLK];
+#pragma unroll
+                        for (int m = 0; m < MBLK; ++m) av[m] = __builtin_bit_cast(bf16x8, ap[m * 32 * fp8 + 2 * cs]);
+#pragma unroll
+                        for (int n = 0; n < NBLK; ++n) bv[n] = __builtin_bit_cast(bf16x8, bp[posoff[n] + 2 * cs * TB]);
+#pragma unroll
+                        for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                            for (int n = 0; n < NBLK; ++n)
+                                acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[m], bv[n], acc[m][n], 0, 0, 0);
+                    }
+                }
+            }
+        }
+
+        if (!have_next || nxt.t != cur.t) {
+#pragma unroll
+            for (int n = 0; n < NBLK; ++n) {
+                const int nn = (wn * NBLK + n) * 32 + j;
+                const int b = cur.tc.b0 + nn % TB, w = cur.tc.w0 + (nn / TB) % TW, h = cur.tc.h0 + nn / (TB * TW);
+                const bool pos_ok = nn < NT && b < a.B && w < a.W && h < a.H;
+#pragma unroll
+                for (int m = 0; m < MBLK; ++m) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int k = cur.tc.k0 + (wm * MBLK + m) * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+                        if (pos_ok && k < a.K) a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b] = acc[m][n][v];
+                        acc[m][n][v] = 0.f;
+                    }
+                }
+            }
+        }
+        cur = nxt;
+        if (have_next) advance_unit(a, nxt, KT, TB, TW, TH);
+        buf ^= 1;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
 // launch table
 
 template <typename KernelT>
@@ -501,12 +1078,32 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 
 #define CACNN_VARIANT(DT, KERNEL, NAME, WM, WN, MBLK, NBLK, TB, TW, TH)                                  \
     {                                                                                                    \
-        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH},                                                      \
+        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH, 0, 0, 0, 2, 0},                                             \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                         \
                 static bool attr_done = false;                                                           \
                 return launch_kernel(KERNEL<WM, WN, MBLK, NBLK, TB, TW, TH>, attr_done, WM * WN * 64, a, \
                                      grid, lds, stream);                                                 \
             }                                                                                            \
+    }
+
+#define CACNN_PIPE_VARIANT(DT, KERNEL, NAME, WM, WN, MBLK, NBLK, TB, TW, TH, MAXI, MAXF, OCC)                   \
+    {                                                                                                          \
+        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH, 1, MAXI, MAXF, OCC, 0},                                     \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                return launch_kernel(KERNEL<WM, WN, MBLK, NBLK, TB, TW, TH, MAXI, MAXF>, attr_done,            \
+                                     WM * WN * 64, a, grid, lds, stream);                                      \
+            }                                                                                                  \
+    }
+
+#define CACNN_REUSE_VARIANT(NAME, WM, WN, MBLK, NBLK, TB, TW, TH, MAXI, MAXF, OCC, BR)                          \
+    {                                                                                                          \
+        {NAME, 1, WM, WN, MBLK, NBLK, TB, TW, TH, 1, MAXI, MAXF, OCC, BR},                                     \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                return launch_kernel(conv_bf16_pipe_kernel<WM, WN, MBLK, NBLK, TB, TW, TH, MAXI, MAXF, BR>,    \
+                                     attr_done, WM * WN * 64, a, grid, lds, stream);                           \
+            }                                                                                                  \
     }
 
 static const Variant g_variants[] = {
@@ -522,6 +1119,23 @@ static const Variant g_variants[] = {
     CACNN_VARIANT(1, conv_bf16_kernel, "bf16 k64 b8w4h4 w2x2 m1n2", 2, 2, 1, 2, 8, 4, 4),
     CACNN_VARIANT(1, conv_bf16_kernel, "bf16 k32 b1w16h16 w1x4 m1n2", 1, 4, 1, 2, 1, 16, 16),
     CACNN_VARIANT(1, conv_bf16_kernel, "bf16 k64 b64w2h1 w2x2 m1n2", 2, 2, 1, 2, 64, 2, 1),
+    // pipelined, fp32
+    CACNN_PIPE_VARIANT(0, conv_f32_pipe_kernel, "f32 pipe k64 b8w4h4 w2x2 m1n2", 2, 2, 1, 2, 8, 4, 4, 6, 10, 1),
+    CACNN_PIPE_VARIANT(0, conv_f32_pipe_kernel, "f32 pipe k64 b8w8h4 w2x2 m1n4", 2, 2, 1, 4, 8, 8, 4, 10, 10, 1),
+    CACNN_PIPE_VARIANT(0, conv_f32_pipe_kernel, "f32 pipe k64 b32w4h2 w2x2 m1n4", 2, 2, 1, 4, 32, 4, 2, 12, 10, 1),
+    CACNN_PIPE_VARIANT(0, conv_f32_pipe_kernel, "f32 pipe k64 b32w2h2 w2x2 m1n2", 2, 2, 1, 2, 32, 2, 2, 8, 10, 1),
+    // pipelined, bf16 (MAXI counts 8x8 staging blocks, MAXF 16-byte Filter chunks)
+    CACNN_PIPE_VARIANT(1, conv_bf16_pipe_kernel, "bf16 pipe k128 b32w2h2 w2x2 m2n2", 2, 2, 2, 2, 32, 2, 2, 1, 10, 1),
+    CACNN_PIPE_VARIANT(1, conv_bf16_pipe_kernel, "bf16 pipe k128 b32w7h1 w4x1 m1n7", 4, 1, 1, 7, 32, 7, 1, 1, 10, 1),
+    CACNN_PIPE_VARIANT(1, conv_bf16_pipe_kernel, "bf16 pipe k64 b64w2h1 w2x2 m1n2", 2, 2, 1, 2, 64, 2, 1, 1, 6, 2),
+    CACNN_PIPE_VARIANT(1, conv_bf16_pipe_kernel, "bf16 pipe k128 b64w2h2 w2x2 m2n4", 2, 2, 2, 4, 64, 2, 2, 1, 10, 1),
+    CACNN_PIPE_VARIANT(1, conv_bf16_pipe_kernel, "bf16 pipe k64 b16w4h2 w2x2 m1n2", 2, 2, 1, 2, 16, 4, 2, 1, 6, 2),
+    CACNN_PIPE_VARIANT(1, conv_bf16_pipe_kernel, "bf16 pipe k64 b8w4h4 w2x2 m1n2", 2, 2, 1, 2, 8, 4, 4, 1, 6, 2),
+    // pipelined bf16 with filter-row reuse (3 taps)
+    CACNN_REUSE_VARIANT("bf16 pipe3 k128 b32w2h2 w2x2 m2n2", 2, 2, 2, 2, 32, 2, 2, 1, 10, 1, 3),
+    CACNN_REUSE_VARIANT("bf16 pipe3 k128 b32w7h1 w4x1 m1n7", 4, 1, 1, 7, 32, 7, 1, 1, 10, 1, 3),
+    CACNN_REUSE_VARIANT("bf16 pipe3 k64 b32w7h2 w2x2 m1n7", 2, 2, 1, 7, 32, 7, 2, 2, 6, 1, 3),
+    CACNN_REUSE_VARIANT("bf16 pipe3 k128 b32w4h1 w4x1 m1n4", 4, 1, 1, 4, 32, 4, 1, 1, 10, 1, 3),
 };
 
 int num_variants() { return (int)(sizeof(g_variants) / sizeof(g_variants[0])); }

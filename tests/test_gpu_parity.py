@@ -53,7 +53,15 @@ RAGGED = [
     ("c_one", 4, 1, 5, 7, 8, 2, 3, 1, 2),
     ("big_filter", 2, 3, 6, 4, 3, 9, 8, 1, 1),
     ("seven_by_seven", 40, 16, 96, 7, 7, 3, 3, 1, 1),
+    # shapes the pipelined persistent kernels accept (16-byte-legal b and c), ragged in k, w, h
+    ("pipe_friendly", 64, 24, 70, 9, 5, 3, 3, 1, 1),
+    ("pipe_stride", 32, 16, 40, 6, 7, 5, 3, 2, 2),
+    ("pipe_many_tiles", 32, 8, 64, 50, 46, 3, 3, 1, 1),      # more tiles than resident workgroups
+    ("pipe_resident_filter", 32, 3, 64, 21, 20, 7, 7, 2, 2),  # one Filter tile for the whole grid, odd C
+    ("pipe_b8", 8, 16, 64, 13, 12, 3, 3, 1, 1),
 ]
+
+RAN = {}
 
 
 def variants_for(cc, dtype):
@@ -77,10 +85,19 @@ def test_every_variant_on_ragged_shapes(env, shape, dtype):
             try:
                 out = gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
             except cc.CacnnError as e:
-                # a forced whole-contraction tile may not fit in LDS: the library must say so, not launch
-                assert e.status == 3 and bc == 1 << 20, (e.status, bc)
+                # a forced tile may not fit in LDS, and the pipelined kernels only take 16-byte-legal shapes whose
+                # slice fits their staging registers: the library must say so, not launch
+                assert e.status == 3 and (bc == 1 << 20 or "pipe" in cc.cacnn_variant_name(vi)), (e.status, bc)
                 continue
             gu.assert_parity(cfg, out, ref, ab, f"variant {vi} tile ({bc},{br},{bs})")
+            RAN[(dtype, vi)] = RAN.get((dtype, vi), 0) + 1
+
+
+def test_every_variant_ran_on_some_ragged_shape(env):
+    cc, torch = env
+    for dtype in ("f32", "bf16"):
+        for vi in variants_for(cc, dtype):
+            assert RAN.get((dtype, vi), 0) >= 2, f"variant {vi} '{cc.cacnn_variant_name(vi)}' never ran"
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -88,7 +105,7 @@ def test_integer_inputs_are_exact(env, dtype):
     """Small integers: every product and partial sum is exact in bf16/fp32/fp64, so the result must be bit-exact
     whatever the summation order."""
     cc, torch = env
-    cfg = ci.custom("ints", 12, 20, 50, 9, 6, 3, 4, 2, 1, dtype=dtype, dist="smallint", seed=7)
+    cfg = ci.custom("ints", 32, 24, 50, 9, 6, 3, 4, 2, 1, dtype=dtype, dist="smallint", seed=7)
     img, flt = ci.make_inputs(cfg)
     ref, _ = gu.oracle_full(cfg, img, flt)
     say(f"[parity] ints {dtype} planner")
@@ -98,7 +115,11 @@ def test_integer_inputs_are_exact(env, dtype):
         plan = cc.Plan()
         plan.variant, plan.b_c, plan.b_r, plan.b_s = vi, 16, 2, 3
         say(f"[parity] ints {dtype} variant={vi}")
-        out = gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
+        try:
+            out = gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
+        except cc.CacnnError as e:
+            assert e.status == 3 and "pipe" in cc.cacnn_variant_name(vi)
+            continue
         assert np.array_equal(out.astype(np.float64), ref)
 
 
