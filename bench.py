@@ -52,6 +52,22 @@ def time_config(cc, torch, ci, np, cfg, steps, warmup, repeats=1):
     return best[0] / steps, best[1] / steps, (img, flt, d_out)
 
 
+def committed_traffic(name):
+    """HBM-side bytes of one launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs, scaled
+    by the copy-kernel calibration recorded there).  Counters cannot be read from inside this process, so the
+    figure is the recorded one for this shape, not a measurement of this run; None if the summary is absent."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_c1-c5.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                t = line.split()
+                if len(t) >= 5 and t[0] == "traffic" and t[1] == name:
+                    return float(t[4])
+    except OSError:
+        pass
+    return None
+
+
 def shape_report(cc, cfg, sec):
     dt = 0 if cfg.dtype == "f32" else 1
     esz = 4 if dt == 0 else 2
@@ -72,7 +88,7 @@ def shape_report(cc, cfg, sec):
         "compulsory_bytes": compulsory, "paper_bound_bytes_at_M_lds": lb_bytes,
         "planned_staged_bytes": esz * (plan.predicted_words - n_out) + 4 * n_out,
         "variant": cc.cacnn_variant_name(plan.variant), "grid": plan.grid[0], "lds_bytes": plan.lds_bytes_used,
-        "b_c": plan.b_c,
+        "b_c": plan.b_c, "hbm_bytes_profiled": committed_traffic(cfg.name),
     }
 
 
@@ -96,6 +112,34 @@ def cpu_baseline(cfg, img, flt, np):
             "sample": f"{cfg.name}: output channels 0..{k_use - 1} of {K} ({macs:.3g} MACs, fp64, {dt:.2f} s)"}, ref, ab, k_use
 
 
+def traffic_probe(cc, torch, ci, np, cfg):
+    """Dispatch sequence for the HBM-traffic counters (FETCH_SIZE / WRITE_SIZE, KiB per dispatch):
+    a plain copy of known size to scale the counters by, then the workload cold (caches evicted) and warm."""
+    n = 512 * 1024 * 1024
+    src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+    img, flt = ci.make_inputs(cfg)
+    if cfg.dtype == "bf16":
+        d_img = torch.from_numpy(ci.bf16_bits(img).view(np.int16).reshape(-1)).cuda()
+        d_flt = torch.from_numpy(ci.bf16_bits(flt).view(np.int16).reshape(-1)).cuda()
+    else:
+        d_img = torch.from_numpy(img.reshape(-1)).cuda()
+        d_flt = torch.from_numpy(flt.reshape(-1)).cuda()
+    d_out = torch.empty(int(np.prod(cfg.out_shape)), dtype=torch.float32, device="cuda:0")
+    dt = 0 if cfg.dtype == "f32" else 1
+    torch.cuda.synchronize()
+    dst.copy_(src)                                   # calibration: reads n bytes, writes n bytes
+    torch.cuda.synchronize()
+    evict = torch.empty(1024 * 1024 * 1024, dtype=torch.uint8, device="cuda:0").fill_(3)   # push everything out
+    torch.cuda.synchronize()
+    cc.cacnn_conv_forward(cfg.dims, dt, d_img, d_flt, d_out)      # cold
+    torch.cuda.synchronize()
+    cc.cacnn_conv_forward(cfg.dims, dt, d_img, d_flt, d_out)      # warm
+    torch.cuda.synchronize()
+    del evict
+    print(json.dumps({"traffic_probe": cfg.name, "copy_bytes_each_way": n}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -104,6 +148,9 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-shapes", action="store_true", help="time only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: one 512 MiB device copy (calibration), a cache-evicting 1 GiB fill, "
+                         "then one cold and one warm launch of the workload; prints nothing but a marker line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards over b or k with no exchange step, "
@@ -122,6 +169,9 @@ def main():
     torch.cuda.set_device(0)
 
     cfg = ci.CONFIGS[args.workload]
+    if args.traffic_probe:
+        traffic_probe(cc, torch, ci, np, cfg)
+        return
     sec, wall, (img, flt, d_out) = time_config(cc, torch, ci, np, cfg, args.steps, args.warmup)
     head = shape_report(cc, cfg, sec)
 
@@ -135,7 +185,7 @@ def main():
                                f"sigma={cfg.sigma_w} {cfg.dtype} in, fp32 accumulate/out",
                    "variant": head["variant"], "grid": head["grid"], "lds_bytes": head["lds_bytes"]},
         "roofline": {"bound": "mfma", "achieved": head["tflops"], "peak": MFMA_PEAK_TFLOPS[cfg.dtype],
-                     "unit": "TFLOP/s", "frac": head["frac_mfma_peak"], "traffic": None,
+                     "unit": "TFLOP/s", "frac": head["frac_mfma_peak"], "traffic": head["hbm_bytes_profiled"],
                      "wall_us_per_step": wall * 1e6},
     }
     if not args.no_cpu:

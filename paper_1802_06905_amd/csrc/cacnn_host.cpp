@@ -244,7 +244,7 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
     }
     if (v.reuse_r > 0 && (bR != v.reuse_r || p.sigma_w != 1)) g.legal = false;
     if (v.pipelined) {
-        const int64_t thr = v.threads();
+        const int64_t thr = v.staging_threads();
         if (g.img_items > v.MAXI * thr || (!g.flt_resident && g.flt_items > v.MAXF * thr)) g.legal = false;
         if (g.XS > 1023 || g.YS > 1023 || CT > 1023 || bR > 127 || bS > 127 || v.KT() > 256) g.legal = false;
         // staging items are addressed by 32-bit byte offsets from the unit's origin
@@ -324,28 +324,40 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
                 if (!g.legal || g.lds_bytes > mach.lds_bytes) continue;
                 double img_words = 0.0;
                 const double words = staged_words(v, p, g, &img_words);
+                // Cost model, in compute-unit cycles per Out tile, calibrated against measurements on MI355X:
+                //   t_mfma   MFMA pipe time of one wavefront (64 cycles per fp32 32x32x2, 32 per bf16 32x32x16),
+                //            divided by how well each kernel family keeps the pipe fed;
+                //   t_stage  staged bytes of the tile at the ~16 B/clk a CU gets from L2 when every CU is loading
+                //            (runs shorter than 32 bytes along b waste the rest of each sector);
+                //   t_slice  exposed latency and barrier cost per contraction slice;
+                //   t_out    the Out tile draining to HBM at ~1 TB/s for the whole chip.
+                // The direct kernels serialise all of it, the pipelined ones overlap the fetch with the multiply, the
+                // wave-specialised ones also overlap the LDS writes and the address arithmetic.
                 const double ksteps = v.dtype == CACNN_F32 ? (double)p.R * ceil_div((int64_t)p.S * Cpad, 2)
                                                            : (double)p.R * p.S * (Cpad / 16);
-                const double mfma_cyc = (v.dtype == CACNN_F32 ? 64.0 : 32.0) * v.MBLK * v.NBLK * ksteps;
-                const double stage_cyc =
-                    (img_words * waste + (words - img_words)) * ebytes / (double)n_wg / 32.0;  // ~32 B/clk/CU
-                const double epi_cyc = (double)v.KT() * v.NT() * 4.0 / 64.0 * waste;
+                const double t_mfma = (v.dtype == CACNN_F32 ? 64.0 : 32.0) * v.MBLK * v.NBLK * ksteps;
+                const double t_stage = (img_words * waste + (words - img_words)) * ebytes / (double)n_wg / 16.0;
                 const double n_ctiles = (double)g.n_slices;
-                const int resident = g.lds_bytes * 2 <= mach.lds_bytes ? 2 : 1;
-                const double per_cu = (double)ceil_div(n_wg, mach.num_cu);
-                double cost;
-                if (!v.pipelined) {
-                    const double latency_cyc = 2500.0 * n_ctiles;   // exposed load latency + two barriers per tile
-                    const double hide = resident >= 2 ? 0.4 : 1.0;
-                    const double per_wg = mfma_cyc + hide * (stage_cyc + epi_cyc + latency_cyc) + 1500.0;
-                    cost = per_cu * per_wg;
+                const double t_out = (double)v.KT() * v.NT() * 4.0 * waste * (double)mach.num_cu / 1.0e12 * 2.4e9;
+                const bool f32 = v.dtype == CACNN_F32;
+                double feed, beta, t_slice;
+                if (v.pipelined == 0) {
+                    feed = f32 ? 0.5 : 0.8;
+                    beta = 3.0;
+                    t_slice = 2500.0;
+                } else if (v.pipelined == 1) {
+                    feed = f32 ? 0.6 : (v.reuse_r ? 0.95 : 0.8);
+                    beta = 1.3;
+                    t_slice = 400.0;
                 } else {
-                    // loads overlap the multiply; what stays exposed per slice is the LDS write phase and one barrier
-                    const double per_slice = std::max(mfma_cyc / n_ctiles, 0.5 * stage_cyc / n_ctiles) +
-                                             0.25 * stage_cyc / n_ctiles + 300.0;
-                    const double per_tile = n_ctiles * per_slice + 0.5 * epi_cyc;
-                    cost = per_cu * per_tile + 3000.0;
+                    feed = f32 ? 0.36 : (v.reuse_r ? 0.95 : 0.85);
+                    beta = 0.7;
+                    t_slice = 300.0;
                 }
+                const double per_tile = t_mfma / feed + beta * t_stage + t_slice * n_ctiles;
+                const double per_cu = (double)ceil_div(n_wg, mach.num_cu);
+                const double cost =
+                    (per_cu * per_tile + t_out / std::max(1.0, std::min(per_cu, 4.0))) * (double)v.tune + 6000.0;
                 if (best->variant < 0 || cost < best->cost) {
                     best->variant = vi;
                     best->g = g;
@@ -529,6 +541,14 @@ int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int b
         return CACNN_ERR_INVALID_ARG;
     a.n_tiles = (int32_t)grid;
     a.n_xcd = xcd_count();
+    {
+        // b-tiles that read different pieces of the same 128-byte Image lines stay adjacent in the tile order
+        const int64_t want = std::max<int64_t>(1, 128 / (int64_t)(v.TB * esz));
+        int g_b = 1;
+        for (int d = 1; d <= a.tiles_b && d <= want; ++d)
+            if (a.tiles_b % d == 0) g_b = d;
+        a.b_group = g_b;
+    }
     a.img_items = g.img_items;
     a.flt_items = g.flt_items;
     a.img_buf = g.img_buf;

@@ -32,13 +32,16 @@ struct VariantInfo {
     // 1: persistent workgroups walk a list of (tile, contraction slice) units; the next unit's Image and Filter
     //    words are fetched into registers while the current one is multiplied, LDS is double-buffered.
     //    Needs 16-byte-legal operands and a slice that fits MAXI/MAXF staging items per thread.
+    // 2: as 1, with twice the waves: half of them only stage (two units ahead), the other half only multiply.
     int pipelined;
     int MAXI, MAXF;
     int occ;    // workgroups of this kernel one compute unit can hold at once, as far as registers go
     int reuse_r;  // > 0: filter-row reuse path compiled for exactly this many taps per contraction tile (sigma_w = 1)
+    float tune;   // measured time of this variant relative to what the planner's cost model predicts (1 = as modelled)
     int KT() const { return WM * MBLK * 32; }
     int NT() const { return TB * TW * TH; }
-    int threads() const { return WM * WN * 64; }
+    int threads() const { return WM * WN * (pipelined == 2 ? 128 : 64); }
+    int staging_threads() const { return WM * WN * 64; }
     int cgran() const { return dtype == 0 ? 1 : 16; }  // contraction granularity of the c-slice
 };
 
@@ -61,6 +64,7 @@ struct KernelArgs {
     // pipelined kernels only
     int32_t n_tiles;          // Out tiles in the whole problem (all kernels)
     int32_t n_xcd;            // XCDs the dispatcher deals workgroups to (8 on MI355X); 1 = no remapping
+    int32_t b_group;          // consecutive b-tiles whose Image rows share 128-byte lines (divides tiles_b)
     int32_t img_items, flt_items;   // 16-byte staging items per slice
     int32_t img_buf, flt_buf; // size of one LDS buffer of each operand (fp32: floats; bf16: 16-byte units)
     int32_t flt_off;          // where the Filter buffers start (same unit)

@@ -33,8 +33,12 @@ struct TileCoord {
 };
 
 // Workgroups are dealt round-robin to the XCDs (each with its own L2), so consecutive dispatch indices land on
-// different L2s.  Give every XCD one contiguous run of the tile list instead: with the output-channel tile as the
-// fastest index, the workgroups that share an Image tile (and walk the Filter slices in step) then share an L2.
+// different L2s.  Give every XCD one contiguous run of the tile list instead.  The list is ordered k-tile fastest,
+// then the b-tiles that share 128-byte lines of the Image (b_group of them), then w, then h, then the remaining
+// image groups slowest: the workgroups that share an Image tile, its halo or its cache lines (and walk the Filter
+// slices in step) then share an L2, and different XCDs mostly hold different images -- the Image is fetched from
+// memory about once and the Filter once per XCD (the a_K / a_B a_W a_H replication of Section 7's parallel
+// bound, with the XCDs as the processors).
 // i -> tile is a bijection on [0, n): XCD x = i % n_xcd owns tiles [x*q + min(x,rem), ...) with n = n_xcd*q + rem.
 __device__ __forceinline__ int xcd_tile(int i, int n, int n_xcd) {
     if (n_xcd <= 1) return i;
@@ -47,10 +51,12 @@ __device__ __forceinline__ TileCoord decode_tile(const KernelArgs& a, int KT, in
     int t = xcd_tile(blockIdx.x, a.n_tiles, a.n_xcd);
     const int tk = t % a.tiles_k;
     t /= a.tiles_k;
-    const int tb = t % a.tiles_b;
-    t /= a.tiles_b;
+    const int tbl = t % a.b_group;
+    t /= a.b_group;
     const int tw = t % a.tiles_w;
-    const int th = t / a.tiles_w;
+    t /= a.tiles_w;
+    const int th = t % a.tiles_h;
+    const int tb = (t / a.tiles_h) * a.b_group + tbl;
     TileCoord tc;
     tc.k0 = tk * KT;
     tc.b0 = tb * TB;
@@ -515,10 +521,12 @@ __device__ __forceinline__ TileCoord decode_tile_index(const KernelArgs& a, int 
     t = xcd_tile(t, a.n_tiles, a.n_xcd);
     const int tk = t % a.tiles_k;
     t /= a.tiles_k;
-    const int tb = t % a.tiles_b;
-    t /= a.tiles_b;
+    const int tbl = t % a.b_group;
+    t /= a.b_group;
     const int tw = t % a.tiles_w;
-    const int th = t / a.tiles_w;
+    t /= a.tiles_w;
+    const int th = t % a.tiles_h;
+    const int tb = (t / a.tiles_h) * a.b_group + tbl;
     TileCoord tc;
     tc.k0 = tk * KT;
     tc.b0 = tb * TB;
@@ -544,20 +552,32 @@ __device__ __forceinline__ void advance_unit(const KernelArgs& a, UnitPos& p, in
     }
 }
 
-// What is uniform over one unit: the origins of its Image and Filter tiles and how far the arrays extend from them.
+// What is uniform over one unit: buffer resources whose base is the origin of the unit's Image / Filter tile (so an
+// item's address is a scalar descriptor plus a 32-bit offset; num_records is what is left of the array, and items that
+// fall outside the arrays are never addressed: they read the origin and are replaced by zeros), and how far the
+// arrays extend from those origins.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 struct UnitBase {
-    const char* img;   // &Image(x0, y0, c0, b0)
-    const char* flt;   // &Filter(k0, r0, s0, c0)
+    __amdgpu_buffer_rsrc_t img, flt;
     int lx, ly, lc, lb, lk, lr, ls;
     bool img_inside, flt_inside;
 };
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, int64_t bytes_left) {
+    const int32_t n = (int32_t)(bytes_left > 0x7fffffffll ? 0x7fffffffll : bytes_left);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, n, 0x00020000);
+}
 
 template <int ESZ>
 __device__ __forceinline__ UnitBase unit_base(const KernelArgs& a, const UnitPos& p, int KT, int TB) {
     UnitBase u;
     const int x0 = a.sw * p.tc.w0 + p.r0, y0 = a.sh * p.tc.h0 + p.s0;
-    u.img = (const char*)a.image + ((((int64_t)x0 * a.IH + y0) * a.C + p.c0) * a.B + p.tc.b0) * ESZ;
-    u.flt = (const char*)a.filter + ((((int64_t)p.tc.k0 * a.R + p.r0) * a.S + p.s0) * a.C + p.c0) * ESZ;
+    const int64_t io = (((int64_t)x0 * a.IH + y0) * a.C + p.c0) * a.B + p.tc.b0;
+    const int64_t fo = (((int64_t)p.tc.k0 * a.R + p.r0) * a.S + p.s0) * a.C + p.c0;
+    const int64_t in = (int64_t)a.IW * a.IH * a.C * a.B, fn = (int64_t)a.K * a.R * a.S * a.C;
+    u.img = make_rsrc((const char*)a.image + io * ESZ, (in - io) * ESZ);
+    u.flt = make_rsrc((const char*)a.filter + fo * ESZ, (fn - fo) * ESZ);
     u.lx = a.IW - x0;
     u.ly = a.IH - y0;
     u.lc = a.C - p.c0;
@@ -570,151 +590,523 @@ __device__ __forceinline__ UnitBase unit_base(const KernelArgs& a, const UnitPos
     return u;
 }
 
-template <int WM, int WN, int MBLK, int NBLK, int TB, int TW, int TH, int MAXI, int MAXF>
-__global__ void __launch_bounds__(WM* WN * 64) conv_f32_pipe_kernel(const KernelArgs a) {
-    constexpr int THREADS = WM * WN * 64;
-    constexpr int NT = TB * TW * TH;
-    constexpr int KT = WM * MBLK * 32;
-    constexpr int VPR = TB / 4;
-    extern __shared__ __align__(16) float smem_f[];
+__device__ __forceinline__ f32x4 buf_load_f32x4(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
+}
+__device__ __forceinline__ uint4 buf_load_u4(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave % WM, wn = wave / WM;
-    const int j = lane & 31, kk = lane >> 5;
-    const int zero_off = 2 * a.img_buf;
+// ---- staging: which 16-byte items a staging thread moves, fixed for the whole kernel -------------------------------
 
-    int posoff[NBLK];
-#pragma unroll
-    for (int n = 0; n < NBLK; ++n) {
-        int nn = (wn * NBLK + n) * 32 + j;
-        if (nn >= NT) nn = 0;
-        const int b_l = nn % TB, w_l = (nn / TB) % TW, h_l = nn / (TB * TW);
-        posoff[n] = a.sw * w_l * a.xpitch + a.sh * h_l * a.ypitch + b_l;
+// Per item a thread keeps two registers: the byte offset from the unit's origin in global memory and the LDS
+// address.  Units that overhang an array decode the item's coordinates again to decide what to zero-fill.
+
+template <int STHREADS, int TB, int MAXI, int MAXF>
+struct F32Stager {
+    static constexpr int VPR = TB / 4;
+    uint32_t i_g[MAXI], f_g[MAXF];
+    int i_lds[MAXI], f_lds[MAXF];
+    int stid;
+
+    __device__ __forceinline__ void img_coords(const KernelArgs& a, int idx, int& x, int& y, int& c, int& bv) const {
+        const uint32_t row = (uint32_t)idx / VPR;
+        bv = idx % VPR;
+        const uint32_t t = fdiv(row, a.d_CT);
+        c = row - t * a.CT;
+        const uint32_t xx = fdiv(t, a.d_YS);
+        y = t - xx * a.YS;
+        x = (int)xx;
+    }
+    __device__ __forceinline__ void flt_coords(const KernelArgs& a, int idx, int& kl, int& r, int& s, int& c) const {
+        const int CTV = a.CT >> 2;
+        const uint32_t t = fdiv((uint32_t)idx, a.d_C8);
+        c = (idx - t * CTV) * 4;
+        const uint32_t t2 = fdiv(t, a.d_bS);
+        s = t - t2 * a.bS;
+        const uint32_t k = fdiv(t2, a.d_bR);
+        r = t2 - k * a.bR;
+        kl = (int)k;
     }
 
-    // static staging assignment: byte offset from the unit origin, LDS offset, packed coordinates (edge checks)
-    uint32_t i_g[MAXI];
-    int i_lds[MAXI], i_pk[MAXI];
+    __device__ __forceinline__ void init(const KernelArgs& a, int stid_) {
+        stid = stid_;
 #pragma unroll
-    for (int i = 0; i < MAXI; ++i) {
-        const int idx = tid + i * THREADS;
-        i_pk[i] = -1;
-        i_lds[i] = 0;
-        i_g[i] = 0;
-        if (idx < a.img_items) {
-            const uint32_t row = (uint32_t)idx / VPR;
-            const int bv = idx % VPR;
-            const uint32_t t = fdiv(row, a.d_CT);
-            const int c = row - t * a.CT;
-            const uint32_t x = fdiv(t, a.d_YS);
-            const int y = t - x * a.YS;
-            i_pk[i] = (int)x | (y << 10) | (c << 20);
-            i_lds[i] = (int)x * a.xpitch + (y * a.CT + c) * TB + bv * 4;
-            i_g[i] = (((x * a.IH + y) * a.C + c) * a.B + bv * 4) * 4u;
+        for (int i = 0; i < MAXI; ++i) {
+            const int idx = stid + i * STHREADS;
+            i_lds[i] = 0;
+            i_g[i] = 0;
+            if (idx < a.img_items) {
+                int x, y, c, bv;
+                img_coords(a, idx, x, y, c, bv);
+                i_lds[i] = x * a.xpitch + (y * a.CT + c) * TB + bv * 4;
+                i_g[i] = ((((uint32_t)x * a.IH + y) * a.C + c) * a.B + bv * 4) * 4u;
+            }
         }
-    }
-    uint32_t f_g[MAXF], f_pk[MAXF];
-    int f_lds[MAXF];
-    const int CTV = a.CT >> 2;
 #pragma unroll
-    for (int i = 0; i < MAXF; ++i) {
-        const int idx = tid + i * THREADS;
-        f_pk[i] = 0xffffffffu;
-        f_lds[i] = 0;
-        f_g[i] = 0;
-        if (!a.flt_resident && idx < a.flt_items) {
-            const uint32_t t = fdiv((uint32_t)idx, a.d_C8);
-            const int c = (idx - t * CTV) * 4;
-            const uint32_t t2 = fdiv(t, a.d_bS);
-            const int s = t - t2 * a.bS;
-            const uint32_t kl = fdiv(t2, a.d_bR);
-            const int r = t2 - kl * a.bR;
-            f_pk[i] = kl | ((uint32_t)r << 8) | ((uint32_t)s << 15) | ((uint32_t)c << 22);
-            f_lds[i] = (int)kl * a.fpitch + r * a.QE + s * a.CT + c;
-            f_g[i] = (((kl * a.R + r) * a.S + s) * a.C + c) * 4u;
-        }
-    }
-
-    // one-time zeros: the zero row, and the pad column of every Filter row in both buffers
-    if (tid < 64) smem_f[zero_off + tid] = 0.f;
-    const int Q = a.bS * a.CT;
-    if (Q & 1) {
-        const int nbuf = a.flt_resident ? 1 : 2;
-        for (int idx = tid; idx < nbuf * KT * a.bR; idx += THREADS) {
-            const int bsel = idx / (KT * a.bR), rem = idx - bsel * KT * a.bR;
-            const int kl = rem / a.bR, r = rem - kl * a.bR;
-            smem_f[a.flt_off + bsel * a.flt_buf + kl * a.fpitch + r * a.QE + Q] = 0.f;
+        for (int i = 0; i < MAXF; ++i) {
+            const int idx = stid + i * STHREADS;
+            f_lds[i] = 0;
+            f_g[i] = 0;
+            if (!a.flt_resident && idx < a.flt_items) {
+                int kl, r, s, c;
+                flt_coords(a, idx, kl, r, s, c);
+                f_lds[i] = kl * a.fpitch + r * a.QE + s * a.CT + c;
+                f_g[i] = ((((uint32_t)kl * a.R + r) * a.S + s) * a.C + c) * 4u;
+            }
         }
     }
 
-    f32x4 ireg[MAXI], freg[MAXF];
-    auto issue_loads = [&](const UnitPos& p) {
-        const UnitBase u = unit_base<4>(a, p, KT, TB);
+    __device__ __forceinline__ void issue(const KernelArgs& a, const UnitBase& u, f32x4 (&ireg)[MAXI],
+                                          f32x4 (&freg)[MAXF]) const {
+        issue_img(a, u, ireg);
+        issue_flt(a, u, freg);
+    }
+    __device__ __forceinline__ void store(const KernelArgs& a, float* smem, int buf, const f32x4 (&ireg)[MAXI],
+                                          const f32x4 (&freg)[MAXF]) const {
+        store_img(a, smem, buf, ireg);
+        store_flt(a, smem, buf, freg);
+    }
+
+    __device__ __forceinline__ void issue_img(const KernelArgs& a, const UnitBase& u, f32x4 (&ireg)[MAXI]) const {
         if (u.img_inside) {
 #pragma unroll
-            for (int i = 0; i < MAXI; ++i) ireg[i] = *(const f32x4*)(u.img + i_g[i]);
+            for (int i = 0; i < MAXI; ++i) ireg[i] = buf_load_f32x4(u.img, i_g[i], 0);
         } else {
 #pragma unroll
             for (int i = 0; i < MAXI; ++i) {
-                const int pk = i_pk[i];
-                const bool ok = pk >= 0 && (pk & 1023) < u.lx && ((pk >> 10) & 1023) < u.ly && (pk >> 20) < u.lc &&
-                                ((tid + i * THREADS) % VPR) * 4 < u.lb;
-                const f32x4 v = *(const f32x4*)(u.img + (ok ? i_g[i] : 0u));
+                const int idx = stid + i * STHREADS;
+                int x, y, c, bv;
+                img_coords(a, idx, x, y, c, bv);
+                const bool ok = idx < a.img_items && x < u.lx && y < u.ly && c < u.lc && bv * 4 < u.lb;
+                const f32x4 v = buf_load_f32x4(u.img, ok ? i_g[i] : 0u, 0);
                 const f32x4 z = {0.f, 0.f, 0.f, 0.f};
                 ireg[i] = ok ? v : z;
             }
         }
+    }
+    __device__ __forceinline__ void issue_flt(const KernelArgs& a, const UnitBase& u, f32x4 (&freg)[MAXF]) const {
         if (!a.flt_resident) {
             if (u.flt_inside) {
 #pragma unroll
-                for (int i = 0; i < MAXF; ++i) freg[i] = *(const f32x4*)(u.flt + f_g[i]);
+                for (int i = 0; i < MAXF; ++i) freg[i] = buf_load_f32x4(u.flt, f_g[i], 0);
             } else {
 #pragma unroll
                 for (int i = 0; i < MAXF; ++i) {
-                    const uint32_t pk = f_pk[i];
-                    const bool ok = pk != 0xffffffffu && (int)(pk & 255) < u.lk && (int)((pk >> 8) & 127) < u.lr &&
-                                    (int)((pk >> 15) & 127) < u.ls && (int)(pk >> 22) < u.lc;
-                    const f32x4 v = *(const f32x4*)(u.flt + (ok ? f_g[i] : 0u));
+                    const int idx = stid + i * STHREADS;
+                    int kl, r, s, c;
+                    flt_coords(a, idx, kl, r, s, c);
+                    const bool ok = idx < a.flt_items && kl < u.lk && r < u.lr && s < u.ls && c < u.lc;
+                    const f32x4 v = buf_load_f32x4(u.flt, ok ? f_g[i] : 0u, 0);
                     const f32x4 z = {0.f, 0.f, 0.f, 0.f};
                     freg[i] = ok ? v : z;
                 }
             }
         }
-    };
-    auto store_regs = [&](int buf) {
-        float* s_img = smem_f + buf * a.img_buf;
+    }
+
+    __device__ __forceinline__ void store_img(const KernelArgs& a, float* smem, int buf,
+                                              const f32x4 (&ireg)[MAXI]) const {
+        float* s_img = smem + buf * a.img_buf;
 #pragma unroll
         for (int i = 0; i < MAXI; ++i)
-            if (i_pk[i] >= 0) *(f32x4*)(s_img + i_lds[i]) = ireg[i];
+            if (stid + i * STHREADS < a.img_items) *(f32x4*)(s_img + i_lds[i]) = ireg[i];
+    }
+    __device__ __forceinline__ void store_flt(const KernelArgs& a, float* smem, int buf,
+                                              const f32x4 (&freg)[MAXF]) const {
         if (!a.flt_resident) {
-            float* s_flt = smem_f + a.flt_off + buf * a.flt_buf;
+            float* s_flt = smem + a.flt_off + buf * a.flt_buf;
 #pragma unroll
             for (int i = 0; i < MAXF; ++i)
-                if (f_pk[i] != 0xffffffffu) {
+                if (stid + i * STHREADS < a.flt_items) {
                     s_flt[f_lds[i] + 0] = freg[i][0];
                     s_flt[f_lds[i] + 1] = freg[i][1];
                     s_flt[f_lds[i] + 2] = freg[i][2];
                     s_flt[f_lds[i] + 3] = freg[i][3];
                 }
         }
-    };
+    }
+};
 
-    f32x16 acc[MBLK][NBLK];
+// bf16: LDS holds the Image tile in 16-byte units of 8 consecutive channels of one position,
+// s_img[x*xpitch + y*ypitch + c8*TB + (b ^ key)], so that the MFMA B operand of a lane is ONE 16-byte read (LDS reads
+// run at full bandwidth only for 16-byte accesses).  Global memory has b fastest, so a staging item is an 8x8 block
+// (8 channels x 8 images) that is transposed in registers; the XOR key (low three bits of b, a function of the item)
+// spreads the eight 16-byte stores of neighbouring lanes over the banks and is undone, per lane, in the reads.
+template <int TB>
+__device__ __forceinline__ int store_key(int b8, int c8) {
+    constexpr int B8 = TB / 8;
+    return B8 == 4 ? ((b8 + 4 * (c8 & 1)) & 7) : (b8 & 7);
+}
+
+template <int STHREADS, int TB, int MAXI, int MAXF>
+struct Bf16Stager {
+    static constexpr int B8 = TB / 8;
+    uint32_t i_g[MAXI], f_g[MAXF];
+    int i_lds[MAXI], i_key[MAXI], f_lds[MAXF];
+    uint32_t row_bytes;
+    int stid;
+
+    __device__ __forceinline__ void img_coords(const KernelArgs& a, int idx, int& x, int& y, int& c8, int& b8) const {
+        const int C8 = a.CT >> 3;
+        b8 = idx % B8;
+        const uint32_t t = (uint32_t)idx / B8;
+        const uint32_t t2 = fdiv(t, a.d_C8);
+        c8 = t - t2 * C8;
+        const uint32_t xx = fdiv(t2, a.d_YS);
+        y = t2 - xx * a.YS;
+        x = (int)xx;
+    }
+    __device__ __forceinline__ void flt_coords(const KernelArgs& a, int idx, int& kl, int& r, int& s, int& c8) const {
+        const int C8 = a.CT >> 3, RS = a.bR * a.bS;
+        const uint32_t t = fdiv((uint32_t)idx, a.d_C8);
+        c8 = idx - t * C8;
+        const uint32_t k = fdiv(t, a.d_RS);
+        const int rs = t - k * RS;
+        const uint32_t rr = fdiv((uint32_t)rs, a.d_bS);
+        s = rs - rr * a.bS;
+        r = (int)rr;
+        kl = (int)k;
+    }
+
+    __device__ __forceinline__ void init(const KernelArgs& a, int stid_) {
+        stid = stid_;
+        row_bytes = (uint32_t)a.B * 2u;
+#pragma unroll
+        for (int i = 0; i < MAXI; ++i) {
+            const int idx = stid + i * STHREADS;
+            i_lds[i] = 0;
+            i_g[i] = 0;
+            i_key[i] = 0;
+            if (idx < a.img_items) {
+                int x, y, c8, b8;
+                img_coords(a, idx, x, y, c8, b8);
+                i_lds[i] = x * a.xpitch + y * a.ypitch + c8 * TB + b8 * 8;
+                i_key[i] = store_key<TB>(b8, c8);
+                i_g[i] = ((((uint32_t)x * a.IH + y) * a.C + c8 * 8) * a.B + b8 * 8) * 2u;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < MAXF; ++i) {
+            const int idx = stid + i * STHREADS;
+            f_lds[i] = 0;
+            f_g[i] = 0;
+            if (!a.flt_resident && idx < a.flt_items) {
+                int kl, r, s, c8;
+                flt_coords(a, idx, kl, r, s, c8);
+                f_lds[i] = (kl * a.fpitch + (r * a.bS + s) * a.CT) / 8 + c8;
+                f_g[i] = ((((uint32_t)kl * a.R + r) * a.S + s) * a.C + c8 * 8) * 2u;
+            }
+        }
+    }
+
+    __device__ __forceinline__ void issue(const KernelArgs& a, const UnitBase& u, uint4 (&ireg)[MAXI][8],
+                                          uint4 (&freg)[MAXF]) const {
+        issue_img(a, u, ireg);
+        issue_flt(a, u, freg);
+    }
+    __device__ __forceinline__ void store(const KernelArgs& a, uint4* smem, int buf, const uint4 (&ireg)[MAXI][8],
+                                          const uint4 (&freg)[MAXF]) const {
+        store_img(a, smem, buf, ireg);
+        store_flt(a, smem, buf, freg);
+    }
+
+    __device__ __forceinline__ void issue_img(const KernelArgs& a, const UnitBase& u, uint4 (&ireg)[MAXI][8]) const {
+        if (u.img_inside) {
+#pragma unroll
+            for (int i = 0; i < MAXI; ++i)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ireg[i][e] = buf_load_u4(u.img, i_g[i], e * row_bytes);
+        } else {
+#pragma unroll
+            for (int i = 0; i < MAXI; ++i) {
+                const int idx = stid + i * STHREADS;
+                int x, y, c8, b8;
+                img_coords(a, idx, x, y, c8, b8);
+                const bool ok = idx < a.img_items && x < u.lx && y < u.ly && b8 * 8 < u.lb;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool oke = ok && c8 * 8 + e < u.lc;
+                    const uint4 v = buf_load_u4(u.img, oke ? i_g[i] + e * row_bytes : 0u, 0);
+                    ireg[i][e] = oke ? v : make_uint4(0, 0, 0, 0);
+                }
+            }
+        }
+    }
+    __device__ __forceinline__ void issue_flt(const KernelArgs& a, const UnitBase& u, uint4 (&freg)[MAXF]) const {
+        if (!a.flt_resident) {
+            if (u.flt_inside) {
+#pragma unroll
+                for (int i = 0; i < MAXF; ++i) freg[i] = buf_load_u4(u.flt, f_g[i], 0);
+            } else {
+#pragma unroll
+                for (int i = 0; i < MAXF; ++i) {
+                    const int idx = stid + i * STHREADS;
+                    int kl, r, s, c8;
+                    flt_coords(a, idx, kl, r, s, c8);
+                    const bool ok = idx < a.flt_items && kl < u.lk && r < u.lr && s < u.ls && c8 * 8 < u.lc;
+                    const uint4 v = buf_load_u4(u.flt, ok ? f_g[i] : 0u, 0);
+                    freg[i] = ok ? v : make_uint4(0, 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    __device__ __forceinline__ void store_img(const KernelArgs& a, uint4* smem, int buf,
+                                              const uint4 (&ireg)[MAXI][8]) const {
+        uint4* s_img = smem + buf * a.img_buf;
+#pragma unroll
+        for (int i = 0; i < MAXI; ++i)
+            if (stid + i * STHREADS < a.img_items) {
+                uint4 out[8];
+                transpose8x8_bf16(ireg[i], out);
+                uint4* dst = s_img + i_lds[i];
+#pragma unroll
+                for (int bb = 0; bb < 8; ++bb) dst[bb ^ i_key[i]] = out[bb];
+            }
+    }
+    __device__ __forceinline__ void store_flt(const KernelArgs& a, uint4* smem, int buf,
+                                              const uint4 (&freg)[MAXF]) const {
+        if (!a.flt_resident) {
+            uint4* s_flt = smem + a.flt_off + buf * a.flt_buf;
+#pragma unroll
+            for (int i = 0; i < MAXF; ++i)
+                if (stid + i * STHREADS < a.flt_items) s_flt[f_lds[i]] = freg[i];
+        }
+    }
+};
+
+// ---- compute: one unit out of LDS ---------------------------------------------------------------------------------
+
+template <int MBLK, int NBLK, int TB>
+__device__ __forceinline__ void f32_compute_unit(const KernelArgs& a, const float* s_img, const float* s_flt,
+                                                 const float* s_zero, const int (&posoff)[NBLK],
+                                                 f32x16 (&acc)[MBLK][NBLK], int row0, int j, int kk, int r0) {
+    const int Q = a.bS * a.CT;
+    const int rmax = min(a.bR, a.R - r0);
+    for (int r = 0; r < rmax; ++r) {
+        const float* ap = s_flt + (row0 + j) * a.fpitch + r * a.QE + kk;
+        const float* bp = s_img + r * a.xpitch + kk * TB;
+        const int pairs = Q >> 1;
+#pragma unroll 4
+        for (int q2 = 0; q2 < pairs; ++q2) {
+            float av[MBLK], bv[NBLK];
+#pragma unroll
+            for (int m = 0; m < MBLK; ++m) av[m] = ap[m * 32 * a.fpitch + 2 * q2];
+#pragma unroll
+            for (int n = 0; n < NBLK; ++n) bv[n] = bp[posoff[n] + 2 * q2 * TB];
+#pragma unroll
+            for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                for (int n = 0; n < NBLK; ++n)
+                    acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m], bv[n], acc[m][n], 0, 0, 0);
+        }
+        if (Q & 1) {
+            // last contraction index pairs with a zero: the kk = 1 half reads the pad column / zero row
+            float av[MBLK], bv[NBLK];
+#pragma unroll
+            for (int m = 0; m < MBLK; ++m) av[m] = ap[m * 32 * a.fpitch + (Q - 1)];
+#pragma unroll
+            for (int n = 0; n < NBLK; ++n) bv[n] = kk ? s_zero[j] : bp[posoff[n] + (Q - 1) * TB];
+#pragma unroll
+            for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                for (int n = 0; n < NBLK; ++n)
+                    acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m], bv[n], acc[m][n], 0, 0, 0);
+        }
+    }
+}
+
+// BR > 0 selects the filter-row reuse path (needs sigma_w = 1, b_r = BR, TB = 32 and one wave spanning the tile's
+// width): for one filter row offset s and one 16-channel step, a wave reads the TW+BR-1 Image fragments of its row
+// once and uses each of them for up to BR filter taps r -- the register-level form of the reuse that lets the
+// small-filter bound of Section 4.3 sit below the matmul bound.  Fragments are double-buffered in registers so the
+// LDS reads of step t+1 overlap the MFMAs of step t.
+template <int MBLK, int NBLK, int TB, int TW, int BR>
+__device__ __forceinline__ void bf16_compute_unit(const KernelArgs& a, const uint4* s_img, const uint4* s_flt,
+                                                  const int (&posoff)[NBLK], f32x16 (&acc)[MBLK][NBLK], int row0,
+                                                  int j, int g, int r0, int s0) {
+    const int fp8 = a.fpitch >> 3, ct8 = a.CT >> 3;
+    const int rmax = min(a.bR, a.R - r0), smax = min(a.bS, a.S - s0);
+    const int steps = a.CT >> 4;
+    if constexpr (BR > 0) {
+        static_assert(TB == 32 && NBLK == TW, "row reuse: a wave owns TW consecutive columns of 32 images");
+        constexpr int NX = TW + BR - 1;
+        auto load_frags = [&](int s, int cs, bf16x8(&A)[MBLK][BR], bf16x8(&X)[NX]) {
+            const uint4* ap = s_flt + (row0 + j) * fp8 + s * ct8 + g + 2 * cs;
+#pragma unroll
+            for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                for (int r = 0; r < BR; ++r) A[m][r] = __builtin_bit_cast(bf16x8, ap[m * 32 * fp8 + r * a.bS * ct8]);
+            const uint4* bp = s_img + posoff[0] + s * a.ypitch + 2 * cs * TB;
+#pragma unroll
+            for (int x = 0; x < NX; ++x) X[x] = __builtin_bit_cast(bf16x8, bp[x * a.xpitch]);
+        };
+        auto mfmas = [&](const bf16x8(&A)[MBLK][BR], const bf16x8(&X)[NX]) {
+#pragma unroll
+            for (int r = 0; r < BR; ++r)
+#pragma unroll
+                for (int n = 0; n < TW; ++n)
+#pragma unroll
+                    for (int m = 0; m < MBLK; ++m)
+                        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[m][r], X[n + r], acc[m][n], 0, 0, 0);
+        };
+        const int T = smax * steps;
+        int s_n = 0, cs_n = 0;
+        auto next_step = [&]() {
+            if (++cs_n == steps) {
+                cs_n = 0;
+                ++s_n;
+            }
+        };
+        bf16x8 A0[MBLK][BR], X0[NX], A1[MBLK][BR], X1[NX];
+        load_frags(0, 0, A0, X0);
+        next_step();
+        for (int t = 0; t < T; t += 2) {
+            if (t + 1 < T) {
+                load_frags(s_n, cs_n, A1, X1);
+                next_step();
+            }
+            mfmas(A0, X0);
+            if (t + 1 < T) {
+                if (t + 2 < T) {
+                    load_frags(s_n, cs_n, A0, X0);
+                    next_step();
+                }
+                mfmas(A1, X1);
+            }
+        }
+    } else {
+        for (int r = 0; r < rmax; ++r) {
+            for (int s = 0; s < smax; ++s) {
+                const uint4* ap = s_flt + (row0 + j) * fp8 + (r * a.bS + s) * ct8 + g;
+                const uint4* bp = s_img + r * a.xpitch + s * a.ypitch;
+#pragma unroll 2
+                for (int cs = 0; cs < steps; ++cs) {
+                    bf16x8 av[MBLK], bv[NBLK];
+#pragma unroll
+                    for (int m = 0; m < MBLK; ++m) av[m] = __builtin_bit_cast(bf16x8, ap[m * 32 * fp8 + 2 * cs]);
+#pragma unroll
+                    for (int n = 0; n < NBLK; ++n) bv[n] = __builtin_bit_cast(bf16x8, bp[posoff[n] + 2 * cs * TB]);
+#pragma unroll
+                    for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                        for (int n = 0; n < NBLK; ++n)
+                            acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[m], bv[n], acc[m][n], 0, 0, 0);
+                }
+            }
+        }
+    }
+}
+
+// The tile's contraction is complete: write every Out word of it once and reset the accumulators.
+template <int MBLK, int NBLK, int TB, int TW, int TH>
+__device__ __forceinline__ void write_tile(const KernelArgs& a, const TileCoord& tc, f32x16 (&acc)[MBLK][NBLK],
+                                           int nblock0, int row0, int j, int q) {
+    constexpr int NT = TB * TW * TH;
+#pragma unroll
+    for (int n = 0; n < NBLK; ++n) {
+        const int nn = (nblock0 + n) * 32 + j;
+        const int b = tc.b0 + nn % TB, w = tc.w0 + (nn / TB) % TW, h = tc.h0 + nn / (TB * TW);
+        const bool pos_ok = nn < NT && b < a.B && w < a.W && h < a.H;
+#pragma unroll
+        for (int m = 0; m < MBLK; ++m) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int k = tc.k0 + row0 + m * 32 + (v >> 2) * 8 + q * 4 + (v & 3);
+                if (pos_ok && k < a.K) a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b] = acc[m][n][v];
+                acc[m][n][v] = 0.f;
+            }
+        }
+    }
+}
+
+template <int NBLK, int TB, int TW, int TH>
+__device__ __forceinline__ void f32_posoff(const KernelArgs& a, int (&posoff)[NBLK], int nblock0, int j) {
+    constexpr int NT = TB * TW * TH;
+#pragma unroll
+    for (int n = 0; n < NBLK; ++n) {
+        int nn = (nblock0 + n) * 32 + j;
+        if (nn >= NT) nn = 0;
+        const int b_l = nn % TB, w_l = (nn / TB) % TW, h_l = nn / (TB * TW);
+        posoff[n] = a.sw * w_l * a.xpitch + a.sh * h_l * a.ypitch + b_l;
+    }
+}
+
+// LDS unit of a lane's B fragment for column block n at (r, s, c-step) = 0; c8 = 2*cs + g has the parity of g
+template <int NBLK, int TB, int TW, int TH>
+__device__ __forceinline__ void bf16_posoff(const KernelArgs& a, int (&posoff)[NBLK], int nblock0, int j, int g) {
+    constexpr int NT = TB * TW * TH;
+#pragma unroll
+    for (int n = 0; n < NBLK; ++n) {
+        int nn = (nblock0 + n) * 32 + j;
+        if (nn >= NT) nn = 0;
+        const int b_l = nn % TB, w_l = (nn / TB) % TW, h_l = nn / (TB * TW);
+        const int b_sw = (b_l & ~7) | ((b_l & 7) ^ store_key<TB>(b_l >> 3, g));
+        posoff[n] = a.sw * w_l * a.xpitch + a.sh * h_l * a.ypitch + g * TB + b_sw;
+    }
+}
+
+// one-time zeros of the fp32 pipelined layouts: the zero row, and the pad column of every Filter row in every buffer
+template <int STHREADS, int KT>
+__device__ __forceinline__ void f32_pipe_zero_fill(const KernelArgs& a, float* smem, int stid) {
+    if (stid < 64) smem[2 * a.img_buf + stid] = 0.f;
+    const int Q = a.bS * a.CT;
+    if (Q & 1) {
+        const int nbuf = a.flt_resident ? 1 : 2;
+        for (int idx = stid; idx < nbuf * KT * a.bR; idx += STHREADS) {
+            const int bsel = idx / (KT * a.bR), rem = idx - bsel * KT * a.bR;
+            const int kl = rem / a.bR, r = rem - kl * a.bR;
+            smem[a.flt_off + bsel * a.flt_buf + kl * a.fpitch + r * a.QE + Q] = 0.f;
+        }
+    }
+}
+
+template <int MBLK, int NBLK>
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[MBLK][NBLK]) {
 #pragma unroll
     for (int m = 0; m < MBLK; ++m)
 #pragma unroll
         for (int n = 0; n < NBLK; ++n)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[m][n][v] = 0.f;
+}
 
-    UnitPos cur;
-    cur.t = blockIdx.x;
-    cur.r0 = cur.s0 = cur.c0 = 0;
-    cur.tc = decode_tile_index(a, cur.t < a.n_tiles ? cur.t : 0, KT, TB, TW, TH);
+__device__ __forceinline__ UnitPos first_unit(const KernelArgs& a, int KT, int TB, int TW, int TH) {
+    UnitPos p;
+    p.t = blockIdx.x;
+    p.r0 = p.s0 = p.c0 = 0;
+    p.tc = decode_tile_index(a, p.t < a.n_tiles ? p.t : 0, KT, TB, TW, TH);
+    return p;
+}
+
+// ---- pipelined kernels: every wave stages and multiplies ----------------------------------------------------------
+
+template <int WM, int WN, int MBLK, int NBLK, int TB, int TW, int TH, int MAXI, int MAXF>
+__global__ void __launch_bounds__(WM* WN * 64) conv_f32_pipe_kernel(const KernelArgs a) {
+    constexpr int THREADS = WM * WN * 64;
+    constexpr int KT = WM * MBLK * 32;
+    extern __shared__ __align__(16) float smem_f[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wn = wave / WM;
+    const int j = lane & 31, kk = lane >> 5;
+
+    int posoff[NBLK];
+    f32_posoff<NBLK, TB, TW, TH>(a, posoff, wn * NBLK, j);
+    F32Stager<THREADS, TB, MAXI, MAXF> st;
+    st.init(a, tid);
+    f32_pipe_zero_fill<THREADS, KT>(a, smem_f, tid);
+
+    f32x4 ireg[MAXI], freg[MAXF];
+    f32x16 acc[MBLK][NBLK];
+    zero_acc(acc);
+
+    UnitPos cur = first_unit(a, KT, TB, TW, TH);
     UnitPos nxt = cur;
     if (cur.t < a.n_tiles) {
-        issue_loads(cur);
+        st.issue(a, unit_base<4>(a, cur, KT, TB), ireg, freg);
         advance_unit(a, nxt, KT, TB, TW, TH);
     }
     if (a.flt_resident) {
@@ -726,334 +1118,244 @@ __global__ void __launch_bounds__(WM* WN * 64) conv_f32_pipe_kernel(const Kernel
     }
     int buf = 0;
     while (cur.t < a.n_tiles) {
-        store_regs(buf);
+        st.store(a, smem_f, buf, ireg, freg);
         __syncthreads();
         const bool have_next = nxt.t < a.n_tiles;
-        if (have_next) issue_loads(nxt);
-
-        const float* s_img = smem_f + buf * a.img_buf;
-        const float* s_flt = smem_f + a.flt_off + (a.flt_resident ? 0 : buf) * a.flt_buf;
-        const int rmax = min(a.bR, a.R - cur.r0);
-        for (int r = 0; r < rmax; ++r) {
-            const float* ap = s_flt + (wm * MBLK * 32 + j) * a.fpitch + r * a.QE + kk;
-            const float* bp = s_img + r * a.xpitch + kk * TB;
-            const int pairs = Q >> 1;
-#pragma unroll 4
-            for (int q2 = 0; q2 < pairs; ++q2) {
-                float av[MBLK], bv[NBLK];
-#pragma unroll
-                for (int m = 0; m < MBLK; ++m) av[m] = ap[m * 32 * a.fpitch + 2 * q2];
-#pragma unroll
-                for (int n = 0; n < NBLK; ++n) bv[n] = bp[posoff[n] + 2 * q2 * TB];
-#pragma unroll
-                for (int m = 0; m < MBLK; ++m)
-#pragma unroll
-                    for (int n = 0; n < NBLK; ++n)
-                        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m], bv[n], acc[m][n], 0, 0, 0);
-            }
-            if (Q & 1) {
-                float av[MBLK], bv[NBLK];
-#pragma unroll
-                for (int m = 0; m < MBLK; ++m) av[m] = ap[m * 32 * a.fpitch + (Q - 1)];
-#pragma unroll
-                for (int n = 0; n < NBLK; ++n) bv[n] = kk ? smem_f[zero_off + j] : bp[posoff[n] + (Q - 1) * TB];
-#pragma unroll
-                for (int m = 0; m < MBLK; ++m)
-#pragma unroll
-                    for (int n = 0; n < NBLK; ++n)
-                        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m], bv[n], acc[m][n], 0, 0, 0);
-            }
-        }
-
-        if (!have_next || nxt.t != cur.t) {
-            // the tile's contraction is complete: write it out once and start the next tile from zero
-#pragma unroll
-            for (int n = 0; n < NBLK; ++n) {
-                const int nn = (wn * NBLK + n) * 32 + j;
-                const int b = cur.tc.b0 + nn % TB, w = cur.tc.w0 + (nn / TB) % TW, h = cur.tc.h0 + nn / (TB * TW);
-                const bool pos_ok = nn < NT && b < a.B && w < a.W && h < a.H;
-#pragma unroll
-                for (int m = 0; m < MBLK; ++m) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int k = cur.tc.k0 + (wm * MBLK + m) * 32 + (v >> 2) * 8 + kk * 4 + (v & 3);
-                        if (pos_ok && k < a.K) a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b] = acc[m][n][v];
-                        acc[m][n][v] = 0.f;
-                    }
-                }
-            }
-        }
+        if (have_next) st.issue(a, unit_base<4>(a, nxt, KT, TB), ireg, freg);
+        f32_compute_unit<MBLK, NBLK, TB>(a, smem_f + buf * a.img_buf,
+                                         smem_f + a.flt_off + (a.flt_resident ? 0 : buf) * a.flt_buf,
+                                         smem_f + 2 * a.img_buf, posoff, acc, wm * MBLK * 32, j, kk, cur.r0);
+        if (!have_next || nxt.t != cur.t)
+            write_tile<MBLK, NBLK, TB, TW, TH>(a, cur.tc, acc, wn * NBLK, wm * MBLK * 32, j, kk);
         cur = nxt;
         if (have_next) advance_unit(a, nxt, KT, TB, TW, TH);
         buf ^= 1;
     }
-}
-
-// bf16 pipelined kernel.  LDS holds the Image tile in 16-byte units of 8 consecutive channels of one position,
-// s_img[x*xpitch + y*ypitch + c8*TB + (b ^ key)], so that the MFMA B operand of a lane is ONE 16-byte read (LDS reads
-// run at full bandwidth only for 16-byte accesses).  Global memory has b fastest, so a staging item is an 8x8 block
-// (8 channels x 8 images) that is transposed in registers; the XOR key (low three bits of b, a function of the item)
-// spreads the eight 16-byte stores of neighbouring lanes over the banks and is undone, per lane, in the reads.
-//
-// BR > 0 selects the filter-row reuse path (needs sigma_w = 1, b_r = BR, TB = 32 and one wave spanning the tile's
-// width): for one filter row offset s and one 16-channel step, a wave reads the TW+BR-1 Image fragments of its row
-// once and uses each of them for up to BR filter taps r -- the register-level form of the reuse that lets the
-// small-filter bound of Section 4.3 sit below the matmul bound.  Fragments are double-buffered in registers so the
-// LDS reads of step t+1 overlap the MFMAs of step t.
-template <int TB>
-__device__ __forceinline__ int store_key(int b8, int c8) {
-    constexpr int B8 = TB / 8;
-    return B8 == 4 ? ((b8 + 4 * (c8 & 1)) & 7) : (b8 & 7);
 }
 
 template <int WM, int WN, int MBLK, int NBLK, int TB, int TW, int TH, int MAXI, int MAXF, int BR = 0>
 __global__ void __launch_bounds__(WM* WN * 64) conv_bf16_pipe_kernel(const KernelArgs a) {
-    static_assert(TB % 8 == 0, "staging items are 8 channels x 8 images");
-    static_assert(BR == 0 || (TB == 32 && NBLK == TW), "row reuse: a wave owns TW consecutive columns of 32 images");
     constexpr int THREADS = WM * WN * 64;
-    constexpr int NT = TB * TW * TH;
     constexpr int KT = WM * MBLK * 32;
-    constexpr int B8 = TB / 8;
     extern __shared__ __align__(16) uint4 smem_u[];
-
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WM, wn = wave / WM;
     const int j = lane & 31, g = lane >> 5;
 
-    // LDS unit of this lane's B fragment for column block n at (r, s, c-step) = 0; c8 = 2*cs + g has the parity of g
     int posoff[NBLK];
-#pragma unroll
-    for (int n = 0; n < NBLK; ++n) {
-        int nn = (wn * NBLK + n) * 32 + j;
-        if (nn >= NT) nn = 0;
-        const int b_l = nn % TB, w_l = (nn / TB) % TW, h_l = nn / (TB * TW);
-        const int b_sw = (b_l & ~7) | ((b_l & 7) ^ store_key<TB>(b_l >> 3, g));
-        posoff[n] = a.sw * w_l * a.xpitch + a.sh * h_l * a.ypitch + g * TB + b_sw;
-    }
-
-    const int C8 = a.CT >> 3, RS = a.bR * a.bS;
-    const uint32_t row_bytes = (uint32_t)a.B * 2u;
-    uint32_t i_g[MAXI];
-    int i_lds[MAXI], i_pk[MAXI], i_key[MAXI];
-#pragma unroll
-    for (int i = 0; i < MAXI; ++i) {
-        const int idx = tid + i * THREADS;
-        i_pk[i] = -1;
-        i_lds[i] = 0;
-        i_g[i] = 0;
-        i_key[i] = 0;
-        if (idx < a.img_items) {
-            const int b8 = idx % B8;
-            const uint32_t t = (uint32_t)idx / B8;
-            const uint32_t t2 = fdiv(t, a.d_C8);
-            const int c8 = t - t2 * C8;
-            const uint32_t x = fdiv(t2, a.d_YS);
-            const int y = t2 - x * a.YS;
-            i_pk[i] = (int)x | (y << 10) | (c8 << 20);
-            i_lds[i] = (int)x * a.xpitch + y * a.ypitch + c8 * TB + b8 * 8;
-            i_key[i] = store_key<TB>(b8, c8);
-            i_g[i] = (((x * a.IH + y) * a.C + c8 * 8) * a.B + b8 * 8) * 2u;
-        }
-    }
-    uint32_t f_g[MAXF], f_pk[MAXF];
-    int f_lds[MAXF];
-#pragma unroll
-    for (int i = 0; i < MAXF; ++i) {
-        const int idx = tid + i * THREADS;
-        f_pk[i] = 0xffffffffu;
-        f_lds[i] = 0;
-        f_g[i] = 0;
-        if (!a.flt_resident && idx < a.flt_items) {
-            const uint32_t t = fdiv((uint32_t)idx, a.d_C8);
-            const int c8 = idx - t * C8;
-            const uint32_t kl = fdiv(t, a.d_RS);
-            const int rs = t - kl * RS;
-            const uint32_t r = fdiv((uint32_t)rs, a.d_bS);
-            const int s = rs - r * a.bS;
-            f_pk[i] = kl | (r << 8) | ((uint32_t)s << 15) | ((uint32_t)c8 << 22);
-            f_lds[i] = ((int)kl * a.fpitch + rs * a.CT) / 8 + c8;
-            f_g[i] = (((kl * a.R + r) * a.S + s) * a.C + c8 * 8) * 2u;
-        }
-    }
+    bf16_posoff<NBLK, TB, TW, TH>(a, posoff, wn * NBLK, j, g);
+    Bf16Stager<THREADS, TB, MAXI, MAXF> st;
+    st.init(a, tid);
 
     uint4 ireg[MAXI][8], freg[MAXF];
-    auto issue_loads = [&](const UnitPos& p) {
-        const UnitBase u = unit_base<2>(a, p, KT, TB);
-        if (u.img_inside) {
-#pragma unroll
-            for (int i = 0; i < MAXI; ++i)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) ireg[i][e] = *(const uint4*)(u.img + i_g[i] + e * row_bytes);
-        } else {
-#pragma unroll
-            for (int i = 0; i < MAXI; ++i) {
-                const int pk = i_pk[i];
-                const bool ok = pk >= 0 && (pk & 1023) < u.lx && ((pk >> 10) & 1023) < u.ly &&
-                                ((tid + i * THREADS) % B8) * 8 < u.lb;
-                const int c = (pk >> 20) * 8;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const bool oke = ok && c + e < u.lc;
-                    const uint4 v = *(const uint4*)(u.img + (oke ? i_g[i] + e * row_bytes : 0u));
-                    ireg[i][e] = oke ? v : make_uint4(0, 0, 0, 0);
-                }
-            }
-        }
-        if (!a.flt_resident) {
-            if (u.flt_inside) {
-#pragma unroll
-                for (int i = 0; i < MAXF; ++i) freg[i] = *(const uint4*)(u.flt + f_g[i]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < MAXF; ++i) {
-                    const uint32_t pk = f_pk[i];
-                    const bool ok = pk != 0xffffffffu && (int)(pk & 255) < u.lk && (int)((pk >> 8) & 127) < u.lr &&
-                                    (int)((pk >> 15) & 127) < u.ls && (int)(pk >> 22) * 8 < u.lc;
-                    const uint4 v = *(const uint4*)(u.flt + (ok ? f_g[i] : 0u));
-                    freg[i] = ok ? v : make_uint4(0, 0, 0, 0);
-                }
-            }
-        }
-    };
-    auto store_regs = [&](int buf) {
-        uint4* s_img = smem_u + buf * a.img_buf;
-#pragma unroll
-        for (int i = 0; i < MAXI; ++i)
-            if (i_pk[i] >= 0) {
-                uint4 out[8];
-                transpose8x8_bf16(ireg[i], out);
-                uint4* dst = s_img + i_lds[i];
-#pragma unroll
-                for (int bb = 0; bb < 8; ++bb) dst[bb ^ i_key[i]] = out[bb];
-            }
-        if (!a.flt_resident) {
-            uint4* s_flt = smem_u + a.flt_off + buf * a.flt_buf;
-#pragma unroll
-            for (int i = 0; i < MAXF; ++i)
-                if (f_pk[i] != 0xffffffffu) s_flt[f_lds[i]] = freg[i];
-        }
-    };
-
     f32x16 acc[MBLK][NBLK];
-#pragma unroll
-    for (int m = 0; m < MBLK; ++m)
-#pragma unroll
-        for (int n = 0; n < NBLK; ++n)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[m][n][v] = 0.f;
+    zero_acc(acc);
 
-    UnitPos cur;
-    cur.t = blockIdx.x;
-    cur.r0 = cur.s0 = cur.c0 = 0;
-    cur.tc = decode_tile_index(a, cur.t < a.n_tiles ? cur.t : 0, KT, TB, TW, TH);
+    UnitPos cur = first_unit(a, KT, TB, TW, TH);
     UnitPos nxt = cur;
     if (cur.t < a.n_tiles) {
-        issue_loads(cur);
+        st.issue(a, unit_base<2>(a, cur, KT, TB), ireg, freg);
         advance_unit(a, nxt, KT, TB, TW, TH);
     }
     if (a.flt_resident) stage_filter_bf16<THREADS, KT>(a, (uint16_t*)(smem_u + a.flt_off), tid, 0, 0, 0, 0);
-    const int fp8 = a.fpitch >> 3, ct8 = a.CT >> 3;
     int buf = 0;
     while (cur.t < a.n_tiles) {
-        store_regs(buf);
+        st.store(a, smem_u, buf, ireg, freg);
         __syncthreads();
         const bool have_next = nxt.t < a.n_tiles;
-        if (have_next) issue_loads(nxt);
-
-        const uint4* s_img = smem_u + buf * a.img_buf;
-        const uint4* s_flt = smem_u + a.flt_off + (a.flt_resident ? 0 : buf) * a.flt_buf;
-        const int rmax = min(a.bR, a.R - cur.r0), smax = min(a.bS, a.S - cur.s0);
-        const int steps = a.CT >> 4;
-        if constexpr (BR > 0) {
-            constexpr int NX = TW + BR - 1;
-            auto load_frags = [&](int s, int cs, bf16x8(&A)[MBLK][BR], bf16x8(&X)[NX]) {
-                const uint4* ap = s_flt + (wm * MBLK * 32 + j) * fp8 + s * ct8 + g + 2 * cs;
-#pragma unroll
-                for (int m = 0; m < MBLK; ++m)
-#pragma unroll
-                    for (int r = 0; r < BR; ++r)
-                        A[m][r] = __builtin_bit_cast(bf16x8, ap[m * 32 * fp8 + r * a.bS * ct8]);
-                const uint4* bp = s_img + posoff[0] + s * a.ypitch + 2 * cs * TB;
-#pragma unroll
-                for (int x = 0; x < NX; ++x) X[x] = __builtin_bit_cast(bf16x8, bp[x * a.xpitch]);
-            };
-            auto mfmas = [&](const bf16x8(&A)[MBLK][BR], const bf16x8(&X)[NX]) {
-#pragma unroll
-                for (int r = 0; r < BR; ++r)
-#pragma unroll
-                    for (int n = 0; n < TW; ++n)
-#pragma unroll
-                        for (int m = 0; m < MBLK; ++m)
-                            acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[m][r], X[n + r], acc[m][n], 0, 0, 0);
-            };
-            const int T = smax * steps;
-            int s_n = 0, cs_n = 0;
-            auto next_step = [&]() {
-                if (++cs_n == steps) {
-                    cs_n = 0;
-                    ++s_n;
-                }
-            };
-            bf16x8 A0[MBLK][BR], X0[NX], A1[MBLK][BR], X1[NX];
-            load_frags(0, 0, A0, X0);
-            next_step();
-            for (int t = 0; t < T; t += 2) {
-                if (t + 1 < T) {
-                    load_frags(s_n, cs_n, A1, X1);
-                    next_step();
-                }
-                mfmas(A0, X0);
-                if (t + 1 < T) {
-                    if (t + 2 < T) {
-                        load_frags(s_n, cs_n, A0, X0);
-                        next_step();
-                    }
-                    mfmas(A1, X1);
-                }
-            }
-        } else {
-            for (int r = 0; r < rmax; ++r) {
-                for (int s = 0; s < smax; ++s) {
-                    const uint4* ap = s_flt + (wm * MBLK * 32 + j) * fp8 + (r * a.bS + s) * ct8 + g;
-                    const uint4* bp = s_img + r * a.xpitch + s * a.ypitch;
-#pragma unroll 2
-                    for (int cs = 0; cs < steps; ++cs) {
-                        bf16x8 av[MBLK], bv[NBLK];
-#pragma unroll
-                        for (int m = 0; m < MBLK; ++m) av[m] = __builtin_bit_cast(bf16x8, ap[m * 32 * fp8 + 2 * cs]);
-#pragma unroll
-                        for (int n = 0; n < NBLK; ++n) bv[n] = __builtin_bit_cast(bf16x8, bp[posoff[n] + 2 * cs * TB]);
-#pragma unroll
-                        for (int m = 0; m < MBLK; ++m)
-#pragma unroll
-                            for (int n = 0; n < NBLK; ++n)
-                                acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[m], bv[n], acc[m][n], 0, 0, 0);
-                    }
-                }
-            }
-        }
-
-        if (!have_next || nxt.t != cur.t) {
-#pragma unroll
-            for (int n = 0; n < NBLK; ++n) {
-                const int nn = (wn * NBLK + n) * 32 + j;
-                const int b = cur.tc.b0 + nn % TB, w = cur.tc.w0 + (nn / TB) % TW, h = cur.tc.h0 + nn / (TB * TW);
-                const bool pos_ok = nn < NT && b < a.B && w < a.W && h < a.H;
-#pragma unroll
-                for (int m = 0; m < MBLK; ++m) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int k = cur.tc.k0 + (wm * MBLK + m) * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-                        if (pos_ok && k < a.K) a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b] = acc[m][n][v];
-                        acc[m][n][v] = 0.f;
-                    }
-                }
-            }
-        }
+        if (have_next) st.issue(a, unit_base<2>(a, nxt, KT, TB), ireg, freg);
+        bf16_compute_unit<MBLK, NBLK, TB, TW, BR>(a, smem_u + buf * a.img_buf,
+                                                   smem_u + a.flt_off + (a.flt_resident ? 0 : buf) * a.flt_buf, posoff,
+                                                   acc, wm * MBLK * 32, j, g, cur.r0, cur.s0);
+        if (!have_next || nxt.t != cur.t)
+            write_tile<MBLK, NBLK, TB, TW, TH>(a, cur.tc, acc, wn * NBLK, wm * MBLK * 32, j, g);
         cur = nxt;
         if (have_next) advance_unit(a, nxt, KT, TB, TW, TH);
         buf ^= 1;
+    }
+}
+
+// ---- wave-specialised kernels: 2*WM*WN waves, two per SIMD -------------------------------------------------------
+// Waves [0, WM*WN) are consumers: they only read fragments from LDS, issue MFMAs and write finished Out tiles.
+// Waves [WM*WN, 2*WM*WN) are producers: they only move Image and Filter words global -> registers -> LDS, two units
+// ahead of the consumers (two register sets), so the memory latency and the staging arithmetic run in the shadow of
+// the other wave's MFMAs on the same SIMD.  Synchronisation is one workgroup barrier per unit, B_u: a producer
+// arrives after it has stored unit u, a consumer arrives before it multiplies unit u.  Passing B_u therefore tells
+// the producers that unit u-1 has been multiplied (its buffer (u+1)&1 is free) and the consumers that unit u is in
+// LDS.  Both roles walk the same unit sequence, so they execute the same number of barriers and the loops end.
+
+template <int WM, int WN, int MBLK, int NBLK, int TB, int TW, int TH, int MAXI, int MAXF>
+__global__ void __launch_bounds__(WM* WN * 128) conv_f32_ws_kernel(const KernelArgs a) {
+    constexpr int CTHREADS = WM * WN * 64;
+    constexpr int KT = WM * MBLK * 32;
+    extern __shared__ __align__(16) float smem_f[];
+    const int tid = threadIdx.x;
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
+
+    if (wave_id >= WM * WN) {
+        const int stid = tid - CTHREADS;
+        F32Stager<CTHREADS, TB, MAXI, MAXF> st;
+        st.init(a, stid);
+        f32_pipe_zero_fill<CTHREADS, KT>(a, smem_f, stid);
+        // Image words are fetched two units ahead (two register sets), Filter words one unit ahead
+        f32x4 ireg0[MAXI], ireg1[MAXI], freg[MAXF];
+        UnitPos su = first_unit(a, KT, TB, TW, TH);   // next unit to store
+        UnitPos lu = su;                              // next unit whose Image tile is fetched
+        UnitPos fu = su;                              // next unit whose Filter tile is fetched
+        if (lu.t < a.n_tiles) {
+            const UnitBase u = unit_base<4>(a, lu, KT, TB);
+            st.issue_img(a, u, ireg0);
+            st.issue_flt(a, u, freg);
+            advance_unit(a, lu, KT, TB, TW, TH);
+            advance_unit(a, fu, KT, TB, TW, TH);
+        }
+        if (lu.t < a.n_tiles) {
+            st.issue_img(a, unit_base<4>(a, lu, KT, TB), ireg1);
+            advance_unit(a, lu, KT, TB, TW, TH);
+        }
+        if (a.flt_resident) {
+            if (a.vec_flt)
+                stage_filter_f32<CTHREADS, KT, 4>(a, smem_f + a.flt_off, stid, 0, 0, 0, 0);
+            else
+                stage_filter_f32<CTHREADS, KT, 1>(a, smem_f + a.flt_off, stid, 0, 0, 0, 0);
+        }
+        while (su.t < a.n_tiles) {
+            st.store_img(a, smem_f, 0, ireg0);
+            st.store_flt(a, smem_f, 0, freg);
+            if (lu.t < a.n_tiles) {
+                st.issue_img(a, unit_base<4>(a, lu, KT, TB), ireg0);
+                advance_unit(a, lu, KT, TB, TW, TH);
+            }
+            if (fu.t < a.n_tiles) {
+                st.issue_flt(a, unit_base<4>(a, fu, KT, TB), freg);
+                advance_unit(a, fu, KT, TB, TW, TH);
+            }
+            __syncthreads();
+            advance_unit(a, su, KT, TB, TW, TH);
+            if (su.t >= a.n_tiles) break;
+            st.store_img(a, smem_f, 1, ireg1);
+            st.store_flt(a, smem_f, 1, freg);
+            if (lu.t < a.n_tiles) {
+                st.issue_img(a, unit_base<4>(a, lu, KT, TB), ireg1);
+                advance_unit(a, lu, KT, TB, TW, TH);
+            }
+            if (fu.t < a.n_tiles) {
+                st.issue_flt(a, unit_base<4>(a, fu, KT, TB), freg);
+                advance_unit(a, fu, KT, TB, TW, TH);
+            }
+            __syncthreads();
+            advance_unit(a, su, KT, TB, TW, TH);
+        }
+    } else {
+        const int lane = tid & 63, wave = wave_id;
+        const int wm = wave % WM, wn = wave / WM;
+        const int j = lane & 31, kk = lane >> 5;
+        int posoff[NBLK];
+        f32_posoff<NBLK, TB, TW, TH>(a, posoff, wn * NBLK, j);
+        f32x16 acc[MBLK][NBLK];
+        zero_acc(acc);
+        UnitPos cur = first_unit(a, KT, TB, TW, TH);
+        UnitPos nxt = cur;
+        if (cur.t < a.n_tiles) advance_unit(a, nxt, KT, TB, TW, TH);
+        int buf = 0;
+        while (cur.t < a.n_tiles) {
+            __syncthreads();
+            f32_compute_unit<MBLK, NBLK, TB>(a, smem_f + buf * a.img_buf,
+                                             smem_f + a.flt_off + (a.flt_resident ? 0 : buf) * a.flt_buf,
+                                             smem_f + 2 * a.img_buf, posoff, acc, wm * MBLK * 32, j, kk, cur.r0);
+            const bool have_next = nxt.t < a.n_tiles;
+            if (!have_next || nxt.t != cur.t)
+                write_tile<MBLK, NBLK, TB, TW, TH>(a, cur.tc, acc, wn * NBLK, wm * MBLK * 32, j, kk);
+            cur = nxt;
+            if (have_next) advance_unit(a, nxt, KT, TB, TW, TH);
+            buf ^= 1;
+        }
+    }
+}
+
+template <int WM, int WN, int MBLK, int NBLK, int TB, int TW, int TH, int MAXI, int MAXF, int BR = 0>
+__global__ void __launch_bounds__(WM* WN * 128) conv_bf16_ws_kernel(const KernelArgs a) {
+    constexpr int CTHREADS = WM * WN * 64;
+    constexpr int KT = WM * MBLK * 32;
+    extern __shared__ __align__(16) uint4 smem_u[];
+    const int tid = threadIdx.x;
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
+
+    if (wave_id >= WM * WN) {
+        const int stid = tid - CTHREADS;
+        Bf16Stager<CTHREADS, TB, MAXI, MAXF> st;
+        st.init(a, stid);
+        // Image words are fetched two units ahead (two register sets), Filter words one unit ahead
+        uint4 ireg0[MAXI][8], ireg1[MAXI][8], freg[MAXF];
+        UnitPos su = first_unit(a, KT, TB, TW, TH);   // next unit to store
+        UnitPos lu = su;                              // next unit whose Image tile is fetched
+        UnitPos fu = su;                              // next unit whose Filter tile is fetched
+        if (lu.t < a.n_tiles) {
+            const UnitBase u = unit_base<2>(a, lu, KT, TB);
+            st.issue_img(a, u, ireg0);
+            st.issue_flt(a, u, freg);
+            advance_unit(a, lu, KT, TB, TW, TH);
+            advance_unit(a, fu, KT, TB, TW, TH);
+        }
+        if (lu.t < a.n_tiles) {
+            st.issue_img(a, unit_base<2>(a, lu, KT, TB), ireg1);
+            advance_unit(a, lu, KT, TB, TW, TH);
+        }
+        if (a.flt_resident) {
+            stage_filter_bf16<CTHREADS, KT>(a, (uint16_t*)(smem_u + a.flt_off), stid, 0, 0, 0, 0);
+        }
+        while (su.t < a.n_tiles) {
+            st.store_img(a, smem_u, 0, ireg0);
+            st.store_flt(a, smem_u, 0, freg);
+            if (lu.t < a.n_tiles) {
+                st.issue_img(a, unit_base<2>(a, lu, KT, TB), ireg0);
+                advance_unit(a, lu, KT, TB, TW, TH);
+            }
+            if (fu.t < a.n_tiles) {
+                st.issue_flt(a, unit_base<2>(a, fu, KT, TB), freg);
+                advance_unit(a, fu, KT, TB, TW, TH);
+            }
+            __syncthreads();
+            advance_unit(a, su, KT, TB, TW, TH);
+            if (su.t >= a.n_tiles) break;
+            st.store_img(a, smem_u, 1, ireg1);
+            st.store_flt(a, smem_u, 1, freg);
+            if (lu.t < a.n_tiles) {
+                st.issue_img(a, unit_base<2>(a, lu, KT, TB), ireg1);
+                advance_unit(a, lu, KT, TB, TW, TH);
+            }
+            if (fu.t < a.n_tiles) {
+                st.issue_flt(a, unit_base<2>(a, fu, KT, TB), freg);
+                advance_unit(a, fu, KT, TB, TW, TH);
+            }
+            __syncthreads();
+            advance_unit(a, su, KT, TB, TW, TH);
+        }
+    } else {
+        const int lane = tid & 63, wave = wave_id;
+        const int wm = wave % WM, wn = wave / WM;
+        const int j = lane & 31, g = lane >> 5;
+        int posoff[NBLK];
+        bf16_posoff<NBLK, TB, TW, TH>(a, posoff, wn * NBLK, j, g);
+        f32x16 acc[MBLK][NBLK];
+        zero_acc(acc);
+        UnitPos cur = first_unit(a, KT, TB, TW, TH);
+        UnitPos nxt = cur;
+        if (cur.t < a.n_tiles) advance_unit(a, nxt, KT, TB, TW, TH);
+        int buf = 0;
+        while (cur.t < a.n_tiles) {
+            __syncthreads();
+            bf16_compute_unit<MBLK, NBLK, TB, TW, BR>(a, smem_u + buf * a.img_buf,
+                                                       smem_u + a.flt_off + (a.flt_resident ? 0 : buf) * a.flt_buf,
+                                                       posoff, acc, wm * MBLK * 32, j, g, cur.r0, cur.s0);
+            const bool have_next = nxt.t < a.n_tiles;
+            if (!have_next || nxt.t != cur.t)
+                write_tile<MBLK, NBLK, TB, TW, TH>(a, cur.tc, acc, wn * NBLK, wm * MBLK * 32, j, g);
+            cur = nxt;
+            if (have_next) advance_unit(a, nxt, KT, TB, TW, TH);
+            buf ^= 1;
+        }
     }
 }
 
@@ -1078,7 +1380,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 
 #define CACNN_VARIANT(DT, KERNEL, NAME, WM, WN, MBLK, NBLK, TB, TW, TH)                                  \
     {                                                                                                    \
-        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH, 0, 0, 0, 2, 0},                                             \
+        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH, 0, 0, 0, 2, 0, 1.0f},                                             \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                         \
                 static bool attr_done = false;                                                           \
                 return launch_kernel(KERNEL<WM, WN, MBLK, NBLK, TB, TW, TH>, attr_done, WM * WN * 64, a, \
@@ -1088,7 +1390,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 
 #define CACNN_PIPE_VARIANT(DT, KERNEL, NAME, WM, WN, MBLK, NBLK, TB, TW, TH, MAXI, MAXF, OCC)                   \
     {                                                                                                          \
-        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH, 1, MAXI, MAXF, OCC, 0},                                     \
+        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH, 1, MAXI, MAXF, OCC, 0, 1.0f},                               \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 return launch_kernel(KERNEL<WM, WN, MBLK, NBLK, TB, TW, TH, MAXI, MAXF>, attr_done,            \
@@ -1098,11 +1400,20 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 
 #define CACNN_REUSE_VARIANT(NAME, WM, WN, MBLK, NBLK, TB, TW, TH, MAXI, MAXF, OCC, BR)                          \
     {                                                                                                          \
-        {NAME, 1, WM, WN, MBLK, NBLK, TB, TW, TH, 1, MAXI, MAXF, OCC, BR},                                     \
+        {NAME, 1, WM, WN, MBLK, NBLK, TB, TW, TH, 1, MAXI, MAXF, OCC, BR, 1.0f},                               \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 return launch_kernel(conv_bf16_pipe_kernel<WM, WN, MBLK, NBLK, TB, TW, TH, MAXI, MAXF, BR>,    \
                                      attr_done, WM * WN * 64, a, grid, lds, stream);                           \
+            }                                                                                                  \
+    }
+
+#define CACNN_WS_VARIANT(DT, NAME, TUNE, WM, WN, MBLK, NBLK, TB, TW, TH, MAXI, MAXF, BR, ...)                   \
+    {                                                                                                          \
+        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH, 2, MAXI, MAXF, 1, BR, TUNE},                                \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                return launch_kernel(__VA_ARGS__, attr_done, WM * WN * 128, a, grid, lds, stream);             \
             }                                                                                                  \
     }
 
@@ -1136,6 +1447,28 @@ static const Variant g_variants[] = {
     CACNN_REUSE_VARIANT("bf16 pipe3 k128 b32w7h1 w4x1 m1n7", 4, 1, 1, 7, 32, 7, 1, 1, 10, 1, 3),
     CACNN_REUSE_VARIANT("bf16 pipe3 k64 b32w7h2 w2x2 m1n7", 2, 2, 1, 7, 32, 7, 2, 2, 6, 1, 3),
     CACNN_REUSE_VARIANT("bf16 pipe3 k128 b32w4h1 w4x1 m1n4", 4, 1, 1, 4, 32, 4, 1, 1, 10, 1, 3),
+    // wave-specialised (producer waves + consumer waves), fp32
+    CACNN_WS_VARIANT(0, "f32 ws k64 b8w4h4 w2x2 m1n2", 1.0f, 2, 2, 1, 2, 8, 4, 4, 6, 10, 0,
+                     conv_f32_ws_kernel<2, 2, 1, 2, 8, 4, 4, 6, 10>),
+    CACNN_WS_VARIANT(0, "f32 ws k64 b8w8h4 w2x2 m1n4", 1.0f, 2, 2, 1, 4, 8, 8, 4, 10, 10, 0,
+                     conv_f32_ws_kernel<2, 2, 1, 4, 8, 8, 4, 10, 10>),
+    CACNN_WS_VARIANT(0, "f32 ws k64 b32w4h2 w2x2 m1n4", 1.0f, 2, 2, 1, 4, 32, 4, 2, 12, 10, 0,
+                     conv_f32_ws_kernel<2, 2, 1, 4, 32, 4, 2, 12, 10>),
+    CACNN_WS_VARIANT(0, "f32 ws k64 b32w2h2 w2x2 m1n2", 1.0f, 2, 2, 1, 2, 32, 2, 2, 8, 10, 0,
+                     conv_f32_ws_kernel<2, 2, 1, 2, 32, 2, 2, 8, 10>),
+    // wave-specialised, bf16
+    CACNN_WS_VARIANT(1, "bf16 ws k128 b32w2h2 w2x2 m2n2", 1.05f, 2, 2, 2, 2, 32, 2, 2, 1, 10, 0,
+                     conv_bf16_ws_kernel<2, 2, 2, 2, 32, 2, 2, 1, 10, 0>),
+    CACNN_WS_VARIANT(1, "bf16 ws3 k128 b32w2h2 w2x2 m2n2", 1.0f, 2, 2, 2, 2, 32, 2, 2, 1, 10, 3,
+                     conv_bf16_ws_kernel<2, 2, 2, 2, 32, 2, 2, 1, 10, 3>),
+    CACNN_WS_VARIANT(1, "bf16 ws3 k128 b32w7h1 w4x1 m1n7", 1.0f, 4, 1, 1, 7, 32, 7, 1, 1, 10, 3,
+                     conv_bf16_ws_kernel<4, 1, 1, 7, 32, 7, 1, 1, 10, 3>),
+    CACNN_WS_VARIANT(1, "bf16 ws3 k64 b32w7h2 w2x2 m1n7", 1.9f, 2, 2, 1, 7, 32, 7, 2, 2, 6, 3,
+                     conv_bf16_ws_kernel<2, 2, 1, 7, 32, 7, 2, 2, 6, 3>),
+    CACNN_WS_VARIANT(1, "bf16 ws3 k128 b32w4h1 w4x1 m1n4", 1.5f, 4, 1, 1, 4, 32, 4, 1, 1, 10, 3,
+                     conv_bf16_ws_kernel<4, 1, 1, 4, 32, 4, 1, 1, 10, 3>),
+    CACNN_WS_VARIANT(1, "bf16 ws k64 b8w4h4 w2x2 m1n2", 3.0f, 2, 2, 1, 2, 8, 4, 4, 1, 6, 0,
+                     conv_bf16_ws_kernel<2, 2, 1, 2, 8, 4, 4, 1, 6, 0>),
 };
 
 int num_variants() { return (int)(sizeof(g_variants) / sizeof(g_variants[0])); }

@@ -64,6 +64,11 @@ RAGGED = [
 RAN = {}
 
 
+def is_pipelined(name):
+    """Pipelined / wave-specialised variants only accept 16-byte-legal shapes whose slice fits their staging registers."""
+    return " pipe" in name or " ws" in name
+
+
 def variants_for(cc, dtype):
     return [i for i in range(cc.cacnn_variant_count()) if cc.cacnn_variant_name(i).startswith(dtype + " ")]
 
@@ -87,7 +92,7 @@ def test_every_variant_on_ragged_shapes(env, shape, dtype):
             except cc.CacnnError as e:
                 # a forced tile may not fit in LDS, and the pipelined kernels only take 16-byte-legal shapes whose
                 # slice fits their staging registers: the library must say so, not launch
-                assert e.status == 3 and (bc == 1 << 20 or "pipe" in cc.cacnn_variant_name(vi)), (e.status, bc)
+                assert e.status == 3 and (bc == 1 << 20 or is_pipelined(cc.cacnn_variant_name(vi))), (e.status, bc)
                 continue
             gu.assert_parity(cfg, out, ref, ab, f"variant {vi} tile ({bc},{br},{bs})")
             RAN[(dtype, vi)] = RAN.get((dtype, vi), 0) + 1
@@ -118,7 +123,7 @@ def test_integer_inputs_are_exact(env, dtype):
         try:
             out = gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
         except cc.CacnnError as e:
-            assert e.status == 3 and "pipe" in cc.cacnn_variant_name(vi)
+            assert e.status == 3 and is_pipelined(cc.cacnn_variant_name(vi))
             continue
         assert np.array_equal(out.astype(np.float64), ref)
 
