@@ -350,7 +350,7 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
                     beta = 1.3;
                     t_slice = 400.0;
                 } else {
-                    feed = f32 ? 0.36 : (v.reuse_r ? 0.95 : 0.85);
+                    feed = f32 ? 0.75 : (v.reuse_r ? 0.95 : 0.85);
                     beta = 0.7;
                     t_slice = 300.0;
                 }
@@ -418,15 +418,9 @@ int fill_plan(const cacnn_problem& p, int dtype, const cacnn_machine& mach, cons
     return CACNN_OK;
 }
 
-int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, cacnn_plan* out,
-              bool allow_pipelined = true) {
-    if (!p || !out) return CACNN_ERR_NULL;
-    if (!valid_problem(p)) return CACNN_ERR_INVALID_ARG;
-    if (dtype != CACNN_F32 && dtype != CACNN_BF16_F32ACC) return CACNN_ERR_UNSUPPORTED;
-    cacnn_machine mach = machine ? *machine : kDefaultMachine;
-    if (mach.lds_bytes < 1024 || mach.num_cu < 1) return CACNN_ERR_INVALID_ARG;
-    mach.lds_bytes = std::min<int64_t>(mach.lds_bytes, 160 * 1024);  // the kernels cannot address more
-    // per-array element counts must fit the kernels' 31-bit tile arithmetic
+// per-array element counts must fit the kernels' 31-bit tile arithmetic
+int validate_dims(const cacnn_problem& pr) {
+    const cacnn_problem* p = &pr;
     const int64_t IW = p->sigma_w * (p->W - 1) + p->R, IH = p->sigma_h * (p->H - 1) + p->S;
     int64_t t;
     const int64_t lim = INT32_MAX;
@@ -439,6 +433,21 @@ int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, c
         return CACNN_ERR_INVALID_ARG;
     if (!mul_check(p->K, p->H, lim, &t) || !mul_check(t, p->W, lim, &t) || !mul_check(t, p->B, lim, &t))
         return CACNN_ERR_INVALID_ARG;
+    return CACNN_OK;
+}
+
+int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, cacnn_plan* out,
+              bool allow_pipelined = true) {
+    if (!p || !out) return CACNN_ERR_NULL;
+    if (!valid_problem(p)) return CACNN_ERR_INVALID_ARG;
+    if (dtype != CACNN_F32 && dtype != CACNN_BF16_F32ACC) return CACNN_ERR_UNSUPPORTED;
+    cacnn_machine mach = machine ? *machine : kDefaultMachine;
+    if (mach.lds_bytes < 1024 || mach.num_cu < 1) return CACNN_ERR_INVALID_ARG;
+    mach.lds_bytes = std::min<int64_t>(mach.lds_bytes, 160 * 1024);  // the kernels cannot address more
+    {
+        const int vrc = validate_dims(*p);
+        if (vrc != CACNN_OK) return vrc;
+    }
     Choice best;
     for (int vi = 0; vi < num_variants(); ++vi) {
         if (variant(vi).info.dtype != dtype) continue;
@@ -614,9 +623,8 @@ int cacnn_conv_forward_with_plan(const cacnn_problem* problem, int dtype, const 
                                  const void* filter, void* out, void* hip_stream) {
     if (!problem || !plan || !image || !filter || !out) return CACNN_ERR_NULL;
     if (dtype != CACNN_F32 && dtype != CACNN_BF16_F32ACC) return CACNN_ERR_UNSUPPORTED;
-    // same dimension checks as the planner
-    cacnn_plan scratch;
-    const int rc = plan_impl(problem, dtype, nullptr, &scratch);
+    if (!valid_problem(problem)) return CACNN_ERR_INVALID_ARG;
+    const int rc = validate_dims(*problem);
     if (rc != CACNN_OK) return rc;
     if (plan->variant < 0 || plan->variant >= num_variants()) return CACNN_ERR_UNSUPPORTED;
     const VariantInfo& v = variant(plan->variant).info;

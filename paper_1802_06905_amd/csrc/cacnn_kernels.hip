@@ -877,20 +877,69 @@ struct Bf16Stager {
     }
 };
 
+// Scheduling hint for a region that holds NMFMA matrix instructions and NDS LDS reads that do not depend on each
+// other: ask the backend to issue them alternately (one MFMA, then its share of the reads), so that the reads of the
+// next step are issued in the shadow of the matrix pipe instead of in front of it.  A wave issues in order: what is
+// placed behind a run of MFMAs cannot start until the last of them has been issued.
+template <int NMFMA, int NDS>
+__device__ __forceinline__ void interleave_hint() {
+    constexpr int PER = (NDS + NMFMA - 1) / NMFMA;
+#pragma unroll
+    for (int i = 0; i < NMFMA; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, PER, 0);   // up to PER LDS reads
+    }
+}
+
 // ---- compute: one unit out of LDS ---------------------------------------------------------------------------------
 
+// fp32: one MFMA consumes two contraction indices.  Fragments are fetched U index pairs at a time into one of two
+// register sets, so the LDS reads of the next U pairs are in flight while the MFMAs of the current U pairs issue.
 template <int MBLK, int NBLK, int TB>
 __device__ __forceinline__ void f32_compute_unit(const KernelArgs& a, const float* s_img, const float* s_flt,
                                                  const float* s_zero, const int (&posoff)[NBLK],
                                                  f32x16 (&acc)[MBLK][NBLK], int row0, int j, int kk, int r0) {
+    constexpr int U = 4;
     const int Q = a.bS * a.CT;
     const int rmax = min(a.bR, a.R - r0);
+    const int pairs = Q >> 1;
+    const int chunks = pairs / U;
     for (int r = 0; r < rmax; ++r) {
         const float* ap = s_flt + (row0 + j) * a.fpitch + r * a.QE + kk;
         const float* bp = s_img + r * a.xpitch + kk * TB;
-        const int pairs = Q >> 1;
-#pragma unroll 4
-        for (int q2 = 0; q2 < pairs; ++q2) {
+        auto load_chunk = [&](int q2, float(&av)[U][MBLK], float(&bv)[U][NBLK]) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int m = 0; m < MBLK; ++m) av[u][m] = ap[m * 32 * a.fpitch + 2 * (q2 + u)];
+#pragma unroll
+                for (int n = 0; n < NBLK; ++n) bv[u][n] = bp[posoff[n] + 2 * (q2 + u) * TB];
+            }
+        };
+        auto mfma_chunk = [&](const float(&av)[U][MBLK], const float(&bv)[U][NBLK]) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                    for (int n = 0; n < NBLK; ++n)
+                        acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u][m], bv[u][n], acc[m][n], 0, 0, 0);
+        };
+        float a0[U][MBLK], b0[U][NBLK], a1[U][MBLK], b1[U][NBLK];
+        // branch-free body: past the end the last chunk is simply read again
+        const int last = chunks > 0 ? chunks - 1 : 0;
+        if (chunks > 0) load_chunk(0, a0, b0);
+        int c = 0;
+        for (; c + 2 <= chunks; c += 2) {
+            load_chunk(min(c + 1, last) * U, a1, b1);
+            mfma_chunk(a0, b0);
+            interleave_hint<U * MBLK * NBLK, U*(MBLK + NBLK)>();
+            load_chunk(min(c + 2, last) * U, a0, b0);
+            mfma_chunk(a1, b1);
+            interleave_hint<U * MBLK * NBLK, U*(MBLK + NBLK)>();
+        }
+        if (c < chunks) mfma_chunk(a0, b0);
+        for (int q2 = chunks * U; q2 < pairs; ++q2) {
             float av[MBLK], bv[NBLK];
 #pragma unroll
             for (int m = 0; m < MBLK; ++m) av[m] = ap[m * 32 * a.fpitch + 2 * q2];
@@ -952,31 +1001,32 @@ __device__ __forceinline__ void bf16_compute_unit(const KernelArgs& a, const uin
                     for (int m = 0; m < MBLK; ++m)
                         acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[m][r], X[n + r], acc[m][n], 0, 0, 0);
         };
+        // steps t = (s, cs) in order; the loop body has no branches, so the reads of step t+1 and the MFMAs of step t
+        // sit in one scheduling region (past the end the last step is simply read again)
         const int T = smax * steps;
-        int s_n = 0, cs_n = 0;
+        int s_n = 0, cs_n = 0, t_n = 0;
         auto next_step = [&]() {
-            if (++cs_n == steps) {
-                cs_n = 0;
-                ++s_n;
-            }
+            const int adv = t_n < T - 1 ? 1 : 0;
+            t_n += adv;
+            cs_n += adv;
+            const int wrap = cs_n == steps ? 1 : 0;
+            cs_n = wrap ? 0 : cs_n;
+            s_n += wrap;
         };
         bf16x8 A0[MBLK][BR], X0[NX], A1[MBLK][BR], X1[NX];
         load_frags(0, 0, A0, X0);
-        next_step();
-        for (int t = 0; t < T; t += 2) {
-            if (t + 1 < T) {
-                load_frags(s_n, cs_n, A1, X1);
-                next_step();
-            }
+        int t = 0;
+        for (; t + 2 <= T; t += 2) {
+            next_step();
+            load_frags(s_n, cs_n, A1, X1);
             mfmas(A0, X0);
-            if (t + 1 < T) {
-                if (t + 2 < T) {
-                    load_frags(s_n, cs_n, A0, X0);
-                    next_step();
-                }
-                mfmas(A1, X1);
-            }
+            interleave_hint<BR * TW * MBLK, NX + MBLK * BR>();
+            next_step();
+            load_frags(s_n, cs_n, A0, X0);
+            mfmas(A1, X1);
+            interleave_hint<BR * TW * MBLK, NX + MBLK * BR>();
         }
+        if (t < T) mfmas(A0, X0);
     } else {
         for (int r = 0; r < rmax; ++r) {
             for (int s = 0; s < smax; ++s) {
