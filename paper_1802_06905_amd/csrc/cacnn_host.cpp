@@ -187,7 +187,31 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
     g.n_slices = ceil_div(p.R, bR) * ceil_div(p.S, bS) * ceil_div(Cpad, CT);
     g.flt_resident = (g.n_slices == 1 && ceil_div(p.K, v.KT()) == 1) ? 1 : 0;
     const int nbuf_f = g.flt_resident ? 1 : 2;
-    if (v.dtype == CACNN_F32) {
+    if (v.dtype == CACNN_F32 && v.f32v4()) {
+        // 16-byte units: four consecutive contraction indices of one position
+        const int G = CT / 4;
+        g.ypitch = G * v.TB;
+        const int base = g.YS * g.ypitch;
+        int pad = 0;
+        if (v.TB < 32) {
+            // eight neighbouring staging lanes (b-quads fastest, then x) must land in eight different 16-byte slots
+            const int want = v.TB >= 16 ? 2 : 1;
+            while (((base + pad) & 7) != want) ++pad;
+        }
+        g.xpitch = base + pad;
+        g.QE = (int)round_up((int64_t)bS * CT, 8);
+        int f4 = bR * g.QE / 4;
+        if ((f4 & 1) == 0) f4 += 1;     // odd count of 16-byte units: conflict-free A fragments
+        g.fpitch = 4 * f4;
+        g.img_buf = g.XS * g.xpitch;
+        g.zero_off = 2 * g.img_buf;
+        g.flt_off = g.zero_off + 32;
+        g.flt_buf = v.KT() * f4;
+        g.lds_bytes = 16ll * (g.flt_off + (int64_t)nbuf_f * g.flt_buf);
+        g.img_items = g.XS * g.YS * G * (v.TB / 4);
+        g.flt_items = v.KT() * bR * bS * G;
+        g.legal = vec_img && v.TB % 4 == 0 && CT % 4 == 0 && (g.flt_resident || p.C % 4 == 0);
+    } else if (v.dtype == CACNN_F32) {
         g.ypitch = CT * v.TB;
         int base = g.YS * g.ypitch;
         int pad = 0;
@@ -296,7 +320,7 @@ bool vec_img_ok(const VariantInfo& v, const cacnn_problem& p) {
 bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice* best) {
     const VariantInfo& v = variant(vi).info;
     // fp32 slices in multiples of 4 channels keep the 16-byte Filter loads legal
-    const int gran = (v.dtype == CACNN_F32 && p.C % 4 == 0) ? 4 : v.cgran();
+    const int gran = (v.dtype == CACNN_F32 && p.C % 4 == 0) ? 4 : v.cgran();   // v.cgran() is 4 for the v4 layout
     const int Cpad = (int)std::min<int64_t>(round_up(p.C, gran), 1 << 20);
     // candidate contraction tiles: every even split of the (padded) channel range, and halvings of the s and r ranges
     std::vector<int> cts;
@@ -333,8 +357,9 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
                 //   t_out    the Out tile draining to HBM at ~1 TB/s for the whole chip.
                 // The direct kernels serialise all of it, the pipelined ones overlap the fetch with the multiply, the
                 // wave-specialised ones also overlap the LDS writes and the address arithmetic.
-                const double ksteps = v.dtype == CACNN_F32 ? (double)p.R * ceil_div((int64_t)p.S * Cpad, 2)
-                                                           : (double)p.R * p.S * (Cpad / 16);
+                const double ksteps = v.dtype != CACNN_F32 ? (double)p.R * p.S * (Cpad / 16)
+                                      : v.f32v4()          ? (double)p.R * (double)round_up((int64_t)p.S * Cpad, 8) / 2.0
+                                                           : (double)p.R * ceil_div((int64_t)p.S * Cpad, 2);
                 const double t_mfma = (v.dtype == CACNN_F32 ? 64.0 : 32.0) * v.MBLK * v.NBLK * ksteps;
                 const double t_stage = (img_words * waste + (words - img_words)) * ebytes / (double)n_wg / 16.0;
                 const double n_ctiles = (double)g.n_slices;
@@ -350,7 +375,7 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
                     beta = 1.3;
                     t_slice = 400.0;
                 } else {
-                    feed = f32 ? 0.75 : (v.reuse_r ? 0.95 : 0.85);
+                    feed = f32 ? (v.f32v4() ? 0.9 : 0.75) : (v.reuse_r ? 0.95 : 0.85);
                     beta = 0.7;
                     t_slice = 300.0;
                 }
@@ -540,6 +565,8 @@ int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int b
     a.d_bS = make_fastdiv((uint32_t)g.bS);
     a.d_bR = make_fastdiv((uint32_t)g.bR);
     a.d_RS = make_fastdiv((uint32_t)(g.bR * g.bS));
+    a.d_XS = make_fastdiv((uint32_t)g.XS);
+    a.d_C4 = make_fastdiv((uint32_t)std::max(1, g.CT / 4));
     if (dtype == CACNN_F32)
         a.d_C8 = make_fastdiv((uint32_t)(a.vec_flt ? g.CT / 4 : g.CT));
     else

@@ -36,13 +36,15 @@ struct VariantInfo {
     int pipelined;
     int MAXI, MAXF;
     int occ;    // workgroups of this kernel one compute unit can hold at once, as far as registers go
-    int reuse_r;  // > 0: filter-row reuse path compiled for exactly this many taps per contraction tile (sigma_w = 1)
+    int reuse_r;  // > 0: filter-row reuse path compiled for exactly this many taps per contraction tile (sigma_w = 1);
+                  // -4: fp32 kernel with the 16-byte-fragment LDS layout (c-slices in multiples of 4 channels)
     float tune;   // measured time of this variant relative to what the planner's cost model predicts (1 = as modelled)
     int KT() const { return WM * MBLK * 32; }
     int NT() const { return TB * TW * TH; }
     int threads() const { return WM * WN * (pipelined == 2 ? 128 : 64); }
     int staging_threads() const { return WM * WN * 64; }
-    int cgran() const { return dtype == 0 ? 1 : 16; }  // contraction granularity of the c-slice
+    bool f32v4() const { return reuse_r == -4; }
+    int cgran() const { return dtype == 0 ? (f32v4() ? 4 : 1) : 16; }  // contraction granularity of the c-slice
 };
 
 // Everything a kernel needs, passed by value.
@@ -60,7 +62,7 @@ struct KernelArgs {
     int32_t zero_off;         // fp32: offset (floats) of a zeroed row of 64 floats inside the Image region
     int32_t tiles_k, tiles_b, tiles_w, tiles_h;
     int32_t vec_img, vec_flt; // 1 = 16-byte global loads are legal for this operand
-    FastDiv d_CT, d_YS, d_bS, d_bR, d_C8, d_RS;
+    FastDiv d_CT, d_YS, d_bS, d_bR, d_C8, d_RS, d_XS, d_C4;
     // pipelined kernels only
     int32_t n_tiles;          // Out tiles in the whole problem (all kernels)
     int32_t n_xcd;            // XCDs the dispatcher deals workgroups to (8 on MI355X); 1 = no remapping

@@ -859,11 +859,22 @@ struct Bf16Stager {
 #pragma unroll
         for (int i = 0; i < MAXI; ++i)
             if (stid + i * STHREADS < a.img_items) {
-                uint4 out[8];
-                transpose8x8_bf16(ireg[i], out);
+                // 8x8 transpose, two columns (b = 2m, 2m+1) at a time to keep few registers live
                 uint4* dst = s_img + i_lds[i];
 #pragma unroll
-                for (int bb = 0; bb < 8; ++bb) dst[bb ^ i_key[i]] = out[bb];
+                for (int m = 0; m < 4; ++m) {
+                    uint32_t lo[4], hi[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const uint4 re = ireg[i][2 * q], ro = ireg[i][2 * q + 1];
+                        const uint32_t e = m == 0 ? re.x : m == 1 ? re.y : m == 2 ? re.z : re.w;
+                        const uint32_t o = m == 0 ? ro.x : m == 1 ? ro.y : m == 2 ? ro.z : ro.w;
+                        lo[q] = (e & 0xffffu) | (o << 16);
+                        hi[q] = (e >> 16) | (o & 0xffff0000u);
+                    }
+                    dst[(2 * m) ^ i_key[i]] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                    dst[(2 * m + 1) ^ i_key[i]] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+                }
             }
     }
     __device__ __forceinline__ void store_flt(const KernelArgs& a, uint4* smem, int buf,
@@ -1336,51 +1347,50 @@ __global__ void __launch_bounds__(WM* WN * 128) conv_bf16_ws_kernel(const Kernel
         const int stid = tid - CTHREADS;
         Bf16Stager<CTHREADS, TB, MAXI, MAXF> st;
         st.init(a, stid);
-        // Image words are fetched two units ahead (two register sets), Filter words one unit ahead
-        uint4 ireg0[MAXI][8], ireg1[MAXI][8], freg[MAXF];
+        // Memory latency under load is about two microseconds while a unit is multiplied in less than one, so the
+        // producers keep several units in flight in registers: Image tiles ID units ahead, Filter tiles FD units ahead
+        // (FD drops to 1 where two sets of each would not fit the register file).
+        // The loop is unrolled over lcm(ID, FD) units so that every register set has a fixed name.
+        constexpr int ID = 2, FD = (ID * MAXI * 32 + 2 * MAXF * 4 <= 160) ? 2 : 1, PERIOD = 2;
+        uint4 ireg[ID][MAXI][8], freg[FD][MAXF];
         UnitPos su = first_unit(a, KT, TB, TW, TH);   // next unit to store
         UnitPos lu = su;                              // next unit whose Image tile is fetched
         UnitPos fu = su;                              // next unit whose Filter tile is fetched
-        if (lu.t < a.n_tiles) {
-            const UnitBase u = unit_base<2>(a, lu, KT, TB);
-            st.issue_img(a, u, ireg0);
-            st.issue_flt(a, u, freg);
-            advance_unit(a, lu, KT, TB, TW, TH);
-            advance_unit(a, fu, KT, TB, TW, TH);
-        }
-        if (lu.t < a.n_tiles) {
-            st.issue_img(a, unit_base<2>(a, lu, KT, TB), ireg1);
-            advance_unit(a, lu, KT, TB, TW, TH);
-        }
+#pragma unroll
+        for (int d = 0; d < ID; ++d)
+            if (lu.t < a.n_tiles) {
+                st.issue_img(a, unit_base<2>(a, lu, KT, TB), ireg[d]);
+                advance_unit(a, lu, KT, TB, TW, TH);
+            }
+#pragma unroll
+        for (int d = 0; d < FD; ++d)
+            if (fu.t < a.n_tiles) {
+                st.issue_flt(a, unit_base<2>(a, fu, KT, TB), freg[d]);
+                advance_unit(a, fu, KT, TB, TW, TH);
+            }
         if (a.flt_resident) {
             stage_filter_bf16<CTHREADS, KT>(a, (uint16_t*)(smem_u + a.flt_off), stid, 0, 0, 0, 0);
         }
-        while (su.t < a.n_tiles) {
-            st.store_img(a, smem_u, 0, ireg0);
-            st.store_flt(a, smem_u, 0, freg);
-            if (lu.t < a.n_tiles) {
-                st.issue_img(a, unit_base<2>(a, lu, KT, TB), ireg0);
-                advance_unit(a, lu, KT, TB, TW, TH);
+        bool done = su.t >= a.n_tiles;
+        while (!done) {
+#pragma unroll
+            for (int ph = 0; ph < PERIOD; ++ph) {
+                if (!done) {
+                    st.store_img(a, smem_u, ph & 1, ireg[ph % ID]);
+                    st.store_flt(a, smem_u, ph & 1, freg[ph % FD]);
+                    if (lu.t < a.n_tiles) {
+                        st.issue_img(a, unit_base<2>(a, lu, KT, TB), ireg[ph % ID]);
+                        advance_unit(a, lu, KT, TB, TW, TH);
+                    }
+                    if (fu.t < a.n_tiles) {
+                        st.issue_flt(a, unit_base<2>(a, fu, KT, TB), freg[ph % FD]);
+                        advance_unit(a, fu, KT, TB, TW, TH);
+                    }
+                    __syncthreads();
+                    advance_unit(a, su, KT, TB, TW, TH);
+                    done = su.t >= a.n_tiles;
+                }
             }
-            if (fu.t < a.n_tiles) {
-                st.issue_flt(a, unit_base<2>(a, fu, KT, TB), freg);
-                advance_unit(a, fu, KT, TB, TW, TH);
-            }
-            __syncthreads();
-            advance_unit(a, su, KT, TB, TW, TH);
-            if (su.t >= a.n_tiles) break;
-            st.store_img(a, smem_u, 1, ireg1);
-            st.store_flt(a, smem_u, 1, freg);
-            if (lu.t < a.n_tiles) {
-                st.issue_img(a, unit_base<2>(a, lu, KT, TB), ireg1);
-                advance_unit(a, lu, KT, TB, TW, TH);
-            }
-            if (fu.t < a.n_tiles) {
-                st.issue_flt(a, unit_base<2>(a, fu, KT, TB), freg);
-                advance_unit(a, fu, KT, TB, TW, TH);
-            }
-            __syncthreads();
-            advance_unit(a, su, KT, TB, TW, TH);
         }
     } else {
         const int lane = tid & 63, wave = wave_id;
@@ -1402,6 +1412,313 @@ __global__ void __launch_bounds__(WM* WN * 128) conv_bf16_ws_kernel(const Kernel
             const bool have_next = nxt.t < a.n_tiles;
             if (!have_next || nxt.t != cur.t)
                 write_tile<MBLK, NBLK, TB, TW, TH>(a, cur.tc, acc, wn * NBLK, wm * MBLK * 32, j, g);
+            cur = nxt;
+            if (have_next) advance_unit(a, nxt, KT, TB, TW, TH);
+            buf ^= 1;
+        }
+    }
+}
+
+// ---- fp32 with 16-byte LDS fragments ("v4" layout) ---------------------------------------------------------------
+// LDS instructions cost about the same pipe time whatever their width (measured: 4-, 8- and 16-byte reads issue at the
+// same rate), so the fp32 path above, one 4-byte read per operand and MFMA, runs out of LDS issue slots before it
+// runs out of MFMA time.  Here four consecutive contraction indices q = s*CT + c of one position sit in one 16-byte
+// unit, img[x*xpitch + (q/4 rows)*TB + (b ^ key)], and the Filter row is 16-byte aligned, so one read per operand
+// feeds four MFMAs.  An MFMA takes two indices, one per half-wave: in step e of group t the halves use
+// q = 8t + e and 8t + 4 + e.  Staging items are 4 channels x 4 images, transposed by register renaming only.
+// Needs CT % 4 == 0 (a channel count that is not a multiple of 4 is padded with zero channels inside LDS).
+
+__device__ __forceinline__ int v4_swz(int b) { return (b & ~3) | ((b & 3) ^ ((b >> 3) & 3)); }
+
+template <int STHREADS, int TB, int MAXI, int MAXF>
+struct F32V4Stager {
+    static constexpr int VPR = TB / 4;
+    uint32_t i_g[MAXI], f_g[MAXF];
+    int i_lds[MAXI], i_key[MAXI], f_lds[MAXF];
+    uint32_t row_bytes;
+    int stid;
+
+    __device__ __forceinline__ void img_coords(const KernelArgs& a, int idx, int& x, int& y, int& c4, int& bv) const {
+        bv = idx % VPR;
+        const uint32_t t = (uint32_t)idx / VPR;
+        const uint32_t G = fdiv(t, a.d_XS);           // x is the faster index: neighbouring lanes, different banks
+        x = t - G * a.XS;
+        const uint32_t yy = fdiv(G, a.d_C4);
+        c4 = G - yy * (a.CT >> 2);
+        y = (int)yy;
+    }
+    __device__ __forceinline__ void flt_coords(const KernelArgs& a, int idx, int& kl, int& r, int& s, int& c) const {
+        const int CTV = a.CT >> 2;
+        const uint32_t t = fdiv((uint32_t)idx, a.d_C4);
+        c = (idx - t * CTV) * 4;
+        const uint32_t t2 = fdiv(t, a.d_bS);
+        s = t - t2 * a.bS;
+        const uint32_t k = fdiv(t2, a.d_bR);
+        r = t2 - k * a.bR;
+        kl = (int)k;
+    }
+
+    __device__ __forceinline__ void init(const KernelArgs& a, int stid_) {
+        stid = stid_;
+        row_bytes = (uint32_t)a.B * 4u;
+#pragma unroll
+        for (int i = 0; i < MAXI; ++i) {
+            const int idx = stid + i * STHREADS;
+            i_lds[i] = 0;
+            i_g[i] = 0;
+            i_key[i] = 0;
+            if (idx < a.img_items) {
+                int x, y, c4, bv;
+                img_coords(a, idx, x, y, c4, bv);
+                i_lds[i] = x * a.xpitch + y * a.ypitch + c4 * TB + bv * 4;
+                i_key[i] = (bv >> 1) & 3;
+                i_g[i] = ((((uint32_t)x * a.IH + y) * a.C + c4 * 4) * a.B + bv * 4) * 4u;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < MAXF; ++i) {
+            const int idx = stid + i * STHREADS;
+            f_lds[i] = 0;
+            f_g[i] = 0;
+            if (!a.flt_resident && idx < a.flt_items) {
+                int kl, r, s, c;
+                flt_coords(a, idx, kl, r, s, c);
+                f_lds[i] = (kl * a.fpitch + r * a.QE + s * a.CT + c) >> 2;
+                f_g[i] = ((((uint32_t)kl * a.R + r) * a.S + s) * a.C + c) * 4u;
+            }
+        }
+    }
+
+    __device__ __forceinline__ void issue_img(const KernelArgs& a, const UnitBase& u, f32x4 (&ireg)[MAXI][4]) const {
+        if (u.img_inside) {
+#pragma unroll
+            for (int i = 0; i < MAXI; ++i)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) ireg[i][e] = buf_load_f32x4(u.img, i_g[i], e * row_bytes);
+        } else {
+#pragma unroll
+            for (int i = 0; i < MAXI; ++i) {
+                const int idx = stid + i * STHREADS;
+                int x, y, c4, bv;
+                img_coords(a, idx, x, y, c4, bv);
+                const bool ok = idx < a.img_items && x < u.lx && y < u.ly && bv * 4 < u.lb;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool oke = ok && c4 * 4 + e < u.lc;
+                    const f32x4 v = buf_load_f32x4(u.img, oke ? i_g[i] + e * row_bytes : 0u, 0);
+                    const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+                    ireg[i][e] = oke ? v : z;
+                }
+            }
+        }
+    }
+    __device__ __forceinline__ void issue_flt(const KernelArgs& a, const UnitBase& u, f32x4 (&freg)[MAXF]) const {
+        if (!a.flt_resident) {
+            if (u.flt_inside) {
+#pragma unroll
+                for (int i = 0; i < MAXF; ++i) freg[i] = buf_load_f32x4(u.flt, f_g[i], 0);
+            } else {
+#pragma unroll
+                for (int i = 0; i < MAXF; ++i) {
+                    const int idx = stid + i * STHREADS;
+                    int kl, r, s, c;
+                    flt_coords(a, idx, kl, r, s, c);
+                    const bool ok = idx < a.flt_items && kl < u.lk && r < u.lr && s < u.ls && c < u.lc;
+                    const f32x4 v = buf_load_f32x4(u.flt, ok ? f_g[i] : 0u, 0);
+                    const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+                    freg[i] = ok ? v : z;
+                }
+            }
+        }
+    }
+    __device__ __forceinline__ void store_img(const KernelArgs& a, f32x4* smem, int buf,
+                                              const f32x4 (&ireg)[MAXI][4]) const {
+        f32x4* s_img = smem + buf * a.img_buf;
+#pragma unroll
+        for (int i = 0; i < MAXI; ++i)
+            if (stid + i * STHREADS < a.img_items) {
+                f32x4* dst = s_img + i_lds[i];
+#pragma unroll
+                for (int bb = 0; bb < 4; ++bb) {
+                    const f32x4 o = {ireg[i][0][bb], ireg[i][1][bb], ireg[i][2][bb], ireg[i][3][bb]};
+                    dst[bb ^ i_key[i]] = o;
+                }
+            }
+    }
+    __device__ __forceinline__ void store_flt(const KernelArgs& a, f32x4* smem, int buf,
+                                              const f32x4 (&freg)[MAXF]) const {
+        if (!a.flt_resident) {
+            f32x4* s_flt = smem + a.flt_off + buf * a.flt_buf;
+#pragma unroll
+            for (int i = 0; i < MAXF; ++i)
+                if (stid + i * STHREADS < a.flt_items) s_flt[f_lds[i]] = freg[i];
+        }
+    }
+};
+
+// One unit out of LDS.  Groups (r, t) form one flat sequence; the fragments of the next group are read while the 4*MBLK*NBLK
+// MFMAs of the current one issue (no branches in the loop body; past the end the last group is read again).
+template <int MBLK, int NBLK, int TB>
+__device__ __forceinline__ void f32v4_compute_unit(const KernelArgs& a, const f32x4* s_img, const f32x4* s_flt,
+                                                   const f32x4* s_zero, const int (&posoff)[NBLK],
+                                                   f32x16 (&acc)[MBLK][NBLK], int row0, int j, int kk, int r0) {
+    const int Q = a.bS * a.CT;                 // multiple of 4
+    const int G8 = a.QE >> 3;                  // groups of 8 indices per filter column
+    const int rmax = min(a.bR, a.R - r0);
+    const int total = rmax * G8;
+    const int f4 = a.fpitch >> 2, q4 = a.QE >> 2;
+    const bool half_tail = (Q & 7) != 0;       // the last group of a column has only its first four indices
+    const f32x4* ap0 = s_flt + (row0 + j) * f4 + kk;
+    int r_n = 0, t_n = 0, n_loaded = 0;
+    auto load_group = [&](f32x4(&av)[MBLK], f32x4(&bv)[NBLK]) {
+        const f32x4* ap = ap0 + r_n * q4 + 2 * t_n;
+        const bool zero_half = half_tail && t_n == G8 - 1 && kk;
+#pragma unroll
+        for (int m = 0; m < MBLK; ++m) av[m] = ap[m * 32 * f4];
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n)
+            bv[n] = zero_half ? s_zero[j] : s_img[posoff[n] + r_n * a.xpitch + 2 * t_n * TB];
+    };
+    auto advance = [&]() {
+        const int adv = n_loaded < total - 1 ? 1 : 0;
+        n_loaded += adv;
+        t_n += adv;
+        const int wrap = t_n == G8 ? 1 : 0;
+        t_n = wrap ? 0 : t_n;
+        r_n += wrap;
+    };
+    auto mfma_group = [&](const f32x4(&av)[MBLK], const f32x4(&bv)[NBLK]) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                for (int n = 0; n < NBLK; ++n)
+                    acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[m][e], bv[n][e], acc[m][n], 0, 0, 0);
+    };
+    f32x4 a0[MBLK], b0[NBLK], a1[MBLK], b1[NBLK];
+    if (total > 0) load_group(a0, b0);
+    int t = 0;
+    for (; t + 2 <= total; t += 2) {
+        advance();
+        load_group(a1, b1);
+        mfma_group(a0, b0);
+        interleave_hint<4 * MBLK * NBLK, MBLK + NBLK>();
+        advance();
+        load_group(a0, b0);
+        mfma_group(a1, b1);
+        interleave_hint<4 * MBLK * NBLK, MBLK + NBLK>();
+    }
+    if (t < total) mfma_group(a0, b0);
+}
+
+template <int NBLK, int TB, int TW, int TH>
+__device__ __forceinline__ void f32v4_posoff(const KernelArgs& a, int (&posoff)[NBLK], int nblock0, int j, int kk) {
+    constexpr int NT = TB * TW * TH;
+#pragma unroll
+    for (int n = 0; n < NBLK; ++n) {
+        int nn = (nblock0 + n) * 32 + j;
+        if (nn >= NT) nn = 0;
+        const int b_l = nn % TB, w_l = (nn / TB) % TW, h_l = nn / (TB * TW);
+        posoff[n] = a.sw * w_l * a.xpitch + a.sh * h_l * a.ypitch + kk * TB + v4_swz(b_l);
+    }
+}
+
+template <int WM, int WN, int MBLK, int NBLK, int TB, int TW, int TH, int MAXI, int MAXF>
+__global__ void __launch_bounds__(WM* WN * 128) conv_f32v4_ws_kernel(const KernelArgs a) {
+    constexpr int CTHREADS = WM * WN * 64;
+    constexpr int KT = WM * MBLK * 32;
+    extern __shared__ __align__(16) f32x4 smem_v[];
+    const int tid = threadIdx.x;
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
+    const int zero_off = 2 * a.img_buf;
+
+    if (wave_id >= WM * WN) {
+        const int stid = tid - CTHREADS;
+        F32V4Stager<CTHREADS, TB, MAXI, MAXF> st;
+        st.init(a, stid);
+        // one-time zeros: the zero units, the pad columns of every Filter row in every buffer
+        {
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            if (stid < 32) smem_v[zero_off + stid] = z;
+            const int q4 = a.QE >> 2, used4 = (a.bS * a.CT) >> 2, f4 = a.fpitch >> 2;
+            const int nbuf = a.flt_resident ? 1 : 2;
+            if (q4 > used4) {
+                for (int idx = stid; idx < nbuf * KT * a.bR; idx += CTHREADS) {
+                    const int bsel = idx / (KT * a.bR), rem = idx - bsel * KT * a.bR;
+                    const int kl = rem / a.bR, r = rem - kl * a.bR;
+                    smem_v[a.flt_off + bsel * a.flt_buf + kl * f4 + r * q4 + used4] = z;
+                }
+            }
+        }
+        // Image words are fetched two units ahead (two register sets), Filter words one unit ahead
+        f32x4 ireg0[MAXI][4], ireg1[MAXI][4], freg[MAXF];
+        UnitPos su = first_unit(a, KT, TB, TW, TH);
+        UnitPos lu = su, fu = su;
+        if (lu.t < a.n_tiles) {
+            const UnitBase u = unit_base<4>(a, lu, KT, TB);
+            st.issue_img(a, u, ireg0);
+            st.issue_flt(a, u, freg);
+            advance_unit(a, lu, KT, TB, TW, TH);
+            advance_unit(a, fu, KT, TB, TW, TH);
+        }
+        if (lu.t < a.n_tiles) {
+            st.issue_img(a, unit_base<4>(a, lu, KT, TB), ireg1);
+            advance_unit(a, lu, KT, TB, TW, TH);
+        }
+        if (a.flt_resident) {
+            if (a.vec_flt)
+                stage_filter_f32<CTHREADS, KT, 4>(a, (float*)(smem_v + a.flt_off), stid, 0, 0, 0, 0);
+            else
+                stage_filter_f32<CTHREADS, KT, 1>(a, (float*)(smem_v + a.flt_off), stid, 0, 0, 0, 0);
+        }
+        while (su.t < a.n_tiles) {
+            st.store_img(a, smem_v, 0, ireg0);
+            st.store_flt(a, smem_v, 0, freg);
+            if (lu.t < a.n_tiles) {
+                st.issue_img(a, unit_base<4>(a, lu, KT, TB), ireg0);
+                advance_unit(a, lu, KT, TB, TW, TH);
+            }
+            if (fu.t < a.n_tiles) {
+                st.issue_flt(a, unit_base<4>(a, fu, KT, TB), freg);
+                advance_unit(a, fu, KT, TB, TW, TH);
+            }
+            __syncthreads();
+            advance_unit(a, su, KT, TB, TW, TH);
+            if (su.t >= a.n_tiles) break;
+            st.store_img(a, smem_v, 1, ireg1);
+            st.store_flt(a, smem_v, 1, freg);
+            if (lu.t < a.n_tiles) {
+                st.issue_img(a, unit_base<4>(a, lu, KT, TB), ireg1);
+                advance_unit(a, lu, KT, TB, TW, TH);
+            }
+            if (fu.t < a.n_tiles) {
+                st.issue_flt(a, unit_base<4>(a, fu, KT, TB), freg);
+                advance_unit(a, fu, KT, TB, TW, TH);
+            }
+            __syncthreads();
+            advance_unit(a, su, KT, TB, TW, TH);
+        }
+    } else {
+        const int lane = tid & 63, wave = wave_id;
+        const int wm = wave % WM, wn = wave / WM;
+        const int j = lane & 31, kk = lane >> 5;
+        int posoff[NBLK];
+        f32v4_posoff<NBLK, TB, TW, TH>(a, posoff, wn * NBLK, j, kk);
+        f32x16 acc[MBLK][NBLK];
+        zero_acc(acc);
+        UnitPos cur = first_unit(a, KT, TB, TW, TH);
+        UnitPos nxt = cur;
+        if (cur.t < a.n_tiles) advance_unit(a, nxt, KT, TB, TW, TH);
+        int buf = 0;
+        while (cur.t < a.n_tiles) {
+            __syncthreads();
+            f32v4_compute_unit<MBLK, NBLK, TB>(a, smem_v + buf * a.img_buf,
+                                               smem_v + a.flt_off + (a.flt_resident ? 0 : buf) * a.flt_buf,
+                                               smem_v + zero_off, posoff, acc, wm * MBLK * 32, j, kk, cur.r0);
+            const bool have_next = nxt.t < a.n_tiles;
+            if (!have_next || nxt.t != cur.t)
+                write_tile<MBLK, NBLK, TB, TW, TH>(a, cur.tc, acc, wn * NBLK, wm * MBLK * 32, j, kk);
             cur = nxt;
             if (have_next) advance_unit(a, nxt, KT, TB, TW, TH);
             buf ^= 1;
@@ -1506,17 +1823,28 @@ static const Variant g_variants[] = {
                      conv_f32_ws_kernel<2, 2, 1, 4, 32, 4, 2, 12, 10>),
     CACNN_WS_VARIANT(0, "f32 ws k64 b32w2h2 w2x2 m1n2", 1.0f, 2, 2, 1, 2, 32, 2, 2, 8, 10, 0,
                      conv_f32_ws_kernel<2, 2, 1, 2, 32, 2, 2, 8, 10>),
+    // wave-specialised fp32 with 16-byte LDS fragments
+    CACNN_WS_VARIANT(0, "f32 ws4 k64 b8w4h4 w2x2 m1n2", 1.0f, 2, 2, 1, 2, 8, 4, 4, 2, 10, -4,
+                     conv_f32v4_ws_kernel<2, 2, 1, 2, 8, 4, 4, 2, 10>),
+    CACNN_WS_VARIANT(0, "f32 ws4 k64 b8w8h4 w2x2 m1n4", 1.0f, 2, 2, 1, 4, 8, 8, 4, 3, 10, -4,
+                     conv_f32v4_ws_kernel<2, 2, 1, 4, 8, 8, 4, 3, 10>),
+    CACNN_WS_VARIANT(0, "f32 ws4 k64 b32w4h2 w2x2 m1n4", 1.0f, 2, 2, 1, 4, 32, 4, 2, 4, 10, -4,
+                     conv_f32v4_ws_kernel<2, 2, 1, 4, 32, 4, 2, 4, 10>),
+    CACNN_WS_VARIANT(0, "f32 ws4 k64 b32w2h2 w2x2 m1n2", 1.0f, 2, 2, 1, 2, 32, 2, 2, 3, 10, -4,
+                     conv_f32v4_ws_kernel<2, 2, 1, 2, 32, 2, 2, 3, 10>),
+    CACNN_WS_VARIANT(0, "f32 ws4 k64 b16w4h2 w2x2 m1n2", 1.0f, 2, 2, 1, 2, 16, 4, 2, 3, 10, -4,
+                     conv_f32v4_ws_kernel<2, 2, 1, 2, 16, 4, 2, 3, 10>),
     // wave-specialised, bf16
-    CACNN_WS_VARIANT(1, "bf16 ws k128 b32w2h2 w2x2 m2n2", 1.05f, 2, 2, 2, 2, 32, 2, 2, 1, 10, 0,
-                     conv_bf16_ws_kernel<2, 2, 2, 2, 32, 2, 2, 1, 10, 0>),
-    CACNN_WS_VARIANT(1, "bf16 ws3 k128 b32w2h2 w2x2 m2n2", 1.0f, 2, 2, 2, 2, 32, 2, 2, 1, 10, 3,
-                     conv_bf16_ws_kernel<2, 2, 2, 2, 32, 2, 2, 1, 10, 3>),
-    CACNN_WS_VARIANT(1, "bf16 ws3 k128 b32w7h1 w4x1 m1n7", 1.0f, 4, 1, 1, 7, 32, 7, 1, 1, 10, 3,
-                     conv_bf16_ws_kernel<4, 1, 1, 7, 32, 7, 1, 1, 10, 3>),
+    CACNN_WS_VARIANT(1, "bf16 ws k128 b32w2h2 w2x2 m2n2", 1.05f, 2, 2, 2, 2, 32, 2, 2, 1, 9, 0,
+                     conv_bf16_ws_kernel<2, 2, 2, 2, 32, 2, 2, 1, 9, 0>),
+    CACNN_WS_VARIANT(1, "bf16 ws3 k128 b32w2h2 w2x2 m2n2", 1.0f, 2, 2, 2, 2, 32, 2, 2, 1, 9, 3,
+                     conv_bf16_ws_kernel<2, 2, 2, 2, 32, 2, 2, 1, 9, 3>),
+    CACNN_WS_VARIANT(1, "bf16 ws3 k128 b32w7h1 w4x1 m1n7", 1.0f, 4, 1, 1, 7, 32, 7, 1, 1, 9, 3,
+                     conv_bf16_ws_kernel<4, 1, 1, 7, 32, 7, 1, 1, 9, 3>),
     CACNN_WS_VARIANT(1, "bf16 ws3 k64 b32w7h2 w2x2 m1n7", 1.9f, 2, 2, 1, 7, 32, 7, 2, 2, 6, 3,
                      conv_bf16_ws_kernel<2, 2, 1, 7, 32, 7, 2, 2, 6, 3>),
-    CACNN_WS_VARIANT(1, "bf16 ws3 k128 b32w4h1 w4x1 m1n4", 1.5f, 4, 1, 1, 4, 32, 4, 1, 1, 10, 3,
-                     conv_bf16_ws_kernel<4, 1, 1, 4, 32, 4, 1, 1, 10, 3>),
+    CACNN_WS_VARIANT(1, "bf16 ws3 k128 b32w4h1 w4x1 m1n4", 1.5f, 4, 1, 1, 4, 32, 4, 1, 1, 9, 3,
+                     conv_bf16_ws_kernel<4, 1, 1, 4, 32, 4, 1, 1, 9, 3>),
     CACNN_WS_VARIANT(1, "bf16 ws k64 b8w4h4 w2x2 m1n2", 3.0f, 2, 2, 1, 2, 8, 4, 4, 1, 6, 0,
                      conv_bf16_ws_kernel<2, 2, 1, 2, 8, 4, 4, 1, 6, 0>),
 };
