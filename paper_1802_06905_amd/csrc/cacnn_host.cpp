@@ -185,7 +185,7 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
     g.YS = (int)(p.sigma_h * (v.TH - 1) + bS);
     const int64_t Cpad = round_up(p.C, v.cgran());
     g.n_slices = ceil_div(p.R, bR) * ceil_div(p.S, bS) * ceil_div(Cpad, CT);
-    g.flt_resident = (g.n_slices == 1 && ceil_div(p.K, v.KT()) == 1) ? 1 : 0;
+    g.flt_resident = (g.n_slices == 1 && ceil_div(p.K, v.KT()) == 1 && v.fx_ct == 0) ? 1 : 0;
     const int nbuf_f = g.flt_resident ? 1 : 2;
     if (v.dtype == CACNN_F32 && v.f32v4()) {
         // 16-byte units: four consecutive contraction indices of one position
@@ -267,6 +267,13 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
         }
     }
     if (v.reuse_r > 0 && (bR != v.reuse_r || p.sigma_w != 1)) g.legal = false;
+    if (v.fx_ct > 0) {
+        // fixed-geometry kernels: their own contraction tile, unit strides, a shape the tiles divide exactly
+        if (CT != v.fx_ct || bR != v.fx_br || bS != v.fx_bs || g.YS != v.fx_ys || p.sigma_w != 1 || p.sigma_h != 1 ||
+            p.R != bR || p.S % bS != 0 || p.C % CT != 0 || p.B % v.TB != 0 || p.W % v.TW != 0 || p.H % v.TH != 0 ||
+            p.K % v.KT() != 0 || !vec_img)
+            g.legal = false;
+    }
     if (v.pipelined) {
         const int64_t thr = v.staging_threads();
         if (g.img_items > v.MAXI * thr || (!g.flt_resident && g.flt_items > v.MAXF * thr)) g.legal = false;

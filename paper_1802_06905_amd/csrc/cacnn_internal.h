@@ -39,6 +39,9 @@ struct VariantInfo {
     int reuse_r;  // > 0: filter-row reuse path compiled for exactly this many taps per contraction tile (sigma_w = 1);
                   // -4: fp32 kernel with the 16-byte-fragment LDS layout (c-slices in multiples of 4 channels)
     float tune;   // measured time of this variant relative to what the planner's cost model predicts (1 = as modelled)
+    // fixed-geometry kernels: the only contraction tile (c-slice, b_r, b_s) the kernel was compiled for; 0 = any
+    // and the staged Image rows sigma_h*(TH-1)+b_s it assumes
+    int fx_ct = 0, fx_br = 0, fx_bs = 0, fx_ys = 0;
     int KT() const { return WM * MBLK * 32; }
     int NT() const { return TB * TW * TH; }
     int threads() const { return WM * WN * (pipelined == 2 ? 128 : 64); }

@@ -1624,6 +1624,77 @@ __device__ __forceinline__ void f32v4_posoff(const KernelArgs& a, int (&posoff)[
     }
 }
 
+// Producer half of the 16-byte-fragment fp32 kernels: stages every unit of this workgroup's tile sequence, one barrier
+// per unit (the consumers execute the matching barriers).
+template <int CTHREADS, int KT, int TB, int TW, int TH, int MAXI, int MAXF>
+__device__ __forceinline__ void f32v4_producer(const KernelArgs& a, f32x4* smem_v, int stid) {
+    const int zero_off = 2 * a.img_buf;
+    F32V4Stager<CTHREADS, TB, MAXI, MAXF> st;
+    st.init(a, stid);
+    // one-time zeros: the zero units, the pad columns of every Filter row in every buffer
+    {
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        if (stid < 32) smem_v[zero_off + stid] = z;
+        const int q4 = a.QE >> 2, used4 = (a.bS * a.CT) >> 2, f4 = a.fpitch >> 2;
+        const int nbuf = a.flt_resident ? 1 : 2;
+        if (q4 > used4) {
+            for (int idx = stid; idx < nbuf * KT * a.bR; idx += CTHREADS) {
+                const int bsel = idx / (KT * a.bR), rem = idx - bsel * KT * a.bR;
+                const int kl = rem / a.bR, r = rem - kl * a.bR;
+                smem_v[a.flt_off + bsel * a.flt_buf + kl * f4 + r * q4 + used4] = z;
+            }
+        }
+    }
+    // Image words are fetched two units ahead (two register sets), Filter words one unit ahead
+    f32x4 ireg0[MAXI][4], ireg1[MAXI][4], freg[MAXF];
+    UnitPos su = first_unit(a, KT, TB, TW, TH);
+    UnitPos lu = su, fu = su;
+    if (lu.t < a.n_tiles) {
+        const UnitBase u = unit_base<4>(a, lu, KT, TB);
+        st.issue_img(a, u, ireg0);
+        st.issue_flt(a, u, freg);
+        advance_unit(a, lu, KT, TB, TW, TH);
+        advance_unit(a, fu, KT, TB, TW, TH);
+    }
+    if (lu.t < a.n_tiles) {
+        st.issue_img(a, unit_base<4>(a, lu, KT, TB), ireg1);
+        advance_unit(a, lu, KT, TB, TW, TH);
+    }
+    if (a.flt_resident) {
+        if (a.vec_flt)
+            stage_filter_f32<CTHREADS, KT, 4>(a, (float*)(smem_v + a.flt_off), stid, 0, 0, 0, 0);
+        else
+            stage_filter_f32<CTHREADS, KT, 1>(a, (float*)(smem_v + a.flt_off), stid, 0, 0, 0, 0);
+    }
+    while (su.t < a.n_tiles) {
+        st.store_img(a, smem_v, 0, ireg0);
+        st.store_flt(a, smem_v, 0, freg);
+        if (lu.t < a.n_tiles) {
+            st.issue_img(a, unit_base<4>(a, lu, KT, TB), ireg0);
+            advance_unit(a, lu, KT, TB, TW, TH);
+        }
+        if (fu.t < a.n_tiles) {
+            st.issue_flt(a, unit_base<4>(a, fu, KT, TB), freg);
+            advance_unit(a, fu, KT, TB, TW, TH);
+        }
+        __syncthreads();
+        advance_unit(a, su, KT, TB, TW, TH);
+        if (su.t >= a.n_tiles) break;
+        st.store_img(a, smem_v, 1, ireg1);
+        st.store_flt(a, smem_v, 1, freg);
+        if (lu.t < a.n_tiles) {
+            st.issue_img(a, unit_base<4>(a, lu, KT, TB), ireg1);
+            advance_unit(a, lu, KT, TB, TW, TH);
+        }
+        if (fu.t < a.n_tiles) {
+            st.issue_flt(a, unit_base<4>(a, fu, KT, TB), freg);
+            advance_unit(a, fu, KT, TB, TW, TH);
+        }
+        __syncthreads();
+        advance_unit(a, su, KT, TB, TW, TH);
+    }
+}
+
 template <int WM, int WN, int MBLK, int NBLK, int TB, int TW, int TH, int MAXI, int MAXF>
 __global__ void __launch_bounds__(WM* WN * 128) conv_f32v4_ws_kernel(const KernelArgs a) {
     constexpr int CTHREADS = WM * WN * 64;
@@ -1634,71 +1705,7 @@ __global__ void __launch_bounds__(WM* WN * 128) conv_f32v4_ws_kernel(const Kerne
     const int zero_off = 2 * a.img_buf;
 
     if (wave_id >= WM * WN) {
-        const int stid = tid - CTHREADS;
-        F32V4Stager<CTHREADS, TB, MAXI, MAXF> st;
-        st.init(a, stid);
-        // one-time zeros: the zero units, the pad columns of every Filter row in every buffer
-        {
-            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-            if (stid < 32) smem_v[zero_off + stid] = z;
-            const int q4 = a.QE >> 2, used4 = (a.bS * a.CT) >> 2, f4 = a.fpitch >> 2;
-            const int nbuf = a.flt_resident ? 1 : 2;
-            if (q4 > used4) {
-                for (int idx = stid; idx < nbuf * KT * a.bR; idx += CTHREADS) {
-                    const int bsel = idx / (KT * a.bR), rem = idx - bsel * KT * a.bR;
-                    const int kl = rem / a.bR, r = rem - kl * a.bR;
-                    smem_v[a.flt_off + bsel * a.flt_buf + kl * f4 + r * q4 + used4] = z;
-                }
-            }
-        }
-        // Image words are fetched two units ahead (two register sets), Filter words one unit ahead
-        f32x4 ireg0[MAXI][4], ireg1[MAXI][4], freg[MAXF];
-        UnitPos su = first_unit(a, KT, TB, TW, TH);
-        UnitPos lu = su, fu = su;
-        if (lu.t < a.n_tiles) {
-            const UnitBase u = unit_base<4>(a, lu, KT, TB);
-            st.issue_img(a, u, ireg0);
-            st.issue_flt(a, u, freg);
-            advance_unit(a, lu, KT, TB, TW, TH);
-            advance_unit(a, fu, KT, TB, TW, TH);
-        }
-        if (lu.t < a.n_tiles) {
-            st.issue_img(a, unit_base<4>(a, lu, KT, TB), ireg1);
-            advance_unit(a, lu, KT, TB, TW, TH);
-        }
-        if (a.flt_resident) {
-            if (a.vec_flt)
-                stage_filter_f32<CTHREADS, KT, 4>(a, (float*)(smem_v + a.flt_off), stid, 0, 0, 0, 0);
-            else
-                stage_filter_f32<CTHREADS, KT, 1>(a, (float*)(smem_v + a.flt_off), stid, 0, 0, 0, 0);
-        }
-        while (su.t < a.n_tiles) {
-            st.store_img(a, smem_v, 0, ireg0);
-            st.store_flt(a, smem_v, 0, freg);
-            if (lu.t < a.n_tiles) {
-                st.issue_img(a, unit_base<4>(a, lu, KT, TB), ireg0);
-                advance_unit(a, lu, KT, TB, TW, TH);
-            }
-            if (fu.t < a.n_tiles) {
-                st.issue_flt(a, unit_base<4>(a, fu, KT, TB), freg);
-                advance_unit(a, fu, KT, TB, TW, TH);
-            }
-            __syncthreads();
-            advance_unit(a, su, KT, TB, TW, TH);
-            if (su.t >= a.n_tiles) break;
-            st.store_img(a, smem_v, 1, ireg1);
-            st.store_flt(a, smem_v, 1, freg);
-            if (lu.t < a.n_tiles) {
-                st.issue_img(a, unit_base<4>(a, lu, KT, TB), ireg1);
-                advance_unit(a, lu, KT, TB, TW, TH);
-            }
-            if (fu.t < a.n_tiles) {
-                st.issue_flt(a, unit_base<4>(a, fu, KT, TB), freg);
-                advance_unit(a, fu, KT, TB, TW, TH);
-            }
-            __syncthreads();
-            advance_unit(a, su, KT, TB, TW, TH);
-        }
+        f32v4_producer<CTHREADS, KT, TB, TW, TH, MAXI, MAXF>(a, smem_v, tid - CTHREADS);
     } else {
         const int lane = tid & 63, wave = wave_id;
         const int wm = wave % WM, wn = wave / WM;
@@ -1722,6 +1729,456 @@ __global__ void __launch_bounds__(WM* WN * 128) conv_f32v4_ws_kernel(const Kerne
             cur = nxt;
             if (have_next) advance_unit(a, nxt, KT, TB, TW, TH);
             buf ^= 1;
+        }
+    }
+}
+
+// ---- fixed-geometry kernels ("fx") ---------------------------------------------------------------------------------
+// Measured on MI355X: a vector-ALU instruction or an LDS read issued by the wave that also issues the MFMAs is not
+// hidden behind a running MFMA (each costs the matrix pipe 6-10 cycles); the same work in another wave of the SIMD
+// is hidden, but an fp32 MFMA stream leaves that other wave only about one vector instruction per MFMA.  So the
+// multiplying waves must carry no address arithmetic at all and the staging waves very little.
+// With the contraction tile (c-slice, b_r = 3, b_s), unit strides and a shape that the tiles divide exactly, all of it
+// is known at compile time: every LDS address of a unit is one per-lane base register plus an immediate offset, a
+// unit is straight-line code (reads and MFMAs only), and a staging item is two registers (global offset, LDS address).
+// The layout constants repeat the host's formulas; the launcher refuses a geometry that differs.
+
+__device__ __forceinline__ void lds_done_then_barrier() {
+    // every LDS access issued so far has completed; then meet the other waves
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+template <int TB, int TW, int TH, int KT, int CT, int BS>
+struct F32V4Fixed {
+    static constexpr int BR = 3;
+    static constexpr int XS = TW + BR - 1, YS = TH - 1 + BS;
+    static constexpr int G = CT / 4, VPR = TB / 4;
+    static constexpr int YP = G * TB;
+    static constexpr int xpitch() {
+        int base = YS * YP, pad = 0;
+        if (TB < 32) {
+            const int want = TB >= 16 ? 2 : 1;
+            while (((base + pad) & 7) != want) ++pad;
+        }
+        return base + pad;
+    }
+    static constexpr int XP = xpitch();
+    static constexpr int Q = BS * CT, QE = (Q + 7) / 8 * 8, G8 = QE / 8, Q4 = QE / 4;
+    static constexpr int F4 = (BR * QE / 4) | 1;
+    static constexpr int GROUPS = BR * G8;
+    static constexpr int IMG_BUF = XS * XP, ZERO_OFF = 2 * IMG_BUF, FLT_OFF = ZERO_OFF + 32, FLT_BUF = KT * F4;
+    static constexpr int PT = 256;      // staging threads
+    static constexpr int IMG_ITEMS = XS * YS * G * VPR, FLT_ITEMS = KT * BR * BS * G;
+    static constexpr int MAXI = (IMG_ITEMS + PT - 1) / PT, MAXF = (FLT_ITEMS + PT - 1) / PT;
+    static_assert(Q % 8 == 0, "fixed fp32 geometry: b_s * c-slice must be a multiple of 8");
+    static_assert(GROUPS % 2 == 0, "fixed fp32 geometry: an even number of fragment groups per unit");
+    static_assert(VPR <= 2, "fixed fp32 geometry: no store swizzle, so at most 8 images per tile row");
+    static_assert(16 * IMG_BUF < 65536 && 16 * FLT_BUF < 65536, "LDS offsets must fit the 16-bit immediate");
+    static bool matches_host(const KernelArgs& a) {
+        return a.sw == 1 && a.sh == 1 && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
+               a.xpitch == XP && a.ypitch == YP && a.QE == QE && a.fpitch == 4 * F4 && a.img_buf == IMG_BUF &&
+               a.flt_off == FLT_OFF && a.flt_buf == FLT_BUF && !a.flt_resident && a.R == BR && a.S % BS == 0 &&
+               a.C % CT == 0 && a.B % TB == 0 && a.W % TW == 0 && a.H % TH == 0 && a.K % KT == 0 && a.vec_img &&
+               a.vec_flt;
+    }
+};
+
+// Staging half of the fixed fp32 kernel.  Image units are fetched two units ahead, Filter units two units ahead.
+template <class GEO, int TB, int TW, int TH, int KT, int CT, int BS>
+__device__ __forceinline__ void f32v4_fx_producer(const KernelArgs& a, f32x4* smem_v, int stid) {
+    constexpr int MAXI = GEO::MAXI, MAXF = GEO::MAXF, PT = GEO::PT;
+    char* const lds = (char*)smem_v;
+    uint32_t ig[MAXI], il[MAXI], fg[MAXF], fl[MAXF];
+    const uint32_t row_bytes = (uint32_t)a.B * 4u;
+#pragma unroll
+    for (int i = 0; i < MAXI; ++i) {
+        int idx = stid + i * PT;
+        if (idx >= GEO::IMG_ITEMS) idx = 0;
+        const int bv = idx % GEO::VPR, t = idx / GEO::VPR;
+        const int x = t % GEO::XS, gq = t / GEO::XS;      // x is the faster index: neighbouring lanes, different banks
+        const int c4 = gq % GEO::G, y = gq / GEO::G;
+        il[i] = (uint32_t)(x * GEO::XP + y * GEO::YP + c4 * TB + bv * 4) * 16u;
+        ig[i] = ((((uint32_t)x * a.IH + y) * a.C + c4 * 4) * a.B + bv * 4) * 4u;
+    }
+#pragma unroll
+    for (int i = 0; i < MAXF; ++i) {
+        int idx = stid + i * PT;
+        if (idx >= GEO::FLT_ITEMS) idx = 0;
+        const int c = (idx % GEO::G) * 4, t = idx / GEO::G;
+        const int sl = t % BS, t2 = t / BS;
+        const int r = t2 % GEO::BR, kl = t2 / GEO::BR;
+        fl[i] = (uint32_t)(GEO::FLT_OFF * 4 + kl * GEO::F4 * 4 + r * GEO::QE + sl * CT + c) * 4u;
+        fg[i] = ((((uint32_t)kl * a.R + r) * a.S + sl) * a.C + c) * 4u;
+    }
+    if (stid < 32) smem_v[GEO::ZERO_OFF + stid] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    f32x4 ireg[2][MAXI][4], freg[2][MAXF];
+    auto issue = [&](const UnitPos& p, int set) {
+        const UnitBase u = unit_base<4>(a, p, KT, TB);
+#pragma unroll
+        for (int i = 0; i < MAXI; ++i)
+            if (i * PT + PT <= GEO::IMG_ITEMS || stid < GEO::IMG_ITEMS - i * PT) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) ireg[set][i][e] = buf_load_f32x4(u.img, ig[i], e * row_bytes);
+            }
+#pragma unroll
+        for (int i = 0; i < MAXF; ++i)
+            if (i * PT + PT <= GEO::FLT_ITEMS || stid < GEO::FLT_ITEMS - i * PT)
+                freg[set][i] = buf_load_f32x4(u.flt, fg[i], 0);
+    };
+    auto store = [&](int set) {   // set is also the LDS buffer
+#pragma unroll
+        for (int i = 0; i < MAXI; ++i)
+            if (i * PT + PT <= GEO::IMG_ITEMS || stid < GEO::IMG_ITEMS - i * PT) {
+#pragma unroll
+                for (int bb = 0; bb < 4; ++bb) {
+                    const f32x4 o = {ireg[set][i][0][bb], ireg[set][i][1][bb], ireg[set][i][2][bb],
+                                     ireg[set][i][3][bb]};
+                    *(f32x4*)(lds + il[i] + 16 * (bb + set * GEO::IMG_BUF)) = o;
+                }
+            }
+#pragma unroll
+        for (int i = 0; i < MAXF; ++i)
+            if (i * PT + PT <= GEO::FLT_ITEMS || stid < GEO::FLT_ITEMS - i * PT)
+                *(f32x4*)(lds + fl[i] + 16 * set * GEO::FLT_BUF) = freg[set][i];
+    };
+
+    UnitPos su = first_unit(a, KT, TB, TW, TH);   // next unit to store
+    UnitPos lu = su;                              // next unit to fetch
+#pragma unroll
+    for (int d = 0; d < 2; ++d)
+        if (lu.t < a.n_tiles) {
+            issue(lu, d);
+            advance_unit(a, lu, KT, TB, TW, TH);
+        }
+    bool done = su.t >= a.n_tiles;
+    while (!done) {
+#pragma unroll
+        for (int ph = 0; ph < 2; ++ph) {
+            if (!done) {
+                store(ph);
+                if (lu.t < a.n_tiles) {
+                    issue(lu, ph);
+                    advance_unit(a, lu, KT, TB, TW, TH);
+                }
+                lds_done_then_barrier();
+                advance_unit(a, su, KT, TB, TW, TH);
+                done = su.t >= a.n_tiles;
+            }
+        }
+    }
+}
+
+template <int WM, int WN, int MBLK, int NBLK, int TB, int TW, int TH, int CT, int BS>
+__global__ void __launch_bounds__(WM* WN * 64 + 256) conv_f32v4_fx_kernel(const KernelArgs a) {
+    constexpr int KT = WM * MBLK * 32;
+    using GEO = F32V4Fixed<TB, TW, TH, KT, CT, BS>;
+    constexpr int CTHREADS = WM * WN * 64;
+    extern __shared__ __align__(16) f32x4 smem_v[];
+    const int tid = threadIdx.x;
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
+
+    if (wave_id >= WM * WN) {
+        f32v4_fx_producer<GEO, TB, TW, TH, KT, CT, BS>(a, smem_v, tid - CTHREADS);
+    } else {
+        const int lane = tid & 63, wave = wave_id;
+        const int wm = wave % WM, wn = wave / WM;
+        const int j = lane & 31, kk = lane >> 5;
+        int posoff[NBLK];
+        f32v4_posoff<NBLK, TB, TW, TH>(a, posoff, wn * NBLK, j, kk);
+        f32x16 acc[MBLK][NBLK];
+        zero_acc(acc);
+        // per-lane bases of the two LDS buffers; everything else in a unit is an immediate offset
+        const f32x4* ap[2];
+        const f32x4* bp[2][NBLK];
+#pragma unroll
+        for (int buf = 0; buf < 2; ++buf) {
+            ap[buf] = smem_v + GEO::FLT_OFF + buf * GEO::FLT_BUF + (wm * MBLK * 32 + j) * GEO::F4 + kk;
+#pragma unroll
+            for (int n = 0; n < NBLK; ++n) bp[buf][n] = smem_v + buf * GEO::IMG_BUF + posoff[n];
+        }
+        f32x4 av[2][MBLK], bv[2][NBLK];
+        auto load_group = [&](int buf, int g, int set) {
+            const int r = g / GEO::G8, t = g % GEO::G8;
+#pragma unroll
+            for (int m = 0; m < MBLK; ++m)
+                av[set][m] = ap[buf][m * 32 * GEO::F4 + r * GEO::Q4 + 2 * t];
+#pragma unroll
+            for (int n = 0; n < NBLK; ++n) bv[set][n] = bp[buf][n][r * GEO::XP + 2 * t * TB];
+        };
+        auto mfma_group = [&](int set) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                    for (int n = 0; n < NBLK; ++n)
+                        acc[m][n] =
+                            __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][m][e], bv[set][n][e], acc[m][n], 0, 0, 0);
+        };
+
+        UnitPos cur = first_unit(a, KT, TB, TW, TH);
+        UnitPos nxt = cur;
+        bool have = cur.t < a.n_tiles;
+        if (have) {
+            advance_unit(a, nxt, KT, TB, TW, TH);
+            lds_done_then_barrier();        // unit 0 is staged
+            load_group(0, 0, 0);
+        }
+        while (have) {
+#pragma unroll
+            for (int buf = 0; buf < 2; ++buf) {
+                if (have) {
+                    const bool have_next = nxt.t < a.n_tiles;
+#pragma unroll
+                    for (int g = 0; g < GEO::GROUPS; ++g) {
+                        if (g + 1 < GEO::GROUPS) {
+                            load_group(buf, g + 1, (g + 1) & 1);
+                        } else if (have_next) {
+                            // the last fragments of this unit are on their way: once they have landed the buffer is
+                            // free for the staging waves, and the first fragments of the next unit are read under
+                            // this group's MFMAs (the staging waves execute one barrier per unit, so the last unit
+                            // has none to meet)
+                            lds_done_then_barrier();
+                            load_group(buf ^ 1, 0, 0);
+                        }
+                        mfma_group(g & 1);
+                        interleave_hint<4 * MBLK * NBLK, MBLK + NBLK>();
+                    }
+                    if (!have_next || nxt.t != cur.t)
+                        write_tile<MBLK, NBLK, TB, TW, TH>(a, cur.tc, acc, wn * NBLK, wm * MBLK * 32, j, kk);
+                    cur = nxt;
+                    have = have_next;
+                    if (have_next) advance_unit(a, nxt, KT, TB, TW, TH);
+                }
+            }
+        }
+    }
+}
+
+// bf16, b_r = 3 taps reused from registers; a wave owns 32 output channels x 32 images x the tile's TW x TH positions
+template <int WM, int MBLK, int TB, int TW, int TH, int CT, int BS>
+struct Bf16Fixed {
+    static constexpr int BR = 3;
+    static constexpr int WN = TB / 32, KT = WM * MBLK * 32, NBLK = TW * TH;
+    static constexpr int C8 = CT / 8, B8 = TB / 8, STEPS = BS * (CT / 16);
+    static constexpr int XS = TW + BR - 1, YS = TH - 1 + BS;
+    static constexpr int YP = C8 * TB, XP = YS * YP;
+    static constexpr int F8 = (BR * BS * C8) | 1;
+    static constexpr int IMG_BUF = XS * XP, FLT_OFF = 2 * IMG_BUF, FLT_BUF = KT * F8;
+    static constexpr int PT = 256;      // staging threads
+    static constexpr int IMG_ITEMS = XS * YS * C8 * B8, FLT_ITEMS = KT * BR * BS * C8;
+    static constexpr int MAXI = (IMG_ITEMS + PT - 1) / PT, MAXF = (FLT_ITEMS + PT - 1) / PT;
+    static_assert(TB == 32 || TB == 64, "fixed bf16 geometry: 32 or 64 images per tile");
+    static_assert(CT % 16 == 0 && STEPS % 2 == 0, "fixed bf16 geometry: an even number of 16-channel steps per unit");
+    static_assert(16 * IMG_BUF < 65536 && 16 * FLT_BUF < 65536, "LDS offsets must fit the 16-bit immediate");
+    static bool matches_host(const KernelArgs& a) {
+        return a.sw == 1 && a.sh == 1 && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
+               a.xpitch == XP && a.ypitch == YP && a.fpitch == 8 * F8 && a.img_buf == IMG_BUF &&
+               a.flt_off == FLT_OFF && a.flt_buf == FLT_BUF && !a.flt_resident && a.R == BR && a.S % BS == 0 &&
+               a.C % CT == 0 && a.B % TB == 0 && a.W % TW == 0 && a.H % TH == 0 && a.K % KT == 0 && a.vec_img &&
+               a.vec_flt;
+    }
+};
+
+template <class GEO, int TB, int TW, int TH, int KT, int CT, int BS>
+__device__ __forceinline__ void bf16_fx_producer(const KernelArgs& a, uint4* smem_u, int stid) {
+    constexpr int MAXI = GEO::MAXI, MAXF = GEO::MAXF, PT = GEO::PT;
+    char* const lds = (char*)smem_u;
+    uint32_t ig[MAXI], il[MAXI], fg[MAXF], fl[MAXF];
+    const uint32_t row_bytes = (uint32_t)a.B * 2u;
+#pragma unroll
+    for (int i = 0; i < MAXI; ++i) {
+        int idx = stid + i * PT;
+        if (idx >= GEO::IMG_ITEMS) idx = 0;
+        const int b8 = idx % GEO::B8, t = idx / GEO::B8;
+        const int c8 = t % GEO::C8, t2 = t / GEO::C8;
+        const int y = t2 % GEO::YS, x = t2 / GEO::YS;
+        // the eight 16-byte units of an item fill one aligned 128-byte group; unit m goes to slot m ^ key
+        il[i] = ((uint32_t)(x * GEO::XP + y * GEO::YP + c8 * TB + b8 * 8) ^ (uint32_t)store_key<TB>(b8, c8)) * 16u;
+        ig[i] = ((((uint32_t)x * a.IH + y) * a.C + c8 * 8) * a.B + b8 * 8) * 2u;
+    }
+#pragma unroll
+    for (int i = 0; i < MAXF; ++i) {
+        int idx = stid + i * PT;
+        if (idx >= GEO::FLT_ITEMS) idx = 0;
+        const int c8 = idx % GEO::C8, t = idx / GEO::C8;
+        const int rs = t % (GEO::BR * BS), kl = t / (GEO::BR * BS);
+        const int r = rs / BS, sl = rs % BS;
+        fl[i] = (uint32_t)(GEO::FLT_OFF + kl * GEO::F8 + rs * GEO::C8 + c8) * 16u;
+        fg[i] = ((((uint32_t)kl * a.R + r) * a.S + sl) * a.C + c8 * 8) * 2u;
+    }
+
+    uint4 ireg[2][MAXI][8], freg[2][MAXF];
+    auto issue = [&](const UnitPos& p, int set) {
+        const UnitBase u = unit_base<2>(a, p, KT, TB);
+#pragma unroll
+        for (int i = 0; i < MAXI; ++i)
+            if (i * PT + PT <= GEO::IMG_ITEMS || stid < GEO::IMG_ITEMS - i * PT) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ireg[set][i][e] = buf_load_u4(u.img, ig[i], e * row_bytes);
+            }
+#pragma unroll
+        for (int i = 0; i < MAXF; ++i)
+            if (i * PT + PT <= GEO::FLT_ITEMS || stid < GEO::FLT_ITEMS - i * PT)
+                freg[set][i] = buf_load_u4(u.flt, fg[i], 0);
+    };
+    auto store = [&](int set) {   // set is also the LDS buffer
+#pragma unroll
+        for (int i = 0; i < MAXI; ++i)
+            if (i * PT + PT <= GEO::IMG_ITEMS || stid < GEO::IMG_ITEMS - i * PT) {
+                // 8x8 transpose of 16-bit words, two columns (images 2m, 2m+1) at a time
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    uint32_t lo[4], hi[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const uint4 re = ireg[set][i][2 * q], ro = ireg[set][i][2 * q + 1];
+                        const uint32_t e = m == 0 ? re.x : m == 1 ? re.y : m == 2 ? re.z : re.w;
+                        const uint32_t o = m == 0 ? ro.x : m == 1 ? ro.y : m == 2 ? ro.z : ro.w;
+                        lo[q] = __builtin_amdgcn_perm(o, e, 0x05040100u);   // low halves:  e.lo | o.lo << 16
+                        hi[q] = __builtin_amdgcn_perm(o, e, 0x07060302u);   // high halves: e.hi | o.hi << 16
+                    }
+                    // il already carries the key in its slot bits, so slot m ^ key is an XOR of the address
+                    *(uint4*)(lds + (il[i] ^ (uint32_t)(32 * m)) + 16 * set * GEO::IMG_BUF) =
+                        make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                    *(uint4*)(lds + (il[i] ^ (uint32_t)(32 * m + 16)) + 16 * set * GEO::IMG_BUF) =
+                        make_uint4(hi[0], hi[1], hi[2], hi[3]);
+                }
+            }
+#pragma unroll
+        for (int i = 0; i < MAXF; ++i)
+            if (i * PT + PT <= GEO::FLT_ITEMS || stid < GEO::FLT_ITEMS - i * PT)
+                *(uint4*)(lds + fl[i] + 16 * set * GEO::FLT_BUF) = freg[set][i];
+    };
+
+    UnitPos su = first_unit(a, KT, TB, TW, TH);   // next unit to store
+    UnitPos lu = su;                              // next unit to fetch
+#pragma unroll
+    for (int d = 0; d < 2; ++d)
+        if (lu.t < a.n_tiles) {
+            issue(lu, d);
+            advance_unit(a, lu, KT, TB, TW, TH);
+        }
+    bool done = su.t >= a.n_tiles;
+    while (!done) {
+#pragma unroll
+        for (int ph = 0; ph < 2; ++ph) {
+            if (!done) {
+                store(ph);
+                if (lu.t < a.n_tiles) {
+                    issue(lu, ph);
+                    advance_unit(a, lu, KT, TB, TW, TH);
+                }
+                lds_done_then_barrier();
+                advance_unit(a, su, KT, TB, TW, TH);
+                done = su.t >= a.n_tiles;
+            }
+        }
+    }
+}
+
+template <int WM, int MBLK, int TB, int TW, int TH, int CT, int BS>
+__global__ void __launch_bounds__(WM*(TB / 32) * 64 + 256) conv_bf16_fx_kernel(const KernelArgs a) {
+    using GEO = Bf16Fixed<WM, MBLK, TB, TW, TH, CT, BS>;
+    constexpr int WN = GEO::WN, KT = GEO::KT, NBLK = GEO::NBLK, BR = GEO::BR, XS = GEO::XS;
+    constexpr int CTHREADS = WM * WN * 64;
+    extern __shared__ __align__(16) uint4 smem_u[];
+    const int tid = threadIdx.x;
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
+
+    if (wave_id >= WM * WN) {
+        bf16_fx_producer<GEO, TB, TW, TH, KT, CT, BS>(a, smem_u, tid - CTHREADS);
+    } else {
+        const int lane = tid & 63, wave = wave_id;
+        const int wm = wave % WM, wn = wave / WM;
+        const int j = lane & 31, g = lane >> 5;
+        f32x16 acc[MBLK][NBLK];
+        zero_acc(acc);
+        // per-lane bases of the two LDS buffers (a lane's c8 has the parity of g, which is all the store key looks at)
+        const int b_l = 32 * wn + j;
+        const int b_sw = (b_l & ~7) | ((b_l & 7) ^ store_key<TB>(b_l >> 3, g));
+        const uint4* ap[2];
+        const uint4* bp[2];
+#pragma unroll
+        for (int buf = 0; buf < 2; ++buf) {
+            ap[buf] = smem_u + GEO::FLT_OFF + buf * GEO::FLT_BUF + (wm * MBLK * 32 + j) * GEO::F8 + g;
+            bp[buf] = smem_u + buf * GEO::IMG_BUF + g * TB + b_sw;
+        }
+        bf16x8 A[2][MBLK][BR], X[2][TH][XS];
+        auto load_step = [&](int buf, int t, int set) {
+            const int sl = t / (CT / 16), cs = t % (CT / 16);
+#pragma unroll
+            for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                for (int r = 0; r < BR; ++r)
+                    A[set][m][r] = __builtin_bit_cast(
+                        bf16x8, ap[buf][m * 32 * GEO::F8 + (r * BS + sl) * GEO::C8 + 2 * cs]);
+#pragma unroll
+            for (int h = 0; h < TH; ++h)
+#pragma unroll
+                for (int x = 0; x < XS; ++x)
+                    X[set][h][x] = __builtin_bit_cast(
+                        bf16x8, bp[buf][x * GEO::XP + (h + sl) * GEO::YP + 2 * cs * TB]);
+        };
+        auto mfma_step = [&](int set) {
+#pragma unroll
+            for (int r = 0; r < BR; ++r)
+#pragma unroll
+                for (int h = 0; h < TH; ++h)
+#pragma unroll
+                    for (int w = 0; w < TW; ++w)
+#pragma unroll
+                        for (int m = 0; m < MBLK; ++m)
+                            acc[m][h * TW + w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                A[set][m][r], X[set][h][w + r], acc[m][h * TW + w], 0, 0, 0);
+        };
+
+        UnitPos cur = first_unit(a, KT, TB, TW, TH);
+        UnitPos nxt = cur;
+        bool have = cur.t < a.n_tiles;
+        if (have) {
+            advance_unit(a, nxt, KT, TB, TW, TH);
+            lds_done_then_barrier();        // unit 0 is staged
+            load_step(0, 0, 0);
+        }
+        while (have) {
+#pragma unroll
+            for (int buf = 0; buf < 2; ++buf) {
+                if (have) {
+                    const bool have_next = nxt.t < a.n_tiles;
+#pragma unroll
+                    for (int t = 0; t < GEO::STEPS; ++t) {
+                        if (t + 1 < GEO::STEPS) {
+                            load_step(buf, t + 1, (t + 1) & 1);
+                        } else if (have_next) {
+                            // as in the fp32 kernel: release the buffer once the last fragments have landed, read
+                            // the next unit's first fragments under this step's MFMAs
+                            lds_done_then_barrier();
+                            load_step(buf ^ 1, 0, 0);
+                        }
+                        mfma_step(t & 1);
+                        interleave_hint<BR * NBLK * MBLK, TH * XS + MBLK * BR>();
+                    }
+                    if (!have_next || nxt.t != cur.t) {
+#pragma unroll
+                        for (int n = 0; n < NBLK; ++n) {
+                            const int b = cur.tc.b0 + b_l, w = cur.tc.w0 + n % TW, h = cur.tc.h0 + n / TW;
+#pragma unroll
+                            for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+                                for (int v = 0; v < 16; ++v) {
+                                    const int k = cur.tc.k0 + (wm * MBLK + m) * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+                                    a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b] = acc[m][n][v];
+                                    acc[m][n][v] = 0.f;
+                                }
+                        }
+                    }
+                    cur = nxt;
+                    have = have_next;
+                    if (have_next) advance_unit(a, nxt, KT, TB, TW, TH);
+                }
+            }
         }
     }
 }
@@ -1784,6 +2241,21 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
+// fixed-geometry variants: GEO is the geometry class whose constants the launch must match
+#define CACNN_FX_VARIANT(DT, NAME, TUNE, WM, WN, MBLK, NBLK, TB, TW, TH, BR, FXCT, FXBS, GEO, ...)             \
+    {                                                                                                          \
+        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH, 2, GEO::MAXI, GEO::MAXF, 1, BR, TUNE, FXCT, 3, FXBS, GEO::YS}, \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                if (!GEO::matches_host(a)) return 1;                                                           \
+                return launch_kernel(__VA_ARGS__, attr_done, WM * WN * 64 + 256, a, grid, lds, stream);        \
+            }                                                                                                  \
+    }
+
+using FxF32B8W4H4 = F32V4Fixed<8, 4, 4, 64, 16, 3>;
+using FxBf16B64W7H1 = Bf16Fixed<2, 1, 64, 7, 1, 32, 1>;
+using FxBf16B64W2H2 = Bf16Fixed<2, 1, 64, 2, 2, 32, 1>;
+
 static const Variant g_variants[] = {
     // fp32
     CACNN_VARIANT(0, conv_f32_kernel, "f32 k32 b1w16h16 w1x4 m1n2", 1, 4, 1, 2, 1, 16, 16),
@@ -1834,6 +2306,13 @@ static const Variant g_variants[] = {
                      conv_f32v4_ws_kernel<2, 2, 1, 2, 32, 2, 2, 3, 10>),
     CACNN_WS_VARIANT(0, "f32 ws4 k64 b16w4h2 w2x2 m1n2", 1.0f, 2, 2, 1, 2, 16, 4, 2, 3, 10, -4,
                      conv_f32v4_ws_kernel<2, 2, 1, 2, 16, 4, 2, 3, 10>),
+    // fixed-geometry kernels (3x3 taps, unit strides, shapes the tiles divide exactly)
+    CACNN_FX_VARIANT(0, "f32 fx k64 b8w4h4 w2x2 m1n2 c16r3s3", 0.85f, 2, 2, 1, 2, 8, 4, 4, -4, 16, 3, FxF32B8W4H4,
+                     conv_f32v4_fx_kernel<2, 2, 1, 2, 8, 4, 4, 16, 3>),
+    CACNN_FX_VARIANT(1, "bf16 fx k64 b64w7h1 w2x2 m1n7 c32r3s1", 0.7f, 2, 2, 1, 7, 64, 7, 1, 3, 32, 1, FxBf16B64W7H1,
+                     conv_bf16_fx_kernel<2, 1, 64, 7, 1, 32, 1>),
+    CACNN_FX_VARIANT(1, "bf16 fx k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.7f, 2, 2, 1, 4, 64, 2, 2, 3, 32, 1, FxBf16B64W2H2,
+                     conv_bf16_fx_kernel<2, 1, 64, 2, 2, 32, 1>),
     // wave-specialised, bf16
     CACNN_WS_VARIANT(1, "bf16 ws k128 b32w2h2 w2x2 m2n2", 1.05f, 2, 2, 2, 2, 32, 2, 2, 1, 9, 0,
                      conv_bf16_ws_kernel<2, 2, 2, 2, 32, 2, 2, 1, 9, 0>),

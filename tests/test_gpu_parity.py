@@ -59,14 +59,19 @@ RAGGED = [
     ("pipe_many_tiles", 32, 8, 64, 50, 46, 3, 3, 1, 1),      # more tiles than resident workgroups
     ("pipe_resident_filter", 32, 3, 64, 21, 20, 7, 7, 2, 2),  # one Filter tile for the whole grid, odd C
     ("pipe_b8", 8, 16, 64, 13, 12, 3, 3, 1, 1),
+    # shapes the fixed-geometry kernels tile exactly (3x3 taps, unit strides), several tiles and several c-slices
+    ("fx_w7", 128, 64, 128, 7, 3, 3, 3, 1, 1),
+    ("fx_w2h2", 64, 96, 192, 4, 6, 3, 3, 1, 1),
+    ("fx_w4h4", 64, 32, 128, 8, 12, 3, 3, 1, 1),
 ]
 
 RAN = {}
 
 
 def is_pipelined(name):
-    """Pipelined / wave-specialised variants only accept 16-byte-legal shapes whose slice fits their staging registers."""
-    return " pipe" in name or " ws" in name
+    """Pipelined / wave-specialised variants only accept 16-byte-legal shapes whose slice fits their staging registers;
+    fixed-geometry variants only their own contraction tile."""
+    return " pipe" in name or " ws" in name or " fx" in name
 
 
 def variants_for(cc, dtype):
@@ -83,7 +88,8 @@ def test_every_variant_on_ragged_shapes(env, shape, dtype):
     img, flt = ci.make_inputs(cfg)
     ref, ab = gu.oracle_full(cfg, img, flt)
     for vi in variants_for(cc, dtype):
-        for (bc, br, bs) in ((1 << 20, 1 << 20, 1 << 20), (16 if dtype == "bf16" else 3, 2, 1)):
+        # the last two tilings are the ones the fixed-geometry kernels are compiled for
+        for (bc, br, bs) in ((1 << 20, 1 << 20, 1 << 20), (16 if dtype == "bf16" else 3, 2, 1), (16, 3, 3), (32, 3, 1)):
             plan = cc.Plan()
             plan.variant, plan.b_c, plan.b_r, plan.b_s = vi, bc, br, bs
             say(f"[parity] {shape[0]} {dtype} variant={vi} '{cc.cacnn_variant_name(vi)}' b_c={bc} b_r={br} b_s={bs}")
@@ -102,7 +108,9 @@ def test_every_variant_ran_on_some_ragged_shape(env):
     cc, torch = env
     for dtype in ("f32", "bf16"):
         for vi in variants_for(cc, dtype):
-            assert RAN.get((dtype, vi), 0) >= 2, f"variant {vi} '{cc.cacnn_variant_name(vi)}' never ran"
+            name = cc.cacnn_variant_name(vi)
+            need = 1 if " fx" in name else 2     # a fixed-geometry kernel accepts one contraction tile only
+            assert RAN.get((dtype, vi), 0) >= need, f"variant {vi} '{name}' ran {RAN.get((dtype, vi), 0)} times"
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
