@@ -1076,7 +1076,12 @@ __device__ __forceinline__ void write_tile(const KernelArgs& a, const TileCoord&
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int k = tc.k0 + row0 + m * 32 + (v >> 2) * 8 + q * 4 + (v & 3);
-                if (pos_ok && k < a.K) a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b] = acc[m][n][v];
+                if (pos_ok && k < a.K) {
+                    float* dst = &a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b];
+                    // whole 128-byte lines per half-wave: stream them past the caches, nobody reads them again
+                    if constexpr (TB >= 32) __builtin_nontemporal_store(acc[m][n][v], dst);
+                    else *dst = acc[m][n][v];
+                }
                 acc[m][n][v] = 0.f;
             }
         }
@@ -1748,6 +1753,53 @@ __device__ __forceinline__ void lds_done_then_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// Wave-uniform walk over the units this workgroup stages, for the fixed-geometry kernels (unit strides, b_r = R, a
+// shape the tiles divide exactly): tiles blockIdx.x, blockIdx.x + gridDim.x, ... of the tile list, and within a tile
+// the contraction slices with c fastest, then s.  Per unit it costs a handful of scalar instructions: the staging
+// waves share the SIMD's issue slots with the MFMA stream and get few of them.
+template <int ESZ, int KT, int TB, int TW, int TH, int CT, int BS>
+struct FxWalk {
+    int t, s0, c0;
+    int64_t img_org, flt_org;      // byte offsets of the current tile's Image / Filter origin (s0 = c0 = 0)
+    int64_t img_bytes, flt_bytes;  // array sizes
+    __device__ __forceinline__ void set_tile(const KernelArgs& a) {
+        const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
+        img_org = ((((int64_t)tc.w0 * a.IH + tc.h0) * a.C) * a.B + tc.b0) * ESZ;
+        flt_org = (int64_t)tc.k0 * a.R * a.S * a.C * ESZ;
+    }
+    __device__ __forceinline__ void init(const KernelArgs& a) {
+        t = blockIdx.x;
+        s0 = c0 = 0;
+        img_bytes = (int64_t)a.IW * a.IH * a.C * a.B * ESZ;
+        flt_bytes = (int64_t)a.K * a.R * a.S * a.C * ESZ;
+        if (t < a.n_tiles) set_tile(a);
+    }
+    __device__ __forceinline__ bool valid(const KernelArgs& a) const { return t < a.n_tiles; }
+    static __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* base, int64_t off, int64_t total) {
+        const uint64_t left = (uint64_t)(total - off);
+        const int32_t n = (left >> 31) ? 0x7fffffff : (int32_t)left;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>((const char*)base + off), 0, n, 0x00020000);
+    }
+    __device__ __forceinline__ __amdgpu_buffer_rsrc_t img(const KernelArgs& a) const {
+        return rsrc(a.image, img_org + (int64_t)((uint32_t)(s0 * a.C + c0) * (uint32_t)a.B) * ESZ, img_bytes);
+    }
+    __device__ __forceinline__ __amdgpu_buffer_rsrc_t flt(const KernelArgs& a) const {
+        return rsrc(a.filter, flt_org + (int64_t)(s0 * a.C + c0) * ESZ, flt_bytes);
+    }
+    __device__ __forceinline__ void next(const KernelArgs& a) {
+        c0 += CT;
+        if (c0 >= a.C) {
+            c0 = 0;
+            s0 += BS;
+            if (s0 >= a.S) {
+                s0 = 0;
+                t += gridDim.x;
+                if (t < a.n_tiles) set_tile(a);
+            }
+        }
+    }
+};
+
 template <int TB, int TW, int TH, int KT, int CT, int BS>
 struct F32V4Fixed {
     static constexpr int BR = 3;
@@ -1783,12 +1835,12 @@ struct F32V4Fixed {
     }
 };
 
-// Staging half of the fixed fp32 kernel.  Image units are fetched two units ahead, Filter units two units ahead.
+// Staging half of the fixed fp32 kernel.  Image and Filter words are fetched two units ahead into two register sets.
 template <class GEO, int TB, int TW, int TH, int KT, int CT, int BS>
 __device__ __forceinline__ void f32v4_fx_producer(const KernelArgs& a, f32x4* smem_v, int stid) {
     constexpr int MAXI = GEO::MAXI, MAXF = GEO::MAXF, PT = GEO::PT;
     char* const lds = (char*)smem_v;
-    uint32_t ig[MAXI], il[MAXI], fg[MAXF], fl[MAXF];
+    uint32_t ig[MAXI], il[MAXI], fg[MAXF], fl[2][MAXF];
     const uint32_t row_bytes = (uint32_t)a.B * 4u;
 #pragma unroll
     for (int i = 0; i < MAXI; ++i) {
@@ -1807,24 +1859,30 @@ __device__ __forceinline__ void f32v4_fx_producer(const KernelArgs& a, f32x4* sm
         const int c = (idx % GEO::G) * 4, t = idx / GEO::G;
         const int sl = t % BS, t2 = t / BS;
         const int r = t2 % GEO::BR, kl = t2 / GEO::BR;
-        fl[i] = (uint32_t)(GEO::FLT_OFF * 4 + kl * GEO::F4 * 4 + r * GEO::QE + sl * CT + c) * 4u;
+        fl[0][i] = (uint32_t)(GEO::FLT_OFF * 4 + kl * GEO::F4 * 4 + r * GEO::QE + sl * CT + c) * 4u;
+        fl[1][i] = fl[0][i] + 16u * GEO::FLT_BUF;
         fg[i] = ((((uint32_t)kl * a.R + r) * a.S + sl) * a.C + c) * 4u;
     }
     if (stid < 32) smem_v[GEO::ZERO_OFF + stid] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    FxWalk<4, KT, TB, TW, TH, CT, BS> lu;     // next unit to fetch
+    lu.init(a);
+    int to_store = 0;                          // units fetched and not yet stored
     f32x4 ireg[2][MAXI][4], freg[2][MAXF];
-    auto issue = [&](const UnitPos& p, int set) {
-        const UnitBase u = unit_base<4>(a, p, KT, TB);
+    auto issue = [&](int set) {
+        const __amdgpu_buffer_rsrc_t ri = lu.img(a), rf = lu.flt(a);
 #pragma unroll
         for (int i = 0; i < MAXI; ++i)
             if (i * PT + PT <= GEO::IMG_ITEMS || stid < GEO::IMG_ITEMS - i * PT) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) ireg[set][i][e] = buf_load_f32x4(u.img, ig[i], e * row_bytes);
+                for (int e = 0; e < 4; ++e) ireg[set][i][e] = buf_load_f32x4(ri, ig[i], e * row_bytes);
             }
 #pragma unroll
         for (int i = 0; i < MAXF; ++i)
             if (i * PT + PT <= GEO::FLT_ITEMS || stid < GEO::FLT_ITEMS - i * PT)
-                freg[set][i] = buf_load_f32x4(u.flt, fg[i], 0);
+                freg[set][i] = buf_load_f32x4(rf, fg[i], 0);
+        lu.next(a);
+        ++to_store;
     };
     auto store = [&](int set) {   // set is also the LDS buffer
 #pragma unroll
@@ -1840,30 +1898,20 @@ __device__ __forceinline__ void f32v4_fx_producer(const KernelArgs& a, f32x4* sm
 #pragma unroll
         for (int i = 0; i < MAXF; ++i)
             if (i * PT + PT <= GEO::FLT_ITEMS || stid < GEO::FLT_ITEMS - i * PT)
-                *(f32x4*)(lds + fl[i] + 16 * set * GEO::FLT_BUF) = freg[set][i];
+                *(f32x4*)(lds + fl[set][i]) = freg[set][i];
+        --to_store;
     };
 
-    UnitPos su = first_unit(a, KT, TB, TW, TH);   // next unit to store
-    UnitPos lu = su;                              // next unit to fetch
 #pragma unroll
     for (int d = 0; d < 2; ++d)
-        if (lu.t < a.n_tiles) {
-            issue(lu, d);
-            advance_unit(a, lu, KT, TB, TW, TH);
-        }
-    bool done = su.t >= a.n_tiles;
-    while (!done) {
+        if (lu.valid(a)) issue(d);
+    while (to_store > 0) {
 #pragma unroll
         for (int ph = 0; ph < 2; ++ph) {
-            if (!done) {
+            if (to_store > 0) {
                 store(ph);
-                if (lu.t < a.n_tiles) {
-                    issue(lu, ph);
-                    advance_unit(a, lu, KT, TB, TW, TH);
-                }
+                if (lu.valid(a)) issue(ph);
                 lds_done_then_barrier();
-                advance_unit(a, su, KT, TB, TW, TH);
-                done = su.t >= a.n_tiles;
             }
         }
     }
@@ -1981,11 +2029,14 @@ struct Bf16Fixed {
     }
 };
 
+// Staging half of the fixed bf16 kernel: two register sets, two units ahead; every store address is precomputed.
 template <class GEO, int TB, int TW, int TH, int KT, int CT, int BS>
 __device__ __forceinline__ void bf16_fx_producer(const KernelArgs& a, uint4* smem_u, int stid) {
+    // staging instructions are few and each unblocks a long latency: let them win issue arbitration where they can
+    __builtin_amdgcn_s_setprio(3);
     constexpr int MAXI = GEO::MAXI, MAXF = GEO::MAXF, PT = GEO::PT;
     char* const lds = (char*)smem_u;
-    uint32_t ig[MAXI], il[MAXI], fg[MAXF], fl[MAXF];
+    uint32_t ig[MAXI], il[2][MAXI][8], fg[MAXF], fl[2][MAXF];
     const uint32_t row_bytes = (uint32_t)a.B * 2u;
 #pragma unroll
     for (int i = 0; i < MAXI; ++i) {
@@ -1994,8 +2045,15 @@ __device__ __forceinline__ void bf16_fx_producer(const KernelArgs& a, uint4* sme
         const int b8 = idx % GEO::B8, t = idx / GEO::B8;
         const int c8 = t % GEO::C8, t2 = t / GEO::C8;
         const int y = t2 % GEO::YS, x = t2 / GEO::YS;
-        // the eight 16-byte units of an item fill one aligned 128-byte group; unit m goes to slot m ^ key
-        il[i] = ((uint32_t)(x * GEO::XP + y * GEO::YP + c8 * TB + b8 * 8) ^ (uint32_t)store_key<TB>(b8, c8)) * 16u;
+        // the eight 16-byte units of an item (one per image) fill one aligned 128-byte group; image m goes to
+        // slot m ^ key so that neighbouring lanes' stores land in different banks
+        const uint32_t base = (uint32_t)(x * GEO::XP + y * GEO::YP + c8 * TB + b8 * 8);
+        const uint32_t key = (uint32_t)store_key<TB>(b8, c8);
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            il[0][i][m] = (base + ((uint32_t)m ^ key)) * 16u;
+            il[1][i][m] = il[0][i][m] + 16u * GEO::IMG_BUF;
+        }
         ig[i] = ((((uint32_t)x * a.IH + y) * a.C + c8 * 8) * a.B + b8 * 8) * 2u;
     }
 #pragma unroll
@@ -2005,23 +2063,29 @@ __device__ __forceinline__ void bf16_fx_producer(const KernelArgs& a, uint4* sme
         const int c8 = idx % GEO::C8, t = idx / GEO::C8;
         const int rs = t % (GEO::BR * BS), kl = t / (GEO::BR * BS);
         const int r = rs / BS, sl = rs % BS;
-        fl[i] = (uint32_t)(GEO::FLT_OFF + kl * GEO::F8 + rs * GEO::C8 + c8) * 16u;
+        fl[0][i] = (uint32_t)(GEO::FLT_OFF + kl * GEO::F8 + rs * GEO::C8 + c8) * 16u;
+        fl[1][i] = fl[0][i] + 16u * GEO::FLT_BUF;
         fg[i] = ((((uint32_t)kl * a.R + r) * a.S + sl) * a.C + c8 * 8) * 2u;
     }
 
+    FxWalk<2, KT, TB, TW, TH, CT, BS> lu;     // next unit to fetch
+    lu.init(a);
+    int to_store = 0;                          // units fetched and not yet stored
     uint4 ireg[2][MAXI][8], freg[2][MAXF];
-    auto issue = [&](const UnitPos& p, int set) {
-        const UnitBase u = unit_base<2>(a, p, KT, TB);
+    auto issue = [&](int set) {
+        const __amdgpu_buffer_rsrc_t ri = lu.img(a), rf = lu.flt(a);
 #pragma unroll
         for (int i = 0; i < MAXI; ++i)
             if (i * PT + PT <= GEO::IMG_ITEMS || stid < GEO::IMG_ITEMS - i * PT) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) ireg[set][i][e] = buf_load_u4(u.img, ig[i], e * row_bytes);
+                for (int e = 0; e < 8; ++e) ireg[set][i][e] = buf_load_u4(ri, ig[i], e * row_bytes);
             }
 #pragma unroll
         for (int i = 0; i < MAXF; ++i)
             if (i * PT + PT <= GEO::FLT_ITEMS || stid < GEO::FLT_ITEMS - i * PT)
-                freg[set][i] = buf_load_u4(u.flt, fg[i], 0);
+                freg[set][i] = buf_load_u4(rf, fg[i], 0);
+        lu.next(a);
+        ++to_store;
     };
     auto store = [&](int set) {   // set is also the LDS buffer
 #pragma unroll
@@ -2039,40 +2103,27 @@ __device__ __forceinline__ void bf16_fx_producer(const KernelArgs& a, uint4* sme
                         lo[q] = __builtin_amdgcn_perm(o, e, 0x05040100u);   // low halves:  e.lo | o.lo << 16
                         hi[q] = __builtin_amdgcn_perm(o, e, 0x07060302u);   // high halves: e.hi | o.hi << 16
                     }
-                    // il already carries the key in its slot bits, so slot m ^ key is an XOR of the address
-                    *(uint4*)(lds + (il[i] ^ (uint32_t)(32 * m)) + 16 * set * GEO::IMG_BUF) =
-                        make_uint4(lo[0], lo[1], lo[2], lo[3]);
-                    *(uint4*)(lds + (il[i] ^ (uint32_t)(32 * m + 16)) + 16 * set * GEO::IMG_BUF) =
-                        make_uint4(hi[0], hi[1], hi[2], hi[3]);
+                    *(uint4*)(lds + il[set][i][2 * m]) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                    *(uint4*)(lds + il[set][i][2 * m + 1]) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
                 }
             }
 #pragma unroll
         for (int i = 0; i < MAXF; ++i)
             if (i * PT + PT <= GEO::FLT_ITEMS || stid < GEO::FLT_ITEMS - i * PT)
-                *(uint4*)(lds + fl[i] + 16 * set * GEO::FLT_BUF) = freg[set][i];
+                *(uint4*)(lds + fl[set][i]) = freg[set][i];
+        --to_store;
     };
 
-    UnitPos su = first_unit(a, KT, TB, TW, TH);   // next unit to store
-    UnitPos lu = su;                              // next unit to fetch
 #pragma unroll
     for (int d = 0; d < 2; ++d)
-        if (lu.t < a.n_tiles) {
-            issue(lu, d);
-            advance_unit(a, lu, KT, TB, TW, TH);
-        }
-    bool done = su.t >= a.n_tiles;
-    while (!done) {
+        if (lu.valid(a)) issue(d);
+    while (to_store > 0) {
 #pragma unroll
         for (int ph = 0; ph < 2; ++ph) {
-            if (!done) {
+            if (to_store > 0) {
                 store(ph);
-                if (lu.t < a.n_tiles) {
-                    issue(lu, ph);
-                    advance_unit(a, lu, KT, TB, TW, TH);
-                }
+                if (lu.valid(a)) issue(ph);
                 lds_done_then_barrier();
-                advance_unit(a, su, KT, TB, TW, TH);
-                done = su.t >= a.n_tiles;
             }
         }
     }
@@ -2169,7 +2220,7 @@ __global__ void __launch_bounds__(WM*(TB / 32) * 64 + 256) conv_bf16_fx_kernel(c
 #pragma unroll
                                 for (int v = 0; v < 16; ++v) {
                                     const int k = cur.tc.k0 + (wm * MBLK + m) * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-                                    a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b] = acc[m][n][v];
+                                    __builtin_nontemporal_store(acc[m][n][v], &a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b]);
                                     acc[m][n][v] = 0.f;
                                 }
                         }
