@@ -187,6 +187,15 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
     g.n_slices = ceil_div(p.R, bR) * ceil_div(p.S, bS) * ceil_div(Cpad, CT);
     g.flt_resident = (g.n_slices == 1 && ceil_div(p.K, v.KT()) == 1 && v.fx_ct == 0) ? 1 : 0;
     const int nbuf_f = g.flt_resident ? 1 : 2;
+    if (v.fx_lds > 0) {
+        // a fixed-geometry kernel with its own LDS layout: one unit per tile, nothing to derive here
+        g.lds_bytes = v.fx_lds;
+        g.img_items = g.flt_items = 1;
+        g.legal = CT == v.fx_ct && bR == v.fx_br && bS == v.fx_bs && g.YS == v.fx_ys && p.sigma_w == v.fx_sw &&
+                  p.sigma_h == v.fx_sh && p.R == bR && p.S == bS && p.C == CT && p.B % v.TB == 0 && p.W % v.TW == 0 &&
+                  p.H % v.TH == 0 && p.K % v.KT() == 0 && vec_img;
+        return g;
+    }
     if (v.dtype == CACNN_F32 && v.f32v4()) {
         // 16-byte units: four consecutive contraction indices of one position
         const int G = CT / 4;
@@ -268,10 +277,10 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
     }
     if (v.reuse_r > 0 && (bR != v.reuse_r || p.sigma_w != 1)) g.legal = false;
     if (v.fx_ct > 0) {
-        // fixed-geometry kernels: their own contraction tile, unit strides, a shape the tiles divide exactly
-        if (CT != v.fx_ct || bR != v.fx_br || bS != v.fx_bs || g.YS != v.fx_ys || p.sigma_w != 1 || p.sigma_h != 1 ||
-            p.R != bR || p.S % bS != 0 || p.C % CT != 0 || p.B % v.TB != 0 || p.W % v.TW != 0 || p.H % v.TH != 0 ||
-            p.K % v.KT() != 0 || !vec_img)
+        // fixed-geometry kernels: their own contraction tile and strides, a shape the tiles divide exactly
+        if (CT != v.fx_ct || bR != v.fx_br || bS != v.fx_bs || g.YS != v.fx_ys || p.sigma_w != v.fx_sw ||
+            p.sigma_h != v.fx_sh || p.R != bR || p.S % bS != 0 || p.C % CT != 0 || p.B % v.TB != 0 ||
+            p.W % v.TW != 0 || p.H % v.TH != 0 || p.K % v.KT() != 0 || !vec_img)
             g.legal = false;
     }
     if (v.pipelined) {

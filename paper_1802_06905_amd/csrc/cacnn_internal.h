@@ -42,6 +42,8 @@ struct VariantInfo {
     // fixed-geometry kernels: the only contraction tile (c-slice, b_r, b_s) the kernel was compiled for; 0 = any
     // and the staged Image rows sigma_h*(TH-1)+b_s it assumes
     int fx_ct = 0, fx_br = 0, fx_bs = 0, fx_ys = 0;
+    int fx_sw = 1, fx_sh = 1;   // the strides it assumes
+    int fx_lds = 0;             // > 0: the kernel has its own LDS layout of this many bytes (and needs C == fx_ct)
     int KT() const { return WM * MBLK * 32; }
     int NT() const { return TB * TW * TH; }
     int threads() const { return WM * WN * (pipelined == 2 ? 128 : 64); }

@@ -1753,8 +1753,8 @@ __device__ __forceinline__ void lds_done_then_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// Wave-uniform walk over the units this workgroup stages, for the fixed-geometry kernels (unit strides, b_r = R, a
-// shape the tiles divide exactly): tiles blockIdx.x, blockIdx.x + gridDim.x, ... of the tile list, and within a tile
+// Wave-uniform walk over the units this workgroup stages, for the fixed-geometry kernels (b_r = R, a shape the tiles
+// divide exactly): tiles blockIdx.x, blockIdx.x + gridDim.x, ... of the tile list, and within a tile
 // the contraction slices with c fastest, then s.  Per unit it costs a handful of scalar instructions: the staging
 // waves share the SIMD's issue slots with the MFMA stream and get few of them.
 template <int ESZ, int KT, int TB, int TW, int TH, int CT, int BS>
@@ -1764,7 +1764,7 @@ struct FxWalk {
     int64_t img_bytes, flt_bytes;  // array sizes
     __device__ __forceinline__ void set_tile(const KernelArgs& a) {
         const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
-        img_org = ((((int64_t)tc.w0 * a.IH + tc.h0) * a.C) * a.B + tc.b0) * ESZ;
+        img_org = ((((int64_t)a.sw * tc.w0 * a.IH + (int64_t)a.sh * tc.h0) * a.C) * a.B + tc.b0) * ESZ;
         flt_org = (int64_t)tc.k0 * a.R * a.S * a.C * ESZ;
     }
     __device__ __forceinline__ void init(const KernelArgs& a) {
@@ -2234,6 +2234,226 @@ __global__ void __launch_bounds__(WM*(TB / 32) * 64 + 256) conv_bf16_fx_kernel(c
     }
 }
 
+// ---- fixed geometry, large strided filter, few channels (the stem-layer shape) --------------------------------------
+// With C = 3 the 16-byte fragments of the kernels above would be mostly padding.  Here the four consecutive
+// contraction indices of a fragment are four filter-row offsets s (padded from S = 7 to 8) of one (r, c):
+// LDS Image [x][c][b][y] with y fastest (YPAD rows per image, XCP floats per (x, c) plane), so a lane's fragment for output row h and tap group kk is the 16 bytes at
+// y = sigma_h*h + 4*kk (read as two 8-byte halves: the address is only 8-byte aligned for odd h), and LDS Filter
+// [k][r][c][s8].  The whole contraction of a tile is one unit; the Filter tile is staged once per workgroup.
+// One zero word per fragment pair is needed: tap s = 7 does not exist, the Filter holds 0 there, and the lanes
+// that would multiply it by the Image row beyond the window supply 0 as well (0 * NaN must not happen).
+template <int TW, int TH, int R, int S, int SW, int SH, int C>
+struct F32StemFixed {
+    static constexpr int TB = 32, KT = 64, WM = 2, WN = 2, NBLK = TW * TH / WN;
+    static constexpr int XS = SW * (TW - 1) + R, YS = SH * (TH - 1) + S;
+    static constexpr int YPAD = SH * (TH - 1) + 8;          // rows a fragment can touch: s runs to 7
+    static constexpr int XCP = TB * YPAD + 2;               // floats per (x, c) plane; +2 spreads the staging stores over the banks
+    static constexpr int IMG_BUF = XS * C * XCP;            // floats
+    static constexpr int FQ = (R * C * 2) | 1;              // Filter row in 16-byte units, odd: conflict-free
+    static constexpr int FLT_OFF = 2 * IMG_BUF;             // floats
+    static constexpr int LDS_BYTES = 4 * FLT_OFF + 16 * KT * FQ;
+    static constexpr int PT = 256;
+    static constexpr int IMG_ITEMS = XS * C * (TB / 4);
+    static constexpr int MAXI = 1, MAXF = 1;
+    static_assert(S == 7 && YS <= YPAD && YPAD % 2 == 0 && (SH * (TH - 1)) % 2 == 0, "stem geometry: 7 taps padded to 8");
+    static_assert((TW * TH) % WN == 0 && IMG_ITEMS <= PT, "stem geometry: one staging item per thread");
+    static_assert(4 * IMG_BUF < 65536 && 16 * 32 * FQ < 65536, "LDS offsets must fit the 16-bit immediate");
+    static bool matches_host(const KernelArgs& a) {
+        return a.sw == SW && a.sh == SH && a.R == R && a.S == S && a.C == C && a.bR == R && a.bS == S && a.CT == C &&
+               a.B % TB == 0 && a.W % TW == 0 && a.H % TH == 0 && a.K % KT == 0 && a.vec_img;
+    }
+};
+
+template <int TW, int TH, int R, int S, int SW, int SH, int C>
+__global__ void __launch_bounds__(512) conv_f32_stem_kernel(const KernelArgs a) {
+    using GEO = F32StemFixed<TW, TH, R, S, SW, SH, C>;
+    constexpr int TB = GEO::TB, KT = GEO::KT, WM = GEO::WM, WN = GEO::WN, NBLK = GEO::NBLK, YPAD = GEO::YPAD;
+    constexpr int CTHREADS = WM * WN * 64;
+    extern __shared__ __align__(16) float smem_f[];
+    const int tid = threadIdx.x;
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
+
+    if (wave_id >= WM * WN) {
+        const int stid = tid - CTHREADS;
+        // ---- once per workgroup: the Filter tile, LDS [k][r][c][s8] (K = KT is not required: k-tile of the first
+        // tile is used for all, the tile order keeps a workgroup inside one k-tile only if tiles_k == 1, so the
+        // Filter tile is restaged whenever the k-tile changes)
+        FxWalk<4, KT, TB, TW, TH, C, S> lu;
+        lu.init(a);
+        int to_store = 0;
+        // Image item of this thread: (x, c, 4 images), rows y = 0 .. YS-1
+        const bool active = stid < GEO::IMG_ITEMS;
+        const int idx = active ? stid : 0;
+        const int bq = idx % (TB / 4), t = idx / (TB / 4);
+        const int c = t % C, x = t / C;
+        const uint32_t ig = (((uint32_t)x * a.IH * a.C + c) * a.B + bq * 4) * 4u;
+        const uint32_t row_bytes = (uint32_t)a.C * a.B * 4u;
+        const uint32_t il = (uint32_t)((x * C + c) * GEO::XCP + bq * 4 * YPAD) * 4u;
+        char* const lds = (char*)smem_f;
+        // rows beyond the window (y >= YS) are only ever multiplied by 0, and must hold 0 themselves
+        if (active) {
+#pragma unroll
+            for (int buf = 0; buf < 2; ++buf)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+#pragma unroll
+                    for (int y = GEO::YS; y < YPAD; ++y)
+                        *(float*)(lds + il + 4 * (buf * GEO::IMG_BUF + b * YPAD + y)) = 0.f;
+        }
+        f32x4 ireg[2][GEO::YS];
+        int flt_k0 = -1;
+        auto issue = [&](int set) {
+            const __amdgpu_buffer_rsrc_t ri = lu.img(a);
+            if (active) {
+#pragma unroll
+                for (int y = 0; y < GEO::YS; ++y) ireg[set][y] = buf_load_f32x4(ri, ig, y * row_bytes);
+            }
+            lu.next(a);
+            ++to_store;
+        };
+        auto store = [&](int set) {
+            if (active) {
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    float* dst = (float*)(lds + il + 4 * (set * GEO::IMG_BUF + b * YPAD));
+#pragma unroll
+                    for (int y = 0; y < GEO::YS; ++y) dst[y] = ireg[set][y][b];
+                }
+            }
+            --to_store;
+        };
+        auto stage_filter = [&](int k0) {
+            // Filter [K][R][S][C] -> LDS [k][r][c][s8], s = 7 zero
+            float* s_flt = smem_f + GEO::FLT_OFF;
+            for (int e = stid; e < KT * R * C * 8; e += GEO::PT) {
+                const int sl = e & 7, rc = (e >> 3) % (R * C), kl = (e >> 3) / (R * C);
+                const int r = rc / C, cc = rc % C;
+                float v = 0.f;
+                if (sl < S) v = ((const float*)a.filter)[(((int64_t)(k0 + kl) * R + r) * S + sl) * C + cc];
+                s_flt[kl * GEO::FQ * 4 + rc * 8 + sl] = v;
+            }
+        };
+        // tile sequence of this workgroup, as the consumers walk it
+        UnitPos su = first_unit(a, KT, TB, TW, TH);
+#pragma unroll
+        for (int d = 0; d < 2; ++d)
+            if (lu.valid(a)) issue(d);
+        while (to_store > 0) {
+#pragma unroll
+            for (int ph = 0; ph < 2; ++ph) {
+                if (to_store > 0) {
+                    if (su.tc.k0 != flt_k0) {
+                        // the consumers are between tiles of different k-tiles only at a barrier; the Filter tile
+                        // is single-buffered, so hand over in two steps: wait until they have finished the old one
+                        if (flt_k0 >= 0) lds_done_then_barrier();
+                        flt_k0 = su.tc.k0;
+                        stage_filter(flt_k0);
+                    }
+                    store(ph);
+                    if (lu.valid(a)) issue(ph);
+                    lds_done_then_barrier();
+                    su.t += gridDim.x;
+                    if (su.t < a.n_tiles) su.tc = decode_tile_index(a, su.t, KT, TB, TW, TH);
+                }
+            }
+        }
+    } else {
+        const int lane = tid & 63, wave = wave_id;
+        const int wm = wave % WM, wn = wave / WM;
+        const int j = lane & 31, kk = lane >> 5;
+        f32x16 acc[NBLK];
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
+        const char* const lds = (const char*)smem_f;
+        const char* const ap = lds + 4 * GEO::FLT_OFF + ((wm * 32 + j) * GEO::FQ + kk) * 16;
+        // one base register per (x, c) plane and buffer: the 8-byte pair reads reach only 2 KB past their base
+        uint32_t plane[2][GEO::XS * C];
+#pragma unroll
+        for (int buf = 0; buf < 2; ++buf)
+#pragma unroll
+            for (int pl = 0; pl < GEO::XS * C; ++pl) {
+                plane[buf][pl] = 4u * (uint32_t)(buf * GEO::IMG_BUF + pl * GEO::XCP + j * YPAD + 4 * kk);
+                asm volatile("" : "+v"(plane[buf][pl]));     // keep it in its register, do not re-derive it per read
+            }
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+        UnitPos cur = first_unit(a, KT, TB, TW, TH);
+        bool have = cur.t < a.n_tiles;
+        int flt_k0 = have ? cur.tc.k0 : -1;
+        if (have) lds_done_then_barrier();        // tile 0 (and the Filter tile) is staged
+        while (have) {
+#pragma unroll
+            for (int buf = 0; buf < 2; ++buf) {
+                if (have) {
+                    UnitPos nxt = cur;
+                    nxt.t += gridDim.x;
+                    const bool have_next = nxt.t < a.n_tiles;
+                    if (have_next) nxt.tc = decode_tile_index(a, nxt.t, KT, TB, TW, TH);
+                    f32x4 av[2];
+                    f32x2 blo[2][NBLK], bhi[2][NBLK];
+                    auto load_rc = [&](int rc, int set) {
+                        const int r = rc / C, cc = rc % C;
+                        av[set] = *(const f32x4*)(ap + rc * 32);
+#pragma unroll
+                        for (int n = 0; n < NBLK; ++n) {
+                            const int nn = wn * NBLK + n, w_l = nn % TW, h_l = nn / TW;
+                            const char* src = lds + plane[buf][(SW * w_l + r) * C + cc] + 4 * SH * h_l;
+                            blo[set][n] = *(const f32x2*)(src);
+                            bhi[set][n] = *(const f32x2*)(src + 8);
+                        }
+                    };
+                    auto mfma_rc = [&](int set) {
+                        float b3[NBLK];
+#pragma unroll
+                        for (int n = 0; n < NBLK; ++n) b3[n] = kk ? 0.f : bhi[set][n][1];     // tap s = 7 does not exist
+#pragma unroll
+                        for (int n = 0; n < NBLK; ++n)
+                            acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][0], blo[set][n][0], acc[n], 0, 0, 0);
+#pragma unroll
+                        for (int n = 0; n < NBLK; ++n)
+                            acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][1], blo[set][n][1], acc[n], 0, 0, 0);
+#pragma unroll
+                        for (int n = 0; n < NBLK; ++n)
+                            acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][2], bhi[set][n][0], acc[n], 0, 0, 0);
+#pragma unroll
+                        for (int n = 0; n < NBLK; ++n)
+                            acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][3], b3[n], acc[n], 0, 0, 0);
+                    };
+                    load_rc(0, 0);
+#pragma unroll
+                    for (int rc = 0; rc < R * C; ++rc) {
+                        if (rc + 1 < R * C) load_rc(rc + 1, (rc + 1) & 1);
+                        mfma_rc(rc & 1);
+                    }
+                    // Out tile: block n is output column w_l, row h_l; a lane owns image j
+#pragma unroll
+                    for (int n = 0; n < NBLK; ++n) {
+                        const int nn = wn * NBLK + n;
+                        const int b = cur.tc.b0 + j, w = cur.tc.w0 + nn % TW, h = cur.tc.h0 + nn / TW;
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int k = cur.tc.k0 + wm * 32 + (v >> 2) * 8 + kk * 4 + (v & 3);
+                            __builtin_nontemporal_store(acc[n][v], &a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b]);
+                            acc[n][v] = 0.f;
+                        }
+                    }
+                    if (have_next) {
+                        if (nxt.tc.k0 != flt_k0) {
+                            lds_done_then_barrier();      // done with the old Filter tile
+                            flt_k0 = nxt.tc.k0;
+                        }
+                        lds_done_then_barrier();          // next tile staged; this tile's buffer is free again
+                    }
+                    cur = nxt;
+                    have = have_next;
+                }
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------------
 // launch table
 
@@ -2295,7 +2515,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 // fixed-geometry variants: GEO is the geometry class whose constants the launch must match
 #define CACNN_FX_VARIANT(DT, NAME, TUNE, WM, WN, MBLK, NBLK, TB, TW, TH, BR, FXCT, FXBS, GEO, ...)             \
     {                                                                                                          \
-        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH, 2, GEO::MAXI, GEO::MAXF, 1, BR, TUNE, FXCT, 3, FXBS, GEO::YS}, \
+        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH, 2, GEO::MAXI, GEO::MAXF, 1, BR, TUNE, FXCT, 3, FXBS, GEO::YS},    \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!GEO::matches_host(a)) return 1;                                                           \
@@ -2303,6 +2523,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
+using FxStem7 = F32StemFixed<2, 2, 7, 7, 2, 2, 3>;
 using FxF32B8W4H4 = F32V4Fixed<8, 4, 4, 64, 16, 3>;
 using FxBf16B64W7H1 = Bf16Fixed<2, 1, 64, 7, 1, 32, 1>;
 using FxBf16B64W2H2 = Bf16Fixed<2, 1, 64, 2, 2, 32, 1>;
@@ -2364,6 +2585,14 @@ static const Variant g_variants[] = {
                      conv_bf16_fx_kernel<2, 1, 64, 7, 1, 32, 1>),
     CACNN_FX_VARIANT(1, "bf16 fx k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.7f, 2, 2, 1, 4, 64, 2, 2, 3, 32, 1, FxBf16B64W2H2,
                      conv_bf16_fx_kernel<2, 1, 64, 2, 2, 32, 1>),
+    // fixed geometry for the stem-layer shape: 7x7 taps, strides 2, three channels
+    {{"f32 fxs k64 b32w2h2 w2x2 m1n2 c3r7s7 s2", 0, 2, 2, 1, FxStem7::NBLK, 32, 2, 2, 2, 1, 1, 1, 0, 0.6f, 3, 7, 7, FxStem7::YS, 2,
+      2, FxStem7::LDS_BYTES},
+     [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {
+         static bool attr_done = false;
+         if (!FxStem7::matches_host(a) || lds != (size_t)FxStem7::LDS_BYTES) return 1;
+         return launch_kernel(conv_f32_stem_kernel<2, 2, 7, 7, 2, 2, 3>, attr_done, 512, a, grid, lds, stream);
+     }},
     // wave-specialised, bf16
     CACNN_WS_VARIANT(1, "bf16 ws k128 b32w2h2 w2x2 m2n2", 1.05f, 2, 2, 2, 2, 32, 2, 2, 1, 9, 0,
                      conv_bf16_ws_kernel<2, 2, 2, 2, 32, 2, 2, 1, 9, 0>),

@@ -145,7 +145,7 @@ def test_plan_gpu_block_is_feasible(name):
     assert 0 < plan.lds_bytes_used <= 160 * 1024
     cdiv = lambda a, b: -(-a // b)
     tiles = cdiv(cfg.K, plan.b_k) * cdiv(cfg.B, plan.b_b) * cdiv(cfg.W, plan.b_w) * cdiv(cfg.H, plan.b_h)
-    if " pipe" in cc.cacnn_variant_name(plan.variant) or " ws" in cc.cacnn_variant_name(plan.variant):
+    if any(f in cc.cacnn_variant_name(plan.variant) for f in (" pipe", " ws", " fx")):
         assert 1 <= plan.grid[0] <= min(tiles, 2 * 256)      # persistent workgroups walk the tiles
     else:
         assert plan.grid[0] == tiles
