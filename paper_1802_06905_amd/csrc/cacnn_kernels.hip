@@ -2323,15 +2323,31 @@ __global__ void __launch_bounds__(512) conv_f32_stem_kernel(const KernelArgs a) 
             --to_store;
         };
         auto stage_filter = [&](int k0) {
-            // Filter [K][R][S][C] -> LDS [k][r][c][s8], s = 7 zero
+            // Filter [K][R][S][C] -> LDS [k][r][c][s8], s = 7 zero.  The KT rows of the tile are one contiguous run in
+            // global memory: read it in order (coalesced, all loads of a batch in flight together), scatter into LDS.
             float* s_flt = smem_f + GEO::FLT_OFF;
-            for (int e = stid; e < KT * R * C * 8; e += GEO::PT) {
-                const int sl = e & 7, rc = (e >> 3) % (R * C), kl = (e >> 3) / (R * C);
-                const int r = rc / C, cc = rc % C;
-                float v = 0.f;
-                if (sl < S) v = ((const float*)a.filter)[(((int64_t)(k0 + kl) * R + r) * S + sl) * C + cc];
-                s_flt[kl * GEO::FQ * 4 + rc * 8 + sl] = v;
+            constexpr int ROW = R * S * C, TOTAL = KT * ROW, BATCH = 8;
+            const float* src = (const float*)a.filter + (int64_t)k0 * ROW;
+            for (int e0 = 0; e0 < TOTAL; e0 += BATCH * GEO::PT) {
+                float v[BATCH];
+#pragma unroll
+                for (int u = 0; u < BATCH; ++u) {
+                    const int e = e0 + u * GEO::PT + stid;
+                    v[u] = e < TOTAL ? src[e] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < BATCH; ++u) {
+                    const int e = e0 + u * GEO::PT + stid;
+                    if (e < TOTAL) {
+                        const int kl = e / ROW, q = e % ROW;
+                        const int r = q / (S * C), sc = q % (S * C);
+                        const int sl = sc / C, cc = sc % C;
+                        s_flt[kl * GEO::FQ * 4 + (r * C + cc) * 8 + sl] = v[u];
+                    }
+                }
             }
+            for (int e = stid; e < KT * R * C; e += GEO::PT)
+                s_flt[(e / (R * C)) * GEO::FQ * 4 + (e % (R * C)) * 8 + 7] = 0.f;
         };
         // tile sequence of this workgroup, as the consumers walk it
         UnitPos su = first_unit(a, KT, TB, TW, TH);
@@ -2379,6 +2395,8 @@ __global__ void __launch_bounds__(512) conv_f32_stem_kernel(const KernelArgs a) 
             }
         typedef float f32x2 __attribute__((ext_vector_type(2)));
 
+        const int64_t out_kstride = (int64_t)a.H * a.W * a.B;                    // floats between output channels
+        const uint32_t out_lane = (uint32_t)(kk * 4) * (uint32_t)out_kstride + j;  // < 2^31: checked by the host
         UnitPos cur = first_unit(a, KT, TB, TW, TH);
         bool have = cur.t < a.n_tiles;
         int flt_k0 = have ? cur.tc.k0 : -1;
@@ -2426,16 +2444,19 @@ __global__ void __launch_bounds__(512) conv_f32_stem_kernel(const KernelArgs a) 
                     for (int rc = 0; rc < R * C; ++rc) {
                         if (rc + 1 < R * C) load_rc(rc + 1, (rc + 1) & 1);
                         mfma_rc(rc & 1);
+                        interleave_hint<4 * NBLK, 1 + NBLK>();
                     }
-                    // Out tile: block n is output column w_l, row h_l; a lane owns image j
+                    // Out tile: block n is output column w_l, row h_l; a lane owns image j.  Every address is a
+                    // wave-uniform base (scalar arithmetic) plus the lane's constant 32-bit offset.
 #pragma unroll
                     for (int n = 0; n < NBLK; ++n) {
                         const int nn = wn * NBLK + n;
-                        const int b = cur.tc.b0 + j, w = cur.tc.w0 + nn % TW, h = cur.tc.h0 + nn / TW;
+                        const int w = cur.tc.w0 + nn % TW, h = cur.tc.h0 + nn / TW;
+                        float* const blk = a.out + ((((int64_t)(cur.tc.k0 + wm * 32) * a.H + h) * a.W + w) * a.B + cur.tc.b0);
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
-                            const int k = cur.tc.k0 + wm * 32 + (v >> 2) * 8 + kk * 4 + (v & 3);
-                            __builtin_nontemporal_store(acc[n][v], &a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b]);
+                            float* const row = blk + (int64_t)((v >> 2) * 8 + (v & 3)) * out_kstride;
+                            __builtin_nontemporal_store(acc[n][v], row + out_lane);
                             acc[n][v] = 0.f;
                         }
                     }
