@@ -2397,10 +2397,44 @@ __global__ void __launch_bounds__(512) conv_f32_stem_kernel(const KernelArgs a) 
 
         const int64_t out_kstride = (int64_t)a.H * a.W * a.B;                    // floats between output channels
         const uint32_t out_lane = (uint32_t)(kk * 4) * (uint32_t)out_kstride + j;  // < 2^31: checked by the host
+        f32x4 av[2];
+        f32x2 blo[2][NBLK], bhi[2][NBLK];
+        auto load_rc = [&](int buf, int rc, int set) {
+            const int r = rc / C, cc = rc % C;
+            av[set] = *(const f32x4*)(ap + rc * 32);
+#pragma unroll
+            for (int n = 0; n < NBLK; ++n) {
+                const int nn = wn * NBLK + n, w_l = nn % TW, h_l = nn / TW;
+                const char* src = lds + plane[buf][(SW * w_l + r) * C + cc] + 4 * SH * h_l;
+                blo[set][n] = *(const f32x2*)(src);
+                bhi[set][n] = *(const f32x2*)(src + 8);
+            }
+        };
+        auto mfma_rc = [&](int set) {
+            float b3[NBLK];
+#pragma unroll
+            for (int n = 0; n < NBLK; ++n) b3[n] = kk ? 0.f : bhi[set][n][1];     // tap s = 7 does not exist
+#pragma unroll
+            for (int n = 0; n < NBLK; ++n)
+                acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][0], blo[set][n][0], acc[n], 0, 0, 0);
+#pragma unroll
+            for (int n = 0; n < NBLK; ++n)
+                acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][1], blo[set][n][1], acc[n], 0, 0, 0);
+#pragma unroll
+            for (int n = 0; n < NBLK; ++n)
+                acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][2], bhi[set][n][0], acc[n], 0, 0, 0);
+#pragma unroll
+            for (int n = 0; n < NBLK; ++n)
+                acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][3], b3[n], acc[n], 0, 0, 0);
+        };
+
         UnitPos cur = first_unit(a, KT, TB, TW, TH);
         bool have = cur.t < a.n_tiles;
         int flt_k0 = have ? cur.tc.k0 : -1;
-        if (have) lds_done_then_barrier();        // tile 0 (and the Filter tile) is staged
+        if (have) {
+            lds_done_then_barrier();        // tile 0 (and the Filter tile) is staged
+            load_rc(0, 0, 0);
+        }
         while (have) {
 #pragma unroll
             for (int buf = 0; buf < 2; ++buf) {
@@ -2409,41 +2443,26 @@ __global__ void __launch_bounds__(512) conv_f32_stem_kernel(const KernelArgs a) 
                     nxt.t += gridDim.x;
                     const bool have_next = nxt.t < a.n_tiles;
                     if (have_next) nxt.tc = decode_tile_index(a, nxt.t, KT, TB, TW, TH);
-                    f32x4 av[2];
-                    f32x2 blo[2][NBLK], bhi[2][NBLK];
-                    auto load_rc = [&](int rc, int set) {
-                        const int r = rc / C, cc = rc % C;
-                        av[set] = *(const f32x4*)(ap + rc * 32);
-#pragma unroll
-                        for (int n = 0; n < NBLK; ++n) {
-                            const int nn = wn * NBLK + n, w_l = nn % TW, h_l = nn / TW;
-                            const char* src = lds + plane[buf][(SW * w_l + r) * C + cc] + 4 * SH * h_l;
-                            blo[set][n] = *(const f32x2*)(src);
-                            bhi[set][n] = *(const f32x2*)(src + 8);
-                        }
-                    };
-                    auto mfma_rc = [&](int set) {
-                        float b3[NBLK];
-#pragma unroll
-                        for (int n = 0; n < NBLK; ++n) b3[n] = kk ? 0.f : bhi[set][n][1];     // tap s = 7 does not exist
-#pragma unroll
-                        for (int n = 0; n < NBLK; ++n)
-                            acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][0], blo[set][n][0], acc[n], 0, 0, 0);
-#pragma unroll
-                        for (int n = 0; n < NBLK; ++n)
-                            acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][1], blo[set][n][1], acc[n], 0, 0, 0);
-#pragma unroll
-                        for (int n = 0; n < NBLK; ++n)
-                            acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][2], bhi[set][n][0], acc[n], 0, 0, 0);
-#pragma unroll
-                        for (int n = 0; n < NBLK; ++n)
-                            acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][3], b3[n], acc[n], 0, 0, 0);
-                    };
-                    load_rc(0, 0);
+                    // group rc of the tile in buffer buf uses register set (rc + buf) & 1: R*C is odd, so the first
+                    // group of the next tile lands in the set the last group of this one does not use
+                    static_assert((R * C) % 2 == 1, "stem geometry: odd number of (r, c) groups");
 #pragma unroll
                     for (int rc = 0; rc < R * C; ++rc) {
-                        if (rc + 1 < R * C) load_rc(rc + 1, (rc + 1) & 1);
-                        mfma_rc(rc & 1);
+                        const int set = (rc + buf) & 1;
+                        if (rc + 1 < R * C) {
+                            load_rc(buf, rc + 1, set ^ 1);
+                        } else if (have_next) {
+                            // every fragment of this tile has been requested: once they have landed the buffer goes
+                            // back to the staging waves, and the first fragments of the next tile are read under
+                            // this group's MFMAs and the Out stores
+                            if (nxt.tc.k0 != flt_k0) {
+                                lds_done_then_barrier();      // done with the old Filter tile
+                                flt_k0 = nxt.tc.k0;
+                            }
+                            lds_done_then_barrier();
+                            load_rc(buf ^ 1, 0, set ^ 1);
+                        }
+                        mfma_rc(set);
                         interleave_hint<4 * NBLK, 1 + NBLK>();
                     }
                     // Out tile: block n is output column w_l, row h_l; a lane owns image j.  Every address is a
@@ -2459,13 +2478,6 @@ __global__ void __launch_bounds__(512) conv_f32_stem_kernel(const KernelArgs a) 
                             __builtin_nontemporal_store(acc[n][v], row + out_lane);
                             acc[n][v] = 0.f;
                         }
-                    }
-                    if (have_next) {
-                        if (nxt.tc.k0 != flt_k0) {
-                            lds_done_then_barrier();      // done with the old Filter tile
-                            flt_k0 = nxt.tc.k0;
-                        }
-                        lds_done_then_barrier();          // next tile staged; this tile's buffer is free again
                     }
                     cur = nxt;
                     have = have_next;
