@@ -1748,6 +1748,20 @@ __global__ void __launch_bounds__(WM* WN * 128) conv_f32v4_ws_kernel(const Kerne
 // unit is straight-line code (reads and MFMAs only), and a staging item is two registers (global offset, LDS address).
 // The layout constants repeat the host's formulas; the launcher refuses a geometry that differs.
 
+// Out words of one 32x32 accumulator block of a tile that lies wholly inside Out: every address is a wave-uniform base
+// (scalar arithmetic) plus the lane's constant 32-bit offset, which holds the lane's row group q*4*kstride and its
+// column.  Resets the accumulators.
+template <bool STREAM>
+__device__ __forceinline__ void store_block_exact(float* base, int64_t kstride, uint32_t lane_off, f32x16& acc) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        float* const row = base + (int64_t)((v >> 2) * 8 + (v & 3)) * kstride;
+        if constexpr (STREAM) __builtin_nontemporal_store(acc[v], row + lane_off);
+        else row[lane_off] = acc[v];
+        acc[v] = 0.f;
+    }
+}
+
 __device__ __forceinline__ void lds_done_then_barrier() {
     // every LDS access issued so far has completed; then meet the other waves
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -1965,6 +1979,8 @@ __global__ void __launch_bounds__(WM* WN * 64 + 256) conv_f32v4_fx_kernel(const 
                             __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][m][e], bv[set][n][e], acc[m][n], 0, 0, 0);
         };
 
+        const int64_t out_kstride = (int64_t)a.H * a.W * a.B;      // floats between output channels
+        const uint32_t out_lane = (uint32_t)(kk * 4) * (uint32_t)out_kstride + (uint32_t)((j / TB) * a.B + j % TB);
         UnitPos cur = first_unit(a, KT, TB, TW, TH);
         UnitPos nxt = cur;
         bool have = cur.t < a.n_tiles;
@@ -1993,8 +2009,18 @@ __global__ void __launch_bounds__(WM* WN * 64 + 256) conv_f32v4_fx_kernel(const 
                         mfma_group(g & 1);
                         interleave_hint<4 * MBLK * NBLK, MBLK + NBLK>();
                     }
-                    if (!have_next || nxt.t != cur.t)
-                        write_tile<MBLK, NBLK, TB, TW, TH>(a, cur.tc, acc, wn * NBLK, wm * MBLK * 32, j, kk);
+                    if (!have_next || nxt.t != cur.t) {
+                        // one block of 32 columns is one output row of the tile (TB * TW = 32)
+                        static_assert(TB * TW == 32, "fixed fp32 kernel: a column block is one tile row");
+#pragma unroll
+                        for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+                            for (int m = 0; m < MBLK; ++m) {
+                                float* const blk = a.out + ((((int64_t)(cur.tc.k0 + (wm * MBLK + m) * 32) * a.H +
+                                                              cur.tc.h0 + wn * NBLK + n) * a.W + cur.tc.w0) * a.B + cur.tc.b0);
+                                store_block_exact<false>(blk, out_kstride, out_lane, acc[m][n]);
+                            }
+                    }
                     cur = nxt;
                     have = have_next;
                     if (have_next) advance_unit(a, nxt, KT, TB, TW, TH);
@@ -2185,6 +2211,8 @@ __global__ void __launch_bounds__(WM*(TB / 32) * 64 + 256) conv_bf16_fx_kernel(c
                                 A[set][m][r], X[set][h][w + r], acc[m][h * TW + w], 0, 0, 0);
         };
 
+        const int64_t out_kstride = (int64_t)a.H * a.W * a.B;      // floats between output channels
+        const uint32_t out_lane = (uint32_t)(g * 4) * (uint32_t)out_kstride + (uint32_t)b_l;
         UnitPos cur = first_unit(a, KT, TB, TW, TH);
         UnitPos nxt = cur;
         bool have = cur.t < a.n_tiles;
@@ -2213,17 +2241,13 @@ __global__ void __launch_bounds__(WM*(TB / 32) * 64 + 256) conv_bf16_fx_kernel(c
                     }
                     if (!have_next || nxt.t != cur.t) {
 #pragma unroll
-                        for (int n = 0; n < NBLK; ++n) {
-                            const int b = cur.tc.b0 + b_l, w = cur.tc.w0 + n % TW, h = cur.tc.h0 + n / TW;
+                        for (int n = 0; n < NBLK; ++n)
 #pragma unroll
-                            for (int m = 0; m < MBLK; ++m)
-#pragma unroll
-                                for (int v = 0; v < 16; ++v) {
-                                    const int k = cur.tc.k0 + (wm * MBLK + m) * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-                                    __builtin_nontemporal_store(acc[m][n][v], &a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b]);
-                                    acc[m][n][v] = 0.f;
-                                }
-                        }
+                            for (int m = 0; m < MBLK; ++m) {
+                                float* const blk = a.out + ((((int64_t)(cur.tc.k0 + (wm * MBLK + m) * 32) * a.H +
+                                                              cur.tc.h0 + n / TW) * a.W + cur.tc.w0 + n % TW) * a.B + cur.tc.b0);
+                                store_block_exact<true>(blk, out_kstride, out_lane, acc[m][n]);
+                            }
                     }
                     cur = nxt;
                     have = have_next;
