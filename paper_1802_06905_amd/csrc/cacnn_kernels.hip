@@ -2058,8 +2058,6 @@ struct Bf16Fixed {
 // Staging half of the fixed bf16 kernel: two register sets, two units ahead; every store address is precomputed.
 template <class GEO, int TB, int TW, int TH, int KT, int CT, int BS>
 __device__ __forceinline__ void bf16_fx_producer(const KernelArgs& a, uint4* smem_u, int stid) {
-    // staging instructions are few and each unblocks a long latency: let them win issue arbitration where they can
-    __builtin_amdgcn_s_setprio(3);
     constexpr int MAXI = GEO::MAXI, MAXF = GEO::MAXF, PT = GEO::PT;
     char* const lds = (char*)smem_u;
     uint32_t ig[MAXI], il[2][MAXI][8], fg[MAXF], fl[2][MAXF];
