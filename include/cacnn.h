@@ -132,7 +132,8 @@ int cacnn_tile_plan(const cacnn_problem* problem, int dtype, const cacnn_machine
  * keeps no reference to the buffers.  The caller owns all three buffers.  Pointers must be aligned to their
  * element size; 16-byte alignment enables the vector paths.
  * Parameters outside the paper's assumptions (sigma > R, R > sigma_w*W) are computed correctly.
- * Errors: CACNN_ERR_NULL, CACNN_ERR_INVALID_ARG (dimension < 1, element counts beyond 2^31-1 per array),
+ * Errors: CACNN_ERR_NULL, CACNN_ERR_INVALID_ARG (dimension < 1, element counts beyond 2^31-1 per array, or so many
+ * tiles along one dimension that tiles * tiles-per-dimension reaches 2^32),
  * CACNN_ERR_UNSUPPORTED (dtype), CACNN_ERR_NO_DEVICE, CACNN_ERR_LAUNCH.  On error nothing is enqueued.
  */
 int cacnn_conv_forward(const cacnn_problem* problem, int dtype, const void* image, const void* filter,

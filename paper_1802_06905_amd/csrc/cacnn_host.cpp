@@ -601,6 +601,16 @@ int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int b
             if (a.tiles_b % d == 0) g_b = d;
         a.b_group = g_b;
     }
+    // tile-list decoding divides by launch constants with one multiply-high each, exact while dividend * divisor < 2^32
+    if ((int64_t)a.n_tiles * std::max<int64_t>(std::max(a.tiles_k, a.tiles_w), std::max(a.tiles_h, 64)) >= (1ll << 32))
+        return CACNN_ERR_INVALID_ARG;
+    a.xcd_q = a.n_tiles / a.n_xcd;
+    a.xcd_rem = a.n_tiles % a.n_xcd;
+    a.d_nxcd = make_fastdiv((uint32_t)a.n_xcd);
+    a.d_tk = make_fastdiv((uint32_t)a.tiles_k);
+    a.d_bg = make_fastdiv((uint32_t)a.b_group);
+    a.d_tw = make_fastdiv((uint32_t)a.tiles_w);
+    a.d_th = make_fastdiv((uint32_t)a.tiles_h);
     a.img_items = g.img_items;
     a.flt_items = g.flt_items;
     a.img_buf = g.img_buf;

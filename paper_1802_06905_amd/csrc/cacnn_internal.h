@@ -72,6 +72,8 @@ struct KernelArgs {
     int32_t n_tiles;          // Out tiles in the whole problem (all kernels)
     int32_t n_xcd;            // XCDs the dispatcher deals workgroups to (8 on MI355X); 1 = no remapping
     int32_t b_group;          // consecutive b-tiles whose Image rows share 128-byte lines (divides tiles_b)
+    int32_t xcd_q, xcd_rem;   // n_tiles = n_xcd * xcd_q + xcd_rem
+    FastDiv d_nxcd, d_tk, d_bg, d_tw, d_th;   // reciprocals of n_xcd, tiles_k, b_group, tiles_w, tiles_h
     int32_t img_items, flt_items;   // 16-byte staging items per slice
     int32_t img_buf, flt_buf; // size of one LDS buffer of each operand (fp32: floats; bf16: 16-byte units)
     int32_t flt_off;          // where the Filter buffers start (same unit)

@@ -40,29 +40,37 @@ struct TileCoord {
 // memory about once and the Filter once per XCD (the a_K / a_B a_W a_H replication of Section 7's parallel
 // bound, with the XCDs as the processors).
 // i -> tile is a bijection on [0, n): XCD x = i % n_xcd owns tiles [x*q + min(x,rem), ...) with n = n_xcd*q + rem.
-__device__ __forceinline__ int xcd_tile(int i, int n, int n_xcd) {
-    if (n_xcd <= 1) return i;
-    const int q = n / n_xcd, rem = n - q * n_xcd;
-    const int x = i % n_xcd, l = i / n_xcd;
-    return x * q + min(x, rem) + l;
+__device__ __forceinline__ int xcd_tile(const KernelArgs& a, int i) {
+    if (a.n_xcd <= 1) return i;
+    const int l = (int)fdiv((uint32_t)i, a.d_nxcd), x = i - l * a.n_xcd;
+    return x * a.xcd_q + min(x, a.xcd_rem) + l;
 }
 
-__device__ __forceinline__ TileCoord decode_tile(const KernelArgs& a, int KT, int TB, int TW, int TH) {
-    int t = xcd_tile(blockIdx.x, a.n_tiles, a.n_xcd);
-    const int tk = t % a.tiles_k;
-    t /= a.tiles_k;
-    const int tbl = t % a.b_group;
-    t /= a.b_group;
-    const int tw = t % a.tiles_w;
-    t /= a.tiles_w;
-    const int th = t % a.tiles_h;
-    const int tb = (t / a.tiles_h) * a.b_group + tbl;
+// tile list index -> tile origin; the divisors are fixed for the launch, so each division is one multiply-high
+// (the host only enables the remapping and these reciprocals when the tile count keeps them exact)
+__device__ __forceinline__ TileCoord tile_coords(const KernelArgs& a, int t, int KT, int TB, int TW, int TH) {
+    int q = (int)fdiv((uint32_t)t, a.d_tk);
+    const int tk = t - q * a.tiles_k;
+    t = q;
+    q = (int)fdiv((uint32_t)t, a.d_bg);
+    const int tbl = t - q * a.b_group;
+    t = q;
+    q = (int)fdiv((uint32_t)t, a.d_tw);
+    const int tw = t - q * a.tiles_w;
+    t = q;
+    q = (int)fdiv((uint32_t)t, a.d_th);
+    const int th = t - q * a.tiles_h;
+    const int tb = q * a.b_group + tbl;
     TileCoord tc;
     tc.k0 = tk * KT;
     tc.b0 = tb * TB;
     tc.w0 = tw * TW;
     tc.h0 = th * TH;
     return tc;
+}
+
+__device__ __forceinline__ TileCoord decode_tile(const KernelArgs& a, int KT, int TB, int TW, int TH) {
+    return tile_coords(a, xcd_tile(a, blockIdx.x), KT, TB, TW, TH);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -518,21 +526,7 @@ struct UnitPos {
 };
 
 __device__ __forceinline__ TileCoord decode_tile_index(const KernelArgs& a, int t, int KT, int TB, int TW, int TH) {
-    t = xcd_tile(t, a.n_tiles, a.n_xcd);
-    const int tk = t % a.tiles_k;
-    t /= a.tiles_k;
-    const int tbl = t % a.b_group;
-    t /= a.b_group;
-    const int tw = t % a.tiles_w;
-    t /= a.tiles_w;
-    const int th = t % a.tiles_h;
-    const int tb = (t / a.tiles_h) * a.b_group + tbl;
-    TileCoord tc;
-    tc.k0 = tk * KT;
-    tc.b0 = tb * TB;
-    tc.w0 = tw * TW;
-    tc.h0 = th * TH;
-    return tc;
+    return tile_coords(a, xcd_tile(a, t), KT, TB, TW, TH);
 }
 
 __device__ __forceinline__ void advance_unit(const KernelArgs& a, UnitPos& p, int KT, int TB, int TW, int TH) {
