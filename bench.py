@@ -56,15 +56,15 @@ def committed_traffic(name):
     """HBM-side bytes of one launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs, scaled
     by the copy-kernel calibration recorded there).  Counters cannot be read from inside this process, so the
     figure is the recorded one for this shape, not a measurement of this run; None if the summary is absent."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_c1-c5.txt")
-    try:
-        with open(path) as f:
-            for line in f:
-                t = line.split()
-                if len(t) >= 5 and t[0] == "traffic" and t[1] == name:
-                    return float(t[4])
-    except OSError:
-        pass
+    for fname in ("hbm_traffic_c1-c5.txt", "pooling_p1.txt"):
+        try:
+            with open(os.path.join(ROOT, "profiles", fname)) as f:
+                for line in f:
+                    t = line.split()
+                    if len(t) >= 5 and t[0] == "traffic" and t[1] == name:
+                        return float(t[4])
+        except OSError:
+            pass
     return None
 
 
@@ -140,12 +140,71 @@ def traffic_probe(cc, torch, ci, np, cfg):
     print(json.dumps({"traffic_probe": cfg.name, "copy_bytes_each_way": n}))
 
 
+def pool_traffic_probe(cc, torch, ci, np, cfg):
+    """As traffic_probe, for the pooling workload (max pooling): calibration copy, eviction, cold launch, warm launch."""
+    n = 512 * 1024 * 1024
+    src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+    img, _ = ci.make_inputs(cfg)
+    d_img = torch.from_numpy(img.reshape(-1)).cuda()
+    d_out = torch.empty(int(np.prod(cfg.out_shape)), dtype=torch.float32, device="cuda:0")
+    torch.cuda.synchronize()
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    evict = torch.empty(1024 * 1024 * 1024, dtype=torch.uint8, device="cuda:0").fill_(3)
+    torch.cuda.synchronize()
+    cc.cacnn_pool_forward(cfg.dims, 0, 1, d_img, d_out)      # cold
+    torch.cuda.synchronize()
+    cc.cacnn_pool_forward(cfg.dims, 0, 1, d_img, d_out)      # warm
+    torch.cuda.synchronize()
+    del evict
+    print(json.dumps({"traffic_probe": cfg.name, "copy_bytes_each_way": n}))
+
+
+def pooling_report(cc, torch, ci, np, steps, warmup, with_cpu):
+    """The pooling path (Section 6 of the paper) on its workload p1, max and average: HBM-bound, so the figure is
+    compulsory bytes (Image once + Out once) over time against the published HBM peak, with the oracle timed beside it."""
+    cfg = ci.POOL_CONFIGS["p1"]
+    img, _ = ci.make_inputs(cfg)
+    d_img = torch.from_numpy(img.reshape(-1)).cuda()
+    d_out = torch.empty(int(np.prod(cfg.out_shape)), dtype=torch.float32, device="cuda:0")
+    nbytes = 4 * (int(np.prod(cfg.image_shape)) + int(np.prod(cfg.out_shape)))
+    rep = {"workload": f"p1: B={cfg.B} C=K={cfg.C} W=H={cfg.W} R=S={cfg.R} sigma={cfg.sigma_w} f32",
+           "compulsory_bytes": nbytes, "bound": "hbm", "peak_GBps": HBM_PEAK_GBS}
+    for mode, code in (("max", 1), ("avg", 0)):
+        for _ in range(warmup):
+            cc.cacnn_pool_forward(cfg.dims, 0, code, d_img, d_out)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            cc.cacnn_pool_forward(cfg.dims, 0, code, d_img, d_out)
+        e1.record()
+        torch.cuda.synchronize()
+        sec = e0.elapsed_time(e1) / steps * 1e-3
+        rep[mode] = {"us": sec * 1e6, "GBps": nbytes / sec / 1e9, "frac_hbm_peak": nbytes / sec / 1e9 / HBM_PEAK_GBS}
+    if with_cpu:
+        from oracle import conv as oconv
+        from oracle import pool as opool
+        p = oconv.Problem(*cfg.dims)
+        t0 = time.perf_counter()
+        ref = opool.pool_fp64(p, img, "avg")
+        dt = time.perf_counter() - t0
+        got = d_out.cpu().numpy().reshape(cfg.out_shape).astype(np.float64)
+        scale = opool.pool_fp64(p, np.abs(img), "avg")
+        rep["cpu_baseline"] = {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": f"p1 average pooling, whole workload, numpy fp64, {dt:.2f} s",
+                               "max_rel_err_gpu_vs_oracle": float(np.max(np.abs(got - ref) / np.maximum(scale, 1e-300)))}
+    return rep
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "p1"],
+                    help="c1..c5: the convolution shapes (c2 is the headline); p1: the pooling workload")
     ap.add_argument("--no-shapes", action="store_true", help="time only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -168,6 +227,23 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
+    if args.workload == "p1":
+        pcfg = ci.POOL_CONFIGS["p1"]
+        if args.traffic_probe:
+            pool_traffic_probe(cc, torch, ci, np, pcfg)
+            return
+        rep = pooling_report(cc, torch, ci, np, args.steps, args.warmup, not args.no_cpu)
+        out = {"metric": "max-pooling GB/s at 1 MI355X (compulsory bytes / time)", "value": rep["max"]["GBps"],
+               "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+               "ms_per_step": rep["max"]["us"] * 1e-3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+               "dtype": "f32", "data": "synthetic", "config": {"workload": rep["workload"]},
+               "roofline": {"bound": "hbm", "achieved": rep["max"]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": rep["max"]["frac_hbm_peak"], "traffic": committed_traffic("p1")},
+               "average_pooling": rep["avg"]}
+        if "cpu_baseline" in rep:
+            out["cpu_baseline"] = rep["cpu_baseline"]
+        print(json.dumps(out))
+        return
     cfg = ci.CONFIGS[args.workload]
     if args.traffic_probe:
         traffic_probe(cc, torch, ci, np, cfg)
@@ -203,6 +279,7 @@ def main():
             s, _, _ = time_config(cc, torch, ci, np, c, args.steps, args.warmup)
             shapes[name] = shape_report(cc, c, s)
         result["shapes"] = shapes
+        result["pooling"] = pooling_report(cc, torch, ci, np, args.steps, args.warmup, not args.no_cpu)
     print(json.dumps(result))
 
 

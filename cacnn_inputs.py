@@ -68,6 +68,13 @@ CONFIGS: Dict[str, Config] = {
 }
 
 
+# Pooling workload (the paper's Section 6 names no shape; this is the 3x3 stride-2 pooling that follows a stem layer
+# of c3's size): Image 113 x 113 x 64 x 32, Out 64 x 56 x 56 x 32.  The Filter half of make_inputs is unused.
+POOL_CONFIGS: Dict[str, Config] = {
+    "p1": Config("p1", 32, 64, 64, 56, 56, 3, 3, 2, 2, "f32", "uniform", SEED_BASE + 6),
+}
+
+
 def custom(name, B, C, K, W, H, R, S, sigma_w=1, sigma_h=1, dtype="f32", dist="uniform", seed=1) -> Config:
     """A shape outside the five benchmark ones (edge cases, ragged sizes)."""
     return Config(name, B, C, K, W, H, R, S, sigma_w, sigma_h, dtype, dist, seed)

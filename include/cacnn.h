@@ -151,6 +151,49 @@ int cacnn_conv_forward(const cacnn_problem* problem, int dtype, const void* imag
 int cacnn_conv_forward_with_plan(const cacnn_problem* problem, int dtype, const cacnn_plan* plan,
                                  const void* image, const void* filter, void* out, void* hip_stream);
 
+/*
+ * Pooling (Section 6 of the paper, "Application to Pooling"): the convolution's loop nest without the Filter,
+ *     Out(k,h,w,b) (+)= Image(r + sigma_w*w, s + sigma_h*h, c, b),
+ * where (+) adds the element divided by R*S (average) or keeps the maximum.  The printed nest runs over k and c
+ * independently although no array carries both; it is executed as per-channel pooling, k = c, so problem->K must equal
+ * problem->C.  Arrays and layouts as for cacnn_conv_forward (Image [IW][IH][C][B] fp32 or bf16, Out [K][H][W][B] fp32).
+ */
+typedef enum {
+    CACNN_POOL_AVG = 0,  /* Out = (1/(R*S)) * sum over the window, summed in fp32 in the order r, then s */
+    CACNN_POOL_MAX = 1   /* Out = maximum over the window (exact; a NaN in the window is ignored unless all are NaN) */
+} cacnn_pool_mode;
+
+/* Section 6: the three terms BKWH, sw*sh*BCWH, BCKWHRS/M, their maximum and which one it is (first of equals). */
+typedef struct {
+    double term[3];
+    double bound;
+    int32_t argmax;
+} cacnn_pool_bound;
+
+/*
+ * Section 6: lower bound on words moved by the pooling nest as printed (all seven loops; for the per-channel reading
+ * the multiply-free work is F/K, and the array-size terms are what binds).  Host only.  Strides above the window
+ * extent are clamped in the Image term as in cacnn_lower_bound.
+ * Errors: CACNN_ERR_NULL; CACNN_ERR_INVALID_ARG for any parameter < 1 or M_words <= 0 (out untouched).
+ */
+int cacnn_pool_lower_bound(const cacnn_problem* problem, double M_words, cacnn_pool_bound* out);
+
+/*
+ * Section 6, executed on the GPU: one thread per (h, w, c, group of adjacent images) reads its R*S window elements
+ * with coalesced vector loads (c and b are contiguous in Image) and writes its Out words once.  HBM-bound.
+ *   problem  in   host pointer; problem->K must equal problem->C
+ *   dtype    in   cacnn_dtype of the Image (Out is fp32)
+ *   mode     in   cacnn_pool_mode
+ *   image    in   DEVICE pointer, IW*IH*C*B elements, read-only
+ *   out      out  DEVICE pointer, K*H*W*B fp32, overwritten; must not alias image
+ *   hip_stream    hipStream_t cast to void*; NULL is the default stream
+ * Enqueues and returns; never synchronises, allocates nothing, keeps no reference.
+ * Errors: CACNN_ERR_NULL, CACNN_ERR_INVALID_ARG (dimension < 1, K != C, element counts beyond 2^31-1 per array,
+ * misaligned pointers), CACNN_ERR_UNSUPPORTED (dtype, mode), CACNN_ERR_NO_DEVICE, CACNN_ERR_LAUNCH.
+ */
+int cacnn_pool_forward(const cacnn_problem* problem, int dtype, int mode, const void* image, void* out,
+                       void* hip_stream);
+
 /* Number of compiled kernel variants, and a static, NUL-terminated description of one
  * ("f32 k64 b8w4h4 ..."); NULL if the index is out of range.  Host only. */
 int cacnn_variant_count(void);

@@ -37,6 +37,14 @@ class Bound(ctypes.Structure):
     _fields_ = [("term", ctypes.c_double * 5), ("bound", ctypes.c_double), ("argmax", ctypes.c_int32)]
 
 
+class PoolBound(ctypes.Structure):
+    _fields_ = [("term", ctypes.c_double * 3), ("bound", ctypes.c_double), ("argmax", ctypes.c_int32)]
+
+
+CACNN_POOL_AVG = 0
+CACNN_POOL_MAX = 1
+
+
 class Machine(ctypes.Structure):
     _fields_ = [("lds_bytes", ctypes.c_int64), ("vgpr_bytes_per_cu", ctypes.c_int64), ("num_cu", ctypes.c_int64)]
 
@@ -79,6 +87,11 @@ _lib.cacnn_conv_forward.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctype
 _lib.cacnn_conv_forward_with_plan.restype = ctypes.c_int
 _lib.cacnn_conv_forward_with_plan.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctypes.POINTER(Plan),
                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.cacnn_pool_lower_bound.restype = ctypes.c_int
+_lib.cacnn_pool_lower_bound.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, ctypes.POINTER(PoolBound)]
+_lib.cacnn_pool_forward.restype = ctypes.c_int
+_lib.cacnn_pool_forward.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                    ctypes.c_void_p]
 _lib.cacnn_variant_count.restype = ctypes.c_int
 _lib.cacnn_variant_name.restype = ctypes.c_char_p
 _lib.cacnn_variant_name.argtypes = [ctypes.c_int]
@@ -151,6 +164,23 @@ def cacnn_conv_forward(problem, dtype: int, image, filt, out, stream=None) -> No
                                  _stream_handle(stream))
     if rc != 0:
         raise CacnnError(rc, "cacnn_conv_forward")
+
+
+def cacnn_pool_lower_bound(problem, M_words: float) -> PoolBound:
+    """The three terms of the pooling bound and their maximum (host only)."""
+    out = PoolBound()
+    rc = _lib.cacnn_pool_lower_bound(ctypes.byref(_as_problem(problem)), float(M_words), ctypes.byref(out))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_pool_lower_bound")
+    return out
+
+
+def cacnn_pool_forward(problem, dtype: int, mode: int, image, out, stream=None) -> None:
+    """Enqueue per-channel average (mode 0) or max (mode 1) pooling of Image[IW,IH,C,B] into Out[K=C,H,W,B] (fp32)."""
+    rc = _lib.cacnn_pool_forward(ctypes.byref(_as_problem(problem)), int(dtype), int(mode), _ptr(image), _ptr(out),
+                                 _stream_handle(stream))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_pool_forward")
 
 
 def cacnn_conv_forward_with_plan(problem, dtype: int, plan: Plan, image, filt, out, stream=None) -> None:

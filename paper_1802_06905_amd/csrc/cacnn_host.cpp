@@ -690,6 +690,83 @@ int cacnn_conv_forward_with_plan(const cacnn_problem* problem, int dtype, const 
     return launch_with(*problem, dtype, plan->variant, CT, bR, bS, image, filter, out, hip_stream);
 }
 
+int cacnn_pool_lower_bound(const cacnn_problem* problem, double M_words, cacnn_pool_bound* out) {
+    if (!problem || !out) return CACNN_ERR_NULL;
+    if (!valid_problem(problem) || !(M_words > 0.0) || !std::isfinite(M_words)) return CACNN_ERR_INVALID_ARG;
+    const cacnn_problem& p = *problem;
+    const double sw = (double)std::min(p.sigma_w, p.R), sh = (double)std::min(p.sigma_h, p.S);
+    const double bkwh = (double)p.B * p.K * p.W * p.H, bcwh = (double)p.B * p.C * p.W * p.H;
+    out->term[0] = bkwh;
+    out->term[1] = sw * sh * bcwh;
+    out->term[2] = bkwh * (double)p.C * p.R * p.S / M_words;
+    out->argmax = 0;
+    for (int i = 1; i < 3; ++i)
+        if (out->term[i] > out->term[out->argmax]) out->argmax = i;
+    out->bound = out->term[out->argmax];
+    return CACNN_OK;
+}
+
+int cacnn_pool_forward(const cacnn_problem* problem, int dtype, int mode, const void* image, void* out,
+                       void* hip_stream) {
+    if (!problem || !image || !out) return CACNN_ERR_NULL;
+    if (dtype != CACNN_F32 && dtype != CACNN_BF16_F32ACC) return CACNN_ERR_UNSUPPORTED;
+    if (mode != CACNN_POOL_AVG && mode != CACNN_POOL_MAX) return CACNN_ERR_UNSUPPORTED;
+    if (!valid_problem(problem) || problem->K != problem->C) return CACNN_ERR_INVALID_ARG;
+    const cacnn_problem& p = *problem;
+    {
+        // element counts of Image and Out within the kernel's 32-bit indexing
+        const int64_t lim = INT32_MAX;
+        if (p.sigma_w > lim || p.sigma_h > lim || p.W > lim || p.H > lim || p.R > lim || p.S > lim) return CACNN_ERR_INVALID_ARG;
+        const int64_t IW = p.sigma_w * (p.W - 1) + p.R, IH = p.sigma_h * (p.H - 1) + p.S;
+        int64_t t;
+        if (IW > lim || IH > lim || !mul_check(IW, IH, lim, &t) || !mul_check(t, p.C, lim, &t) || !mul_check(t, p.B, lim, &t))
+            return CACNN_ERR_INVALID_ARG;
+        if (!mul_check(p.K, p.H, lim, &t) || !mul_check(t, p.W, lim, &t) || !mul_check(t, p.B, lim, &t))
+            return CACNN_ERR_INVALID_ARG;
+    }
+    const size_t esz = dtype == CACNN_F32 ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(image) % esz || reinterpret_cast<uintptr_t>(out) % 4) return CACNN_ERR_INVALID_ARG;
+    const int full = dtype == CACNN_F32 ? 4 : 8;
+    const bool wide = p.B % full == 0 && reinterpret_cast<uintptr_t>(image) % 16 == 0 &&
+                      reinterpret_cast<uintptr_t>(out) % 16 == 0;
+    const int vec = wide ? full : 1;
+    PoolArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.image = image;
+    a.out = (float*)out;
+    a.B = (int32_t)p.B;
+    a.C = (int32_t)p.C;
+    a.W = (int32_t)p.W;
+    a.H = (int32_t)p.H;
+    a.R = (int32_t)p.R;
+    a.S = (int32_t)p.S;
+    a.sw = (int32_t)p.sigma_w;
+    a.sh = (int32_t)p.sigma_h;
+    a.IH = (int32_t)(p.sigma_h * (p.H - 1) + p.S);
+    a.BV = (int32_t)(p.B / vec);
+    a.n_xcd = xcd_count();
+    a.TWC = (int32_t)ceil_div(p.W, a.n_xcd);              // one band of output columns per XCD
+    const int64_t chunks = ceil_div(p.W, a.TWC);
+    int64_t n = 0;
+    if (!mul_check(p.H, chunks * a.TWC, INT32_MAX, &n) || !mul_check(n, p.C, INT32_MAX, &n) ||
+        !mul_check(n, a.BV, INT32_MAX, &n))
+        return CACNN_ERR_INVALID_ARG;
+    a.n_threads = (int32_t)n;
+    a.n_wg = (int32_t)ceil_div(n, 256);
+    // the reciprocal divisions in the kernel are exact while dividend * divisor < 2^32
+    if ((double)n * (double)std::max<int64_t>(std::max<int64_t>(a.BV, p.C), std::max<int64_t>(p.H, 64)) >= 4294967296.0)
+        return CACNN_ERR_INVALID_ARG;
+    a.xcd_q = a.n_wg / a.n_xcd;
+    a.xcd_rem = a.n_wg % a.n_xcd;
+    a.d_BV = make_fastdiv((uint32_t)a.BV);
+    a.d_C = make_fastdiv((uint32_t)a.C);
+    a.d_TWC = make_fastdiv((uint32_t)a.TWC);
+    a.d_H = make_fastdiv((uint32_t)a.H);
+    a.d_nxcd = make_fastdiv((uint32_t)a.n_xcd);
+    if (!have_device()) return CACNN_ERR_NO_DEVICE;
+    return launch_pool(a, dtype, mode, vec, hip_stream) == 0 ? CACNN_OK : CACNN_ERR_LAUNCH;
+}
+
 int cacnn_variant_count(void) { return num_variants(); }
 
 const char* cacnn_variant_name(int i) {

@@ -87,6 +87,20 @@ struct Variant {
     LaunchFn launch;
 };
 
+// Pooling (cacnn_pool.hip): everything the kernel needs, by value.
+struct PoolArgs {
+    const void* image;
+    float* out;
+    int32_t B, C, W, H, R, S, sw, sh, IH;
+    int32_t BV;               // groups of VEC adjacent images per (x, y, c): B / VEC
+    int32_t TWC;              // output columns per chunk (the last chunk may overhang W)
+    int32_t n_threads;        // chunks * H * TWC * C * BV
+    int32_t n_wg, n_xcd, xcd_q, xcd_rem;   // workgroups, and the XCD remapping of their order
+    FastDiv d_BV, d_C, d_TWC, d_H, d_nxcd;
+};
+// dtype: cacnn_dtype; mode: cacnn_pool_mode; vec: images per thread (1, or 4 for fp32 / 8 for bf16). 0 = launched.
+int launch_pool(const PoolArgs& a, int dtype, int mode, int vec, void* stream);
+
 // Defined in cacnn_kernels.hip.
 int num_variants();
 const Variant& variant(int i);

@@ -32,7 +32,7 @@ def test_struct_sizes_match_the_header():
     src = r'''
     #include <stdio.h>
     #include "cacnn.h"
-    int main(void){ printf("%zu %zu %zu %zu\n", sizeof(cacnn_problem), sizeof(cacnn_bound), sizeof(cacnn_machine), sizeof(cacnn_plan)); return 0; }
+    int main(void){ printf("%zu %zu %zu %zu %zu\n", sizeof(cacnn_problem), sizeof(cacnn_bound), sizeof(cacnn_machine), sizeof(cacnn_plan), sizeof(cacnn_pool_bound)); return 0; }
     '''
     with tempfile.TemporaryDirectory() as d:
         open(os.path.join(d, "t.c"), "w").write(src)
@@ -41,7 +41,7 @@ def test_struct_sizes_match_the_header():
         sizes = [int(x) for x in subprocess.run([os.path.join(d, "t")], capture_output=True, text=True,
                                                 check=True).stdout.split()]
     assert sizes == [ctypes.sizeof(cc.Problem), ctypes.sizeof(cc.Bound), ctypes.sizeof(cc.Machine),
-                     ctypes.sizeof(cc.Plan)]
+                     ctypes.sizeof(cc.Plan), ctypes.sizeof(cc.PoolBound)]
 
 
 def test_fastdiv_is_exact_over_its_domain():
@@ -195,3 +195,36 @@ def test_conv_forward_without_a_gpu_reports_no_device():
                                        ctypes.c_void_p, ctypes.c_void_p]
     p = cc.Problem(1, 3, 8, 16, 16, 3, 3, 1, 1)
     assert lib.cacnn_conv_forward(ctypes.byref(p), 0, 4096, 8192, 16384, None) == 5   # never dereferenced
+
+
+def test_pool_bound_matches_the_oracle_and_rejects_bad_arguments():
+    from oracle import lower_bound as olb
+    for dims, M in (((4, 8, 8, 10, 10, 3, 3, 2, 2), 64.0), ((32, 64, 64, 56, 56, 3, 3, 2, 2), 40960.0),
+                    ((2, 3, 3, 5, 4, 2, 5, 4, 1), 7.0)):
+        got = cc.cacnn_pool_lower_bound(dims, M)
+        ref = olb.pooling_lower_bound(*dims, M)
+        assert list(got.term) == pytest.approx(ref.terms, rel=1e-15)
+        assert got.bound == pytest.approx(ref.bound, rel=1e-15) and got.argmax == ref.argmax
+    with pytest.raises(cc.CacnnError) as e:
+        cc.cacnn_pool_lower_bound((4, 8, 8, 10, 10, 3, 3, 2, 0), 64.0)
+    assert e.value.status == 2
+    with pytest.raises(cc.CacnnError) as e:
+        cc.cacnn_pool_lower_bound((4, 8, 8, 10, 10, 3, 3, 2, 2), 0.0)
+    assert e.value.status == 2
+
+
+def test_pool_forward_rejects_bad_arguments_before_touching_the_gpu():
+    ok = (2, 4, 4, 3, 3, 2, 2, 1, 1)
+    for dims, dtype, mode, img, out, status in (
+            (ok, 0, 0, 0, 16, 1),                      # null image
+            (ok, 0, 0, 16, 0, 1),                      # null out
+            (ok, 7, 0, 16, 16, 3),                     # unknown dtype
+            (ok, 0, 5, 16, 16, 3),                     # unknown mode
+            ((2, 4, 5, 3, 3, 2, 2, 1, 1), 0, 0, 16, 16, 2),   # K != C
+            ((2, 4, 4, 0, 3, 2, 2, 1, 1), 0, 0, 16, 16, 2),   # W < 1
+            ((1 << 20, 4, 4, 1 << 10, 3, 2, 2, 1, 1), 0, 0, 16, 16, 2),   # too many elements
+            (ok, 0, 0, 18, 16, 2),                     # image pointer not aligned to its element size
+    ):
+        with pytest.raises(cc.CacnnError) as e:
+            cc.cacnn_pool_forward(dims, dtype, mode, img, out, stream=0)
+        assert e.value.status == status, (dims, dtype, mode, img, out)
