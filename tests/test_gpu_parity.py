@@ -63,6 +63,10 @@ RAGGED = [
     ("fx_w7", 128, 64, 128, 7, 3, 3, 3, 1, 1),
     ("fx_w2h2", 64, 96, 192, 4, 6, 3, 3, 1, 1),
     ("fx_w4h4", 64, 32, 128, 8, 12, 3, 3, 1, 1),
+    # more tiles than workgroups (a workgroup walks several tiles), and a filter taller than the fixed b_s
+    ("fx_many_tiles", 64, 32, 128, 24, 24, 3, 3, 1, 1),
+    ("fx_w7_many_tiles", 64, 32, 64, 7, 300, 3, 3, 1, 1),
+    ("fx_s6", 64, 32, 64, 4, 4, 3, 6, 1, 1),
     # the stem-layer kernel: 7x7 taps, strides 2, three channels; more tiles than workgroups and three k-tiles, so a
     # workgroup walks several tiles and restages its Filter tile
     ("fx_stem", 32, 3, 192, 28, 16, 7, 7, 2, 2),
