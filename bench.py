@@ -80,15 +80,24 @@ def shape_report(cc, cfg, sec):
     n_flt = cfg.K * cfg.R * cfg.S * cfg.C
     n_out = cfg.K * cfg.H * cfg.W * cfg.B
     compulsory = esz * (n_img + n_flt) + 4 * n_out
-    lb = cc.cacnn_lower_bound(cfg.dims, LDS_BYTES / esz)
-    lb_bytes = max(4 * lb.term[0], esz * max(lb.term[1:]))
+    def bound_bytes(fast_bytes):
+        b = cc.cacnn_lower_bound(cfg.dims, fast_bytes / esz)
+        return max(4 * b.term[0], esz * max(b.term[1:]))
+    lb_bytes = bound_bytes(LDS_BYTES)
+    hbm = committed_traffic(cfg.name)
     return {
         "us": sec * 1e6, "tflops": tflops, "frac_mfma_peak": tflops / MFMA_PEAK_TFLOPS[cfg.dtype],
         "frac_hbm_roofline": compulsory / sec / 1e9 / HBM_PEAK_GBS,
         "compulsory_bytes": compulsory, "paper_bound_bytes_at_M_lds": lb_bytes,
+        # the same bound with a CU's registers counted as fast memory too, and with one XCD's 4 MiB L2 as the fast
+        # memory (the level whose misses the profiled HBM-side bytes are)
+        "paper_bound_bytes_at_M_lds_plus_vgpr": bound_bytes(LDS_BYTES + 512 * 1024),
+        "paper_bound_bytes_at_M_l2": bound_bytes(4 * 1024 * 1024),
+        "hbm_bytes_over_bound_at_M_lds": (hbm / lb_bytes) if hbm else None,
+        "hbm_bytes_over_bound_at_M_l2": (hbm / bound_bytes(4 * 1024 * 1024)) if hbm else None,
         "planned_staged_bytes": esz * (plan.predicted_words - n_out) + 4 * n_out,
         "variant": cc.cacnn_variant_name(plan.variant), "grid": plan.grid[0], "lds_bytes": plan.lds_bytes_used,
-        "b_c": plan.b_c, "hbm_bytes_profiled": committed_traffic(cfg.name),
+        "b_c": plan.b_c, "hbm_bytes_profiled": hbm,
     }
 
 
