@@ -397,8 +397,10 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
                 }
                 const double per_tile = t_mfma / feed + beta * t_stage + t_slice * n_ctiles;
                 const double per_cu = (double)ceil_div(n_wg, mach.num_cu);
-                const double cost =
-                    (per_cu * per_tile + t_out / std::max(1.0, std::min(per_cu, 4.0))) * (double)v.tune + 6000.0;
+                double cost = (per_cu * per_tile + t_out / std::max(1.0, std::min(per_cu, 4.0))) * (double)v.tune + 6000.0;
+                // the fixed-geometry kernels run one schedule: priced by what a unit was measured to take
+                if (v.fx_unit_us > 0.f)
+                    cost = (per_cu * n_ctiles * (double)v.fx_unit_us + (double)v.fx_fixed_us) * 2400.0;
                 if (best->variant < 0 || cost < best->cost) {
                     best->variant = vi;
                     best->g = g;
@@ -490,10 +492,18 @@ int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, c
         if (vrc != CACNN_OK) return vrc;
     }
     Choice best;
-    for (int vi = 0; vi < num_variants(); ++vi) {
-        if (variant(vi).info.dtype != dtype) continue;
-        if (variant(vi).info.pipelined && !allow_pipelined) continue;
-        evaluate(vi, *p, mach, &best);
+    // Where a fixed-geometry kernel fits the problem and gives at least an eighth of the machine a tile, it has beaten
+    // every generic kernel measured (by 2-3x on mid-size layers), and its cost above is a measurement while the
+    // generic kernels' is a model: choose among those first.
+    for (int vi = 0; vi < num_variants() && allow_pipelined; ++vi)
+        if (variant(vi).info.dtype == dtype && variant(vi).info.fx_ct > 0) evaluate(vi, *p, mach, &best);
+    if (best.variant < 0 || best.n_wg * 8 < mach.num_cu) {
+        for (int vi = 0; vi < num_variants(); ++vi) {
+            if (variant(vi).info.dtype != dtype) continue;
+            if (variant(vi).info.pipelined && !allow_pipelined) continue;
+            if (variant(vi).info.fx_ct > 0) continue;      // already in
+            evaluate(vi, *p, mach, &best);
+        }
     }
     if (best.variant < 0) return CACNN_ERR_INVALID_ARG;  // nothing fits the given LDS size
     return fill_plan(*p, dtype, mach, best, out);

@@ -44,6 +44,9 @@ struct VariantInfo {
     int fx_ct = 0, fx_br = 0, fx_bs = 0, fx_ys = 0;
     int fx_sw = 1, fx_sh = 1;   // the strides it assumes
     int fx_lds = 0;             // > 0: the kernel has its own LDS layout of this many bytes (and needs C == fx_ct)
+    // measured on MI355X with every CU busy: microseconds per unit (tile and contraction slice) of one workgroup, and the
+    // fixed part of a launch (first loads, last Out tile, dispatch); the planner prices these kernels with them
+    float fx_unit_us = 0.f, fx_fixed_us = 0.f;
     int KT() const { return WM * MBLK * 32; }
     int NT() const { return TB * TW * TH; }
     int threads() const { return WM * WN * (pipelined == 2 ? 128 : 64); }

@@ -2562,9 +2562,10 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
     }
 
 // fixed-geometry variants: GEO is the geometry class whose constants the launch must match
-#define CACNN_FX_VARIANT(DT, NAME, TUNE, WM, WN, MBLK, NBLK, TB, TW, TH, BR, FXCT, FXBS, GEO, ...)             \
+#define CACNN_FX_VARIANT(DT, NAME, UNIT_US, FIXED_US, WM, WN, MBLK, NBLK, TB, TW, TH, BR, FXCT, FXBS, GEO, ...) \
     {                                                                                                          \
-        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH, 2, GEO::MAXI, GEO::MAXF, 1, BR, TUNE, FXCT, 3, FXBS, GEO::YS},    \
+        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH, 2, GEO::MAXI, GEO::MAXF, 1, BR, 1.0f, FXCT, 3, FXBS, GEO::YS, 1, 1, 0, \
+         UNIT_US, FIXED_US},                                                                                  \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!GEO::matches_host(a)) return 1;                                                           \
@@ -2628,15 +2629,15 @@ static const Variant g_variants[] = {
     CACNN_WS_VARIANT(0, "f32 ws4 k64 b16w4h2 w2x2 m1n2", 1.0f, 2, 2, 1, 2, 16, 4, 2, 3, 10, -4,
                      conv_f32v4_ws_kernel<2, 2, 1, 2, 16, 4, 2, 3, 10>),
     // fixed-geometry kernels (3x3 taps, unit strides, shapes the tiles divide exactly)
-    CACNN_FX_VARIANT(0, "f32 fx k64 b8w4h4 w2x2 m1n2 c16r3s3", 0.85f, 2, 2, 1, 2, 8, 4, 4, -4, 16, 3, FxF32B8W4H4,
+    CACNN_FX_VARIANT(0, "f32 fx k64 b8w4h4 w2x2 m1n2 c16r3s3", 4.8f, 5.5f, 2, 2, 1, 2, 8, 4, 4, -4, 16, 3, FxF32B8W4H4,
                      conv_f32v4_fx_kernel<2, 2, 1, 2, 8, 4, 4, 16, 3>),
-    CACNN_FX_VARIANT(1, "bf16 fx k64 b64w7h1 w2x2 m1n7 c32r3s1", 0.7f, 2, 2, 1, 7, 64, 7, 1, 3, 32, 1, FxBf16B64W7H1,
+    CACNN_FX_VARIANT(1, "bf16 fx k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.16f, 8.0f, 2, 2, 1, 7, 64, 7, 1, 3, 32, 1, FxBf16B64W7H1,
                      conv_bf16_fx_kernel<2, 1, 64, 7, 1, 32, 1>),
-    CACNN_FX_VARIANT(1, "bf16 fx k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.7f, 2, 2, 1, 4, 64, 2, 2, 3, 32, 1, FxBf16B64W2H2,
+    CACNN_FX_VARIANT(1, "bf16 fx k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.86f, 4.0f, 2, 2, 1, 4, 64, 2, 2, 3, 32, 1, FxBf16B64W2H2,
                      conv_bf16_fx_kernel<2, 1, 64, 2, 2, 32, 1>),
     // fixed geometry for the stem-layer shape: 7x7 taps, strides 2, three channels
-    {{"f32 fxs k64 b32w2h2 w2x2 m1n2 c3r7s7 s2", 0, 2, 2, 1, FxStem7::NBLK, 32, 2, 2, 2, 1, 1, 1, 0, 0.6f, 3, 7, 7, FxStem7::YS, 2,
-      2, FxStem7::LDS_BYTES},
+    {{"f32 fxs k64 b32w2h2 w2x2 m1n2 c3r7s7 s2", 0, 2, 2, 1, FxStem7::NBLK, 32, 2, 2, 2, 1, 1, 1, 0, 1.0f, 3, 7, 7, FxStem7::YS, 2,
+      2, FxStem7::LDS_BYTES, 6.3f, 5.5f},
      [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {
          static bool attr_done = false;
          if (!FxStem7::matches_host(a) || lds != (size_t)FxStem7::LDS_BYTES) return 1;
