@@ -210,8 +210,9 @@ def pooling_report(cc, torch, ci, np, steps, warmup, with_cpu):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=2000,
+                    help="timed launches; the clocks take on the order of a thousand back-to-back launches to settle")
+    ap.add_argument("--warmup", type=int, default=1000)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "p1"],
                     help="c1..c5: the convolution shapes (c2 is the headline); p1: the pooling workload")
     ap.add_argument("--no-shapes", action="store_true", help="time only the headline workload")
