@@ -188,12 +188,18 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
     g.flt_resident = (g.n_slices == 1 && ceil_div(p.K, v.KT()) == 1 && v.fx_ct == 0) ? 1 : 0;
     const int nbuf_f = g.flt_resident ? 1 : 2;
     if (v.fx_lds > 0) {
-        // a fixed-geometry kernel with its own LDS layout: one unit per tile, nothing to derive here
+        // a fixed-geometry kernel with its own LDS layout: nothing to derive here
         g.lds_bytes = v.fx_lds;
         g.img_items = g.flt_items = 1;
         g.legal = CT == v.fx_ct && bR == v.fx_br && bS == v.fx_bs && g.YS == v.fx_ys && p.sigma_w == v.fx_sw &&
-                  p.sigma_h == v.fx_sh && p.R == bR && p.S == bS && p.C == CT && p.B % v.TB == 0 && p.W % v.TW == 0 &&
-                  p.H % v.TH == 0 && p.K % v.KT() == 0 && vec_img;
+                  p.sigma_h == v.fx_sh && p.R == bR && p.S % bS == 0 && p.C % CT == 0 && p.B % v.TB == 0 &&
+                  p.W % v.TW == 0 && p.H % v.TH == 0 && p.K % v.KT() == 0 && vec_img;
+        if (v.fx_whole && (p.S != bS || p.C != CT)) g.legal = false;
+        // staged words are addressed by 32-bit byte offsets from the unit's origin
+        const double esz = v.dtype == CACNN_F32 ? 4.0 : 2.0;
+        const double IHd = (double)(p.sigma_h * (p.H - 1) + p.S);
+        if ((double)(g.XS + 1) * IHd * (double)p.C * (double)p.B * esz >= 2147483648.0) g.legal = false;
+        if ((double)(v.KT() + 1) * (double)p.R * (double)p.S * (double)p.C * esz >= 2147483648.0) g.legal = false;
         return g;
     }
     if (v.dtype == CACNN_F32 && v.f32v4()) {

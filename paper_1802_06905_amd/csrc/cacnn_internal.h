@@ -43,10 +43,11 @@ struct VariantInfo {
     // and the staged Image rows sigma_h*(TH-1)+b_s it assumes
     int fx_ct = 0, fx_br = 0, fx_bs = 0, fx_ys = 0;
     int fx_sw = 1, fx_sh = 1;   // the strides it assumes
-    int fx_lds = 0;             // > 0: the kernel has its own LDS layout of this many bytes (and needs C == fx_ct)
+    int fx_lds = 0;             // > 0: the kernel has its own LDS layout of this many bytes
     // measured on MI355X with every CU busy: microseconds per unit (tile and contraction slice) of one workgroup, and the
     // fixed part of a launch (first loads, last Out tile, dispatch); the planner prices these kernels with them
     float fx_unit_us = 0.f, fx_fixed_us = 0.f;
+    int fx_whole = 0;           // 1: with its own LDS layout, the kernel takes a tile's whole contraction as one unit (C == fx_ct, S == fx_bs)
     int KT() const { return WM * MBLK * 32; }
     int NT() const { return TB * TW * TH; }
     int threads() const { return WM * WN * (pipelined == 2 ? 128 : 64); }

@@ -19,6 +19,7 @@
 // shapes and for the 7x7 stride-2 three-channel stem shape; the variant table at the end lists what is compiled.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "cacnn_internal.h"
 
@@ -897,6 +898,17 @@ __device__ __forceinline__ void interleave_hint() {
     for (int i = 0; i < NMFMA; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA
         __builtin_amdgcn_sched_group_barrier(0x100, PER, 0);   // up to PER LDS reads
+    }
+}
+
+// The same with the reads packed PER to an MFMA at the front of the region, for regions that end in a wait for all of
+// their reads: the last read then has the remaining MFMAs to land in.
+template <int NMFMA, int NDS, int PER>
+__device__ __forceinline__ void interleave_front_hint() {
+#pragma unroll
+    for (int i = 0; i < NMFMA; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (i * PER < NDS) __builtin_amdgcn_sched_group_barrier(0x100, PER, 0);
     }
 }
 
@@ -2254,6 +2266,239 @@ __global__ void __launch_bounds__(WM*(TB / 32) * 64 + 256) conv_bf16_fx_kernel(c
     }
 }
 
+// ---- fixed geometry, bf16, Image loaded straight into LDS ---------------------------------------------------------------
+// Measured on the kernel above: next to a bf16 MFMA stream a staging wave gets about one instruction per 11 cycles,
+// and its ~130 instructions per unit (loads, the 8x8 transposes, LDS stores) are what a unit ends up waiting for.
+// Here the Image words never pass through registers: a buffer load with the LDS as its destination puts 64 lanes x
+// 16 bytes, in lane order, at a wave-uniform LDS address, so one instruction moves 8 channel rows of the tile's 64
+// images (1 KiB) and a staging wave issues 8 or 9 of them per unit.  The Image keeps its global order in LDS,
+// [x][y][c][b] with b fastest (128-byte rows), and the transpose is left to the LDS read: the transposing 64-bit read
+// hands lane i of a 16-lane group the i-th 16-bit word of each of the four 32-byte runs that lanes 4e..4e+3 (e = 0..3)
+// point at, so with the four runs in four consecutive channel rows a lane ends up with four channels of one image,
+// and two such reads make one MFMA operand.  Which 16-byte piece of a row a lane loads is free, so rows with bit 1 of
+// c set are stored with their upper and lower halves exchanged: the 16 pieces that one half-wave reads at once
+// (4 rows x 64 bytes) then lie in 16 different groups of four banks.
+// Data reaches LDS when it arrives, so there are three buffers: a unit's loads are issued two units ahead, and a
+// staging wave waits on its own load counter before it announces the unit at the barrier.  The Filter tile (a
+// quarter of the bytes) still goes through registers; its LDS stores are written as assembly so that the compiler's
+// wait-count bookkeeping, which makes every LDS access it knows of wait for all outstanding loads into LDS, does not
+// see them (their operands are still tracked: the store waits for its own Filter load).
+template <int TW, int TH>
+struct Bf16DirectFixed {
+    static constexpr int TB = 64, KT = 64, WM = 2, WN = 2, CT = 32, BS = 1, BR = 3, NBLK = TW * TH;
+    static constexpr int C8 = CT / 8, STEPS = BS * (CT / 16);
+    static constexpr int XS = TW + BR - 1, YS = TH - 1 + BS;
+    static constexpr int ROW = TB * 2;                              // bytes of one (x, y, c) row
+    static constexpr int IMG_BYTES = XS * YS * CT * ROW;
+    static constexpr int F8 = (BR * BS * C8) | 1;                   // Filter row in 16-byte units, odd: conflict-free
+    static constexpr int FLT_BYTES = KT * F8 * 16;
+    static constexpr int BUF_BYTES = IMG_BYTES + FLT_BYTES, NBUF = 3, LDS_BYTES = NBUF * BUF_BYTES;
+    static constexpr int PT = 256, PW = PT / 64;                    // staging threads, staging waves
+    static constexpr int CPW = XS * YS;                             // 1 KiB Image chunks per unit and staging wave
+    static constexpr int FLT_ITEMS = KT * BR * BS * C8, MAXF = FLT_ITEMS / PT, MAXI = 1;
+    static constexpr int LOADS = CPW + MAXF;                        // loads one staging wave issues per unit
+    static_assert(C8 == PW, "direct bf16 geometry: staging wave p loads channels 8p..8p+7 of every (x, y)");
+    static_assert(FLT_ITEMS % PT == 0, "direct bf16 geometry: whole Filter items per thread");
+    static_assert(BUF_BYTES < 65536 && LDS_BYTES <= 160 * 1024, "direct bf16 geometry: LDS offsets and size");
+    static_assert(STEPS == 2 && 2 * LOADS < 64, "direct bf16 geometry: two steps per unit, load counter range");
+    static bool matches_host(const KernelArgs& a) {
+        return a.sw == 1 && a.sh == 1 && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
+               a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % TB == 0 && a.W % TW == 0 && a.H % TH == 0 &&
+               a.K % KT == 0 && a.vec_img && a.vec_flt;
+    }
+};
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+#define CACNN_LDS(T) __attribute__((address_space(3))) T
+
+// s_waitcnt immediate that waits only for the vector-memory counter to drop to n (6 bits: [3:0] and [15:14])
+constexpr int vmcnt_only(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+__device__ __forceinline__ void lds_done_then_barrier_known() {
+    lds_done_then_barrier();
+    // true already: restated in a form the compiler's wait-count bookkeeping reads, so that it does not make the
+    // first MFMAs behind the barrier wait for the LDS reads issued after it
+    __builtin_amdgcn_s_waitcnt(vmcnt_only(63) & ~(15 << 8));
+}
+
+// 64 lanes x 16 bytes from global memory (lane offset voff, wave-uniform offset soff) to dst, dst + 16, ... in lane order.
+// dst is wave-uniform.  Not inside the kernel template: the host pass of the compiler rejects the 16-byte form there.
+__device__ __forceinline__ void load_16_bytes_per_lane_to_lds(__amdgpu_buffer_rsrc_t r, CACNN_LDS(char)* dst, uint32_t voff,
+                                                              uint32_t soff) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (CACNN_LDS(void)*)dst, 16, voff, soff, 0, 0);
+}
+
+template <int TW, int TH>
+__global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs a) {
+    using GEO = Bf16DirectFixed<TW, TH>;
+    constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, BR = GEO::BR, WM = GEO::WM, NBLK = GEO::NBLK;
+    constexpr int XS = GEO::XS, YS = GEO::YS, C8 = GEO::C8, F8 = GEO::F8, ROW = GEO::ROW, BUF = GEO::BUF_BYTES;
+    constexpr int CTHREADS = GEO::WM * GEO::WN * 64;
+    extern __shared__ __align__(16) uint4 smem_u[];
+    CACNN_LDS(char)* const lds = (CACNN_LDS(char)*)smem_u;
+    const int tid = threadIdx.x;
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
+    const int lane = tid & 63;
+    // units this workgroup works through: its tiles blockIdx.x, blockIdx.x + gridDim.x, ... times the slices of a tile
+    const int upt = (a.C / CT) * (a.S / BS);
+    int total = 0;
+    for (int t = blockIdx.x; t < a.n_tiles; t += gridDim.x) total += upt;
+
+    if (wave_id >= GEO::WM * GEO::WN) {
+        const int pw = wave_id - GEO::WM * GEO::WN, stid = tid - CTHREADS;
+        constexpr int MAXF = GEO::MAXF, CPW = GEO::CPW, PT = GEO::PT;
+        // Image: lane L of a chunk load fetches channel row L / 8 of the chunk, 16-byte piece (L % 8) ^ 4 * (bit 1 of the row)
+        const uint32_t row_bytes = (uint32_t)a.B * 2u;
+        const uint32_t ivoff = (uint32_t)(lane >> 3) * row_bytes + (uint32_t)(((lane & 7) ^ (((lane >> 4) & 1) << 2)) * 16);
+        uint32_t isoff[CPW];
+#pragma unroll
+        for (int i = 0; i < CPW; ++i)
+            isoff[i] = (uint32_t)(((i / YS) * a.IH + (i % YS)) * a.C + pw * 8) * row_bytes;
+        uint32_t fg[MAXF], fl[MAXF];
+#pragma unroll
+        for (int i = 0; i < MAXF; ++i) {
+            const int idx = stid + i * PT;
+            const int c8 = idx % C8, t = idx / C8;
+            const int rs = t % (BR * BS), kl = t / (BR * BS);
+            const int r = rs / BS, sl = rs % BS;
+            fl[i] = (uint32_t)(uintptr_t)(lds + GEO::IMG_BYTES + (kl * F8 + rs * C8 + c8) * 16);
+            fg[i] = ((((uint32_t)kl * a.R + r) * a.S + sl) * a.C + c8 * 8) * 2u;
+        }
+        FxWalk<2, KT, TB, TW, TH, CT, BS> lu;     // next unit to fetch
+        lu.init(a);
+        u32x4 freg[2][MAXF];
+        int boff_issue = 0, boff_store = 0;       // the buffers the next fetch / the next announced unit use
+        auto issue = [&](int set) {
+            const __amdgpu_buffer_rsrc_t ri = lu.img(a), rf = lu.flt(a);
+#pragma unroll
+            for (int i = 0; i < CPW; ++i)
+                load_16_bytes_per_lane_to_lds(ri, lds + boff_issue + (i * C8 + pw) * 1024, ivoff, isoff[i]);
+#pragma unroll
+            for (int i = 0; i < MAXF; ++i) {
+                const uint4 v = buf_load_u4(rf, fg[i], 0);
+                freg[set][i] = u32x4{v.x, v.y, v.z, v.w};
+            }
+            lu.next(a);
+            boff_issue = boff_issue + BUF == GEO::NBUF * BUF ? 0 : boff_issue + BUF;
+        };
+        // announce the unit whose Filter words are in register set `set`: its loads are in once at most `later`
+        // younger loads are outstanding (loads complete in order)
+        auto announce = [&](int set, auto later) {
+            __builtin_amdgcn_s_waitcnt(vmcnt_only(decltype(later)::value));
+#pragma unroll
+            for (int i = 0; i < MAXF; ++i)
+                asm volatile("ds_write_b128 %0, %1" ::"v"(fl[i] + (uint32_t)boff_store), "v"(freg[set][i]) : "memory");
+            lds_done_then_barrier();
+            boff_store = boff_store + BUF == GEO::NBUF * BUF ? 0 : boff_store + BUF;
+        };
+        using NextUnit = std::integral_constant<int, GEO::LOADS>;
+        using Nothing = std::integral_constant<int, 0>;
+        // Every path below is straight-line code or a loop whose state at the back edge equals its state on entry,
+        // so the compiler's own count of outstanding loads (it waits for a Filter register before the store that
+        // reads it) is exact; a load issued under a condition would make it wait for everything.
+        if (total == 1) {
+            issue(0);
+            announce(0, Nothing{});
+        } else if (total >= 2) {
+            issue(0);
+            issue(1);
+            int u = 0;
+            for (; u + 4 <= total; u += 2) {
+                announce(0, NextUnit{});
+                issue(0);               // the multiplying waves have left the buffer two units back: refill it
+                announce(1, NextUnit{});
+                issue(1);
+            }
+            if (total - u == 3) {
+                announce(0, NextUnit{});
+                issue(0);
+                announce(1, NextUnit{});
+                announce(0, Nothing{});
+            } else {
+                announce(0, NextUnit{});
+                announce(1, Nothing{});
+            }
+        }
+    } else {
+        const int wm = wave_id % WM, wn = wave_id / WM;
+        const int j = lane & 31, g = lane >> 5, i16 = lane & 15, jhalf = (lane >> 4) & 1;
+        f32x16 acc[1][NBLK];
+        zero_acc(acc);
+        // per-lane LDS offsets inside a buffer: Filter row of output channel wm*32 + j, contraction half g;
+        // Image: row 8g + i16/4 of a 16-channel step, the 8 bytes that hold images 4*(i16 % 4).. of this lane group
+        const uint32_t al = (uint32_t)(GEO::IMG_BYTES + ((wm * 32 + j) * F8 + g) * 16);
+        const int q = wn * 4 + 2 * jhalf + ((i16 & 3) >> 1);
+        const uint32_t xl = (uint32_t)((8 * g + (i16 >> 2)) * ROW + ((q ^ (((i16 >> 3) & 1) << 2)) * 16) + (i16 & 1) * 8);
+        bf16x8 A[2][BR], X[2][TH][XS];
+        auto load_step = [&](uint32_t ab, uint32_t xb, int t, int set) {
+            const int sl = t / (CT / 16), cs = t % (CT / 16);
+#pragma unroll
+            for (int r = 0; r < BR; ++r)
+                A[set][r] = *(const CACNN_LDS(bf16x8)*)(lds + ab + ((r * BS + sl) * C8 + 2 * cs) * 16);
+#pragma unroll
+            for (int h = 0; h < TH; ++h)
+#pragma unroll
+                for (int x = 0; x < XS; ++x) {
+                    CACNN_LDS(char)* const p = lds + xb + ((x * YS + h + sl) * CT + 16 * cs) * ROW;
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CACNN_LDS(s16x4)*)p);
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CACNN_LDS(s16x4)*)(p + 4 * ROW));
+                    X[set][h][x] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                }
+        };
+        auto mfma_step = [&](int set) {
+#pragma unroll
+            for (int r = 0; r < BR; ++r)
+#pragma unroll
+                for (int h = 0; h < TH; ++h)
+#pragma unroll
+                    for (int w = 0; w < TW; ++w)
+                        acc[0][h * TW + w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[set][r], X[set][h][w + r],
+                                                                                     acc[0][h * TW + w], 0, 0, 0);
+        };
+        const int64_t out_kstride = (int64_t)a.H * a.W * a.B;      // floats between output channels
+        const uint32_t out_lane = (uint32_t)(g * 4) * (uint32_t)out_kstride + (uint32_t)(32 * wn + j);
+        int left = total, in_tile = upt, t = blockIdx.x;
+        uint32_t boff = 0;
+        // one unit; MORE: another one follows (its buffer is the next of the three)
+        auto unit = [&](auto more) {
+            constexpr bool MORE = decltype(more)::value;
+            load_step(al + boff, xl + boff, 1, 1);
+            mfma_step(0);
+            interleave_front_hint<BR * NBLK, 2 * TH * XS + BR, 2>();
+            if constexpr (MORE) {
+                // hand the buffer back once the last fragments have landed, read the next unit's first fragments
+                // under this step's MFMAs
+                boff = boff + BUF == GEO::NBUF * BUF ? 0u : boff + BUF;
+                lds_done_then_barrier_known();
+                load_step(al + boff, xl + boff, 0, 0);
+            }
+            mfma_step(1);
+            if constexpr (MORE) interleave_front_hint<BR * NBLK, 2 * TH * XS + BR, 2>();
+            // keep the reads above where they are: left alone, the compiler sinks them to the top of the next
+            // unit, in front of the MFMAs that need them
+            asm volatile("" ::: "memory");
+            --left;
+            if (--in_tile == 0) {
+                const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
+#pragma unroll
+                for (int n = 0; n < NBLK; ++n) {
+                    float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + tc.h0 + n / TW) * a.W + tc.w0 + n % TW) * a.B + tc.b0);
+                    store_block_exact<true>(blk, out_kstride, out_lane, acc[0][n]);
+                }
+                in_tile = upt;
+                t += gridDim.x;
+            }
+        };
+        if (left > 0) {
+            lds_done_then_barrier_known();      // unit 0 is staged
+            load_step(al, xl, 0, 0);
+            while (left > 1) unit(std::true_type{});
+            unit(std::false_type{});
+        }
+    }
+}
+
 // ---- fixed geometry, large strided filter, few channels (the stem-layer shape) --------------------------------------
 // With C = 3 the 16-byte fragments of the kernels above would be mostly padding.  Here the four consecutive
 // contraction indices of a fragment are four filter-row offsets s (padded from S = 7 to 8) of one (r, c):
@@ -2577,6 +2822,18 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
+// bf16 with the Image loaded straight into LDS: 64 images, 64 output channels, 32-channel slices of one filter row
+#define CACNN_DIRECT_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                                   \
+    {                                                                                                          \
+        {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, TH>::NBLK, 64, TW, TH, 2, 1, Bf16DirectFixed<TW, TH>::MAXF, 1, 3, 1.0f, 32, 3,  \
+         1, Bf16DirectFixed<TW, TH>::YS, 1, 1, Bf16DirectFixed<TW, TH>::LDS_BYTES, UNIT_US, FIXED_US, 0},       \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                if (!Bf16DirectFixed<TW, TH>::matches_host(a) || lds != (size_t)Bf16DirectFixed<TW, TH>::LDS_BYTES) return 1; \
+                return launch_kernel(conv_bf16_direct_kernel<TW, TH>, attr_done, 512, a, grid, lds, stream);    \
+            }                                                                                                  \
+    }
+
 using FxStem7 = F32StemFixed<2, 2, 7, 7, 2, 2, 3>;
 using FxF32B8W4H4 = F32V4Fixed<8, 4, 4, 64, 16, 3>;
 using FxBf16B64W7H1 = Bf16Fixed<2, 1, 64, 7, 1, 32, 1>;
@@ -2639,9 +2896,11 @@ static const Variant g_variants[] = {
                      conv_bf16_fx_kernel<2, 1, 64, 7, 1, 32, 1>),
     CACNN_FX_VARIANT(1, "bf16 fx k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.86f, 4.0f, 2, 2, 1, 4, 64, 2, 2, 3, 32, 1, FxBf16B64W2H2,
                      conv_bf16_fx_kernel<2, 1, 64, 2, 2, 32, 1>),
+    CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 0.9f, 8.0f, 7, 1),
+    CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.6f, 4.0f, 2, 2),
     // fixed geometry for the stem-layer shape: 7x7 taps, strides 2, three channels
     {{"f32 fxs k64 b32w2h2 w2x2 m1n2 c3r7s7 s2", 0, 2, 2, 1, FxStem7::NBLK, 32, 2, 2, 2, 1, 1, 1, 0, 1.0f, 3, 7, 7, FxStem7::YS, 2,
-      2, FxStem7::LDS_BYTES, 6.3f, 5.5f},
+      2, FxStem7::LDS_BYTES, 6.3f, 5.5f, 1},
      [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {
          static bool attr_done = false;
          if (!FxStem7::matches_host(a) || lds != (size_t)FxStem7::LDS_BYTES) return 1;
