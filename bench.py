@@ -52,6 +52,45 @@ def time_config(cc, torch, ci, np, cfg, steps, warmup, repeats=1):
     return best[0] / steps, best[1] / steps, (img, flt, d_out)
 
 
+def machine_sustained(cc, torch, ci, np):
+    """What this machine sustains, measured now: a register-only MFMA loop on every CU (operands with the value mix of the
+    workloads, and all-zero operands, which toggle nothing and let the clock stay high) and a 1 GiB streaming copy.
+    The published peaks assume 2.4 GHz; an all-CU matrix load is power-managed below that."""
+    def timed(fn, warm, reps):
+        for _ in range(warm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+    rng = np.random.default_rng(18020690)
+    sink = torch.empty(65536, dtype=torch.float32, device="cuda:0")
+    out = {}
+    for name, dt, flops, iters in (("f32", 0, 4096.0, 800), ("bf16", 1, 32768.0, 1600)):
+        if dt == 0:
+            words = rng.uniform(-1.0, 1.0, 4096).astype(np.float32).view(np.int32)
+        else:
+            words = np.ascontiguousarray(ci.bf16_bits(ci.round_to_bf16(rng.standard_normal(8192).astype(np.float32)))).view(np.int32)
+        for label, host in (("", words), ("_zero_operands", np.zeros(4096, dtype=np.int32))):
+            ops = torch.from_numpy(np.ascontiguousarray(host)).cuda()
+            n = [0]
+            def launch():
+                n[0] = cc.cacnn_probe_mfma(dt, ops, sink, iters)
+            sec = timed(launch, 30, 30)
+            out[f"mfma_{name}_tflops{label}"] = n[0] * flops / sec / 1e12
+    nbytes = 1 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    sec = timed(lambda: cc.cacnn_probe_copy(src, dst, nbytes), 5, 10)
+    out["copy_GBps_read_plus_write"] = 2.0 * nbytes / sec / 1e9
+    del src, dst
+    return out
+
+
 def committed_traffic(name):
     """HBM-side bytes of one launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs, scaled
     by the copy-kernel calibration recorded there).  Counters cannot be read from inside this process, so the
@@ -267,6 +306,8 @@ def main():
         return
     sec, wall, (img, flt, d_out) = time_config(cc, torch, ci, np, cfg, args.steps, args.warmup)
     head = shape_report(cc, cfg, sec)
+    sustained = machine_sustained(cc, torch, ci, np)
+    head["frac_mfma_sustained"] = head["tflops"] / sustained[f"mfma_{cfg.dtype}_tflops"]
 
     # parity of the timed launch against the oracle (also the cpu_baseline leg)
     result = {
@@ -279,7 +320,8 @@ def main():
                    "variant": head["variant"], "grid": head["grid"], "lds_bytes": head["lds_bytes"]},
         "roofline": {"bound": "mfma", "achieved": head["tflops"], "peak": MFMA_PEAK_TFLOPS[cfg.dtype],
                      "unit": "TFLOP/s", "frac": head["frac_mfma_peak"], "traffic": head["hbm_bytes_profiled"],
-                     "wall_us_per_step": wall * 1e6},
+                     "wall_us_per_step": wall * 1e6, "frac_of_sustained_mfma": head["frac_mfma_sustained"]},
+        "machine_sustained": sustained,
     }
     if not args.no_cpu:
         base, ref, ab, k_use = cpu_baseline(cfg, img, flt, np)
@@ -295,6 +337,7 @@ def main():
                 continue
             s, _, _ = time_config(cc, torch, ci, np, c, args.steps, args.warmup)
             shapes[name] = shape_report(cc, c, s)
+            shapes[name]["frac_mfma_sustained"] = shapes[name]["tflops"] / sustained[f"mfma_{c.dtype}_tflops"]
         result["shapes"] = shapes
         result["pooling"] = pooling_report(cc, torch, ci, np, args.steps, args.warmup, not args.no_cpu)
     print(json.dumps(result))

@@ -22,6 +22,7 @@
 #ifndef CACNN_H
 #define CACNN_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -193,6 +194,26 @@ int cacnn_pool_lower_bound(const cacnn_problem* problem, double M_words, cacnn_p
  */
 int cacnn_pool_forward(const cacnn_problem* problem, int dtype, int mode, const void* image, void* out,
                        void* hip_stream);
+
+/*
+ * Measurement support: what this machine sustains, for reading the convolution's rates against (the published peaks
+ * assume the peak clock; under an all-CU matrix load the clock is power-managed and depends on the operand bits).
+ *
+ * cacnn_probe_mfma: a register-only MFMA loop, one workgroup of four wavefronts on each of the 256 compute units, with
+ * the instruction mix of the convolution kernels' inner step (21 MFMAs on 7 accumulators, 3 + 9 operand fragments).
+ *   dtype        in   CACNN_F32 (32x32x2 fp32 MFMAs, 4096 flops each) or CACNN_BF16_F32ACC (32x32x16 bf16, 32768 flops)
+ *   operands     in   DEVICE pointer, 16-byte aligned, 16 KiB: the operand fragments are taken from here (fp32 words or
+ *                     packed bf16 pairs); all zeros gives the rate with nothing toggling
+ *   sink         out  DEVICE pointer, 65536 fp32, overwritten with sums of the accumulators (so the work is kept)
+ *   iters        in   1 .. 2^24; the launch issues 256 * 4 * iters * 42 MFMAs, returned in *mfma_issued (host)
+ * cacnn_probe_copy: dst[0..bytes) = src[0..bytes) with streaming loads and stores: bytes read and bytes written.
+ *   src, dst     DEVICE pointers, 16-byte aligned, not overlapping; bytes a positive multiple of 16
+ * Both enqueue on hip_stream and return; they never synchronise and allocate nothing.  The caller times them.
+ * Errors: CACNN_ERR_NULL, CACNN_ERR_INVALID_ARG (alignment, sizes, iters), CACNN_ERR_UNSUPPORTED (dtype),
+ * CACNN_ERR_NO_DEVICE, CACNN_ERR_LAUNCH.
+ */
+int cacnn_probe_mfma(int dtype, const void* operands, float* sink, int32_t iters, int64_t* mfma_issued, void* hip_stream);
+int cacnn_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
 
 /* Number of compiled kernel variants, and a static, NUL-terminated description of one
  * ("f32 k64 b8w4h4 ..."); NULL if the index is out of range.  Host only. */

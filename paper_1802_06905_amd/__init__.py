@@ -19,6 +19,8 @@ from .binding import (  # noqa: F401
     cacnn_lower_bound,
     cacnn_pool_forward,
     cacnn_pool_lower_bound,
+    cacnn_probe_copy,
+    cacnn_probe_mfma,
     cacnn_status_string,
     cacnn_tile_plan,
     cacnn_variant_count,

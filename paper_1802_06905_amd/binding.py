@@ -92,6 +92,11 @@ _lib.cacnn_pool_lower_bound.argtypes = [ctypes.POINTER(Problem), ctypes.c_double
 _lib.cacnn_pool_forward.restype = ctypes.c_int
 _lib.cacnn_pool_forward.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                     ctypes.c_void_p]
+_lib.cacnn_probe_mfma.restype = ctypes.c_int
+_lib.cacnn_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                  ctypes.POINTER(ctypes.c_int64), ctypes.c_void_p]
+_lib.cacnn_probe_copy.restype = ctypes.c_int
+_lib.cacnn_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.cacnn_variant_count.restype = ctypes.c_int
 _lib.cacnn_variant_name.restype = ctypes.c_char_p
 _lib.cacnn_variant_name.argtypes = [ctypes.c_int]
@@ -181,6 +186,22 @@ def cacnn_pool_forward(problem, dtype: int, mode: int, image, out, stream=None) 
                                  _stream_handle(stream))
     if rc != 0:
         raise CacnnError(rc, "cacnn_pool_forward")
+
+
+def cacnn_probe_mfma(dtype: int, operands, sink, iters: int, stream=None) -> int:
+    """Enqueue the register-only MFMA loop (operands: 16 KiB device tensor, sink: 65536 fp32); returns the MFMAs issued."""
+    n = ctypes.c_int64(0)
+    rc = _lib.cacnn_probe_mfma(int(dtype), _ptr(operands), _ptr(sink), int(iters), ctypes.byref(n), _stream_handle(stream))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_probe_mfma")
+    return n.value
+
+
+def cacnn_probe_copy(src, dst, nbytes: int, stream=None) -> None:
+    """Enqueue the streaming copy dst[0..nbytes) = src[0..nbytes) (device tensors)."""
+    rc = _lib.cacnn_probe_copy(_ptr(src), _ptr(dst), int(nbytes), _stream_handle(stream))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_probe_copy")
 
 
 def cacnn_conv_forward_with_plan(problem, dtype: int, plan: Plan, image, filt, out, stream=None) -> None:

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcacnn.so")
-SOURCES = ["cacnn_host.cpp", "cacnn_kernels.hip", "cacnn_pool.hip"]
+SOURCES = ["cacnn_host.cpp", "cacnn_kernels.hip", "cacnn_pool.hip", "cacnn_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -783,6 +783,25 @@ int cacnn_pool_forward(const cacnn_problem* problem, int dtype, int mode, const 
     return launch_pool(a, dtype, mode, vec, hip_stream) == 0 ? CACNN_OK : CACNN_ERR_LAUNCH;
 }
 
+int cacnn_probe_mfma(int dtype, const void* operands, float* sink, int32_t iters, int64_t* mfma_issued, void* hip_stream) {
+    if (!operands || !sink || !mfma_issued) return CACNN_ERR_NULL;
+    if (dtype != CACNN_F32 && dtype != CACNN_BF16_F32ACC) return CACNN_ERR_UNSUPPORTED;
+    if (iters < 1 || iters > (1 << 24) || reinterpret_cast<uintptr_t>(operands) % 16 || reinterpret_cast<uintptr_t>(sink) % 4)
+        return CACNN_ERR_INVALID_ARG;
+    if (!have_device()) return CACNN_ERR_NO_DEVICE;
+    const int grid = kDefaultMachine.num_cu;
+    *mfma_issued = (int64_t)grid * 4 * iters * 42;
+    return launch_mfma_probe(dtype, operands, sink, iters, grid, hip_stream) == 0 ? CACNN_OK : CACNN_ERR_LAUNCH;
+}
+
+int cacnn_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
+    if (!src || !dst) return CACNN_ERR_NULL;
+    if (bytes == 0 || bytes % 16 || reinterpret_cast<uintptr_t>(src) % 16 || reinterpret_cast<uintptr_t>(dst) % 16)
+        return CACNN_ERR_INVALID_ARG;
+    if (!have_device()) return CACNN_ERR_NO_DEVICE;
+    return launch_copy_probe(src, dst, bytes, kDefaultMachine.num_cu * 8, hip_stream) == 0 ? CACNN_OK : CACNN_ERR_LAUNCH;
+}
+
 int cacnn_variant_count(void) { return num_variants(); }
 
 const char* cacnn_variant_name(int i) {

@@ -3,6 +3,7 @@
 #ifndef CACNN_INTERNAL_H
 #define CACNN_INTERNAL_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 namespace cacnn {
@@ -104,6 +105,10 @@ struct PoolArgs {
 };
 // dtype: cacnn_dtype; mode: cacnn_pool_mode; vec: images per thread (1, or 4 for fp32 / 8 for bf16). 0 = launched.
 int launch_pool(const PoolArgs& a, int dtype, int mode, int vec, void* stream);
+
+// Measurement kernels (cacnn_probe.hip).  0 = launched.
+int launch_mfma_probe(int dtype, const void* operands, float* sink, int iters, int grid, void* stream);
+int launch_copy_probe(const void* src, void* dst, size_t bytes, int grid, void* stream);
 
 // Defined in cacnn_kernels.hip.
 int num_variants();

@@ -1,0 +1,86 @@
+// Measurement support for gfx950: what this machine sustains, to read the convolution's rates against.
+//   mfma_rate_kernel  a register-only MFMA loop on every compute unit (one wavefront per SIMD, the same instruction
+//                     mix as the convolution kernels' inner step: 21 MFMAs on 7 accumulators, 3 + 9 operand fragments)
+//   copy_kernel       a streaming copy through HBM
+// The published peaks assume the peak clock; under an all-CU matrix load the clock is power-managed and depends on
+// how much the operand bits toggle, so the sustained MFMA rate is a property of the box and of the data.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cacnn_internal.h"
+
+namespace cacnn {
+
+typedef float pr_f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 pr_bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int pr_u32x4 __attribute__((ext_vector_type(4)));
+
+// operands: 4096 32-bit words.  DT 0: fp32 32x32x2 MFMAs, DT 1: bf16 32x32x16 MFMAs.  One launch issues
+// gridDim.x * 4 * iters * 42 MFMAs.  The accumulators go to sink so that nothing is optimised away.
+template <int DT>
+__global__ void __launch_bounds__(256) mfma_rate_kernel(const uint32_t* operands, float* sink, int iters) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    pr_f32x16 acc[7];
+#pragma unroll
+    for (int n = 0; n < 7; ++n)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
+    if constexpr (DT == 0) {
+        float A[3], X[9];
+#pragma unroll
+        for (int r = 0; r < 3; ++r) A[r] = __uint_as_float(operands[(lane + 64 * r) & 4095]);
+#pragma unroll
+        for (int x = 0; x < 9; ++x) X[x] = __uint_as_float(operands[(lane + 64 * (3 + x)) & 4095]);
+        for (int it = 0; it < 2 * iters; ++it) {
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int w = 0; w < 7; ++w) acc[w] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[r], X[w + r], acc[w], 0, 0, 0);
+        }
+    } else {
+        pr_bf16x8 A[3], X[9];
+        const pr_u32x4* const op = (const pr_u32x4*)operands;      // 1024 16-byte fragments
+#pragma unroll
+        for (int r = 0; r < 3; ++r) A[r] = __builtin_bit_cast(pr_bf16x8, op[(lane + 64 * r) & 1023]);
+#pragma unroll
+        for (int x = 0; x < 9; ++x) X[x] = __builtin_bit_cast(pr_bf16x8, op[(lane + 64 * (3 + x)) & 1023]);
+        for (int it = 0; it < 2 * iters; ++it) {
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int w = 0; w < 7; ++w)
+                    acc[w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[r], X[w + r], acc[w], 0, 0, 0);
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int n = 0; n < 7; ++n)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s += acc[n][v];
+    sink[blockIdx.x * 256 + tid] = s;
+}
+
+// dst[i] = src[i] for n 16-byte words; every wave reads and writes whole 1 KiB runs, streaming hints on both sides
+__global__ void __launch_bounds__(256) copy_kernel(const pr_u32x4* src, pr_u32x4* dst, size_t n) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+int launch_mfma_probe(int dtype, const void* operands, float* sink, int iters, int grid, void* stream) {
+    if (dtype == 0)
+        hipLaunchKernelGGL(mfma_rate_kernel<0>, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint32_t*)operands,
+                           sink, iters);
+    else
+        hipLaunchKernelGGL(mfma_rate_kernel<1>, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint32_t*)operands,
+                           sink, iters);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int launch_copy_probe(const void* src, void* dst, size_t bytes, int grid, void* stream) {
+    hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const pr_u32x4*)src, (pr_u32x4*)dst,
+                       bytes / 16);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+}  // namespace cacnn

@@ -228,3 +228,21 @@ def test_pool_forward_rejects_bad_arguments_before_touching_the_gpu():
         with pytest.raises(cc.CacnnError) as e:
             cc.cacnn_pool_forward(dims, dtype, mode, img, out, stream=0)
         assert e.value.status == status, (dims, dtype, mode, img, out)
+
+
+def test_probes_reject_bad_arguments_before_touching_the_gpu():
+    for dtype, ops, sink, iters, status in (
+            (0, 0, 16, 10, 1),          # null operands
+            (0, 16, 0, 10, 1),          # null sink
+            (9, 16, 16, 10, 3),         # unknown dtype
+            (0, 16, 16, 0, 2),          # iters < 1
+            (0, 16, 16, 1 << 25, 2),    # iters too large
+            (1, 24, 16, 10, 2),         # operands not 16-byte aligned
+    ):
+        with pytest.raises(cc.CacnnError) as e:
+            cc.cacnn_probe_mfma(dtype, ops, sink, iters, stream=0)
+        assert e.value.status == status, (dtype, ops, sink, iters)
+    for src, dst, n, status in ((0, 16, 64, 1), (16, 0, 64, 1), (16, 32, 0, 2), (16, 32, 24, 2), (8, 32, 64, 2)):
+        with pytest.raises(cc.CacnnError) as e:
+            cc.cacnn_probe_copy(src, dst, n, stream=0)
+        assert e.value.status == status, (src, dst, n)
