@@ -2040,235 +2040,10 @@ __global__ void __launch_bounds__(WM* WN * 64 + 256) conv_f32v4_fx_kernel(const 
     }
 }
 
-// bf16, b_r = 3 taps reused from registers; a wave owns 32 output channels x 32 images x the tile's TW x TH positions
-template <int WM, int MBLK, int TB, int TW, int TH, int CT, int BS>
-struct Bf16Fixed {
-    static constexpr int BR = 3;
-    static constexpr int WN = TB / 32, KT = WM * MBLK * 32, NBLK = TW * TH;
-    static constexpr int C8 = CT / 8, B8 = TB / 8, STEPS = BS * (CT / 16);
-    static constexpr int XS = TW + BR - 1, YS = TH - 1 + BS;
-    static constexpr int YP = C8 * TB, XP = YS * YP;
-    static constexpr int F8 = (BR * BS * C8) | 1;
-    static constexpr int IMG_BUF = XS * XP, FLT_OFF = 2 * IMG_BUF, FLT_BUF = KT * F8;
-    static constexpr int PT = 256;      // staging threads
-    static constexpr int IMG_ITEMS = XS * YS * C8 * B8, FLT_ITEMS = KT * BR * BS * C8;
-    static constexpr int MAXI = (IMG_ITEMS + PT - 1) / PT, MAXF = (FLT_ITEMS + PT - 1) / PT;
-    static_assert(TB == 32 || TB == 64, "fixed bf16 geometry: 32 or 64 images per tile");
-    static_assert(CT % 16 == 0 && STEPS % 2 == 0, "fixed bf16 geometry: an even number of 16-channel steps per unit");
-    static_assert(16 * IMG_BUF < 65536 && 16 * FLT_BUF < 65536, "LDS offsets must fit the 16-bit immediate");
-    static bool matches_host(const KernelArgs& a) {
-        return a.sw == 1 && a.sh == 1 && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
-               a.xpitch == XP && a.ypitch == YP && a.fpitch == 8 * F8 && a.img_buf == IMG_BUF &&
-               a.flt_off == FLT_OFF && a.flt_buf == FLT_BUF && !a.flt_resident && a.R == BR && a.S % BS == 0 &&
-               a.C % CT == 0 && a.B % TB == 0 && a.W % TW == 0 && a.H % TH == 0 && a.K % KT == 0 && a.vec_img &&
-               a.vec_flt;
-    }
-};
-
-// Staging half of the fixed bf16 kernel: two register sets, two units ahead; every store address is precomputed.
-template <class GEO, int TB, int TW, int TH, int KT, int CT, int BS>
-__device__ __forceinline__ void bf16_fx_producer(const KernelArgs& a, uint4* smem_u, int stid) {
-    constexpr int MAXI = GEO::MAXI, MAXF = GEO::MAXF, PT = GEO::PT;
-    char* const lds = (char*)smem_u;
-    uint32_t ig[MAXI], il[2][MAXI][8], fg[MAXF], fl[2][MAXF];
-    const uint32_t row_bytes = (uint32_t)a.B * 2u;
-#pragma unroll
-    for (int i = 0; i < MAXI; ++i) {
-        int idx = stid + i * PT;
-        if (idx >= GEO::IMG_ITEMS) idx = 0;
-        const int b8 = idx % GEO::B8, t = idx / GEO::B8;
-        const int c8 = t % GEO::C8, t2 = t / GEO::C8;
-        const int y = t2 % GEO::YS, x = t2 / GEO::YS;
-        // the eight 16-byte units of an item (one per image) fill one aligned 128-byte group; image m goes to
-        // slot m ^ key so that neighbouring lanes' stores land in different banks
-        const uint32_t base = (uint32_t)(x * GEO::XP + y * GEO::YP + c8 * TB + b8 * 8);
-        const uint32_t key = (uint32_t)store_key<TB>(b8, c8);
-#pragma unroll
-        for (int m = 0; m < 8; ++m) {
-            il[0][i][m] = (base + ((uint32_t)m ^ key)) * 16u;
-            il[1][i][m] = il[0][i][m] + 16u * GEO::IMG_BUF;
-        }
-        ig[i] = ((((uint32_t)x * a.IH + y) * a.C + c8 * 8) * a.B + b8 * 8) * 2u;
-    }
-#pragma unroll
-    for (int i = 0; i < MAXF; ++i) {
-        int idx = stid + i * PT;
-        if (idx >= GEO::FLT_ITEMS) idx = 0;
-        const int c8 = idx % GEO::C8, t = idx / GEO::C8;
-        const int rs = t % (GEO::BR * BS), kl = t / (GEO::BR * BS);
-        const int r = rs / BS, sl = rs % BS;
-        fl[0][i] = (uint32_t)(GEO::FLT_OFF + kl * GEO::F8 + rs * GEO::C8 + c8) * 16u;
-        fl[1][i] = fl[0][i] + 16u * GEO::FLT_BUF;
-        fg[i] = ((((uint32_t)kl * a.R + r) * a.S + sl) * a.C + c8 * 8) * 2u;
-    }
-
-    FxWalk<2, KT, TB, TW, TH, CT, BS> lu;     // next unit to fetch
-    lu.init(a);
-    int to_store = 0;                          // units fetched and not yet stored
-    uint4 ireg[2][MAXI][8], freg[2][MAXF];
-    auto issue = [&](int set) {
-        const __amdgpu_buffer_rsrc_t ri = lu.img(a), rf = lu.flt(a);
-#pragma unroll
-        for (int i = 0; i < MAXI; ++i)
-            if (i * PT + PT <= GEO::IMG_ITEMS || stid < GEO::IMG_ITEMS - i * PT) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) ireg[set][i][e] = buf_load_u4(ri, ig[i], e * row_bytes);
-            }
-#pragma unroll
-        for (int i = 0; i < MAXF; ++i)
-            if (i * PT + PT <= GEO::FLT_ITEMS || stid < GEO::FLT_ITEMS - i * PT)
-                freg[set][i] = buf_load_u4(rf, fg[i], 0);
-        lu.next(a);
-        ++to_store;
-    };
-    auto store = [&](int set) {   // set is also the LDS buffer
-#pragma unroll
-        for (int i = 0; i < MAXI; ++i)
-            if (i * PT + PT <= GEO::IMG_ITEMS || stid < GEO::IMG_ITEMS - i * PT) {
-                // 8x8 transpose of 16-bit words, two columns (images 2m, 2m+1) at a time
-#pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    uint32_t lo[4], hi[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const uint4 re = ireg[set][i][2 * q], ro = ireg[set][i][2 * q + 1];
-                        const uint32_t e = m == 0 ? re.x : m == 1 ? re.y : m == 2 ? re.z : re.w;
-                        const uint32_t o = m == 0 ? ro.x : m == 1 ? ro.y : m == 2 ? ro.z : ro.w;
-                        lo[q] = __builtin_amdgcn_perm(o, e, 0x05040100u);   // low halves:  e.lo | o.lo << 16
-                        hi[q] = __builtin_amdgcn_perm(o, e, 0x07060302u);   // high halves: e.hi | o.hi << 16
-                    }
-                    *(uint4*)(lds + il[set][i][2 * m]) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-                    *(uint4*)(lds + il[set][i][2 * m + 1]) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-                }
-            }
-#pragma unroll
-        for (int i = 0; i < MAXF; ++i)
-            if (i * PT + PT <= GEO::FLT_ITEMS || stid < GEO::FLT_ITEMS - i * PT)
-                *(uint4*)(lds + fl[set][i]) = freg[set][i];
-        --to_store;
-    };
-
-#pragma unroll
-    for (int d = 0; d < 2; ++d)
-        if (lu.valid(a)) issue(d);
-    while (to_store > 0) {
-#pragma unroll
-        for (int ph = 0; ph < 2; ++ph) {
-            if (to_store > 0) {
-                store(ph);
-                if (lu.valid(a)) issue(ph);
-                lds_done_then_barrier();
-            }
-        }
-    }
-}
-
-template <int WM, int MBLK, int TB, int TW, int TH, int CT, int BS>
-__global__ void __launch_bounds__(WM*(TB / 32) * 64 + 256) conv_bf16_fx_kernel(const KernelArgs a) {
-    using GEO = Bf16Fixed<WM, MBLK, TB, TW, TH, CT, BS>;
-    constexpr int WN = GEO::WN, KT = GEO::KT, NBLK = GEO::NBLK, BR = GEO::BR, XS = GEO::XS;
-    constexpr int CTHREADS = WM * WN * 64;
-    extern __shared__ __align__(16) uint4 smem_u[];
-    const int tid = threadIdx.x;
-    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
-
-    if (wave_id >= WM * WN) {
-        bf16_fx_producer<GEO, TB, TW, TH, KT, CT, BS>(a, smem_u, tid - CTHREADS);
-    } else {
-        const int lane = tid & 63, wave = wave_id;
-        const int wm = wave % WM, wn = wave / WM;
-        const int j = lane & 31, g = lane >> 5;
-        f32x16 acc[MBLK][NBLK];
-        zero_acc(acc);
-        // per-lane bases of the two LDS buffers (a lane's c8 has the parity of g, which is all the store key looks at)
-        const int b_l = 32 * wn + j;
-        const int b_sw = (b_l & ~7) | ((b_l & 7) ^ store_key<TB>(b_l >> 3, g));
-        const uint4* ap[2];
-        const uint4* bp[2];
-#pragma unroll
-        for (int buf = 0; buf < 2; ++buf) {
-            ap[buf] = smem_u + GEO::FLT_OFF + buf * GEO::FLT_BUF + (wm * MBLK * 32 + j) * GEO::F8 + g;
-            bp[buf] = smem_u + buf * GEO::IMG_BUF + g * TB + b_sw;
-        }
-        bf16x8 A[2][MBLK][BR], X[2][TH][XS];
-        auto load_step = [&](int buf, int t, int set) {
-            const int sl = t / (CT / 16), cs = t % (CT / 16);
-#pragma unroll
-            for (int m = 0; m < MBLK; ++m)
-#pragma unroll
-                for (int r = 0; r < BR; ++r)
-                    A[set][m][r] = __builtin_bit_cast(
-                        bf16x8, ap[buf][m * 32 * GEO::F8 + (r * BS + sl) * GEO::C8 + 2 * cs]);
-#pragma unroll
-            for (int h = 0; h < TH; ++h)
-#pragma unroll
-                for (int x = 0; x < XS; ++x)
-                    X[set][h][x] = __builtin_bit_cast(
-                        bf16x8, bp[buf][x * GEO::XP + (h + sl) * GEO::YP + 2 * cs * TB]);
-        };
-        auto mfma_step = [&](int set) {
-#pragma unroll
-            for (int r = 0; r < BR; ++r)
-#pragma unroll
-                for (int h = 0; h < TH; ++h)
-#pragma unroll
-                    for (int w = 0; w < TW; ++w)
-#pragma unroll
-                        for (int m = 0; m < MBLK; ++m)
-                            acc[m][h * TW + w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                A[set][m][r], X[set][h][w + r], acc[m][h * TW + w], 0, 0, 0);
-        };
-
-        const int64_t out_kstride = (int64_t)a.H * a.W * a.B;      // floats between output channels
-        const uint32_t out_lane = (uint32_t)(g * 4) * (uint32_t)out_kstride + (uint32_t)b_l;
-        UnitPos cur = first_unit(a, KT, TB, TW, TH);
-        UnitPos nxt = cur;
-        bool have = cur.t < a.n_tiles;
-        if (have) {
-            advance_unit(a, nxt, KT, TB, TW, TH);
-            lds_done_then_barrier();        // unit 0 is staged
-            load_step(0, 0, 0);
-        }
-        while (have) {
-#pragma unroll
-            for (int buf = 0; buf < 2; ++buf) {
-                if (have) {
-                    const bool have_next = nxt.t < a.n_tiles;
-#pragma unroll
-                    for (int t = 0; t < GEO::STEPS; ++t) {
-                        if (t + 1 < GEO::STEPS) {
-                            load_step(buf, t + 1, (t + 1) & 1);
-                        } else if (have_next) {
-                            // as in the fp32 kernel: release the buffer once the last fragments have landed, read
-                            // the next unit's first fragments under this step's MFMAs
-                            lds_done_then_barrier();
-                            load_step(buf ^ 1, 0, 0);
-                        }
-                        mfma_step(t & 1);
-                        interleave_hint<BR * NBLK * MBLK, TH * XS + MBLK * BR>();
-                    }
-                    if (!have_next || nxt.t != cur.t) {
-#pragma unroll
-                        for (int n = 0; n < NBLK; ++n)
-#pragma unroll
-                            for (int m = 0; m < MBLK; ++m) {
-                                float* const blk = a.out + ((((int64_t)(cur.tc.k0 + (wm * MBLK + m) * 32) * a.H +
-                                                              cur.tc.h0 + n / TW) * a.W + cur.tc.w0 + n % TW) * a.B + cur.tc.b0);
-                                store_block_exact<true>(blk, out_kstride, out_lane, acc[m][n]);
-                            }
-                    }
-                    cur = nxt;
-                    have = have_next;
-                    if (have_next) advance_unit(a, nxt, KT, TB, TW, TH);
-                }
-            }
-        }
-    }
-}
-
 // ---- fixed geometry, bf16, Image loaded straight into LDS ---------------------------------------------------------------
-// Measured on the kernel above: next to a bf16 MFMA stream a staging wave gets about one instruction per 11 cycles,
-// and its ~130 instructions per unit (loads, the 8x8 transposes, LDS stores) are what a unit ends up waiting for.
+// A kernel that staged the Image through registers (8 loads, a 8x8 transpose of 16-bit words and 8 LDS stores per
+// item, ~130 instructions per unit and staging wave) was measured to wait for its staging waves: next to a bf16 MFMA
+// stream a staging wave gets about one instruction per 11 cycles.
 // Here the Image words never pass through registers: a buffer load with the LDS as its destination puts 64 lanes x
 // 16 bytes, in lane order, at a wave-uniform LDS address, so one instruction moves 8 channel rows of the tile's 64
 // images (1 KiB) and a staging wave issues 8 or 9 of them per unit.  The Image keeps its global order in LDS,
@@ -2493,6 +2268,212 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
         if (left > 0) {
             lds_done_then_barrier_known();      // unit 0 is staged
             load_step(al, xl, 0, 0);
+            while (left > 1) unit(std::true_type{});
+            unit(std::false_type{});
+        }
+    }
+}
+
+// ---- fixed geometry, fp32, Image loaded straight into LDS -------------------------------------------------------------
+// The same staging for fp32 tiles of 8 images x 4 x 4 output positions.  Next to an fp32 MFMA stream a staging wave
+// gets even fewer issue slots than next to a bf16 one, and the register-staged kernel above was measured with its
+// staging waves arriving at the barrier as late as the multiplying ones.  An fp32 MFMA takes one word per lane and
+// operand, so nothing has to be transposed: the Image keeps its global order in LDS, [x][y][c][b] with the tile's 8
+// images fastest (32-byte rows, 512 bytes per position, one x plane = 6 positions + 32 bytes of padding so that the four
+// output columns of an MFMA column block fall into different banks), and lane (column j, contraction half g) reads
+// its word of channel c0 + 4g + t for the t-th MFMA of a group of four.  The Filter tile keeps [k][r][s][c] order (rows
+// padded to 592 bytes: conflict-free 16-byte reads); a lane's 16-byte fragment holds channels c0 + 4g .. c0 + 4g + 3.
+// Three Image buffers (loads into LDS two units ahead), two Filter buffers (staged through registers and stored just
+// before the unit is announced).
+template <int TW, int TH>
+struct F32DirectFixed {
+    static constexpr int TB = 8, KT = 64, WM = 2, WN = 2, CT = 16, BS = 3, BR = 3, NBLK = TH / WN;
+    static constexpr int XS = TW + BR - 1, YS = TH - 1 + BS;
+    static constexpr int POS = CT * TB * 4;                         // bytes of one (x, y) position
+    static constexpr int XP = YS * POS + 32;                        // bytes of one x plane
+    static constexpr int IMG_BYTES = XS * XP, NBUF_I = 3;
+    static constexpr int FP = BR * BS * CT * 4 + 16;                // bytes of one Filter row
+    static constexpr int FLT_BYTES = KT * FP, NBUF_F = 2;
+    static constexpr int FLT_OFF = NBUF_I * IMG_BYTES;
+    static constexpr int LDS_BYTES = FLT_OFF + NBUF_F * FLT_BYTES;
+    static constexpr int PT = 256, PW = PT / 64;
+    static constexpr int CHUNKS = XS * YS / 2, CPW = (CHUNKS + PW - 1) / PW;   // 1 KiB chunks: two positions (y, y + 1)
+    static constexpr int FLT_ITEMS = KT * BR * BS * (CT / 4), MAXF = FLT_ITEMS / PT, MAXI = 1;
+    static constexpr int LOADS = CPW + MAXF;
+    static constexpr int GROUPS = BR * BS * (CT / 8);               // groups of four MFMAs per column block and unit
+    static_assert(TB * TW == 32 && TH % WN == 0, "direct fp32 geometry: a column block is one tile row");
+    static_assert(YS % 2 == 0 && POS == 512, "direct fp32 geometry: two positions of one x plane per chunk");
+    static_assert(FLT_ITEMS % PT == 0 && GROUPS % 2 == 0, "direct fp32 geometry: whole Filter items, even group count");
+    static_assert(IMG_BYTES < 65536 && LDS_BYTES <= 160 * 1024 && 2 * LOADS < 64, "direct fp32 geometry: LDS offsets, size, load counter");
+    static bool matches_host(const KernelArgs& a) {
+        return a.sw == 1 && a.sh == 1 && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
+               a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % TB == 0 && a.W % TW == 0 && a.H % TH == 0 &&
+               a.K % KT == 0 && a.vec_img && a.vec_flt;
+    }
+};
+
+template <int TW, int TH>
+__global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a) {
+    using GEO = F32DirectFixed<TW, TH>;
+    constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, BR = GEO::BR, WM = GEO::WM, NBLK = GEO::NBLK;
+    constexpr int XS = GEO::XS, YS = GEO::YS, XP = GEO::XP, POS = GEO::POS, FP = GEO::FP;
+    constexpr int IBUF = GEO::IMG_BYTES, FBUF = GEO::FLT_BYTES;
+    constexpr int CTHREADS = GEO::WM * GEO::WN * 64;
+    extern __shared__ __align__(16) f32x4 smem_v[];
+    CACNN_LDS(char)* const lds = (CACNN_LDS(char)*)smem_v;
+    const int tid = threadIdx.x;
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
+    const int lane = tid & 63;
+    // units this workgroup works through: its tiles blockIdx.x, blockIdx.x + gridDim.x, ... times the slices of a tile
+    const int upt = (a.C / CT) * (a.S / BS);
+    int total = 0;
+    for (int t = blockIdx.x; t < a.n_tiles; t += gridDim.x) total += upt;
+
+    if (wave_id >= GEO::WM * GEO::WN) {
+        const int pw = wave_id - GEO::WM * GEO::WN, stid = tid - CTHREADS;
+        constexpr int MAXF = GEO::MAXF, CPW = GEO::CPW, PT = GEO::PT;
+        // Image: lane L of a chunk load fetches 16-byte piece L % 32 (channel (L % 32) / 2, images 4 * (L % 2)..) of
+        // position y + L / 32
+        const uint32_t row_bytes = (uint32_t)a.B * 4u;
+        const uint32_t ivoff = (uint32_t)(lane >> 5) * (uint32_t)a.C * row_bytes + (uint32_t)((lane & 31) >> 1) * row_bytes +
+                               (uint32_t)(lane & 1) * 16u;
+        uint32_t isoff[CPW], ildst[CPW];
+#pragma unroll
+        for (int i = 0; i < CPW; ++i) {
+            // the waves that would run out of chunks fetch the last one again (same words to the same place)
+            const int ch = min(pw + GEO::PW * i, GEO::CHUNKS - 1);
+            const int x = ch / (YS / 2), yy = ch % (YS / 2);
+            isoff[i] = (uint32_t)((x * a.IH + 2 * yy) * a.C) * row_bytes;
+            ildst[i] = (uint32_t)(x * XP + yy * 2 * POS);
+        }
+        uint32_t fg[MAXF], fl[MAXF];
+#pragma unroll
+        for (int i = 0; i < MAXF; ++i) {
+            const int idx = stid + i * PT;
+            const int c4 = idx % (CT / 4), t = idx / (CT / 4);
+            const int rs = t % (BR * BS), kl = t / (BR * BS);
+            const int r = rs / BS, sl = rs % BS;
+            fl[i] = (uint32_t)(uintptr_t)(lds + GEO::FLT_OFF + kl * FP + (rs * CT + c4 * 4) * 4);
+            fg[i] = ((((uint32_t)kl * a.R + r) * a.S + sl) * a.C + c4 * 4) * 4u;
+        }
+        FxWalk<4, KT, TB, TW, TH, CT, BS> lu;     // next unit to fetch
+        lu.init(a);
+        f32x4 freg[2][MAXF];
+        int ioff_issue = 0;                       // Image buffer the next fetch goes to
+        int foff_store = 0;                       // Filter buffer of the next announced unit
+        auto issue = [&](int set) {
+            const __amdgpu_buffer_rsrc_t ri = lu.img(a), rf = lu.flt(a);
+#pragma unroll
+            for (int i = 0; i < CPW; ++i) load_16_bytes_per_lane_to_lds(ri, lds + ioff_issue + ildst[i], ivoff, isoff[i]);
+#pragma unroll
+            for (int i = 0; i < MAXF; ++i) freg[set][i] = buf_load_f32x4(rf, fg[i], 0);
+            lu.next(a);
+            ioff_issue = ioff_issue + IBUF == GEO::NBUF_I * IBUF ? 0 : ioff_issue + IBUF;
+        };
+        // announce the unit whose Filter words are in register set `set`: its loads are in once at most `later`
+        // younger loads are outstanding (loads complete in order)
+        auto announce = [&](int set, auto later) {
+            __builtin_amdgcn_s_waitcnt(vmcnt_only(decltype(later)::value));
+#pragma unroll
+            for (int i = 0; i < MAXF; ++i)
+                asm volatile("ds_write_b128 %0, %1" ::"v"(fl[i] + (uint32_t)foff_store), "v"(freg[set][i]) : "memory");
+            lds_done_then_barrier();
+            foff_store = FBUF - foff_store;
+        };
+        using NextUnit = std::integral_constant<int, GEO::LOADS>;
+        using Nothing = std::integral_constant<int, 0>;
+        // straight-line phases and a loop whose state at the back edge equals its state on entry: the compiler's own
+        // count of outstanding loads (it waits for a Filter register before the store that reads it) stays exact
+        if (total == 1) {
+            issue(0);
+            announce(0, Nothing{});
+        } else if (total >= 2) {
+            issue(0);
+            issue(1);
+            int u = 0;
+            for (; u + 4 <= total; u += 2) {
+                announce(0, NextUnit{});
+                issue(0);               // the multiplying waves have left the Image buffer two units back: refill it
+                announce(1, NextUnit{});
+                issue(1);
+            }
+            if (total - u == 3) {
+                announce(0, NextUnit{});
+                issue(0);
+                announce(1, NextUnit{});
+                announce(0, Nothing{});
+            } else {
+                announce(0, NextUnit{});
+                announce(1, Nothing{});
+            }
+        }
+    } else {
+        const int wm = wave_id % WM, wn = wave_id / WM;
+        const int j = lane & 31, g = lane >> 5;
+        f32x16 acc[1][NBLK];
+        zero_acc(acc);
+        // per-lane LDS offsets: Filter row of output channel wm*32 + j, channels 4g..4g+3 of a group of 8;
+        // Image: output column j / 8 of the tile row, image j % 8, channel 4g of a group of 8, tile row wn * NBLK
+        const uint32_t al = (uint32_t)(GEO::FLT_OFF + (wm * 32 + j) * FP + g * 16);
+        const uint32_t xl = (uint32_t)((j >> 3) * XP + wn * NBLK * POS + g * 4 * TB * 4 + (j & 7) * 4);
+        f32x4 A[2];
+        float X[2][NBLK][4];
+        auto load_group = [&](uint32_t ab, uint32_t xb, int grp, int set) {
+            const int c8 = grp % (CT / 8), rs = grp / (CT / 8);
+            const int r = rs / BS, sl = rs % BS;
+            A[set] = *(const CACNN_LDS(f32x4)*)(lds + ab + (rs * CT + c8 * 8) * 4);
+#pragma unroll
+            for (int n = 0; n < NBLK; ++n)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    X[set][n][t] = *(const CACNN_LDS(float)*)(lds + xb + r * XP + (n + sl) * POS + (c8 * 8 + t) * TB * 4);
+        };
+        auto mfma_group = [&](int set) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int n = 0; n < NBLK; ++n)
+                    acc[0][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[set][t], X[set][n][t], acc[0][n], 0, 0, 0);
+        };
+        const int64_t out_kstride = (int64_t)a.H * a.W * a.B;      // floats between output channels
+        const uint32_t out_lane = (uint32_t)(g * 4) * (uint32_t)out_kstride + (uint32_t)((j / TB) * a.B + j % TB);
+        int left = total, in_tile = upt, t = blockIdx.x;
+        uint32_t ioff = 0, foff = 0;
+        // one unit; MORE: another one follows (in the next Image buffer of the three, the other Filter buffer)
+        auto unit = [&](auto more) {
+            constexpr bool MORE = decltype(more)::value;
+#pragma unroll
+            for (int grp = 0; grp < GEO::GROUPS; ++grp) {
+                if (grp + 1 < GEO::GROUPS) {
+                    load_group(al + foff, xl + ioff, grp + 1, (grp + 1) & 1);
+                } else if constexpr (MORE) {
+                    // hand the buffers back once the last fragments have landed, read the next unit's first
+                    // fragments under this group's MFMAs
+                    ioff = ioff + IBUF == GEO::NBUF_I * IBUF ? 0u : ioff + IBUF;
+                    foff = FBUF - foff;
+                    lds_done_then_barrier_known();
+                    load_group(al + foff, xl + ioff, 0, 0);
+                }
+                mfma_group(grp & 1);
+                if (grp + 1 < GEO::GROUPS || MORE) interleave_hint<4 * NBLK, 1 + 4 * NBLK>();
+            }
+            // keep the reads above where they are (the compiler would sink them to the top of the next unit)
+            asm volatile("" ::: "memory");
+            --left;
+            if (--in_tile == 0) {
+                const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
+#pragma unroll
+                for (int n = 0; n < NBLK; ++n) {
+                    float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + tc.h0 + wn * NBLK + n) * a.W + tc.w0) * a.B + tc.b0);
+                    store_block_exact<false>(blk, out_kstride, out_lane, acc[0][n]);
+                }
+                in_tile = upt;
+                t += gridDim.x;
+            }
+        };
+        if (left > 0) {
+            lds_done_then_barrier_known();      // unit 0 is staged
+            load_group(al, xl, 0, 0);
             while (left > 1) unit(std::true_type{});
             unit(std::false_type{});
         }
@@ -2834,10 +2815,20 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
+// fp32 with the Image loaded straight into LDS: 8 images x 4 x 4 positions, 64 output channels, 16-channel slices of three filter rows
+#define CACNN_F32_DIRECT_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                               \
+    {                                                                                                          \
+        {NAME, 0, 2, 2, 1, F32DirectFixed<TW, TH>::NBLK, 8, TW, TH, 2, 1, F32DirectFixed<TW, TH>::MAXF, 1, -4, 1.0f, 16, 3,    \
+         3, F32DirectFixed<TW, TH>::YS, 1, 1, F32DirectFixed<TW, TH>::LDS_BYTES, UNIT_US, FIXED_US, 0},         \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                if (!F32DirectFixed<TW, TH>::matches_host(a) || lds != (size_t)F32DirectFixed<TW, TH>::LDS_BYTES) return 1; \
+                return launch_kernel(conv_f32_direct_kernel<TW, TH>, attr_done, 512, a, grid, lds, stream);     \
+            }                                                                                                  \
+    }
+
 using FxStem7 = F32StemFixed<2, 2, 7, 7, 2, 2, 3>;
 using FxF32B8W4H4 = F32V4Fixed<8, 4, 4, 64, 16, 3>;
-using FxBf16B64W7H1 = Bf16Fixed<2, 1, 64, 7, 1, 32, 1>;
-using FxBf16B64W2H2 = Bf16Fixed<2, 1, 64, 2, 2, 32, 1>;
 
 static const Variant g_variants[] = {
     // fp32
@@ -2892,10 +2883,7 @@ static const Variant g_variants[] = {
     // fixed-geometry kernels (3x3 taps, unit strides, shapes the tiles divide exactly)
     CACNN_FX_VARIANT(0, "f32 fx k64 b8w4h4 w2x2 m1n2 c16r3s3", 4.8f, 5.5f, 2, 2, 1, 2, 8, 4, 4, -4, 16, 3, FxF32B8W4H4,
                      conv_f32v4_fx_kernel<2, 2, 1, 2, 8, 4, 4, 16, 3>),
-    CACNN_FX_VARIANT(1, "bf16 fx k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.16f, 8.0f, 2, 2, 1, 7, 64, 7, 1, 3, 32, 1, FxBf16B64W7H1,
-                     conv_bf16_fx_kernel<2, 1, 64, 7, 1, 32, 1>),
-    CACNN_FX_VARIANT(1, "bf16 fx k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.86f, 4.0f, 2, 2, 1, 4, 64, 2, 2, 3, 32, 1, FxBf16B64W2H2,
-                     conv_bf16_fx_kernel<2, 1, 64, 2, 2, 32, 1>),
+    CACNN_F32_DIRECT_VARIANT("f32 fxd k64 b8w4h4 w2x2 m1n2 c16r3s3", 4.2f, 4.5f, 4, 4),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 0.9f, 8.0f, 7, 1),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.6f, 4.0f, 2, 2),
     // fixed geometry for the stem-layer shape: 7x7 taps, strides 2, three channels
