@@ -1749,14 +1749,19 @@ __global__ void __launch_bounds__(WM* WN * 128) conv_f32v4_ws_kernel(const Kerne
 }
 
 // ---- fixed-geometry kernels ("fx") ---------------------------------------------------------------------------------
-// Measured on MI355X: a vector-ALU instruction or an LDS read issued by the wave that also issues the MFMAs is not
-// hidden behind a running MFMA (each costs the matrix pipe 6-10 cycles); the same work in another wave of the SIMD
-// is hidden, but an fp32 MFMA stream leaves that other wave only about one vector instruction per MFMA.  So the
-// multiplying waves must carry no address arithmetic at all and the staging waves very little.
-// With the contraction tile (c-slice, b_r = 3, b_s), unit strides and a shape that the tiles divide exactly, all of it
-// is known at compile time: every LDS address of a unit is one per-lane base register plus an immediate offset, a
-// unit is straight-line code (reads and MFMAs only), and a staging item is two registers (global offset, LDS address).
-// The layout constants repeat the host's formulas; the launcher refuses a geometry that differs.
+// Measured on MI355X:
+//  * LDS reads interleaved one to one with independent MFMAs in the same wave cost about one cycle each (a
+//    register-only loop runs 32.2 cycles per bf16 32x32x16 MFMA, 33.0-33.4 with 12-21 reads per 21 MFMAs), provided
+//    the wave never has to wait for one: everything a unit needs is a per-lane base register plus an immediate.
+//  * A second wave on the SIMD gets few issue slots next to an MFMA stream (about one instruction per 11 cycles next
+//    to bf16 MFMAs, next to fp32 MFMAs hardly any until the multiplying wave waits at the barrier), vector-ALU
+//    instructions least of all.  Staging waves must therefore issue very little and no vector arithmetic in their
+//    steady state: addresses are precomputed, the unit walk is scalar.
+//  * Under an all-CU bf16 MFMA load the clock is power-managed (about 1.5-1.8 GHz on operands with the workloads'
+//    value mix, 2.2-2.4 GHz on zeros): cycles saved beyond that point come back as a lower clock.
+// With the contraction tile (c-slice, b_r = 3, b_s), unit strides and a shape that the tiles divide exactly, all
+// addressing is known at compile time and a unit is straight-line code (reads and MFMAs only).
+// The layout constants are the kernels' own; the launcher refuses a launch whose geometry differs.
 
 // Out words of one 32x32 accumulator block of a tile that lies wholly inside Out: every address is a wave-uniform base
 // (scalar arithmetic) plus the lane's constant 32-bit offset, which holds the lane's row group q*4*kstride and its
@@ -1800,8 +1805,11 @@ struct FxWalk {
     }
     __device__ __forceinline__ bool valid(const KernelArgs& a) const { return t < a.n_tiles; }
     static __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* base, int64_t off, int64_t total) {
+        // in 32-bit pieces: a 64-bit compare is a vector instruction, and next to an MFMA stream the staging waves
+        // hardly ever get the vector issue port
         const uint64_t left = (uint64_t)(total - off);
-        const int32_t n = (left >> 31) ? 0x7fffffff : (int32_t)left;
+        const uint32_t lo = (uint32_t)left, hi = (uint32_t)(left >> 32);
+        const int32_t n = (hi | (lo >> 31)) ? 0x7fffffff : (int32_t)lo;
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>((const char*)base + off), 0, n, 0x00020000);
     }
     __device__ __forceinline__ __amdgpu_buffer_rsrc_t img(const KernelArgs& a) const {
@@ -1823,222 +1831,6 @@ struct FxWalk {
         }
     }
 };
-
-template <int TB, int TW, int TH, int KT, int CT, int BS>
-struct F32V4Fixed {
-    static constexpr int BR = 3;
-    static constexpr int XS = TW + BR - 1, YS = TH - 1 + BS;
-    static constexpr int G = CT / 4, VPR = TB / 4;
-    static constexpr int YP = G * TB;
-    static constexpr int xpitch() {
-        int base = YS * YP, pad = 0;
-        if (TB < 32) {
-            const int want = TB >= 16 ? 2 : 1;
-            while (((base + pad) & 7) != want) ++pad;
-        }
-        return base + pad;
-    }
-    static constexpr int XP = xpitch();
-    static constexpr int Q = BS * CT, QE = (Q + 7) / 8 * 8, G8 = QE / 8, Q4 = QE / 4;
-    static constexpr int F4 = (BR * QE / 4) | 1;
-    static constexpr int GROUPS = BR * G8;
-    static constexpr int IMG_BUF = XS * XP, ZERO_OFF = 2 * IMG_BUF, FLT_OFF = ZERO_OFF + 32, FLT_BUF = KT * F4;
-    static constexpr int PT = 256;      // staging threads
-    static constexpr int IMG_ITEMS = XS * YS * G * VPR, FLT_ITEMS = KT * BR * BS * G;
-    static constexpr int MAXI = (IMG_ITEMS + PT - 1) / PT, MAXF = (FLT_ITEMS + PT - 1) / PT;
-    static_assert(Q % 8 == 0, "fixed fp32 geometry: b_s * c-slice must be a multiple of 8");
-    static_assert(GROUPS % 2 == 0, "fixed fp32 geometry: an even number of fragment groups per unit");
-    static_assert(VPR <= 2, "fixed fp32 geometry: no store swizzle, so at most 8 images per tile row");
-    static_assert(16 * IMG_BUF < 65536 && 16 * FLT_BUF < 65536, "LDS offsets must fit the 16-bit immediate");
-    static bool matches_host(const KernelArgs& a) {
-        return a.sw == 1 && a.sh == 1 && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
-               a.xpitch == XP && a.ypitch == YP && a.QE == QE && a.fpitch == 4 * F4 && a.img_buf == IMG_BUF &&
-               a.flt_off == FLT_OFF && a.flt_buf == FLT_BUF && !a.flt_resident && a.R == BR && a.S % BS == 0 &&
-               a.C % CT == 0 && a.B % TB == 0 && a.W % TW == 0 && a.H % TH == 0 && a.K % KT == 0 && a.vec_img &&
-               a.vec_flt;
-    }
-};
-
-// Staging half of the fixed fp32 kernel.  Image and Filter words are fetched two units ahead into two register sets.
-template <class GEO, int TB, int TW, int TH, int KT, int CT, int BS>
-__device__ __forceinline__ void f32v4_fx_producer(const KernelArgs& a, f32x4* smem_v, int stid) {
-    constexpr int MAXI = GEO::MAXI, MAXF = GEO::MAXF, PT = GEO::PT;
-    char* const lds = (char*)smem_v;
-    uint32_t ig[MAXI], il[MAXI], fg[MAXF], fl[2][MAXF];
-    const uint32_t row_bytes = (uint32_t)a.B * 4u;
-#pragma unroll
-    for (int i = 0; i < MAXI; ++i) {
-        int idx = stid + i * PT;
-        if (idx >= GEO::IMG_ITEMS) idx = 0;
-        const int bv = idx % GEO::VPR, t = idx / GEO::VPR;
-        const int x = t % GEO::XS, gq = t / GEO::XS;      // x is the faster index: neighbouring lanes, different banks
-        const int c4 = gq % GEO::G, y = gq / GEO::G;
-        il[i] = (uint32_t)(x * GEO::XP + y * GEO::YP + c4 * TB + bv * 4) * 16u;
-        ig[i] = ((((uint32_t)x * a.IH + y) * a.C + c4 * 4) * a.B + bv * 4) * 4u;
-    }
-#pragma unroll
-    for (int i = 0; i < MAXF; ++i) {
-        int idx = stid + i * PT;
-        if (idx >= GEO::FLT_ITEMS) idx = 0;
-        const int c = (idx % GEO::G) * 4, t = idx / GEO::G;
-        const int sl = t % BS, t2 = t / BS;
-        const int r = t2 % GEO::BR, kl = t2 / GEO::BR;
-        fl[0][i] = (uint32_t)(GEO::FLT_OFF * 4 + kl * GEO::F4 * 4 + r * GEO::QE + sl * CT + c) * 4u;
-        fl[1][i] = fl[0][i] + 16u * GEO::FLT_BUF;
-        fg[i] = ((((uint32_t)kl * a.R + r) * a.S + sl) * a.C + c) * 4u;
-    }
-    if (stid < 32) smem_v[GEO::ZERO_OFF + stid] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    FxWalk<4, KT, TB, TW, TH, CT, BS> lu;     // next unit to fetch
-    lu.init(a);
-    int to_store = 0;                          // units fetched and not yet stored
-    f32x4 ireg[2][MAXI][4], freg[2][MAXF];
-    auto issue = [&](int set) {
-        const __amdgpu_buffer_rsrc_t ri = lu.img(a), rf = lu.flt(a);
-#pragma unroll
-        for (int i = 0; i < MAXI; ++i)
-            if (i * PT + PT <= GEO::IMG_ITEMS || stid < GEO::IMG_ITEMS - i * PT) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) ireg[set][i][e] = buf_load_f32x4(ri, ig[i], e * row_bytes);
-            }
-#pragma unroll
-        for (int i = 0; i < MAXF; ++i)
-            if (i * PT + PT <= GEO::FLT_ITEMS || stid < GEO::FLT_ITEMS - i * PT)
-                freg[set][i] = buf_load_f32x4(rf, fg[i], 0);
-        lu.next(a);
-        ++to_store;
-    };
-    auto store = [&](int set) {   // set is also the LDS buffer
-#pragma unroll
-        for (int i = 0; i < MAXI; ++i)
-            if (i * PT + PT <= GEO::IMG_ITEMS || stid < GEO::IMG_ITEMS - i * PT) {
-#pragma unroll
-                for (int bb = 0; bb < 4; ++bb) {
-                    const f32x4 o = {ireg[set][i][0][bb], ireg[set][i][1][bb], ireg[set][i][2][bb],
-                                     ireg[set][i][3][bb]};
-                    *(f32x4*)(lds + il[i] + 16 * (bb + set * GEO::IMG_BUF)) = o;
-                }
-            }
-#pragma unroll
-        for (int i = 0; i < MAXF; ++i)
-            if (i * PT + PT <= GEO::FLT_ITEMS || stid < GEO::FLT_ITEMS - i * PT)
-                *(f32x4*)(lds + fl[set][i]) = freg[set][i];
-        --to_store;
-    };
-
-#pragma unroll
-    for (int d = 0; d < 2; ++d)
-        if (lu.valid(a)) issue(d);
-    while (to_store > 0) {
-#pragma unroll
-        for (int ph = 0; ph < 2; ++ph) {
-            if (to_store > 0) {
-                store(ph);
-                if (lu.valid(a)) issue(ph);
-                lds_done_then_barrier();
-            }
-        }
-    }
-}
-
-template <int WM, int WN, int MBLK, int NBLK, int TB, int TW, int TH, int CT, int BS>
-__global__ void __launch_bounds__(WM* WN * 64 + 256) conv_f32v4_fx_kernel(const KernelArgs a) {
-    constexpr int KT = WM * MBLK * 32;
-    using GEO = F32V4Fixed<TB, TW, TH, KT, CT, BS>;
-    constexpr int CTHREADS = WM * WN * 64;
-    extern __shared__ __align__(16) f32x4 smem_v[];
-    const int tid = threadIdx.x;
-    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
-
-    if (wave_id >= WM * WN) {
-        f32v4_fx_producer<GEO, TB, TW, TH, KT, CT, BS>(a, smem_v, tid - CTHREADS);
-    } else {
-        const int lane = tid & 63, wave = wave_id;
-        const int wm = wave % WM, wn = wave / WM;
-        const int j = lane & 31, kk = lane >> 5;
-        int posoff[NBLK];
-        f32v4_posoff<NBLK, TB, TW, TH>(a, posoff, wn * NBLK, j, kk);
-        f32x16 acc[MBLK][NBLK];
-        zero_acc(acc);
-        // per-lane bases of the two LDS buffers; everything else in a unit is an immediate offset
-        const f32x4* ap[2];
-        const f32x4* bp[2][NBLK];
-#pragma unroll
-        for (int buf = 0; buf < 2; ++buf) {
-            ap[buf] = smem_v + GEO::FLT_OFF + buf * GEO::FLT_BUF + (wm * MBLK * 32 + j) * GEO::F4 + kk;
-#pragma unroll
-            for (int n = 0; n < NBLK; ++n) bp[buf][n] = smem_v + buf * GEO::IMG_BUF + posoff[n];
-        }
-        f32x4 av[2][MBLK], bv[2][NBLK];
-        auto load_group = [&](int buf, int g, int set) {
-            const int r = g / GEO::G8, t = g % GEO::G8;
-#pragma unroll
-            for (int m = 0; m < MBLK; ++m)
-                av[set][m] = ap[buf][m * 32 * GEO::F4 + r * GEO::Q4 + 2 * t];
-#pragma unroll
-            for (int n = 0; n < NBLK; ++n) bv[set][n] = bp[buf][n][r * GEO::XP + 2 * t * TB];
-        };
-        auto mfma_group = [&](int set) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-#pragma unroll
-                for (int m = 0; m < MBLK; ++m)
-#pragma unroll
-                    for (int n = 0; n < NBLK; ++n)
-                        acc[m][n] =
-                            __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][m][e], bv[set][n][e], acc[m][n], 0, 0, 0);
-        };
-
-        const int64_t out_kstride = (int64_t)a.H * a.W * a.B;      // floats between output channels
-        const uint32_t out_lane = (uint32_t)(kk * 4) * (uint32_t)out_kstride + (uint32_t)((j / TB) * a.B + j % TB);
-        UnitPos cur = first_unit(a, KT, TB, TW, TH);
-        UnitPos nxt = cur;
-        bool have = cur.t < a.n_tiles;
-        if (have) {
-            advance_unit(a, nxt, KT, TB, TW, TH);
-            lds_done_then_barrier();        // unit 0 is staged
-            load_group(0, 0, 0);
-        }
-        while (have) {
-#pragma unroll
-            for (int buf = 0; buf < 2; ++buf) {
-                if (have) {
-                    const bool have_next = nxt.t < a.n_tiles;
-#pragma unroll
-                    for (int g = 0; g < GEO::GROUPS; ++g) {
-                        if (g + 1 < GEO::GROUPS) {
-                            load_group(buf, g + 1, (g + 1) & 1);
-                        } else if (have_next) {
-                            // the last fragments of this unit are on their way: once they have landed the buffer is
-                            // free for the staging waves, and the first fragments of the next unit are read under
-                            // this group's MFMAs (the staging waves execute one barrier per unit, so the last unit
-                            // has none to meet)
-                            lds_done_then_barrier();
-                            load_group(buf ^ 1, 0, 0);
-                        }
-                        mfma_group(g & 1);
-                        interleave_hint<4 * MBLK * NBLK, MBLK + NBLK>();
-                    }
-                    if (!have_next || nxt.t != cur.t) {
-                        // one block of 32 columns is one output row of the tile (TB * TW = 32)
-                        static_assert(TB * TW == 32, "fixed fp32 kernel: a column block is one tile row");
-#pragma unroll
-                        for (int n = 0; n < NBLK; ++n)
-#pragma unroll
-                            for (int m = 0; m < MBLK; ++m) {
-                                float* const blk = a.out + ((((int64_t)(cur.tc.k0 + (wm * MBLK + m) * 32) * a.H +
-                                                              cur.tc.h0 + wn * NBLK + n) * a.W + cur.tc.w0) * a.B + cur.tc.b0);
-                                store_block_exact<false>(blk, out_kstride, out_lane, acc[m][n]);
-                            }
-                    }
-                    cur = nxt;
-                    have = have_next;
-                    if (have_next) advance_unit(a, nxt, KT, TB, TW, TH);
-                }
-            }
-        }
-    }
-}
 
 // ---- fixed geometry, bf16, Image loaded straight into LDS ---------------------------------------------------------------
 // A kernel that staged the Image through registers (8 loads, a 8x8 transpose of 16-bit words and 8 LDS stores per
@@ -2130,7 +1922,7 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
 #pragma unroll
         for (int i = 0; i < CPW; ++i)
             isoff[i] = (uint32_t)(((i / YS) * a.IH + (i % YS)) * a.C + pw * 8) * row_bytes;
-        uint32_t fg[MAXF], fl[MAXF];
+        uint32_t fg[MAXF], fl[MAXF], fl2[MAXF];
 #pragma unroll
         for (int i = 0; i < MAXF; ++i) {
             const int idx = stid + i * PT;
@@ -2138,6 +1930,7 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
             const int rs = t % (BR * BS), kl = t / (BR * BS);
             const int r = rs / BS, sl = rs % BS;
             fl[i] = (uint32_t)(uintptr_t)(lds + GEO::IMG_BYTES + (kl * F8 + rs * C8 + c8) * 16);
+            fl2[i] = fl[i] + 2 * BUF;
             fg[i] = ((((uint32_t)kl * a.R + r) * a.S + sl) * a.C + c8 * 8) * 2u;
         }
         FxWalk<2, KT, TB, TW, TH, CT, BS> lu;     // next unit to fetch
@@ -2161,9 +1954,22 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
         // younger loads are outstanding (loads complete in order)
         auto announce = [&](int set, auto later) {
             __builtin_amdgcn_s_waitcnt(vmcnt_only(decltype(later)::value));
+            // the buffer offset goes into the instruction (the third buffer is beyond the 16-bit field: second base
+            // register), chosen by a scalar branch: a vector add here would wait for the vector issue port, which
+            // the MFMA stream of the SIMD's other wave hardly ever leaves free
+            if (boff_store == 0) {
 #pragma unroll
-            for (int i = 0; i < MAXF; ++i)
-                asm volatile("ds_write_b128 %0, %1" ::"v"(fl[i] + (uint32_t)boff_store), "v"(freg[set][i]) : "memory");
+                for (int i = 0; i < MAXF; ++i)
+                    asm volatile("ds_write_b128 %0, %1" ::"v"(fl[i]), "v"(freg[set][i]) : "memory");
+            } else if (boff_store == BUF) {
+#pragma unroll
+                for (int i = 0; i < MAXF; ++i)
+                    asm volatile("ds_write_b128 %0, %1 offset:%2" ::"v"(fl[i]), "v"(freg[set][i]), "n"(BUF) : "memory");
+            } else {
+#pragma unroll
+                for (int i = 0; i < MAXF; ++i)
+                    asm volatile("ds_write_b128 %0, %1" ::"v"(fl2[i]), "v"(freg[set][i]) : "memory");
+            }
             lds_done_then_barrier();
             boff_store = boff_store + BUF == GEO::NBUF * BUF ? 0 : boff_store + BUF;
         };
@@ -2276,8 +2082,8 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
 
 // ---- fixed geometry, fp32, Image loaded straight into LDS -------------------------------------------------------------
 // The same staging for fp32 tiles of 8 images x 4 x 4 output positions.  Next to an fp32 MFMA stream a staging wave
-// gets even fewer issue slots than next to a bf16 one, and the register-staged kernel above was measured with its
-// staging waves arriving at the barrier as late as the multiplying ones.  An fp32 MFMA takes one word per lane and
+// gets even fewer issue slots than next to a bf16 one, and a register-staged kernel was measured with its staging
+// waves arriving at the barrier as late as the multiplying ones.  An fp32 MFMA takes one word per lane and
 // operand, so nothing has to be transposed: the Image keeps its global order in LDS, [x][y][c][b] with the tile's 8
 // images fastest (32-byte rows, 512 bytes per position, one x plane = 6 positions + 32 bytes of padding so that the four
 // output columns of an MFMA column block fall into different banks), and lane (column j, contraction half g) reads
@@ -2346,21 +2152,21 @@ __global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a
             isoff[i] = (uint32_t)((x * a.IH + 2 * yy) * a.C) * row_bytes;
             ildst[i] = (uint32_t)(x * XP + yy * 2 * POS);
         }
-        uint32_t fg[MAXF], fl[MAXF];
+        uint32_t fg[MAXF], fl[2][MAXF];
 #pragma unroll
         for (int i = 0; i < MAXF; ++i) {
             const int idx = stid + i * PT;
             const int c4 = idx % (CT / 4), t = idx / (CT / 4);
             const int rs = t % (BR * BS), kl = t / (BR * BS);
             const int r = rs / BS, sl = rs % BS;
-            fl[i] = (uint32_t)(uintptr_t)(lds + GEO::FLT_OFF + kl * FP + (rs * CT + c4 * 4) * 4);
+            fl[0][i] = (uint32_t)(uintptr_t)(lds + GEO::FLT_OFF + kl * FP + (rs * CT + c4 * 4) * 4);
+            fl[1][i] = fl[0][i] + FBUF;
             fg[i] = ((((uint32_t)kl * a.R + r) * a.S + sl) * a.C + c4 * 4) * 4u;
         }
         FxWalk<4, KT, TB, TW, TH, CT, BS> lu;     // next unit to fetch
         lu.init(a);
         f32x4 freg[2][MAXF];
         int ioff_issue = 0;                       // Image buffer the next fetch goes to
-        int foff_store = 0;                       // Filter buffer of the next announced unit
         auto issue = [&](int set) {
             const __amdgpu_buffer_rsrc_t ri = lu.img(a), rf = lu.flt(a);
 #pragma unroll
@@ -2370,15 +2176,15 @@ __global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a
             lu.next(a);
             ioff_issue = ioff_issue + IBUF == GEO::NBUF_I * IBUF ? 0 : ioff_issue + IBUF;
         };
-        // announce the unit whose Filter words are in register set `set`: its loads are in once at most `later`
-        // younger loads are outstanding (loads complete in order)
+        // announce the unit whose Filter words are in register set `set` (also its Filter buffer): its loads are in
+        // once at most `later` younger loads are outstanding (loads complete in order).  No vector-ALU instruction
+        // on this path: next to an fp32 MFMA stream a staging wave practically never gets that issue port.
         auto announce = [&](int set, auto later) {
             __builtin_amdgcn_s_waitcnt(vmcnt_only(decltype(later)::value));
 #pragma unroll
             for (int i = 0; i < MAXF; ++i)
-                asm volatile("ds_write_b128 %0, %1" ::"v"(fl[i] + (uint32_t)foff_store), "v"(freg[set][i]) : "memory");
+                asm volatile("ds_write_b128 %0, %1" ::"v"(fl[set][i]), "v"(freg[set][i]) : "memory");
             lds_done_then_barrier();
-            foff_store = FBUF - foff_store;
         };
         using NextUnit = std::integral_constant<int, GEO::LOADS>;
         using Nothing = std::integral_constant<int, 0>;
@@ -2791,18 +2597,6 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
-// fixed-geometry variants: GEO is the geometry class whose constants the launch must match
-#define CACNN_FX_VARIANT(DT, NAME, UNIT_US, FIXED_US, WM, WN, MBLK, NBLK, TB, TW, TH, BR, FXCT, FXBS, GEO, ...) \
-    {                                                                                                          \
-        {NAME, DT, WM, WN, MBLK, NBLK, TB, TW, TH, 2, GEO::MAXI, GEO::MAXF, 1, BR, 1.0f, FXCT, 3, FXBS, GEO::YS, 1, 1, 0, \
-         UNIT_US, FIXED_US},                                                                                  \
-            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
-                static bool attr_done = false;                                                                 \
-                if (!GEO::matches_host(a)) return 1;                                                           \
-                return launch_kernel(__VA_ARGS__, attr_done, WM * WN * 64 + 256, a, grid, lds, stream);        \
-            }                                                                                                  \
-    }
-
 // bf16 with the Image loaded straight into LDS: 64 images, 64 output channels, 32-channel slices of one filter row
 #define CACNN_DIRECT_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                                   \
     {                                                                                                          \
@@ -2828,7 +2622,6 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
     }
 
 using FxStem7 = F32StemFixed<2, 2, 7, 7, 2, 2, 3>;
-using FxF32B8W4H4 = F32V4Fixed<8, 4, 4, 64, 16, 3>;
 
 static const Variant g_variants[] = {
     // fp32
@@ -2881,8 +2674,6 @@ static const Variant g_variants[] = {
     CACNN_WS_VARIANT(0, "f32 ws4 k64 b16w4h2 w2x2 m1n2", 1.0f, 2, 2, 1, 2, 16, 4, 2, 3, 10, -4,
                      conv_f32v4_ws_kernel<2, 2, 1, 2, 16, 4, 2, 3, 10>),
     // fixed-geometry kernels (3x3 taps, unit strides, shapes the tiles divide exactly)
-    CACNN_FX_VARIANT(0, "f32 fx k64 b8w4h4 w2x2 m1n2 c16r3s3", 4.8f, 5.5f, 2, 2, 1, 2, 8, 4, 4, -4, 16, 3, FxF32B8W4H4,
-                     conv_f32v4_fx_kernel<2, 2, 1, 2, 8, 4, 4, 16, 3>),
     CACNN_F32_DIRECT_VARIANT("f32 fxd k64 b8w4h4 w2x2 m1n2 c16r3s3", 4.2f, 4.5f, 4, 4),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 0.9f, 8.0f, 7, 1),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.6f, 4.0f, 2, 2),
