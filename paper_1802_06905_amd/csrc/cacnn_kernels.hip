@@ -20,6 +20,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <type_traits>
+#include <utility>
 
 #include "cacnn_internal.h"
 
@@ -1879,6 +1880,18 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 #define CACNN_LDS(T) __attribute__((address_space(3))) T
 
+// 16-byte LDS stores regs[0..N) to addr + BASE + i * STEP, offsets in the instruction.  Assembly: the compiler must not
+// count them among the LDS accesses that wait for outstanding loads into LDS (the operands are still tracked).
+template <int OFF, class V>
+__device__ __forceinline__ void lds_store16_at(uint32_t addr, const V& v) {
+    static_assert(OFF >= 0 && OFF < 65536, "LDS store offset must fit the instruction's 16-bit field");
+    asm volatile("ds_write_b128 %0, %1 offset:%2" ::"v"(addr), "v"(v), "n"(OFF) : "memory");
+}
+template <int BASE, int STEP, class V, size_t... I>
+__device__ __forceinline__ void lds_store16_seq(uint32_t addr, const V* regs, std::index_sequence<I...>) {
+    (lds_store16_at<BASE + (int)I * STEP>(addr, regs[I]), ...);
+}
+
 // s_waitcnt immediate that waits only for the vector-memory counter to drop to n (6 bits: [3:0] and [15:14])
 constexpr int vmcnt_only(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
@@ -1922,17 +1935,17 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
 #pragma unroll
         for (int i = 0; i < CPW; ++i)
             isoff[i] = (uint32_t)(((i / YS) * a.IH + (i % YS)) * a.C + pw * 8) * row_bytes;
-        uint32_t fg[MAXF], fl[MAXF], fl2[MAXF];
+        // Filter: thread (kl = stid / C8, c8 = stid % C8) fetches the 16 bytes of channels 8*c8.. of output channel kl
+        // for every tap (r, s) of the unit: one global offset and one LDS address per thread, the tap in the
+        // instruction (scalar offset of the load, immediate of the store)
+        static_assert(MAXF == BR * BS && PT == KT * C8, "direct bf16 geometry: one Filter item per thread and tap");
+        const int f_c8 = stid % C8, f_kl = stid / C8;
+        const uint32_t fg0 = ((uint32_t)f_kl * a.R * a.S * a.C + f_c8 * 8) * 2u;
+        const uint32_t fl0 = (uint32_t)(uintptr_t)(lds + GEO::IMG_BYTES + (f_kl * F8 + f_c8) * 16);
+        const uint32_t fl2 = fl0 + 2 * BUF;
+        uint32_t fsoff[MAXF];
 #pragma unroll
-        for (int i = 0; i < MAXF; ++i) {
-            const int idx = stid + i * PT;
-            const int c8 = idx % C8, t = idx / C8;
-            const int rs = t % (BR * BS), kl = t / (BR * BS);
-            const int r = rs / BS, sl = rs % BS;
-            fl[i] = (uint32_t)(uintptr_t)(lds + GEO::IMG_BYTES + (kl * F8 + rs * C8 + c8) * 16);
-            fl2[i] = fl[i] + 2 * BUF;
-            fg[i] = ((((uint32_t)kl * a.R + r) * a.S + sl) * a.C + c8 * 8) * 2u;
-        }
+        for (int i = 0; i < MAXF; ++i) fsoff[i] = (uint32_t)((i / BS) * a.S + i % BS) * (uint32_t)a.C * 2u;
         FxWalk<2, KT, TB, TW, TH, CT, BS> lu;     // next unit to fetch
         lu.init(a);
         u32x4 freg[2][MAXF];
@@ -1944,7 +1957,7 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
                 load_16_bytes_per_lane_to_lds(ri, lds + boff_issue + (i * C8 + pw) * 1024, ivoff, isoff[i]);
 #pragma unroll
             for (int i = 0; i < MAXF; ++i) {
-                const uint4 v = buf_load_u4(rf, fg[i], 0);
+                const uint4 v = buf_load_u4(rf, fg0, fsoff[i]);
                 freg[set][i] = u32x4{v.x, v.y, v.z, v.w};
             }
             lu.next(a);
@@ -1957,19 +1970,9 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
             // the buffer offset goes into the instruction (the third buffer is beyond the 16-bit field: second base
             // register), chosen by a scalar branch: a vector add here would wait for the vector issue port, which
             // the MFMA stream of the SIMD's other wave hardly ever leaves free
-            if (boff_store == 0) {
-#pragma unroll
-                for (int i = 0; i < MAXF; ++i)
-                    asm volatile("ds_write_b128 %0, %1" ::"v"(fl[i]), "v"(freg[set][i]) : "memory");
-            } else if (boff_store == BUF) {
-#pragma unroll
-                for (int i = 0; i < MAXF; ++i)
-                    asm volatile("ds_write_b128 %0, %1 offset:%2" ::"v"(fl[i]), "v"(freg[set][i]), "n"(BUF) : "memory");
-            } else {
-#pragma unroll
-                for (int i = 0; i < MAXF; ++i)
-                    asm volatile("ds_write_b128 %0, %1" ::"v"(fl2[i]), "v"(freg[set][i]) : "memory");
-            }
+            if (boff_store == 0) lds_store16_seq<0, C8 * 16>(fl0, freg[set], std::make_index_sequence<MAXF>{});
+            else if (boff_store == BUF) lds_store16_seq<BUF, C8 * 16>(fl0, freg[set], std::make_index_sequence<MAXF>{});
+            else lds_store16_seq<0, C8 * 16>(fl2, freg[set], std::make_index_sequence<MAXF>{});
             lds_done_then_barrier();
             boff_store = boff_store + BUF == GEO::NBUF * BUF ? 0 : boff_store + BUF;
         };
@@ -2152,17 +2155,15 @@ __global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a
             isoff[i] = (uint32_t)((x * a.IH + 2 * yy) * a.C) * row_bytes;
             ildst[i] = (uint32_t)(x * XP + yy * 2 * POS);
         }
-        uint32_t fg[MAXF], fl[2][MAXF];
+        // Filter: thread (kl = stid / 4, c4 = stid % 4) fetches the 16 bytes of channels 4*c4.. of output channel kl for
+        // every tap (r, s) of the unit: one global offset and one LDS address per thread, the tap in the instruction
+        static_assert(MAXF == BR * BS && PT == KT * (CT / 4), "direct fp32 geometry: one Filter item per thread and tap");
+        const int f_c4 = stid % (CT / 4), f_kl = stid / (CT / 4);
+        const uint32_t fg0 = ((uint32_t)f_kl * a.R * a.S * a.C + f_c4 * 4) * 4u;
+        const uint32_t fl0 = (uint32_t)(uintptr_t)(lds + GEO::FLT_OFF + f_kl * FP + f_c4 * 16);
+        uint32_t fsoff[MAXF];
 #pragma unroll
-        for (int i = 0; i < MAXF; ++i) {
-            const int idx = stid + i * PT;
-            const int c4 = idx % (CT / 4), t = idx / (CT / 4);
-            const int rs = t % (BR * BS), kl = t / (BR * BS);
-            const int r = rs / BS, sl = rs % BS;
-            fl[0][i] = (uint32_t)(uintptr_t)(lds + GEO::FLT_OFF + kl * FP + (rs * CT + c4 * 4) * 4);
-            fl[1][i] = fl[0][i] + FBUF;
-            fg[i] = ((((uint32_t)kl * a.R + r) * a.S + sl) * a.C + c4 * 4) * 4u;
-        }
+        for (int i = 0; i < MAXF; ++i) fsoff[i] = (uint32_t)((i / BS) * a.S + i % BS) * (uint32_t)a.C * 4u;
         FxWalk<4, KT, TB, TW, TH, CT, BS> lu;     // next unit to fetch
         lu.init(a);
         f32x4 freg[2][MAXF];
@@ -2172,7 +2173,7 @@ __global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a
 #pragma unroll
             for (int i = 0; i < CPW; ++i) load_16_bytes_per_lane_to_lds(ri, lds + ioff_issue + ildst[i], ivoff, isoff[i]);
 #pragma unroll
-            for (int i = 0; i < MAXF; ++i) freg[set][i] = buf_load_f32x4(rf, fg[i], 0);
+            for (int i = 0; i < MAXF; ++i) freg[set][i] = buf_load_f32x4(rf, fg0, fsoff[i]);
             lu.next(a);
             ioff_issue = ioff_issue + IBUF == GEO::NBUF_I * IBUF ? 0 : ioff_issue + IBUF;
         };
@@ -2181,9 +2182,8 @@ __global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a
         // on this path: next to an fp32 MFMA stream a staging wave practically never gets that issue port.
         auto announce = [&](int set, auto later) {
             __builtin_amdgcn_s_waitcnt(vmcnt_only(decltype(later)::value));
-#pragma unroll
-            for (int i = 0; i < MAXF; ++i)
-                asm volatile("ds_write_b128 %0, %1" ::"v"(fl[set][i]), "v"(freg[set][i]) : "memory");
+            if (set == 0) lds_store16_seq<0, CT * 4>(fl0, freg[0], std::make_index_sequence<MAXF>{});
+            else lds_store16_seq<FBUF, CT * 4>(fl0, freg[1], std::make_index_sequence<MAXF>{});
             lds_done_then_barrier();
         };
         using NextUnit = std::integral_constant<int, GEO::LOADS>;
