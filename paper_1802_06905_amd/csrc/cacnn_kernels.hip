@@ -2539,6 +2539,198 @@ __global__ void __launch_bounds__(512) conv_f32_stem_kernel(const KernelArgs a) 
     }
 }
 
+// ---- the stem-layer shape with the Image loaded straight into LDS ------------------------------------------------------
+// 7x7 taps, strides 2, three channels, 32 images per tile.  The Image keeps its global order in LDS: one x plane is the
+// run of (y, c) rows of the tile's 32 images (128 bytes each, 27 rows for a tile two output rows high), so the
+// contraction over (s, c) for a fixed r is a walk down consecutive rows: row 6*h_l + q, q = 3 s + c = 0..20.  An fp32
+// MFMA takes two contraction indices, one per half-wave: the halves take q and q + 11 (a constant 11 rows apart, so it
+// sits in the lane's base register), 11 MFMAs per filter column r and 77 per 32x32 block where the unpadded
+// contraction needs 73.5 (q = 21 does not exist: the Filter holds 0 there and the lanes that would pair it with the
+// row below the window supply 0 as well, so no 0 * NaN can occur).  Planes are 4 KiB apart: a plane is 216 16-byte
+// pieces, moved by four loads of 64 lanes, and the lanes beyond the last piece fetch it again into the padding.
+// Filter in LDS: [k][r][22] words, rows of 155 words (odd: the 32 rows of an operand hit 32 banks).  It is staged
+// once per workgroup and k-tile.  Three Image buffers, loads two tiles ahead; a tile is one unit.
+template <int TW, int TH>
+struct F32StemDirect {
+    static constexpr int R = 7, S = 7, SW = 2, SH = 2, C = 3, TB = 32, KT = 64, WM = 2, WN = 2, NBLK = TW * TH / WN;
+    static constexpr int XS = SW * (TW - 1) + R, YS = SH * (TH - 1) + S;
+    static constexpr int ROWB = TB * 4;                           // bytes of one (y, c) row
+    static constexpr int PIECES = YS * C * ROWB / 16;             // 16-byte pieces of one x plane
+    static constexpr int XPB = 4096, PARTS = XPB / 1024;          // plane pitch; 1 KiB loads per plane
+    static constexpr int Q = S * C, QH = (Q + 1) / 2, QP = 2 * QH; // 21 contraction indices per r, 11 per half-wave, 22 slots
+    static constexpr int IMG_BYTES = XS * XPB, NBUF = 3;
+    static constexpr int FPW = (R * QP) | 1, FLT_BYTES = KT * FPW * 4;
+    static constexpr int FLT_OFF = NBUF * IMG_BYTES, LDS_BYTES = FLT_OFF + FLT_BYTES;
+    static constexpr int PT = 256, PW = PT / 64, CPW = XS;        // staging wave p moves part p of every plane
+    static constexpr int MAXI = 1, MAXF = 1;
+    static constexpr int G0 = (QH + 1) / 2, G1 = QH - G0;         // MFMAs per column block in the two groups of one r
+    static_assert(PARTS == PW && PIECES <= PARTS * 64 && PIECES > (PARTS - 1) * 64, "stem geometry: four loads per plane");
+    static_assert((SH * (TH - 1) * C + QP) * ROWB <= XPB, "stem geometry: the row below the window lies inside the plane's pitch");
+    static_assert((TW * TH) % WN == 0 && 2 * CPW < 64, "stem geometry: column blocks per wave, load counter range");
+    static_assert(IMG_BYTES < 65536 && LDS_BYTES <= 160 * 1024, "stem geometry: LDS offsets and size");
+    static bool matches_host(const KernelArgs& a) {
+        return a.sw == SW && a.sh == SH && a.R == R && a.S == S && a.C == C && a.bR == R && a.bS == S && a.CT == C &&
+               a.B % TB == 0 && a.W % TW == 0 && a.H % TH == 0 && a.K % KT == 0 && a.vec_img;
+    }
+};
+
+template <int TW, int TH>
+__global__ void __launch_bounds__(512) conv_f32_stem_direct_kernel(const KernelArgs a) {
+    using GEO = F32StemDirect<TW, TH>;
+    constexpr int R = GEO::R, S = GEO::S, C = GEO::C, SW = GEO::SW, SH = GEO::SH;
+    constexpr int TB = GEO::TB, KT = GEO::KT, WM = GEO::WM, NBLK = GEO::NBLK, XPB = GEO::XPB, ROWB = GEO::ROWB;
+    constexpr int QH = GEO::QH, QP = GEO::QP, FPW = GEO::FPW, IBUF = GEO::IMG_BYTES;
+    constexpr int CTHREADS = GEO::WM * GEO::WN * 64;
+    extern __shared__ __align__(16) float smem_f[];
+    CACNN_LDS(char)* const lds = (CACNN_LDS(char)*)smem_f;
+    const int tid = threadIdx.x;
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
+    const int lane = tid & 63;
+    int total = 0;                                                  // tiles of this workgroup
+    for (int t = blockIdx.x; t < a.n_tiles; t += gridDim.x) ++total;
+
+    if (wave_id >= GEO::WM * GEO::WN) {
+        const int pw = wave_id - GEO::WM * GEO::WN, stid = tid - CTHREADS;
+        // Image: lane L of staging wave p fetches piece 64 p + L of a plane: row piece / 8 (rows are B words apart in
+        // global memory), 16 bytes (piece % 8) of its 128; lanes beyond the last piece fetch the last one again
+        const int piece = min(pw * 64 + lane, GEO::PIECES - 1);
+        const uint32_t ivoff = (uint32_t)(piece >> 3) * (uint32_t)a.B * 4u + (uint32_t)(piece & 7) * 16u;
+        const uint32_t plane_bytes = (uint32_t)a.IH * a.C * a.B * 4u;
+        FxWalk<4, KT, TB, TW, TH, C, S> lu;     // next tile to fetch
+        lu.init(a);
+        int ioff_issue = 0;
+        auto issue = [&]() {
+            const __amdgpu_buffer_rsrc_t ri = lu.img(a);
+#pragma unroll
+            for (int x = 0; x < GEO::XS; ++x)
+                load_16_bytes_per_lane_to_lds(ri, lds + ioff_issue + x * XPB + pw * 1024, ivoff, (uint32_t)x * plane_bytes);
+            lu.next(a);
+            ioff_issue = ioff_issue + IBUF == GEO::NBUF * IBUF ? 0 : ioff_issue + IBUF;
+        };
+        auto stage_filter = [&](int k0) {
+            // Filter [K][R][S][C] -> LDS [k][r][22], slot 21 zero.  The KT rows of the tile are one contiguous run in
+            // global memory: read it in order (coalesced, all loads of a batch in flight together), scatter into LDS.
+            float* const s_flt = smem_f + GEO::FLT_OFF / 4;
+            constexpr int ROW = R * S * C, TOTAL = KT * ROW, BATCH = 8;
+            const float* src = (const float*)a.filter + (int64_t)k0 * ROW;
+            for (int e0 = 0; e0 < TOTAL; e0 += BATCH * GEO::PT) {
+                float v[BATCH];
+#pragma unroll
+                for (int u = 0; u < BATCH; ++u) {
+                    const int e = e0 + u * GEO::PT + stid;
+                    v[u] = e < TOTAL ? src[e] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < BATCH; ++u) {
+                    const int e = e0 + u * GEO::PT + stid;
+                    if (e < TOTAL) {
+                        const int kl = e / ROW, q = e % ROW;
+                        s_flt[kl * FPW + (q / (S * C)) * QP + q % (S * C)] = v[u];
+                    }
+                }
+            }
+            for (int e = stid; e < KT * R; e += GEO::PT) s_flt[(e / R) * FPW + (e % R) * QP + QP - 1] = 0.f;
+        };
+        int flt_k0 = -1;
+        int st = blockIdx.x;                    // tile about to be announced
+        if (total > 0) issue();
+        if (total > 1) issue();
+        for (int u = 0; u < total; ++u) {
+            const TileCoord tc = decode_tile_index(a, st, KT, TB, TW, TH);
+            if (tc.k0 != flt_k0) {
+                // the Filter tile is single-buffered: wait until the multiplying waves have finished the old one
+                if (flt_k0 >= 0) lds_done_then_barrier();
+                flt_k0 = tc.k0;
+                stage_filter(flt_k0);
+            }
+            // loads complete in order: this tile is in once at most the next tile's loads are outstanding
+            if (u + 1 < total) __builtin_amdgcn_s_waitcnt(vmcnt_only(GEO::CPW));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+            lds_done_then_barrier();
+            if (u + 2 < total) issue();         // the buffer the multiplying waves left two tiles back
+            st += gridDim.x;
+        }
+    } else {
+        const int wm = wave_id % WM, wn = wave_id / WM;
+        const int j = lane & 31, g = lane >> 5;
+        f32x16 acc[1][NBLK];
+        zero_acc(acc);
+        // per-lane LDS offsets: Filter row of output channel wm*32 + j, slots 11 g ..; Image: image j, rows 11 g ..
+        const uint32_t al = (uint32_t)(GEO::FLT_OFF + ((wm * 32 + j) * FPW + g * QH) * 4);
+        static_assert(NBLK == TW, "stem geometry: a wave owns one tile row");
+        const uint32_t xl = (uint32_t)(j * 4 + g * QH * ROWB + wn * SH * C * ROWB);
+        float A[2][GEO::G0], X[2][NBLK][GEO::G0];
+        // group gi = 2 r + half: slots q0 .. q0 + n - 1 of filter column r
+        auto load_group = [&](uint32_t xb, int gi, int set) {
+            const int r = gi >> 1, q0 = (gi & 1) ? GEO::G0 : 0, n = (gi & 1) ? GEO::G1 : GEO::G0;
+#pragma unroll
+            for (int t = 0; t < n; ++t) A[set][t] = *(const CACNN_LDS(float)*)(lds + al + (r * QP + q0 + t) * 4);
+#pragma unroll
+            for (int nb = 0; nb < NBLK; ++nb)       // column block nb of this wave: output column nb of tile row wn
+#pragma unroll
+                for (int t = 0; t < n; ++t)
+                    X[set][nb][t] = *(const CACNN_LDS(float)*)(lds + xb + (r + nb * SW) * XPB + (q0 + t) * ROWB);
+        };
+        auto mfma_group = [&](int gi, int set) {
+            const int n = (gi & 1) ? GEO::G1 : GEO::G0;
+#pragma unroll
+            for (int t = 0; t < n; ++t)
+#pragma unroll
+                for (int nb = 0; nb < NBLK; ++nb) {
+                    float x = X[set][nb][t];
+                    // slot 21 (q = 10 in the upper half-wave) does not exist
+                    if ((gi & 1) && t == n - 1) x = g ? 0.f : x;
+                    acc[0][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[set][t], x, acc[0][nb], 0, 0, 0);
+                }
+        };
+        const int64_t out_kstride = (int64_t)a.H * a.W * a.B;                    // floats between output channels
+        const uint32_t out_lane = (uint32_t)(g * 4) * (uint32_t)out_kstride + j;  // < 2^31: checked by the host
+        int left = total, t = blockIdx.x;
+        uint32_t ioff = 0;
+        TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
+        int flt_k0 = tc.k0;
+        auto unit = [&](auto more) {
+            constexpr bool MORE = decltype(more)::value;
+            TileCoord ntc = tc;
+            if constexpr (MORE) ntc = decode_tile_index(a, t + gridDim.x, KT, TB, TW, TH);
+#pragma unroll
+            for (int gi = 0; gi < 2 * R; ++gi) {
+                if (gi + 1 < 2 * R) {
+                    load_group(xl + ioff, gi + 1, (gi + 1) & 1);
+                } else if constexpr (MORE) {
+                    // every fragment of this tile has been requested: once they have landed the buffer goes back to
+                    // the staging waves, and the first fragments of the next tile are read under this group's MFMAs
+                    if (ntc.k0 != flt_k0) {
+                        lds_done_then_barrier();      // done with the old Filter tile
+                        flt_k0 = ntc.k0;
+                    }
+                    ioff = ioff + IBUF == GEO::NBUF * IBUF ? 0u : ioff + IBUF;
+                    lds_done_then_barrier_known();
+                    load_group(xl + ioff, 0, 0);
+                }
+                mfma_group(gi, gi & 1);
+                if (gi + 1 < 2 * R || MORE) interleave_hint<GEO::G0 * NBLK, GEO::G0 * (NBLK + 1)>();
+            }
+            asm volatile("" ::: "memory");       // keep the reads above where they are
+            // Out tile: block n is output column w_l, row h_l; a lane owns image j
+#pragma unroll
+            for (int nb = 0; nb < NBLK; ++nb) {
+                float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + tc.h0 + wn) * a.W + tc.w0 + nb) * a.B + tc.b0);
+                store_block_exact<true>(blk, out_kstride, out_lane, acc[0][nb]);
+            }
+            --left;
+            t += gridDim.x;
+            tc = ntc;
+        };
+        if (left > 0) {
+            lds_done_then_barrier_known();      // tile 0 and the Filter tile are staged
+            load_group(xl, 0, 0);
+            while (left > 1) unit(std::true_type{});
+            unit(std::false_type{});
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------------
 // launch table
 
@@ -2684,6 +2876,13 @@ static const Variant g_variants[] = {
          static bool attr_done = false;
          if (!FxStem7::matches_host(a) || lds != (size_t)FxStem7::LDS_BYTES) return 1;
          return launch_kernel(conv_f32_stem_kernel<2, 2, 7, 7, 2, 2, 3>, attr_done, 512, a, grid, lds, stream);
+     }},
+    {{"f32 fxsd k64 b32w2h2 w2x2 m1n2 c3r7s7 s2", 0, 2, 2, 1, F32StemDirect<2, 2>::NBLK, 32, 2, 2, 2, 1, 1, 1, 0, 1.0f, 3, 7, 7,
+      F32StemDirect<2, 2>::YS, 2, 2, F32StemDirect<2, 2>::LDS_BYTES, 5.0f, 5.0f, 1},
+     [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {
+         static bool attr_done = false;
+         if (!F32StemDirect<2, 2>::matches_host(a) || lds != (size_t)F32StemDirect<2, 2>::LDS_BYTES) return 1;
+         return launch_kernel(conv_f32_stem_direct_kernel<2, 2>, attr_done, 512, a, grid, lds, stream);
      }},
     // wave-specialised, bf16
     CACNN_WS_VARIANT(1, "bf16 ws k128 b32w2h2 w2x2 m2n2", 1.05f, 2, 2, 2, 2, 32, 2, 2, 1, 9, 0,
