@@ -2286,261 +2286,9 @@ __global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a
     }
 }
 
-// ---- fixed geometry, large strided filter, few channels (the stem-layer shape) --------------------------------------
-// With C = 3 the 16-byte fragments of the kernels above would be mostly padding.  Here the four consecutive
-// contraction indices of a fragment are four filter-row offsets s (padded from S = 7 to 8) of one (r, c):
-// LDS Image [x][c][b][y] with y fastest (YPAD rows per image, XCP floats per (x, c) plane), so a lane's fragment for output row h and tap group kk is the 16 bytes at
-// y = sigma_h*h + 4*kk (read as two 8-byte halves: the address is only 8-byte aligned for odd h), and LDS Filter
-// [k][r][c][s8].  The whole contraction of a tile is one unit; the Filter tile is staged once per workgroup.
-// One zero word per fragment pair is needed: tap s = 7 does not exist, the Filter holds 0 there, and the lanes
-// that would multiply it by the Image row beyond the window supply 0 as well (0 * NaN must not happen).
-template <int TW, int TH, int R, int S, int SW, int SH, int C>
-struct F32StemFixed {
-    static constexpr int TB = 32, KT = 64, WM = 2, WN = 2, NBLK = TW * TH / WN;
-    static constexpr int XS = SW * (TW - 1) + R, YS = SH * (TH - 1) + S;
-    static constexpr int YPAD = SH * (TH - 1) + 8;          // rows a fragment can touch: s runs to 7
-    static constexpr int XCP = TB * YPAD + 2;               // floats per (x, c) plane; +2 spreads the staging stores over the banks
-    static constexpr int IMG_BUF = XS * C * XCP;            // floats
-    static constexpr int FQ = (R * C * 2) | 1;              // Filter row in 16-byte units, odd: conflict-free
-    static constexpr int FLT_OFF = 2 * IMG_BUF;             // floats
-    static constexpr int LDS_BYTES = 4 * FLT_OFF + 16 * KT * FQ;
-    static constexpr int PT = 256;
-    static constexpr int IMG_ITEMS = XS * C * (TB / 4);
-    static constexpr int MAXI = 1, MAXF = 1;
-    static_assert(S == 7 && YS <= YPAD && YPAD % 2 == 0 && (SH * (TH - 1)) % 2 == 0, "stem geometry: 7 taps padded to 8");
-    static_assert((TW * TH) % WN == 0 && IMG_ITEMS <= PT, "stem geometry: one staging item per thread");
-    static_assert(4 * IMG_BUF < 65536 && 16 * 32 * FQ < 65536, "LDS offsets must fit the 16-bit immediate");
-    static bool matches_host(const KernelArgs& a) {
-        return a.sw == SW && a.sh == SH && a.R == R && a.S == S && a.C == C && a.bR == R && a.bS == S && a.CT == C &&
-               a.B % TB == 0 && a.W % TW == 0 && a.H % TH == 0 && a.K % KT == 0 && a.vec_img;
-    }
-};
-
-template <int TW, int TH, int R, int S, int SW, int SH, int C>
-__global__ void __launch_bounds__(512) conv_f32_stem_kernel(const KernelArgs a) {
-    using GEO = F32StemFixed<TW, TH, R, S, SW, SH, C>;
-    constexpr int TB = GEO::TB, KT = GEO::KT, WM = GEO::WM, WN = GEO::WN, NBLK = GEO::NBLK, YPAD = GEO::YPAD;
-    constexpr int CTHREADS = WM * WN * 64;
-    extern __shared__ __align__(16) float smem_f[];
-    const int tid = threadIdx.x;
-    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
-
-    if (wave_id >= WM * WN) {
-        const int stid = tid - CTHREADS;
-        // ---- once per workgroup: the Filter tile, LDS [k][r][c][s8] (K = KT is not required: k-tile of the first
-        // tile is used for all, the tile order keeps a workgroup inside one k-tile only if tiles_k == 1, so the
-        // Filter tile is restaged whenever the k-tile changes)
-        FxWalk<4, KT, TB, TW, TH, C, S> lu;
-        lu.init(a);
-        int to_store = 0;
-        // Image item of this thread: (x, c, 4 images), rows y = 0 .. YS-1
-        const bool active = stid < GEO::IMG_ITEMS;
-        const int idx = active ? stid : 0;
-        const int bq = idx % (TB / 4), t = idx / (TB / 4);
-        const int c = t % C, x = t / C;
-        const uint32_t ig = (((uint32_t)x * a.IH * a.C + c) * a.B + bq * 4) * 4u;
-        const uint32_t row_bytes = (uint32_t)a.C * a.B * 4u;
-        const uint32_t il = (uint32_t)((x * C + c) * GEO::XCP + bq * 4 * YPAD) * 4u;
-        char* const lds = (char*)smem_f;
-        // rows beyond the window (y >= YS) are only ever multiplied by 0, and must hold 0 themselves
-        if (active) {
-#pragma unroll
-            for (int buf = 0; buf < 2; ++buf)
-#pragma unroll
-                for (int b = 0; b < 4; ++b)
-#pragma unroll
-                    for (int y = GEO::YS; y < YPAD; ++y)
-                        *(float*)(lds + il + 4 * (buf * GEO::IMG_BUF + b * YPAD + y)) = 0.f;
-        }
-        f32x4 ireg[2][GEO::YS];
-        int flt_k0 = -1;
-        auto issue = [&](int set) {
-            const __amdgpu_buffer_rsrc_t ri = lu.img(a);
-            if (active) {
-#pragma unroll
-                for (int y = 0; y < GEO::YS; ++y) ireg[set][y] = buf_load_f32x4(ri, ig, y * row_bytes);
-            }
-            lu.next(a);
-            ++to_store;
-        };
-        auto store = [&](int set) {
-            if (active) {
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    float* dst = (float*)(lds + il + 4 * (set * GEO::IMG_BUF + b * YPAD));
-#pragma unroll
-                    for (int y = 0; y < GEO::YS; ++y) dst[y] = ireg[set][y][b];
-                }
-            }
-            --to_store;
-        };
-        auto stage_filter = [&](int k0) {
-            // Filter [K][R][S][C] -> LDS [k][r][c][s8], s = 7 zero.  The KT rows of the tile are one contiguous run in
-            // global memory: read it in order (coalesced, all loads of a batch in flight together), scatter into LDS.
-            float* s_flt = smem_f + GEO::FLT_OFF;
-            constexpr int ROW = R * S * C, TOTAL = KT * ROW, BATCH = 8;
-            const float* src = (const float*)a.filter + (int64_t)k0 * ROW;
-            for (int e0 = 0; e0 < TOTAL; e0 += BATCH * GEO::PT) {
-                float v[BATCH];
-#pragma unroll
-                for (int u = 0; u < BATCH; ++u) {
-                    const int e = e0 + u * GEO::PT + stid;
-                    v[u] = e < TOTAL ? src[e] : 0.f;
-                }
-#pragma unroll
-                for (int u = 0; u < BATCH; ++u) {
-                    const int e = e0 + u * GEO::PT + stid;
-                    if (e < TOTAL) {
-                        const int kl = e / ROW, q = e % ROW;
-                        const int r = q / (S * C), sc = q % (S * C);
-                        const int sl = sc / C, cc = sc % C;
-                        s_flt[kl * GEO::FQ * 4 + (r * C + cc) * 8 + sl] = v[u];
-                    }
-                }
-            }
-            for (int e = stid; e < KT * R * C; e += GEO::PT)
-                s_flt[(e / (R * C)) * GEO::FQ * 4 + (e % (R * C)) * 8 + 7] = 0.f;
-        };
-        // tile sequence of this workgroup, as the consumers walk it
-        UnitPos su = first_unit(a, KT, TB, TW, TH);
-#pragma unroll
-        for (int d = 0; d < 2; ++d)
-            if (lu.valid(a)) issue(d);
-        while (to_store > 0) {
-#pragma unroll
-            for (int ph = 0; ph < 2; ++ph) {
-                if (to_store > 0) {
-                    if (su.tc.k0 != flt_k0) {
-                        // the consumers are between tiles of different k-tiles only at a barrier; the Filter tile
-                        // is single-buffered, so hand over in two steps: wait until they have finished the old one
-                        if (flt_k0 >= 0) lds_done_then_barrier();
-                        flt_k0 = su.tc.k0;
-                        stage_filter(flt_k0);
-                    }
-                    store(ph);
-                    if (lu.valid(a)) issue(ph);
-                    lds_done_then_barrier();
-                    su.t += gridDim.x;
-                    if (su.t < a.n_tiles) su.tc = decode_tile_index(a, su.t, KT, TB, TW, TH);
-                }
-            }
-        }
-    } else {
-        const int lane = tid & 63, wave = wave_id;
-        const int wm = wave % WM, wn = wave / WM;
-        const int j = lane & 31, kk = lane >> 5;
-        f32x16 acc[NBLK];
-#pragma unroll
-        for (int n = 0; n < NBLK; ++n)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
-        const char* const lds = (const char*)smem_f;
-        const char* const ap = lds + 4 * GEO::FLT_OFF + ((wm * 32 + j) * GEO::FQ + kk) * 16;
-        // one base register per (x, c) plane and buffer: the 8-byte pair reads reach only 2 KB past their base
-        uint32_t plane[2][GEO::XS * C];
-#pragma unroll
-        for (int buf = 0; buf < 2; ++buf)
-#pragma unroll
-            for (int pl = 0; pl < GEO::XS * C; ++pl) {
-                plane[buf][pl] = 4u * (uint32_t)(buf * GEO::IMG_BUF + pl * GEO::XCP + j * YPAD + 4 * kk);
-                asm volatile("" : "+v"(plane[buf][pl]));     // keep it in its register, do not re-derive it per read
-            }
-        typedef float f32x2 __attribute__((ext_vector_type(2)));
-
-        const int64_t out_kstride = (int64_t)a.H * a.W * a.B;                    // floats between output channels
-        const uint32_t out_lane = (uint32_t)(kk * 4) * (uint32_t)out_kstride + j;  // < 2^31: checked by the host
-        f32x4 av[2];
-        f32x2 blo[2][NBLK], bhi[2][NBLK];
-        auto load_rc = [&](int buf, int rc, int set) {
-            const int r = rc / C, cc = rc % C;
-            av[set] = *(const f32x4*)(ap + rc * 32);
-#pragma unroll
-            for (int n = 0; n < NBLK; ++n) {
-                const int nn = wn * NBLK + n, w_l = nn % TW, h_l = nn / TW;
-                const char* src = lds + plane[buf][(SW * w_l + r) * C + cc] + 4 * SH * h_l;
-                blo[set][n] = *(const f32x2*)(src);
-                bhi[set][n] = *(const f32x2*)(src + 8);
-            }
-        };
-        auto mfma_rc = [&](int set) {
-            float b3[NBLK];
-#pragma unroll
-            for (int n = 0; n < NBLK; ++n) b3[n] = kk ? 0.f : bhi[set][n][1];     // tap s = 7 does not exist
-#pragma unroll
-            for (int n = 0; n < NBLK; ++n)
-                acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][0], blo[set][n][0], acc[n], 0, 0, 0);
-#pragma unroll
-            for (int n = 0; n < NBLK; ++n)
-                acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][1], blo[set][n][1], acc[n], 0, 0, 0);
-#pragma unroll
-            for (int n = 0; n < NBLK; ++n)
-                acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][2], bhi[set][n][0], acc[n], 0, 0, 0);
-#pragma unroll
-            for (int n = 0; n < NBLK; ++n)
-                acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[set][3], b3[n], acc[n], 0, 0, 0);
-        };
-
-        UnitPos cur = first_unit(a, KT, TB, TW, TH);
-        bool have = cur.t < a.n_tiles;
-        int flt_k0 = have ? cur.tc.k0 : -1;
-        if (have) {
-            lds_done_then_barrier();        // tile 0 (and the Filter tile) is staged
-            load_rc(0, 0, 0);
-        }
-        while (have) {
-#pragma unroll
-            for (int buf = 0; buf < 2; ++buf) {
-                if (have) {
-                    UnitPos nxt = cur;
-                    nxt.t += gridDim.x;
-                    const bool have_next = nxt.t < a.n_tiles;
-                    if (have_next) nxt.tc = decode_tile_index(a, nxt.t, KT, TB, TW, TH);
-                    // group rc of the tile in buffer buf uses register set (rc + buf) & 1: R*C is odd, so the first
-                    // group of the next tile lands in the set the last group of this one does not use
-                    static_assert((R * C) % 2 == 1, "stem geometry: odd number of (r, c) groups");
-#pragma unroll
-                    for (int rc = 0; rc < R * C; ++rc) {
-                        const int set = (rc + buf) & 1;
-                        if (rc + 1 < R * C) {
-                            load_rc(buf, rc + 1, set ^ 1);
-                        } else if (have_next) {
-                            // every fragment of this tile has been requested: once they have landed the buffer goes
-                            // back to the staging waves, and the first fragments of the next tile are read under
-                            // this group's MFMAs and the Out stores
-                            if (nxt.tc.k0 != flt_k0) {
-                                lds_done_then_barrier();      // done with the old Filter tile
-                                flt_k0 = nxt.tc.k0;
-                            }
-                            lds_done_then_barrier();
-                            load_rc(buf ^ 1, 0, set ^ 1);
-                        }
-                        mfma_rc(set);
-                        interleave_hint<4 * NBLK, 1 + NBLK>();
-                    }
-                    // Out tile: block n is output column w_l, row h_l; a lane owns image j.  Every address is a
-                    // wave-uniform base (scalar arithmetic) plus the lane's constant 32-bit offset.
-#pragma unroll
-                    for (int n = 0; n < NBLK; ++n) {
-                        const int nn = wn * NBLK + n;
-                        const int w = cur.tc.w0 + nn % TW, h = cur.tc.h0 + nn / TW;
-                        float* const blk = a.out + ((((int64_t)(cur.tc.k0 + wm * 32) * a.H + h) * a.W + w) * a.B + cur.tc.b0);
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            float* const row = blk + (int64_t)((v >> 2) * 8 + (v & 3)) * out_kstride;
-                            __builtin_nontemporal_store(acc[n][v], row + out_lane);
-                            acc[n][v] = 0.f;
-                        }
-                    }
-                    cur = nxt;
-                    have = have_next;
-                }
-            }
-        }
-    }
-}
-
-// ---- the stem-layer shape with the Image loaded straight into LDS ------------------------------------------------------
-// 7x7 taps, strides 2, three channels, 32 images per tile.  The Image keeps its global order in LDS: one x plane is the
+// ---- fixed geometry, large strided filter, few channels (the stem-layer shape), Image loaded straight into LDS ------
+// 7x7 taps, strides 2, three channels, 32 images per tile.  (With C = 3 the 16-byte channel fragments of the generic
+// kernels would be mostly padding.)  The Image keeps its global order in LDS: one x plane is the
 // run of (y, c) rows of the tile's 32 images (128 bytes each, 27 rows for a tile two output rows high), so the
 // contraction over (s, c) for a fixed r is a walk down consecutive rows: row 6*h_l + q, q = 3 s + c = 0..20.  An fp32
 // MFMA takes two contraction indices, one per half-wave: the halves take q and q + 11 (a constant 11 rows apart, so it
@@ -2813,7 +2561,6 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
-using FxStem7 = F32StemFixed<2, 2, 7, 7, 2, 2, 3>;
 
 static const Variant g_variants[] = {
     // fp32
@@ -2870,13 +2617,6 @@ static const Variant g_variants[] = {
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 0.9f, 8.0f, 7, 1),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.6f, 4.0f, 2, 2),
     // fixed geometry for the stem-layer shape: 7x7 taps, strides 2, three channels
-    {{"f32 fxs k64 b32w2h2 w2x2 m1n2 c3r7s7 s2", 0, 2, 2, 1, FxStem7::NBLK, 32, 2, 2, 2, 1, 1, 1, 0, 1.0f, 3, 7, 7, FxStem7::YS, 2,
-      2, FxStem7::LDS_BYTES, 6.3f, 5.5f, 1},
-     [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {
-         static bool attr_done = false;
-         if (!FxStem7::matches_host(a) || lds != (size_t)FxStem7::LDS_BYTES) return 1;
-         return launch_kernel(conv_f32_stem_kernel<2, 2, 7, 7, 2, 2, 3>, attr_done, 512, a, grid, lds, stream);
-     }},
     {{"f32 fxsd k64 b32w2h2 w2x2 m1n2 c3r7s7 s2", 0, 2, 2, 1, F32StemDirect<2, 2>::NBLK, 32, 2, 2, 2, 1, 1, 1, 0, 1.0f, 3, 7, 7,
       F32StemDirect<2, 2>::YS, 2, 2, F32StemDirect<2, 2>::LDS_BYTES, 5.0f, 5.0f, 1},
      [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {
