@@ -87,6 +87,10 @@ typedef struct {
     double tile_volume;      /* b_b*b_c*b_k*b_w*b_h*b_r*b_s */
     double predicted_words;  /* words this schedule moves between HBM/L2 and the compute units:
                                 staged Image halo tiles + staged Filter tiles + Out written once */
+    int32_t xcd_split_k;     /* Section 7 with the eight XCDs (each has its own L2) as the processors: the XCDs are
+                                divided into this many groups of output channels (a_K; 1, 2, 4 or 8, a divisor of the
+                                k-tile count) and 8 / a_K ranges of positions, whichever makes a_K*|Image| +
+                                (8/a_K)*|Filter| bytes smallest.  cacnn_conv_forward_with_plan: 0 = choose. */
 } cacnn_plan;
 
 /*
@@ -151,6 +155,27 @@ int cacnn_conv_forward(const cacnn_problem* problem, int dtype, const void* imag
  */
 int cacnn_conv_forward_with_plan(const cacnn_problem* problem, int dtype, const cacnn_plan* plan,
                                  const void* image, const void* filter, void* out, void* hip_stream);
+
+/*
+ * Section 7 ("Parallel Algorithm"): p processors share one memory, each gets one block B/a_B x K/a_K x W/a_W x H/a_H of
+ * the output and runs the sequential algorithm on it.  Total traffic is bounded below by
+ *     max(BKWH, a_K*sw*sh*BCWH, a_B*a_W*a_H*CKRS, BCKWHRS/M, BCKWH*sqrt(RS*sw*sh/M)):
+ * the Image term is replicated over the a_K groups of output channels, the Filter term over the a_B*a_W*a_H groups
+ * of positions.  Host only.
+ * cacnn_parallel_bound: the five terms for a given division (strides clamped as in cacnn_lower_bound).
+ * cacnn_work_division: the division to use for p processors.  Readings the paper leaves open: an a may be anything
+ * from 1 to the size of its dimension; the work is divided over as many processors as the dimensions allow (the
+ * largest product a_B*a_K*a_W*a_H <= p); among those the maximum above is minimised, ties go to the least replicated
+ * traffic a_K*term2 + a_B*a_W*a_H*term3, then to the lexicographically smallest (a_B, a_K, a_W, a_H).
+ * Errors: CACNN_ERR_NULL; CACNN_ERR_INVALID_ARG for any parameter < 1, M_words <= 0, an a above its dimension,
+ * p > 4096 (outputs untouched).
+ */
+typedef struct {
+    int32_t a_b, a_k, a_w, a_h;
+} cacnn_division;
+int cacnn_parallel_bound(const cacnn_problem* problem, double M_words, const cacnn_division* a, cacnn_bound* out);
+int cacnn_work_division(const cacnn_problem* problem, double M_words, int32_t p, cacnn_division* out_a,
+                        cacnn_bound* out_bound);
 
 /*
  * Pooling (Section 6 of the paper, "Application to Pooling"): the convolution's loop nest without the Filter,

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     CACNN_POOL_MAX,
     CacnnError,
     Bound,
+    Division,
     Machine,
     Plan,
     PoolBound,
@@ -17,6 +18,7 @@ from .binding import (  # noqa: F401
     cacnn_conv_forward,
     cacnn_conv_forward_with_plan,
     cacnn_lower_bound,
+    cacnn_parallel_bound,
     cacnn_pool_forward,
     cacnn_pool_lower_bound,
     cacnn_probe_copy,
@@ -25,5 +27,6 @@ from .binding import (  # noqa: F401
     cacnn_tile_plan,
     cacnn_variant_count,
     cacnn_variant_name,
+    cacnn_work_division,
     library_path,
 )

@@ -61,7 +61,12 @@ class Plan(ctypes.Structure):
         ("grid", ctypes.c_int32 * 3), ("block", ctypes.c_int32),
         ("lds_bytes_used", ctypes.c_int64),
         ("tile_volume", ctypes.c_double), ("predicted_words", ctypes.c_double),
+        ("xcd_split_k", ctypes.c_int32),
     ]
+
+
+class Division(ctypes.Structure):
+    _fields_ = [("a_b", ctypes.c_int32), ("a_k", ctypes.c_int32), ("a_w", ctypes.c_int32), ("a_h", ctypes.c_int32)]
 
 
 def library_path() -> str:
@@ -87,6 +92,12 @@ _lib.cacnn_conv_forward.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctype
 _lib.cacnn_conv_forward_with_plan.restype = ctypes.c_int
 _lib.cacnn_conv_forward_with_plan.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctypes.POINTER(Plan),
                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.cacnn_parallel_bound.restype = ctypes.c_int
+_lib.cacnn_parallel_bound.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, ctypes.POINTER(Division),
+                                      ctypes.POINTER(Bound)]
+_lib.cacnn_work_division.restype = ctypes.c_int
+_lib.cacnn_work_division.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, ctypes.c_int32, ctypes.POINTER(Division),
+                                     ctypes.POINTER(Bound)]
 _lib.cacnn_pool_lower_bound.restype = ctypes.c_int
 _lib.cacnn_pool_lower_bound.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, ctypes.POINTER(PoolBound)]
 _lib.cacnn_pool_forward.restype = ctypes.c_int
@@ -169,6 +180,26 @@ def cacnn_conv_forward(problem, dtype: int, image, filt, out, stream=None) -> No
                                  _stream_handle(stream))
     if rc != 0:
         raise CacnnError(rc, "cacnn_conv_forward")
+
+
+def cacnn_parallel_bound(problem, M_words: float, a) -> Bound:
+    """Section 7: the five terms for the division a = (a_B, a_K, a_W, a_H) (host only)."""
+    out = Bound()
+    div = a if isinstance(a, Division) else Division(*[int(x) for x in a])
+    rc = _lib.cacnn_parallel_bound(ctypes.byref(_as_problem(problem)), float(M_words), ctypes.byref(div), ctypes.byref(out))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_parallel_bound")
+    return out
+
+
+def cacnn_work_division(problem, M_words: float, p: int):
+    """Section 7: ((a_B, a_K, a_W, a_H), Bound) for p processors (host only)."""
+    div, out = Division(), Bound()
+    rc = _lib.cacnn_work_division(ctypes.byref(_as_problem(problem)), float(M_words), int(p), ctypes.byref(div),
+                                  ctypes.byref(out))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_work_division")
+    return (div.a_b, div.a_k, div.a_w, div.a_h), out
 
 
 def cacnn_pool_lower_bound(problem, M_words: float) -> PoolBound:

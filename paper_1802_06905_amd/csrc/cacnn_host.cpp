@@ -159,6 +159,18 @@ void bound_terms(const cacnn_problem& p, double M, cacnn_bound* out) {
     out->bound = out->term[out->argmax];
 }
 
+// Section 7: Theorem 1's terms with the Image replicated over the a_K groups of output channels and the Filter over
+// the a_B a_W a_H groups of positions.
+void parallel_terms(const cacnn_problem& p, double M, int64_t ab, int64_t ak, int64_t aw, int64_t ah, cacnn_bound* out) {
+    bound_terms(p, M, out);
+    out->term[1] *= (double)ak;
+    out->term[2] *= (double)ab * (double)aw * (double)ah;
+    out->argmax = 0;
+    for (int i = 1; i < 5; ++i)
+        if (out->term[i] > out->term[out->argmax]) out->argmax = i;
+    out->bound = out->term[out->argmax];
+}
+
 // ------------------------------------------------------------------------------------------------------------
 // gfx950 tile geometry for one (variant, contraction tile)
 
@@ -429,6 +441,37 @@ int64_t launch_grid(const VariantInfo& v, const Geometry& g, int64_t n_tiles, co
     return std::min<int64_t>(n_tiles, mach.num_cu * resident);
 }
 
+// XCD count used for the tile remapping; CACNN_XCDS=1 switches the remapping off (debugging aid)
+int xcd_count() {
+    static int n = [] {
+        const char* e = std::getenv("CACNN_XCDS");
+        const int v = e ? std::atoi(e) : 8;
+        return v >= 1 && v <= 64 ? v : 8;
+    }();
+    return n;
+}
+
+// Section 7 with the XCDs as the processors and the arrays' real sizes: divide the XCDs into a_K groups of output
+// channels and n_xcd / a_K ranges of positions; an XCD then fetches 1 / a_K of the Filter and the Image is fetched a_K
+// times over all XCDs.  a_K must divide both the XCD count and the k-tile count (whole k-tiles per group).
+int choose_xcd_split_k(const cacnn_problem& p, int dtype, int64_t tiles_k, int n_xcd) {
+    const double esz = dtype == CACNN_F32 ? 4.0 : 2.0;
+    const double img = (double)(p.sigma_w * (p.W - 1) + p.R) * (double)(p.sigma_h * (p.H - 1) + p.S) * (double)p.C *
+                       (double)p.B * esz;
+    const double flt = (double)p.K * p.R * p.S * p.C * esz;
+    int best = 1;
+    double best_bytes = img + (double)n_xcd * flt;
+    for (int ak = 2; ak <= n_xcd; ak *= 2) {
+        if (n_xcd % ak || tiles_k % ak) continue;
+        const double bytes = (double)ak * img + (double)(n_xcd / ak) * flt;
+        if (bytes < best_bytes) {
+            best = ak;
+            best_bytes = bytes;
+        }
+    }
+    return best;
+}
+
 int fill_plan(const cacnn_problem& p, int dtype, const cacnn_machine& mach, const Choice& ch, cacnn_plan* out) {
     const VariantInfo& v = variant(ch.variant).info;
     const double esz = dtype == CACNN_F32 ? 4.0 : 2.0;
@@ -464,6 +507,7 @@ int fill_plan(const cacnn_problem& p, int dtype, const cacnn_machine& mach, cons
     out->lds_bytes_used = ch.g.lds_bytes;
     out->tile_volume = (double)v.TB * ch.g.CT * v.KT() * v.TW * v.TH * ch.g.bR * ch.g.bS;
     out->predicted_words = ch.words + (double)p.K * p.H * p.W * p.B;
+    out->xcd_split_k = choose_xcd_split_k(p, dtype, ceil_div(p.K, v.KT()), xcd_count());
     return CACNN_OK;
 }
 
@@ -515,16 +559,6 @@ int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, c
     return fill_plan(*p, dtype, mach, best, out);
 }
 
-// XCD count used for the tile remapping; CACNN_XCDS=1 switches the remapping off (debugging aid)
-int xcd_count() {
-    static int n = [] {
-        const char* e = std::getenv("CACNN_XCDS");
-        const int v = e ? std::atoi(e) : 8;
-        return v >= 1 && v <= 64 ? v : 8;
-    }();
-    return n;
-}
-
 bool g_device_checked = false;
 bool g_device_ok = false;
 std::mutex g_mutex;
@@ -541,7 +575,7 @@ bool have_device() {
     return g_device_ok;
 }
 
-int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int bS, const void* image,
+int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int bS, int split_k, const void* image,
                 const void* filter, void* out, void* stream) {
     const Variant& var = variant(vi);
     const VariantInfo& v = var.info;
@@ -623,7 +657,12 @@ int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int b
     a.xcd_q = a.n_tiles / a.n_xcd;
     a.xcd_rem = a.n_tiles % a.n_xcd;
     a.d_nxcd = make_fastdiv((uint32_t)a.n_xcd);
-    a.d_tk = make_fastdiv((uint32_t)a.tiles_k);
+    if (split_k == 0) split_k = choose_xcd_split_k(p, dtype, a.tiles_k, a.n_xcd);
+    if (split_k < 1 || split_k > 8 || (split_k & (split_k - 1)) || a.tiles_k % split_k) return CACNN_ERR_INVALID_ARG;
+    a.k_groups = split_k;
+    a.kpg = a.tiles_k / split_k;
+    a.grp = a.n_tiles / split_k;
+    a.d_tk = make_fastdiv((uint32_t)a.kpg);
     a.d_bg = make_fastdiv((uint32_t)a.b_group);
     a.d_tw = make_fastdiv((uint32_t)a.tiles_w);
     a.d_th = make_fastdiv((uint32_t)a.tiles_h);
@@ -685,7 +724,8 @@ int cacnn_conv_forward(const cacnn_problem* problem, int dtype, const void* imag
         if (cache.size() >= 64) cache.erase(cache.begin());
         cache.push_back(Entry{*problem, key, plan});
     }
-    return launch_with(*problem, dtype, plan.variant, plan.b_c, plan.b_r, plan.b_s, image, filter, out, hip_stream);
+    return launch_with(*problem, dtype, plan.variant, plan.b_c, plan.b_r, plan.b_s, plan.xcd_split_k, image, filter, out,
+                       hip_stream);
 }
 
 int cacnn_conv_forward_with_plan(const cacnn_problem* problem, int dtype, const cacnn_plan* plan, const void* image,
@@ -703,7 +743,56 @@ int cacnn_conv_forward_with_plan(const cacnn_problem* problem, int dtype, const 
     const int CT = (int)std::min<int64_t>(round_up(plan->b_c, v.cgran()), Cpad);
     const int bR = (int)std::min<int64_t>(plan->b_r, problem->R);
     const int bS = (int)std::min<int64_t>(plan->b_s, problem->S);
-    return launch_with(*problem, dtype, plan->variant, CT, bR, bS, image, filter, out, hip_stream);
+    if (plan->xcd_split_k < 0) return CACNN_ERR_INVALID_ARG;
+    return launch_with(*problem, dtype, plan->variant, CT, bR, bS, plan->xcd_split_k, image, filter, out, hip_stream);
+}
+
+int cacnn_parallel_bound(const cacnn_problem* problem, double M_words, const cacnn_division* a, cacnn_bound* out) {
+    if (!problem || !a || !out) return CACNN_ERR_NULL;
+    if (!valid_problem(problem) || !(M_words > 0.0) || !std::isfinite(M_words)) return CACNN_ERR_INVALID_ARG;
+    const cacnn_problem& p = *problem;
+    if (a->a_b < 1 || a->a_k < 1 || a->a_w < 1 || a->a_h < 1 || a->a_b > p.B || a->a_k > p.K || a->a_w > p.W ||
+        a->a_h > p.H)
+        return CACNN_ERR_INVALID_ARG;
+    parallel_terms(p, M_words, a->a_b, a->a_k, a->a_w, a->a_h, out);
+    return CACNN_OK;
+}
+
+int cacnn_work_division(const cacnn_problem* problem, double M_words, int32_t p_count, cacnn_division* out_a,
+                        cacnn_bound* out_bound) {
+    if (!problem || !out_a || !out_bound) return CACNN_ERR_NULL;
+    if (!valid_problem(problem) || !(M_words > 0.0) || !std::isfinite(M_words) || p_count < 1 || p_count > 4096)
+        return CACNN_ERR_INVALID_ARG;
+    const cacnn_problem& p = *problem;
+    bool have = false;
+    int64_t best_prod = 0;
+    double best_rep = 0.0;
+    cacnn_division best_a = {1, 1, 1, 1};
+    cacnn_bound best_b;
+    std::memset(&best_b, 0, sizeof(best_b));
+    // every admissible division, in lexicographic order (so the first of equals is the lexicographically smallest)
+    for (int64_t ab = 1; ab <= std::min<int64_t>(p.B, p_count); ++ab)
+        for (int64_t ak = 1; ak <= std::min<int64_t>(p.K, p_count / ab); ++ak)
+            for (int64_t aw = 1; aw <= std::min<int64_t>(p.W, p_count / (ab * ak)); ++aw)
+                for (int64_t ah = 1; ah <= std::min<int64_t>(p.H, p_count / (ab * ak * aw)); ++ah) {
+                    cacnn_bound b;
+                    parallel_terms(p, M_words, ab, ak, aw, ah, &b);
+                    const int64_t prod = ab * ak * aw * ah;
+                    const double rep = b.term[1] + b.term[2];
+                    const bool better = !have || prod > best_prod ||
+                                        (prod == best_prod && (b.bound < best_b.bound ||
+                                                               (b.bound == best_b.bound && rep < best_rep)));
+                    if (better) {
+                        have = true;
+                        best_prod = prod;
+                        best_rep = rep;
+                        best_b = b;
+                        best_a = cacnn_division{(int32_t)ab, (int32_t)ak, (int32_t)aw, (int32_t)ah};
+                    }
+                }
+    *out_a = best_a;
+    *out_bound = best_b;
+    return CACNN_OK;
 }
 
 int cacnn_pool_lower_bound(const cacnn_problem* problem, double M_words, cacnn_pool_bound* out) {

@@ -78,6 +78,9 @@ struct KernelArgs {
     int32_t n_xcd;            // XCDs the dispatcher deals workgroups to (8 on MI355X); 1 = no remapping
     int32_t b_group;          // consecutive b-tiles whose Image rows share 128-byte lines (divides tiles_b)
     int32_t xcd_q, xcd_rem;   // n_tiles = n_xcd * xcd_q + xcd_rem
+    // the tile list is k_groups blocks of grp tiles; inside a block the kpg k-tiles of the group are the fastest index
+    // (k_groups = 1: the whole list is one block with all tiles_k k-tiles fastest); d_tk divides by kpg
+    int32_t k_groups, kpg, grp;
     FastDiv d_nxcd, d_tk, d_bg, d_tw, d_th;   // reciprocals of n_xcd, tiles_k, b_group, tiles_w, tiles_h
     int32_t img_items, flt_items;   // 16-byte staging items per slice
     int32_t img_buf, flt_buf; // size of one LDS buffer of each operand (fp32: floats; bf16: 16-byte units)

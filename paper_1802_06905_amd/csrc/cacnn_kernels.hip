@@ -44,7 +44,9 @@ struct TileCoord {
 // image groups slowest: the workgroups that share an Image tile, its halo or its cache lines (and walk the Filter
 // slices in step) then share an L2, and different XCDs mostly hold different images -- the Image is fetched from
 // memory about once and the Filter once per XCD (the a_K / a_B a_W a_H replication of Section 7's parallel
-// bound, with the XCDs as the processors).
+// bound, with the XCDs as the processors).  Where the Filter is the bigger array the host divides the k-tiles into
+// k_groups groups first (the list is then k_groups blocks, each ordered as above over its own k-tiles): an XCD sees
+// 1 / k_groups of the Filter and the Image is fetched k_groups times.
 // i -> tile is a bijection on [0, n): XCD x = i % n_xcd owns tiles [x*q + min(x,rem), ...) with n = n_xcd*q + rem.
 __device__ __forceinline__ int xcd_tile(const KernelArgs& a, int i) {
     if (a.n_xcd <= 1) return i;
@@ -55,8 +57,12 @@ __device__ __forceinline__ int xcd_tile(const KernelArgs& a, int i) {
 // tile list index -> tile origin; the divisors are fixed for the launch, so each division is one multiply-high
 // (the host only enables the remapping and these reciprocals when the tile count keeps them exact)
 __device__ __forceinline__ TileCoord tile_coords(const KernelArgs& a, int t, int KT, int TB, int TW, int TH) {
+    // which group of output channels (at most 8: a few scalar compares), then the k-tile inside the group
+    int kg = 0;
+    for (int i = 1; i < a.k_groups; ++i) kg += (t >= i * a.grp) ? 1 : 0;
+    t -= kg * a.grp;
     int q = (int)fdiv((uint32_t)t, a.d_tk);
-    const int tk = t - q * a.tiles_k;
+    const int tk = kg * a.kpg + (t - q * a.kpg);
     t = q;
     q = (int)fdiv((uint32_t)t, a.d_bg);
     const int tbl = t - q * a.b_group;

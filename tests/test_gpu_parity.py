@@ -209,3 +209,45 @@ def test_error_paths_enqueue_nothing(env):
     assert e.value.status == 3
     torch.cuda.synchronize()
     assert not d_out.any()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_every_xcd_division_computes_the_same_convolution(env, dtype):
+    """Section 7 with the XCDs as processors: the tile order may divide the output channels into 1, 2, 4 or 8 groups.
+    Every division is a permutation of the tile list, so every one must give the oracle's result: on a shape with 8
+    k-tiles and several position tiles, for the planner's kernel, a direct one and a fixed-geometry one.  Divisions that do not divide the k-tile count are refused."""
+    cc, torch = env
+    B, C = (8, 32) if dtype == "f32" else (64, 64)
+    cfg = ci.custom("xcd_div", B, C, 512, 8, 4, 3, 3, 1, 1, dtype=dtype, dist="normal", seed=321)
+    img, flt = ci.make_inputs(cfg)
+    ref, ab = gu.oracle_full(cfg, img, flt)
+    base = cc.cacnn_tile_plan(cfg.dims, gu.dtype_code(cfg))
+    names = {cc.cacnn_variant_name(i): i for i in variants_for(cc, dtype)}
+    picks = {"planner": (base.variant, base.b_c, base.b_r, base.b_s)}
+    picks["direct"] = (names[f"{dtype} k64 b8w4h4 w2x2 m1n2"], 16, 3, 3)
+    fx = [n for n in names if " fxd " in n and ("b8w4h4" in n or "b64w2h2" in n)]
+    assert fx, "no fixed-geometry kernel for this shape"
+    picks["fixed"] = (names[fx[0]], 16 if dtype == "f32" else 32, 3, 3 if dtype == "f32" else 1)
+    for what, (vi, bc, br, bs) in picks.items():
+        for split in (1, 2, 4, 8, 0):
+            plan = cc.Plan()
+            plan.variant, plan.b_c, plan.b_r, plan.b_s, plan.xcd_split_k = vi, bc, br, bs, split
+            say(f"[xcd division] {dtype} {what} '{cc.cacnn_variant_name(vi)}' a_K={split}")
+            out = gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
+            gu.assert_parity(cfg, out, ref, ab, f"{what} a_K={split}")
+    for bad in (3, 16, -1):
+        plan = cc.Plan()
+        plan.variant, plan.b_c, plan.b_r, plan.b_s, plan.xcd_split_k = base.variant, base.b_c, base.b_r, base.b_s, bad
+        with pytest.raises(cc.CacnnError) as e:
+            gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
+        assert e.value.status == 2
+    # an odd number of k-tiles cannot be divided into two groups
+    odd = ci.custom("xcd_div_odd", B, C, 192, 4, 4, 3, 3, 1, 1, dtype=dtype, dist="normal", seed=322)
+    plan = cc.cacnn_tile_plan(odd.dims, gu.dtype_code(odd))
+    assert plan.xcd_split_k == 1
+    if (192 // plan.b_k) % 2 == 1:
+        plan.xcd_split_k = 2
+        i2, f2 = ci.make_inputs(odd)
+        with pytest.raises(cc.CacnnError) as e:
+            gu.run_gpu(cc, torch, odd, i2, f2, plan=plan)
+        assert e.value.status == 2

@@ -32,7 +32,7 @@ def test_struct_sizes_match_the_header():
     src = r'''
     #include <stdio.h>
     #include "cacnn.h"
-    int main(void){ printf("%zu %zu %zu %zu %zu\n", sizeof(cacnn_problem), sizeof(cacnn_bound), sizeof(cacnn_machine), sizeof(cacnn_plan), sizeof(cacnn_pool_bound)); return 0; }
+    int main(void){ printf("%zu %zu %zu %zu %zu %zu\n", sizeof(cacnn_problem), sizeof(cacnn_bound), sizeof(cacnn_machine), sizeof(cacnn_plan), sizeof(cacnn_pool_bound), sizeof(cacnn_division)); return 0; }
     '''
     with tempfile.TemporaryDirectory() as d:
         open(os.path.join(d, "t.c"), "w").write(src)
@@ -41,7 +41,7 @@ def test_struct_sizes_match_the_header():
         sizes = [int(x) for x in subprocess.run([os.path.join(d, "t")], capture_output=True, text=True,
                                                 check=True).stdout.split()]
     assert sizes == [ctypes.sizeof(cc.Problem), ctypes.sizeof(cc.Bound), ctypes.sizeof(cc.Machine),
-                     ctypes.sizeof(cc.Plan), ctypes.sizeof(cc.PoolBound)]
+                     ctypes.sizeof(cc.Plan), ctypes.sizeof(cc.PoolBound), ctypes.sizeof(cc.Division)]
 
 
 def test_fastdiv_is_exact_over_its_domain():
@@ -246,3 +246,49 @@ def test_probes_reject_bad_arguments_before_touching_the_gpu():
         with pytest.raises(cc.CacnnError) as e:
             cc.cacnn_probe_copy(src, dst, n, stream=0)
         assert e.value.status == status, (src, dst, n)
+
+
+PAR_SHAPES = [(8, 64, 64, 56, 56, 3, 3, 1, 1), (32, 3, 64, 112, 112, 7, 7, 2, 2), (256, 512, 512, 7, 7, 3, 3, 1, 1),
+              (8, 1024, 1024, 7, 7, 3, 3, 1, 1), (1, 3, 8, 16, 16, 3, 3, 1, 1), (4, 5, 6, 7, 8, 3, 2, 4, 1),
+              (1, 4, 1, 1, 3, 1, 1, 1, 1)]
+
+
+@pytest.mark.parametrize("dims", PAR_SHAPES)
+def test_parallel_bound_and_work_division_match_the_oracle(dims):
+    from oracle import parallel as opar
+    for M in (16.0, 40960.0, 1e7):
+        for a in ((1, 1, 1, 1), (1, dims[2], 1, 1), (dims[0], 1, dims[3], dims[4])):
+            got = cc.cacnn_parallel_bound(dims, M, a)
+            ref = opar.parallel_bound(*dims, M, *a)
+            assert list(got.term) == ref.terms and got.bound == ref.bound and got.argmax == ref.argmax
+        for p in (1, 2, 3, 8, 12, 64, 256):
+            a, b = cc.cacnn_work_division(dims, M, p)
+            ref = opar.work_division(*dims, M, p)
+            assert a == ref.a, (dims, M, p)
+            assert list(b.term) == ref.bound.terms and b.bound == ref.bound.bound and b.argmax == ref.bound.argmax
+
+
+def test_parallel_entry_points_reject_bad_arguments():
+    ok = (2, 3, 4, 5, 6, 2, 2, 1, 1)
+    for dims, M, a, status in ((ok, 16.0, (3, 1, 1, 1), 2), (ok, 16.0, (1, 1, 0, 1), 2), (ok, 0.0, (1, 1, 1, 1), 2),
+                               ((2, 3, 0, 5, 6, 2, 2, 1, 1), 16.0, (1, 1, 1, 1), 2)):
+        with pytest.raises(cc.CacnnError) as e:
+            cc.cacnn_parallel_bound(dims, M, a)
+        assert e.value.status == status
+    for p in (0, -3, 4097):
+        with pytest.raises(cc.CacnnError) as e:
+            cc.cacnn_work_division(ok, 16.0, p)
+        assert e.value.status == 2
+
+
+def test_plan_divides_the_xcds_by_output_channels_only_where_the_filter_is_the_bigger_array():
+    # Filter 18.9 MB against an Image of 1.3 MB, 16 k-tiles: every XCD gets its own output channels
+    assert cc.cacnn_tile_plan((8, 1024, 1024, 7, 7, 3, 3, 1, 1), 1).xcd_split_k == 8
+    # the benchmark shapes are Image-heavy (or have one k-tile): positions only
+    for name, cfg in ci.CONFIGS.items():
+        assert cc.cacnn_tile_plan(cfg.dims, 0 if cfg.dtype == "f32" else 1).xcd_split_k == 1, name
+    # in between: 2 * Image + 4 * Filter is the smallest sum
+    p = cc.cacnn_tile_plan((16, 512, 512, 14, 14, 3, 3, 1, 1), 1)
+    img, flt = 16 * 16 * 512 * 16 * 2, 512 * 9 * 512 * 2
+    sums = {ak: ak * img + (8 // ak) * flt for ak in (1, 2, 4, 8)}
+    assert p.xcd_split_k == min(sums, key=sums.get)
