@@ -95,7 +95,7 @@ def committed_traffic(name):
     """HBM-side bytes of one launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs, scaled
     by the copy-kernel calibration recorded there).  Counters cannot be read from inside this process, so the
     figure is the recorded one for this shape, not a measurement of this run; None if the summary is absent."""
-    for fname in ("hbm_traffic_c1-c5.txt", "pooling_p1.txt"):
+    for fname in ("hbm_traffic_c1-c5.txt", "pooling_p1.txt", "work_division_d1.txt"):
         try:
             with open(os.path.join(ROOT, "profiles", fname)) as f:
                 for line in f:
@@ -167,9 +167,10 @@ def cpu_baseline(cfg, img, flt, np):
                       f"{reps} passes)"}, ref, ab, k_use
 
 
-def traffic_probe(cc, torch, ci, np, cfg):
+def traffic_probe(cc, torch, ci, np, cfg, xcd_split_k=0):
     """Dispatch sequence for the HBM-traffic counters (FETCH_SIZE / WRITE_SIZE, KiB per dispatch):
-    a plain copy of known size to scale the counters by, then the workload cold (caches evicted) and warm."""
+    a plain copy of known size to scale the counters by, then the workload cold (caches evicted) and warm.
+    xcd_split_k > 0 forces that division of the XCDs over the output channels (0: the planner's)."""
     n = 512 * 1024 * 1024
     src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
     dst = torch.empty(n, dtype=torch.uint8, device="cuda:0")
@@ -187,12 +188,53 @@ def traffic_probe(cc, torch, ci, np, cfg):
     torch.cuda.synchronize()
     evict = torch.empty(1024 * 1024 * 1024, dtype=torch.uint8, device="cuda:0").fill_(3)   # push everything out
     torch.cuda.synchronize()
-    cc.cacnn_conv_forward(cfg.dims, dt, d_img, d_flt, d_out)      # cold
+    plan = cc.cacnn_tile_plan(cfg.dims, dt)
+    if xcd_split_k:
+        plan.xcd_split_k = xcd_split_k
+    cc.cacnn_conv_forward_with_plan(cfg.dims, dt, plan, d_img, d_flt, d_out)      # cold
     torch.cuda.synchronize()
-    cc.cacnn_conv_forward(cfg.dims, dt, d_img, d_flt, d_out)      # warm
+    cc.cacnn_conv_forward_with_plan(cfg.dims, dt, plan, d_img, d_flt, d_out)      # warm
     torch.cuda.synchronize()
     del evict
-    print(json.dumps({"traffic_probe": cfg.name, "copy_bytes_each_way": n}))
+    print(json.dumps({"traffic_probe": cfg.name, "copy_bytes_each_way": n, "xcd_split_k": plan.xcd_split_k}))
+
+
+def division_report(cc, torch, ci, np, cfg, steps, warmup):
+    """Section 7 with the eight XCDs as the processors: time of the workload for every division of the XCDs over the
+    output channels (a_K = 1, 2, 4, 8), the one the planner chooses, and the paper's bound for each (M = LDS words,
+    p = 8, the positions divided along h)."""
+    img, flt = ci.make_inputs(cfg)
+    d_img = torch.from_numpy(ci.bf16_bits(img).view(np.int16).reshape(-1)).cuda()
+    d_flt = torch.from_numpy(ci.bf16_bits(flt).view(np.int16).reshape(-1)).cuda()
+    d_out = torch.empty(int(np.prod(cfg.out_shape)), dtype=torch.float32, device="cuda:0")
+    plan = cc.cacnn_tile_plan(cfg.dims, 1)
+    chosen = plan.xcd_split_k
+    esz = 2.0
+    img_b = float(np.prod(cfg.image_shape)) * esz
+    flt_b = float(np.prod(cfg.filter_shape)) * esz
+    M = LDS_BYTES / esz
+    rep = {"workload": f"{cfg.name}: B={cfg.B} C={cfg.C} K={cfg.K} W=H={cfg.W} R=S={cfg.R} bf16", "chosen_a_K": chosen,
+           "variant": cc.cacnn_variant_name(plan.variant), "image_bytes": img_b, "filter_bytes": flt_b, "divisions": {}}
+    a, b = cc.cacnn_work_division(cfg.dims, M, 8)
+    rep["paper_division_p8"] = {"a_B_a_K_a_W_a_H": list(a), "bound_words": b.bound}
+    for ak in (1, 2, 4, 8):
+        plan.xcd_split_k = ak
+        for _ in range(warmup):
+            cc.cacnn_conv_forward_with_plan(cfg.dims, 1, plan, d_img, d_flt, d_out)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            cc.cacnn_conv_forward_with_plan(cfg.dims, 1, plan, d_img, d_flt, d_out)
+        e1.record()
+        torch.cuda.synchronize()
+        sec = e0.elapsed_time(e1) * 1e-3 / steps
+        pb = cc.cacnn_parallel_bound(cfg.dims, M, (1, ak, 1, min(8 // ak, cfg.H)))
+        rep["divisions"][str(ak)] = {"us": sec * 1e6, "tflops": 2.0 * cfg.macs / sec / 1e12,
+                                     "replicated_bytes_model": ak * img_b + (8 // ak) * flt_b,
+                                     "paper_bound_words": pb.bound, "paper_bound_argmax": pb.argmax,
+                                     "hbm_bytes_profiled": committed_traffic(f"{cfg.name}_aK{ak}")}
+    return rep
 
 
 def pool_traffic_probe(cc, torch, ci, np, cfg):
@@ -259,8 +301,11 @@ def main():
     ap.add_argument("--steps", type=int, default=2000,
                     help="timed launches; the clocks take on the order of a thousand back-to-back launches to settle")
     ap.add_argument("--warmup", type=int, default=1000)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "p1"],
-                    help="c1..c5: the convolution shapes (c2 is the headline); p1: the pooling workload")
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "p1", "d1"],
+                    help="c1..c5: the convolution shapes (c2 is the headline); p1: the pooling workload; "
+                         "d1: the work-division workload (a Filter-heavy layer, every division of the XCDs)")
+    ap.add_argument("--xcd-split-k", type=int, default=0,
+                    help="with --traffic-probe: force this division of the XCDs over the output channels (0: planner's)")
     ap.add_argument("--no-shapes", action="store_true", help="time only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -300,9 +345,25 @@ def main():
             out["cpu_baseline"] = rep["cpu_baseline"]
         print(json.dumps(out))
         return
+    if args.workload == "d1":
+        dcfg = ci.DIVISION_CONFIGS["d1"]
+        if args.traffic_probe:
+            traffic_probe(cc, torch, ci, np, dcfg, args.xcd_split_k)
+            return
+        rep = division_report(cc, torch, ci, np, dcfg, args.steps, args.warmup)
+        best = rep["divisions"][str(rep["chosen_a_K"])]
+        print(json.dumps({"metric": "conv TFLOP/s at 1 MI355X", "value": best["tflops"], "unit": "TFLOP/s", "n_gpus": 1,
+                          "steps": args.steps, "warmup": args.warmup, "ms_per_step": best["us"] * 1e-3,
+                          "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+                          "data": "synthetic", "config": {"workload": rep["workload"], "variant": rep["variant"]},
+                          "roofline": {"bound": "mfma", "achieved": best["tflops"], "peak": MFMA_PEAK_TFLOPS["bf16"],
+                                       "unit": "TFLOP/s", "frac": best["tflops"] / MFMA_PEAK_TFLOPS["bf16"],
+                                       "traffic": best["hbm_bytes_profiled"]},
+                          "work_division": rep}))
+        return
     cfg = ci.CONFIGS[args.workload]
     if args.traffic_probe:
-        traffic_probe(cc, torch, ci, np, cfg)
+        traffic_probe(cc, torch, ci, np, cfg, args.xcd_split_k)
         return
     sec, wall, (img, flt, d_out) = time_config(cc, torch, ci, np, cfg, args.steps, args.warmup)
     head = shape_report(cc, cfg, sec)

@@ -74,6 +74,12 @@ POOL_CONFIGS: Dict[str, Config] = {
     "p1": Config("p1", 32, 64, 64, 56, 56, 3, 3, 2, 2, "f32", "uniform", SEED_BASE + 6),
 }
 
+# Work-division workload (Section 7 with the XCDs as processors): a late layer whose Filter (18.9 MB) is larger than
+# its Image (10.6 MB), 16 k-tiles.  The paper names no such shape; this is a 3x3 layer of 1024 channels on 7x7 outputs.
+DIVISION_CONFIGS: Dict[str, Config] = {
+    "d1": Config("d1", 64, 1024, 1024, 7, 7, 3, 3, 1, 1, "bf16", "normal", SEED_BASE + 7),
+}
+
 
 def custom(name, B, C, K, W, H, R, S, sigma_w=1, sigma_h=1, dtype="f32", dist="uniform", seed=1) -> Config:
     """A shape outside the five benchmark ones (edge cases, ragged sizes)."""
