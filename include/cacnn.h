@@ -157,6 +157,18 @@ int cacnn_conv_forward_with_plan(const cacnn_problem* problem, int dtype, const 
                                  const void* image, const void* filter, void* out, void* hip_stream);
 
 /*
+ * Measured plan selection for problems the cost model was not calibrated on: runs every kernel variant that accepts
+ * the problem (each with the contraction tile the model prefers for it) a few times on the caller's buffers, keeps
+ * the fastest, and remembers it for later cacnn_conv_forward calls with the same problem, dtype and operand alignment.
+ * Unlike the other entry points it SYNCHRONISES with hip_stream (it reads event timings) and creates and destroys two
+ * HIP events; it allocates no device memory.  `out` is overwritten by every candidate and ends up holding a valid
+ * result.  Arguments as for cacnn_conv_forward; out_plan (host, may be NULL) receives the chosen plan.
+ * Errors: as cacnn_conv_forward; CACNN_ERR_UNSUPPORTED if no variant accepts the problem.
+ */
+int cacnn_tune(const cacnn_problem* problem, int dtype, const void* image, const void* filter, void* out,
+               void* hip_stream, cacnn_plan* out_plan);
+
+/*
  * Section 7 ("Parallel Algorithm"): p processors share one memory, each gets one block B/a_B x K/a_K x W/a_W x H/a_H of
  * the output and runs the sequential algorithm on it.  Total traffic is bounded below by
  *     max(BKWH, a_K*sw*sh*BCWH, a_B*a_W*a_H*CKRS, BCKWHRS/M, BCKWH*sqrt(RS*sw*sh/M)):

@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     cacnn_probe_mfma,
     cacnn_status_string,
     cacnn_tile_plan,
+    cacnn_tune,
     cacnn_variant_count,
     cacnn_variant_name,
     cacnn_work_division,

@@ -92,6 +92,9 @@ _lib.cacnn_conv_forward.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctype
 _lib.cacnn_conv_forward_with_plan.restype = ctypes.c_int
 _lib.cacnn_conv_forward_with_plan.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctypes.POINTER(Plan),
                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.cacnn_tune.restype = ctypes.c_int
+_lib.cacnn_tune.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                            ctypes.c_void_p, ctypes.POINTER(Plan)]
 _lib.cacnn_parallel_bound.restype = ctypes.c_int
 _lib.cacnn_parallel_bound.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, ctypes.POINTER(Division),
                                       ctypes.POINTER(Bound)]
@@ -180,6 +183,16 @@ def cacnn_conv_forward(problem, dtype: int, image, filt, out, stream=None) -> No
                                  _stream_handle(stream))
     if rc != 0:
         raise CacnnError(rc, "cacnn_conv_forward")
+
+
+def cacnn_tune(problem, dtype: int, image, filt, out, stream=None) -> Plan:
+    """Time every kernel variant that accepts the problem on these buffers (synchronises), remember and return the fastest."""
+    plan = Plan()
+    rc = _lib.cacnn_tune(ctypes.byref(_as_problem(problem)), int(dtype), _ptr(image), _ptr(filt), _ptr(out),
+                         _stream_handle(stream), ctypes.byref(plan))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_tune")
+    return plan
 
 
 def cacnn_parallel_bound(problem, M_words: float, a) -> Bound:

@@ -677,6 +677,35 @@ int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int b
     return var.launch(a, (int)grid, (size_t)g.lds_bytes, stream) == 0 ? CACNN_OK : CACNN_ERR_LAUNCH;
 }
 
+// plan cache of cacnn_conv_forward, keyed by (problem, dtype | misaligned << 8)
+struct PlanEntry {
+    cacnn_problem p;
+    int key;
+    cacnn_plan plan;
+};
+std::vector<PlanEntry> g_plans;
+
+bool lookup_plan(const cacnn_problem& p, int key, cacnn_plan* out) {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    for (const PlanEntry& e : g_plans)
+        if (e.key == key && std::memcmp(&e.p, &p, sizeof(cacnn_problem)) == 0) {
+            *out = e.plan;
+            return true;
+        }
+    return false;
+}
+
+void store_plan(const cacnn_problem& p, int key, const cacnn_plan& plan) {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    for (PlanEntry& e : g_plans)
+        if (e.key == key && std::memcmp(&e.p, &p, sizeof(cacnn_problem)) == 0) {
+            e.plan = plan;
+            return;
+        }
+    if (g_plans.size() >= 64) g_plans.erase(g_plans.begin());
+    g_plans.push_back(PlanEntry{p, key, plan});
+}
+
 }  // namespace
 
 extern "C" {
@@ -696,33 +725,15 @@ int cacnn_conv_forward(const cacnn_problem* problem, int dtype, const void* imag
                        void* hip_stream) {
     if (!problem || !image || !filter || !out) return CACNN_ERR_NULL;
     if (dtype != CACNN_F32 && dtype != CACNN_BF16_F32ACC) return CACNN_ERR_UNSUPPORTED;
-    // plans are cached per (problem, dtype): planning costs tens of microseconds, a launch a few
-    struct Entry {
-        cacnn_problem p;
-        int dtype;
-        cacnn_plan plan;
-    };
-    // the pipelined kernels need 16-byte aligned operands; a misaligned call is planned without them
+    // plans are cached per (problem, dtype): planning costs tens of microseconds, a launch a few.
+    // The pipelined kernels need 16-byte aligned operands; a misaligned call is planned without them.
     const bool aligned = reinterpret_cast<uintptr_t>(image) % 16 == 0 && reinterpret_cast<uintptr_t>(filter) % 16 == 0;
     const int key = dtype | (aligned ? 0 : 0x100);
-    static std::vector<Entry> cache;
     cacnn_plan plan;
-    bool hit = false;
-    {
-        std::lock_guard<std::mutex> lock(g_mutex);
-        for (const Entry& e : cache)
-            if (e.dtype == key && std::memcmp(&e.p, problem, sizeof(cacnn_problem)) == 0) {
-                plan = e.plan;
-                hit = true;
-                break;
-            }
-    }
-    if (!hit) {
+    if (!lookup_plan(*problem, key, &plan)) {
         const int rc = plan_impl(problem, dtype, nullptr, &plan, aligned);
         if (rc != CACNN_OK) return rc;
-        std::lock_guard<std::mutex> lock(g_mutex);
-        if (cache.size() >= 64) cache.erase(cache.begin());
-        cache.push_back(Entry{*problem, key, plan});
+        store_plan(*problem, key, plan);
     }
     return launch_with(*problem, dtype, plan.variant, plan.b_c, plan.b_r, plan.b_s, plan.xcd_split_k, image, filter, out,
                        hip_stream);
@@ -792,6 +803,63 @@ int cacnn_work_division(const cacnn_problem* problem, double M_words, int32_t p_
                 }
     *out_a = best_a;
     *out_bound = best_b;
+    return CACNN_OK;
+}
+
+int cacnn_tune(const cacnn_problem* problem, int dtype, const void* image, const void* filter, void* out, void* hip_stream,
+               cacnn_plan* out_plan) {
+    if (!problem || !image || !filter || !out) return CACNN_ERR_NULL;
+    if (dtype != CACNN_F32 && dtype != CACNN_BF16_F32ACC) return CACNN_ERR_UNSUPPORTED;
+    if (!valid_problem(problem)) return CACNN_ERR_INVALID_ARG;
+    {
+        const int vrc = validate_dims(*problem);
+        if (vrc != CACNN_OK) return vrc;
+    }
+    if (!have_device()) return CACNN_ERR_NO_DEVICE;
+    const bool aligned = reinterpret_cast<uintptr_t>(image) % 16 == 0 && reinterpret_cast<uintptr_t>(filter) % 16 == 0;
+    const int key = dtype | (aligned ? 0 : 0x100);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return CACNN_ERR_LAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return CACNN_ERR_LAUNCH;
+    }
+    // every kernel variant that accepts the problem, each with the contraction tile the cost model likes best for it
+    Choice best;
+    float best_ms = 0.f;
+    int status = CACNN_ERR_UNSUPPORTED;
+    for (int vi = 0; vi < num_variants(); ++vi) {
+        const VariantInfo& v = variant(vi).info;
+        if (v.dtype != dtype || (v.pipelined && !aligned)) continue;
+        Choice c;
+        if (!evaluate(vi, *problem, kDefaultMachine, &c)) continue;
+        constexpr int WARM = 2, TIMED = 5;
+        bool ok = true;
+        for (int i = 0; i < WARM + TIMED && ok; ++i) {
+            if (i == WARM) ok = hipEventRecord(e0, stream) == hipSuccess;
+            ok = ok && launch_with(*problem, dtype, vi, c.g.CT, c.g.bR, c.g.bS, 0, image, filter, out, hip_stream) == CACNN_OK;
+        }
+        if (!ok) continue;
+        float ms = 0.f;
+        if (hipEventRecord(e1, stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+            hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+            status = CACNN_ERR_LAUNCH;
+            continue;
+        }
+        if (best.variant < 0 || ms < best_ms) {
+            best = c;
+            best_ms = ms;
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (best.variant < 0) return status;
+    cacnn_plan plan;
+    const int rc = fill_plan(*problem, dtype, kDefaultMachine, best, &plan);
+    if (rc != CACNN_OK) return rc;
+    store_plan(*problem, key, plan);
+    if (out_plan) *out_plan = plan;
     return CACNN_OK;
 }
 

@@ -251,3 +251,41 @@ def test_every_xcd_division_computes_the_same_convolution(env, dtype):
         with pytest.raises(cc.CacnnError) as e:
             gu.run_gpu(cc, torch, odd, i2, f2, plan=plan)
         assert e.value.status == 2
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tuned_plan_is_correct_and_no_slower_than_the_planned_one(env, dtype):
+    """cacnn_tune times every variant that accepts the problem and remembers the fastest: `out` holds a valid result
+    afterwards, later cacnn_conv_forward calls use the remembered plan and still match the oracle, and that plan is
+    not slower than the cost model's choice (it was among the candidates)."""
+    cc, torch = env
+    cfg = ci.custom("tune", 8, 64, 64, 28, 28, 3, 3, 1, 1, dtype=dtype, dist="normal", seed=77)
+    img, flt = ci.make_inputs(cfg)
+    ref, ab = gu.oracle_full(cfg, img, flt)
+    d_img, d_flt = gu.upload(cfg, img, flt, torch)
+    d_out = torch.full((int(np.prod(cfg.out_shape)),), float("nan"), dtype=torch.float32, device="cuda:0")
+    dt = gu.dtype_code(cfg)
+
+    def timed():
+        for _ in range(20):
+            cc.cacnn_conv_forward(cfg.dims, dt, d_img, d_flt, d_out)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(100):
+            cc.cacnn_conv_forward(cfg.dims, dt, d_img, d_flt, d_out)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / 100
+
+    planned = cc.cacnn_tile_plan(cfg.dims, dt)
+    t_planned = timed()
+    tuned = cc.cacnn_tune(cfg.dims, dt, d_img, d_flt, d_out)
+    torch.cuda.synchronize()
+    gu.assert_parity(cfg, d_out.cpu().numpy().reshape(cfg.out_shape), ref, ab, "out after cacnn_tune")
+    say(f"[tune] {dtype}: planned '{cc.cacnn_variant_name(planned.variant)}' {t_planned * 1e3:.1f} us, "
+        f"tuned '{cc.cacnn_variant_name(tuned.variant)}' b_c={tuned.b_c} b_r={tuned.b_r} b_s={tuned.b_s}")
+    d_out.fill_(float("nan"))
+    t_tuned = timed()
+    gu.assert_parity(cfg, d_out.cpu().numpy().reshape(cfg.out_shape), ref, ab, "cacnn_conv_forward after cacnn_tune")
+    say(f"[tune] {dtype}: tuned plan {t_tuned * 1e3:.1f} us")
+    assert t_tuned <= 1.25 * t_planned

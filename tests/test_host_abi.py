@@ -292,3 +292,17 @@ def test_plan_divides_the_xcds_by_output_channels_only_where_the_filter_is_the_b
     img, flt = 16 * 16 * 512 * 16 * 2, 512 * 9 * 512 * 2
     sums = {ak: ak * img + (8 // ak) * flt for ak in (1, 2, 4, 8)}
     assert p.xcd_split_k == min(sums, key=sums.get)
+
+
+def test_tune_rejects_bad_arguments_and_needs_a_gpu():
+    ok = (2, 4, 4, 3, 3, 2, 2, 1, 1)
+    for dims, dtype, img, flt, out, status in ((ok, 0, 0, 16, 16, 1), (ok, 0, 16, 0, 16, 1), (ok, 0, 16, 16, 0, 1),
+                                               (ok, 5, 16, 16, 16, 3), ((2, 4, 4, 0, 3, 2, 2, 1, 1), 0, 16, 16, 16, 2)):
+        with pytest.raises(cc.CacnnError) as e:
+            cc.cacnn_tune(dims, dtype, img, flt, out, stream=0)
+        assert e.value.status == status, (dims, dtype, img, flt, out)
+    import torch
+    if not torch.cuda.is_available():
+        with pytest.raises(cc.CacnnError) as e:
+            cc.cacnn_tune(ok, 0, 16, 32, 48, stream=0)
+        assert e.value.status == 5
