@@ -1901,6 +1901,13 @@ __device__ __forceinline__ void lds_store16_seq(uint32_t addr, const V* regs, st
 // s_waitcnt immediate that waits only for the vector-memory counter to drop to n (6 bits: [3:0] and [15:14])
 constexpr int vmcnt_only(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
+// `after` is the accumulator the last MFMA in front of the barrier writes: an MFMA touches no memory, so nothing else
+// keeps the compiler from moving the barrier up over the MFMAs that are meant to cover the latency of the reads it
+// waits for.
+__device__ __forceinline__ void lds_done_then_barrier_known(f32x16& after) {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : "+v"(after)::"memory");
+    __builtin_amdgcn_s_waitcnt(vmcnt_only(63) & ~(15 << 8));
+}
 __device__ __forceinline__ void lds_done_then_barrier_known() {
     lds_done_then_barrier();
     // true already: restated in a form the compiler's wait-count bookkeeping reads, so that it does not make the
@@ -2060,7 +2067,7 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
                 // hand the buffer back once the last fragments have landed, read the next unit's first fragments
                 // under this step's MFMAs
                 boff = boff + BUF == GEO::NBUF * BUF ? 0u : boff + BUF;
-                lds_done_then_barrier_known();
+                lds_done_then_barrier_known(acc[0][NBLK - 1]);
                 load_step(al + boff, xl + boff, 0, 0);
             }
             mfma_step(1);
@@ -2069,7 +2076,7 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
             // unit, in front of the MFMAs that need them
             asm volatile("" ::: "memory");
             --left;
-            if (--in_tile == 0) {
+            if (__builtin_expect(--in_tile == 0, 0)) {
                 const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
 #pragma unroll
                 for (int n = 0; n < NBLK; ++n) {
@@ -2263,7 +2270,7 @@ __global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a
                     // fragments under this group's MFMAs
                     ioff = ioff + IBUF == GEO::NBUF_I * IBUF ? 0u : ioff + IBUF;
                     foff = FBUF - foff;
-                    lds_done_then_barrier_known();
+                    lds_done_then_barrier_known(acc[0][NBLK - 1]);
                     load_group(al + foff, xl + ioff, 0, 0);
                 }
                 mfma_group(grp & 1);
@@ -2272,7 +2279,7 @@ __global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a
             // keep the reads above where they are (the compiler would sink them to the top of the next unit)
             asm volatile("" ::: "memory");
             --left;
-            if (--in_tile == 0) {
+            if (__builtin_expect(--in_tile == 0, 0)) {
                 const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
 #pragma unroll
                 for (int n = 0; n < NBLK; ++n) {
@@ -2459,7 +2466,7 @@ __global__ void __launch_bounds__(512) conv_f32_stem_direct_kernel(const KernelA
                         flt_k0 = ntc.k0;
                     }
                     ioff = ioff + IBUF == GEO::NBUF * IBUF ? 0u : ioff + IBUF;
-                    lds_done_then_barrier_known();
+                    lds_done_then_barrier_known(acc[0][NBLK - 1]);
                     load_group(xl + ioff, 0, 0);
                 }
                 mfma_group(gi, gi & 1);
