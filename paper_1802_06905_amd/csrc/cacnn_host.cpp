@@ -200,7 +200,7 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
     g.flt_resident = (g.n_slices == 1 && ceil_div(p.K, v.KT()) == 1 && v.fx_ct == 0) ? 1 : 0;
     const int nbuf_f = g.flt_resident ? 1 : 2;
     if (v.fx_lds > 0) {
-        // a fixed-geometry kernel with its own LDS layout: nothing to derive here
+        // a fixed-geometry kernel: its own LDS layout, contraction tile and strides, a shape the tiles divide exactly
         g.lds_bytes = v.fx_lds;
         g.img_items = g.flt_items = 1;
         g.legal = CT == v.fx_ct && bR == v.fx_br && bS == v.fx_bs && g.YS == v.fx_ys && p.sigma_w == v.fx_sw &&
@@ -294,13 +294,6 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
         }
     }
     if (v.reuse_r > 0 && (bR != v.reuse_r || p.sigma_w != 1)) g.legal = false;
-    if (v.fx_ct > 0) {
-        // fixed-geometry kernels: their own contraction tile and strides, a shape the tiles divide exactly
-        if (CT != v.fx_ct || bR != v.fx_br || bS != v.fx_bs || g.YS != v.fx_ys || p.sigma_w != v.fx_sw ||
-            p.sigma_h != v.fx_sh || p.R != bR || p.S % bS != 0 || p.C % CT != 0 || p.B % v.TB != 0 ||
-            p.W % v.TW != 0 || p.H % v.TH != 0 || p.K % v.KT() != 0 || !vec_img)
-            g.legal = false;
-    }
     if (v.pipelined) {
         const int64_t thr = v.staging_threads();
         if (g.img_items > v.MAXI * thr || (!g.flt_resident && g.flt_items > v.MAXF * thr)) g.legal = false;

@@ -40,11 +40,11 @@ struct VariantInfo {
     int reuse_r;  // > 0: filter-row reuse path compiled for exactly this many taps per contraction tile (sigma_w = 1);
                   // -4: fp32 kernel with the 16-byte-fragment LDS layout (c-slices in multiples of 4 channels)
     float tune;   // measured time of this variant relative to what the planner's cost model predicts (1 = as modelled)
-    // fixed-geometry kernels: the only contraction tile (c-slice, b_r, b_s) the kernel was compiled for; 0 = any
+    // fixed-geometry kernels: the only contraction tile (c-slice, b_r, b_s) the kernel was compiled for (0 = any)
     // and the staged Image rows sigma_h*(TH-1)+b_s it assumes
     int fx_ct = 0, fx_br = 0, fx_bs = 0, fx_ys = 0;
     int fx_sw = 1, fx_sh = 1;   // the strides it assumes
-    int fx_lds = 0;             // > 0: the kernel has its own LDS layout of this many bytes
+    int fx_lds = 0;             // the fixed-geometry kernels' own LDS layout, bytes (they all have one)
     // measured on MI355X with every CU busy: microseconds per unit (tile and contraction slice) of one workgroup, and the
     // fixed part of a launch (first loads, last Out tile, dispatch); the planner prices these kernels with them
     float fx_unit_us = 0.f, fx_fixed_us = 0.f;
