@@ -2626,12 +2626,12 @@ static const Variant g_variants[] = {
     CACNN_WS_VARIANT(0, "f32 ws4 k64 b16w4h2 w2x2 m1n2", 1.0f, 2, 2, 1, 2, 16, 4, 2, 3, 10, -4,
                      conv_f32v4_ws_kernel<2, 2, 1, 2, 16, 4, 2, 3, 10>),
     // fixed-geometry kernels (3x3 taps, unit strides, shapes the tiles divide exactly)
-    CACNN_F32_DIRECT_VARIANT("f32 fxd k64 b8w4h4 w2x2 m1n2 c16r3s3", 4.2f, 4.5f, 4, 4),
-    CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 0.9f, 8.0f, 7, 1),
-    CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.6f, 4.0f, 2, 2),
+    CACNN_F32_DIRECT_VARIANT("f32 fxd k64 b8w4h4 w2x2 m1n2 c16r3s3", 4.4f, 3.0f, 4, 4),
+    CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.0f, 4.5f, 7, 1),
+    CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.62f, 4.2f, 2, 2),
     // fixed geometry for the stem-layer shape: 7x7 taps, strides 2, three channels
     {{"f32 fxsd k64 b32w2h2 w2x2 m1n2 c3r7s7 s2", 0, 2, 2, 1, F32StemDirect<2, 2>::NBLK, 32, 2, 2, 2, 1, 1, 1, 0, 1.0f, 3, 7, 7,
-      F32StemDirect<2, 2>::YS, 2, 2, F32StemDirect<2, 2>::LDS_BYTES, 5.0f, 5.0f, 1},
+      F32StemDirect<2, 2>::YS, 2, 2, F32StemDirect<2, 2>::LDS_BYTES, 5.15f, 4.5f, 1},
      [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {
          static bool attr_done = false;
          if (!F32StemDirect<2, 2>::matches_host(a) || lds != (size_t)F32StemDirect<2, 2>::LDS_BYTES) return 1;
