@@ -124,6 +124,21 @@ def shape_report(cc, cfg, sec):
         return max(4 * b.term[0], esz * max(b.term[1:]))
     lb_bytes = bound_bytes(LDS_BYTES)
     hbm = committed_traffic(cfg.name)
+
+    def xcd_level_bound_bytes():
+        # Two levels: an LDS tile inside an XCD's share.  The HBM-side bytes are the misses of eight 4 MiB L2s, so the
+        # bound that applies to them is Section 7's (eight processors, M = one L2) for the division the launch uses:
+        # a_K groups of output channels x 8 / a_K ranges of positions (only the product a_B a_W a_H enters the bound)
+        ak = max(1, plan.xcd_split_k)
+        rest, a = 8 // ak, [1, ak, 1, 1]
+        for i, extent in ((0, cfg.B), (3, cfg.H), (2, cfg.W)):
+            f = 1
+            while f * 2 <= min(rest, extent):
+                f *= 2
+            a[i], rest = f, rest // f
+        b = cc.cacnn_parallel_bound(cfg.dims, 4 * 1024 * 1024 / esz, a)
+        return max(4 * b.term[0], esz * max(b.term[1:])), a
+    xcd_bound, xcd_div = xcd_level_bound_bytes()
     return {
         "us": sec * 1e6, "tflops": tflops, "frac_mfma_peak": tflops / MFMA_PEAK_TFLOPS[cfg.dtype],
         "frac_hbm_roofline": compulsory / sec / 1e9 / HBM_PEAK_GBS,
@@ -134,6 +149,8 @@ def shape_report(cc, cfg, sec):
         "paper_bound_bytes_at_M_l2": bound_bytes(4 * 1024 * 1024),
         "hbm_bytes_over_bound_at_M_lds": (hbm / lb_bytes) if hbm else None,
         "hbm_bytes_over_bound_at_M_l2": (hbm / bound_bytes(4 * 1024 * 1024)) if hbm else None,
+        "xcd_division_a_B_a_K_a_W_a_H": xcd_div, "paper_parallel_bound_bytes_8_xcds_M_l2": xcd_bound,
+        "hbm_bytes_over_parallel_bound": (hbm / xcd_bound) if hbm else None,
         "planned_staged_bytes": esz * (plan.predicted_words - n_out) + 4 * n_out,
         "variant": cc.cacnn_variant_name(plan.variant), "grid": plan.grid[0], "lds_bytes": plan.lds_bytes_used,
         "b_c": plan.b_c, "hbm_bytes_profiled": hbm,
