@@ -1915,6 +1915,41 @@ __device__ __forceinline__ void lds_done_then_barrier_known() {
     __builtin_amdgcn_s_waitcnt(vmcnt_only(63) & ~(15 << 8));
 }
 
+// The staging schedule of the direct kernels: unit u's loads are issued two units ahead (register set and Filter
+// buffer u % 2), and a unit is announced at the barrier once its loads are in, which the load counter says when at most
+// the next unit's LOADS loads are outstanding (loads complete in order).  Every path is straight-line code or a loop
+// whose state at the back edge equals its state on entry, so the compiler's own count of outstanding loads (it waits
+// for a Filter register before the store that reads it) stays exact; a load issued under a condition would make it
+// wait for everything.
+template <int LOADS, class Issue, class Announce>
+__device__ __forceinline__ void direct_staging_schedule(int total, Issue issue, Announce announce) {
+    using NextUnit = std::integral_constant<int, LOADS>;
+    using Nothing = std::integral_constant<int, 0>;
+    if (total == 1) {
+        issue(0);
+        announce(0, Nothing{});
+    } else if (total >= 2) {
+        issue(0);
+        issue(1);
+        int u = 0;
+        for (; u + 4 <= total; u += 2) {
+            announce(0, NextUnit{});
+            issue(0);               // the multiplying waves have left the buffer two units back: refill it
+            announce(1, NextUnit{});
+            issue(1);
+        }
+        if (total - u == 3) {
+            announce(0, NextUnit{});
+            issue(0);
+            announce(1, NextUnit{});
+            announce(0, Nothing{});
+        } else {
+            announce(0, NextUnit{});
+            announce(1, Nothing{});
+        }
+    }
+}
+
 // 64 lanes x 16 bytes from global memory (lane offset voff, wave-uniform offset soff) to dst, dst + 16, ... in lane order.
 // dst is wave-uniform.  Not inside the kernel template: the host pass of the compiler rejects the 16-byte form there.
 __device__ __forceinline__ void load_16_bytes_per_lane_to_lds(__amdgpu_buffer_rsrc_t r, CACNN_LDS(char)* dst, uint32_t voff,
@@ -1989,34 +2024,7 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
             lds_done_then_barrier();
             boff_store = boff_store + BUF == GEO::NBUF * BUF ? 0 : boff_store + BUF;
         };
-        using NextUnit = std::integral_constant<int, GEO::LOADS>;
-        using Nothing = std::integral_constant<int, 0>;
-        // Every path below is straight-line code or a loop whose state at the back edge equals its state on entry,
-        // so the compiler's own count of outstanding loads (it waits for a Filter register before the store that
-        // reads it) is exact; a load issued under a condition would make it wait for everything.
-        if (total == 1) {
-            issue(0);
-            announce(0, Nothing{});
-        } else if (total >= 2) {
-            issue(0);
-            issue(1);
-            int u = 0;
-            for (; u + 4 <= total; u += 2) {
-                announce(0, NextUnit{});
-                issue(0);               // the multiplying waves have left the buffer two units back: refill it
-                announce(1, NextUnit{});
-                issue(1);
-            }
-            if (total - u == 3) {
-                announce(0, NextUnit{});
-                issue(0);
-                announce(1, NextUnit{});
-                announce(0, Nothing{});
-            } else {
-                announce(0, NextUnit{});
-                announce(1, Nothing{});
-            }
-        }
+        direct_staging_schedule<GEO::LOADS>(total, issue, announce);
     } else {
         const int wm = wave_id % WM, wn = wave_id / WM;
         const int j = lane & 31, g = lane >> 5, i16 = lane & 15, jhalf = (lane >> 4) & 1;
@@ -2199,33 +2207,7 @@ __global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a
             else lds_store16_seq<FBUF, CT * 4>(fl0, freg[1], std::make_index_sequence<MAXF>{});
             lds_done_then_barrier();
         };
-        using NextUnit = std::integral_constant<int, GEO::LOADS>;
-        using Nothing = std::integral_constant<int, 0>;
-        // straight-line phases and a loop whose state at the back edge equals its state on entry: the compiler's own
-        // count of outstanding loads (it waits for a Filter register before the store that reads it) stays exact
-        if (total == 1) {
-            issue(0);
-            announce(0, Nothing{});
-        } else if (total >= 2) {
-            issue(0);
-            issue(1);
-            int u = 0;
-            for (; u + 4 <= total; u += 2) {
-                announce(0, NextUnit{});
-                issue(0);               // the multiplying waves have left the Image buffer two units back: refill it
-                announce(1, NextUnit{});
-                issue(1);
-            }
-            if (total - u == 3) {
-                announce(0, NextUnit{});
-                issue(0);
-                announce(1, NextUnit{});
-                announce(0, Nothing{});
-            } else {
-                announce(0, NextUnit{});
-                announce(1, Nothing{});
-            }
-        }
+        direct_staging_schedule<GEO::LOADS>(total, issue, announce);
     } else {
         const int wm = wave_id % WM, wn = wave_id / WM;
         const int j = lane & 31, g = lane >> 5;
