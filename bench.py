@@ -91,6 +91,35 @@ def machine_sustained(cc, torch, ci, np):
     return out
 
 
+def graph_replay_us(cc, torch, ci, np, cfg, launches=200, replays=20):
+    """Per-launch time of the workload when `launches` back-to-back launches are captured in one HIP graph and replayed:
+    what a launch-bound caller gets (the plain figure is bound by the host's launch path for a problem as small as c1)."""
+    img, flt = ci.make_inputs(cfg)
+    d_img = torch.from_numpy(img.reshape(-1)).cuda()
+    d_flt = torch.from_numpy(flt.reshape(-1)).cuda()
+    d_out = torch.empty(int(np.prod(cfg.out_shape)), dtype=torch.float32, device="cuda:0")
+    cc.cacnn_conv_forward(cfg.dims, 0, d_img, d_flt, d_out)     # plan and kernel set-up happen outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(launches):
+                cc.cacnn_conv_forward(cfg.dims, 0, d_img, d_flt, d_out)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        graph.replay()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(replays):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / (replays * launches)
+
+
 def committed_traffic(name):
     """HBM-side bytes of one launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs, scaled
     by the copy-kernel calibration recorded there).  Counters cannot be read from inside this process, so the
@@ -416,6 +445,8 @@ def main():
             s, _, _ = time_config(cc, torch, ci, np, c, args.steps, args.warmup)
             shapes[name] = shape_report(cc, c, s)
             shapes[name]["frac_mfma_sustained"] = shapes[name]["tflops"] / sustained[f"mfma_{c.dtype}_tflops"]
+            if name == "c1":
+                shapes[name]["us_per_launch_in_a_hip_graph"] = graph_replay_us(cc, torch, ci, np, c)
         result["shapes"] = shapes
         result["pooling"] = pooling_report(cc, torch, ci, np, args.steps, args.warmup, not args.no_cpu)
     print(json.dumps(result))

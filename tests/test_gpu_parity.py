@@ -289,3 +289,36 @@ def test_tuned_plan_is_correct_and_no_slower_than_the_planned_one(env, dtype):
     gu.assert_parity(cfg, d_out.cpu().numpy().reshape(cfg.out_shape), ref, ab, "cacnn_conv_forward after cacnn_tune")
     say(f"[tune] {dtype}: tuned plan {t_tuned * 1e3:.1f} us")
     assert t_tuned <= 1.25 * t_planned
+
+
+def test_launches_can_be_captured_in_a_graph_and_replayed(env):
+    """cacnn_conv_forward only enqueues a kernel, so a run of launches can be captured into a HIP graph (what a
+    launch-bound caller would do with c1).  Every replay, with eager work and synchronisation between the replays, must
+    reproduce the eager result bit for bit."""
+    cc, torch = env
+    cfg = ci.CONFIGS["c1"]
+    img, flt = ci.make_inputs(cfg)
+    ref, ab = gu.oracle_full(cfg, img, flt)
+    d_img, d_flt = gu.upload(cfg, img, flt, torch)
+    n_out = int(np.prod(cfg.out_shape))
+    eager = torch.full((n_out,), float("nan"), dtype=torch.float32, device="cuda:0")
+    cc.cacnn_conv_forward(cfg.dims, 0, d_img, d_flt, eager)          # also plans and sets the kernel up outside the capture
+    torch.cuda.synchronize()
+    gu.assert_parity(cfg, eager.cpu().numpy().reshape(cfg.out_shape), ref, ab, "eager")
+    outs = [torch.full((n_out,), float("nan"), dtype=torch.float32, device="cuda:0") for _ in range(4)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for o in outs:
+                cc.cacnn_conv_forward(cfg.dims, 0, d_img, d_flt, o)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for o in outs:
+            o.fill_(float("nan"))                                    # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, o in enumerate(outs):
+            assert torch.equal(o, eager), f"replay {rep}, launch {i}"
