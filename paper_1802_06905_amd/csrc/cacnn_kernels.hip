@@ -14,7 +14,7 @@
 // Every staged Image word is reused for all b_k channels and for every (r,s) shift that touches it -- the extra
 // (RS/sigma_w sigma_h)^(1/2) reuse over matmul that the small-filter bound of Section 4.3 expresses.
 //
-// Kernel families in this file, in order: direct (one workgroup per tile, any shape), pipelined persistent, wave-
+// Kernel families in this file, in order: one tile per workgroup (any shape), pipelined persistent, wave-
 // specialised (staging waves + multiplying waves), and fixed-geometry wave-specialised kernels for 3x3 unit-stride
 // shapes and for the 7x7 stride-2 three-channel stem shape; the variant table at the end lists what is compiled.
 #include <hip/hip_runtime.h>
