@@ -215,7 +215,7 @@ def test_error_paths_enqueue_nothing(env):
 def test_every_xcd_division_computes_the_same_convolution(env, dtype):
     """Section 7 with the XCDs as processors: the tile order may divide the output channels into 1, 2, 4 or 8 groups.
     Every division is a permutation of the tile list, so every one must give the oracle's result: on a shape with 8
-    k-tiles and several position tiles, for the planner's kernel, a direct one and a fixed-geometry one.  Divisions that do not divide the k-tile count are refused."""
+    k-tiles and several position tiles, for the planner's kernel, a one-tile-per-workgroup one and a fixed-geometry one.  Divisions that do not divide the k-tile count are refused."""
     cc, torch = env
     B, C = (8, 32) if dtype == "f32" else (64, 64)
     cfg = ci.custom("xcd_div", B, C, 512, 8, 4, 3, 3, 1, 1, dtype=dtype, dist="normal", seed=321)
@@ -224,7 +224,7 @@ def test_every_xcd_division_computes_the_same_convolution(env, dtype):
     base = cc.cacnn_tile_plan(cfg.dims, gu.dtype_code(cfg))
     names = {cc.cacnn_variant_name(i): i for i in variants_for(cc, dtype)}
     picks = {"planner": (base.variant, base.b_c, base.b_r, base.b_s)}
-    picks["direct"] = (names[f"{dtype} k64 b8w4h4 w2x2 m1n2"], 16, 3, 3)
+    picks["one tile per workgroup"] = (names[f"{dtype} k64 b8w4h4 w2x2 m1n2"], 16, 3, 3)
     fx = [n for n in names if " fxd " in n and ("b8w4h4" in n or "b64w2h2" in n)]
     assert fx, "no fixed-geometry kernel for this shape"
     picks["fixed"] = (names[fx[0]], 16 if dtype == "f32" else 32, 3, 3 if dtype == "f32" else 1)
