@@ -28,6 +28,7 @@ namespace cacnn {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv& f) {
@@ -1904,7 +1905,8 @@ constexpr int vmcnt_only(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) 
 // `after` is the accumulator the last MFMA in front of the barrier writes: an MFMA touches no memory, so nothing else
 // keeps the compiler from moving the barrier up over the MFMAs that are meant to cover the latency of the reads it
 // waits for.
-__device__ __forceinline__ void lds_done_then_barrier_known(f32x16& after) {
+template <class ACC>
+__device__ __forceinline__ void lds_done_then_barrier_known(ACC& after) {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : "+v"(after)::"memory");
     __builtin_amdgcn_s_waitcnt(vmcnt_only(63) & ~(15 << 8));
 }
@@ -1917,35 +1919,40 @@ __device__ __forceinline__ void lds_done_then_barrier_known() {
 
 // The staging schedule of the direct kernels: unit u's loads are issued two units ahead (register set and Filter
 // buffer u % 2), and a unit is announced at the barrier once its loads are in, which the load counter says when at most
-// the next unit's LOADS loads are outstanding (loads complete in order).  Every path is straight-line code or a loop
-// whose state at the back edge equals its state on entry, so the compiler's own count of outstanding loads (it waits
-// for a Filter register before the store that reads it) stays exact; a load issued under a condition would make it
-// wait for everything.
+// the next unit's LOADS loads are outstanding (loads complete in order).  The first unit is announced before anything
+// else is fetched: at the start of a launch every compute unit fetches at once and the L2 caches' bandwidth sets the
+// pace, so with two units requested up front the multiplying waves would start one unit's transfer time later.
+// Every path is straight-line code or a loop whose state at the back edge equals its state on entry, so the
+// compiler's own count of outstanding loads (it waits for a Filter register before the store that reads it) stays
+// exact; a load issued under a condition would make it wait for everything.
 template <int LOADS, class Issue, class Announce>
 __device__ __forceinline__ void direct_staging_schedule(int total, Issue issue, Announce announce) {
     using NextUnit = std::integral_constant<int, LOADS>;
     using Nothing = std::integral_constant<int, 0>;
-    if (total == 1) {
-        issue(0);
-        announce(0, Nothing{});
-    } else if (total >= 2) {
-        issue(0);
+    if (total <= 0) return;
+    issue(0);
+    announce(0, Nothing{});
+    if (total == 2) {
         issue(1);
-        int u = 0;
-        for (; u + 4 <= total; u += 2) {
-            announce(0, NextUnit{});
-            issue(0);               // the multiplying waves have left the buffer two units back: refill it
+        announce(1, Nothing{});
+    } else if (total >= 3) {
+        issue(1);
+        issue(0);                   // unit 2: set 0 went to LDS with the announcement of unit 0
+        int issued = 3;
+        for (; issued + 2 <= total; issued += 2) {
             announce(1, NextUnit{});
-            issue(1);
-        }
-        if (total - u == 3) {
+            issue(1);               // the multiplying waves have left the buffer two units back: refill it
             announce(0, NextUnit{});
             issue(0);
+        }
+        if (total - issued == 1) {
             announce(1, NextUnit{});
-            announce(0, Nothing{});
-        } else {
+            issue(1);
             announce(0, NextUnit{});
             announce(1, Nothing{});
+        } else {
+            announce(1, NextUnit{});
+            announce(0, Nothing{});
         }
     }
 }
@@ -2117,8 +2124,8 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
 // before the unit is announced).
 template <int TW, int TH>
 struct F32DirectFixed {
-    static constexpr int TB = 8, KT = 64, WM = 2, WN = 2, CT = 16, BS = 3, BR = 3, NBLK = TH / WN;
-    static constexpr int XS = TW + BR - 1, YS = TH - 1 + BS;
+    static constexpr int TB = 8, KT = 64, WM = 2, WN = 2, CT = 16, BS = 3, BR = 3, NBLK = TH / WN, TW_ = TW, TH_ = TH;
+    static constexpr int XS = TW + BR - 1, YS = TH - 1 + BS, YSL = YS, CWAVES = WM * WN;
     static constexpr int POS = CT * TB * 4;                         // bytes of one (x, y) position
     static constexpr int XP = YS * POS + 32;                        // bytes of one x plane
     static constexpr int IMG_BYTES = XS * XP, NBUF_I = 3;
@@ -2142,13 +2149,70 @@ struct F32DirectFixed {
     }
 };
 
+// The staging waves of the fp32 direct kernels (GEO: F32DirectFixed or F32Direct16): Image chunks straight into LDS,
+// Filter items through registers.
+template <class GEO>
+__device__ __forceinline__ void f32_direct_stage(const KernelArgs& a, CACNN_LDS(char)* const lds, int tid, int wave_id,
+                                                 int lane, int total) {
+    constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, BR = GEO::BR, TW = GEO::TW_, TH = GEO::TH_;
+    constexpr int YS = GEO::YSL, XP = GEO::XP, POS = GEO::POS, FP = GEO::FP;   // YS: the rows a plane holds in LDS
+    constexpr int IBUF = GEO::IMG_BYTES, FBUF = GEO::FLT_BYTES, CTHREADS = GEO::CWAVES * 64;
+    const int pw = wave_id - GEO::CWAVES, stid = tid - CTHREADS;
+    constexpr int MAXF = GEO::MAXF, CPW = GEO::CPW, PT = GEO::PT;
+    // Image: lane L of a chunk load fetches 16-byte piece L % 32 (channel (L % 32) / 2, images 4 * (L % 2)..) of
+    // position y + L / 32
+    const uint32_t row_bytes = (uint32_t)a.B * 4u;
+    const uint32_t ivoff = (uint32_t)(lane >> 5) * (uint32_t)a.C * row_bytes + (uint32_t)((lane & 31) >> 1) * row_bytes +
+                           (uint32_t)(lane & 1) * 16u;
+    uint32_t isoff[CPW], ildst[CPW];
+#pragma unroll
+    for (int i = 0; i < CPW; ++i) {
+        // the waves that would run out of chunks fetch the last one again (same words to the same place)
+        const int ch = min(pw + GEO::PW * i, GEO::CHUNKS - 1);
+        const int x = ch / (YS / 2), yy = ch % (YS / 2);
+        isoff[i] = (uint32_t)((x * a.IH + 2 * yy) * a.C) * row_bytes;
+        ildst[i] = (uint32_t)(x * XP + yy * 2 * POS);
+    }
+    // Filter: thread (kl = stid / 4, c4 = stid % 4) fetches the 16 bytes of channels 4*c4.. of output channel kl for
+    // every tap (r, s) of the unit: one global offset and one LDS address per thread, the tap in the instruction
+    static_assert(MAXF == BR * BS && PT == KT * (CT / 4), "direct fp32 geometry: one Filter item per thread and tap");
+    const int f_c4 = stid % (CT / 4), f_kl = stid / (CT / 4);
+    const uint32_t fg0 = ((uint32_t)f_kl * a.R * a.S * a.C + f_c4 * 4) * 4u;
+    const uint32_t fl0 = (uint32_t)(uintptr_t)(lds + GEO::FLT_OFF + f_kl * FP + f_c4 * 16);
+    uint32_t fsoff[MAXF];
+#pragma unroll
+    for (int i = 0; i < MAXF; ++i) fsoff[i] = (uint32_t)((i / BS) * a.S + i % BS) * (uint32_t)a.C * 4u;
+    FxWalk<4, KT, TB, TW, TH, CT, BS> lu;     // next unit to fetch
+    lu.init(a);
+    f32x4 freg[2][MAXF];
+    int ioff_issue = 0;                       // Image buffer the next fetch goes to
+    auto issue = [&](int set) {
+        const __amdgpu_buffer_rsrc_t ri = lu.img(a), rf = lu.flt(a);
+#pragma unroll
+        for (int i = 0; i < CPW; ++i) load_16_bytes_per_lane_to_lds(ri, lds + ioff_issue + ildst[i], ivoff, isoff[i]);
+#pragma unroll
+        for (int i = 0; i < MAXF; ++i) freg[set][i] = buf_load_f32x4(rf, fg0, fsoff[i]);
+        lu.next(a);
+        ioff_issue = ioff_issue + IBUF == GEO::NBUF_I * IBUF ? 0 : ioff_issue + IBUF;
+    };
+    // announce the unit whose Filter words are in register set `set` (also its Filter buffer): its loads are in
+    // once at most `later` younger loads are outstanding (loads complete in order).  No vector-ALU instruction
+    // on this path: next to an fp32 MFMA stream a staging wave practically never gets that issue port.
+    auto announce = [&](int set, auto later) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_only(decltype(later)::value));
+        if (set == 0) lds_store16_seq<0, CT * 4>(fl0, freg[0], std::make_index_sequence<MAXF>{});
+        else lds_store16_seq<FBUF, CT * 4>(fl0, freg[1], std::make_index_sequence<MAXF>{});
+        lds_done_then_barrier();
+    };
+    direct_staging_schedule<GEO::LOADS>(total, issue, announce);
+}
+
 template <int TW, int TH>
 __global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a) {
     using GEO = F32DirectFixed<TW, TH>;
     constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, BR = GEO::BR, WM = GEO::WM, NBLK = GEO::NBLK;
-    constexpr int XS = GEO::XS, YS = GEO::YS, XP = GEO::XP, POS = GEO::POS, FP = GEO::FP;
+    constexpr int XP = GEO::XP, POS = GEO::POS, FP = GEO::FP;
     constexpr int IBUF = GEO::IMG_BYTES, FBUF = GEO::FLT_BYTES;
-    constexpr int CTHREADS = GEO::WM * GEO::WN * 64;
     extern __shared__ __align__(16) f32x4 smem_v[];
     CACNN_LDS(char)* const lds = (CACNN_LDS(char)*)smem_v;
     const int tid = threadIdx.x;
@@ -2159,55 +2223,8 @@ __global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a
     int total = 0;
     for (int t = blockIdx.x; t < a.n_tiles; t += gridDim.x) total += upt;
 
-    if (wave_id >= GEO::WM * GEO::WN) {
-        const int pw = wave_id - GEO::WM * GEO::WN, stid = tid - CTHREADS;
-        constexpr int MAXF = GEO::MAXF, CPW = GEO::CPW, PT = GEO::PT;
-        // Image: lane L of a chunk load fetches 16-byte piece L % 32 (channel (L % 32) / 2, images 4 * (L % 2)..) of
-        // position y + L / 32
-        const uint32_t row_bytes = (uint32_t)a.B * 4u;
-        const uint32_t ivoff = (uint32_t)(lane >> 5) * (uint32_t)a.C * row_bytes + (uint32_t)((lane & 31) >> 1) * row_bytes +
-                               (uint32_t)(lane & 1) * 16u;
-        uint32_t isoff[CPW], ildst[CPW];
-#pragma unroll
-        for (int i = 0; i < CPW; ++i) {
-            // the waves that would run out of chunks fetch the last one again (same words to the same place)
-            const int ch = min(pw + GEO::PW * i, GEO::CHUNKS - 1);
-            const int x = ch / (YS / 2), yy = ch % (YS / 2);
-            isoff[i] = (uint32_t)((x * a.IH + 2 * yy) * a.C) * row_bytes;
-            ildst[i] = (uint32_t)(x * XP + yy * 2 * POS);
-        }
-        // Filter: thread (kl = stid / 4, c4 = stid % 4) fetches the 16 bytes of channels 4*c4.. of output channel kl for
-        // every tap (r, s) of the unit: one global offset and one LDS address per thread, the tap in the instruction
-        static_assert(MAXF == BR * BS && PT == KT * (CT / 4), "direct fp32 geometry: one Filter item per thread and tap");
-        const int f_c4 = stid % (CT / 4), f_kl = stid / (CT / 4);
-        const uint32_t fg0 = ((uint32_t)f_kl * a.R * a.S * a.C + f_c4 * 4) * 4u;
-        const uint32_t fl0 = (uint32_t)(uintptr_t)(lds + GEO::FLT_OFF + f_kl * FP + f_c4 * 16);
-        uint32_t fsoff[MAXF];
-#pragma unroll
-        for (int i = 0; i < MAXF; ++i) fsoff[i] = (uint32_t)((i / BS) * a.S + i % BS) * (uint32_t)a.C * 4u;
-        FxWalk<4, KT, TB, TW, TH, CT, BS> lu;     // next unit to fetch
-        lu.init(a);
-        f32x4 freg[2][MAXF];
-        int ioff_issue = 0;                       // Image buffer the next fetch goes to
-        auto issue = [&](int set) {
-            const __amdgpu_buffer_rsrc_t ri = lu.img(a), rf = lu.flt(a);
-#pragma unroll
-            for (int i = 0; i < CPW; ++i) load_16_bytes_per_lane_to_lds(ri, lds + ioff_issue + ildst[i], ivoff, isoff[i]);
-#pragma unroll
-            for (int i = 0; i < MAXF; ++i) freg[set][i] = buf_load_f32x4(rf, fg0, fsoff[i]);
-            lu.next(a);
-            ioff_issue = ioff_issue + IBUF == GEO::NBUF_I * IBUF ? 0 : ioff_issue + IBUF;
-        };
-        // announce the unit whose Filter words are in register set `set` (also its Filter buffer): its loads are in
-        // once at most `later` younger loads are outstanding (loads complete in order).  No vector-ALU instruction
-        // on this path: next to an fp32 MFMA stream a staging wave practically never gets that issue port.
-        auto announce = [&](int set, auto later) {
-            __builtin_amdgcn_s_waitcnt(vmcnt_only(decltype(later)::value));
-            if (set == 0) lds_store16_seq<0, CT * 4>(fl0, freg[0], std::make_index_sequence<MAXF>{});
-            else lds_store16_seq<FBUF, CT * 4>(fl0, freg[1], std::make_index_sequence<MAXF>{});
-            lds_done_then_barrier();
-        };
-        direct_staging_schedule<GEO::LOADS>(total, issue, announce);
+    if (wave_id >= GEO::CWAVES) {
+        f32_direct_stage<GEO>(a, lds, tid, wave_id, lane, total);
     } else {
         const int wm = wave_id % WM, wn = wave_id / WM;
         const int j = lane & 31, g = lane >> 5;
@@ -2275,6 +2292,157 @@ __global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a
         if (left > 0) {
             lds_done_then_barrier_known();      // unit 0 is staged
             load_group(al, xl, 0, 0);
+            while (left > 1) unit(std::true_type{});
+            unit(std::false_type{});
+        }
+    }
+}
+
+// ---- fixed geometry, fp32, 16x16 MFMA blocks -------------------------------------------------------------------------
+// The same staging and LDS layouts with the tile cut into 16x16 blocks (the 16x16x4 MFMA has the 32x32x2 one's rate):
+// a tile of 8 images x 2 x 7 positions is 7 column blocks of 16 (one output row each: 2 columns x 8 images), and each
+// of the four multiplying waves owns 16 of the 64 output channels and all 7 blocks.  112 columns per tile instead of
+// 128 is what a layer with 56 x 56 positions and 8 images wants: 224 tiles, one per compute unit, where tiles of 128
+// columns leave 60 of the 256 compute units idle.
+// An MFMA takes four contraction indices, one per quarter-wave q: channels 2q + e + 8h for the MFMA (h, e) of a
+// 16-channel slice, so a lane's Filter words for e = 0, 1 are one 8-byte read and the Image rows of the four
+// quarters are 64 bytes apart: with the two output columns of a block 32 bytes (mod 256) apart, the 64 lanes of an
+// Image read fall into 64 different banks.  For fixed (r, channel) the 9 Image rows y = 0..8 serve all 7 blocks and 3 taps s
+// (block j with tap s reads row j + s): 18 Image reads and 3 Filter reads per 42 MFMAs.  A plane holds 10 rows in LDS
+// (whole 1 KiB chunks of two rows; the tenth is fetched and never read).
+template <int TW, int TH>
+struct F32Direct16 {
+    static constexpr int TB = 8, KT = 64, CWAVES = 4, CT = 16, BS = 3, BR = 3, NBLK = TH, TW_ = TW, TH_ = TH;
+    static constexpr int XS = TW + BR - 1, YS = TH - 1 + BS, YSL = YS + (YS & 1);
+    static constexpr int POS = CT * TB * 4;                         // bytes of one (x, y) position
+    static constexpr int XP = YSL * POS + 32;                       // bytes of one x plane
+    static constexpr int IMG_BYTES = XS * XP, NBUF_I = 3;
+    static constexpr int FP = BR * BS * CT * 4 + 16;                // bytes of one Filter row
+    static constexpr int FLT_BYTES = KT * FP, NBUF_F = 2;
+    static constexpr int FLT_OFF = NBUF_I * IMG_BYTES;
+    static constexpr int LDS_BYTES = FLT_OFF + NBUF_F * FLT_BYTES;
+    static constexpr int PT = 256, PW = PT / 64;
+    static constexpr int CHUNKS = XS * YSL / 2, CPW = (CHUNKS + PW - 1) / PW;
+    static constexpr int FLT_ITEMS = KT * BR * BS * (CT / 4), MAXF = FLT_ITEMS / PT, MAXI = 1;
+    static constexpr int LOADS = CPW + MAXF;
+    static constexpr int GROUPS = BR * (CT / 8);                    // groups of 2 * BS * NBLK MFMAs per unit
+    static_assert(TB * TW == 16 && KT == CWAVES * 16, "direct fp32 16x16 geometry: a column block is one tile row, a wave 16 channels");
+    static_assert(POS == 512 && (YSL * POS) % 256 == 0, "direct fp32 16x16 geometry: chunks, bank spread of the two columns");
+    static_assert(FLT_ITEMS % PT == 0 && GROUPS % 2 == 0, "direct fp32 16x16 geometry: whole Filter items, even group count");
+    static_assert(IMG_BYTES < 65536 && LDS_BYTES <= 160 * 1024 && 2 * LOADS < 64, "direct fp32 16x16 geometry: LDS offsets, size, load counter");
+    static bool matches_host(const KernelArgs& a) {
+        return a.sw == 1 && a.sh == 1 && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
+               a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % TB == 0 && a.W % TW == 0 && a.H % TH == 0 &&
+               a.K % KT == 0 && a.vec_img && a.vec_flt;
+    }
+};
+
+template <int TW, int TH>
+__global__ void __launch_bounds__(512) conv_f32_direct16_kernel(const KernelArgs a) {
+    using GEO = F32Direct16<TW, TH>;
+    constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, NBLK = GEO::NBLK;
+    constexpr int YS = GEO::YS, XP = GEO::XP, POS = GEO::POS, FP = GEO::FP;
+    constexpr int IBUF = GEO::IMG_BYTES, FBUF = GEO::FLT_BYTES;
+    extern __shared__ __align__(16) f32x4 smem_v[];
+    CACNN_LDS(char)* const lds = (CACNN_LDS(char)*)smem_v;
+    const int tid = threadIdx.x;
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
+    const int lane = tid & 63;
+    const int upt = (a.C / CT) * (a.S / BS);
+    int total = 0;
+    for (int t = blockIdx.x; t < a.n_tiles; t += gridDim.x) total += upt;
+
+    if (wave_id >= GEO::CWAVES) {
+        f32_direct_stage<GEO>(a, lds, tid, wave_id, lane, total);
+    } else {
+        const int n = lane & 15, q = lane >> 4;
+        f32x4 acc[NBLK];
+#pragma unroll
+        for (int j = 0; j < NBLK; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // per-lane LDS offsets: Filter row of output channel 16 * wave + n, channels 2q, 2q + 1 of a group of 8;
+        // Image: output column n / 8 of the tile row, image n % 8, channel 2q of a group of 8
+        const uint32_t al = (uint32_t)(GEO::FLT_OFF + (wave_id * 16 + n) * FP + q * 8);
+        const uint32_t xl = (uint32_t)((n >> 3) * XP + q * 2 * TB * 4 + (n & 7) * 4);
+        f32x2 A[2][BS];
+        float X[2][YS][2];
+        // Every read is one base register plus an offset in the instruction: a base per filter column r and channel
+        // parity e for the Image (the compiler must not fold them into one, the offsets would then outgrow the
+        // instruction's field and every read would need an address addition, which costs the MFMA stream an issue
+        // slot), one for the Filter.  They change once per unit.
+        uint32_t xr[GEO::BR][2], ar;
+        auto set_bases = [&](uint32_t ioff, uint32_t foff) {
+#pragma unroll
+            for (int r = 0; r < GEO::BR; ++r)
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    xr[r][e] = xl + ioff + r * XP + e * TB * 4;
+                    asm("" : "+v"(xr[r][e]));
+                }
+            ar = al + foff;
+            asm("" : "+v"(ar));
+        };
+        auto load_group = [&](int grp, int set) {
+            const int r = grp / (CT / 8), c8 = grp % (CT / 8);
+#pragma unroll
+            for (int s = 0; s < BS; ++s) A[set][s] = *(const CACNN_LDS(f32x2)*)(lds + ar + ((r * BS + s) * CT + c8 * 8) * 4);
+#pragma unroll
+            for (int y = 0; y < YS; ++y)
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+                    X[set][y][e] = *(const CACNN_LDS(float)*)(lds + xr[r][e] + y * POS + c8 * 8 * TB * 4);
+        };
+        auto mfma_group = [&](int set) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+#pragma unroll
+                for (int s = 0; s < BS; ++s)
+#pragma unroll
+                    for (int j = 0; j < NBLK; ++j)
+                        acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(A[set][s][e], X[set][j + s][e], acc[j], 0, 0, 0);
+        };
+        const int64_t out_kstride = (int64_t)a.H * a.W * a.B;      // floats between output channels
+        const uint32_t out_lane = (uint32_t)(q * 4) * (uint32_t)out_kstride + (uint32_t)((n / TB) * a.B + n % TB);
+        int left = total, in_tile = upt, t = blockIdx.x;
+        uint32_t ioff = 0, foff = 0;
+        // one unit; MORE: another one follows (in the next Image buffer of the three, the other Filter buffer)
+        auto unit = [&](auto more) {
+            constexpr bool MORE = decltype(more)::value;
+#pragma unroll
+            for (int grp = 0; grp < GEO::GROUPS; ++grp) {
+                if (grp + 1 < GEO::GROUPS) {
+                    load_group(grp + 1, (grp + 1) & 1);
+                } else if constexpr (MORE) {
+                    ioff = ioff + IBUF == GEO::NBUF_I * IBUF ? 0u : ioff + IBUF;
+                    foff = FBUF - foff;
+                    lds_done_then_barrier_known(acc[NBLK - 1]);
+                    set_bases(ioff, foff);
+                    load_group(0, 0);
+                }
+                mfma_group(grp & 1);
+                if (grp + 1 < GEO::GROUPS || MORE) interleave_hint<2 * BS * NBLK, BS + 2 * YS>();
+            }
+            // keep the reads above where they are (the compiler would sink them to the top of the next unit)
+            asm volatile("" ::: "memory");
+            --left;
+            if (__builtin_expect(--in_tile == 0, 0)) {
+                const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
+#pragma unroll
+                for (int j = 0; j < NBLK; ++j) {
+                    float* const blk = a.out + ((((int64_t)(tc.k0 + wave_id * 16) * a.H + tc.h0 + j) * a.W + tc.w0) * a.B + tc.b0);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        (blk + (int64_t)v * out_kstride)[out_lane] = acc[j][v];
+                        acc[j][v] = 0.f;
+                    }
+                }
+                in_tile = upt;
+                t += gridDim.x;
+            }
+        };
+        if (left > 0) {
+            lds_done_then_barrier_known();      // unit 0 is staged
+            set_bases(0, 0);
+            load_group(0, 0);
             while (left > 1) unit(std::true_type{});
             unit(std::false_type{});
         }
@@ -2556,6 +2724,17 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
+// the same with 16x16 MFMA blocks: 8 images x 2 x 7 positions
+#define CACNN_F32_DIRECT16_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                             \
+    {                                                                                                          \
+        {NAME, 0, 2, 2, 1, F32Direct16<TW, TH>::NBLK, 8, TW, TH, 2, 1, F32Direct16<TW, TH>::MAXF, 1, -4, 1.0f, 16, 3,    \
+         3, F32Direct16<TW, TH>::YS, 1, 1, F32Direct16<TW, TH>::LDS_BYTES, UNIT_US, FIXED_US, 0},               \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                if (!F32Direct16<TW, TH>::matches_host(a) || lds != (size_t)F32Direct16<TW, TH>::LDS_BYTES) return 1; \
+                return launch_kernel(conv_f32_direct16_kernel<TW, TH>, attr_done, 512, a, grid, lds, stream);   \
+            }                                                                                                  \
+    }
 
 static const Variant g_variants[] = {
     // fp32
@@ -2609,6 +2788,7 @@ static const Variant g_variants[] = {
                      conv_f32v4_ws_kernel<2, 2, 1, 2, 16, 4, 2, 3, 10>),
     // fixed-geometry kernels (3x3 taps, unit strides, shapes the tiles divide exactly)
     CACNN_F32_DIRECT_VARIANT("f32 fxd k64 b8w4h4 w2x2 m1n2 c16r3s3", 4.4f, 3.0f, 4, 4),
+    CACNN_F32_DIRECT16_VARIANT("f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r3s3", 3.6f, 3.0f, 2, 7),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.0f, 4.5f, 7, 1),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.62f, 4.2f, 2, 2),
     // fixed geometry for the stem-layer shape: 7x7 taps, strides 2, three channels

@@ -67,6 +67,10 @@ RAGGED = [
     ("fx_many_tiles", 64, 32, 128, 24, 24, 3, 3, 1, 1),
     ("fx_w7_many_tiles", 64, 32, 64, 7, 300, 3, 3, 1, 1),
     ("fx_s6", 64, 32, 64, 4, 4, 3, 6, 1, 1),
+    # the fp32 kernel with 16x16 blocks (tiles of 8 images x 2 x 7 positions): two tiles in every dimension and two
+    # c-slices; a taller filter with more tiles than workgroups
+    ("fx16_two_each", 16, 32, 128, 4, 14, 3, 3, 1, 1),
+    ("fx16_many_tiles_s6", 8, 16, 64, 46, 42, 3, 6, 1, 1),
     # the stem-layer kernel: 7x7 taps, strides 2, three channels; more tiles than workgroups and three k-tiles, so a
     # workgroup walks several tiles and restages its Filter tile
     ("fx_stem", 32, 3, 192, 28, 16, 7, 7, 2, 2),
