@@ -2788,7 +2788,7 @@ static const Variant g_variants[] = {
                      conv_f32v4_ws_kernel<2, 2, 1, 2, 16, 4, 2, 3, 10>),
     // fixed-geometry kernels (3x3 taps, unit strides, shapes the tiles divide exactly)
     CACNN_F32_DIRECT_VARIANT("f32 fxd k64 b8w4h4 w2x2 m1n2 c16r3s3", 4.4f, 3.0f, 4, 4),
-    CACNN_F32_DIRECT16_VARIANT("f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r3s3", 3.6f, 3.0f, 2, 7),
+    CACNN_F32_DIRECT16_VARIANT("f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r3s3", 4.1f, 2.6f, 2, 7),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.0f, 4.5f, 7, 1),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.62f, 4.2f, 2, 2),
     // fixed geometry for the stem-layer shape: 7x7 taps, strides 2, three channels
