@@ -158,6 +158,17 @@ def test_plan_gpu_block_is_feasible(name):
     assert plan.tile_volume == plan.b_b * plan.b_c * plan.b_k * plan.b_w * plan.b_h * plan.b_r * plan.b_s
 
 
+def test_plan_fills_the_compute_units_on_the_benchmark_shapes():
+    """The four large shapes get one tile per workgroup or an even share of many (the machine has 256 compute units),
+    and c2's 56 x 56 x 8 outputs are cut into 224 tiles of 2 x 7 positions rather than 196 of 4 x 4."""
+    want = {"c2": (224, 2, 7), "c3": (256, 2, 2), "c4": (196, 2, 2), "c5": (224, 7, 1)}
+    for name, (grid, bw, bh) in want.items():
+        cfg = ci.CONFIGS[name]
+        plan = cc.cacnn_tile_plan(cfg.dims, 0 if cfg.dtype == "f32" else 1)
+        assert " fx" in cc.cacnn_variant_name(plan.variant), (name, cc.cacnn_variant_name(plan.variant))
+        assert (plan.grid[0], plan.b_w, plan.b_h) == (grid, bw, bh), (name, plan.grid[0], plan.b_w, plan.b_h)
+
+
 def test_plan_errors():
     with pytest.raises(cc.CacnnError) as e:
         cc.cacnn_tile_plan((1, 1, 1, 1, 1, 1, 1, 1, 0), 0)
