@@ -1,6 +1,7 @@
 """GPU parity: the HIP path (through the C ABI) against the fp64 loop-nest oracle, element by element on the same
 seeded inputs.  Tolerance (benchmark definition): max|err| / sum|Image*Filter| <= 1e-5 for fp32, <= 1e-2 for bf16
 inputs with fp32 accumulation; integer-valued inputs must match exactly."""
+import re
 import sys
 
 import numpy as np
@@ -122,6 +123,33 @@ def test_every_variant_ran_on_some_ragged_shape(env):
             name = cc.cacnn_variant_name(vi)
             need = 1 if " fx" in name else 2     # a fixed-geometry kernel accepts one contraction tile only
             assert RAN.get((dtype, vi), 0) >= need, f"variant {vi} '{name}' ran {RAN.get((dtype, vi), 0)} times"
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_direct_kernels_with_one_to_seven_units_per_workgroup(env, dtype):
+    """The staging schedule of the fixed-geometry kernels has separate code for workgroups with one, two, and three
+    or more units (tile x contraction slice) and two different ways out of its loop (odd and even counts): one tile
+    with 1..7 slices, on every such kernel."""
+    cc, torch = env
+    names = {cc.cacnn_variant_name(i): i for i in variants_for(cc, dtype)}
+    fx = [n for n in names if " fxd " in n or " fxd16 " in n]
+    assert len(fx) >= 2
+    for name in fx:
+        v = names[name]
+        tb, tw, th = (int(x) for x in re.search(r" b(\d+)w(\d+)h(\d+) ", name).groups())
+        for units in range(1, 8):
+            if dtype == "f32":
+                C, S, bc, bs = 16 * units, 3, 16, 3
+            else:
+                C, S, bc, bs = 32, units, 32, 1
+            cfg = ci.custom(f"units{units}", tb, C, 64, tw, th, 3, S, 1, 1, dtype=dtype, dist="normal", seed=500 + units)
+            img, flt = ci.make_inputs(cfg)
+            ref, ab = gu.oracle_full(cfg, img, flt)
+            plan = cc.Plan()
+            plan.variant, plan.b_c, plan.b_r, plan.b_s = v, bc, 3, bs
+            say(f"[parity] {units} unit(s) '{name}' dims={cfg.dims}")
+            out = gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
+            gu.assert_parity(cfg, out, ref, ab, f"{name}, {units} units")
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
