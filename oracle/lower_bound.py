@@ -1,4 +1,4 @@
-"""Oracle for the communication lower bound (paper, Theorem 1 in Section 4, Eq. eqn_LB1; also stated
+"""Oracle for the communication lower bound (paper, Theorem 1 in Section 4; also stated
 in Section 1).
 
 TEST INFRASTRUCTURE ONLY.  The bound is a closed form, so the oracle is that closed form written out:

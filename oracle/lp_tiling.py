@@ -2,14 +2,16 @@
 
 TEST INFRASTRUCTURE ONLY.  Three things, each written from the paper's statement of it:
 
-  solve_lp        -- the nine-variable linear program of Section 5 (the one labelled eq:mplp): maximise the
+  solve_lp        -- the nine-variable linear program of Section 5: maximise the
                      log (base M) of the tile volume subject to the tile fitting the loop bounds and the three
                      array footprints fitting in M.  scipy's LP solver is the library step.
   solve_lp_sigma1 -- the seven-variable program of Appendix A (strides 1).
   appendix_a_case -- the decision tree of Appendix A, Theorem 2, with the tile volume G each leaf's
-                     construction reaches.
+                     construction reaches (Case 1 down to its sub-cases 1.1 to 1.10).
+  integer_tiles   -- integer tile sizes near the LP's real ones (the paper leaves the rounding open), with
+                     tile_footprint and outer_iterations, the two quantities it trades.
 
-Cost of a tiling (Section 5.2, Eq. eq:ccost_tile, and Appendix A): words moved = F * M / G with
+Cost of a tiling (the cost expression of Section 5.2, and Appendix A): words moved = F * M / G with
 F = BCKWHRS and G the tile volume.
 
 Readings: R/sigma_w need not be an integer (AlexNet: 11/4); the LP is over reals, so that is harmless
@@ -112,16 +114,33 @@ def solve_lp_sigma1(B, C, K, W, H, R, S, M) -> LPResult:
 
 def appendix_a_case(B, C, K, W, H, R, S, M) -> Tuple[str, float, float]:
     """Appendix A, Theorem 2 (strides 1).  Returns (case label, attainable lower bound ALB, tile volume G of
-    the leaf's construction or nan where the appendix gives several sub-constructions)."""
+    the leaf's construction).  Case 1 (some array fits in M) is split into the ten sub-cases of the proof of its
+    lemma, by which of Image (CHWB), Filter (KCRS) and Out (KHWB) exceed M; where two sub-cases meet (an array of
+    exactly M words) the later one is taken, and their constructions agree there."""
     img, flt, out = C * H * W * B, K * C * R * S, K * H * W * B
+    hwb = H * W * B
     F = float(B) * C * K * W * H * R * S
     if min(img, flt, out) <= M:
-        if img > M and out > M and flt <= M:
-            G = min(K, C) * M * R * S         # Case 1.6
-            return "1.6", float(max(out, img)), float(G)
-        if img <= M and flt <= M and out <= M:
-            return "1.1", float(max(img, flt, out)), F  # unblocked: one tile is the whole nest
-        return "1", float(max(img, flt, out)), float("nan")
+        big_i, big_f, big_o = img > M, flt > M, out > M
+        if not (big_i or big_f or big_o):
+            return "1.1", float(max(img, flt, out)), F   # unblocked: one tile is the whole nest
+        if big_i and not big_f and not big_o:
+            return "1.2", float(img), float(K) * R * S * M          # one image, all k, M/(HW) channels
+        if big_o and not big_f and not big_i:
+            return "1.3", float(out), float(C) * R * S * M          # Case 1.2 with C and K exchanged
+        if big_f and not big_i and not big_o:
+            # 1.4 (KC <= M: tile r, s) and 1.5 (KC >= M: tile k, c) reach the same volume
+            return ("1.4" if K * C <= M else "1.5"), float(flt), float(hwb) * M
+        if big_i and big_o:
+            return "1.6", float(max(out, img)), float(min(K, C)) * M * R * S
+        if big_i and big_f:
+            if K >= hwb:
+                return "1.7", float(flt), float(hwb) * M
+            return "1.8", float(max(img, flt)), min(float(K) * M * R * S, float(hwb) * M)
+        # Filter and Out exceed M, Image fits: Cases 1.7 / 1.8 with C and K exchanged
+        if C >= hwb:
+            return "1.9", float(flt), float(hwb) * M
+        return "1.10", float(max(out, flt)), min(float(C) * M * R * S, float(hwb) * M)
     if R * S >= M:
         return "2.1", F / M, float(M) ** 2
     if M * R * S >= (B * H * W) ** 2:
@@ -131,37 +150,88 @@ def appendix_a_case(B, C, K, W, H, R, S, M) -> Tuple[str, float, float]:
     return "2.2.2.2", float(max(out, img)), float(min(C, K)) * R * S * M
 
 
+def _tile_caps(B, C, K, W, H, R, S, sigma_w, sigma_h) -> Dict[str, int]:
+    sw, sh = min(sigma_w, R), min(sigma_h, S)
+    return {"b": B, "c": C, "k": K, "w": W, "h": H, "r1": -(-R // sw), "r2": sw, "s1": -(-S // sh), "s2": sh}
+
+
+def tile_footprint(t: Dict[str, int], R, S, sigma_w, sigma_h) -> int:
+    """Words one tile of each array occupies together: Out b*k*w*h, Filter c*k*(taps in the tile), Image
+    b*c*(distinct first-axis indices)*(distinct second-axis indices), the Image extent per axis being the set
+    of indices r'' + sigma*(r' + w) the tile touches (Section 5, item 3)."""
+    sw, sh = min(sigma_w, R), min(sigma_h, S)
+
+    def axis(nw, n1, n2, sg, ext):
+        taps = sum(1 for r1 in range(n1) for r2 in range(n2) if sg * r1 + r2 < ext)
+        idx = {r2 + sg * (r1 + w) for r1 in range(n1) for r2 in range(n2) if sg * r1 + r2 < ext for w in range(nw)}
+        return taps, len(idx)
+
+    nr, fx = axis(t["w"], t["r1"], t["r2"], sw, R)
+    ns, fy = axis(t["h"], t["s1"], t["s2"], sh, S)
+    return t["b"] * t["k"] * t["w"] * t["h"] + t["c"] * t["k"] * nr * ns + t["b"] * t["c"] * fx * fy
+
+
+def outer_iterations(t: Dict[str, int], B, C, K, W, H, R, S, sigma_w, sigma_h) -> int:
+    """Iterations of the nine outer (tile) loops of the blocked schedule: the product of ceil(extent / tile)."""
+    cap = _tile_caps(B, C, K, W, H, R, S, sigma_w, sigma_h)
+    n = 1
+    for x in cap:
+        n *= -(-cap[x] // t[x])
+    return n
+
+
 def integer_tiles(real_tiles: Dict[str, float], B, C, K, W, H, R, S, sigma_w, sigma_h, M) -> Dict[str, int]:
     """Turn the LP's real tile sizes into integers whose three exact footprints fit in M words TOGETHER.
 
-    Not from the paper (it leaves rounding open: "the exact tile sizes may not necessarily give the best
-    performance", Section 5): floor every size, then grow sizes one at a time, largest relative gain first,
-    while Out + Filter + Image footprints (Image with its exact halo extent) still sum to at most M."""
-    sw, sh = min(sigma_w, R), min(sigma_h, S)
-    cap = {"b": B, "c": C, "k": K, "w": W, "h": H, "r1": -(-R // sw), "r2": sw, "s1": -(-S // sh), "s2": sh}
+    Not from the paper: Section 5 leaves the rounding open and remarks that the exact LP sizes need not perform
+    best.  What is minimised here is the number of outer-loop iterations, because Appendix A's cost model charges
+    each of them at most M words: start from the floor of the LP sizes, then repeat the single best move among
+    "grow one size to x+1 or to the next size that needs fewer tiles along its loop" and the same move paid for by
+    shrinking one other size just enough to fit, as long as the iteration count falls (ties: smaller footprint)."""
+    cap = _tile_caps(B, C, K, W, H, R, S, sigma_w, sigma_h)
     t = {k: max(1, min(cap[k], int(math.floor(v + 1e-9)))) for k, v in real_tiles.items()}
 
-    def footprint(t):
-        nr = min(R, sw * (t["r1"] - 1) + t["r2"]) if t["r2"] == sw else t["r1"] * t["r2"]
-        ns = min(S, sh * (t["s1"] - 1) + t["s2"]) if t["s2"] == sh else t["s1"] * t["s2"]
-        out = t["b"] * t["k"] * t["w"] * t["h"]
-        flt = t["c"] * t["k"] * nr * ns
-        img = t["b"] * t["c"] * (t["w"] + t["r1"] - 1) * t["r2"] * (t["h"] + t["s1"] - 1) * t["s2"]
-        return out + flt + img
+    def fp(u):
+        return tile_footprint(u, R, S, sigma_w, sigma_h)
 
-    while footprint(t) > M:            # floor can still overshoot because the LP bounds each array by M alone
+    def iters(u):
+        n = 1
+        for x in cap:
+            n *= -(-cap[x] // u[x])
+        return n
+
+    while fp(t) > M:            # the floor can still overshoot: the LP bounds each array by M alone
         big = max((k for k in t if t[k] > 1), key=lambda k: t[k], default=None)
         if big is None:
             break
         t[big] -= 1
-    grew = True
-    while grew:
-        grew = False
-        for k in sorted(t, key=lambda k: t[k]):
-            if t[k] < cap[k]:
-                t[k] += 1
-                if footprint(t) <= M:
-                    grew = True
-                else:
-                    t[k] -= 1
-    return t
+    names = list(t)
+    while True:
+        n0, best = iters(t), None
+        for x in names:
+            cur = -(-cap[x] // t[x])
+            sizes = set()
+            if t[x] < cap[x]:
+                sizes.add(t[x] + 1)
+            if cur > 1:
+                sizes.add(-(-cap[x] // (cur - 1)))
+            for nx in sorted(sizes):
+                u = dict(t)
+                u[x] = nx
+                trials = [u] if fp(u) <= M else []
+                if not trials:
+                    for y in names:
+                        if y == x:
+                            continue
+                        v = dict(u)
+                        while v[y] > 1 and fp(v) > M:
+                            v[y] -= 1
+                        if fp(v) <= M:
+                            trials.append(v)
+                for v in trials:
+                    key = (iters(v), fp(v))
+                    if key[0] < n0 and (best is None or key < best[0]):
+                        best = (key, v)
+        if best is None:
+            return t
+        t = best[1]

@@ -99,10 +99,10 @@ SHAPES = {
 def test_tiled_schedule_is_between_bound_and_small_multiple(name, M):
     """The paper's claim (Sections 4 and 5): the LP tiling moves Theta(max of the five terms) words.  The
     schedule keeps all three tiles resident, so the LP is solved for M/3 (Section 3 uses the same M/3) and
-    rounded to integers.  The slack the paper itself names bounds the constant: three arrays of up to M/3
-    words per outer iteration at a tile volume computed for M/3 cost at most 3*sqrt(3) times the M-word
-    expression, and the Image halo at most 4 times its interior (Appendix A) -- so the count must land in
-    [bound, 3*sqrt(3)*4*bound]; the measured constants are 1.7 to 12.4."""
+    rounded to integers (integer_tiles, pinned by brute force in test_oracle_bound_lp.py).  Three arrays of up to
+    M/3 words per outer iteration at a tile volume computed for M/3 already cost 3*sqrt(3) = 5.2 times the M-word
+    expression; the Image halo and the integer sizes add the rest.  Measured constants: c2_quarter 6.5, c3_small
+    1.4, c4 5.8 (7.7 at M = 8192), c5_half 5.6, AlexNet conv1 7.9 (M = 1024) and 8.0 (M = 4096); asserted: at most 8.5."""
     dims = SHAPES[name]
     bound = lb.lower_bound(*dims, float(M)).bound
     real = lp.solve_lp(*dims, M / 3.0).tiles
@@ -114,4 +114,4 @@ def test_tiled_schedule_is_between_bound_and_small_multiple(name, M):
         w = cs.tiled_schedule_words(*dims, tiles, order)
         best = w.total if best is None else min(best, w.total)
     assert best >= bound
-    assert best <= 3 * math.sqrt(3) * 4 * bound, (best / bound, tiles)
+    assert best <= 8.5 * bound, (best / bound, tiles)
