@@ -86,7 +86,11 @@ typedef struct {
     int64_t lds_bytes_used;
     double tile_volume;      /* b_b*b_c*b_k*b_w*b_h*b_r*b_s */
     double predicted_words;  /* words this schedule moves between HBM/L2 and the compute units:
-                                staged Image halo tiles + staged Filter tiles + Out written once */
+                                staged Image halo tiles + staged Filter tiles + Out written once.  Every workgroup
+                                stages what its tile needs (nothing is shared between workgroups), the staged Image
+                                tile is the contiguous range sigma*(b-1)+b_r by sigma*(b-1)+b_s clipped to the array
+                                (so it includes untouched rows when a stride exceeds the tile's filter extent, and a
+                                full b_r, b_s range where the last contraction tile is ragged) */
     int32_t xcd_split_k;     /* Section 7 with the eight XCDs (each has its own L2) as the processors: the XCDs are
                                 divided into this many groups of output channels (a_K; 1, 2, 4 or 8, a divisor of the
                                 k-tile count) and 8 / a_K ranges of positions, whichever makes a_K*|Image| +

@@ -167,6 +167,24 @@ def _ptr(t) -> int:
     return t.data_ptr()
 
 
+def _check_operands(where: str, problem: Problem, dtype: int, image, filt, out, pooling: bool = False) -> None:
+    """Refuse tensors that are too small or of the wrong element size for the problem: the library trusts its pointers,
+    so an undersized Out would become an out-of-bounds device write.  Plain integer addresses are taken as they are."""
+    esz = 4 if int(dtype) == CACNN_F32 else 2
+    need = (("image", image, problem.IW * problem.IH * problem.C * problem.B, esz),
+            ("filter", filt, problem.K * problem.R * problem.S * problem.C, esz),
+            ("out", out, (problem.C if pooling else problem.K) * problem.H * problem.W * problem.B, 4))
+    for name, t, numel, size in need:
+        if t is None or isinstance(t, int):
+            continue
+        if t.element_size() != size:
+            raise ValueError(f"{where}: {name} has {t.element_size()}-byte elements, the call needs {size}-byte ones")
+        if name == "out" and not t.dtype.is_floating_point:
+            raise ValueError(f"{where}: out must be a float32 tensor")
+        if t.numel() < numel:
+            raise ValueError(f"{where}: {name} holds {t.numel()} elements, the problem needs {numel}")
+
+
 def _stream_handle(stream) -> int:
     if stream is None:
         import torch
@@ -179,7 +197,9 @@ def _stream_handle(stream) -> int:
 def cacnn_conv_forward(problem, dtype: int, image, filt, out, stream=None) -> None:
     """Enqueue Out = conv(Image, Filter) on `stream` (torch stream, raw handle, or None = torch's current stream).
     image/filt/out are device tensors laid out Image[IW,IH,C,B], Filter[K,R,S,C], Out[K,H,W,B] (fp32)."""
-    rc = _lib.cacnn_conv_forward(ctypes.byref(_as_problem(problem)), int(dtype), _ptr(image), _ptr(filt), _ptr(out),
+    prob = _as_problem(problem)
+    _check_operands("cacnn_conv_forward", prob, dtype, image, filt, out)
+    rc = _lib.cacnn_conv_forward(ctypes.byref(prob), int(dtype), _ptr(image), _ptr(filt), _ptr(out),
                                  _stream_handle(stream))
     if rc != 0:
         raise CacnnError(rc, "cacnn_conv_forward")
@@ -188,6 +208,7 @@ def cacnn_conv_forward(problem, dtype: int, image, filt, out, stream=None) -> No
 def cacnn_tune(problem, dtype: int, image, filt, out, stream=None) -> Plan:
     """Time every kernel variant that accepts the problem on these buffers (synchronises), remember and return the fastest."""
     plan = Plan()
+    _check_operands("cacnn_tune", _as_problem(problem), dtype, image, filt, out)
     rc = _lib.cacnn_tune(ctypes.byref(_as_problem(problem)), int(dtype), _ptr(image), _ptr(filt), _ptr(out),
                          _stream_handle(stream), ctypes.byref(plan))
     if rc != 0:
@@ -226,6 +247,7 @@ def cacnn_pool_lower_bound(problem, M_words: float) -> PoolBound:
 
 def cacnn_pool_forward(problem, dtype: int, mode: int, image, out, stream=None) -> None:
     """Enqueue per-channel average (mode 0) or max (mode 1) pooling of Image[IW,IH,C,B] into Out[K=C,H,W,B] (fp32)."""
+    _check_operands("cacnn_pool_forward", _as_problem(problem), dtype, image, None, out, pooling=True)
     rc = _lib.cacnn_pool_forward(ctypes.byref(_as_problem(problem)), int(dtype), int(mode), _ptr(image), _ptr(out),
                                  _stream_handle(stream))
     if rc != 0:
@@ -250,6 +272,7 @@ def cacnn_probe_copy(src, dst, nbytes: int, stream=None) -> None:
 
 def cacnn_conv_forward_with_plan(problem, dtype: int, plan: Plan, image, filt, out, stream=None) -> None:
     """Same as cacnn_conv_forward with a caller-chosen kernel variant and contraction tile."""
+    _check_operands("cacnn_conv_forward_with_plan", _as_problem(problem), dtype, image, filt, out)
     rc = _lib.cacnn_conv_forward_with_plan(ctypes.byref(_as_problem(problem)), int(dtype), ctypes.byref(plan),
                                            _ptr(image), _ptr(filt), _ptr(out), _stream_handle(stream))
     if rc != 0:

