@@ -170,6 +170,8 @@ def _ptr(t) -> int:
 def _check_operands(where: str, problem: Problem, dtype: int, image, filt, out, pooling: bool = False) -> None:
     """Refuse tensors that are too small or of the wrong element size for the problem: the library trusts its pointers,
     so an undersized Out would become an out-of-bounds device write.  Plain integer addresses are taken as they are."""
+    if int(dtype) not in (CACNN_F32, CACNN_BF16_F32ACC) or min(getattr(problem, n) for n, _ in Problem._fields_) < 1:
+        return                                  # the library reports these itself
     esz = 4 if int(dtype) == CACNN_F32 else 2
     need = (("image", image, problem.IW * problem.IH * problem.C * problem.B, esz),
             ("filter", filt, problem.K * problem.R * problem.S * problem.C, esz),

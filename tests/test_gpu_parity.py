@@ -101,7 +101,9 @@ def staged_tile_fits(cc, cfg, vi, bc, br, bs):
     xs = cfg.sigma_w * (tw - 1) + min(br, cfg.R)
     ys = cfg.sigma_h * (th - 1) + min(bs, cfg.S)
     esz = 4 if cfg.dtype == "f32" else 2
-    return xs * ys * min(bc, cfg.C) * tb * esz <= 160 * 1024
+    gran = 1 if cfg.dtype == "f32" else 16         # bf16 c-slices are whole 16-channel MFMA steps
+    ct = min(-(-bc // gran) * gran, -(-cfg.C // gran) * gran)
+    return xs * ys * ct * tb * esz <= 160 * 1024
 
 
 def run_every_variant(cc, torch, shape, dtype, ran):
