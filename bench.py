@@ -1,9 +1,16 @@
 """Benchmark: one "step" = one pass of the whole hot path (plan lookup, Image-halo and Filter staging, MFMA
 contraction, Out epilogue: one cacnn_conv_forward call) over one batch of synthetic input resident in HBM.
 
-Prints ONE JSON line.  metric/unit follow the benchmark definition (conv TFLOP/s on one MI355X); `roofline`
-prices the kernel against the MFMA peak of its dtype; `cpu_baseline` is the fp64 loop-nest oracle timed on the
-host in the same run; `shapes` carries the same measurements for all five benchmark shapes.
+Prints ONE JSON line.  metric/unit follow the benchmark definition (conv TFLOP/s on one MI355X); the headline
+workload is c5, the largest of the five shapes; `roofline` prices the kernel against the MFMA peak of its dtype;
+`cpu_baseline` is the fp64 loop-nest oracle timed on the host in the same run; `shapes` carries the same
+measurements for all five benchmark shapes.
+
+Order of the run: every input is generated and uploaded first; then the machine's sustained rates are measured
+(register-only MFMA loops and a streaming copy); then, per shape: about 0.3 s of the register-only MFMA loop of the
+shape's dtype (power-state conditioning: the board's power management needs a few hundred milliseconds of matrix load
+to settle, and a cold chip runs the first launches of c5 up to 25 % slower, see profiles/clock_ramp.txt), then the W
+warm-up launches, then exactly K timed launches between two events on the launch stream.
 """
 import argparse
 import json
@@ -20,9 +27,8 @@ HBM_PEAK_GBS = 8000.0
 LDS_BYTES = 160 * 1024
 
 
-def time_config(cc, torch, ci, np, cfg, steps, warmup, repeats=1):
-    """Average launch duration (seconds) of cacnn_conv_forward over `steps` back-to-back launches, measured with
-    events on the stream the kernel runs on (torch's current stream)."""
+def upload_config(torch, ci, np, cfg):
+    """Seeded host inputs and their device copies (bf16 as raw 16-bit patterns), plus the Out buffer."""
     img, flt = ci.make_inputs(cfg)
     if cfg.dtype == "bf16":
         d_img = torch.from_numpy(ci.bf16_bits(img).view(np.int16).reshape(-1)).cuda()
@@ -31,14 +37,44 @@ def time_config(cc, torch, ci, np, cfg, steps, warmup, repeats=1):
         d_img = torch.from_numpy(img.reshape(-1)).cuda()
         d_flt = torch.from_numpy(flt.reshape(-1)).cuda()
     d_out = torch.empty(int(np.prod(cfg.out_shape)), dtype=torch.float32, device="cuda:0")
+    return img, flt, d_img, d_flt, d_out
+
+
+_COND = {}
+
+
+def condition_power_state(cc, torch, ci, np, dtype, ms=300.0):
+    """About `ms` milliseconds of the register-only MFMA loop of this dtype on every compute unit: brings the board's
+    power management to the state a steady matrix load runs in.  Untimed; no workload kernel runs in it."""
+    dt = 0 if dtype == "f32" else 1
+    if dt not in _COND:
+        rng = np.random.default_rng(18020690)
+        if dt == 0:
+            words = rng.uniform(-1.0, 1.0, 4096).astype(np.float32).view(np.int32)
+        else:
+            words = np.ascontiguousarray(
+                ci.bf16_bits(ci.round_to_bf16(rng.standard_normal(8192).astype(np.float32)))).view(np.int32)
+        _COND[dt] = (torch.from_numpy(np.ascontiguousarray(words)).cuda(),
+                     torch.empty(65536, dtype=torch.float32, device="cuda:0"))
+    ops, sink = _COND[dt]
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < ms:
+        cc.cacnn_probe_mfma(dt, ops, sink, 800 if dt == 0 else 1600)
+        torch.cuda.synchronize()
+
+
+def time_config(cc, torch, ci, np, cfg, steps, warmup, buffers, repeats=1, condition=True):
+    """Average launch duration (seconds) of cacnn_conv_forward over `steps` back-to-back launches, measured with
+    events on the stream the kernel runs on (torch's current stream)."""
+    img, flt, d_img, d_flt, d_out = buffers
     dt = 0 if cfg.dtype == "f32" else 1
+    if condition:
+        condition_power_state(cc, torch, ci, np, cfg.dtype)
     for _ in range(warmup):
         cc.cacnn_conv_forward(cfg.dims, dt, d_img, d_flt, d_out)
-    torch.cuda.synchronize()
     best = None
     for _ in range(repeats):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
         t0 = time.perf_counter()
         e0.record()
         for _ in range(steps):
@@ -49,7 +85,7 @@ def time_config(cc, torch, ci, np, cfg, steps, warmup, repeats=1):
         ev = e0.elapsed_time(e1) * 1e-3
         if best is None or ev < best[0]:
             best = (ev, wall)
-    return best[0] / steps, best[1] / steps, (img, flt, d_out)
+    return best[0] / steps, best[1] / steps
 
 
 def machine_sustained(cc, torch, ci, np):
@@ -120,18 +156,24 @@ def graph_replay_us(cc, torch, ci, np, cfg, launches=200, replays=20):
     return e0.elapsed_time(e1) * 1e3 / (replays * launches)
 
 
-def committed_traffic(name):
+def committed_traffic(name, variant=None, xcd_split_k=None):
     """HBM-side bytes of one launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs, scaled
-    by the copy-kernel calibration recorded there).  Counters cannot be read from inside this process, so the
-    figure is the recorded one for this shape, not a measurement of this run; None if the summary is absent."""
+    by the copy-kernel calibration recorded there).  Counters cannot be read from inside this process, so the figure is
+    the one RECORDED for this shape, not a measurement of this run.  Each `traffic` row names the kernel variant and the
+    XCD division it was recorded with; if the plan of this run differs (or the row names none), the figure would
+    belong to another launch configuration and None is returned instead."""
     for fname in ("hbm_traffic_c1-c5.txt", "pooling_p1.txt", "work_division_d1.txt"):
         try:
             with open(os.path.join(ROOT, "profiles", fname)) as f:
                 for line in f:
                     t = line.split()
                     if len(t) >= 5 and t[0] == "traffic" and t[1] == name:
+                        if variant is not None:
+                            rec = line.split("|")
+                            if len(rec) < 3 or rec[1].strip() != variant or int(rec[2].split()[0]) != int(xcd_split_k):
+                                return None
                         return float(t[4])
-        except OSError:
+        except (OSError, ValueError):
             pass
     return None
 
@@ -152,7 +194,11 @@ def shape_report(cc, cfg, sec):
         b = cc.cacnn_lower_bound(cfg.dims, fast_bytes / esz)
         return max(4 * b.term[0], esz * max(b.term[1:]))
     lb_bytes = bound_bytes(LDS_BYTES)
-    hbm = committed_traffic(cfg.name)
+    vname = cc.cacnn_variant_name(plan.variant)
+    hbm = committed_traffic(cfg.name, vname, plan.xcd_split_k)
+    F = float(cfg.macs)
+    M_lds = LDS_BYTES / esz
+    staged = esz * (plan.predicted_words - n_out) + 4 * n_out
 
     def xcd_level_bound_bytes():
         # Two levels: an LDS tile inside an XCD's share.  The HBM-side bytes are the misses of eight 4 MiB L2s, so the
@@ -180,9 +226,14 @@ def shape_report(cc, cfg, sec):
         "hbm_bytes_over_bound_at_M_l2": (hbm / bound_bytes(4 * 1024 * 1024)) if hbm else None,
         "xcd_division_a_B_a_K_a_W_a_H": xcd_div, "paper_parallel_bound_bytes_8_xcds_M_l2": xcd_bound,
         "hbm_bytes_over_parallel_bound": (hbm / xcd_bound) if hbm else None,
-        "planned_staged_bytes": esz * (plan.predicted_words - n_out) + 4 * n_out,
-        "variant": cc.cacnn_variant_name(plan.variant), "grid": plan.grid[0], "lds_bytes": plan.lds_bytes_used,
-        "b_c": plan.b_c, "hbm_bytes_profiled": hbm,
+        # global -> LDS bytes of the launched schedule plus Out once (cacnn_plan.predicted_words, in bytes): the traffic
+        # the paper's model counts at M = LDS, against Theorem 1 and against matmul-style reuse F / sqrt(M) (Section 1)
+        "planned_staged_bytes": staged,
+        "staged_bytes_over_bound_at_M_lds": staged / lb_bytes,
+        "matmul_reuse_bytes_at_M_lds": esz * F / M_lds ** 0.5,
+        "staged_bytes_over_matmul_reuse": staged / (esz * F / M_lds ** 0.5),
+        "variant": vname, "grid": plan.grid[0], "lds_bytes": plan.lds_bytes_used,
+        "b_c": plan.b_c, "hbm_bytes_recorded": hbm,
     }
 
 
@@ -344,11 +395,13 @@ def pooling_report(cc, torch, ci, np, steps, warmup, with_cpu):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000,
-                    help="timed launches; the clocks take on the order of a thousand back-to-back launches to settle")
-    ap.add_argument("--warmup", type=int, default=1000)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "p1", "d1"],
-                    help="c1..c5: the convolution shapes (c2 is the headline); p1: the pooling workload; "
+    ap.add_argument("--steps", type=int, default=500, help="timed launches")
+    ap.add_argument("--warmup", type=int, default=50, help="untimed launches in front of the timed ones")
+    ap.add_argument("--no-conditioning", action="store_true",
+                    help="skip the 0.3 s of register-only MFMA load that precedes each shape's warm-up launches (a cold "
+                         "board's power management makes the first hundreds of launches slower)")
+    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5", "p1", "d1"],
+                    help="c1..c5: the convolution shapes (c5, the largest, is the headline); p1: the pooling workload; "
                          "d1: the work-division workload (a Filter-heavy layer, every division of the XCDs)")
     ap.add_argument("--xcd-split-k", type=int, default=0,
                     help="with --traffic-probe: force this division of the XCDs over the output channels (0: planner's)")
@@ -411,9 +464,18 @@ def main():
     if args.traffic_probe:
         traffic_probe(cc, torch, ci, np, cfg, args.xcd_split_k)
         return
-    sec, wall, (img, flt, d_out) = time_config(cc, torch, ci, np, cfg, args.steps, args.warmup)
+    # inputs first (host work), so that nothing idles the GPU between conditioning, warm-up and the timed launches
+    names = [cfg.name] if args.no_shapes else list(ci.CONFIGS)
+    buffers = {n: upload_config(torch, ci, np, ci.CONFIGS[n]) for n in names}
+    torch.cuda.synchronize()
+    # (with --no-conditioning the sustained-rate loops run after the timed launches instead: they are a matrix load too)
+    sustained = None if args.no_conditioning else machine_sustained(cc, torch, ci, np)
+    sec, wall = time_config(cc, torch, ci, np, cfg, args.steps, args.warmup, buffers[cfg.name],
+                            condition=not args.no_conditioning)
+    if sustained is None:
+        sustained = machine_sustained(cc, torch, ci, np)
+    img, flt, _, _, d_out = buffers[cfg.name]
     head = shape_report(cc, cfg, sec)
-    sustained = machine_sustained(cc, torch, ci, np)
     head["frac_mfma_sustained"] = head["tflops"] / sustained[f"mfma_{cfg.dtype}_tflops"]
 
     # parity of the timed launch against the oracle (also the cpu_baseline leg)
@@ -426,7 +488,7 @@ def main():
                                f"sigma={cfg.sigma_w} {cfg.dtype} in, fp32 accumulate/out",
                    "variant": head["variant"], "grid": head["grid"], "lds_bytes": head["lds_bytes"]},
         "roofline": {"bound": "mfma", "achieved": head["tflops"], "peak": MFMA_PEAK_TFLOPS[cfg.dtype],
-                     "unit": "TFLOP/s", "frac": head["frac_mfma_peak"], "traffic": head["hbm_bytes_profiled"],
+                     "unit": "TFLOP/s", "frac": head["frac_mfma_peak"], "traffic": head["hbm_bytes_recorded"],
                      "wall_us_per_step": wall * 1e6, "frac_of_sustained_mfma": head["frac_mfma_sustained"]},
         "machine_sustained": sustained,
     }
@@ -442,7 +504,8 @@ def main():
             if name == cfg.name:
                 shapes[name] = head
                 continue
-            s, _, _ = time_config(cc, torch, ci, np, c, args.steps, args.warmup)
+            s, _ = time_config(cc, torch, ci, np, c, args.steps, args.warmup, buffers[name],
+                               condition=not args.no_conditioning)
             shapes[name] = shape_report(cc, c, s)
             shapes[name]["frac_mfma_sustained"] = shapes[name]["tflops"] / sustained[f"mfma_{c.dtype}_tflops"]
             if name == "c1":

@@ -2111,6 +2111,271 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
     }
 }
 
+// ---- fixed geometry, bf16, staged through registers with a deep prefetch ----------------------------------------------
+// Measured on the kernel above (timing-only builds of it that leave out one thing at a time, 256 compute units busy):
+// without its MFMAs it takes as long as with them (3 x 3 taps over 14 x 14 outputs, 64 images, 256 channels: 19.3 us either
+// way; 7 x 7 outputs, 256 images, 512 channels: 48 us against 52.5), and leaving out the Image fetches, all LDS reads or
+// the Out stores each gains about a tenth.  What sets its pace is the time a fetch takes divided by how many units of
+// fetches are in flight: a unit's words arrive 1.3 to 2 us after they are requested (most first requests of a line miss
+// the L2, and every compute unit asks at once), and with the loads' destination in LDS only the two buffers that are not
+// being read can be in flight, so a unit cannot take less than about half of that, whatever it holds.
+// Here the words in flight wait in the staging waves' registers instead, of which those waves have plenty (a staging
+// wave needs a dozen for its addresses): Filter words are requested three or four sub-units ahead and Image words
+// two to four Image units ahead, and a set of registers is written to LDS (16-byte stores, the same layouts as above:
+// the Image keeps its global order, the transposing LDS read does the rest) one sub-unit before it is multiplied.  Two
+// LDS buffers of each operand then suffice, which leaves room for the other half of the paper's small-filter reuse
+// (Section 4.3) inside LDS: with BSI = 3 an Image unit holds the TH + 2 rows that all three filter rows s of a c-slice
+// read, staged once, and only the Filter taps change from one sub-unit (one s) to the next.
+//   sub-unit  = (tile, c-slice of 32 channels, filter row s): 2 steps x 3 taps r x NBLK MFMAs per multiplying wave
+//   Image unit = BSI consecutive sub-units of one c-slice (rows h0 + s0 .. h0 + s0 + TH - 2 + BSI of the tile)
+// Barrier number v (one per sub-unit, executed by all eight waves) says "sub-unit v is in LDS" and, for the multiplying
+// waves, "every read of sub-unit v - 1 has landed", so the staging waves may overwrite that sub-unit's buffers.
+template <int TW, int TH, int BSI>
+struct Bf16StagedFixed {
+    static constexpr int TB = 64, KT = 64, WM = 2, WN = 2, CT = 32, BR = 3, NBLK = TW * TH;
+    static constexpr int C8 = CT / 8;
+    static constexpr int XS = TW + BR - 1, YSI = TH - 1 + BSI;
+    static constexpr int ROW = TB * 2;                              // bytes of one (x, y, c) row
+    static constexpr int IMG_BYTES = XS * YSI * CT * ROW;
+    static constexpr int F8 = (BR * C8) | 1;                        // Filter row in 16-byte units, odd: conflict-free
+    static constexpr int FLT_BYTES = KT * F8 * 16;
+    static constexpr int FLT_OFF = 2 * IMG_BYTES, LDS_BYTES = 2 * IMG_BYTES + 2 * FLT_BYTES;
+    static constexpr int PT = 256, PW = PT / 64;                    // staging threads, staging waves
+    static constexpr int CPW = XS * YSI;                            // 1 KiB Image chunks per Image unit and staging wave
+    static constexpr int MAXF = BR, MAXI = 1;                       // Filter items per thread and sub-unit
+    static constexpr int GF = BSI == 1 ? 4 : 3;                     // Filter register sets: sub-units a Filter load runs ahead
+    static constexpr int GI = BSI == 1 ? 4 : 2;                     // Image register sets: Image units an Image load runs ahead
+    static constexpr int PERIOD = BSI == 1 ? 4 : 6;                 // sub-units after which every buffer and set index repeats
+    static_assert(BSI == 1 || BSI == 3, "staged bf16 geometry: an Image unit serves one filter row or three");
+    static_assert(C8 == PW && PT == KT * C8, "staged bf16 geometry: staging wave p moves channels 8p..8p+7; one Filter item per thread and tap");
+    static_assert(PERIOD % GF == 0 && PERIOD % 2 == 0 && PERIOD % (BSI * GI) == 0, "staged bf16 geometry: static buffer rotation");
+    static_assert((CPW - 1) * C8 * 1024 < 65536 && FLT_BYTES + BR * C8 * 16 < 65536, "staged bf16 geometry: LDS store offsets");
+    static_assert(LDS_BYTES <= 160 * 1024, "staged bf16 geometry: LDS size");
+    static_assert((GI * CPW + GF * MAXF) * 4 <= 200, "staged bf16 geometry: registers of a staging wave");
+    static bool matches_host(const KernelArgs& a) {
+        return a.sw == 1 && a.sh == 1 && a.CT == CT && a.bS == BSI && a.bR == BR && a.XS == XS && a.YS == YSI &&
+               a.R == BR && a.S % BSI == 0 && a.C % CT == 0 && a.B % TB == 0 && a.W % TW == 0 && a.H % TH == 0 &&
+               a.K % KT == 0 && a.vec_img && a.vec_flt;
+    }
+};
+
+// f(integral_constant<int, 0>), f(integral_constant<int, 1>), ...: a loop whose index is a compile-time constant in every
+// iteration (register sets and LDS buffers are chosen by it)
+template <class F, size_t... I>
+__device__ __forceinline__ void static_for(F&& f, std::index_sequence<I...>) {
+    (f(std::integral_constant<int, (int)I>{}), ...);
+}
+
+// Where a staging wave is in its walk over the sub-units (or Image units) it fetches: this workgroup's tiles blockIdx.x,
+// blockIdx.x + gridDim.x, ..., within a tile the c-slices, within a c-slice the filter rows s.  All scalar.
+template <int KT, int TB, int TW, int TH, int CT>
+struct StagedWalk {
+    int t, c0, s0;
+    int64_t img_org, flt_org;      // byte offsets of the current tile's Image / Filter origin (c0 = s0 = 0)
+    __device__ __forceinline__ void set_tile(const KernelArgs& a) {
+        const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
+        img_org = ((((int64_t)tc.w0 * a.IH + (int64_t)tc.h0) * a.C) * a.B + tc.b0) * 2;
+        flt_org = (int64_t)tc.k0 * a.R * a.S * a.C * 2;
+    }
+    __device__ __forceinline__ void init(const KernelArgs& a) {
+        t = blockIdx.x;
+        c0 = s0 = 0;
+        img_org = flt_org = 0;
+        if (t < a.n_tiles) set_tile(a);
+    }
+    // a descriptor of the array from `off` on; of length zero once the walk has left the last tile, so that loads
+    // requested past the end touch no memory and return zeros
+    __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const KernelArgs& a, const void* base, int64_t off, int64_t total) const {
+        const bool live = t < a.n_tiles;
+        const uint64_t left = (uint64_t)(total - off);
+        const uint32_t lo = (uint32_t)left, hi = (uint32_t)(left >> 32);
+        const int32_t n = !live ? 0 : ((hi | (lo >> 31)) ? 0x7fffffff : (int32_t)lo);
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>((const char*)base + (live ? off : 0)), 0, n, 0x00020000);
+    }
+    __device__ __forceinline__ __amdgpu_buffer_rsrc_t img(const KernelArgs& a, int64_t img_bytes) const {
+        return rsrc(a, a.image, img_org + (int64_t)((uint32_t)(s0 * a.C + c0) * (uint32_t)a.B) * 2, img_bytes);
+    }
+    __device__ __forceinline__ __amdgpu_buffer_rsrc_t flt(const KernelArgs& a, int64_t flt_bytes) const {
+        return rsrc(a, a.filter, flt_org + (int64_t)(s0 * a.C + c0) * 2, flt_bytes);
+    }
+    __device__ __forceinline__ void next(const KernelArgs& a, int ds) {
+        s0 += ds;
+        if (s0 >= a.S) {
+            s0 = 0;
+            c0 += CT;
+            if (c0 >= a.C) {
+                c0 = 0;
+                if (t < a.n_tiles) t += gridDim.x;
+                if (t < a.n_tiles) set_tile(a);
+            }
+        }
+    }
+};
+
+template <int TW, int TH, int BSI>
+__global__ void __launch_bounds__(512) conv_bf16_staged_kernel(const KernelArgs a) {
+    using GEO = Bf16StagedFixed<TW, TH, BSI>;
+    constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BR = GEO::BR, WM = GEO::WM, NBLK = GEO::NBLK;
+    constexpr int XS = GEO::XS, YSI = GEO::YSI, C8 = GEO::C8, F8 = GEO::F8, ROW = GEO::ROW;
+    constexpr int IBUF = GEO::IMG_BYTES, FBUF = GEO::FLT_BYTES;
+    constexpr int CTHREADS = GEO::WM * GEO::WN * 64;
+    extern __shared__ __align__(16) uint4 smem_u[];
+    CACNN_LDS(char)* const lds = (CACNN_LDS(char)*)smem_u;
+    const int tid = threadIdx.x;
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
+    const int lane = tid & 63;
+    // sub-units this workgroup works through: its tiles blockIdx.x, blockIdx.x + gridDim.x, ... times the sub-units of a tile
+    const int spt = (a.C / CT) * a.S;
+    int total = 0;
+    for (int t = blockIdx.x; t < a.n_tiles; t += gridDim.x) total += spt;
+
+    if (wave_id >= GEO::WM * GEO::WN) {
+        const int pw = wave_id - GEO::WM * GEO::WN, stid = tid - CTHREADS;
+        constexpr int MAXF = GEO::MAXF, CPW = GEO::CPW, GF = GEO::GF, GI = GEO::GI, PERIOD = GEO::PERIOD;
+        const int64_t img_bytes = (int64_t)a.IW * a.IH * a.C * a.B * 2, flt_bytes = (int64_t)a.K * a.R * a.S * a.C * 2;
+        // Image: lane L of chunk i fetches channel row L / 8 of position i, 16-byte piece (L % 8) ^ 4 * (bit 1 of the row),
+        // and stores it at byte 16 L of the chunk: rows with bit 1 of c set keep their halves exchanged in LDS
+        const uint32_t row_bytes = (uint32_t)a.B * 2u;
+        const uint32_t ivoff = (uint32_t)(lane >> 3) * row_bytes + (uint32_t)(((lane & 7) ^ (((lane >> 4) & 1) << 2)) * 16);
+        uint32_t isoff[CPW];
+#pragma unroll
+        for (int i = 0; i < CPW; ++i)
+            isoff[i] = (uint32_t)(((i / YSI) * a.IH + (i % YSI)) * a.C + pw * 8) * row_bytes;
+        const uint32_t il0 = (uint32_t)(uintptr_t)(lds + pw * 1024 + lane * 16), il1 = il0 + IBUF;
+        // Filter: thread (kl = stid / C8, c8 = stid % C8) fetches the 16 bytes of channels 8*c8.. of output channel kl for
+        // each of the three taps r of the sub-unit's filter row
+        const int f_c8 = stid % C8, f_kl = stid / C8;
+        const uint32_t fg0 = ((uint32_t)f_kl * a.R * a.S * a.C + f_c8 * 8) * 2u;
+        const uint32_t fl0 = (uint32_t)(uintptr_t)(lds + GEO::FLT_OFF + (f_kl * F8 + f_c8) * 16);
+        uint32_t fsoff[MAXF];
+#pragma unroll
+        for (int i = 0; i < MAXF; ++i) fsoff[i] = (uint32_t)(i * a.S) * (uint32_t)a.C * 2u;
+        StagedWalk<KT, TB, TW, TH, CT> wf, wi;    // next sub-unit whose Filter taps / next Image unit to request
+        wf.init(a);
+        wi.init(a);
+        u32x4 freg[GF][MAXF], ireg[GI][CPW];
+        auto issue_flt = [&](auto setc) {
+            constexpr int set = decltype(setc)::value;
+            const __amdgpu_buffer_rsrc_t rf = wf.flt(a, flt_bytes);
+#pragma unroll
+            for (int i = 0; i < MAXF; ++i) {
+                const uint4 v = buf_load_u4(rf, fg0, fsoff[i]);
+                freg[set][i] = u32x4{v.x, v.y, v.z, v.w};
+            }
+            wf.next(a, 1);
+        };
+        auto issue_img = [&](auto setc) {
+            constexpr int set = decltype(setc)::value;
+            const __amdgpu_buffer_rsrc_t ri = wi.img(a, img_bytes);
+#pragma unroll
+            for (int i = 0; i < CPW; ++i) {
+                const uint4 v = buf_load_u4(ri, ivoff, isoff[i]);
+                ireg[set][i] = u32x4{v.x, v.y, v.z, v.w};
+            }
+            wi.next(a, BSI);
+        };
+        // sub-unit v = J (mod PERIOD): write its registers to LDS, announce it, refill the registers it leaves
+        auto step = [&](auto jc, int v) {
+            constexpr int J = decltype(jc)::value;
+            constexpr int fs = J % GF, fb = J % 2, is = (J / BSI) % GI, ib = (J / BSI) % 2;
+            constexpr bool img_step = J % BSI == 0;
+            if (v + J < total) {
+                lds_store16_seq<fb * FBUF, C8 * 16>(fl0, freg[fs], std::make_index_sequence<MAXF>{});
+                if constexpr (img_step)
+                    lds_store16_seq<0, C8 * 1024>(ib ? il1 : il0, ireg[is], std::make_index_sequence<CPW>{});
+                lds_done_then_barrier();
+            }
+            issue_flt(std::integral_constant<int, fs>{});
+            if constexpr (img_step) issue_img(std::integral_constant<int, is>{});
+        };
+        static_for(issue_flt, std::make_index_sequence<GF>{});
+        static_for(issue_img, std::make_index_sequence<GI>{});
+        for (int v = 0; v < total; v += PERIOD)
+            static_for([&](auto jc) { step(jc, v); }, std::make_index_sequence<PERIOD>{});
+    } else {
+        const int wm = wave_id % WM, wn = wave_id / WM;
+        const int j = lane & 31, g = lane >> 5, i16 = lane & 15, jhalf = (lane >> 4) & 1;
+        f32x16 acc[1][NBLK];
+        zero_acc(acc);
+        // per-lane LDS offsets inside a buffer: Filter row of output channel wm*32 + j, contraction half g;
+        // Image: row 8g + i16/4 of a 16-channel step, the 8 bytes that hold images 4*(i16 % 4).. of this lane group
+        const uint32_t al = (uint32_t)(GEO::FLT_OFF + ((wm * 32 + j) * F8 + g) * 16);
+        const int q = wn * 4 + 2 * jhalf + ((i16 & 3) >> 1);
+        const uint32_t xl = (uint32_t)((8 * g + (i16 >> 2)) * ROW + ((q ^ (((i16 >> 3) & 1) << 2)) * 16) + (i16 & 1) * 8);
+        bf16x8 A[2][BR], X[2][TH][XS];
+        // one 16-channel step cs of a sub-unit: the three taps r of its filter row, the TH x XS Image positions they read
+        auto load_step = [&](uint32_t ab, uint32_t xb, int cs, int set) {
+#pragma unroll
+            for (int r = 0; r < BR; ++r)
+                A[set][r] = *(const CACNN_LDS(bf16x8)*)(lds + ab + (r * C8 + 2 * cs) * 16);
+#pragma unroll
+            for (int h = 0; h < TH; ++h)
+#pragma unroll
+                for (int x = 0; x < XS; ++x) {
+                    CACNN_LDS(char)* const p = lds + xb + ((x * YSI + h) * CT + 16 * cs) * ROW;
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CACNN_LDS(s16x4)*)p);
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CACNN_LDS(s16x4)*)(p + 4 * ROW));
+                    X[set][h][x] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                }
+        };
+        auto mfma_step = [&](int set) {
+#pragma unroll
+            for (int r = 0; r < BR; ++r)
+#pragma unroll
+                for (int h = 0; h < TH; ++h)
+#pragma unroll
+                    for (int w = 0; w < TW; ++w)
+                        acc[0][h * TW + w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[set][r], X[set][h][w + r],
+                                                                                     acc[0][h * TW + w], 0, 0, 0);
+        };
+        const int64_t out_kstride = (int64_t)a.H * a.W * a.B;      // floats between output channels
+        const uint32_t out_lane = (uint32_t)(g * 4) * (uint32_t)out_kstride + (uint32_t)(32 * wn + j);
+        int left = total, in_tile = spt, t = blockIdx.x;
+        uint32_t foff = 0, ioff = 0;      // the buffers of the sub-unit being multiplied
+        int sl = 0;                       // its filter row within the Image unit: the Image rows it reads start at sl
+        // one sub-unit; MORE: another one follows (the other Filter buffer; the other Image buffer when an Image unit ends)
+        auto unit = [&](auto more) {
+            constexpr bool MORE = decltype(more)::value;
+            load_step(al + foff, xl + ioff + (uint32_t)(sl * CT * ROW), 1, 1);
+            mfma_step(0);
+            interleave_front_hint<BR * NBLK, 2 * TH * XS + BR, 2>();
+            if constexpr (MORE) {
+                // hand the buffers back once the last fragments have landed, read the next sub-unit's first fragments
+                // under this step's MFMAs
+                foff = FBUF - foff;
+                if (++sl == BSI) {
+                    sl = 0;
+                    ioff = IBUF - ioff;
+                }
+                lds_done_then_barrier_known(acc[0][NBLK - 1]);
+                load_step(al + foff, xl + ioff + (uint32_t)(sl * CT * ROW), 0, 0);
+            }
+            mfma_step(1);
+            if constexpr (MORE) interleave_front_hint<BR * NBLK, 2 * TH * XS + BR, 2>();
+            // keep the reads above where they are: left alone, the compiler sinks them to the top of the next
+            // sub-unit, in front of the MFMAs that need them
+            asm volatile("" ::: "memory");
+            --left;
+            if (__builtin_expect(--in_tile == 0, 0)) {
+                const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
+#pragma unroll
+                for (int n = 0; n < NBLK; ++n) {
+                    float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + tc.h0 + n / TW) * a.W + tc.w0 + n % TW) * a.B + tc.b0);
+                    store_block_exact<true>(blk, out_kstride, out_lane, acc[0][n]);
+                }
+                in_tile = spt;
+                t += gridDim.x;
+            }
+        };
+        if (left > 0) {
+            lds_done_then_barrier_known();      // sub-unit 0 is staged
+            load_step(al, xl, 0, 0);
+            while (left > 1) unit(std::true_type{});
+            unit(std::false_type{});
+        }
+    }
+}
+
 // ---- fixed geometry, fp32, Image loaded straight into LDS -------------------------------------------------------------
 // The same staging for fp32 tiles of 8 images x 4 x 4 output positions.  Next to an fp32 MFMA stream a staging wave
 // gets even fewer issue slots than next to a bf16 one, and a register-staged kernel was measured with its staging
@@ -2712,6 +2977,18 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
+// bf16 staged through registers with a deep prefetch: 64 images, 64 output channels, 32-channel slices, Image units of BSI filter rows
+#define CACNN_STAGED_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH, BSI)                                              \
+    {                                                                                                          \
+        {NAME, 1, 2, 2, 1, Bf16StagedFixed<TW, TH, BSI>::NBLK, 64, TW, TH, 2, 1, Bf16StagedFixed<TW, TH, BSI>::MAXF, 1, 3, 1.0f, 32, 3,  \
+         BSI, Bf16StagedFixed<TW, TH, BSI>::YSI, 1, 1, Bf16StagedFixed<TW, TH, BSI>::LDS_BYTES, UNIT_US, FIXED_US, 0},  \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                if (!Bf16StagedFixed<TW, TH, BSI>::matches_host(a) || lds != (size_t)Bf16StagedFixed<TW, TH, BSI>::LDS_BYTES) return 1; \
+                return launch_kernel(conv_bf16_staged_kernel<TW, TH, BSI>, attr_done, 512, a, grid, lds, stream); \
+            }                                                                                                  \
+    }
+
 // fp32 with the Image loaded straight into LDS: 8 images x 4 x 4 positions, 64 output channels, 16-channel slices of three filter rows
 #define CACNN_F32_DIRECT_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                               \
     {                                                                                                          \
@@ -2795,6 +3072,8 @@ static const Variant g_variants[] = {
     CACNN_F32_DIRECT16_VARIANT("f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r3s3", 4.1f, 2.6f, 2, 7),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.0f, 4.5f, 7, 1),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.62f, 4.2f, 2, 2),
+    CACNN_STAGED_VARIANT("bf16 fxr k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.1f, 4.5f, 7, 1, 1),
+    CACNN_STAGED_VARIANT("bf16 fxr k64 b64w2h2 w2x2 m1n4 c32r3s3", 2.0f, 4.2f, 2, 2, 3),
     // fixed geometry for the stem-layer shape: 7x7 taps, strides 2, three channels
     {{"f32 fxsd k64 b32w2h2 w2x2 m1n2 c3r7s7 s2", 0, 2, 2, 1, F32StemDirect<2, 2>::NBLK, 32, 2, 2, 2, 1, 1, 1, 0, 1.0f, 3, 7, 7,
       F32StemDirect<2, 2>::YS, 2, 2, F32StemDirect<2, 2>::LDS_BYTES, 5.15f, 4.5f, 1},

@@ -90,7 +90,7 @@ def variants_for(cc, dtype):
 
 # the forced contraction tiles; the last two are the ones the fixed-geometry kernels are compiled for
 FORCED_TILES = {"f32": ((1 << 20, 1 << 20, 1 << 20), (3, 2, 1), (16, 3, 3), (32, 3, 1)),
-                "bf16": ((1 << 20, 1 << 20, 1 << 20), (16, 2, 1), (16, 3, 3), (32, 3, 1))}
+                "bf16": ((1 << 20, 1 << 20, 1 << 20), (16, 2, 1), (16, 3, 3), (32, 3, 1), (32, 3, 3))}
 
 
 def staged_tile_fits(cc, cfg, vi, bc, br, bs):
@@ -155,21 +155,23 @@ def test_every_variant_runs_on_some_ragged_shape(env, dtype):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_direct_kernels_with_one_to_seven_units_per_workgroup(env, dtype):
-    """The staging schedule of the fixed-geometry kernels has separate code for workgroups with one, two, and three
-    or more units (tile x contraction slice) and two different ways out of its loop (odd and even counts): one tile
-    with 1..7 slices, on every such kernel."""
+    """The staging schedules of the fixed-geometry kernels have separate code for workgroups with one, two, and three
+    or more units (tile x contraction slice), different ways out of their loops (odd and even counts) and, in the
+    register-staged kernels, a rotation of four or six register sets and buffers: one tile with 1..7 units (with
+    3..21 sub-units where an Image unit serves three filter rows), on every such kernel."""
     cc, torch = env
     names = {cc.cacnn_variant_name(i): i for i in variants_for(cc, dtype)}
-    fx = [n for n in names if " fxd " in n or " fxd16 " in n]
+    fx = [n for n in names if " fxd " in n or " fxd16 " in n or " fxr " in n]
     assert len(fx) >= 2
     for name in fx:
         v = names[name]
         tb, tw, th = (int(x) for x in re.search(r" b(\d+)w(\d+)h(\d+) ", name).groups())
+        bc, _, bs = (int(x) for x in re.search(r" c(\d+)r(\d+)s(\d+)", name).groups())
         for units in range(1, 8):
-            if dtype == "f32":
-                C, S, bc, bs = 16 * units, 3, 16, 3
+            if bs == 3:
+                C, S = bc * units, 3          # units c-slices, each with all three filter rows
             else:
-                C, S, bc, bs = 32, units, 32, 1
+                C, S = bc, units              # one c-slice, units filter rows
             cfg = ci.custom(f"units{units}", tb, C, 64, tw, th, 3, S, 1, 1, dtype=dtype, dist="normal", seed=500 + units)
             img, flt = ci.make_inputs(cfg)
             ref, ab = gu.oracle_full(cfg, img, flt)
