@@ -293,7 +293,8 @@ def traffic_probe(cc, torch, ci, np, cfg, xcd_split_k=0):
     cc.cacnn_conv_forward_with_plan(cfg.dims, dt, plan, d_img, d_flt, d_out)      # warm
     torch.cuda.synchronize()
     del evict
-    print(json.dumps({"traffic_probe": cfg.name, "copy_bytes_each_way": n, "xcd_split_k": plan.xcd_split_k}))
+    print(json.dumps({"traffic_probe": cfg.name, "copy_bytes_each_way": n, "xcd_split_k": plan.xcd_split_k,
+                      "variant": cc.cacnn_variant_name(plan.variant)}))
 
 
 def division_report(cc, torch, ci, np, cfg, steps, warmup):
