@@ -73,8 +73,8 @@ typedef struct {
     double lp_volume;        /* G*: product of lp_tile */
     double lp_cost_words;    /* F*M/G*  (Section 5.2) */
     double bound_words;      /* Theorem 1 at the same M */
-    int32_t paper_case;      /* Appendix A leaf for strides 1: 11,16 = Cases 1.1,1.6; 1 = another Case-1 leaf;
-                                21, 221, 2221, 2222 = Cases 2.1 .. 2.2.2.2; 0 = strides are not both 1 */
+    int32_t paper_case;      /* Appendix A leaf for strides 1, its number without the dots: 11 .. 19, 110 = Cases 1.1 .. 1.9,
+                                1.10; 21, 221, 2221, 2222 = Cases 2.1 .. 2.2.2.2; 0 = strides are not both 1 */
     /* --- tiling launched on the GPU --- */
     int32_t variant;         /* index into the compiled kernel table, see cacnn_variant_name */
     int32_t b_b, b_c, b_k, b_w, b_h;       /* tile of (b,c,k,w,h) held by one workgroup per contraction step */

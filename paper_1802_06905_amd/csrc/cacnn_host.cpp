@@ -44,10 +44,13 @@ struct LpSolution {
     double log_volume;
 };
 
-LpSolution solve_tiling_lp(const cacnn_problem& p, double M) {
+// M_out, M_flt, M_img: the words the Out, Filter and Image tiles may occupy (the paper's LP has one M for all three; the
+// gfx950 budget has accumulator registers for Out and LDS for the other two).  l[] and log_volume are logarithms to base
+// `base`.
+LpSolution solve_tiling_lp(const cacnn_problem& p, double M_out, double M_flt, double M_img, double base) {
     const int n = 9;
     enum { b_, c_, k_, w_, h_, r1_, r2_, s1_, s2_ };
-    const double lnM = std::log(M);
+    const double lnM = std::log(base);
     auto lg = [&](double x) { return std::log(x) / lnM; };
     const double sw = (double)std::min(p.sigma_w, p.R), sh = (double)std::min(p.sigma_h, p.S);
 
@@ -68,12 +71,12 @@ LpSolution solve_tiling_lp(const cacnn_problem& p, double M) {
     row({s2_}, lg(sh));
     row({r1_}, lg((double)p.R) - lg(sw));
     row({s1_}, lg((double)p.S) - lg(sh));
-    row({b_, k_, w_, h_}, 1.0);                    // Out tile
-    row({c_, k_, r1_, r2_, s1_, s2_}, 1.0);        // Filter tile
-    row({b_, c_, w_, h_, r2_, s2_}, 1.0);          // Image tile, four products
-    row({b_, c_, w_, s1_, r2_, s2_}, 1.0);
-    row({b_, c_, r1_, h_, r2_, s2_}, 1.0);
-    row({b_, c_, r1_, s1_, r2_, s2_}, 1.0);
+    row({b_, k_, w_, h_}, lg(M_out));                    // Out tile
+    row({c_, k_, r1_, r2_, s1_, s2_}, lg(M_flt));        // Filter tile
+    row({b_, c_, w_, h_, r2_, s2_}, lg(M_img));          // Image tile, four products
+    row({b_, c_, w_, s1_, r2_, s2_}, lg(M_img));
+    row({b_, c_, r1_, h_, r2_, s2_}, lg(M_img));
+    row({b_, c_, r1_, s1_, r2_, s2_}, lg(M_img));
 
     const int m = (int)A.size();
     // tableau: m rows x (n + m + 1) columns, objective row last; maximise sum x  <=>  reduced costs start at -1
@@ -127,15 +130,24 @@ LpSolution solve_tiling_lp(const cacnn_problem& p, double M) {
     return s;
 }
 
+LpSolution solve_tiling_lp(const cacnn_problem& p, double M) { return solve_tiling_lp(p, M, M, M, M); }
+
 // Appendix A, Theorem 2 (strides 1): which leaf of the decision tree the shape falls in.
 int appendix_a_case(const cacnn_problem& p, double M) {
     if (p.sigma_w != 1 || p.sigma_h != 1) return 0;
     const double img = (double)p.C * p.H * p.W * p.B, flt = (double)p.K * p.C * p.R * p.S,
                  out = (double)p.K * p.H * p.W * p.B;
     if (std::min(img, std::min(flt, out)) <= M) {
-        if (img <= M && flt <= M && out <= M) return 11;
-        if (img > M && out > M && flt <= M) return 16;
-        return 1;
+        // Case 1, by which arrays exceed M (the sub-cases of the proof of the Case 1 lemma)
+        const bool bi = img > M, bf = flt > M, bo = out > M;
+        const double hwb = (double)p.H * p.W * p.B;
+        if (!bi && !bf && !bo) return 11;
+        if (bi && !bf && !bo) return 12;
+        if (bo && !bf && !bi) return 13;
+        if (bf && !bi && !bo) return (double)p.K * p.C <= M ? 14 : 15;
+        if (bi && bo) return 16;
+        if (bi && bf) return (double)p.K >= hwb ? 17 : 18;
+        return (double)p.C >= hwb ? 19 : 110;
     }
     const double RS = (double)p.R * p.S, BHW = (double)p.B * p.H * p.W;
     if (RS >= M) return 21;
@@ -441,6 +453,98 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
     return found;
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// The generic kernels' tile, sized from the Section 5 linear program at the gfx950 budget.  The paper bounds three
+// tiles by one M; here the Out tile lives in accumulator registers (at most 7 MFMA blocks of 32 x 32 per multiplying
+// wave, four such waves: 28672 words) and the Image and Filter tiles share the LDS, double-buffered, so each may take a
+// quarter of it (the paper's own slack: per-array bounds instead of a bound on the sum).  The LP's optimum gives the
+// Out tile's two extents k* and P* = b*w*h and says how much of the filter a contraction tile should cover; the compiled
+// variant nearest to (k*, P*) in log distance is launched, where padding (tile extents beyond the problem's), an uneven
+// or short tile count over the compute units (Section 7: divide the output over all processors) and the kernel family
+// (measured ratios between the one-tile, pipelined and wave-specialised kernels on the same tile) add to the distance.
+// The contraction tile is the one of largest volume b_c b_r b_s the LDS really holds, whole filter extents first as in
+// the LP's optimum for R S << M (Appendix A, Case 2.2.2.1: b_R = R, b_S = S).
+struct GpuLpTile {
+    double k, P, c, r, s;
+};
+
+GpuLpTile solve_gpu_lp(const cacnn_problem& p, int dtype, const cacnn_machine& mach) {
+    const double esz = dtype == CACNN_F32 ? 4.0 : 2.0;
+    const double M_acc = 28672.0, M_lds = std::max(2.0, (double)mach.lds_bytes / (4.0 * esz));
+    const LpSolution s = solve_tiling_lp(p, M_acc, M_lds, M_lds, std::exp(1.0));
+    GpuLpTile t;
+    t.k = std::exp(s.l[2]);
+    t.P = std::exp(s.l[0] + s.l[3] + s.l[4]);
+    t.c = std::exp(s.l[1]);
+    t.r = std::exp(s.l[5] + s.l[6]);
+    t.s = std::exp(s.l[7] + s.l[8]);
+    return t;
+}
+
+bool evaluate_lp(int vi, const cacnn_problem& p, const cacnn_machine& mach, const GpuLpTile& lp, Choice* best) {
+    const VariantInfo& v = variant(vi).info;
+    const int gran = (v.dtype == CACNN_F32 && p.C % 4 == 0) ? 4 : v.cgran();
+    const int Cpad = (int)std::min<int64_t>(round_up(p.C, gran), 1 << 20);
+    const bool vimg = vec_img_ok(v, p);
+    const int64_t tiles_k = ceil_div(p.K, v.KT()), tiles_b = ceil_div(p.B, v.TB), tiles_w = ceil_div(p.W, v.TW),
+                  tiles_h = ceil_div(p.H, v.TH);
+    int64_t n_wg = 0, t = 0;
+    if (!mul_check(tiles_k, tiles_b, INT32_MAX, &t) || !mul_check(t, tiles_w, INT32_MAX, &t) ||
+        !mul_check(t, tiles_h, INT32_MAX, &n_wg))
+        return false;
+    // the contraction tile of largest volume that is legal and fits: whole filter extents first, then the c-slice
+    Geometry g_best{};
+    double vol_best = -1.0;
+    for (int bR = (int)std::min<int64_t>(p.R, 1 << 12); bR >= 1; bR = (bR + 1) / 2 == bR ? 0 : (bR + 1) / 2)
+        for (int bS = (int)std::min<int64_t>(p.S, 1 << 12); bS >= 1; bS = (bS + 1) / 2 == bS ? 0 : (bS + 1) / 2)
+            for (int d = 1; d <= 64; ++d) {
+                const int ct = (int)round_up(ceil_div(Cpad, d), gran);
+                const Geometry g = make_geometry(v, p, ct, bR, bS, vimg);
+                if (g.legal && g.lds_bytes <= mach.lds_bytes) {
+                    // volume, with a premium on covering the filter extents (the halo re-staging the LP's optimum avoids)
+                    const double vol = (double)std::min<int64_t>(ct, p.C) * bR * bS * ((int64_t)bR * bS == p.R * p.S ? 4.0 : 1.0);
+                    if (vol > vol_best) {
+                        vol_best = vol;
+                        g_best = g;
+                    }
+                    break;      // smaller c-slices of the same (b_r, b_s) only lose volume
+                }
+                if (ct == gran) break;
+            }
+    if (vol_best < 0.0) return false;
+    const double ku = (double)std::min<int64_t>(v.KT(), p.K);
+    const double Pu = (double)std::min<int64_t>(v.TB, p.B) * (double)std::min<int64_t>(v.TW, p.W) * (double)std::min<int64_t>(v.TH, p.H);
+    double dist = std::fabs(std::log(ku / lp.k)) + std::fabs(std::log(Pu / lp.P));
+    dist += std::log((double)v.KT() * v.NT() / (ku * Pu));                          // padded MFMA rows and columns
+    // global runs along b shorter than a 64-byte half line use a fraction of every line they touch
+    dist += std::log(std::max(1.0, 64.0 / ((double)std::min<int64_t>(v.TB, p.B) * (v.dtype == CACNN_F32 ? 4.0 : 2.0))));
+    const int64_t resident = std::max<int64_t>(1, std::min<int64_t>(v.occ, mach.lds_bytes / std::max<int64_t>(1, g_best.lds_bytes)));
+    const double slots = (double)mach.num_cu * (v.pipelined ? 1.0 : (double)resident);
+    dist += std::log((double)ceil_div(n_wg, (int64_t)slots) * slots / (double)n_wg);    // idle or unevenly loaded compute units
+    dist += v.pipelined == 2 ? 0.0 : (v.pipelined == 1 ? std::log(1.3) : std::log(2.5));  // kernel family
+    dist += std::log((double)v.tune);
+    if (best->variant < 0 || dist < best->cost) {
+        best->variant = vi;
+        best->g = g_best;
+        best->cost = dist;
+        best->n_wg = n_wg;
+        best->words = staged_words(v, p, g_best, &best->img_words);
+    }
+    return true;
+}
+
+// Measured against the fastest of all variants (cacnn_tune) on sixteen mid-size and ragged layers, the LP-sized choice is
+// 1.38x slower in the geometric mean (worst 2.1x) and the calibrated cycle model 1.34x (worst 2.5x): on problems this
+// small what separates the variants is how well each kernel family keeps its pipeline full, which neither the LP nor
+// the model prices well.  The cycle model stays the default; CACNN_PLANNER=lp selects the LP-sized choice.
+bool planner_uses_lp() {
+    static const bool lp = [] {
+        const char* e = std::getenv("CACNN_PLANNER");
+        return e && std::strcmp(e, "lp") == 0;
+    }();
+    return lp;
+}
+
 // workgroups launched: one per Out tile, or for the persistent kernels as many as the machine holds at once
 int64_t launch_grid(const VariantInfo& v, const Geometry& g, int64_t n_tiles, const cacnn_machine& mach) {
     if (!v.pipelined) return n_tiles;
@@ -561,11 +665,15 @@ int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, c
     for (int vi = 0; vi < num_variants() && allow_pipelined; ++vi)
         if (variant(vi).info.dtype == dtype && variant(vi).info.fx_ct > 0) evaluate(vi, *p, mach, &best);
     if (best.variant < 0 || best.n_wg * 8 < mach.num_cu) {
+        const bool use_lp = planner_uses_lp();
+        if (use_lp) best = Choice();
+        const GpuLpTile lp = solve_gpu_lp(*p, dtype, mach);
         for (int vi = 0; vi < num_variants(); ++vi) {
             if (variant(vi).info.dtype != dtype) continue;
             if (variant(vi).info.pipelined && !allow_pipelined) continue;
             if (variant(vi).info.fx_ct > 0) continue;      // already in
-            evaluate(vi, *p, mach, &best);
+            if (use_lp) evaluate_lp(vi, *p, mach, lp, &best);
+            else evaluate(vi, *p, mach, &best);
         }
     }
     if (best.variant < 0) return CACNN_ERR_INVALID_ARG;  // nothing fits the given LDS size

@@ -115,6 +115,21 @@ def test_plan_paper_block_matches_oracle(name):
         assert plan.paper_case == 0
 
 
+def test_plan_appendix_a_leaf_matches_oracle_on_random_shapes():
+    rng = np.random.default_rng(4)
+    seen = set()
+    for _ in range(400):
+        R, S = (int(x) for x in rng.integers(1, 6, 2))
+        W, H = int(rng.integers(R, 20)), int(rng.integers(S, 20))
+        B, C, K = (int(2 ** rng.integers(0, 8)) for _ in range(3))
+        lds = int(2 ** rng.integers(11, 18))
+        plan = cc.cacnn_tile_plan((B, C, K, W, H, R, S, 1, 1), 0, cc.Machine(lds, 512 * 1024, 256))
+        label = olp.appendix_a_case(B, C, K, W, H, R, S, lds / 4)[0]
+        assert str(plan.paper_case) == label.replace(".", ""), (B, C, K, W, H, R, S, lds)
+        seen.add(label)
+    assert len(seen) >= 10, seen
+
+
 def test_plan_lp_volume_matches_oracle_on_random_shapes():
     rng = np.random.default_rng(1)
     for _ in range(150):
