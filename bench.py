@@ -162,7 +162,7 @@ def committed_traffic(name, variant=None, xcd_split_k=None):
     the one RECORDED for this shape, not a measurement of this run.  Each `traffic` row names the kernel variant and the
     XCD division it was recorded with; if the plan of this run differs (or the row names none), the figure would
     belong to another launch configuration and None is returned instead."""
-    for fname in ("hbm_traffic_c1-c5.txt", "pooling_p1.txt", "work_division_d1.txt"):
+    for fname in ("hbm_traffic_c1-c5.txt", "pooling_p1.txt", "two_level_layouts.txt"):
         try:
             with open(os.path.join(ROOT, "profiles", fname)) as f:
                 for line in f:
@@ -264,7 +264,7 @@ def cpu_baseline(cfg, img, flt, np):
                       f"{reps} passes)"}, ref, ab, k_use
 
 
-def traffic_probe(cc, torch, ci, np, cfg, xcd_split_k=0):
+def traffic_probe(cc, torch, ci, np, cfg, xcd_split_k=0, xcd_walk=0):
     """Dispatch sequence for the HBM-traffic counters (FETCH_SIZE / WRITE_SIZE, KiB per dispatch):
     a plain copy of known size to scale the counters by, then the workload cold (caches evicted) and warm.
     xcd_split_k > 0 forces that division of the XCDs over the output channels (0: the planner's)."""
@@ -287,51 +287,57 @@ def traffic_probe(cc, torch, ci, np, cfg, xcd_split_k=0):
     torch.cuda.synchronize()
     plan = cc.cacnn_tile_plan(cfg.dims, dt)
     if xcd_split_k:
-        plan.xcd_split_k = xcd_split_k
+        plan.xcd_split_k, plan.xcd_walk = xcd_split_k, xcd_walk
     cc.cacnn_conv_forward_with_plan(cfg.dims, dt, plan, d_img, d_flt, d_out)      # cold
     torch.cuda.synchronize()
     cc.cacnn_conv_forward_with_plan(cfg.dims, dt, plan, d_img, d_flt, d_out)      # warm
     torch.cuda.synchronize()
     del evict
     print(json.dumps({"traffic_probe": cfg.name, "copy_bytes_each_way": n, "xcd_split_k": plan.xcd_split_k,
-                      "variant": cc.cacnn_variant_name(plan.variant)}))
+                      "xcd_walk": plan.xcd_walk, "variant": cc.cacnn_variant_name(plan.variant)}))
 
 
 def division_report(cc, torch, ci, np, cfg, steps, warmup):
-    """Section 7 with the eight XCDs as the processors: time of the workload for every division of the XCDs over the
-    output channels (a_K = 1, 2, 4, 8), the one the planner chooses, and the paper's bound for each (M = LDS words,
-    p = 8, the positions divided along h)."""
+    """Two levels, the eight XCDs as Section 7's processors: for every layout of an XCD's run of tiles that
+    cacnn_two_level_plan considers (a_K groups of output channels x the order inside a group), the time of the workload, the
+    words the model says the L2s fetch, the recorded counter figure where one is committed, and Section 7's bound."""
     img, flt = ci.make_inputs(cfg)
     d_img = torch.from_numpy(ci.bf16_bits(img).view(np.int16).reshape(-1)).cuda()
     d_flt = torch.from_numpy(ci.bf16_bits(flt).view(np.int16).reshape(-1)).cuda()
     d_out = torch.empty(int(np.prod(cfg.out_shape)), dtype=torch.float32, device="cuda:0")
     plan = cc.cacnn_tile_plan(cfg.dims, 1)
-    chosen = plan.xcd_split_k
+    l2 = cc.cacnn_two_level_plan(cfg.dims, 1)
     esz = 2.0
-    img_b = float(np.prod(cfg.image_shape)) * esz
-    flt_b = float(np.prod(cfg.filter_shape)) * esz
-    M = LDS_BYTES / esz
-    rep = {"workload": f"{cfg.name}: B={cfg.B} C={cfg.C} K={cfg.K} W=H={cfg.W} R=S={cfg.R} bf16", "chosen_a_K": chosen,
-           "variant": cc.cacnn_variant_name(plan.variant), "image_bytes": img_b, "filter_bytes": flt_b, "divisions": {}}
-    a, b = cc.cacnn_work_division(cfg.dims, M, 8)
-    rep["paper_division_p8"] = {"a_B_a_K_a_W_a_H": list(a), "bound_words": b.bound}
-    for ak in (1, 2, 4, 8):
-        plan.xcd_split_k = ak
+    n_out = float(np.prod(cfg.out_shape))
+    M2 = 4 * 1024 * 1024 / esz
+    rep = {"workload": f"{cfg.name}: B={cfg.B} C={cfg.C} K={cfg.K} W=H={cfg.W} R=S={cfg.R} bf16",
+           "chosen_a_K": l2.a_k, "chosen_walk": l2.walk, "variant": cc.cacnn_variant_name(plan.variant), "grid": plan.grid[0],
+           "image_bytes": float(np.prod(cfg.image_shape)) * esz, "filter_bytes": float(np.prod(cfg.filter_shape)) * esz,
+           "lp_at_M_l2": {"tile_b_c_k_w_h": [l2.lp_tile[i] for i in range(5)], "cost_words": l2.lp_cost_words,
+                          "bound_words": l2.bound_words,
+                          "tile_in_whole_lds_tiles_b_k_w_h": [l2.l2_tile_b, l2.l2_tile_k, l2.l2_tile_w, l2.l2_tile_h]},
+           "layouts": {}}
+    a, b = cc.cacnn_work_division(cfg.dims, M2, 8)
+    rep["paper_division_p8_M_l2"] = {"a_B_a_K_a_W_a_H": list(a), "bound_words": b.bound}
+    for i in range(l2.n_candidates):
+        ak, walk = l2.cand_a_k[i], l2.cand_walk[i]
+        plan.xcd_split_k, plan.xcd_walk = ak, walk
+        condition_power_state(cc, torch, ci, np, "bf16")
         for _ in range(warmup):
             cc.cacnn_conv_forward_with_plan(cfg.dims, 1, plan, d_img, d_flt, d_out)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
         e0.record()
         for _ in range(steps):
             cc.cacnn_conv_forward_with_plan(cfg.dims, 1, plan, d_img, d_flt, d_out)
         e1.record()
         torch.cuda.synchronize()
         sec = e0.elapsed_time(e1) * 1e-3 / steps
-        pb = cc.cacnn_parallel_bound(cfg.dims, M, (1, ak, 1, min(8 // ak, cfg.H)))
-        rep["divisions"][str(ak)] = {"us": sec * 1e6, "tflops": 2.0 * cfg.macs / sec / 1e12,
-                                     "replicated_bytes_model": ak * img_b + (8 // ak) * flt_b,
-                                     "paper_bound_words": pb.bound, "paper_bound_argmax": pb.argmax,
-                                     "hbm_bytes_profiled": committed_traffic(f"{cfg.name}_aK{ak}")}
+        pb = cc.cacnn_parallel_bound(cfg.dims, M2, (1, ak, 1, min(8 // ak, cfg.H)))
+        rep["layouts"][f"aK{ak}w{walk}"] = {
+            "us": sec * 1e6, "tflops": 2.0 * cfg.macs / sec / 1e12,
+            "model_bytes": esz * (l2.cand_words[i] - n_out) + 4.0 * n_out,
+            "paper_parallel_bound_words_M_l2": pb.bound,
+            "hbm_bytes_recorded": committed_traffic(f"{cfg.name}_aK{ak}w{walk}")}
     return rep
 
 
@@ -401,11 +407,14 @@ def main():
     ap.add_argument("--no-conditioning", action="store_true",
                     help="skip the 0.3 s of register-only MFMA load that precedes each shape's warm-up launches (a cold "
                          "board's power management makes the first hundreds of launches slower)")
-    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5", "p1", "d1"],
+    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5", "p1", "d1", "d2"],
                     help="c1..c5: the convolution shapes (c5, the largest, is the headline); p1: the pooling workload; "
-                         "d1: the work-division workload (a Filter-heavy layer, every division of the XCDs)")
+                         "d1, d2: the two-level workloads (a Filter-heavy layer on 64 and 256 images, every layout of an "
+                         "XCD's run of tiles)")
     ap.add_argument("--xcd-split-k", type=int, default=0,
                     help="with --traffic-probe: force this division of the XCDs over the output channels (0: planner's)")
+    ap.add_argument("--xcd-walk", type=int, default=0,
+                    help="with --traffic-probe and --xcd-split-k: order inside an XCD's run (0: k-tiles fastest, 1: positions)")
     ap.add_argument("--no-shapes", action="store_true", help="time only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -445,25 +454,25 @@ def main():
             out["cpu_baseline"] = rep["cpu_baseline"]
         print(json.dumps(out))
         return
-    if args.workload == "d1":
-        dcfg = ci.DIVISION_CONFIGS["d1"]
+    if args.workload in ("d1", "d2"):
+        dcfg = ci.DIVISION_CONFIGS[args.workload]
         if args.traffic_probe:
-            traffic_probe(cc, torch, ci, np, dcfg, args.xcd_split_k)
+            traffic_probe(cc, torch, ci, np, dcfg, args.xcd_split_k, args.xcd_walk)
             return
         rep = division_report(cc, torch, ci, np, dcfg, args.steps, args.warmup)
-        best = rep["divisions"][str(rep["chosen_a_K"])]
+        best = rep["layouts"][f"aK{rep['chosen_a_K']}w{rep['chosen_walk']}"]
         print(json.dumps({"metric": "conv TFLOP/s at 1 MI355X", "value": best["tflops"], "unit": "TFLOP/s", "n_gpus": 1,
                           "steps": args.steps, "warmup": args.warmup, "ms_per_step": best["us"] * 1e-3,
                           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
                           "data": "synthetic", "config": {"workload": rep["workload"], "variant": rep["variant"]},
                           "roofline": {"bound": "mfma", "achieved": best["tflops"], "peak": MFMA_PEAK_TFLOPS["bf16"],
                                        "unit": "TFLOP/s", "frac": best["tflops"] / MFMA_PEAK_TFLOPS["bf16"],
-                                       "traffic": best["hbm_bytes_profiled"]},
-                          "work_division": rep}))
+                                       "traffic": best["hbm_bytes_recorded"]},
+                          "two_level": rep}))
         return
     cfg = ci.CONFIGS[args.workload]
     if args.traffic_probe:
-        traffic_probe(cc, torch, ci, np, cfg, args.xcd_split_k)
+        traffic_probe(cc, torch, ci, np, cfg, args.xcd_split_k, args.xcd_walk)
         return
     # inputs first (host work), so that nothing idles the GPU between conditioning, warm-up and the timed launches
     names = [cfg.name] if args.no_shapes else list(ci.CONFIGS)

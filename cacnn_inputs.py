@@ -78,6 +78,9 @@ POOL_CONFIGS: Dict[str, Config] = {
 # its Image (10.6 MB), 16 k-tiles.  The paper names no such shape; this is a 3x3 layer of 1024 channels on 7x7 outputs.
 DIVISION_CONFIGS: Dict[str, Config] = {
     "d1": Config("d1", 64, 1024, 1024, 7, 7, 3, 3, 1, 1, "bf16", "normal", SEED_BASE + 7),
+    # the same layer on four times the images: 448 tiles, more than the compute units hold at once, so an XCD works
+    # through its run in two rounds and the order inside the run decides what its L2 still holds in the second
+    "d2": Config("d2", 256, 1024, 1024, 7, 7, 3, 3, 1, 1, "bf16", "normal", SEED_BASE + 8),
 }
 
 

@@ -95,6 +95,10 @@ typedef struct {
                                 divided into this many groups of output channels (a_K; 1, 2, 4 or 8, a divisor of the
                                 k-tile count) and 8 / a_K ranges of positions, whichever makes a_K*|Image| +
                                 (8/a_K)*|Filter| bytes smallest.  cacnn_conv_forward_with_plan: 0 = choose. */
+    int32_t xcd_walk;        /* order of an XCD's run of tiles: 0 = the k-tiles of a position tile are neighbours (the
+                                Image tile is fetched once, the Filter rows of the k-group stream past once per round of
+                                workgroups), 1 = the position tiles of a k-tile are neighbours (the other way round).
+                                Chosen with xcd_split_k by cacnn_two_level_plan's model; with_plan: used as given. */
 } cacnn_plan;
 
 /*
@@ -190,6 +194,7 @@ typedef struct {
     int32_t a_b, a_k, a_w, a_h;
 } cacnn_division;
 int cacnn_parallel_bound(const cacnn_problem* problem, double M_words, const cacnn_division* a, cacnn_bound* out);
+
 int cacnn_work_division(const cacnn_problem* problem, double M_words, int32_t p, cacnn_division* out_a,
                         cacnn_bound* out_bound);
 
@@ -263,6 +268,43 @@ const char* cacnn_variant_name(int variant);
 
 /* Static, NUL-terminated text for a status code (never NULL). */
 const char* cacnn_status_string(int status);
+
+/*
+ * Two memory levels (Section 4.1: any level of a hierarchy can play the fast memory; Section 7 with the eight XCDs, each
+ * with its own L2, as the processors): the workgroup's LDS tile of cacnn_tile_plan inside an L2-level tile.  Host only.
+ *   - the Section 5 linear program and Theorem 1 at M = one L2 in input words (lp_*, bound_words), and that LP's tile
+ *     rounded to whole LDS tiles (l2_tile_*, in elements: what the paper's schedule would keep in one L2);
+ *   - for every admissible way of laying an XCD's run of tiles out -- a_K groups of k-tiles (1, 2, 4, 8, a divisor of the
+ *     k-tile count) times the walk order inside a group (cacnn_plan.xcd_walk) -- the words the eight L2s fetch according
+ *     to a model of the launch: a workgroup's n-th tile belongs to round n, an XCD's round reads the Filter rows of its
+ *     k-tiles and the Image columns (input pixel x image group, all channels) of its position tiles, each L2 keeps what it
+ *     read in LRU order up to its size, and Out is written once;
+ *   - a_k / walk: candidates are taken in the order a_K = 1, 2, 4, 8, walk 0 before 1, and a later one replaces the
+ *     choice only if it saves a tenth of the chosen one's words; cacnn_tile_plan puts them into xcd_split_k / xcd_walk.
+ * machine_l2 NULL = MI355X (4 MiB, 8 XCDs, 32 compute units each).  Problems with more than two million tile x column
+ * pairs are not simulated: n_candidates = 0 and a_k is the closed-form choice that minimises a_K*|Image| + (8/a_K)*|Filter|.
+ * Errors: as cacnn_tile_plan.
+ */
+typedef struct {
+    int64_t l2_bytes;
+    int32_t n_xcd, cu_per_xcd;
+} cacnn_machine_l2;
+
+typedef struct {
+    double lp_tile[9];       /* Section 5 LP at M = L2 words, order b,c,k,w,h,r',r'',s',s'' */
+    double lp_volume, lp_cost_words, bound_words;
+    int32_t l2_tile_b, l2_tile_k, l2_tile_w, l2_tile_h;   /* lp_tile rounded to whole LDS tiles, clipped to the problem */
+    int32_t a_k, walk;       /* the chosen layout of an XCD's run */
+    int32_t n_candidates;
+    int32_t cand_a_k[8], cand_walk[8];
+    double cand_words[8];    /* modelled words fetched by the L2s plus Out once, per candidate */
+    double chosen_words;     /* the chosen candidate's (0 when nothing was simulated) */
+    double parallel_bound_words;   /* Section 7's expression at M = L2 words for the chosen a_K and the positions divided
+                                      over the remaining 8 / a_K (images first, then rows, then columns) */
+} cacnn_l2_plan;
+
+int cacnn_two_level_plan(const cacnn_problem* problem, int dtype, const cacnn_machine* machine,
+                         const cacnn_machine_l2* machine_l2, cacnn_l2_plan* out);
 
 #ifdef __cplusplus
 }

@@ -15,7 +15,8 @@ TEST INFRASTRUCTURE ONLY.  Three counters:
                            processor works through a list of rounds, a round being the tiles its compute units hold at
                            one time (Section 7's setting, with the caches made explicit): every tile names the
                            "atoms" it reads -- the Filter rows of its output channels as one atom, the Image columns
-                           (one input pixel of one image group, all channels) as one atom each -- and a processor
+                           (one input pixel of one image group, all channels) as one atom each, or the whole Image
+                           footprint of its position tile as one -- and a processor
                            keeps atoms in an LRU cache of M words.  This is a model of this build's own making (the
                            paper has no such level of detail); it is what the host's two-level plan is compared with.
 """
@@ -139,11 +140,14 @@ def processor_cache_words(rounds_per_processor: List[List[List[Tuple]]], atom_wo
 
 
 def launch_rounds(B, C, K, W, H, R, S, sigma_w, sigma_h, KT, TB, TW, TH, a_k: int, walk: int, n_xcd: int, grid: int,
-                  b_group: int = 1):
+                  b_group: int = 1, halo_shared: bool = False):
     """The rounds of this build's launch, for processor_cache_words: the tile list is a_k blocks of k-tile groups; inside a
     block the tiles are ordered k-tile fastest, then the b_group b-tiles that share cache lines, w, h, the remaining
     b-tile index (walk 0) or positions (same order) fastest and k-tile slowest (walk 1); XCD x owns a contiguous run of the list; workgroup i (XCD i % n_xcd) takes the tiles at places i / n_xcd,
     i / n_xcd + grid / n_xcd, ... of its XCD's run; round n holds every workgroup's n-th tile.
+    halo_shared: True makes every Image column an atom of its own, so position tiles that overlap in their halo fetch
+    the overlap once; False (what the measured launches do: a cache has turned a line over before the neighbouring
+    position tile asks for it) makes the whole Image footprint of a position tile one atom.
     Returns (rounds_per_processor, atom_words)."""
     cdiv = lambda a, b: -(-a // b)
     tk, tb, tw, th = cdiv(K, KT), cdiv(B, TB), cdiv(W, TW), cdiv(H, TH)
@@ -180,10 +184,17 @@ def launch_rounds(B, C, K, W, H, R, S, sigma_w, sigma_h, KT, TB, TW, TH, a_k: in
                 fa = ("F", k_i)
                 atom_words[fa] = min(KT, K - k_i * KT) * R * S * C
                 atoms.append(fa)
-                for x_i in range(sigma_w * w_i * TW, min(IW, sigma_w * w_i * TW + sigma_w * (TW - 1) + R)):
-                    for y_i in range(sigma_h * h_i * TH, min(IH, sigma_h * h_i * TH + sigma_h * (TH - 1) + S)):
-                        ia = ("I", b_i, x_i, y_i)
-                        atom_words[ia] = nb * C
-                        atoms.append(ia)
+                xr = range(sigma_w * w_i * TW, min(IW, sigma_w * w_i * TW + sigma_w * (TW - 1) + R))
+                yr = range(sigma_h * h_i * TH, min(IH, sigma_h * h_i * TH + sigma_h * (TH - 1) + S))
+                if halo_shared:
+                    for x_i in xr:
+                        for y_i in yr:
+                            ia = ("I", b_i, x_i, y_i)
+                            atom_words[ia] = nb * C
+                            atoms.append(ia)
+                else:
+                    ia = ("I", b_i, w_i, h_i, "tile")
+                    atom_words[ia] = nb * C * len(xr) * len(yr)
+                    atoms.append(ia)
             rounds[x].append(atoms)
     return rounds, atom_words

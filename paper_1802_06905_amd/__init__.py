@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     Machine,
     Plan,
     PoolBound,
+    MachineL2,
+    L2Plan,
     Problem,
     cacnn_conv_forward,
     cacnn_conv_forward_with_plan,
@@ -21,6 +23,7 @@ from .binding import (  # noqa: F401
     cacnn_parallel_bound,
     cacnn_pool_forward,
     cacnn_pool_lower_bound,
+    cacnn_two_level_plan,
     cacnn_probe_copy,
     cacnn_probe_mfma,
     cacnn_status_string,

@@ -62,6 +62,23 @@ class Plan(ctypes.Structure):
         ("lds_bytes_used", ctypes.c_int64),
         ("tile_volume", ctypes.c_double), ("predicted_words", ctypes.c_double),
         ("xcd_split_k", ctypes.c_int32),
+        ("xcd_walk", ctypes.c_int32),
+    ]
+
+
+class MachineL2(ctypes.Structure):
+    _fields_ = [("l2_bytes", ctypes.c_int64), ("n_xcd", ctypes.c_int32), ("cu_per_xcd", ctypes.c_int32)]
+
+
+class L2Plan(ctypes.Structure):
+    _fields_ = [
+        ("lp_tile", ctypes.c_double * 9), ("lp_volume", ctypes.c_double), ("lp_cost_words", ctypes.c_double),
+        ("bound_words", ctypes.c_double),
+        ("l2_tile_b", ctypes.c_int32), ("l2_tile_k", ctypes.c_int32), ("l2_tile_w", ctypes.c_int32),
+        ("l2_tile_h", ctypes.c_int32),
+        ("a_k", ctypes.c_int32), ("walk", ctypes.c_int32), ("n_candidates", ctypes.c_int32),
+        ("cand_a_k", ctypes.c_int32 * 8), ("cand_walk", ctypes.c_int32 * 8), ("cand_words", ctypes.c_double * 8),
+        ("chosen_words", ctypes.c_double), ("parallel_bound_words", ctypes.c_double),
     ]
 
 
@@ -101,6 +118,9 @@ _lib.cacnn_parallel_bound.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, 
 _lib.cacnn_work_division.restype = ctypes.c_int
 _lib.cacnn_work_division.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, ctypes.c_int32, ctypes.POINTER(Division),
                                      ctypes.POINTER(Bound)]
+_lib.cacnn_two_level_plan.restype = ctypes.c_int
+_lib.cacnn_two_level_plan.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctypes.POINTER(Machine), ctypes.POINTER(MachineL2),
+                                      ctypes.POINTER(L2Plan)]
 _lib.cacnn_pool_lower_bound.restype = ctypes.c_int
 _lib.cacnn_pool_lower_bound.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, ctypes.POINTER(PoolBound)]
 _lib.cacnn_pool_forward.restype = ctypes.c_int
@@ -236,6 +256,18 @@ def cacnn_work_division(problem, M_words: float, p: int):
     if rc != 0:
         raise CacnnError(rc, "cacnn_work_division")
     return (div.a_b, div.a_k, div.a_w, div.a_h), out
+
+
+def cacnn_two_level_plan(problem, dtype: int, machine: Optional[Machine] = None,
+                         machine_l2: Optional[MachineL2] = None) -> L2Plan:
+    """The Section 5 LP at M = one L2, and the layout of an XCD's run of tiles the two-level model prefers (host only)."""
+    out = L2Plan()
+    rc = _lib.cacnn_two_level_plan(ctypes.byref(_as_problem(problem)), int(dtype),
+                                   ctypes.byref(machine) if machine is not None else None,
+                                   ctypes.byref(machine_l2) if machine_l2 is not None else None, ctypes.byref(out))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_two_level_plan")
+    return out
 
 
 def cacnn_pool_lower_bound(problem, M_words: float) -> PoolBound:

@@ -8,7 +8,9 @@
 #include <cstdlib>
 #include <cstring>
 #include <limits>
+#include <list>
 #include <mutex>
+#include <unordered_map>
 #include <vector>
 
 #include "../../include/cacnn.h"
@@ -584,6 +586,140 @@ int choose_xcd_split_k(const cacnn_problem& p, int dtype, int64_t tiles_k, int n
     return best;
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// Two levels: the words the XCDs' L2s fetch for one way of laying out an XCD's run of tiles (a_K groups of k-tiles, walk
+// order inside a group).  A model of the launch: workgroup i belongs to XCD i % n_xcd and takes the tiles at places
+// i / n_xcd, i / n_xcd + grid / n_xcd, ... of its XCD's contiguous run of the tile list; an XCD's round n is every
+// workgroup's n-th tile; a tile reads the Filter rows of its k-tile (one atom) and the Image columns of its position
+// tile (one atom per input pixel and image group: all channels); an L2 keeps atoms in LRU order up to its size.
+struct L2Machine {
+    double words;      // one L2, in input words
+    int n_xcd, cu_per_xcd;
+};
+constexpr L2Machine kDefaultL2Bytes = {4.0 * 1024.0 * 1024.0, 8, 32};
+
+struct TileGeom {
+    int KT, TB, TW, TH, b_group;
+    int64_t grid;
+};
+
+int b_group_of(const VariantInfo& v, int dtype, int64_t tiles_b) {
+    // b-tiles that read different pieces of the same 128-byte Image lines stay adjacent in the tile order
+    const int64_t esz = dtype == CACNN_F32 ? 4 : 2;
+    const int64_t want = std::max<int64_t>(1, 128 / (int64_t)(v.TB * esz));
+    int g_b = 1;
+    for (int d = 1; d <= tiles_b && d <= want; ++d)
+        if (tiles_b % d == 0) g_b = d;
+    return g_b;
+}
+
+// -1: not simulated (too large)
+double l2_model_words(const cacnn_problem& p, const TileGeom& tg, int a_k, int walk, const L2Machine& m2) {
+    const int64_t tk = ceil_div(p.K, tg.KT), tb = ceil_div(p.B, tg.TB), tw = ceil_div(p.W, tg.TW), th = ceil_div(p.H, tg.TH);
+    const int64_t npos = tb * tw * th, n_tiles = tk * npos, kpg = tk / a_k;
+    const int64_t IW = p.sigma_w * (p.W - 1) + p.R, IH = p.sigma_h * (p.H - 1) + p.S;
+    const int64_t XS = p.sigma_w * (tg.TW - 1) + p.R, YS = p.sigma_h * (tg.TH - 1) + p.S;
+    if ((double)n_tiles > 2.0e6) return -1.0;
+    const int64_t q = n_tiles / m2.n_xcd, rem = n_tiles % m2.n_xcd;
+    const int64_t per_xcd = std::max<int64_t>(1, tg.grid / m2.n_xcd);
+    double total = 0.0;
+    std::vector<int64_t> atoms;
+    for (int x = 0; x < m2.n_xcd; ++x) {
+        const int64_t lo = x * q + std::min<int64_t>(x, rem), hi = lo + q + (x < rem ? 1 : 0);
+        // LRU over atom ids: id < tk is the Filter atom of a k-tile, tk + position tile the Image footprint of that tile.
+        // Position tiles that overlap in their halo are separate atoms: measured, an XCD's L2 serves a line to the
+        // workgroups of one position tile (they fetch it in the same microsecond) but has turned it over before a
+        // neighbouring position tile asks for it.
+        std::list<std::pair<int64_t, double>> lru;
+        std::unordered_map<int64_t, std::list<std::pair<int64_t, double>>::iterator> where;
+        double used = 0.0;
+        for (int64_t n0 = lo; n0 < hi; n0 += per_xcd) {
+            atoms.clear();
+            for (int64_t t = n0; t < std::min(hi, n0 + per_xcd); ++t) {
+                const int64_t kg = t / (kpg * npos), tl = t - kg * kpg * npos;
+                int64_t k_l, pos;
+                if (walk == 0) {
+                    k_l = tl % kpg;
+                    pos = tl / kpg;
+                } else {
+                    pos = tl % npos;
+                    k_l = tl / npos;
+                }
+                const int64_t b_lo = pos % tg.b_group, w_i = (pos / tg.b_group) % tw, h_i = (pos / (tg.b_group * tw)) % th,
+                              b_i = (pos / (tg.b_group * tw * th)) * tg.b_group + b_lo;
+                atoms.push_back(kg * kpg + k_l);
+                atoms.push_back(tk + (b_i * tw + w_i) * th + h_i);
+            }
+            std::sort(atoms.begin(), atoms.end());
+            atoms.erase(std::unique(atoms.begin(), atoms.end()), atoms.end());
+            for (int64_t id : atoms) {
+                auto it = where.find(id);
+                if (it != where.end()) {
+                    lru.splice(lru.end(), lru, it->second);
+                    continue;
+                }
+                double sz;
+                if (id < tk) {
+                    sz = (double)std::min<int64_t>(tg.KT, p.K - id * tg.KT) * (double)p.R * p.S * p.C;
+                } else {
+                    const int64_t pt = id - tk, h_i = pt % th, w_i = (pt / th) % tw, b_i = pt / (th * tw);
+                    const int64_t xs = std::min(IW, p.sigma_w * w_i * tg.TW + XS) - p.sigma_w * w_i * tg.TW,
+                                  ys = std::min(IH, p.sigma_h * h_i * tg.TH + YS) - p.sigma_h * h_i * tg.TH;
+                    sz = (double)std::min<int64_t>(tg.TB, p.B - b_i * tg.TB) * (double)p.C * (double)(xs * ys);
+                }
+                total += sz;
+                lru.emplace_back(id, sz);
+                where[id] = std::prev(lru.end());
+                used += sz;
+                while (used > m2.words && lru.size() > 1) {
+                    used -= lru.front().second;
+                    where.erase(lru.front().first);
+                    lru.pop_front();
+                }
+            }
+        }
+    }
+    return total + (double)p.K * p.H * p.W * p.B;
+}
+
+struct L2Choice {
+    int a_k = 1, walk = 0, n = 0;
+    int cand_a_k[8] = {0}, cand_walk[8] = {0};
+    double cand_words[8] = {0.0};
+    double words = 0.0;
+};
+
+L2Choice choose_l2_layout(const cacnn_problem& p, int dtype, const VariantInfo& v, int64_t grid, const L2Machine& m2) {
+    L2Choice c;
+    const int64_t tk = ceil_div(p.K, v.KT());
+    TileGeom tg{v.KT(), v.TB, v.TW, v.TH, b_group_of(v, dtype, ceil_div(p.B, v.TB)), grid};
+    const int64_t n_tiles = tk * ceil_div(p.B, v.TB) * ceil_div(p.W, v.TW) * ceil_div(p.H, v.TH);
+    for (int ak = 1; ak <= m2.n_xcd && ak <= 8; ak *= 2) {
+        if (m2.n_xcd % ak || tk % ak) continue;
+        for (int walk = 0; walk < 2; ++walk) {
+            // the walk order only differs when a group has several k-tiles; its decoding needs n_tiles * npos < 2^32
+            if (walk == 1 && (tk / ak < 2 || (double)n_tiles * (double)(n_tiles / tk) >= 4294967296.0)) continue;
+            const double w = l2_model_words(p, tg, ak, walk, m2);
+            if (w < 0.0) {
+                c = L2Choice();
+                c.a_k = choose_xcd_split_k(p, dtype, tk, m2.n_xcd);
+                return c;
+            }
+            c.cand_a_k[c.n] = ak;
+            c.cand_walk[c.n] = walk;
+            c.cand_words[c.n] = w;
+            // a later layout must save more than the few per cent the model is off by on the measured layouts
+            if (c.n == 0 || w < 0.97 * c.words) {
+                c.words = w;
+                c.a_k = ak;
+                c.walk = walk;
+            }
+            ++c.n;
+        }
+    }
+    return c;
+}
+
 int fill_plan(const cacnn_problem& p, int dtype, const cacnn_machine& mach, const Choice& ch, cacnn_plan* out) {
     const VariantInfo& v = variant(ch.variant).info;
     const double esz = dtype == CACNN_F32 ? 4.0 : 2.0;
@@ -624,7 +760,14 @@ int fill_plan(const cacnn_problem& p, int dtype, const cacnn_machine& mach, cons
     if (v.fx_whole && ceil_div(p.K, v.KT()) == 1)
         staged = ch.img_words + (double)out->grid[0] * (double)p.K * p.R * p.S * p.C;
     out->predicted_words = staged + (double)p.K * p.H * p.W * p.B;
-    out->xcd_split_k = choose_xcd_split_k(p, dtype, ceil_div(p.K, v.KT()), xcd_count());
+    {
+        L2Machine m2 = kDefaultL2Bytes;
+        m2.words /= esz;
+        m2.n_xcd = xcd_count();
+        const L2Choice l2 = choose_l2_layout(p, dtype, v, out->grid[0], m2);
+        out->xcd_split_k = l2.a_k;
+        out->xcd_walk = l2.walk;
+    }
     return CACNN_OK;
 }
 
@@ -696,7 +839,7 @@ bool have_device() {
     return g_device_ok;
 }
 
-int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int bS, int split_k, const void* image,
+int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int bS, int split_k, int walk, const void* image,
                 const void* filter, void* out, void* stream) {
     const Variant& var = variant(vi);
     const VariantInfo& v = var.info;
@@ -778,11 +921,25 @@ int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int b
     a.xcd_q = a.n_tiles / a.n_xcd;
     a.xcd_rem = a.n_tiles % a.n_xcd;
     a.d_nxcd = make_fastdiv((uint32_t)a.n_xcd);
-    if (split_k == 0) split_k = choose_xcd_split_k(p, dtype, a.tiles_k, a.n_xcd);
+    if (split_k == 0) {
+        // no layout given: the two-level model's choice for this variant and grid
+        L2Machine m2 = kDefaultL2Bytes;
+        m2.words /= (double)esz;
+        m2.n_xcd = a.n_xcd;
+        const L2Choice l2 = choose_l2_layout(p, dtype, v, launch_grid(v, g, grid, kDefaultMachine), m2);
+        split_k = l2.a_k;
+        walk = l2.walk;
+    }
     if (split_k < 1 || split_k > 8 || (split_k & (split_k - 1)) || a.tiles_k % split_k) return CACNN_ERR_INVALID_ARG;
+    if (walk != 0 && walk != 1) return CACNN_ERR_INVALID_ARG;
     a.k_groups = split_k;
     a.kpg = a.tiles_k / split_k;
     a.grp = a.n_tiles / split_k;
+    a.npos = a.grp / a.kpg;
+    // positions fastest needs a division by the position tiles of a block: exact while n_tiles * npos < 2^32
+    if (walk == 1 && (double)a.n_tiles * (double)a.npos >= 4294967296.0) return CACNN_ERR_INVALID_ARG;
+    a.pos_fastest = walk;
+    a.d_npos = make_fastdiv((uint32_t)a.npos);
     a.d_tk = make_fastdiv((uint32_t)a.kpg);
     a.d_bg = make_fastdiv((uint32_t)a.b_group);
     a.d_tw = make_fastdiv((uint32_t)a.tiles_w);
@@ -856,7 +1013,7 @@ int cacnn_conv_forward(const cacnn_problem* problem, int dtype, const void* imag
         if (rc != CACNN_OK) return rc;
         store_plan(*problem, key, plan);
     }
-    return launch_with(*problem, dtype, plan.variant, plan.b_c, plan.b_r, plan.b_s, plan.xcd_split_k, image, filter, out,
+    return launch_with(*problem, dtype, plan.variant, plan.b_c, plan.b_r, plan.b_s, plan.xcd_split_k, plan.xcd_walk, image, filter, out,
                        hip_stream);
 }
 
@@ -876,7 +1033,7 @@ int cacnn_conv_forward_with_plan(const cacnn_problem* problem, int dtype, const 
     const int bR = (int)std::min<int64_t>(plan->b_r, problem->R);
     const int bS = (int)std::min<int64_t>(plan->b_s, problem->S);
     if (plan->xcd_split_k < 0) return CACNN_ERR_INVALID_ARG;
-    return launch_with(*problem, dtype, plan->variant, CT, bR, bS, plan->xcd_split_k, image, filter, out, hip_stream);
+    return launch_with(*problem, dtype, plan->variant, CT, bR, bS, plan->xcd_split_k, plan->xcd_walk, image, filter, out, hip_stream);
 }
 
 int cacnn_parallel_bound(const cacnn_problem* problem, double M_words, const cacnn_division* a, cacnn_bound* out) {
@@ -959,7 +1116,7 @@ int cacnn_tune(const cacnn_problem* problem, int dtype, const void* image, const
         bool ok = true;
         for (int i = 0; i < WARM + TIMED && ok; ++i) {
             if (i == WARM) ok = hipEventRecord(e0, stream) == hipSuccess;
-            ok = ok && launch_with(*problem, dtype, vi, c.g.CT, c.g.bR, c.g.bS, 0, image, filter, out, hip_stream) == CACNN_OK;
+            ok = ok && launch_with(*problem, dtype, vi, c.g.CT, c.g.bR, c.g.bS, 0, 0, image, filter, out, hip_stream) == CACNN_OK;
         }
         if (!ok) continue;
         float ms = 0.f;
@@ -981,6 +1138,69 @@ int cacnn_tune(const cacnn_problem* problem, int dtype, const void* image, const
     if (rc != CACNN_OK) return rc;
     store_plan(*problem, key, plan);
     if (out_plan) *out_plan = plan;
+    return CACNN_OK;
+}
+
+int cacnn_two_level_plan(const cacnn_problem* problem, int dtype, const cacnn_machine* machine,
+                         const cacnn_machine_l2* machine_l2, cacnn_l2_plan* out) {
+    if (!problem || !out) return CACNN_ERR_NULL;
+    cacnn_plan plan;
+    const int rc = plan_impl(problem, dtype, machine, &plan);
+    if (rc != CACNN_OK) return rc;
+    const cacnn_problem& p = *problem;
+    const double esz = dtype == CACNN_F32 ? 4.0 : 2.0;
+    L2Machine m2 = kDefaultL2Bytes;
+    if (machine_l2) {
+        if (machine_l2->l2_bytes < 1024 || machine_l2->n_xcd < 1 || machine_l2->n_xcd > 8 ||
+            (machine_l2->n_xcd & (machine_l2->n_xcd - 1)) || machine_l2->cu_per_xcd < 1)
+            return CACNN_ERR_INVALID_ARG;
+        m2.words = (double)machine_l2->l2_bytes;
+        m2.n_xcd = machine_l2->n_xcd;
+        m2.cu_per_xcd = machine_l2->cu_per_xcd;
+    }
+    m2.words /= esz;
+    std::memset(out, 0, sizeof(*out));
+    const double M = m2.words;
+    const LpSolution s = solve_tiling_lp(p, M);
+    for (int i = 0; i < 9; ++i) out->lp_tile[i] = std::pow(M, s.l[i]);
+    out->lp_volume = std::pow(M, s.log_volume);
+    out->lp_cost_words = (double)p.B * p.C * p.K * p.W * p.H * p.R * p.S * M / out->lp_volume;
+    cacnn_bound b;
+    bound_terms(p, M, &b);
+    out->bound_words = b.bound;
+    // the LP's tile rounded to whole LDS tiles
+    auto whole = [](double lp, int tile, int64_t extent) {
+        const int64_t n = std::max<int64_t>(1, (int64_t)std::floor(lp / tile + 0.5));
+        return (int32_t)std::min<int64_t>(n * tile, round_up(extent, tile));
+    };
+    out->l2_tile_b = whole(out->lp_tile[0], plan.b_b, p.B);
+    out->l2_tile_k = whole(out->lp_tile[2], plan.b_k, p.K);
+    out->l2_tile_w = whole(out->lp_tile[3], plan.b_w, p.W);
+    out->l2_tile_h = whole(out->lp_tile[4], plan.b_h, p.H);
+    const VariantInfo& v = variant(plan.variant).info;
+    const int64_t grid = machine_l2 ? std::min<int64_t>(plan.grid[0], (int64_t)m2.n_xcd * m2.cu_per_xcd) : plan.grid[0];
+    const L2Choice l2 = choose_l2_layout(p, dtype, v, grid, m2);
+    out->a_k = l2.a_k;
+    out->walk = l2.walk;
+    out->n_candidates = l2.n;
+    for (int i = 0; i < l2.n; ++i) {
+        out->cand_a_k[i] = l2.cand_a_k[i];
+        out->cand_walk[i] = l2.cand_walk[i];
+        out->cand_words[i] = l2.cand_words[i];
+    }
+    out->chosen_words = l2.words;
+    {
+        // Section 7 for the chosen a_K, the positions divided over the remaining processors: images, then rows, then columns
+        int64_t rest = m2.n_xcd / l2.a_k, ab = 1, ah = 1, aw = 1;
+        for (int64_t* a : {&ab, &ah, &aw}) {
+            const int64_t extent = a == &ab ? p.B : (a == &ah ? p.H : p.W);
+            while (*a * 2 <= std::min<int64_t>(rest, extent)) *a *= 2;
+            rest /= *a;
+        }
+        cacnn_bound pb;
+        parallel_terms(p, M, ab, l2.a_k, aw, ah, &pb);
+        out->parallel_bound_words = pb.bound;
+    }
     return CACNN_OK;
 }
 

@@ -81,6 +81,9 @@ struct KernelArgs {
     // the tile list is k_groups blocks of grp tiles; inside a block the kpg k-tiles of the group are the fastest index
     // (k_groups = 1: the whole list is one block with all tiles_k k-tiles fastest); d_tk divides by kpg
     int32_t k_groups, kpg, grp;
+    int32_t pos_fastest;      // 1: inside a block the position tiles of a k-tile are the fastest index, the k-tile the slowest
+    int32_t npos;             // position tiles per block, grp / kpg
+    FastDiv d_npos;           // its reciprocal
     FastDiv d_nxcd, d_tk, d_bg, d_tw, d_th;   // reciprocals of n_xcd, tiles_k, b_group, tiles_w, tiles_h
     int32_t img_items, flt_items;   // 16-byte staging items per slice
     int32_t img_buf, flt_buf; // size of one LDS buffer of each operand (fp32: floats; bf16: 16-byte units)

@@ -62,9 +62,17 @@ __device__ __forceinline__ TileCoord tile_coords(const KernelArgs& a, int t, int
     int kg = 0;
     for (int i = 1; i < a.k_groups; ++i) kg += (t >= i * a.grp) ? 1 : 0;
     t -= kg * a.grp;
-    int q = (int)fdiv((uint32_t)t, a.d_tk);
-    const int tk = kg * a.kpg + (t - q * a.kpg);
-    t = q;
+    int q, tk;
+    if (a.pos_fastest) {
+        // the position tiles of one k-tile are neighbours in the list, the k-tile is the slowest index of the block
+        q = (int)fdiv((uint32_t)t, a.d_npos);
+        tk = kg * a.kpg + q;
+        t -= q * a.npos;
+    } else {
+        q = (int)fdiv((uint32_t)t, a.d_tk);
+        tk = kg * a.kpg + (t - q * a.kpg);
+        t = q;
+    }
     q = (int)fdiv((uint32_t)t, a.d_bg);
     const int tbl = t - q * a.b_group;
     t = q;

@@ -329,7 +329,8 @@ def test_error_paths_enqueue_nothing(env):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_every_xcd_division_computes_the_same_convolution(env, dtype):
     """Section 7 with the XCDs as processors: the tile order may divide the output channels into 1, 2, 4 or 8 groups.
-    Every division is a permutation of the tile list, so every one must give the oracle's result: on a shape with 8
+    and inside a group either the k-tiles of a position tile or the position tiles of a k-tile may be neighbours.
+    Every such layout is a permutation of the tile list, so every one must give the oracle's result: on a shape with 8
     k-tiles and several position tiles, for the planner's kernel, a one-tile-per-workgroup one and a fixed-geometry one.  Divisions that do not divide the k-tile count are refused."""
     cc, torch = env
     B, C = (8, 32) if dtype == "f32" else (64, 64)
@@ -345,11 +346,17 @@ def test_every_xcd_division_computes_the_same_convolution(env, dtype):
     picks["fixed"] = (names[fx[0]], 16 if dtype == "f32" else 32, 3, 3 if dtype == "f32" else 1)
     for what, (vi, bc, br, bs) in picks.items():
         for split in (1, 2, 4, 8, 0):
-            plan = cc.Plan()
-            plan.variant, plan.b_c, plan.b_r, plan.b_s, plan.xcd_split_k = vi, bc, br, bs, split
-            say(f"[xcd division] {dtype} {what} '{cc.cacnn_variant_name(vi)}' a_K={split}")
-            out = gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
-            gu.assert_parity(cfg, out, ref, ab, f"{what} a_K={split}")
+            for walk in ((0,) if split == 0 else (0, 1)):     # walk 1: the position tiles of a k-tile are neighbours
+                plan = cc.Plan()
+                plan.variant, plan.b_c, plan.b_r, plan.b_s, plan.xcd_split_k, plan.xcd_walk = vi, bc, br, bs, split, walk
+                say(f"[xcd division] {dtype} {what} '{cc.cacnn_variant_name(vi)}' a_K={split} walk={walk}")
+                out = gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
+                gu.assert_parity(cfg, out, ref, ab, f"{what} a_K={split} walk={walk}")
+    plan = cc.Plan()
+    plan.variant, plan.b_c, plan.b_r, plan.b_s, plan.xcd_split_k, plan.xcd_walk = base.variant, base.b_c, base.b_r, base.b_s, 2, 2
+    with pytest.raises(cc.CacnnError) as e:
+        gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
+    assert e.value.status == 2
     for bad in (3, 16, -1):
         plan = cc.Plan()
         plan.variant, plan.b_c, plan.b_r, plan.b_s, plan.xcd_split_k = base.variant, base.b_c, base.b_r, base.b_s, bad

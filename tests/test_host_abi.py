@@ -32,7 +32,7 @@ def test_struct_sizes_match_the_header():
     src = r'''
     #include <stdio.h>
     #include "cacnn.h"
-    int main(void){ printf("%zu %zu %zu %zu %zu %zu\n", sizeof(cacnn_problem), sizeof(cacnn_bound), sizeof(cacnn_machine), sizeof(cacnn_plan), sizeof(cacnn_pool_bound), sizeof(cacnn_division)); return 0; }
+    int main(void){ printf("%zu %zu %zu %zu %zu %zu %zu %zu\n", sizeof(cacnn_problem), sizeof(cacnn_bound), sizeof(cacnn_machine), sizeof(cacnn_plan), sizeof(cacnn_pool_bound), sizeof(cacnn_division), sizeof(cacnn_machine_l2), sizeof(cacnn_l2_plan)); return 0; }
     '''
     with tempfile.TemporaryDirectory() as d:
         open(os.path.join(d, "t.c"), "w").write(src)
@@ -41,7 +41,8 @@ def test_struct_sizes_match_the_header():
         sizes = [int(x) for x in subprocess.run([os.path.join(d, "t")], capture_output=True, text=True,
                                                 check=True).stdout.split()]
     assert sizes == [ctypes.sizeof(cc.Problem), ctypes.sizeof(cc.Bound), ctypes.sizeof(cc.Machine),
-                     ctypes.sizeof(cc.Plan), ctypes.sizeof(cc.PoolBound), ctypes.sizeof(cc.Division)]
+                     ctypes.sizeof(cc.Plan), ctypes.sizeof(cc.PoolBound), ctypes.sizeof(cc.Division),
+                     ctypes.sizeof(cc.MachineL2), ctypes.sizeof(cc.L2Plan)]
 
 
 def test_fastdiv_is_exact_over_its_domain():
@@ -307,17 +308,22 @@ def test_parallel_entry_points_reject_bad_arguments():
         assert e.value.status == 2
 
 
-def test_plan_divides_the_xcds_by_output_channels_only_where_the_filter_is_the_bigger_array():
-    # Filter 18.9 MB against an Image of 1.3 MB, 16 k-tiles: every XCD gets its own output channels
-    assert cc.cacnn_tile_plan((8, 1024, 1024, 7, 7, 3, 3, 1, 1), 1).xcd_split_k == 8
-    # the benchmark shapes are Image-heavy (or have one k-tile): positions only
+def test_plan_lays_out_an_xcds_run_by_the_two_level_model():
+    # Filter 18.9 MB against an Image of 1.3 MB, 16 k-tiles: every XCD should work on its own output channels, which both
+    # a_K = 8 and "position tiles of a k-tile are neighbours" (walk 1) achieve; the k-tiles-fastest order with a_K = 1
+    # would fetch the Filter into every L2
+    dims = (8, 1024, 1024, 7, 7, 3, 3, 1, 1)
+    plan, l2 = cc.cacnn_tile_plan(dims, 1), cc.cacnn_two_level_plan(dims, 1)
+    cand = {(l2.cand_a_k[i], l2.cand_walk[i]): l2.cand_words[i] for i in range(l2.n_candidates)}
+    assert (plan.xcd_split_k, plan.xcd_walk) in ((8, 0), (1, 1), (2, 1), (4, 1), (8, 1))
+    assert cand[(plan.xcd_split_k, plan.xcd_walk)] == min(cand.values()) and cand[(1, 0)] > 3 * min(cand.values())
+    # the benchmark shapes are Image-heavy (or have one k-tile): positions only, k-tiles fastest
     for name, cfg in ci.CONFIGS.items():
-        assert cc.cacnn_tile_plan(cfg.dims, 0 if cfg.dtype == "f32" else 1).xcd_split_k == 1, name
-    # in between: 2 * Image + 4 * Filter is the smallest sum
-    p = cc.cacnn_tile_plan((16, 512, 512, 14, 14, 3, 3, 1, 1), 1)
-    img, flt = 16 * 16 * 512 * 16 * 2, 512 * 9 * 512 * 2
-    sums = {ak: ak * img + (8 // ak) * flt for ak in (1, 2, 4, 8)}
-    assert p.xcd_split_k == min(sums, key=sums.get)
+        p = cc.cacnn_tile_plan(cfg.dims, 0 if cfg.dtype == "f32" else 1)
+        assert (p.xcd_split_k, p.xcd_walk) == (1, 0), name
+    # a layout given to cacnn_conv_forward_with_plan is validated on the host before anything is launched
+    p = cc.cacnn_tile_plan(dims, 1)
+    assert p.xcd_walk in (0, 1)
 
 
 def test_tune_rejects_bad_arguments_and_needs_a_gpu():
@@ -438,3 +444,53 @@ def test_binding_refuses_tensors_that_do_not_fit_the_problem():
     binding._check_operands("t", prob, 1, img.to(torch.int16), flt.to(torch.bfloat16), out)
     with pytest.raises(ValueError, match="float32"):
         binding._check_operands("t", prob, 0, img, flt, out.to(torch.int32))
+
+
+def _variant_tile(name):
+    kt = int(re.search(r" k(\d+) ", name).group(1))
+    tb, tw, th = (int(x) for x in re.search(r" b(\d+)w(\d+)h(\d+)", name).groups())
+    return kt, tb, tw, th
+
+
+def test_two_level_plan_matches_the_oracle():
+    """cacnn_two_level_plan: the Section 5 LP and Theorem 1 at M = one L2 equal the oracle's, and the modelled words of
+    every candidate layout of an XCD's run equal the oracle's per-processor LRU count on the same launch."""
+    from oracle import two_level as tl
+    shapes = [(c.dims, 0 if c.dtype == "f32" else 1) for c in ci.CONFIGS.values()]
+    shapes += [(ci.DIVISION_CONFIGS["d1"].dims, 1), ((256, 256, 512, 7, 7, 3, 3, 1, 1), 1), ((16, 64, 256, 28, 28, 3, 3, 1, 1), 0),
+               ((8, 24, 200, 30, 17, 5, 3, 2, 1), 1), ((3, 5, 33, 9, 7, 5, 4, 2, 3), 0)]
+    walked = 0
+    for dims, dtype in shapes:
+        esz = 4 if dtype == 0 else 2
+        plan = cc.cacnn_tile_plan(dims, dtype)
+        l2 = cc.cacnn_two_level_plan(dims, dtype)
+        M = 4 * 1024 * 1024 / esz
+        want = olp.solve_lp(*dims, M)
+        assert l2.lp_volume == pytest.approx(want.volume, rel=1e-6)
+        assert l2.lp_cost_words == pytest.approx(want.cost, rel=1e-6)
+        assert l2.bound_words == pytest.approx(olb.lower_bound(*dims, M).bound, rel=1e-12)
+        assert (plan.xcd_split_k, plan.xcd_walk) == (l2.a_k, l2.walk)
+        kt, tb, tw, th = _variant_tile(cc.cacnn_variant_name(plan.variant))
+        assert (kt, tb, tw, th) == (plan.b_k, plan.b_b, plan.b_w, plan.b_h)
+        tiles_b = -(-dims[0] // tb)
+        b_group = max(d for d in range(1, max(1, 128 // (tb * esz)) + 1) if tiles_b % d == 0)
+        assert l2.n_candidates >= 1
+        best = None
+        for i in range(l2.n_candidates):
+            ak, walk = l2.cand_a_k[i], l2.cand_walk[i]
+            rounds, words = tl.launch_rounds(*dims, kt, tb, tw, th, ak, walk, 8, plan.grid[0], b_group)
+            model = tl.processor_cache_words(rounds, words, int(M)) + dims[0] * dims[2] * dims[3] * dims[4]
+            assert l2.cand_words[i] == model, (dims, ak, walk)
+            walked += walk
+            if best is None or model < 0.97 * best[0]:
+                best = (model, ak, walk)
+        assert (l2.a_k, l2.walk) == best[1:] and l2.chosen_words == best[0]
+        for nm, lo in (("l2_tile_b", plan.b_b), ("l2_tile_k", plan.b_k), ("l2_tile_w", plan.b_w), ("l2_tile_h", plan.b_h)):
+            assert getattr(l2, nm) % lo == 0 and getattr(l2, nm) >= lo
+    assert walked > 0
+    # a smaller L2 and fewer XCDs are taken as given
+    small = cc.cacnn_two_level_plan(ci.CONFIGS["c5"].dims, 1, None, cc.MachineL2(1 << 20, 4, 16))
+    assert small.bound_words == pytest.approx(olb.lower_bound(*ci.CONFIGS["c5"].dims, (1 << 20) / 2).bound, rel=1e-12)
+    assert all(small.cand_a_k[i] <= 4 for i in range(small.n_candidates))
+    with pytest.raises(cc.CacnnError):
+        cc.cacnn_two_level_plan(ci.CONFIGS["c5"].dims, 1, None, cc.MachineL2(1 << 20, 3, 16))

@@ -110,3 +110,17 @@ def test_processor_cache_capacity_and_walk_order():
         else:
             # a round = 8 position tiles of one k-tile: the Image again for every k-tile, a Filter row group per round
             assert tiny == 8 * img + 64 * (flt // 8)
+
+
+def test_halo_between_position_tiles_shared_or_not():
+    """3 x 3 filter, one processor whose cache holds everything: with every Image column an atom the overlap of
+    neighbouring position tiles is fetched once (the Image once in all); with a position tile's footprint as one atom
+    every tile fetches its own (TW + 2)(TH + 2) columns."""
+    B, C, K, W, H, R, S = 4, 5, 8, 8, 6, 3, 3
+    KT, TB, TW, TH = 8, 4, 4, 2
+    IW, IH = W + R - 1, H + S - 1
+    rounds, words = tl.launch_rounds(B, C, K, W, H, R, S, 1, 1, KT, TB, TW, TH, 1, 0, 1, 2, halo_shared=True)
+    assert tl.processor_cache_words(rounds, words, 10 ** 9) == IW * IH * C * B + K * R * S * C
+    rounds, words = tl.launch_rounds(B, C, K, W, H, R, S, 1, 1, KT, TB, TW, TH, 1, 0, 1, 2, halo_shared=False)
+    n_pos = (W // TW) * (H // TH)
+    assert tl.processor_cache_words(rounds, words, 10 ** 9) == n_pos * (TW + 2) * (TH + 2) * C * B + K * R * S * C
