@@ -277,12 +277,13 @@ const char* cacnn_status_string(int status);
  *   - for every admissible way of laying an XCD's run of tiles out -- a_K groups of k-tiles (1, 2, 4, 8, a divisor of the
  *     k-tile count) times the walk order inside a group (cacnn_plan.xcd_walk) -- the words the eight L2s fetch according
  *     to a model of the launch: a workgroup's n-th tile belongs to round n, an XCD's round reads the Filter rows of its
- *     k-tiles and the Image columns (input pixel x image group, all channels) of its position tiles, each L2 keeps what it
- *     read in LRU order up to its size, and Out is written once;
+ *     k-tiles and the Image footprints (halo included) of its position tiles, each L2 keeps what it read in LRU order
+ *     up to its size, and Out is written once.  Position tiles whose halos overlap each fetch the overlap: that is
+ *     what the counters show on MI355X (a line has left the L2 before the neighbouring tile asks for it);
  *   - a_k / walk: candidates are taken in the order a_K = 1, 2, 4, 8, walk 0 before 1, and a later one replaces the
- *     choice only if it saves a tenth of the chosen one's words; cacnn_tile_plan puts them into xcd_split_k / xcd_walk.
- * machine_l2 NULL = MI355X (4 MiB, 8 XCDs, 32 compute units each).  Problems with more than two million tile x column
- * pairs are not simulated: n_candidates = 0 and a_k is the closed-form choice that minimises a_K*|Image| + (8/a_K)*|Filter|.
+ *     choice only if it saves 3 % of the chosen one's words; cacnn_tile_plan puts them into xcd_split_k / xcd_walk.
+ * machine_l2 NULL = MI355X (4 MiB, 8 XCDs, 32 compute units each).  Problems with more than two million tiles are not
+ * simulated: n_candidates = 0 and a_k is the closed-form choice that minimises a_K*|Image| + (8/a_K)*|Filter|.
  * Errors: as cacnn_tile_plan.
  */
 typedef struct {
@@ -305,6 +306,32 @@ typedef struct {
 
 int cacnn_two_level_plan(const cacnn_problem* problem, int dtype, const cacnn_machine* machine,
                          const cacnn_machine_l2* machine_l2, cacnn_l2_plan* out);
+
+/*
+ * Closed-form tiling (Section 5.1, "Determining the optimal tiling", and the partition algorithm of its figure).
+ * The parameter space theta = log_M (B, C, K, W, H, R, S, sigma_w, sigma_h) is cut into convex regions, in each of
+ * which the optimiser of the Section 5 LP is one affine function of theta; the table compiled into the library was
+ * produced offline by paper_1802_06905_amd/closed_form.py (exact rational arithmetic; a tie-break in the objective
+ * makes the optimiser unique, so there is one region per affine map).  This call evaluates it: no LP is solved.
+ *   M        fast-memory size in words, > 1.
+ *   region   index of the region that holds theta (borders belong to both neighbours; the optimum agrees there);
+ *   theta    the nine logs after clamping into the tabulated box (a loop bound above M acts like M, and a stride
+ *            above its filter extent like that extent: neither changes the LP's feasible set);
+ *   l, tile  the tile logs (base M) and sizes M^l, order b,c,k,w,h,r',r'',s',s'';
+ *   log_volume, volume, cost_words = F*M/volume (Section 5.2), bound_words = Theorem 1 at M;
+ *   worst_violation  the largest amount by which l breaks a row of the LP (rounding only: <= 1e-9).
+ * Errors: NULL pointer -> CACNN_ERR_NULL; non-positive dimension or M <= 1 -> CACNN_ERR_INVALID_ARG.  Host-only.
+ */
+typedef struct {
+    int32_t region, n_regions;
+    double theta[9];
+    double l[9];
+    double tile[9];
+    double log_volume, volume, cost_words, bound_words;
+    double worst_violation;
+} cacnn_closed_form;
+
+int cacnn_closed_form_tiling(const cacnn_problem* problem, double M, cacnn_closed_form* out);
 
 #ifdef __cplusplus
 }

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     Machine,
     Plan,
     PoolBound,
+    ClosedForm,
     MachineL2,
     L2Plan,
     Problem,
@@ -24,6 +25,7 @@ from .binding import (  # noqa: F401
     cacnn_pool_forward,
     cacnn_pool_lower_bound,
     cacnn_two_level_plan,
+    cacnn_closed_form_tiling,
     cacnn_probe_copy,
     cacnn_probe_mfma,
     cacnn_status_string,

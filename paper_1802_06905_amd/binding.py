@@ -82,6 +82,15 @@ class L2Plan(ctypes.Structure):
     ]
 
 
+class ClosedForm(ctypes.Structure):
+    _fields_ = [
+        ("region", ctypes.c_int32), ("n_regions", ctypes.c_int32), ("theta", ctypes.c_double * 9),
+        ("l", ctypes.c_double * 9), ("tile", ctypes.c_double * 9), ("log_volume", ctypes.c_double),
+        ("volume", ctypes.c_double), ("cost_words", ctypes.c_double), ("bound_words", ctypes.c_double),
+        ("worst_violation", ctypes.c_double),
+    ]
+
+
 class Division(ctypes.Structure):
     _fields_ = [("a_b", ctypes.c_int32), ("a_k", ctypes.c_int32), ("a_w", ctypes.c_int32), ("a_h", ctypes.c_int32)]
 
@@ -118,6 +127,8 @@ _lib.cacnn_parallel_bound.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, 
 _lib.cacnn_work_division.restype = ctypes.c_int
 _lib.cacnn_work_division.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, ctypes.c_int32, ctypes.POINTER(Division),
                                      ctypes.POINTER(Bound)]
+_lib.cacnn_closed_form_tiling.restype = ctypes.c_int
+_lib.cacnn_closed_form_tiling.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, ctypes.POINTER(ClosedForm)]
 _lib.cacnn_two_level_plan.restype = ctypes.c_int
 _lib.cacnn_two_level_plan.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctypes.POINTER(Machine), ctypes.POINTER(MachineL2),
                                       ctypes.POINTER(L2Plan)]
@@ -267,6 +278,15 @@ def cacnn_two_level_plan(problem, dtype: int, machine: Optional[Machine] = None,
                                    ctypes.byref(machine_l2) if machine_l2 is not None else None, ctypes.byref(out))
     if rc != 0:
         raise CacnnError(rc, "cacnn_two_level_plan")
+    return out
+
+
+def cacnn_closed_form_tiling(problem, M_words: float) -> ClosedForm:
+    """The optimal tile logs of the Section 5 LP from the tabulated closed form of Section 5.1 (host only, no LP solve)."""
+    out = ClosedForm()
+    rc = _lib.cacnn_closed_form_tiling(ctypes.byref(_as_problem(problem)), float(M_words), ctypes.byref(out))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_closed_form_tiling")
     return out
 
 

@@ -20,6 +20,8 @@ using namespace cacnn;
 
 namespace {
 
+#include "cacnn_closed_form_table.inc"
+
 const cacnn_machine kDefaultMachine = {160 * 1024, 512 * 1024, 256};
 
 bool valid_problem(const cacnn_problem* p) {
@@ -1298,6 +1300,73 @@ int cacnn_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream)
         return CACNN_ERR_INVALID_ARG;
     if (!have_device()) return CACNN_ERR_NO_DEVICE;
     return launch_copy_probe(src, dst, bytes, kDefaultMachine.num_cu * 8, hip_stream) == 0 ? CACNN_OK : CACNN_ERR_LAUNCH;
+}
+
+// Section 5.1: the tabulated closed form.  theta is clamped into the tabulated box first; a region is a set of faces
+// a.theta <= b with integer coefficients, its form nine integer rows over a common denominator.
+int cacnn_closed_form_tiling(const cacnn_problem* p, double M, cacnn_closed_form* out) {
+    if (!p || !out) return CACNN_ERR_NULL;
+    if (!valid_problem(p) || !(M > 1.0)) return CACNN_ERR_INVALID_ARG;
+    std::memset(out, 0, sizeof(*out));
+    const double lnM = std::log(M);
+    auto lg = [&](int64_t v) { return std::log((double)v) / lnM; };
+    double th[9] = {lg(p->B), lg(p->C), lg(p->K), lg(p->W), lg(p->H), lg(p->R), lg(p->S), lg(p->sigma_w), lg(p->sigma_h)};
+    for (int i = 0; i < 5; ++i) th[i] = std::min(th[i], 1.0);
+    for (int i = 0; i < 2; ++i) {       // (R, sigma_w), (S, sigma_h): the LP sees min(sigma, extent) and extent / sigma
+        double sg = std::min(th[7 + i], th[5 + i]);
+        const double rest = std::min(th[5 + i] - sg, 1.0);
+        sg = std::min(sg, 1.0);
+        th[7 + i] = sg;
+        th[5 + i] = sg + rest;
+    }
+    int best = 0;
+    double best_v = std::numeric_limits<double>::infinity();
+    for (int r = 0; r < kClosedFormRegions; ++r) {
+        double worst = -std::numeric_limits<double>::infinity();
+        for (int f = kClosedFormRegion[r][0]; f < kClosedFormRegion[r][0] + kClosedFormRegion[r][1]; ++f) {
+            double v = -(double)kClosedFormFace[f][9];
+            for (int j = 0; j < 9; ++j) v += (double)kClosedFormFace[f][j] * th[j];
+            worst = std::max(worst, v);
+        }
+        if (worst < best_v) {
+            best_v = worst;
+            best = r;
+        }
+        if (worst <= 1e-12) break;
+    }
+    const int form = kClosedFormRegion[best][2];
+    out->region = best;
+    out->n_regions = kClosedFormRegions;
+    double sum = 0.0;
+    for (int i = 0; i < 9; ++i) {
+        double v = (double)kClosedFormNum[form][i][9];
+        for (int j = 0; j < 9; ++j) v += (double)kClosedFormNum[form][i][j] * th[j];
+        v /= (double)kClosedFormDen[form];
+        out->theta[i] = th[i];
+        out->l[i] = std::max(v, 0.0);
+        out->tile[i] = std::pow(M, out->l[i]);
+        sum += out->l[i];
+    }
+    // how far l is from satisfying the LP's rows (the same rows solve_tiling_lp builds)
+    {
+        const double* l = out->l;
+        const double rows[15] = {l[0] - th[0], l[1] - th[1], l[2] - th[2], l[3] - th[3], l[4] - th[4], l[6] - th[7], l[8] - th[8],
+                                 l[5] - (th[5] - th[7]), l[7] - (th[6] - th[8]),
+                                 l[0] + l[2] + l[3] + l[4] - 1.0, l[1] + l[2] + l[5] + l[6] + l[7] + l[8] - 1.0,
+                                 l[0] + l[1] + l[3] + l[4] + l[6] + l[8] - 1.0, l[0] + l[1] + l[3] + l[7] + l[6] + l[8] - 1.0,
+                                 l[0] + l[1] + l[5] + l[4] + l[6] + l[8] - 1.0, l[0] + l[1] + l[5] + l[7] + l[6] + l[8] - 1.0};
+        double worst = 0.0;
+        for (double v : rows) worst = std::max(worst, v);
+        out->worst_violation = worst;
+    }
+    out->log_volume = sum;
+    out->volume = std::pow(M, sum);
+    const double F = (double)p->B * p->C * p->K * p->W * p->H * p->R * p->S;
+    out->cost_words = F * M / out->volume;
+    cacnn_bound b;
+    bound_terms(*p, M, &b);
+    out->bound_words = b.bound;
+    return CACNN_OK;
 }
 
 int cacnn_variant_count(void) { return num_variants(); }
