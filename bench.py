@@ -9,7 +9,7 @@ measurements for all five benchmark shapes.
 Order of the run: every input is generated and uploaded first; then the machine's sustained rates are measured
 (register-only MFMA loops and a streaming copy); then, per shape: about 0.3 s of the register-only MFMA loop of the
 shape's dtype (power-state conditioning: the board's power management needs a few hundred milliseconds of matrix load
-to settle, and a cold chip runs the first launches of c5 up to 25 % slower, see profiles/clock_ramp.txt), then the W
+to settle, and a cold chip runs the first launches of c5 up to 25 % slower, see profiles/clock_ramp_c2_c5.txt), then the W
 warm-up launches, then exactly K timed launches between two events on the launch stream.
 """
 import argparse
@@ -237,6 +237,38 @@ def shape_report(cc, cfg, sec):
     }
 
 
+def alternative_variants_us(cc, torch, cfg, buffers, steps, warmup):
+    """Launch time of every OTHER fixed-geometry kernel variant that accepts the shape (same process, same buffers, right
+    after the planner's own variant was timed): the evidence for the planner's choice among them."""
+    _, _, d_img, d_flt, d_out = buffers
+    dt = 0 if cfg.dtype == "f32" else 1
+    chosen = cc.cacnn_tile_plan(cfg.dims, dt)
+    out = {}
+    for vi in range(cc.cacnn_variant_count()):
+        name = cc.cacnn_variant_name(vi)
+        if vi == chosen.variant or " fx" not in name or not name.startswith(cfg.dtype + " "):
+            continue
+        tile = name.split()[-2 if name.endswith(" s2") else -1]            # c32r3s1
+        ct, rest = tile[1:].split("r")
+        br, bs = rest.split("s")
+        plan = cc.cacnn_tile_plan(cfg.dims, dt)
+        plan.variant, plan.b_c, plan.b_r, plan.b_s = vi, int(ct), int(br), int(bs)
+        plan.xcd_split_k = 0
+        try:
+            for _ in range(warmup):
+                cc.cacnn_conv_forward_with_plan(cfg.dims, dt, plan, d_img, d_flt, d_out)
+        except cc.CacnnError:
+            continue                                                        # the variant does not take this shape
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            cc.cacnn_conv_forward_with_plan(cfg.dims, dt, plan, d_img, d_flt, d_out)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = e0.elapsed_time(e1) * 1e3 / steps
+    return out
+
+
 def cpu_baseline(cfg, img, flt, np):
     """The oracle as it stands, all host threads, on the whole workload when that is a few seconds of CPU work,
     otherwise on the first k output channels (the work per channel is identical)."""
@@ -399,6 +431,54 @@ def pooling_report(cc, torch, ci, np, steps, warmup, with_cpu):
     return rep
 
 
+# Mid-size and ragged layers that no fixed-geometry kernel takes: (dtype, B, C, K, W, H, R, S, sigma_w, sigma_h)
+PLANNER_SHAPES = [
+    ("bf16", 32, 1024, 256, 14, 14, 1, 1, 1, 1), ("bf16", 32, 512, 512, 7, 7, 3, 3, 1, 1), ("bf16", 32, 64, 64, 56, 56, 3, 3, 1, 1),
+    ("bf16", 16, 128, 128, 28, 28, 3, 3, 1, 1), ("bf16", 40, 96, 200, 13, 11, 3, 3, 1, 1), ("bf16", 24, 48, 96, 27, 27, 5, 5, 2, 2),
+    ("bf16", 128, 256, 512, 1, 1, 1, 1, 1, 1), ("bf16", 8, 256, 256, 20, 20, 3, 3, 2, 2),
+    ("f32", 32, 256, 256, 14, 14, 3, 3, 1, 1), ("f32", 4, 128, 128, 28, 28, 3, 3, 1, 1), ("f32", 16, 64, 96, 30, 30, 5, 5, 1, 1),
+    ("f32", 20, 40, 72, 17, 19, 3, 3, 1, 1), ("f32", 64, 16, 32, 55, 55, 7, 7, 2, 2), ("f32", 2, 64, 64, 56, 56, 3, 3, 1, 1),
+    ("f32", 256, 512, 512, 1, 1, 1, 1, 1, 1), ("f32", 12, 100, 60, 25, 9, 1, 3, 1, 2),
+]
+
+
+def planner_compare(cc, torch, ci, np):
+    """The planner's pick against the fastest of all kernel variants (cacnn_tune) on PLANNER_SHAPES; the planner is the
+    one the environment selects (CACNN_PLANNER unset: the calibrated cycle model; lp: the tile sized from the Section 5
+    LP at the gfx950 budget).  One row per shape, then the geometric mean of the ratios."""
+    mode = os.environ.get("CACNN_PLANNER", "model")
+
+    def timed(fn, n=60, w=10):
+        for _ in range(w):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n * 1e3
+
+    ratios = []
+    print("mode | dtype B C K W H R S sw sh | planner's variant [b_c b_r b_s] us | fastest variant [b_c b_r b_s] us | ratio")
+    for sh in PLANNER_SHAPES:
+        dtype, dims = sh[0], sh[1:]
+        cfg = ci.custom("cmp", *dims, dtype=dtype, dist="normal", seed=3)
+        _, _, d_img, d_flt, d_out = upload_config(torch, ci, np, cfg)
+        dt = 0 if dtype == "f32" else 1
+        plan = cc.cacnn_tile_plan(dims, dt)
+        t_plan = timed(lambda: cc.cacnn_conv_forward_with_plan(dims, dt, plan, d_img, d_flt, d_out))
+        tuned = cc.cacnn_tune(dims, dt, d_img, d_flt, d_out)
+        t_tune = timed(lambda: cc.cacnn_conv_forward_with_plan(dims, dt, tuned, d_img, d_flt, d_out))
+        ratios.append(t_plan / t_tune)
+        print(f"{mode} | {dtype} {' '.join(str(v) for v in dims)} | {cc.cacnn_variant_name(plan.variant)} "
+              f"[{plan.b_c}, {plan.b_r}, {plan.b_s}] {t_plan:.2f} | {cc.cacnn_variant_name(tuned.variant)} "
+              f"[{tuned.b_c}, {tuned.b_r}, {tuned.b_s}] {t_tune:.2f} | {t_plan / t_tune:.3f}", flush=True)
+    gm = float(np.exp(np.mean(np.log(ratios))))
+    print(f"{mode}: geometric mean of the ratios {gm:.3f}, worst {max(ratios):.2f}, within 15 % of the fastest on "
+          f"{sum(1 for r in ratios if r <= 1.15)} of {len(ratios)}")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -420,6 +500,9 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 512 MiB device copy (calibration), a cache-evicting 1 GiB fill, "
                          "then one cold and one warm launch of the workload; prints nothing but a marker line")
+    ap.add_argument("--planner-compare", action="store_true",
+                    help="time the planner's pick against cacnn_tune's on sixteen mid-size and ragged layers and print a "
+                         "table (the planner is the one CACNN_PLANNER selects); no JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards over b or k with no exchange step, "
@@ -437,6 +520,9 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
+    if args.planner_compare:
+        planner_compare(cc, torch, ci, np)
+        return
     if args.workload == "p1":
         pcfg = ci.POOL_CONFIGS["p1"]
         if args.traffic_probe:
@@ -518,8 +604,13 @@ def main():
                                condition=not args.no_conditioning)
             shapes[name] = shape_report(cc, c, s)
             shapes[name]["frac_mfma_sustained"] = shapes[name]["tflops"] / sustained[f"mfma_{c.dtype}_tflops"]
+            shapes[name]["other_fixed_geometry_variants_us"] = alternative_variants_us(
+                cc, torch, c, buffers[name], args.steps, args.warmup)
             if name == "c1":
                 shapes[name]["us_per_launch_in_a_hip_graph"] = graph_replay_us(cc, torch, ci, np, c)
+        # (the headline shape's alternatives last, so that its own timed region and parity check come first)
+        head["other_fixed_geometry_variants_us"] = alternative_variants_us(cc, torch, cfg, buffers[cfg.name],
+                                                                           args.steps, args.warmup)
         result["shapes"] = shapes
         result["pooling"] = pooling_report(cc, torch, ci, np, args.steps, args.warmup, not args.no_cpu)
     print(json.dumps(result))

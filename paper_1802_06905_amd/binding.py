@@ -1,6 +1,6 @@
 """ctypes binding with the same names as the C entry points declared in include/cacnn.h.
 
-The shared library must have been built in-tree (python -m paper_1802_06905_amd.build); importing this module without
+The shared library must have been built in-tree (python paper_1802_06905_amd/build.py); importing this module without
 it raises: there is no CPU fallback.
 """
 import ctypes
@@ -100,7 +100,7 @@ def library_path() -> str:
 
 
 if not os.path.exists(_LIB_PATH):
-    raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_1802_06905_amd.build` "
+    raise ImportError(f"{_LIB_PATH} is missing: build it with `python paper_1802_06905_amd/build.py` "
                       "(there is no CPU fallback)")
 
 # PyTorch owns the device memory and the streams handed to this library, so both must talk to the SAME HIP runtime:

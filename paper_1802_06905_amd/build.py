@@ -1,4 +1,4 @@
-"""Build libcacnn.so (host planner + gfx950 kernels) in-tree with hipcc.  Usage: python -m paper_1802_06905_amd.build"""
+"""Build libcacnn.so (host planner + gfx950 kernels) in-tree with hipcc.  Usage: python paper_1802_06905_amd/build.py"""
 import os
 import subprocess
 import sys
