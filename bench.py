@@ -442,6 +442,65 @@ PLANNER_SHAPES = [
 ]
 
 
+# Layers the cost model's constants are fitted on (none of them is in PLANNER_SHAPES)
+CALIBRATION_SHAPES = [
+    ("bf16", 64, 128, 128, 14, 14, 3, 3, 1, 1), ("bf16", 16, 256, 256, 14, 14, 3, 3, 1, 1), ("bf16", 8, 64, 128, 56, 56, 1, 1, 1, 1),
+    ("bf16", 32, 256, 64, 28, 28, 1, 1, 1, 1), ("bf16", 128, 64, 64, 7, 7, 3, 3, 1, 1), ("bf16", 4, 512, 512, 14, 14, 3, 3, 1, 1),
+    ("bf16", 48, 80, 160, 12, 10, 3, 3, 1, 1), ("bf16", 16, 32, 64, 30, 30, 5, 5, 1, 1), ("bf16", 32, 96, 96, 16, 16, 3, 3, 2, 2),
+    ("bf16", 64, 512, 128, 4, 4, 3, 3, 1, 1), ("bf16", 256, 128, 256, 1, 1, 1, 1, 1, 1), ("bf16", 20, 200, 72, 9, 13, 3, 1, 1, 1),
+    ("bf16", 8, 128, 128, 24, 24, 3, 3, 1, 1), ("bf16", 32, 32, 32, 56, 56, 3, 3, 1, 1), ("bf16", 16, 64, 256, 20, 20, 1, 1, 1, 1),
+    ("bf16", 96, 48, 48, 10, 10, 5, 5, 2, 2),
+    ("f32", 16, 128, 128, 14, 14, 3, 3, 1, 1), ("f32", 8, 64, 64, 28, 28, 3, 3, 1, 1), ("f32", 32, 32, 64, 20, 20, 5, 5, 1, 1),
+    ("f32", 1, 64, 64, 56, 56, 3, 3, 1, 1), ("f32", 64, 256, 128, 4, 4, 1, 1, 1, 1), ("f32", 8, 24, 48, 33, 31, 3, 3, 2, 2),
+    ("f32", 4, 96, 96, 24, 24, 3, 3, 1, 1), ("f32", 128, 128, 256, 1, 1, 1, 1, 1, 1), ("f32", 10, 50, 70, 15, 11, 3, 5, 1, 2),
+    ("f32", 32, 8, 32, 48, 48, 7, 7, 2, 2), ("f32", 16, 192, 64, 12, 12, 1, 1, 1, 1), ("f32", 2, 128, 128, 28, 28, 3, 3, 1, 1),
+]
+
+
+def planner_sweep(cc, torch, ci, np, shapes):
+    """Every kernel variant that accepts each shape, with the contraction tile the cost model likes best for it: the
+    model's estimate next to the measured launch time.  The data the model's constants are fitted to and judged by."""
+    print("sweep | dtype B C K W H R S sw sh | variant | b_c b_r b_s | model us | measured us | model terms: tiles per CU, "
+          "MFMA, staging, slices, Out drain (CU cycles)")
+    rows = {}
+    for sh in shapes:
+        dtype, dims = sh[0], sh[1:]
+        cfg = ci.custom("sweep", *dims, dtype=dtype, dist="normal", seed=4)
+        _, _, d_img, d_flt, d_out = upload_config(torch, ci, np, cfg)
+        dt = 0 if dtype == "f32" else 1
+        for vi in range(cc.cacnn_variant_count()):
+            try:
+                plan, model_us, terms = cc.cacnn_plan_variant(dims, dt, vi, True)
+                for _ in range(3):
+                    cc.cacnn_conv_forward_with_plan(dims, dt, plan, d_img, d_flt, d_out)
+            except cc.CacnnError:
+                continue
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(12):
+                cc.cacnn_conv_forward_with_plan(dims, dt, plan, d_img, d_flt, d_out)
+            e1.record()
+            torch.cuda.synchronize()
+            print(f"sweep | {dtype} {' '.join(str(v) for v in dims)} | {cc.cacnn_variant_name(vi)} | {plan.b_c} {plan.b_r} "
+                  f"{plan.b_s} | {model_us:.2f} | {e0.elapsed_time(e1) * 1e3 / 12:.2f} | "
+                  f"{' '.join(f'{t:.6g}' for t in terms)}", flush=True)
+            tag = cc.cacnn_variant_name(vi).split()[1]
+            if not tag.startswith("fx"):
+                family = f"{dtype} {'one-tile' if tag.startswith('k') else tag}"
+                per_cu, t_mfma, t_stage, n_ct, t_out = terms
+                rows.setdefault(family, []).append(
+                    ([per_cu * t_mfma, per_cu * t_stage, per_cu * n_ct, t_out / max(1.0, min(per_cu, 4.0)), 1.0],
+                     e0.elapsed_time(e1) * 1e3 / 12 * 2400.0))
+    # the fit the cost model's coefficients come from: per kernel family, non-negative least squares on the relative error
+    from scipy.optimize import nnls
+    print("fit | family | cycles per MFMA cycle, per staging cycle, per slice, per Out-drain cycle, constant | rms log error | rows")
+    for family in sorted(rows):
+        A = np.array([[f / meas for f in feats] for feats, meas in rows[family]])
+        x, _ = nnls(A, np.ones(len(A)))
+        err = np.log(np.maximum(A @ x, 1e-9))
+        print(f"fit | {family} | {' '.join(f'{c:.4g}' for c in x)} | {float(np.sqrt(np.mean(err ** 2))):.3f} | {len(A)}")
+
+
 def planner_compare(cc, torch, ci, np):
     """The planner's pick against the fastest of all kernel variants (cacnn_tune) on PLANNER_SHAPES; the planner is the
     one the environment selects (CACNN_PLANNER unset: the calibrated cycle model; lp: the tile sized from the Section 5
@@ -500,6 +559,9 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 512 MiB device copy (calibration), a cache-evicting 1 GiB fill, "
                          "then one cold and one warm launch of the workload; prints nothing but a marker line")
+    ap.add_argument("--planner-sweep", choices=["calibration", "test"], default=None,
+                    help="time every kernel variant on the calibration layers (or on the --planner-compare layers) and print "
+                         "the cost model's estimate next to each; no JSON line")
     ap.add_argument("--planner-compare", action="store_true",
                     help="time the planner's pick against cacnn_tune's on sixteen mid-size and ragged layers and print a "
                          "table (the planner is the one CACNN_PLANNER selects); no JSON line")
@@ -520,6 +582,9 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
+    if args.planner_sweep:
+        planner_sweep(cc, torch, ci, np, {"calibration": CALIBRATION_SHAPES, "test": PLANNER_SHAPES}[args.planner_sweep])
+        return
     if args.planner_compare:
         planner_compare(cc, torch, ci, np)
         return

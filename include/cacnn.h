@@ -165,6 +165,19 @@ int cacnn_conv_forward_with_plan(const cacnn_problem* problem, int dtype, const 
                                  const void* image, const void* filter, void* out, void* hip_stream);
 
 /*
+ * The plan cacnn_tile_plan would make if `variant_index` were the only compiled kernel: that variant with the
+ * contraction tile the planner's cost model likes best for it, and the model's estimate of the launch time in
+ * microseconds (model_us, may be NULL) with its terms in compute-unit cycles (model_terms, 5 doubles, may be NULL: Out
+ * tiles per compute unit, MFMA time of a tile, staging time of a tile, contraction slices per tile, Out drain).  What
+ * cacnn_tune times per variant; exposed so that the cost model can be compared with measurements and fitted to them
+ * (bench.py --planner-sweep, --planner-compare).  Host only.
+ * Errors: NULL -> CACNN_ERR_NULL; bad dims -> CACNN_ERR_INVALID_ARG; a variant of the other dtype, out of range, or one
+ * that does not accept the problem -> CACNN_ERR_UNSUPPORTED.
+ */
+int cacnn_plan_variant(const cacnn_problem* problem, int dtype, int variant_index, cacnn_plan* out, double* model_us,
+                       double* model_terms);
+
+/*
  * Measured plan selection for problems the cost model was not calibrated on: runs every kernel variant that accepts
  * the problem (each with the contraction tile the model prefers for it) a few times on the caller's buffers, keeps
  * the fastest, and remembers it for later cacnn_conv_forward calls with the same problem, dtype and operand alignment.

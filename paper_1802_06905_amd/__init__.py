@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     cacnn_pool_forward,
     cacnn_pool_lower_bound,
     cacnn_two_level_plan,
+    cacnn_plan_variant,
     cacnn_closed_form_tiling,
     cacnn_probe_copy,
     cacnn_probe_mfma,

@@ -129,6 +129,9 @@ _lib.cacnn_work_division.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, c
                                      ctypes.POINTER(Bound)]
 _lib.cacnn_closed_form_tiling.restype = ctypes.c_int
 _lib.cacnn_closed_form_tiling.argtypes = [ctypes.POINTER(Problem), ctypes.c_double, ctypes.POINTER(ClosedForm)]
+_lib.cacnn_plan_variant.restype = ctypes.c_int
+_lib.cacnn_plan_variant.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctypes.c_int, ctypes.POINTER(Plan),
+                                    ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
 _lib.cacnn_two_level_plan.restype = ctypes.c_int
 _lib.cacnn_two_level_plan.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctypes.POINTER(Machine), ctypes.POINTER(MachineL2),
                                       ctypes.POINTER(L2Plan)]
@@ -279,6 +282,19 @@ def cacnn_two_level_plan(problem, dtype: int, machine: Optional[Machine] = None,
     if rc != 0:
         raise CacnnError(rc, "cacnn_two_level_plan")
     return out
+
+
+def cacnn_plan_variant(problem, dtype: int, variant: int, with_terms: bool = False):
+    """(plan, model_us[, terms]): the plan if `variant` were the only kernel, the cost model's time estimate and, on
+    request, its five terms (host only)."""
+    out = Plan()
+    us = ctypes.c_double(0.0)
+    terms = (ctypes.c_double * 5)()
+    rc = _lib.cacnn_plan_variant(ctypes.byref(_as_problem(problem)), int(dtype), int(variant), ctypes.byref(out),
+                                 ctypes.byref(us), terms)
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_plan_variant")
+    return (out, us.value, list(terms)) if with_terms else (out, us.value)
 
 
 def cacnn_closed_form_tiling(problem, M_words: float) -> ClosedForm:

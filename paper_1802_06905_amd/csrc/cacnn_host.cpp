@@ -343,6 +343,9 @@ struct Choice {
     int64_t n_wg = 0;
     double words = 0.0;       // words staged from global memory by the whole grid
     double img_words = 0.0;   // the Image part of them
+    // the cost model's terms for the chosen geometry, in CU cycles: tiles per CU, MFMA time, staging time and
+    // contraction slices per tile, Out drain
+    double terms[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
 };
 
 // words staged from global memory by the whole grid for one variant/geometry, clipped to the arrays
@@ -374,6 +377,28 @@ bool vec_img_ok(const VariantInfo& v, const cacnn_problem& p) {
 
 // Cost model in CU cycles: MFMA issue time of one wavefront plus the staging time of the workgroup, times the
 // number of workgroups a compute unit has to run.  Staging overlaps MFMA only when two workgroups share a CU.
+// Coefficients of the generic kernels' cost model (see evaluate): cycles per MFMA-pipe cycle, per staging cycle, per
+// contraction slice, per Out-drain cycle, and the constant part of a launch.
+struct ModelCoef {
+    double mfma, stage, slice, drain, fixed;
+};
+
+const ModelCoef& model_coef(const VariantInfo& v) {
+    static const ModelCoef one_tile_bf16 = {4.926, 1.741, 7.1, 0.02466, 17060.0};
+    static const ModelCoef one_tile_f32 = {2.459, 2.334, 8696.0, 0.1144, 1322.0};
+    static const ModelCoef pipe_bf16 = {2.696, 0.0, 5385.0, 0.0928, 15510.0};
+    static const ModelCoef pipe3_bf16 = {1.525, 0.0, 4127.0, 0.0, 27740.0};
+    static const ModelCoef pipe_f32 = {1.667, 0.0, 6584.0, 0.1336, 4643.0};
+    static const ModelCoef ws_bf16 = {2.236, 0.0, 2918.0, 0.0, 24020.0};
+    static const ModelCoef ws3_bf16 = {1.358, 0.0, 1926.0, 0.0, 34050.0};
+    static const ModelCoef ws_f32 = {1.514, 0.0, 2807.0, 0.2543, 11870.0};
+    static const ModelCoef ws4_f32 = {1.284, 0.0, 5212.0, 0.2865, 7469.0};
+    const bool f32 = v.dtype == CACNN_F32;
+    if (v.pipelined == 0) return f32 ? one_tile_f32 : one_tile_bf16;
+    if (v.pipelined == 1) return f32 ? pipe_f32 : (v.reuse_r > 0 ? pipe3_bf16 : pipe_bf16);
+    return f32 ? (v.f32v4() ? ws4_f32 : ws_f32) : (v.reuse_r > 0 ? ws3_bf16 : ws_bf16);
+}
+
 bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice* best) {
     const VariantInfo& v = variant(vi).info;
     // fp32 slices in multiples of 4 channels keep the 16-byte Filter loads legal
@@ -405,15 +430,17 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
                 if (!g.legal || g.lds_bytes > mach.lds_bytes) continue;
                 double img_words = 0.0;
                 const double words = staged_words(v, p, g, &img_words);
-                // Cost model, in compute-unit cycles per Out tile, calibrated against measurements on MI355X:
-                //   t_mfma   MFMA pipe time of one wavefront (64 cycles per fp32 32x32x2, 32 per bf16 32x32x16),
-                //            divided by how well each kernel family keeps the pipe fed;
-                //   t_stage  staged bytes of the tile at the ~16 B/clk a CU gets from L2 when every CU is loading
-                //            (runs shorter than 32 bytes along b waste the rest of each sector);
-                //   t_slice  exposed latency and barrier cost per contraction slice;
-                //   t_out    the Out tile draining to HBM at ~1 TB/s for the whole chip.
-                // The direct kernels serialise all of it, the pipelined ones overlap the fetch with the multiply, the
-                // wave-specialised ones also overlap the LDS writes and the address arithmetic.
+                // Cost model, in compute-unit cycles, for the generic kernels.  Four quantities of the launch:
+                //   t_mfma   MFMA pipe time of one wavefront for one Out tile (64 cycles per fp32 32x32x2, 32 per bf16
+                //            32x32x16);
+                //   t_stage  staged bytes of the tile at 16 B/clk (runs shorter than 32 bytes along b waste the rest of
+                //            each sector);
+                //   n_ctiles contraction slices per tile (each costs a barrier and exposed latency);
+                //   t_out    the Out tile draining to HBM at ~1 TB/s for the whole chip;
+                // and per_cu, the Out tiles a compute unit runs one after the other.  The launch time is a non-negative
+                // linear combination of them plus a constant, with one set of coefficients per kernel family, fitted
+                // (least squares on the relative error) to the measured launch times of every generic variant on 28
+                // calibration layers (bench.py --planner-sweep calibration).
                 const double ksteps = v.dtype != CACNN_F32 ? (double)p.R * p.S * (Cpad / 16)
                                       : v.f32v4()          ? (double)p.R * (double)round_up((int64_t)p.S * Cpad, 8) / 2.0
                                                            : (double)p.R * ceil_div((int64_t)p.S * Cpad, 2);
@@ -421,24 +448,10 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
                 const double t_stage = (img_words * waste + (words - img_words)) * ebytes / (double)n_wg / 16.0;
                 const double n_ctiles = (double)g.n_slices;
                 const double t_out = (double)v.KT() * v.NT() * 4.0 * waste * (double)mach.num_cu / 1.0e12 * 2.4e9;
-                const bool f32 = v.dtype == CACNN_F32;
-                double feed, beta, t_slice;
-                if (v.pipelined == 0) {
-                    feed = f32 ? 0.5 : 0.8;
-                    beta = 3.0;
-                    t_slice = 2500.0;
-                } else if (v.pipelined == 1) {
-                    feed = f32 ? 0.6 : (v.reuse_r ? 0.95 : 0.8);
-                    beta = 1.3;
-                    t_slice = 400.0;
-                } else {
-                    feed = f32 ? (v.f32v4() ? 0.9 : 0.75) : (v.reuse_r ? 0.95 : 0.85);
-                    beta = 0.7;
-                    t_slice = 300.0;
-                }
-                const double per_tile = t_mfma / feed + beta * t_stage + t_slice * n_ctiles;
+                const ModelCoef& mc = model_coef(v);
                 const double per_cu = (double)ceil_div(n_wg, mach.num_cu);
-                double cost = (per_cu * per_tile + t_out / std::max(1.0, std::min(per_cu, 4.0))) * (double)v.tune + 6000.0;
+                double cost = per_cu * (mc.mfma * t_mfma + mc.stage * t_stage + mc.slice * n_ctiles) +
+                              mc.drain * t_out / std::max(1.0, std::min(per_cu, 4.0)) + mc.fixed;
                 // the fixed-geometry kernels run one schedule: priced by what a unit was measured to take
                 if (v.fx_unit_us > 0.f)
                     cost = (per_cu * n_ctiles * (double)v.fx_unit_us + (double)v.fx_fixed_us) * 2400.0;
@@ -449,6 +462,11 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
                     best->n_wg = n_wg;
                     best->words = words;
                     best->img_words = img_words;
+                    best->terms[0] = per_cu;
+                    best->terms[1] = t_mfma;
+                    best->terms[2] = t_stage;
+                    best->terms[3] = n_ctiles;
+                    best->terms[4] = t_out;
                 }
                 found = true;
             }
@@ -841,6 +859,34 @@ bool have_device() {
     return g_device_ok;
 }
 
+// layouts chosen by the two-level model for launches that name none, keyed by (problem, dtype, variant, grid): the model
+// walks every tile of every candidate, which is host time a launch loop should pay once
+struct LayoutEntry {
+    cacnn_problem p;
+    int dtype, vi;
+    int64_t grid;
+    int a_k, walk;
+};
+std::vector<LayoutEntry> g_layouts;
+
+void cached_l2_layout(const cacnn_problem& p, int dtype, int vi, int64_t grid, const L2Machine& m2, int* a_k, int* walk) {
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        for (const LayoutEntry& e : g_layouts)
+            if (e.dtype == dtype && e.vi == vi && e.grid == grid && std::memcmp(&e.p, &p, sizeof(cacnn_problem)) == 0) {
+                *a_k = e.a_k;
+                *walk = e.walk;
+                return;
+            }
+    }
+    const L2Choice l2 = choose_l2_layout(p, dtype, variant(vi).info, grid, m2);
+    *a_k = l2.a_k;
+    *walk = l2.walk;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (g_layouts.size() >= 64) g_layouts.erase(g_layouts.begin());
+    g_layouts.push_back(LayoutEntry{p, dtype, vi, grid, l2.a_k, l2.walk});
+}
+
 int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int bS, int split_k, int walk, const void* image,
                 const void* filter, void* out, void* stream) {
     const Variant& var = variant(vi);
@@ -928,9 +974,7 @@ int launch_with(const cacnn_problem& p, int dtype, int vi, int CT, int bR, int b
         L2Machine m2 = kDefaultL2Bytes;
         m2.words /= (double)esz;
         m2.n_xcd = a.n_xcd;
-        const L2Choice l2 = choose_l2_layout(p, dtype, v, launch_grid(v, g, grid, kDefaultMachine), m2);
-        split_k = l2.a_k;
-        walk = l2.walk;
+        cached_l2_layout(p, dtype, vi, launch_grid(v, g, grid, kDefaultMachine), m2, &split_k, &walk);
     }
     if (split_k < 1 || split_k > 8 || (split_k & (split_k - 1)) || a.tiles_k % split_k) return CACNN_ERR_INVALID_ARG;
     if (walk != 0 && walk != 1) return CACNN_ERR_INVALID_ARG;
@@ -1141,6 +1185,25 @@ int cacnn_tune(const cacnn_problem* problem, int dtype, const void* image, const
     store_plan(*problem, key, plan);
     if (out_plan) *out_plan = plan;
     return CACNN_OK;
+}
+
+int cacnn_plan_variant(const cacnn_problem* problem, int dtype, int variant_index, cacnn_plan* out, double* model_us,
+                       double* model_terms) {
+    if (!problem || !out) return CACNN_ERR_NULL;
+    if (!valid_problem(problem)) return CACNN_ERR_INVALID_ARG;
+    if (dtype != CACNN_F32 && dtype != CACNN_BF16_F32ACC) return CACNN_ERR_UNSUPPORTED;
+    if (variant_index < 0 || variant_index >= num_variants() || variant(variant_index).info.dtype != dtype)
+        return CACNN_ERR_UNSUPPORTED;
+    {
+        const int vrc = validate_dims(*problem);
+        if (vrc != CACNN_OK) return vrc;
+    }
+    Choice c;
+    if (!evaluate(variant_index, *problem, kDefaultMachine, &c)) return CACNN_ERR_UNSUPPORTED;
+    if (model_us) *model_us = c.cost / 2400.0;
+    if (model_terms)
+        for (int i = 0; i < 5; ++i) model_terms[i] = c.terms[i];
+    return fill_plan(*problem, dtype, kDefaultMachine, c, out);
 }
 
 int cacnn_two_level_plan(const cacnn_problem* problem, int dtype, const cacnn_machine* machine,

@@ -2483,7 +2483,7 @@ __device__ __forceinline__ void f32_direct_stage(const KernelArgs& a, CACNN_LDS(
 template <int TW, int TH>
 __global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a) {
     using GEO = F32DirectFixed<TW, TH>;
-    constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, BR = GEO::BR, WM = GEO::WM, NBLK = GEO::NBLK;
+    constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, WM = GEO::WM, NBLK = GEO::NBLK;
     constexpr int XP = GEO::XP, POS = GEO::POS, FP = GEO::FP;
     constexpr int IBUF = GEO::IMG_BYTES, FBUF = GEO::FLT_BYTES;
     extern __shared__ __align__(16) f32x4 smem_v[];

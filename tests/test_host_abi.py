@@ -316,7 +316,7 @@ def test_plan_lays_out_an_xcds_run_by_the_two_level_model():
     plan, l2 = cc.cacnn_tile_plan(dims, 1), cc.cacnn_two_level_plan(dims, 1)
     cand = {(l2.cand_a_k[i], l2.cand_walk[i]): l2.cand_words[i] for i in range(l2.n_candidates)}
     assert (plan.xcd_split_k, plan.xcd_walk) in ((8, 0), (1, 1), (2, 1), (4, 1), (8, 1))
-    assert cand[(plan.xcd_split_k, plan.xcd_walk)] == min(cand.values()) and cand[(1, 0)] > 3 * min(cand.values())
+    assert cand[(plan.xcd_split_k, plan.xcd_walk)] == min(cand.values()) and cand[(1, 0)] > 2 * min(cand.values())
     # the benchmark shapes are Image-heavy (or have one k-tile): positions only, k-tiles fastest
     for name, cfg in ci.CONFIGS.items():
         p = cc.cacnn_tile_plan(cfg.dims, 0 if cfg.dtype == "f32" else 1)
