@@ -494,3 +494,31 @@ def test_two_level_plan_matches_the_oracle():
     assert all(small.cand_a_k[i] <= 4 for i in range(small.n_candidates))
     with pytest.raises(cc.CacnnError):
         cc.cacnn_two_level_plan(ci.CONFIGS["c5"].dims, 1, None, cc.MachineL2(1 << 20, 3, 16))
+
+
+def test_plan_variant_reports_the_cost_model_per_variant():
+    """cacnn_plan_variant: every variant that accepts a shape comes back as itself with a positive estimate whose terms
+    are consistent with the plan (tiles per CU from the grid of Out tiles), and on a shape no fixed-geometry kernel
+    takes the planner's choice is the variant with the smallest estimate."""
+    dims, dt = (20, 40, 72, 17, 19, 3, 3, 1, 1), 0
+    chosen = cc.cacnn_tile_plan(dims, dt)
+    best = None
+    seen = 0
+    for vi in range(cc.cacnn_variant_count()):
+        name = cc.cacnn_variant_name(vi)
+        try:
+            plan, us, terms = cc.cacnn_plan_variant(dims, dt, vi, True)
+        except cc.CacnnError as e:
+            assert e.status == 3                      # other dtype, or the variant does not take the shape
+            continue
+        seen += 1
+        assert plan.variant == vi and name.startswith("f32 ") and us > 0 and len(terms) == 5
+        tiles = (-(-dims[2] // plan.b_k)) * (-(-dims[0] // plan.b_b)) * (-(-dims[3] // plan.b_w)) * (-(-dims[4] // plan.b_h))
+        assert terms[0] == -(-tiles // 256) and terms[1] > 0 and terms[3] >= 1
+        if best is None or us < best[0]:
+            best = (us, vi)
+    assert seen >= 10 and best[1] == chosen.variant
+    with pytest.raises(cc.CacnnError):
+        cc.cacnn_plan_variant(dims, dt, cc.cacnn_variant_count())
+    with pytest.raises(cc.CacnnError):
+        cc.cacnn_plan_variant((20, 40, 0, 17, 19, 3, 3, 1, 1), dt, 1)
