@@ -123,6 +123,13 @@ def machine_sustained(cc, torch, ci, np):
     dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
     sec = timed(lambda: cc.cacnn_probe_copy(src, dst, nbytes), 5, 10)
     out["copy_GBps_read_plus_write"] = 2.0 * nbytes / sec / 1e9
+    # every CU filling its LDS with the staging waves' loads: from a window one L2 holds, and from one far beyond the L2s
+    for label, window in (("l2_to_lds_GBps", 2 << 20), ("beyond_l2_to_lds_GBps", 512 << 20)):
+        moved = [0]
+        def fill():
+            moved[0] = cc.cacnn_probe_lds_fill(src, window, sink, 400)
+        sec = timed(fill, 3, 10)
+        out[label] = moved[0] / sec / 1e9
     del src, dst
     return out
 

@@ -267,12 +267,21 @@ int cacnn_pool_forward(const cacnn_problem* problem, int dtype, int mode, const 
  *   iters        in   1 .. 2^24; the launch issues 256 * 4 * iters * 42 MFMAs, returned in *mfma_issued (host)
  * cacnn_probe_copy: dst[0..bytes) = src[0..bytes) with streaming loads and stores: bytes read and bytes written.
  *   src, dst     DEVICE pointers, 16-byte aligned, not overlapping; bytes a positive multiple of 16
- * Both enqueue on hip_stream and return; they never synchronise and allocate nothing.  The caller times them.
+ * cacnn_probe_lds_fill: every compute unit fills its LDS from the window [src, src + window_bytes) with the loads the
+ * convolution's staging waves use (64 lanes x 16 bytes to a wave-uniform LDS address, 24 KiB in flight per wave): with a
+ * window that fits one L2 (say 2 MiB) the rate at which the L2s feed the LDS of all compute units at once; with a
+ * window far beyond the L2s, the rate from behind them.
+ *   src          in   DEVICE pointer, 16-byte aligned, at least window_bytes long
+ *   window_bytes in   a power of two, 64 KiB .. 1 GiB
+ *   sink         out  DEVICE pointer, 65536 fp32 (overwritten)
+ *   iters        in   1 .. 2^20; the launch moves 256 * 48 KiB * iters bytes, returned in *bytes_moved (host)
+ * All three enqueue on hip_stream and return; they never synchronise and allocate nothing.  The caller times them.
  * Errors: CACNN_ERR_NULL, CACNN_ERR_INVALID_ARG (alignment, sizes, iters), CACNN_ERR_UNSUPPORTED (dtype),
  * CACNN_ERR_NO_DEVICE, CACNN_ERR_LAUNCH.
  */
 int cacnn_probe_mfma(int dtype, const void* operands, float* sink, int32_t iters, int64_t* mfma_issued, void* hip_stream);
 int cacnn_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
+int cacnn_probe_lds_fill(const void* src, size_t window_bytes, float* sink, int32_t iters, void* hip_stream, int64_t* bytes_moved);
 
 /* Number of compiled kernel variants, and a static, NUL-terminated description of one
  * ("f32 k64 b8w4h4 ..."); NULL if the index is out of range.  Host only. */

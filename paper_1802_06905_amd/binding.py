@@ -143,6 +143,9 @@ _lib.cacnn_pool_forward.argtypes = [ctypes.POINTER(Problem), ctypes.c_int, ctype
 _lib.cacnn_probe_mfma.restype = ctypes.c_int
 _lib.cacnn_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
                                   ctypes.POINTER(ctypes.c_int64), ctypes.c_void_p]
+_lib.cacnn_probe_lds_fill.restype = ctypes.c_int
+_lib.cacnn_probe_lds_fill.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p,
+                                      ctypes.POINTER(ctypes.c_int64)]
 _lib.cacnn_probe_copy.restype = ctypes.c_int
 _lib.cacnn_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.cacnn_variant_count.restype = ctypes.c_int
@@ -338,6 +341,17 @@ def cacnn_probe_copy(src, dst, nbytes: int, stream=None) -> None:
     rc = _lib.cacnn_probe_copy(_ptr(src), _ptr(dst), int(nbytes), _stream_handle(stream))
     if rc != 0:
         raise CacnnError(rc, "cacnn_probe_copy")
+
+
+def cacnn_probe_lds_fill(src, window_bytes: int, sink, iters: int, stream=None) -> int:
+    """Enqueue the LDS-fill loop on every CU over the first window_bytes of src; returns the bytes the launch moves."""
+    if src.numel() * src.element_size() < int(window_bytes) or sink.numel() * sink.element_size() < 65536 * 4:
+        raise ValueError("cacnn_probe_lds_fill: src shorter than the window, or sink shorter than 65536 floats")
+    n = ctypes.c_int64(0)
+    rc = _lib.cacnn_probe_lds_fill(_ptr(src), int(window_bytes), _ptr(sink), int(iters), _stream_handle(stream), ctypes.byref(n))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_probe_lds_fill")
+    return n.value
 
 
 def cacnn_conv_forward_with_plan(problem, dtype: int, plan: Plan, image, filt, out, stream=None) -> None:

@@ -1357,6 +1357,17 @@ int cacnn_probe_mfma(int dtype, const void* operands, float* sink, int32_t iters
     return launch_mfma_probe(dtype, operands, sink, iters, grid, hip_stream) == 0 ? CACNN_OK : CACNN_ERR_LAUNCH;
 }
 
+int cacnn_probe_lds_fill(const void* src, size_t window_bytes, float* sink, int32_t iters, void* hip_stream, int64_t* bytes_moved) {
+    if (!src || !sink || !bytes_moved) return CACNN_ERR_NULL;
+    if (window_bytes < 65536 || window_bytes > (1ull << 30) || (window_bytes & (window_bytes - 1)) || iters < 1 ||
+        iters > (1 << 20) || reinterpret_cast<uintptr_t>(src) % 16)
+        return CACNN_ERR_INVALID_ARG;
+    if (!have_device()) return CACNN_ERR_NO_DEVICE;
+    const int grid = kDefaultMachine.num_cu;
+    *bytes_moved = (int64_t)grid * 4 * 12 * 1024 * iters;
+    return launch_lds_fill_probe(src, (uint32_t)window_bytes, iters, sink, grid, hip_stream) == 0 ? CACNN_OK : CACNN_ERR_LAUNCH;
+}
+
 int cacnn_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
     if (!src || !dst) return CACNN_ERR_NULL;
     if (bytes == 0 || bytes % 16 || reinterpret_cast<uintptr_t>(src) % 16 || reinterpret_cast<uintptr_t>(dst) % 16)

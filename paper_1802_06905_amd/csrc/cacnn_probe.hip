@@ -2,6 +2,8 @@
 //   mfma_rate_kernel  a register-only MFMA loop on every compute unit (one wavefront per SIMD, the same instruction
 //                     mix as the convolution kernels' inner step: 21 MFMAs on 7 accumulators, 3 + 9 operand fragments)
 //   copy_kernel       a streaming copy through HBM
+//   lds_fill_kernel   every compute unit filling its LDS from a window of global memory with the loads the convolution's
+//                     staging waves use: with a window that fits an L2 this is the rate at which the L2s feed the LDS
 // The published peaks assume the peak clock; under an all-CU matrix load the clock is power-managed and depends on
 // how much the operand bits toggle, so the sustained MFMA rate is a property of the box and of the data.
 #include <hip/hip_runtime.h>
@@ -65,6 +67,43 @@ __global__ void __launch_bounds__(256) copy_kernel(const pr_u32x4* src, pr_u32x4
     const size_t stride = (size_t)gridDim.x * 256;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
         __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+// Each of the four waves of a workgroup moves, `iters` times, twelve 1 KiB chunks (64 lanes x 16 bytes, LDS destination)
+// from the window [src, src + window) into its own 12 KiB of LDS, with the twelve loads of the previous round still in
+// flight.  A window below 64 MiB is shared: chunk numbers advance so that the workgroups of an XCD read different chunks at
+// any one time and every chunk is read by many of them (what an L2 serves).  A larger window is divided among the
+// workgroups, each streaming round and round through its own part, so that nothing a workgroup reads has been read by
+// another one (what comes from behind the L2s).  window is a power of two, at least 64 KiB.
+__global__ void __launch_bounds__(256) lds_fill_kernel(const char* src, uint32_t window, int iters, float* sink) {
+    __shared__ __align__(16) char lds[4 * 12 * 1024];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(src), 0, (int)window, 0x00020000);
+    const uint32_t chunks = window >> 10;
+    const bool shared = window < (64u << 20);
+    const uint32_t part = shared ? chunks : chunks / gridDim.x;       // chunks this workgroup walks through
+    const uint32_t base = shared ? 0u : blockIdx.x * part;
+    uint32_t chunk = shared ? (blockIdx.x * 53u + wave * 12u) & (chunks - 1) : (wave * 12u) % part;
+    __attribute__((address_space(3))) char* const mine = (__attribute__((address_space(3))) char*)lds + wave * 12 * 1024;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 12; ++i) {
+            uint32_t c = chunk + i;                 // chunk < part and part >= 64: one conditional step wraps it
+            c = c >= part ? c - part : c;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)(mine + i * 1024), 16,
+                                                     (uint32_t)lane * 16u, (base + c) << 10, 0, 0);
+        }
+        chunk = (chunk + (shared ? 48u * 5u + 12u : 48u)) % part;
+        __builtin_amdgcn_s_waitcnt((12 & 15) | ((12 >> 4) << 14) | (7 << 4) | (15 << 8));   // all but the last twelve loads are in
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    sink[blockIdx.x * 256 + threadIdx.x] = (float)lds[threadIdx.x * 16];
+}
+
+int launch_lds_fill_probe(const void* src, uint32_t window, int iters, float* sink, int grid, void* stream) {
+    hipLaunchKernelGGL(lds_fill_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const char*)src, window, iters, sink);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
 int launch_mfma_probe(int dtype, const void* operands, float* sink, int iters, int grid, void* stream) {
