@@ -98,7 +98,7 @@ __global__ void __launch_bounds__(256) lds_fill_kernel(const char* src, uint32_t
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    sink[blockIdx.x * 256 + threadIdx.x] = (float)lds[threadIdx.x * 16];
+    sink[blockIdx.x * 256 + threadIdx.x] = (float)(unsigned char)lds[threadIdx.x * 16];
 }
 
 int launch_lds_fill_probe(const void* src, uint32_t window, int iters, float* sink, int grid, void* stream) {

@@ -52,3 +52,33 @@ def test_probe_counts_scale_with_iterations(env):
         n4 = cc.cacnn_probe_mfma(dtype, ops, sink, 400)
         torch.cuda.synchronize()
         assert n1 > 0 and n4 == 4 * n1
+
+
+def test_lds_fill_probe_reads_the_window(env):
+    """The LDS-fill loop reports, per thread, one byte of what wave 0 loaded last; with a source whose every byte is its
+    chunk number modulo 251 that identifies the chunks, for the shared window and for the divided one.  Bad arguments
+    are refused on the host."""
+    cc, torch = env
+    sink = torch.zeros(65536, dtype=torch.float32, device="cuda:0")
+    for window in (1 << 20, 64 << 20):
+        chunks = window >> 10
+        src = (torch.arange(chunks, device="cuda:0", dtype=torch.int64) % 251).to(torch.uint8).repeat_interleave(1024)
+        iters = 3
+        moved = cc.cacnn_probe_lds_fill(src, window, sink, iters)
+        torch.cuda.synchronize()
+        assert moved == 256 * 48 * 1024 * iters
+        got = sink.cpu().numpy().reshape(256, 4, 64)          # workgroup, wave, lane
+        shared = window < (64 << 20)
+        part = chunks if shared else chunks // 256
+        step = 48 * 5 + 12 if shared else 48
+        # thread t of a workgroup reports LDS byte 16 t: threads 64 q .. 64 q + 63 look into the q-th KiB of wave 0's
+        # slots, which holds the q-th chunk of wave 0's last round
+        for wg in (0, 1, 17, 255):
+            first = ((wg * 53) % chunks) if shared else 0
+            first = (first + (iters - 1) * step) % part
+            base = 0 if shared else wg * part
+            for q in range(4):
+                assert np.all(got[wg, q, :] == float((base + (first + q) % part) % 251)), (window, wg, q)
+    for bad in (1000, 3 << 20, 1 << 15):
+        with pytest.raises((cc.CacnnError, ValueError)):
+            cc.cacnn_probe_lds_fill(torch.zeros(4 << 20, dtype=torch.uint8, device="cuda:0"), bad, sink, 1)
