@@ -443,3 +443,24 @@ def test_launches_can_be_captured_in_a_graph_and_replayed(env):
         torch.cuda.synchronize()
         for i, o in enumerate(outs):
             assert torch.equal(o, eager), f"replay {rep}, launch {i}"
+
+
+def test_planner_picks_on_mid_size_layers(env):
+    """cacnn_conv_forward with the planner's own choice on the mid-size and ragged layers the cost model is fitted on
+    and judged by (bench.py's two lists): whatever generic kernel and contraction tile the fitted model picks, the
+    result is the oracle's."""
+    import bench
+    cc, torch = env
+    picked = set()
+    for sh in bench.PLANNER_SHAPES + bench.CALIBRATION_SHAPES:
+        dtype, dims = sh[0], sh[1:]
+        cfg = ci.custom("mid", *dims, dtype=dtype, dist="normal", seed=21)
+        plan = cc.cacnn_tile_plan(dims, 0 if dtype == "f32" else 1)
+        vname = cc.cacnn_variant_name(plan.variant)
+        say(f"[parity] mid-size {dtype} {dims} -> {vname} [{plan.b_c} {plan.b_r} {plan.b_s}]")
+        img, flt = ci.make_inputs(cfg)
+        out = gu.run_gpu(cc, torch, cfg, img, flt)
+        ref, ab = gu.oracle_full(cfg, img, flt)
+        gu.assert_parity(cfg, out, ref, ab, vname)
+        picked.add(vname.split()[1] if not vname.split()[1].startswith("k") else "one-tile")
+    assert len(picked) >= 3, picked          # the layers exercise several kernel families
