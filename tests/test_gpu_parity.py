@@ -161,7 +161,7 @@ def test_direct_kernels_with_one_to_seven_units_per_workgroup(env, dtype):
     3..21 sub-units where an Image unit serves three filter rows), on every such kernel."""
     cc, torch = env
     names = {cc.cacnn_variant_name(i): i for i in variants_for(cc, dtype)}
-    fx = [n for n in names if " fxd " in n or " fxd16 " in n or " fxr " in n]
+    fx = [n for n in names if re.search(r" fx(d|d16|r|p\d) ", n)]
     assert len(fx) >= 2
     for name in fx:
         v = names[name]
