@@ -130,6 +130,17 @@ def machine_sustained(cc, torch, ci, np):
             moved[0] = cc.cacnn_probe_lds_fill(src, window, sink, 400)
         sec = timed(fill, 3, 10)
         out[label] = moved[0] / sec / 1e9
+    # the bf16 convolution's unit with nothing that synchronises its two halves: per compute unit and iteration 4 x 42
+    # MFMAs (1344 MFMA cycles per SIMD) and 48 KiB from the L2 into the LDS; alone, and side by side
+    words = np.ascontiguousarray(ci.bf16_bits(ci.round_to_bf16(rng.standard_normal(8192).astype(np.float32)))).view(np.int32)
+    ops = torch.from_numpy(np.ascontiguousarray(words)).cuda()
+    n = 2000
+    for label, (mi, fi) in (("unit_mix_mfma_alone_ns", (n, 0)), ("unit_mix_fill_alone_ns", (0, n)),
+                            ("unit_mix_side_by_side_ns", (n, n)),
+                            # c4's unit: 24 MFMAs per wave and 45 KiB, i.e. 2000 of them are 1143 x 42 MFMAs and 1875 x 48 KiB
+                            ("unit_mix_c4_side_by_side_ns", (1143, 1875))):
+        sec = timed(lambda: cc.cacnn_probe_mfma_and_fill(ops, src, 2 << 20, sink, mi, fi), 3, 10)
+        out[label] = sec / n * 1e9
     del src, dst
     return out
 
@@ -274,6 +285,18 @@ def alternative_variants_us(cc, torch, cfg, buffers, steps, warmup):
         torch.cuda.synchronize()
         out[name] = e0.elapsed_time(e1) * 1e3 / steps
     return out
+
+
+def add_unit_mix(rep, cfg, sustained):
+    """For c4 and c5: the units a workgroup runs (Out tiles per workgroup x c-slices x filter rows) times what the machine
+    takes for one unit's MFMAs and bytes side by side with nothing synchronising them (machine_sustained): the time the
+    launch's loop would take at that rate, without the start and the end of a launch."""
+    key = {"c5": "unit_mix_side_by_side_ns", "c4": "unit_mix_c4_side_by_side_ns"}.get(cfg.name)
+    if key is None or key not in sustained:
+        return
+    units = (cfg.C // 32) * cfg.S            # one tile per workgroup on both shapes
+    rep["units_per_workgroup"] = units
+    rep["loop_us_at_unsynchronised_mix_rate"] = units * sustained[key] * 1e-3
 
 
 def cpu_baseline(cfg, img, flt, np):
@@ -645,6 +668,7 @@ def main():
     img, flt, _, _, d_out = buffers[cfg.name]
     head = shape_report(cc, cfg, sec)
     head["frac_mfma_sustained"] = head["tflops"] / sustained[f"mfma_{cfg.dtype}_tflops"]
+    add_unit_mix(head, cfg, sustained)
 
     # parity of the timed launch against the oracle (also the cpu_baseline leg)
     result = {
@@ -676,6 +700,7 @@ def main():
                                condition=not args.no_conditioning)
             shapes[name] = shape_report(cc, c, s)
             shapes[name]["frac_mfma_sustained"] = shapes[name]["tflops"] / sustained[f"mfma_{c.dtype}_tflops"]
+            add_unit_mix(shapes[name], c, sustained)
             shapes[name]["other_fixed_geometry_variants_us"] = alternative_variants_us(
                 cc, torch, c, buffers[name], args.steps, args.warmup)
             if name == "c1":

@@ -275,13 +275,19 @@ int cacnn_pool_forward(const cacnn_problem* problem, int dtype, int mode, const 
  *   window_bytes in   a power of two, 64 KiB .. 1 GiB
  *   sink         out  DEVICE pointer, 65536 fp32 (overwritten)
  *   iters        in   1 .. 2^20; the launch moves 256 * 48 KiB * iters bytes, returned in *bytes_moved (host)
- * All three enqueue on hip_stream and return; they never synchronise and allocate nothing.  The caller times them.
+ * cacnn_probe_mfma_and_fill: both at once in the proportions of the bf16 convolution's unit, with nothing that
+ * synchronises them: on every compute unit four wavefronts run the bf16 MFMA loop (mfma_iters x 42 MFMAs each) while four
+ * others fill the LDS from a shared window (fill_iters x 12 KiB each); either count may be 0 (not both).
+ *   operands     as for cacnn_probe_mfma; src, window_bytes (64 KiB .. 32 MiB), sink as for cacnn_probe_lds_fill
+ * All of them enqueue on hip_stream and return; they never synchronise and allocate nothing.  The caller times them.
  * Errors: CACNN_ERR_NULL, CACNN_ERR_INVALID_ARG (alignment, sizes, iters), CACNN_ERR_UNSUPPORTED (dtype),
  * CACNN_ERR_NO_DEVICE, CACNN_ERR_LAUNCH.
  */
 int cacnn_probe_mfma(int dtype, const void* operands, float* sink, int32_t iters, int64_t* mfma_issued, void* hip_stream);
 int cacnn_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
 int cacnn_probe_lds_fill(const void* src, size_t window_bytes, float* sink, int32_t iters, void* hip_stream, int64_t* bytes_moved);
+int cacnn_probe_mfma_and_fill(const void* operands, const void* src, size_t window_bytes, float* sink, int32_t mfma_iters,
+                              int32_t fill_iters, void* hip_stream);
 
 /* Number of compiled kernel variants, and a static, NUL-terminated description of one
  * ("f32 k64 b8w4h4 ..."); NULL if the index is out of range.  Host only. */

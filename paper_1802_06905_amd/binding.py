@@ -146,6 +146,9 @@ _lib.cacnn_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p
 _lib.cacnn_probe_lds_fill.restype = ctypes.c_int
 _lib.cacnn_probe_lds_fill.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p,
                                       ctypes.POINTER(ctypes.c_int64)]
+_lib.cacnn_probe_mfma_and_fill.restype = ctypes.c_int
+_lib.cacnn_probe_mfma_and_fill.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int32,
+                                           ctypes.c_int32, ctypes.c_void_p]
 _lib.cacnn_probe_copy.restype = ctypes.c_int
 _lib.cacnn_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.cacnn_variant_count.restype = ctypes.c_int
@@ -352,6 +355,17 @@ def cacnn_probe_lds_fill(src, window_bytes: int, sink, iters: int, stream=None) 
     if rc != 0:
         raise CacnnError(rc, "cacnn_probe_lds_fill")
     return n.value
+
+
+def cacnn_probe_mfma_and_fill(operands, src, window_bytes: int, sink, mfma_iters: int, fill_iters: int, stream=None) -> None:
+    """Enqueue the bf16 MFMA loop and the LDS fill side by side on every CU (either iteration count may be 0)."""
+    if operands.numel() * operands.element_size() < 16384 or src.numel() * src.element_size() < int(window_bytes) or \
+            sink.numel() * sink.element_size() < 65536 * 4:
+        raise ValueError("cacnn_probe_mfma_and_fill: operands (16 KiB), src (the window) or sink (65536 floats) too short")
+    rc = _lib.cacnn_probe_mfma_and_fill(_ptr(operands), _ptr(src), int(window_bytes), _ptr(sink), int(mfma_iters),
+                                        int(fill_iters), _stream_handle(stream))
+    if rc != 0:
+        raise CacnnError(rc, "cacnn_probe_mfma_and_fill")
 
 
 def cacnn_conv_forward_with_plan(problem, dtype: int, plan: Plan, image, filt, out, stream=None) -> None:

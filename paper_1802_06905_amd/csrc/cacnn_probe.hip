@@ -101,6 +101,63 @@ __global__ void __launch_bounds__(256) lds_fill_kernel(const char* src, uint32_t
     sink[blockIdx.x * 256 + threadIdx.x] = (float)(unsigned char)lds[threadIdx.x * 16];
 }
 
+// Both at once, in the proportions of the bf16 convolution's unit: waves 0-3 of a workgroup of eight run the register-only
+// bf16 MFMA loop (42 MFMAs per iteration and wave), waves 4-7 the LDS fill from a shared window (12 KiB per iteration and
+// wave).  Either count may be zero.  What the two cost each other when nothing synchronises them.
+__global__ void __launch_bounds__(512) mfma_and_fill_kernel(const uint32_t* operands, const char* src, uint32_t window,
+                                                            int mfma_iters, int fill_iters, float* sink) {
+    __shared__ __align__(16) char lds[4 * 12 * 1024];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    float result = 0.f;
+    if (wave < 4) {
+        pr_f32x16 acc[7];
+#pragma unroll
+        for (int n = 0; n < 7; ++n)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
+        pr_bf16x8 A[3], X[9];
+        const pr_u32x4* const op = (const pr_u32x4*)operands;
+#pragma unroll
+        for (int r = 0; r < 3; ++r) A[r] = __builtin_bit_cast(pr_bf16x8, op[(lane + 64 * r) & 1023]);
+#pragma unroll
+        for (int x = 0; x < 9; ++x) X[x] = __builtin_bit_cast(pr_bf16x8, op[(lane + 64 * (3 + x)) & 1023]);
+        for (int it = 0; it < 2 * mfma_iters; ++it) {
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int w = 0; w < 7; ++w)
+                    acc[w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[r], X[w + r], acc[w], 0, 0, 0);
+        }
+#pragma unroll
+        for (int n = 0; n < 7; ++n)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) result += acc[n][v];
+    } else {
+        const int fw = wave - 4;
+        const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(src), 0, (int)window, 0x00020000);
+        const uint32_t chunks = window >> 10;
+        uint32_t chunk = (blockIdx.x * 53u + fw * 12u) & (chunks - 1);
+        __attribute__((address_space(3))) char* const mine = (__attribute__((address_space(3))) char*)lds + fw * 12 * 1024;
+        for (int it = 0; it < fill_iters; ++it) {
+#pragma unroll
+            for (int i = 0; i < 12; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)(mine + i * 1024), 16,
+                                                         (uint32_t)lane * 16u, ((chunk + i) & (chunks - 1)) << 10, 0, 0);
+            chunk = (chunk + 48u * 5u + 12u) & (chunks - 1);
+            __builtin_amdgcn_s_waitcnt((12 & 15) | ((12 >> 4) << 14) | (7 << 4) | (15 << 8));
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+    }
+    if (wave < 4) sink[blockIdx.x * 256 + threadIdx.x] = result;
+}
+
+int launch_mfma_and_fill_probe(const void* operands, const void* src, uint32_t window, int mfma_iters, int fill_iters,
+                               float* sink, int grid, void* stream) {
+    hipLaunchKernelGGL(mfma_and_fill_kernel, dim3(grid), dim3(512), 0, (hipStream_t)stream, (const uint32_t*)operands,
+                       (const char*)src, window, mfma_iters, fill_iters, sink);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
 int launch_lds_fill_probe(const void* src, uint32_t window, int iters, float* sink, int grid, void* stream) {
     hipLaunchKernelGGL(lds_fill_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const char*)src, window, iters, sink);
     return hipGetLastError() == hipSuccess ? 0 : 1;

@@ -82,3 +82,24 @@ def test_lds_fill_probe_reads_the_window(env):
     for bad in (1000, 3 << 20, 1 << 15):
         with pytest.raises((cc.CacnnError, ValueError)):
             cc.cacnn_probe_lds_fill(torch.zeros(4 << 20, dtype=torch.uint8, device="cuda:0"), bad, sink, 1)
+
+
+def test_mfma_and_fill_probe_sums_and_refuses(env):
+    """The combined probe's MFMA half computes what the MFMA probe computes (all-ones operands), with and without the
+    fill running next to it; bad arguments are refused on the host."""
+    cc, torch = env
+    ops = torch.from_numpy(np.full(4096, np.int32(0x3f803f80), dtype=np.int32)).cuda()
+    src = torch.zeros(2 << 20, dtype=torch.uint8, device="cuda:0")
+    iters = 4
+    for fill in (0, 7):
+        sink = torch.zeros(65536, dtype=torch.float32, device="cuda:0")
+        cc.cacnn_probe_mfma_and_fill(ops, src, 2 << 20, sink, iters, fill)
+        torch.cuda.synchronize()
+        assert torch.all(sink == float(7 * 16 * 3 * 2 * iters * 16))
+    sink = torch.zeros(65536, dtype=torch.float32, device="cuda:0")
+    cc.cacnn_probe_mfma_and_fill(ops, src, 2 << 20, sink, 0, 5)      # fill alone: runs, leaves the sink alone
+    torch.cuda.synchronize()
+    assert float(sink.abs().sum()) == 0.0
+    for window, mi, fi in ((3 << 20, 1, 1), (2 << 20, 0, 0), (2 << 20, -1, 1), (64 << 20, 1, 1)):
+        with pytest.raises((cc.CacnnError, ValueError)):
+            cc.cacnn_probe_mfma_and_fill(ops, torch.zeros(64 << 20, dtype=torch.uint8, device="cuda:0"), window, sink, mi, fi)
