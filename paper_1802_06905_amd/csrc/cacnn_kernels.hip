@@ -2120,13 +2120,13 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
 }
 
 // ---- fixed geometry, bf16, staged through registers with a deep prefetch ----------------------------------------------
-// Measured on the kernel above (timing-only builds of it that leave out one thing at a time, 256 compute units busy):
-// without its MFMAs it takes as long as with them (3 x 3 taps over 14 x 14 outputs, 64 images, 256 channels: 19.3 us either
-// way; 7 x 7 outputs, 256 images, 512 channels: 48 us against 52.5), and leaving out the Image fetches, all LDS reads or
-// the Out stores each gains about a tenth.  What sets its pace is the time a fetch takes divided by how many units of
-// fetches are in flight: a unit's words arrive 1.3 to 2 us after they are requested (most first requests of a line miss
-// the L2, and every compute unit asks at once), and with the loads' destination in LDS only the two buffers that are not
-// being read can be in flight, so a unit cannot take less than about half of that, whatever it holds.
+// The kernel above can have two units of fetches in flight, the two LDS buffers that are not being read.  This one was
+// built to find out whether that depth is what limits it: it is not.  With fetches up to four units ahead this kernel
+// takes the same time to within a few per cent on both benchmark shapes it accepts, and so does the kernel above when
+// the rows of a unit are pulled into the L2 four to six units early.  (What the machine does with one unit's MFMAs
+// and bytes when nothing synchronises them is measured by the probe kernels; the kernel above runs at 84 to 88 % of it.)
+// It stays as a selectable variant because it halves the LDS the Image needs and makes room for an Image unit that
+// serves all three filter rows.
 // Here the words in flight wait in the staging waves' registers instead, of which those waves have plenty (a staging
 // wave needs a dozen for its addresses): Filter words are requested three or four sub-units ahead and Image words
 // two to four Image units ahead, and a set of registers is written to LDS (16-byte stores, the same layouts as above:
