@@ -138,7 +138,13 @@ def machine_sustained(cc, torch, ci, np):
     for label, (mi, fi) in (("unit_mix_mfma_alone_ns", (n, 0)), ("unit_mix_fill_alone_ns", (0, n)),
                             ("unit_mix_side_by_side_ns", (n, n)),
                             # c4's unit: 24 MFMAs per wave and 45 KiB, i.e. 2000 of them are 1143 x 42 MFMAs and 1875 x 48 KiB
-                            ("unit_mix_c4_side_by_side_ns", (1143, 1875))):
+                            ("unit_mix_c4_side_by_side_ns", (1143, 1875)),
+                            # the same MFMAs with the bytes two other tilings of c4 would stage per unit: an Image unit that
+                            # serves all three filter rows (33.9 KiB per 24 MFMAs), 128 output channels x half the positions
+                            # (41 KiB)
+                            ("unit_mix_c4_three_rows_per_image_unit_ns", (1143, 1412)),
+                            ("unit_mix_c4_k128_half_positions_ns", (1143, 1708)),
+                            ("unit_mix_c4_mfma_alone_ns", (1143, 0))):
         sec = timed(lambda: cc.cacnn_probe_mfma_and_fill(ops, src, 2 << 20, sink, mi, fi), 3, 10)
         out[label] = sec / n * 1e9
     del src, dst
