@@ -522,3 +522,19 @@ def test_plan_variant_reports_the_cost_model_per_variant():
         cc.cacnn_plan_variant(dims, dt, cc.cacnn_variant_count())
     with pytest.raises(cc.CacnnError):
         cc.cacnn_plan_variant((20, 40, 0, 17, 19, 3, 3, 1, 1), dt, 1)
+
+
+def test_lp_tile_at_l2_and_cache_model_agree_on_the_channel_groups():
+    """Two routes to the number of output-channel groups a_K the eight XCDs are divided into: the k-extent of the
+    Section 5 LP's tile at M = one L2 (K / l2_tile_k, rounded to the nearest admissible power of two in log distance) and
+    the per-XCD cache model's cheapest layout.  On the benchmark shapes and the two Filter-heavy workloads they agree."""
+    import math
+    for name in ("c2", "c3", "c4", "c5", "d1", "d2"):
+        cfg = ci.CONFIGS.get(name) or ci.DIVISION_CONFIGS[name]
+        dt = 0 if cfg.dtype == "f32" else 1
+        plan, l2 = cc.cacnn_tile_plan(cfg.dims, dt), cc.cacnn_two_level_plan(cfg.dims, dt)
+        tiles_k = -(-cfg.K // plan.b_k)
+        want = cfg.K / l2.l2_tile_k
+        admissible = [a for a in (1, 2, 4, 8) if tiles_k % a == 0]
+        from_lp = min(admissible, key=lambda a: abs(math.log(a / want)))
+        assert from_lp == l2.a_k, (name, want, l2.a_k)
