@@ -151,14 +151,12 @@ def machine_sustained(cc, torch, ci, np):
     return out
 
 
-def graph_replay_us(cc, torch, ci, np, cfg, launches=200, replays=20):
+def graph_replay_us(cc, torch, ci, np, cfg, buffers, launches=200, replays=20):
     """Per-launch time of the workload when `launches` back-to-back launches are captured in one HIP graph and replayed:
     what a launch-bound caller gets (the plain figure is bound by the host's launch path for a problem as small as c1)."""
-    img, flt = ci.make_inputs(cfg)
-    d_img = torch.from_numpy(img.reshape(-1)).cuda()
-    d_flt = torch.from_numpy(flt.reshape(-1)).cuda()
-    d_out = torch.empty(int(np.prod(cfg.out_shape)), dtype=torch.float32, device="cuda:0")
-    cc.cacnn_conv_forward(cfg.dims, 0, d_img, d_flt, d_out)     # plan and kernel set-up happen outside the capture
+    _, _, d_img, d_flt, d_out = buffers
+    dt = 0 if cfg.dtype == "f32" else 1
+    cc.cacnn_conv_forward(cfg.dims, dt, d_img, d_flt, d_out)     # plan and kernel set-up happen outside the capture
     torch.cuda.synchronize()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -166,7 +164,7 @@ def graph_replay_us(cc, torch, ci, np, cfg, launches=200, replays=20):
     with torch.cuda.stream(side):
         with torch.cuda.graph(graph, stream=side):
             for _ in range(launches):
-                cc.cacnn_conv_forward(cfg.dims, 0, d_img, d_flt, d_out)
+                cc.cacnn_conv_forward(cfg.dims, dt, d_img, d_flt, d_out)
     torch.cuda.synchronize()
     for _ in range(3):
         graph.replay()
@@ -387,22 +385,29 @@ def division_report(cc, torch, ci, np, cfg, steps, warmup):
            "layouts": {}}
     a, b = cc.cacnn_work_division(cfg.dims, M2, 8)
     rep["paper_division_p8_M_l2"] = {"a_B_a_K_a_W_a_H": list(a), "bound_words": b.bound}
-    for i in range(l2.n_candidates):
-        ak, walk = l2.cand_a_k[i], l2.cand_walk[i]
-        plan.xcd_split_k, plan.xcd_walk = ak, walk
-        condition_power_state(cc, torch, ci, np, "bf16")
-        for _ in range(warmup):
-            cc.cacnn_conv_forward_with_plan(cfg.dims, 1, plan, d_img, d_flt, d_out)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(steps):
-            cc.cacnn_conv_forward_with_plan(cfg.dims, 1, plan, d_img, d_flt, d_out)
-        e1.record()
-        torch.cuda.synchronize()
-        sec = e0.elapsed_time(e1) * 1e-3 / steps
+    # four passes over the layouts, alternately forwards and backwards; per layout and pass the power-state conditioning,
+    # `warmup` launches, `steps` timed ones; the figure kept is the median of the four (the clock's slow stretch between
+    # a few dozen and a few hundred launches after a cold start would otherwise land on whichever layout comes first)
+    cands = [(l2.cand_a_k[i], l2.cand_walk[i]) for i in range(l2.n_candidates)]
+    times = {c: [] for c in cands}
+    for rnd in range(4):
+        for (ak, walk) in (cands if rnd % 2 == 0 else cands[::-1]):
+            plan.xcd_split_k, plan.xcd_walk = ak, walk
+            condition_power_state(cc, torch, ci, np, "bf16")
+            for _ in range(warmup):
+                cc.cacnn_conv_forward_with_plan(cfg.dims, 1, plan, d_img, d_flt, d_out)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                cc.cacnn_conv_forward_with_plan(cfg.dims, 1, plan, d_img, d_flt, d_out)
+            e1.record()
+            torch.cuda.synchronize()
+            times[(ak, walk)].append(e0.elapsed_time(e1) * 1e-3 / steps)
+    for i, (ak, walk) in enumerate(cands):
+        sec = float(np.median(times[(ak, walk)]))
         pb = cc.cacnn_parallel_bound(cfg.dims, M2, (1, ak, 1, min(8 // ak, cfg.H)))
         rep["layouts"][f"aK{ak}w{walk}"] = {
-            "us": sec * 1e6, "tflops": 2.0 * cfg.macs / sec / 1e12,
+            "us": sec * 1e6, "us_min": min(times[(ak, walk)]) * 1e6, "tflops": 2.0 * cfg.macs / sec / 1e12,
             "model_bytes": esz * (l2.cand_words[i] - n_out) + 4.0 * n_out,
             "paper_parallel_bound_words_M_l2": pb.bound,
             "hbm_bytes_recorded": committed_traffic(f"{cfg.name}_aK{ak}w{walk}")}
@@ -595,6 +600,9 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 512 MiB device copy (calibration), a cache-evicting 1 GiB fill, "
                          "then one cold and one warm launch of the workload; prints nothing but a marker line")
+    ap.add_argument("--two-level", action="store_true",
+                    help="with --workload c4 or c5: time every layout of an XCD's run of tiles that the two-level plan prices "
+                         "(what --workload d1 / d2 always do)")
     ap.add_argument("--planner-sweep", choices=["calibration", "test"], default=None,
                     help="time every kernel variant on the calibration layers (or on the --planner-compare layers) and print "
                          "the cost model's estimate next to each; no JSON line")
@@ -641,8 +649,8 @@ def main():
             out["cpu_baseline"] = rep["cpu_baseline"]
         print(json.dumps(out))
         return
-    if args.workload in ("d1", "d2"):
-        dcfg = ci.DIVISION_CONFIGS[args.workload]
+    if args.workload in ("d1", "d2") or (args.two_level and args.workload in ("c4", "c5") and not args.traffic_probe):
+        dcfg = ci.DIVISION_CONFIGS[args.workload] if args.workload in ci.DIVISION_CONFIGS else ci.CONFIGS[args.workload]
         if args.traffic_probe:
             traffic_probe(cc, torch, ci, np, dcfg, args.xcd_split_k, args.xcd_walk)
             return
@@ -710,8 +718,10 @@ def main():
             shapes[name]["other_fixed_geometry_variants_us"] = alternative_variants_us(
                 cc, torch, c, buffers[name], args.steps, args.warmup)
             if name == "c1":
-                shapes[name]["us_per_launch_in_a_hip_graph"] = graph_replay_us(cc, torch, ci, np, c)
-        # (the headline shape's alternatives last, so that its own timed region and parity check come first)
+                shapes[name]["us_per_launch_in_a_hip_graph"] = graph_replay_us(cc, torch, ci, np, c, buffers[name])
+        # (the headline shape's extras last, so that its own timed region and parity check come first)
+        condition_power_state(cc, torch, ci, np, cfg.dtype)
+        head["us_per_launch_in_a_hip_graph"] = graph_replay_us(cc, torch, ci, np, cfg, buffers[cfg.name], launches=100, replays=5)
         head["other_fixed_geometry_variants_us"] = alternative_variants_us(cc, torch, cfg, buffers[cfg.name],
                                                                            args.steps, args.warmup)
         result["shapes"] = shapes
