@@ -310,7 +310,7 @@ const char* cacnn_status_string(int status);
  *     what the counters show on MI355X (a line has left the L2 before the neighbouring tile asks for it);
  *   - a_k / walk: candidates are taken in the order a_K = 1, 2, 4, 8, walk 0 before 1, and a later one replaces the
  *     choice only if it saves 3 % of the chosen one's words; cacnn_tile_plan puts them into xcd_split_k / xcd_walk.
- * machine_l2 NULL = MI355X (4 MiB, 8 XCDs, 32 compute units each).  Problems with more than two million tiles are not
+ * machine_l2 NULL = MI355X (4 MiB, 8 XCDs, 32 compute units each).  Problems with more than a hundred thousand tiles are not
  * simulated: n_candidates = 0 and a_k is the closed-form choice that minimises a_K*|Image| + (8/a_K)*|Filter|.
  * Errors: as cacnn_tile_plan.
  */

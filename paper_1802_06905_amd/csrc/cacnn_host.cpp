@@ -639,7 +639,7 @@ double l2_model_words(const cacnn_problem& p, const TileGeom& tg, int a_k, int w
     const int64_t npos = tb * tw * th, n_tiles = tk * npos, kpg = tk / a_k;
     const int64_t IW = p.sigma_w * (p.W - 1) + p.R, IH = p.sigma_h * (p.H - 1) + p.S;
     const int64_t XS = p.sigma_w * (tg.TW - 1) + p.R, YS = p.sigma_h * (tg.TH - 1) + p.S;
-    if ((double)n_tiles > 2.0e6) return -1.0;
+    if ((double)n_tiles > 1.0e5) return -1.0;     // the walk costs about half a microsecond per tile and candidate
     const int64_t q = n_tiles / m2.n_xcd, rem = n_tiles % m2.n_xcd;
     const int64_t per_xcd = std::max<int64_t>(1, tg.grid / m2.n_xcd);
     double total = 0.0;
