@@ -93,8 +93,9 @@ typedef struct {
                                 full b_r, b_s range where the last contraction tile is ragged) */
     int32_t xcd_split_k;     /* Section 7 with the eight XCDs (each has its own L2) as the processors: the XCDs are
                                 divided into this many groups of output channels (a_K; 1, 2, 4 or 8, a divisor of the
-                                k-tile count) and 8 / a_K ranges of positions, whichever makes a_K*|Image| +
-                                (8/a_K)*|Filter| bytes smallest.  cacnn_conv_forward_with_plan: 0 = choose. */
+                                k-tile count) and 8 / a_K ranges of positions.  Chosen together with xcd_walk by the
+                                per-XCD cache model of cacnn_two_level_plan (the layout whose modelled fetches from
+                                behind the L2s are fewest).  cacnn_conv_forward_with_plan: 0 = choose. */
     int32_t xcd_walk;        /* order of an XCD's run of tiles: 0 = the k-tiles of a position tile are neighbours (the
                                 Image tile is fetched once, the Filter rows of the k-group stream past once per round of
                                 workgroups), 1 = the position tiles of a k-tile are neighbours (the other way round).
