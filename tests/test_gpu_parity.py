@@ -464,3 +464,32 @@ def test_planner_picks_on_mid_size_layers(env):
         gu.assert_parity(cfg, out, ref, ab, vname)
         picked.add(vname.split()[1] if not vname.split()[1].startswith("k") else "one-tile")
     assert len(picked) >= 3, picked          # the layers exercise several kernel families
+
+
+def test_planner_path_on_random_shapes(env):
+    """Seeded random problems (both dtypes; batch, channel, image and filter sizes from lists that include 1, primes and
+    the kernels' tile sizes; strides up to 3) through cacnn_conv_forward with the planner's own choice, against the oracle."""
+    import random
+    cc, torch = env
+    rng = random.Random(20260)
+    done, families = 0, set()
+    while done < 60:
+        dtype = rng.choice(["f32", "bf16"])
+        dims = (rng.choice([1, 2, 3, 5, 8, 16, 24, 32, 40, 64, 96, 128]), rng.choice([1, 3, 4, 8, 16, 24, 32, 48, 64, 96, 128, 200, 256]),
+                rng.choice([1, 8, 16, 32, 40, 64, 96, 128, 192, 256, 320]), rng.choice([1, 2, 3, 5, 7, 8, 13, 14, 16, 20, 28]),
+                rng.choice([1, 2, 3, 5, 7, 8, 13, 14, 16, 20, 28]), rng.choice([1, 1, 2, 3, 3, 3, 5, 7]),
+                rng.choice([1, 1, 2, 3, 3, 3, 5, 7]), rng.choice([1, 1, 1, 2, 3]), rng.choice([1, 1, 1, 2, 3]))
+        macs = float(np.prod([float(d) for d in dims[:7]]))
+        if macs > 6e9 or (done % 2 == 1 and macs < 1e8):      # every other one is a mid-size problem
+            continue
+        cfg = ci.custom("rnd", *dims, dtype=dtype, dist="normal", seed=3000 + done)
+        plan = cc.cacnn_tile_plan(dims, 0 if dtype == "f32" else 1)
+        vname = cc.cacnn_variant_name(plan.variant)
+        say(f"[parity] random {done} {dtype} {dims} -> {vname} [{plan.b_c} {plan.b_r} {plan.b_s}]")
+        img, flt = ci.make_inputs(cfg)
+        out = gu.run_gpu(cc, torch, cfg, img, flt)
+        ref, ab = gu.oracle_full(cfg, img, flt)
+        gu.assert_parity(cfg, out, ref, ab, vname)
+        families.add(vname.split()[1] if not vname.split()[1].startswith("k") else "one-tile")
+        done += 1
+    assert len(families) >= 3, families
