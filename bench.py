@@ -542,6 +542,13 @@ def planner_sweep(cc, torch, ci, np, shapes):
         print(f"fit | {family} | {' '.join(f'{c:.4g}' for c in x)} | {float(np.sqrt(np.mean(err ** 2))):.3f} | {len(A)}")
 
 
+# 1 x 1 layers on 64 or more images: the fixed-geometry kernels for 1 x 1 filters take these
+ONE_BY_ONE_SHAPES = [
+    ("bf16", 64, 1024, 256, 14, 14, 1, 1, 1, 1), ("bf16", 128, 256, 512, 7, 7, 1, 1, 1, 1), ("bf16", 64, 512, 2048, 7, 7, 1, 1, 1, 1),
+    ("bf16", 64, 64, 256, 56, 56, 1, 1, 1, 1), ("bf16", 256, 2048, 512, 7, 7, 1, 1, 1, 1),
+]
+
+
 def planner_compare(cc, torch, ci, np):
     """The planner's pick against the fastest of all kernel variants (cacnn_tune) on PLANNER_SHAPES; the planner is the
     one the environment selects (CACNN_PLANNER unset: the calibrated cycle model; lp: the tile sized from the Section 5
@@ -561,7 +568,7 @@ def planner_compare(cc, torch, ci, np):
 
     ratios = []
     print("mode | dtype B C K W H R S sw sh | planner's variant [b_c b_r b_s] us | fastest variant [b_c b_r b_s] us | ratio")
-    for sh in PLANNER_SHAPES:
+    for sh in PLANNER_SHAPES + ONE_BY_ONE_SHAPES:
         dtype, dims = sh[0], sh[1:]
         cfg = ci.custom("cmp", *dims, dtype=dtype, dist="normal", seed=3)
         _, _, d_img, d_flt, d_out = upload_config(torch, ci, np, cfg)
@@ -570,7 +577,8 @@ def planner_compare(cc, torch, ci, np):
         t_plan = timed(lambda: cc.cacnn_conv_forward_with_plan(dims, dt, plan, d_img, d_flt, d_out))
         tuned = cc.cacnn_tune(dims, dt, d_img, d_flt, d_out)
         t_tune = timed(lambda: cc.cacnn_conv_forward_with_plan(dims, dt, tuned, d_img, d_flt, d_out))
-        ratios.append(t_plan / t_tune)
+        if sh in PLANNER_SHAPES:
+            ratios.append(t_plan / t_tune)                # the summary line is about the generic kernels' cost model
         print(f"{mode} | {dtype} {' '.join(str(v) for v in dims)} | {cc.cacnn_variant_name(plan.variant)} "
               f"[{plan.b_c}, {plan.b_r}, {plan.b_s}] {t_plan:.2f} | {cc.cacnn_variant_name(tuned.variant)} "
               f"[{tuned.b_c}, {tuned.b_r}, {tuned.b_s}] {t_tune:.2f} | {t_plan / t_tune:.3f}", flush=True)

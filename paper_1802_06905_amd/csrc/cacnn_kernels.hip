@@ -1866,9 +1866,11 @@ struct FxWalk {
 // quarter of the bytes) still goes through registers; its LDS stores are written as assembly so that the compiler's
 // wait-count bookkeeping, which makes every LDS access it knows of wait for all outstanding loads into LDS, does not
 // see them (their operands are still tracked: the store waits for its own Filter load).
-template <int TW, int TH>
+// BRP: the filter's extent along w the kernel is compiled for (3, or 1 for 1 x 1 filters, where a unit is a plain
+// matrix product of the Filter tile with the tile's positions).
+template <int TW, int TH, int BRP = 3>
 struct Bf16DirectFixed {
-    static constexpr int TB = 64, KT = 64, WM = 2, WN = 2, CT = 32, BS = 1, BR = 3, NBLK = TW * TH;
+    static constexpr int TB = 64, KT = 64, WM = 2, WN = 2, CT = 32, BS = 1, BR = BRP, NBLK = TW * TH;
     static constexpr int C8 = CT / 8, STEPS = BS * (CT / 16);
     static constexpr int XS = TW + BR - 1, YS = TH - 1 + BS;
     static constexpr int ROW = TB * 2;                              // bytes of one (x, y, c) row
@@ -1972,9 +1974,9 @@ __device__ __forceinline__ void load_16_bytes_per_lane_to_lds(__amdgpu_buffer_rs
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (CACNN_LDS(void)*)dst, 16, voff, soff, 0, 0);
 }
 
-template <int TW, int TH>
+template <int TW, int TH, int BRP = 3>
 __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs a) {
-    using GEO = Bf16DirectFixed<TW, TH>;
+    using GEO = Bf16DirectFixed<TW, TH, BRP>;
     constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, BR = GEO::BR, WM = GEO::WM, NBLK = GEO::NBLK;
     constexpr int XS = GEO::XS, YS = GEO::YS, C8 = GEO::C8, F8 = GEO::F8, ROW = GEO::ROW, BUF = GEO::BUF_BYTES;
     constexpr int CTHREADS = GEO::WM * GEO::WN * 64;
@@ -2987,6 +2989,18 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
+// the same for 1 x 1 filters
+#define CACNN_DIRECT_1X1_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                               \
+    {                                                                                                          \
+        {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, TH, 1>::NBLK, 64, TW, TH, 2, 1, Bf16DirectFixed<TW, TH, 1>::MAXF, 1, 1, 1.0f, 32, 1,  \
+         1, Bf16DirectFixed<TW, TH, 1>::YS, 1, 1, Bf16DirectFixed<TW, TH, 1>::LDS_BYTES, UNIT_US, FIXED_US, 0}, \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                if (!Bf16DirectFixed<TW, TH, 1>::matches_host(a) || lds != (size_t)Bf16DirectFixed<TW, TH, 1>::LDS_BYTES) return 1; \
+                return launch_kernel(conv_bf16_direct_kernel<TW, TH, 1>, attr_done, 512, a, grid, lds, stream); \
+            }                                                                                                  \
+    }
+
 // bf16 staged through registers with a deep prefetch: 64 images, 64 output channels, 32-channel slices, Image units of BSI filter rows
 #define CACNN_STAGED_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH, BSI)                                              \
     {                                                                                                          \
@@ -3083,6 +3097,8 @@ static const Variant g_variants[] = {
     CACNN_F32_DIRECT16_VARIANT("f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r3s3", 4.1f, 2.6f, 2, 7),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.0f, 4.5f, 7, 1),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.62f, 4.2f, 2, 2),
+    CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1", 0.50f, 4.5f, 7, 1),
+    CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1", 0.30f, 4.2f, 2, 2),
     CACNN_STAGED_VARIANT("bf16 fxr k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.1f, 4.5f, 7, 1, 1),
     CACNN_STAGED_VARIANT("bf16 fxr k64 b64w2h2 w2x2 m1n4 c32r3s3", 2.0f, 4.2f, 2, 2, 3),
     // fixed geometry for the stem-layer shape: 7x7 taps, strides 2, three channels

@@ -63,6 +63,7 @@ RAGGED = [
     ("pipe_b8", 8, 16, 64, 13, 12, 3, 3, 1, 1),
     # shapes the fixed-geometry kernels tile exactly (3x3 taps, unit strides), several tiles and several c-slices
     ("fx_w7", 128, 64, 128, 7, 3, 3, 3, 1, 1),
+    ("fx_1x1", 64, 96, 128, 14, 4, 1, 1, 1, 1),
     ("fx_w2h2", 64, 96, 192, 4, 6, 3, 3, 1, 1),
     ("fx_w4h4", 64, 32, 128, 8, 12, 3, 3, 1, 1),
     # more tiles than workgroups (a workgroup walks several tiles), and a filter taller than the fixed b_s
@@ -90,7 +91,7 @@ def variants_for(cc, dtype):
 
 # the forced contraction tiles; the last two are the ones the fixed-geometry kernels are compiled for
 FORCED_TILES = {"f32": ((1 << 20, 1 << 20, 1 << 20), (3, 2, 1), (16, 3, 3), (32, 3, 1)),
-                "bf16": ((1 << 20, 1 << 20, 1 << 20), (16, 2, 1), (16, 3, 3), (32, 3, 1), (32, 3, 3))}
+                "bf16": ((1 << 20, 1 << 20, 1 << 20), (16, 2, 1), (16, 3, 3), (32, 3, 1), (32, 3, 3), (32, 1, 1))}
 
 
 def staged_tile_fits(cc, cfg, vi, bc, br, bs):
@@ -143,7 +144,7 @@ def test_every_variant_runs_on_some_ragged_shape(env, dtype):
     fixed-geometry family) every variant launches at least once, the generic ones with at least two tilings."""
     cc, torch = env
     ran = {}
-    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_w2h2", "fx_w4h4", "fx16_two_each", "fx_stem")
+    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_w2h2", "fx_w4h4", "fx16_two_each", "fx_stem")
     for shape in RAGGED:
         if shape[0] in pick:
             run_every_variant(cc, torch, shape, dtype, ran)
@@ -166,17 +167,17 @@ def test_direct_kernels_with_one_to_seven_units_per_workgroup(env, dtype):
     for name in fx:
         v = names[name]
         tb, tw, th = (int(x) for x in re.search(r" b(\d+)w(\d+)h(\d+) ", name).groups())
-        bc, _, bs = (int(x) for x in re.search(r" c(\d+)r(\d+)s(\d+)", name).groups())
+        bc, br, bs = (int(x) for x in re.search(r" c(\d+)r(\d+)s(\d+)", name).groups())
         for units in range(1, 8):
             if bs == 3:
                 C, S = bc * units, 3          # units c-slices, each with all three filter rows
             else:
                 C, S = bc, units              # one c-slice, units filter rows
-            cfg = ci.custom(f"units{units}", tb, C, 64, tw, th, 3, S, 1, 1, dtype=dtype, dist="normal", seed=500 + units)
+            cfg = ci.custom(f"units{units}", tb, C, 64, tw, th, br, S, 1, 1, dtype=dtype, dist="normal", seed=500 + units)
             img, flt = ci.make_inputs(cfg)
             ref, ab = gu.oracle_full(cfg, img, flt)
             plan = cc.Plan()
-            plan.variant, plan.b_c, plan.b_r, plan.b_s = v, bc, 3, bs
+            plan.variant, plan.b_c, plan.b_r, plan.b_s = v, bc, br, bs
             say(f"[parity] {units} unit(s) '{name}' dims={cfg.dims}")
             out = gu.run_gpu(cc, torch, cfg, img, flt, plan=plan)
             gu.assert_parity(cfg, out, ref, ab, f"{name}, {units} units")
