@@ -542,8 +542,10 @@ def planner_sweep(cc, torch, ci, np, shapes):
         print(f"fit | {family} | {' '.join(f'{c:.4g}' for c in x)} | {float(np.sqrt(np.mean(err ** 2))):.3f} | {len(A)}")
 
 
-# 1 x 1 layers on 64 or more images: the fixed-geometry kernels for 1 x 1 filters take these
+# 1 x 1 layers that the fixed-geometry kernels for 1 x 1 filters take (bf16: 64 or more images; fp32: 8 or more, rows in sevens)
 ONE_BY_ONE_SHAPES = [
+    ("f32", 8, 256, 256, 14, 14, 1, 1, 1, 1), ("f32", 32, 512, 128, 28, 28, 1, 1, 1, 1), ("f32", 16, 64, 256, 56, 56, 1, 1, 1, 1),
+    ("f32", 64, 1024, 256, 14, 14, 1, 1, 1, 1),
     ("bf16", 64, 1024, 256, 14, 14, 1, 1, 1, 1), ("bf16", 128, 256, 512, 7, 7, 1, 1, 1, 1), ("bf16", 64, 512, 2048, 7, 7, 1, 1, 1, 1),
     ("bf16", 64, 64, 256, 56, 56, 1, 1, 1, 1), ("bf16", 256, 2048, 512, 7, 7, 1, 1, 1, 1),
 ]

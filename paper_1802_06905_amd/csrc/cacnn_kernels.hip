@@ -2585,9 +2585,10 @@ __global__ void __launch_bounds__(512) conv_f32_direct_kernel(const KernelArgs a
 // Image read fall into 64 different banks.  For fixed (r, channel) the 9 Image rows y = 0..8 serve all 7 blocks and 3 taps s
 // (block j with tap s reads row j + s): 18 Image reads and 3 Filter reads per 42 MFMAs.  A plane holds 10 rows in LDS
 // (whole 1 KiB chunks of two rows; the tenth is fetched and never read).
-template <int TW, int TH>
+// BRS: the filter's extent in both directions (3, or 1 for 1 x 1 filters).
+template <int TW, int TH, int BRS = 3>
 struct F32Direct16 {
-    static constexpr int TB = 8, KT = 64, CWAVES = 4, CT = 16, BS = 3, BR = 3, NBLK = TH, TW_ = TW, TH_ = TH;
+    static constexpr int TB = 8, KT = 64, CWAVES = 4, CT = 16, BS = BRS, BR = BRS, NBLK = TH, TW_ = TW, TH_ = TH;
     static constexpr int XS = TW + BR - 1, YS = TH - 1 + BS, YSL = YS + (YS & 1);
     static constexpr int POS = CT * TB * 4;                         // bytes of one (x, y) position
     static constexpr int XP = YSL * POS + 32;                       // bytes of one x plane
@@ -2612,9 +2613,9 @@ struct F32Direct16 {
     }
 };
 
-template <int TW, int TH>
+template <int TW, int TH, int BRS = 3>
 __global__ void __launch_bounds__(512) conv_f32_direct16_kernel(const KernelArgs a) {
-    using GEO = F32Direct16<TW, TH>;
+    using GEO = F32Direct16<TW, TH, BRS>;
     constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, NBLK = GEO::NBLK;
     constexpr int YS = GEO::YS, XP = GEO::XP, POS = GEO::POS, FP = GEO::FP;
     constexpr int IBUF = GEO::IMG_BYTES, FBUF = GEO::FLT_BYTES;
@@ -3037,6 +3038,18 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
+// the same for 1 x 1 filters
+#define CACNN_F32_DIRECT16_1X1_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                         \
+    {                                                                                                          \
+        {NAME, 0, 2, 2, 1, F32Direct16<TW, TH, 1>::NBLK, 8, TW, TH, 2, 1, F32Direct16<TW, TH, 1>::MAXF, 1, -4, 1.0f, 16, 1,    \
+         1, F32Direct16<TW, TH, 1>::YS, 1, 1, F32Direct16<TW, TH, 1>::LDS_BYTES, UNIT_US, FIXED_US, 0},         \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                if (!F32Direct16<TW, TH, 1>::matches_host(a) || lds != (size_t)F32Direct16<TW, TH, 1>::LDS_BYTES) return 1; \
+                return launch_kernel(conv_f32_direct16_kernel<TW, TH, 1>, attr_done, 512, a, grid, lds, stream); \
+            }                                                                                                  \
+    }
+
 static const Variant g_variants[] = {
     // fp32
     CACNN_VARIANT(0, conv_f32_kernel, "f32 k32 b1w16h16 w1x4 m1n2", 1, 4, 1, 2, 1, 16, 16),
@@ -3095,6 +3108,7 @@ static const Variant g_variants[] = {
     // fixed-geometry kernels (3x3 taps, unit strides, shapes the tiles divide exactly)
     CACNN_F32_DIRECT_VARIANT("f32 fxd k64 b8w4h4 w2x2 m1n2 c16r3s3", 4.4f, 3.0f, 4, 4),
     CACNN_F32_DIRECT16_VARIANT("f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r3s3", 4.1f, 2.6f, 2, 7),
+    CACNN_F32_DIRECT16_1X1_VARIANT("f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r1s1", 0.50f, 2.6f, 2, 7),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.0f, 4.5f, 7, 1),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.62f, 4.2f, 2, 2),
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1", 0.50f, 4.5f, 7, 1),

@@ -73,6 +73,7 @@ RAGGED = [
     # the fp32 kernel with 16x16 blocks (tiles of 8 images x 2 x 7 positions): two tiles in every dimension and two
     # c-slices; a taller filter with more tiles than workgroups
     ("fx16_two_each", 16, 32, 128, 4, 14, 3, 3, 1, 1),
+    ("fx16_1x1", 8, 48, 64, 4, 14, 1, 1, 1, 1),
     ("fx16_many_tiles_s6", 8, 16, 64, 46, 42, 3, 6, 1, 1),
     # the stem-layer kernel: 7x7 taps, strides 2, three channels; more tiles than workgroups and three k-tiles, so a
     # workgroup walks several tiles and restages its Filter tile
@@ -90,7 +91,7 @@ def variants_for(cc, dtype):
 
 
 # the forced contraction tiles; the last two are the ones the fixed-geometry kernels are compiled for
-FORCED_TILES = {"f32": ((1 << 20, 1 << 20, 1 << 20), (3, 2, 1), (16, 3, 3), (32, 3, 1)),
+FORCED_TILES = {"f32": ((1 << 20, 1 << 20, 1 << 20), (3, 2, 1), (16, 3, 3), (32, 3, 1), (16, 1, 1)),
                 "bf16": ((1 << 20, 1 << 20, 1 << 20), (16, 2, 1), (16, 3, 3), (32, 3, 1), (32, 3, 3), (32, 1, 1))}
 
 
@@ -144,7 +145,7 @@ def test_every_variant_runs_on_some_ragged_shape(env, dtype):
     fixed-geometry family) every variant launches at least once, the generic ones with at least two tilings."""
     cc, torch = env
     ran = {}
-    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_w2h2", "fx_w4h4", "fx16_two_each", "fx_stem")
+    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_w2h2", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx_stem")
     for shape in RAGGED:
         if shape[0] in pick:
             run_every_variant(cc, torch, shape, dtype, ran)
