@@ -472,7 +472,8 @@ def pooling_report(cc, torch, ci, np, steps, warmup, with_cpu):
     return rep
 
 
-# Mid-size and ragged layers that no fixed-geometry kernel takes: (dtype, B, C, K, W, H, R, S, sigma_w, sigma_h)
+# Mid-size and ragged layers outside the benchmark shapes' own kernels (two of the bf16 ones with 32 images are taken by the
+# 32-image fixed-geometry kernels, the others by generic kernels): (dtype, B, C, K, W, H, R, S, sigma_w, sigma_h)
 PLANNER_SHAPES = [
     ("bf16", 32, 1024, 256, 14, 14, 1, 1, 1, 1), ("bf16", 32, 512, 512, 7, 7, 3, 3, 1, 1), ("bf16", 32, 64, 64, 56, 56, 3, 3, 1, 1),
     ("bf16", 16, 128, 128, 28, 28, 3, 3, 1, 1), ("bf16", 40, 96, 200, 13, 11, 3, 3, 1, 1), ("bf16", 24, 48, 96, 27, 27, 5, 5, 2, 2),
@@ -542,12 +543,15 @@ def planner_sweep(cc, torch, ci, np, shapes):
         print(f"fit | {family} | {' '.join(f'{c:.4g}' for c in x)} | {float(np.sqrt(np.mean(err ** 2))):.3f} | {len(A)}")
 
 
-# 1 x 1 layers that the fixed-geometry kernels for 1 x 1 filters take (bf16: 64 or more images; fp32: 8 or more, rows in sevens)
+# layers that the fixed-geometry kernels added for 1 x 1 filters and for 32-image tiles take (beside the benchmark shapes' own)
 ONE_BY_ONE_SHAPES = [
     ("f32", 8, 256, 256, 14, 14, 1, 1, 1, 1), ("f32", 32, 512, 128, 28, 28, 1, 1, 1, 1), ("f32", 16, 64, 256, 56, 56, 1, 1, 1, 1),
     ("f32", 64, 1024, 256, 14, 14, 1, 1, 1, 1),
     ("bf16", 64, 1024, 256, 14, 14, 1, 1, 1, 1), ("bf16", 128, 256, 512, 7, 7, 1, 1, 1, 1), ("bf16", 64, 512, 2048, 7, 7, 1, 1, 1, 1),
     ("bf16", 64, 64, 256, 56, 56, 1, 1, 1, 1), ("bf16", 256, 2048, 512, 7, 7, 1, 1, 1, 1),
+    # 32 images (or a multiple that is not one of 64): the fixed-geometry bf16 kernels with 32-image tiles take these
+    ("bf16", 32, 128, 128, 56, 56, 3, 3, 1, 1), ("bf16", 32, 512, 512, 14, 14, 3, 3, 1, 1), ("bf16", 96, 128, 128, 28, 28, 3, 3, 1, 1),
+    ("bf16", 32, 256, 256, 28, 28, 3, 3, 1, 1), ("bf16", 32, 256, 1024, 14, 14, 1, 1, 1, 1),
 ]
 
 

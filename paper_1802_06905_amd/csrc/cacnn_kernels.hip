@@ -1868,9 +1868,14 @@ struct FxWalk {
 // see them (their operands are still tracked: the store waits for its own Filter load).
 // BRP: the filter's extent along w the kernel is compiled for (3, or 1 for 1 x 1 filters, where a unit is a plain
 // matrix product of the Filter tile with the tile's positions).
-template <int TW, int TH, int BRP = 3>
+// TBP: images per tile, 64 or 32.  With 64 a wave column (wn) takes one half of the images and all TW x TH positions; with
+// 32 a row of the tile is 64 bytes, a column block is all 32 images of one position, the tile is two rows high and wave
+// column wn takes row wn.
+template <int TW, int TH, int BRP = 3, int TBP = 64>
 struct Bf16DirectFixed {
-    static constexpr int TB = 64, KT = 64, WM = 2, WN = 2, CT = 32, BS = 1, BR = BRP, NBLK = TW * TH;
+    static constexpr int TB = TBP, KT = 64, WM = 2, WN = 2, CT = 32, BS = 1, BR = BRP;
+    static constexpr int THW = TBP == 64 ? TH : 1;                  // tile rows one wave works on
+    static constexpr int NBLK = TW * THW;                           // column blocks per wave
     static constexpr int C8 = CT / 8, STEPS = BS * (CT / 16);
     static constexpr int XS = TW + BR - 1, YS = TH - 1 + BS;
     static constexpr int ROW = TB * 2;                              // bytes of one (x, y, c) row
@@ -1879,10 +1884,12 @@ struct Bf16DirectFixed {
     static constexpr int FLT_BYTES = KT * F8 * 16;
     static constexpr int BUF_BYTES = IMG_BYTES + FLT_BYTES, NBUF = 3, LDS_BYTES = NBUF * BUF_BYTES;
     static constexpr int PT = 256, PW = PT / 64;                    // staging threads, staging waves
-    static constexpr int CPW = XS * YS;                             // 1 KiB Image chunks per unit and staging wave
+    static constexpr int CPW = IMG_BYTES / 1024 / PW;               // 1 KiB Image chunks per unit and staging wave
     static constexpr int FLT_ITEMS = KT * BR * BS * C8, MAXF = FLT_ITEMS / PT, MAXI = 1;
     static constexpr int LOADS = CPW + MAXF;                        // loads one staging wave issues per unit
-    static_assert(C8 == PW, "direct bf16 geometry: staging wave p loads channels 8p..8p+7 of every (x, y)");
+    static_assert(TBP == 64 || (TBP == 32 && TH == 2), "direct bf16 geometry: 64 images, or 32 images and two rows");
+    static_assert(IMG_BYTES % (1024 * PW) == 0, "direct bf16 geometry: whole chunks per staging wave");
+    static_assert(C8 == PW, "direct bf16 geometry: chunk 4 i + p of a unit is staging wave p's i-th");
     static_assert(FLT_ITEMS % PT == 0, "direct bf16 geometry: whole Filter items per thread");
     static_assert(BUF_BYTES < 65536 && LDS_BYTES <= 160 * 1024, "direct bf16 geometry: LDS offsets and size");
     static_assert(STEPS == 2 && 2 * LOADS < 64, "direct bf16 geometry: two steps per unit, load counter range");
@@ -1974,9 +1981,9 @@ __device__ __forceinline__ void load_16_bytes_per_lane_to_lds(__amdgpu_buffer_rs
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (CACNN_LDS(void)*)dst, 16, voff, soff, 0, 0);
 }
 
-template <int TW, int TH, int BRP = 3>
+template <int TW, int TH, int BRP = 3, int TBP = 64>
 __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs a) {
-    using GEO = Bf16DirectFixed<TW, TH, BRP>;
+    using GEO = Bf16DirectFixed<TW, TH, BRP, TBP>;
     constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, BR = GEO::BR, WM = GEO::WM, NBLK = GEO::NBLK;
     constexpr int XS = GEO::XS, YS = GEO::YS, C8 = GEO::C8, F8 = GEO::F8, ROW = GEO::ROW, BUF = GEO::BUF_BYTES;
     constexpr int CTHREADS = GEO::WM * GEO::WN * 64;
@@ -1995,11 +2002,20 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
         constexpr int MAXF = GEO::MAXF, CPW = GEO::CPW, PT = GEO::PT;
         // Image: lane L of a chunk load fetches channel row L / 8 of the chunk, 16-byte piece (L % 8) ^ 4 * (bit 1 of the row)
         const uint32_t row_bytes = (uint32_t)a.B * 2u;
-        const uint32_t ivoff = (uint32_t)(lane >> 3) * row_bytes + (uint32_t)(((lane & 7) ^ (((lane >> 4) & 1) << 2)) * 16);
+        // (32 images: a chunk is 16 rows of 64 bytes, lane L fetches piece L % 4 of row L / 4, and chunk 4 i + p of a unit
+        // is half (4 i + p) % 2 of position (4 i + p) / 2)
+        const uint32_t ivoff = TB == 64 ? (uint32_t)(lane >> 3) * row_bytes + (uint32_t)(((lane & 7) ^ (((lane >> 4) & 1) << 2)) * 16)
+                                        : (uint32_t)(lane >> 2) * row_bytes + (uint32_t)((lane & 3) * 16);
         uint32_t isoff[CPW];
 #pragma unroll
-        for (int i = 0; i < CPW; ++i)
-            isoff[i] = (uint32_t)(((i / YS) * a.IH + (i % YS)) * a.C + pw * 8) * row_bytes;
+        for (int i = 0; i < CPW; ++i) {
+            if constexpr (TB == 64) {
+                isoff[i] = (uint32_t)(((i / YS) * a.IH + (i % YS)) * a.C + pw * 8) * row_bytes;
+            } else {
+                const int c = 4 * i + pw, xy = c >> 1;
+                isoff[i] = (uint32_t)(((xy / YS) * a.IH + (xy % YS)) * a.C + 16 * (c & 1)) * row_bytes;
+            }
+        }
         // Filter: thread (kl = stid / C8, c8 = stid % C8) fetches the 16 bytes of channels 8*c8.. of output channel kl
         // for every tap (r, s) of the unit: one global offset and one LDS address per thread, the tap in the
         // instruction (scalar offset of the load, immediate of the store)
@@ -2050,16 +2066,18 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
         // per-lane LDS offsets inside a buffer: Filter row of output channel wm*32 + j, contraction half g;
         // Image: row 8g + i16/4 of a 16-channel step, the 8 bytes that hold images 4*(i16 % 4).. of this lane group
         const uint32_t al = (uint32_t)(GEO::IMG_BYTES + ((wm * 32 + j) * F8 + g) * 16);
-        const int q = wn * 4 + 2 * jhalf + ((i16 & 3) >> 1);
-        const uint32_t xl = (uint32_t)((8 * g + (i16 >> 2)) * ROW + ((q ^ (((i16 >> 3) & 1) << 2)) * 16) + (i16 & 1) * 8);
-        bf16x8 A[2][BR], X[2][TH][XS];
+        constexpr int THW = GEO::THW;
+        const int q = (TB == 64 ? wn * 4 : 0) + 2 * jhalf + ((i16 & 3) >> 1);
+        const uint32_t xl = TB == 64 ? (uint32_t)((8 * g + (i16 >> 2)) * ROW + ((q ^ (((i16 >> 3) & 1) << 2)) * 16) + (i16 & 1) * 8)
+                                     : (uint32_t)((wn * CT + 8 * g + (i16 >> 2)) * ROW + q * 16 + (i16 & 1) * 8);
+        bf16x8 A[2][BR], X[2][THW][XS];
         auto load_step = [&](uint32_t ab, uint32_t xb, int t, int set) {
             const int sl = t / (CT / 16), cs = t % (CT / 16);
 #pragma unroll
             for (int r = 0; r < BR; ++r)
                 A[set][r] = *(const CACNN_LDS(bf16x8)*)(lds + ab + ((r * BS + sl) * C8 + 2 * cs) * 16);
 #pragma unroll
-            for (int h = 0; h < TH; ++h)
+            for (int h = 0; h < THW; ++h)
 #pragma unroll
                 for (int x = 0; x < XS; ++x) {
                     CACNN_LDS(char)* const p = lds + xb + ((x * YS + h + sl) * CT + 16 * cs) * ROW;
@@ -2072,14 +2090,14 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
 #pragma unroll
             for (int r = 0; r < BR; ++r)
 #pragma unroll
-                for (int h = 0; h < TH; ++h)
+                for (int h = 0; h < THW; ++h)
 #pragma unroll
                     for (int w = 0; w < TW; ++w)
                         acc[0][h * TW + w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[set][r], X[set][h][w + r],
                                                                                      acc[0][h * TW + w], 0, 0, 0);
         };
         const int64_t out_kstride = (int64_t)a.H * a.W * a.B;      // floats between output channels
-        const uint32_t out_lane = (uint32_t)(g * 4) * (uint32_t)out_kstride + (uint32_t)(32 * wn + j);
+        const uint32_t out_lane = (uint32_t)(g * 4) * (uint32_t)out_kstride + (uint32_t)((TB == 64 ? 32 * wn : 0) + j);
         int left = total, in_tile = upt, t = blockIdx.x;
         uint32_t boff = 0;
         // one unit; MORE: another one follows (its buffer is the next of the three)
@@ -2087,7 +2105,7 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
             constexpr bool MORE = decltype(more)::value;
             load_step(al + boff, xl + boff, 1, 1);
             mfma_step(0);
-            interleave_front_hint<BR * NBLK, 2 * TH * XS + BR, 2>();
+            interleave_front_hint<BR * NBLK, 2 * THW * XS + BR, 2>();
             if constexpr (MORE) {
                 // hand the buffer back once the last fragments have landed, read the next unit's first fragments
                 // under this step's MFMAs
@@ -2096,7 +2114,7 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
                 load_step(al + boff, xl + boff, 0, 0);
             }
             mfma_step(1);
-            if constexpr (MORE) interleave_front_hint<BR * NBLK, 2 * TH * XS + BR, 2>();
+            if constexpr (MORE) interleave_front_hint<BR * NBLK, 2 * THW * XS + BR, 2>();
             // keep the reads above where they are: left alone, the compiler sinks them to the top of the next
             // unit, in front of the MFMAs that need them
             asm volatile("" ::: "memory");
@@ -2105,7 +2123,8 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
                 const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
 #pragma unroll
                 for (int n = 0; n < NBLK; ++n) {
-                    float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + tc.h0 + n / TW) * a.W + tc.w0 + n % TW) * a.B + tc.b0);
+                    const int hrow = TB == 64 ? n / TW : wn;
+                    float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + tc.h0 + hrow) * a.W + tc.w0 + n % TW) * a.B + tc.b0);
                     store_block_exact<true>(blk, out_kstride, out_lane, acc[0][n]);
                 }
                 in_tile = upt;
@@ -2990,6 +3009,18 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
+// the same with 32 images per tile (two rows of TW positions), for 3 x 3 (BR = 3) or 1 x 1 (BR = 1) filters
+#define CACNN_DIRECT_B32_VARIANT(NAME, UNIT_US, FIXED_US, TW, BR)                                               \
+    {                                                                                                          \
+        {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, 2, BR, 32>::NBLK, 32, TW, 2, 2, 1, Bf16DirectFixed<TW, 2, BR, 32>::MAXF, 1, BR, 1.0f, 32, BR,  \
+         1, Bf16DirectFixed<TW, 2, BR, 32>::YS, 1, 1, Bf16DirectFixed<TW, 2, BR, 32>::LDS_BYTES, UNIT_US, FIXED_US, 0},  \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                if (!Bf16DirectFixed<TW, 2, BR, 32>::matches_host(a) || lds != (size_t)Bf16DirectFixed<TW, 2, BR, 32>::LDS_BYTES) return 1; \
+                return launch_kernel(conv_bf16_direct_kernel<TW, 2, BR, 32>, attr_done, 512, a, grid, lds, stream); \
+            }                                                                                                  \
+    }
+
 // the same for 1 x 1 filters
 #define CACNN_DIRECT_1X1_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                               \
     {                                                                                                          \
@@ -3113,6 +3144,8 @@ static const Variant g_variants[] = {
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.62f, 4.2f, 2, 2),
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1", 0.50f, 4.5f, 7, 1),
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1", 0.30f, 4.2f, 2, 2),
+    CACNN_DIRECT_B32_VARIANT("bf16 fxd k64 b32w7h2 w2x2 m1n7 c32r3s1", 1.1f, 4.5f, 7, 3),
+    CACNN_DIRECT_B32_VARIANT("bf16 fxd k64 b32w7h2 w2x2 m1n7 c32r1s1", 0.6f, 4.5f, 7, 1),
     CACNN_STAGED_VARIANT("bf16 fxr k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.1f, 4.5f, 7, 1, 1),
     CACNN_STAGED_VARIANT("bf16 fxr k64 b64w2h2 w2x2 m1n4 c32r3s3", 2.0f, 4.2f, 2, 2, 3),
     // fixed geometry for the stem-layer shape: 7x7 taps, strides 2, three channels

@@ -64,6 +64,8 @@ RAGGED = [
     # shapes the fixed-geometry kernels tile exactly (3x3 taps, unit strides), several tiles and several c-slices
     ("fx_w7", 128, 64, 128, 7, 3, 3, 3, 1, 1),
     ("fx_1x1", 64, 96, 128, 14, 4, 1, 1, 1, 1),
+    ("fx_b32", 96, 64, 128, 7, 6, 3, 3, 1, 1),
+    ("fx_b32_1x1", 32, 96, 64, 14, 2, 1, 1, 1, 1),
     ("fx_w2h2", 64, 96, 192, 4, 6, 3, 3, 1, 1),
     ("fx_w4h4", 64, 32, 128, 8, 12, 3, 3, 1, 1),
     # more tiles than workgroups (a workgroup walks several tiles), and a filter taller than the fixed b_s
@@ -145,7 +147,7 @@ def test_every_variant_runs_on_some_ragged_shape(env, dtype):
     fixed-geometry family) every variant launches at least once, the generic ones with at least two tilings."""
     cc, torch = env
     ran = {}
-    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_w2h2", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx_stem")
+    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx_stem")
     for shape in RAGGED:
         if shape[0] in pick:
             run_every_variant(cc, torch, shape, dtype, ran)
