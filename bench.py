@@ -147,6 +147,22 @@ def machine_sustained(cc, torch, ci, np):
                             ("unit_mix_c4_mfma_alone_ns", (1143, 0))):
         sec = timed(lambda: cc.cacnn_probe_mfma_and_fill(ops, src, 2 << 20, sink, mi, fi), 3, 10)
         out[label] = sec / n * 1e9
+    # the same mixes on as many compute units as the two bf16 shapes have tiles (the others idle), and on half of them:
+    # how a unit's time depends on how many compute units work at once; and with the MFMA waves reading their operands
+    # from the LDS being filled (a window of N(0,1) bf16 words, so that the operands toggle as the register-only loop's do)
+    win = torch.from_numpy(np.ascontiguousarray(ci.bf16_bits(ci.round_to_bf16(rng.standard_normal(1 << 20).astype(np.float32)))
+                                                .view(np.int16))).cuda()
+    for label, cus, reads, (mi, fi) in (("unit_mix_side_by_side_224_cus_ns", 224, 0, (n, n)),
+                                        ("unit_mix_side_by_side_128_cus_ns", 128, 0, (n, n)),
+                                        ("unit_mix_mfma_alone_224_cus_ns", 224, 0, (n, 0)),
+                                        ("unit_mix_mfma_alone_128_cus_ns", 128, 0, (n, 0)),
+                                        ("unit_mix_with_lds_reads_224_cus_ns", 224, 1, (n, n)),
+                                        ("unit_mix_with_lds_reads_256_cus_ns", 256, 1, (n, n)),
+                                        ("unit_mix_mfma_with_lds_reads_no_fill_224_cus_ns", 224, 1, (n, 0)),
+                                        ("unit_mix_c4_side_by_side_196_cus_ns", 196, 0, (1143, 1875)),
+                                        ("unit_mix_c4_side_by_side_128_cus_ns", 128, 0, (1143, 1875))):
+        sec = timed(lambda: cc.cacnn_probe_mfma_and_fill_on(cus, reads, ops, win, 2 << 20, sink, mi, fi), 3, 10)
+        out[label] = sec / n * 1e9
     del src, dst
     return out
 
@@ -293,9 +309,10 @@ def alternative_variants_us(cc, torch, cfg, buffers, steps, warmup):
 
 def add_unit_mix(rep, cfg, sustained):
     """For c4 and c5: the units a workgroup runs (Out tiles per workgroup x c-slices x filter rows) times what the machine
-    takes for one unit's MFMAs and bytes side by side with nothing synchronising them (machine_sustained): the time the
-    launch's loop would take at that rate, without the start and the end of a launch."""
-    key = {"c5": "unit_mix_side_by_side_ns", "c4": "unit_mix_c4_side_by_side_ns"}.get(cfg.name)
+    takes for one unit's MFMAs and bytes side by side with nothing synchronising them, on as many compute units as the
+    shape has tiles (machine_sustained; for c5 with the operands read from the LDS as the kernel reads them): the time
+    the launch's loop would take at that rate, without the start and the end of a launch."""
+    key = {"c5": "unit_mix_with_lds_reads_224_cus_ns", "c4": "unit_mix_c4_side_by_side_196_cus_ns"}.get(cfg.name)
     if key is None or key not in sustained:
         return
     units = (cfg.C // 32) * cfg.S            # one tile per workgroup on both shapes

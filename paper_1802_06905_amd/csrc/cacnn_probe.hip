@@ -101,14 +101,26 @@ __global__ void __launch_bounds__(256) lds_fill_kernel(const char* src, uint32_t
     sink[blockIdx.x * 256 + threadIdx.x] = (float)(unsigned char)lds[threadIdx.x * 16];
 }
 
-// Both at once, in the proportions of the bf16 convolution's unit: waves 0-3 of a workgroup of eight run the register-only
-// bf16 MFMA loop (42 MFMAs per iteration and wave), waves 4-7 the LDS fill from a shared window (12 KiB per iteration and
-// wave).  Either count may be zero.  What the two cost each other when nothing synchronises them.
+// Both at once, in the proportions of the bf16 convolution's unit: waves 0-3 of a workgroup of eight run the bf16 MFMA
+// loop (42 MFMAs per iteration and wave), waves 4-7 the LDS fill from a shared window (12 KiB per iteration and wave).
+// Either count may be zero.  What the two cost each other when nothing synchronises them.
+// lds_reads = 0: the MFMA loop is register-only.  1: before every 21 MFMAs a wave reads its 3 + 9 operand fragments from
+// the LDS the other waves are filling, with the instructions, the addresses and the bank pattern of the convolution
+// kernel's multiplying waves (3 16-byte reads of a Filter row, 18 transposing 8-byte reads of Image rows, laid out as
+// one buffer of that kernel: 36 KiB of Image rows of 128 bytes, then 64 Filter rows of 13 x 16 bytes); still no barrier
+// and no dependence between the two kinds of waves.
+typedef short pr_s16x4 __attribute__((ext_vector_type(4)));
+#define CACNN_PROBE_LDS(T) __attribute__((address_space(3))) T
 __global__ void __launch_bounds__(512) mfma_and_fill_kernel(const uint32_t* operands, const char* src, uint32_t window,
-                                                            int mfma_iters, int fill_iters, float* sink) {
-    __shared__ __align__(16) char lds[4 * 12 * 1024];
+                                                            int mfma_iters, int fill_iters, int lds_reads, float* sink) {
+    __shared__ __align__(16) char lds[50 * 1024];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     float result = 0.f;
+    if (lds_reads) {
+        // what is read before the first fill arrives, and the end of the Filter rows, which no fill reaches
+        for (int i = threadIdx.x; i < (int)sizeof(lds) / 16; i += 512) ((pr_u32x4*)lds)[i] = pr_u32x4{0u, 0u, 0u, 0u};
+        __syncthreads();
+    }
     if (wave < 4) {
         pr_f32x16 acc[7];
 #pragma unroll
@@ -121,12 +133,47 @@ __global__ void __launch_bounds__(512) mfma_and_fill_kernel(const uint32_t* oper
         for (int r = 0; r < 3; ++r) A[r] = __builtin_bit_cast(pr_bf16x8, op[(lane + 64 * r) & 1023]);
 #pragma unroll
         for (int x = 0; x < 9; ++x) X[x] = __builtin_bit_cast(pr_bf16x8, op[(lane + 64 * (3 + x)) & 1023]);
-        for (int it = 0; it < 2 * mfma_iters; ++it) {
+        if (!lds_reads) {
+            for (int it = 0; it < 2 * mfma_iters; ++it) {
 #pragma unroll
-            for (int r = 0; r < 3; ++r)
+                for (int r = 0; r < 3; ++r)
 #pragma unroll
-                for (int w = 0; w < 7; ++w)
-                    acc[w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[r], X[w + r], acc[w], 0, 0, 0);
+                    for (int w = 0; w < 7; ++w)
+                        acc[w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[r], X[w + r], acc[w], 0, 0, 0);
+            }
+        } else {
+            // the multiplying waves' lane offsets (wave = wm + 2 wn; rows of 128 bytes, halves of rows with bit 1 of the
+            // channel set exchanged; Filter rows of 13 x 16 bytes behind 36 KiB of Image rows)
+            const int wm = wave & 1, wn = wave >> 1;
+            const int j = lane & 31, g = lane >> 5, i16 = lane & 15, jhalf = (lane >> 4) & 1;
+            const int q = wn * 4 + 2 * jhalf + ((i16 & 3) >> 1);
+            const uint32_t al = (uint32_t)(36864 + ((wm * 32 + j) * 13 + g) * 16);
+            const uint32_t xl = (uint32_t)((8 * g + (i16 >> 2)) * 128 + ((q ^ (((i16 >> 3) & 1) << 2)) * 16) + (i16 & 1) * 8);
+            CACNN_PROBE_LDS(char)* const l3 = (CACNN_PROBE_LDS(char)*)lds;
+            for (int it = 0; it < 2 * mfma_iters; ++it) {
+                const int cs = it & 1;
+                pr_bf16x8 An[3], Xn[9];
+#pragma unroll
+                for (int r = 0; r < 3; ++r) An[r] = *(const CACNN_PROBE_LDS(pr_bf16x8)*)(l3 + al + (r * 4 + 2 * cs) * 16);
+#pragma unroll
+                for (int x = 0; x < 9; ++x) {
+                    CACNN_PROBE_LDS(char)* const p = l3 + xl + (x * 32 + 16 * cs) * 128;
+                    const pr_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CACNN_PROBE_LDS(pr_s16x4)*)p);
+                    const pr_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CACNN_PROBE_LDS(pr_s16x4)*)(p + 4 * 128));
+                    Xn[x] = __builtin_bit_cast(pr_bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                }
+                // this step's MFMAs run on the fragments read during the last step, under these reads
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+#pragma unroll
+                    for (int w = 0; w < 7; ++w)
+                        acc[w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[r], X[w + r], acc[w], 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 3; ++r) A[r] = An[r];
+#pragma unroll
+                for (int x = 0; x < 9; ++x) X[x] = Xn[x];
+                asm volatile("" ::: "memory");      // the LDS changes under the reads: every step reads again
+            }
         }
 #pragma unroll
         for (int n = 0; n < 7; ++n)
@@ -152,9 +199,20 @@ __global__ void __launch_bounds__(512) mfma_and_fill_kernel(const uint32_t* oper
 }
 
 int launch_mfma_and_fill_probe(const void* operands, const void* src, uint32_t window, int mfma_iters, int fill_iters,
-                               float* sink, int grid, void* stream) {
-    hipLaunchKernelGGL(mfma_and_fill_kernel, dim3(grid), dim3(512), 0, (hipStream_t)stream, (const uint32_t*)operands,
-                       (const char*)src, window, mfma_iters, fill_iters, sink);
+                               int lds_reads, float* sink, int grid, void* stream) {
+    // 46 KiB of unused dynamic LDS on top of the kernel's own 50 KiB: no second workgroup fits the compute unit, so a
+    // grid below the CU count leaves exactly that many compute units idle
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void*)mfma_and_fill_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 46 * 1024) !=
+            hipSuccess) {
+            (void)hipGetLastError();
+            return 1;
+        }
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(mfma_and_fill_kernel, dim3(grid), dim3(512), 46 * 1024, (hipStream_t)stream, (const uint32_t*)operands,
+                       (const char*)src, window, mfma_iters, fill_iters, lds_reads, sink);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

@@ -103,3 +103,32 @@ def test_mfma_and_fill_probe_sums_and_refuses(env):
     for window, mi, fi in ((3 << 20, 1, 1), (2 << 20, 0, 0), (2 << 20, -1, 1), (64 << 20, 1, 1)):
         with pytest.raises((cc.CacnnError, ValueError)):
             cc.cacnn_probe_mfma_and_fill(ops, torch.zeros(64 << 20, dtype=torch.uint8, device="cuda:0"), window, sink, mi, fi)
+
+
+def test_mfma_and_fill_probe_on_some_compute_units(env):
+    """With fewer workgroups than compute units the probe writes exactly that many workgroups' sums and refuses counts
+    outside 1 .. 256."""
+    cc, torch = env
+    ops = torch.from_numpy(np.full(4096, np.int32(0x3f803f80), dtype=np.int32)).cuda()
+    src = torch.zeros(2 << 20, dtype=torch.uint8, device="cuda:0")
+    iters = 3
+    for cus in (1, 196, 224):
+        sink = torch.zeros(65536, dtype=torch.float32, device="cuda:0")
+        cc.cacnn_probe_mfma_and_fill_on(cus, 0, ops, src, 2 << 20, sink, iters, 2)
+        torch.cuda.synchronize()
+        got = sink.reshape(256, 256)
+        assert torch.all(got[:cus] == float(7 * 16 * 3 * 2 * iters * 16))
+        assert float(got[cus:].abs().sum()) == 0.0
+    for cus in (0, 257, -1):
+        with pytest.raises(cc.CacnnError):
+            cc.cacnn_probe_mfma_and_fill_on(cus, 0, ops, src, 2 << 20, sink, 1, 1)
+    # operands read from the LDS: with a window of bf16 ones every fragment is ones once the fills have landed, and zeros
+    # before; the sums are then whole numbers between 0 and the register-only figure
+    ones = torch.from_numpy(np.full(1 << 19, np.int32(0x3f803f80), dtype=np.int32)).cuda()
+    sink = torch.zeros(65536, dtype=torch.float32, device="cuda:0")
+    cc.cacnn_probe_mfma_and_fill_on(224, 1, ops, ones, 2 << 20, sink, 8, 8)
+    torch.cuda.synchronize()
+    got = sink.reshape(256, 256)[:224]
+    assert torch.all(got == got.round()) and float(got.min()) >= 0.0 and float(got.max()) <= float(7 * 16 * 3 * 2 * 8 * 16)
+    with pytest.raises(cc.CacnnError):
+        cc.cacnn_probe_mfma_and_fill_on(224, 2, ops, src, 2 << 20, sink, 1, 1)
