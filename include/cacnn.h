@@ -284,8 +284,8 @@ int cacnn_pool_forward(const cacnn_problem* problem, int dtype, int mode, const 
  * idle): what a compute unit's rate is when fewer of them work, i.e. how much of the rate is the whole chip's (its
  * power-managed clock) and how much the compute unit's own.  lds_reads = 1: the MFMA wavefronts read their operand
  * fragments from the LDS that the others are filling, before every 21 MFMAs, with the instructions and the addresses of the
- * bf16 convolution kernel's multiplying wavefronts (3 16-byte and 18 transposing 8-byte reads); sink then holds sums of
- * whatever the LDS held.  lds_reads = 0: register-only MFMA loop, as cacnn_probe_mfma_and_fill.
+ * bf16 convolution kernel's multiplying wavefronts (3 16-byte and 18 transposing 8-byte reads); the LDS starts
+ * out as copies of the operand words.  lds_reads = 0: register-only MFMA loop, as cacnn_probe_mfma_and_fill.
  * All of them enqueue on hip_stream and return; they never synchronise and allocate nothing.  The caller times them.
  * Errors: CACNN_ERR_NULL, CACNN_ERR_INVALID_ARG (alignment, sizes, iters), CACNN_ERR_UNSUPPORTED (dtype),
  * CACNN_ERR_NO_DEVICE, CACNN_ERR_LAUNCH.

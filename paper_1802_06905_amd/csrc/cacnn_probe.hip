@@ -117,8 +117,9 @@ __global__ void __launch_bounds__(512) mfma_and_fill_kernel(const uint32_t* oper
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     float result = 0.f;
     if (lds_reads) {
-        // what is read before the first fill arrives, and the end of the Filter rows, which no fill reaches
-        for (int i = threadIdx.x; i < (int)sizeof(lds) / 16; i += 512) ((pr_u32x4*)lds)[i] = pr_u32x4{0u, 0u, 0u, 0u};
+        // what is read before the first fill arrives (or all the time, without a fill), and the end of the Filter rows,
+        // which no fill reaches: the operand words, over and over
+        for (int i = threadIdx.x; i < (int)sizeof(lds) / 16; i += 512) ((pr_u32x4*)lds)[i] = ((const pr_u32x4*)operands)[i & 1023];
         __syncthreads();
     }
     if (wave < 4) {

@@ -122,13 +122,13 @@ def test_mfma_and_fill_probe_on_some_compute_units(env):
     for cus in (0, 257, -1):
         with pytest.raises(cc.CacnnError):
             cc.cacnn_probe_mfma_and_fill_on(cus, 0, ops, src, 2 << 20, sink, 1, 1)
-    # operands read from the LDS: with a window of bf16 ones every fragment is ones once the fills have landed, and zeros
-    # before; the sums are then whole numbers between 0 and the register-only figure
+    # operands read from the LDS: it starts out as copies of the operand words (bf16 ones) and a window of bf16 ones is
+    # filled in, so every fragment read is ones and the sums are the register-only figure, with the fill and without
     ones = torch.from_numpy(np.full(1 << 19, np.int32(0x3f803f80), dtype=np.int32)).cuda()
-    sink = torch.zeros(65536, dtype=torch.float32, device="cuda:0")
-    cc.cacnn_probe_mfma_and_fill_on(224, 1, ops, ones, 2 << 20, sink, 8, 8)
-    torch.cuda.synchronize()
-    got = sink.reshape(256, 256)[:224]
-    assert torch.all(got == got.round()) and float(got.min()) >= 0.0 and float(got.max()) <= float(7 * 16 * 3 * 2 * 8 * 16)
+    for fill in (8, 0):
+        sink = torch.zeros(65536, dtype=torch.float32, device="cuda:0")
+        cc.cacnn_probe_mfma_and_fill_on(224, 1, ops, ones, 2 << 20, sink, 8, fill)
+        torch.cuda.synchronize()
+        assert torch.all(sink.reshape(256, 256)[:224] == float(7 * 16 * 3 * 2 * 8 * 16))
     with pytest.raises(cc.CacnnError):
         cc.cacnn_probe_mfma_and_fill_on(224, 2, ops, src, 2 << 20, sink, 1, 1)
