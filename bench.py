@@ -152,16 +152,22 @@ def machine_sustained(cc, torch, ci, np):
     # from the LDS being filled (a window of N(0,1) bf16 words, so that the operands toggle as the register-only loop's do)
     win = torch.from_numpy(np.ascontiguousarray(ci.bf16_bits(ci.round_to_bf16(rng.standard_normal(1 << 20).astype(np.float32)))
                                                 .view(np.int16))).cuda()
-    for label, cus, reads, (mi, fi) in (("unit_mix_side_by_side_224_cus_ns", 224, 0, (n, n)),
-                                        ("unit_mix_side_by_side_128_cus_ns", 128, 0, (n, n)),
-                                        ("unit_mix_mfma_alone_224_cus_ns", 224, 0, (n, 0)),
-                                        ("unit_mix_mfma_alone_128_cus_ns", 128, 0, (n, 0)),
-                                        ("unit_mix_with_lds_reads_224_cus_ns", 224, 1, (n, n)),
-                                        ("unit_mix_with_lds_reads_256_cus_ns", 256, 1, (n, n)),
-                                        ("unit_mix_mfma_with_lds_reads_no_fill_224_cus_ns", 224, 1, (n, 0)),
-                                        ("unit_mix_c4_side_by_side_196_cus_ns", 196, 0, (1143, 1875)),
-                                        ("unit_mix_c4_side_by_side_128_cus_ns", 128, 0, (1143, 1875))):
-        sec = timed(lambda: cc.cacnn_probe_mfma_and_fill_on(cus, reads, ops, win, 2 << 20, sink, mi, fi), 3, 10)
+    for label, cus, tile, reads, (mi, fi) in (("unit_mix_side_by_side_224_cus_ns", 224, 0, 0, (n, n)),
+                                              ("unit_mix_side_by_side_128_cus_ns", 128, 0, 0, (n, n)),
+                                              ("unit_mix_mfma_alone_224_cus_ns", 224, 0, 0, (n, 0)),
+                                              ("unit_mix_mfma_alone_128_cus_ns", 128, 0, 0, (n, 0)),
+                                              ("unit_mix_with_lds_reads_224_cus_ns", 224, 0, 1, (n, n)),
+                                              ("unit_mix_with_lds_reads_256_cus_ns", 256, 0, 1, (n, n)),
+                                              ("unit_mix_mfma_with_lds_reads_no_fill_224_cus_ns", 224, 0, 1, (n, 0)),
+                                              ("unit_mix_c4_side_by_side_196_cus_ns", 196, 0, 0, (1143, 1875)),
+                                              ("unit_mix_c4_side_by_side_128_cus_ns", 128, 0, 0, (1143, 1875)),
+                                              # c4's own MFMA loop (24 MFMAs per wave and iteration on 4 accumulators)
+                                              ("unit_mix_c4_own_loop_mfma_alone_196_cus_ns", 196, 1, 0, (n, 0)),
+                                              ("unit_mix_c4_own_loop_side_by_side_196_cus_ns", 196, 1, 0, (n, 1875)),
+                                              ("unit_mix_c4_own_loop_with_lds_reads_no_fill_196_cus_ns", 196, 1, 1, (n, 0)),
+                                              ("unit_mix_c4_with_lds_reads_196_cus_ns", 196, 1, 1, (n, 1875)),
+                                              ("unit_mix_c4_with_lds_reads_256_cus_ns", 256, 1, 1, (n, 1875))):
+        sec = timed(lambda: cc.cacnn_probe_mfma_and_fill_on(cus, tile, reads, ops, win, 2 << 20, sink, mi, fi), 3, 10)
         out[label] = sec / n * 1e9
     del src, dst
     return out
@@ -310,9 +316,9 @@ def alternative_variants_us(cc, torch, cfg, buffers, steps, warmup):
 def add_unit_mix(rep, cfg, sustained):
     """For c4 and c5: the units a workgroup runs (Out tiles per workgroup x c-slices x filter rows) times what the machine
     takes for one unit's MFMAs and bytes side by side with nothing synchronising them, on as many compute units as the
-    shape has tiles (machine_sustained; for c5 with the operands read from the LDS as the kernel reads them): the time
+    shape has tiles (machine_sustained; with the operands read from the LDS as the shape's kernel reads them): the time
     the launch's loop would take at that rate, without the start and the end of a launch."""
-    key = {"c5": "unit_mix_with_lds_reads_224_cus_ns", "c4": "unit_mix_c4_side_by_side_196_cus_ns"}.get(cfg.name)
+    key = {"c5": "unit_mix_with_lds_reads_224_cus_ns", "c4": "unit_mix_c4_with_lds_reads_196_cus_ns"}.get(cfg.name)
     if key is None or key not in sustained:
         return
     units = (cfg.C // 32) * cfg.S            # one tile per workgroup on both shapes

@@ -116,7 +116,7 @@ int launch_pool(const PoolArgs& a, int dtype, int mode, int vec, void* stream);
 int launch_mfma_probe(int dtype, const void* operands, float* sink, int iters, int grid, void* stream);
 int launch_copy_probe(const void* src, void* dst, size_t bytes, int grid, void* stream);
 int launch_lds_fill_probe(const void* src, uint32_t window, int iters, float* sink, int grid, void* stream);
-int launch_mfma_and_fill_probe(const void* operands, const void* src, uint32_t window, int mfma_iters, int fill_iters,
+int launch_mfma_and_fill_probe(int tile, const void* operands, const void* src, uint32_t window, int mfma_iters, int fill_iters,
                                int lds_reads, float* sink, int grid, void* stream);
 
 // Defined in cacnn_kernels.hip.

@@ -101,18 +101,24 @@ __global__ void __launch_bounds__(256) lds_fill_kernel(const char* src, uint32_t
     sink[blockIdx.x * 256 + threadIdx.x] = (float)(unsigned char)lds[threadIdx.x * 16];
 }
 
-// Both at once, in the proportions of the bf16 convolution's unit: waves 0-3 of a workgroup of eight run the bf16 MFMA
-// loop (42 MFMAs per iteration and wave), waves 4-7 the LDS fill from a shared window (12 KiB per iteration and wave).
-// Either count may be zero.  What the two cost each other when nothing synchronises them.
-// lds_reads = 0: the MFMA loop is register-only.  1: before every 21 MFMAs a wave reads its 3 + 9 operand fragments from
-// the LDS the other waves are filling, with the instructions, the addresses and the bank pattern of the convolution
-// kernel's multiplying waves (3 16-byte reads of a Filter row, 18 transposing 8-byte reads of Image rows, laid out as
-// one buffer of that kernel: 36 KiB of Image rows of 128 bytes, then 64 Filter rows of 13 x 16 bytes); still no barrier
-// and no dependence between the two kinds of waves.
+// Both at once, in the proportions of a bf16 convolution kernel's unit: waves 0-3 of a workgroup of eight run the bf16
+// MFMA loop of that kernel's multiplying waves (per step 3 taps x TW x THW MFMAs on TW x THW accumulators, two steps per
+// iteration), waves 4-7 the LDS fill from a shared window (12 KiB per iteration and wave).  Either count may be zero.
+// What the two cost each other when nothing synchronises them.
+// <TW, THW> = <7, 1>: the tile of 64 images x 7 x 1 positions (42 MFMAs per iteration and wave); <2, 2>: 64 images x 2 x 2
+// positions (24 MFMAs per iteration and wave).
+// lds_reads = 0: the MFMA loop is register-only.  1: before every step a wave reads its 3 + THW x (TW + 2) operand
+// fragments from the LDS the other waves are filling, with the instructions, the addresses and the bank pattern of the
+// convolution kernel's multiplying waves (16-byte reads of a Filter row, pairs of transposing 8-byte reads of Image rows,
+// laid out as one buffer of that kernel: (TW + 2) x THW x 32 Image rows of 128 bytes, then 64 Filter rows of 13 x 16
+// bytes); still no barrier and no dependence between the two kinds of waves.
 typedef short pr_s16x4 __attribute__((ext_vector_type(4)));
 #define CACNN_PROBE_LDS(T) __attribute__((address_space(3))) T
+template <int TW, int THW>
 __global__ void __launch_bounds__(512) mfma_and_fill_kernel(const uint32_t* operands, const char* src, uint32_t window,
                                                             int mfma_iters, int fill_iters, int lds_reads, float* sink) {
+    constexpr int NBLK = TW * THW, XS = TW + 2, NX = THW * XS, IMG_BYTES = XS * THW * 32 * 128;
+    static_assert(IMG_BYTES + 64 * 13 * 16 <= 50 * 1024 && 3 + NX <= 1024 / 64, "probe geometry: LDS size, operand fragments");
     __shared__ __align__(16) char lds[50 * 1024];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     float result = 0.f;
@@ -123,61 +129,62 @@ __global__ void __launch_bounds__(512) mfma_and_fill_kernel(const uint32_t* oper
         __syncthreads();
     }
     if (wave < 4) {
-        pr_f32x16 acc[7];
+        pr_f32x16 acc[NBLK];
 #pragma unroll
-        for (int n = 0; n < 7; ++n)
+        for (int n = 0; n < NBLK; ++n)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
-        pr_bf16x8 A[3], X[9];
+        pr_bf16x8 A[3], X[NX];
         const pr_u32x4* const op = (const pr_u32x4*)operands;
 #pragma unroll
         for (int r = 0; r < 3; ++r) A[r] = __builtin_bit_cast(pr_bf16x8, op[(lane + 64 * r) & 1023]);
 #pragma unroll
-        for (int x = 0; x < 9; ++x) X[x] = __builtin_bit_cast(pr_bf16x8, op[(lane + 64 * (3 + x)) & 1023]);
+        for (int x = 0; x < NX; ++x) X[x] = __builtin_bit_cast(pr_bf16x8, op[(lane + 64 * (3 + x)) & 1023]);
+        auto mfma_step = [&]() {
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int h = 0; h < THW; ++h)
+#pragma unroll
+                    for (int w = 0; w < TW; ++w)
+                        acc[h * TW + w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[r], X[h * XS + w + r], acc[h * TW + w], 0, 0, 0);
+        };
         if (!lds_reads) {
-            for (int it = 0; it < 2 * mfma_iters; ++it) {
-#pragma unroll
-                for (int r = 0; r < 3; ++r)
-#pragma unroll
-                    for (int w = 0; w < 7; ++w)
-                        acc[w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[r], X[w + r], acc[w], 0, 0, 0);
-            }
+            for (int it = 0; it < 2 * mfma_iters; ++it) mfma_step();
         } else {
             // the multiplying waves' lane offsets (wave = wm + 2 wn; rows of 128 bytes, halves of rows with bit 1 of the
-            // channel set exchanged; Filter rows of 13 x 16 bytes behind 36 KiB of Image rows)
+            // channel set exchanged; Filter rows of 13 x 16 bytes behind the Image rows)
             const int wm = wave & 1, wn = wave >> 1;
             const int j = lane & 31, g = lane >> 5, i16 = lane & 15, jhalf = (lane >> 4) & 1;
             const int q = wn * 4 + 2 * jhalf + ((i16 & 3) >> 1);
-            const uint32_t al = (uint32_t)(36864 + ((wm * 32 + j) * 13 + g) * 16);
+            const uint32_t al = (uint32_t)(IMG_BYTES + ((wm * 32 + j) * 13 + g) * 16);
             const uint32_t xl = (uint32_t)((8 * g + (i16 >> 2)) * 128 + ((q ^ (((i16 >> 3) & 1) << 2)) * 16) + (i16 & 1) * 8);
             CACNN_PROBE_LDS(char)* const l3 = (CACNN_PROBE_LDS(char)*)lds;
             for (int it = 0; it < 2 * mfma_iters; ++it) {
                 const int cs = it & 1;
-                pr_bf16x8 An[3], Xn[9];
+                pr_bf16x8 An[3], Xn[NX];
 #pragma unroll
                 for (int r = 0; r < 3; ++r) An[r] = *(const CACNN_PROBE_LDS(pr_bf16x8)*)(l3 + al + (r * 4 + 2 * cs) * 16);
 #pragma unroll
-                for (int x = 0; x < 9; ++x) {
-                    CACNN_PROBE_LDS(char)* const p = l3 + xl + (x * 32 + 16 * cs) * 128;
-                    const pr_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CACNN_PROBE_LDS(pr_s16x4)*)p);
-                    const pr_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CACNN_PROBE_LDS(pr_s16x4)*)(p + 4 * 128));
-                    Xn[x] = __builtin_bit_cast(pr_bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                }
+                for (int h = 0; h < THW; ++h)
+#pragma unroll
+                    for (int x = 0; x < XS; ++x) {
+                        CACNN_PROBE_LDS(char)* const p = l3 + xl + ((x * THW + h) * 32 + 16 * cs) * 128;
+                        const pr_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CACNN_PROBE_LDS(pr_s16x4)*)p);
+                        const pr_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CACNN_PROBE_LDS(pr_s16x4)*)(p + 4 * 128));
+                        Xn[h * XS + x] = __builtin_bit_cast(pr_bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                    }
                 // this step's MFMAs run on the fragments read during the last step, under these reads
-#pragma unroll
-                for (int r = 0; r < 3; ++r)
-#pragma unroll
-                    for (int w = 0; w < 7; ++w)
-                        acc[w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[r], X[w + r], acc[w], 0, 0, 0);
+                mfma_step();
 #pragma unroll
                 for (int r = 0; r < 3; ++r) A[r] = An[r];
 #pragma unroll
-                for (int x = 0; x < 9; ++x) X[x] = Xn[x];
+                for (int x = 0; x < NX; ++x) X[x] = Xn[x];
                 asm volatile("" ::: "memory");      // the LDS changes under the reads: every step reads again
             }
         }
 #pragma unroll
-        for (int n = 0; n < 7; ++n)
+        for (int n = 0; n < NBLK; ++n)
 #pragma unroll
             for (int v = 0; v < 16; ++v) result += acc[n][v];
     } else {
@@ -199,22 +206,30 @@ __global__ void __launch_bounds__(512) mfma_and_fill_kernel(const uint32_t* oper
     if (wave < 4) sink[blockIdx.x * 256 + threadIdx.x] = result;
 }
 
-int launch_mfma_and_fill_probe(const void* operands, const void* src, uint32_t window, int mfma_iters, int fill_iters,
-                               int lds_reads, float* sink, int grid, void* stream) {
+template <int TW, int THW>
+static int launch_mfma_and_fill(const void* operands, const void* src, uint32_t window, int mfma_iters, int fill_iters, int lds_reads,
+                                float* sink, int grid, void* stream) {
     // 46 KiB of unused dynamic LDS on top of the kernel's own 50 KiB: no second workgroup fits the compute unit, so a
     // grid below the CU count leaves exactly that many compute units idle
     static bool attr_done = false;
     if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)mfma_and_fill_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 46 * 1024) !=
+        if (hipFuncSetAttribute((const void*)mfma_and_fill_kernel<TW, THW>, hipFuncAttributeMaxDynamicSharedMemorySize, 46 * 1024) !=
             hipSuccess) {
             (void)hipGetLastError();
             return 1;
         }
         attr_done = true;
     }
-    hipLaunchKernelGGL(mfma_and_fill_kernel, dim3(grid), dim3(512), 46 * 1024, (hipStream_t)stream, (const uint32_t*)operands,
-                       (const char*)src, window, mfma_iters, fill_iters, lds_reads, sink);
+    hipLaunchKernelGGL((mfma_and_fill_kernel<TW, THW>), dim3(grid), dim3(512), 46 * 1024, (hipStream_t)stream,
+                       (const uint32_t*)operands, (const char*)src, window, mfma_iters, fill_iters, lds_reads, sink);
     return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+// tile: 0 = 64 images x 7 x 1 positions, 1 = 64 images x 2 x 2 positions
+int launch_mfma_and_fill_probe(int tile, const void* operands, const void* src, uint32_t window, int mfma_iters, int fill_iters,
+                               int lds_reads, float* sink, int grid, void* stream) {
+    return tile == 0 ? launch_mfma_and_fill<7, 1>(operands, src, window, mfma_iters, fill_iters, lds_reads, sink, grid, stream)
+                     : launch_mfma_and_fill<2, 2>(operands, src, window, mfma_iters, fill_iters, lds_reads, sink, grid, stream);
 }
 
 int launch_lds_fill_probe(const void* src, uint32_t window, int iters, float* sink, int grid, void* stream) {

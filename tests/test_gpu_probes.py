@@ -106,29 +106,32 @@ def test_mfma_and_fill_probe_sums_and_refuses(env):
 
 
 def test_mfma_and_fill_probe_on_some_compute_units(env):
-    """With fewer workgroups than compute units the probe writes exactly that many workgroups' sums and refuses counts
-    outside 1 .. 256."""
+    """With fewer workgroups than compute units the probe writes exactly that many workgroups' sums, for both tile
+    geometries, with operands in registers and read from the LDS; it refuses counts outside 1 .. 256 and unknown modes."""
     cc, torch = env
     ops = torch.from_numpy(np.full(4096, np.int32(0x3f803f80), dtype=np.int32)).cuda()
     src = torch.zeros(2 << 20, dtype=torch.uint8, device="cuda:0")
     iters = 3
-    for cus in (1, 196, 224):
-        sink = torch.zeros(65536, dtype=torch.float32, device="cuda:0")
-        cc.cacnn_probe_mfma_and_fill_on(cus, 0, ops, src, 2 << 20, sink, iters, 2)
-        torch.cuda.synchronize()
-        got = sink.reshape(256, 256)
-        assert torch.all(got[:cus] == float(7 * 16 * 3 * 2 * iters * 16))
-        assert float(got[cus:].abs().sum()) == 0.0
+    for tile, blocks in ((0, 7), (1, 4)):
+        for cus in (1, 196, 224):
+            sink = torch.zeros(65536, dtype=torch.float32, device="cuda:0")
+            cc.cacnn_probe_mfma_and_fill_on(cus, tile, 0, ops, src, 2 << 20, sink, iters, 2)
+            torch.cuda.synchronize()
+            got = sink.reshape(256, 256)
+            assert torch.all(got[:cus] == float(blocks * 16 * 3 * 2 * iters * 16))
+            assert float(got[cus:].abs().sum()) == 0.0
     for cus in (0, 257, -1):
         with pytest.raises(cc.CacnnError):
-            cc.cacnn_probe_mfma_and_fill_on(cus, 0, ops, src, 2 << 20, sink, 1, 1)
+            cc.cacnn_probe_mfma_and_fill_on(cus, 0, 0, ops, src, 2 << 20, sink, 1, 1)
     # operands read from the LDS: it starts out as copies of the operand words (bf16 ones) and a window of bf16 ones is
     # filled in, so every fragment read is ones and the sums are the register-only figure, with the fill and without
     ones = torch.from_numpy(np.full(1 << 19, np.int32(0x3f803f80), dtype=np.int32)).cuda()
-    for fill in (8, 0):
-        sink = torch.zeros(65536, dtype=torch.float32, device="cuda:0")
-        cc.cacnn_probe_mfma_and_fill_on(224, 1, ops, ones, 2 << 20, sink, 8, fill)
-        torch.cuda.synchronize()
-        assert torch.all(sink.reshape(256, 256)[:224] == float(7 * 16 * 3 * 2 * 8 * 16))
-    with pytest.raises(cc.CacnnError):
-        cc.cacnn_probe_mfma_and_fill_on(224, 2, ops, src, 2 << 20, sink, 1, 1)
+    for tile, blocks in ((0, 7), (1, 4)):
+        for fill in (8, 0):
+            sink = torch.zeros(65536, dtype=torch.float32, device="cuda:0")
+            cc.cacnn_probe_mfma_and_fill_on(224, tile, 1, ops, ones, 2 << 20, sink, 8, fill)
+            torch.cuda.synchronize()
+            assert torch.all(sink.reshape(256, 256)[:224] == float(blocks * 16 * 3 * 2 * 8 * 16))
+    for tile, reads in ((0, 2), (2, 0), (-1, 1)):
+        with pytest.raises(cc.CacnnError):
+            cc.cacnn_probe_mfma_and_fill_on(224, tile, reads, ops, src, 2 << 20, sink, 1, 1)
