@@ -275,6 +275,30 @@ def test_probes_reject_bad_arguments_before_touching_the_gpu():
         assert e.value.status == status, (src, dst, n)
 
 
+def test_unit_mix_probe_rejects_bad_arguments_before_touching_the_gpu():
+    """cacnn_probe_mfma_and_fill_on through the raw C ABI with made-up (never dereferenced) pointers: NULLs, compute-unit
+    counts outside 1 .. 256, unknown tile and mode, windows that are no power of two or out of range, iteration counts."""
+    lib = ctypes.CDLL(cc.library_path())
+    f = lib.cacnn_probe_mfma_and_fill_on
+    f.restype = ctypes.c_int
+    f.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                  ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+    ok = dict(cus=224, tile=0, reads=1, ops=4096, src=8192, window=2 << 20, sink=16384, mi=1, fi=1)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["cus"], a["tile"], a["reads"], a["ops"], a["src"], a["window"], a["sink"], a["mi"], a["fi"], None)
+
+    for kw in (dict(ops=None), dict(src=None), dict(sink=None)):
+        assert call(**kw) == 1, kw
+    for kw in (dict(cus=0), dict(cus=257), dict(tile=2), dict(tile=-1), dict(reads=2), dict(window=3 << 20), dict(window=1 << 15),
+               dict(window=64 << 20), dict(mi=-1), dict(mi=0, fi=0), dict(fi=(1 << 20) + 1), dict(ops=4100), dict(src=8200)):
+        assert call(**kw) == 2, kw
+    import torch
+    if not torch.cuda.is_available():
+        assert call() == 5          # valid arguments, no device: nothing is launched
+
+
 PAR_SHAPES = [(8, 64, 64, 56, 56, 3, 3, 1, 1), (32, 3, 64, 112, 112, 7, 7, 2, 2), (256, 512, 512, 7, 7, 3, 3, 1, 1),
               (8, 1024, 1024, 7, 7, 3, 3, 1, 1), (1, 3, 8, 16, 16, 3, 3, 1, 1), (4, 5, 6, 7, 8, 3, 2, 4, 1),
               (1, 4, 1, 1, 3, 1, 1, 1, 1)]
