@@ -166,7 +166,12 @@ def machine_sustained(cc, torch, ci, np):
                                               ("unit_mix_c4_own_loop_side_by_side_196_cus_ns", 196, 1, 0, (n, 1875)),
                                               ("unit_mix_c4_own_loop_with_lds_reads_no_fill_196_cus_ns", 196, 1, 1, (n, 0)),
                                               ("unit_mix_c4_with_lds_reads_196_cus_ns", 196, 1, 1, (n, 1875)),
-                                              ("unit_mix_c4_with_lds_reads_256_cus_ns", 256, 1, 1, (n, 1875))):
+                                              ("unit_mix_c4_with_lds_reads_256_cus_ns", 256, 1, 1, (n, 1875)),
+                                              # with a workgroup barrier per unit as well (mode 3; the c4 unit then with 48
+                                              # instead of 45 KiB: the barrier needs equal iteration counts)
+                                              ("unit_mix_with_lds_reads_and_barrier_224_cus_ns", 224, 0, 3, (n, n)),
+                                              ("unit_mix_c4_with_lds_reads_48k_196_cus_ns", 196, 1, 1, (n, n)),
+                                              ("unit_mix_c4_with_lds_reads_48k_and_barrier_196_cus_ns", 196, 1, 3, (n, n))):
         sec = timed(lambda: cc.cacnn_probe_mfma_and_fill_on(cus, tile, reads, ops, win, 2 << 20, sink, mi, fi), 3, 10)
         out[label] = sec / n * 1e9
     del src, dst

@@ -286,10 +286,11 @@ int cacnn_pool_forward(const cacnn_problem* problem, int dtype, int mode, const 
  *   tile         0: the MFMA loop of the kernel with tiles of 64 images x 7 x 1 positions (mfma_iters x 42 MFMAs per
  *                wavefront, as cacnn_probe_mfma_and_fill); 1: of the kernel with tiles of 64 images x 2 x 2 positions
  *                (mfma_iters x 24 MFMAs per wavefront on 4 accumulators)
- *   lds_reads    0: register-only MFMA loop; 1: the MFMA wavefronts read their operand fragments from the LDS that the others
- *                are filling, before every half iteration, with the instructions and the addresses of that kernel's
- *                multiplying wavefronts (3 16-byte reads and 18 or 16 transposing 8-byte reads); the LDS starts out as copies
- *                of the operand words
+ *   mode         bit 0: the MFMA wavefronts read their operand fragments from the LDS that the others are filling, before
+ *                every half iteration, with the instructions and the addresses of that kernel's multiplying wavefronts (3
+ *                16-byte reads and 18 or 16 transposing 8-byte reads); the LDS starts out as copies of the operand words
+ *                (clear: register-only MFMA loop).  bit 1: all eight wavefronts meet at a workgroup barrier once per
+ *                iteration, as that kernel's do once per unit; needs mfma_iters == fill_iters
  * All of them enqueue on hip_stream and return; they never synchronise and allocate nothing.  The caller times them.
  * Errors: CACNN_ERR_NULL, CACNN_ERR_INVALID_ARG (alignment, sizes, iters), CACNN_ERR_UNSUPPORTED (dtype),
  * CACNN_ERR_NO_DEVICE, CACNN_ERR_LAUNCH.
@@ -299,7 +300,7 @@ int cacnn_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream)
 int cacnn_probe_lds_fill(const void* src, size_t window_bytes, float* sink, int32_t iters, void* hip_stream, int64_t* bytes_moved);
 int cacnn_probe_mfma_and_fill(const void* operands, const void* src, size_t window_bytes, float* sink, int32_t mfma_iters,
                               int32_t fill_iters, void* hip_stream);
-int cacnn_probe_mfma_and_fill_on(int32_t compute_units, int32_t tile, int32_t lds_reads, const void* operands, const void* src,
+int cacnn_probe_mfma_and_fill_on(int32_t compute_units, int32_t tile, int32_t mode, const void* operands, const void* src,
                                  size_t window_bytes, float* sink, int32_t mfma_iters, int32_t fill_iters, void* hip_stream);
 
 /* Number of compiled kernel variants, and a static, NUL-terminated description of one

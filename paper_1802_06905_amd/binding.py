@@ -371,15 +371,15 @@ def cacnn_probe_mfma_and_fill(operands, src, window_bytes: int, sink, mfma_iters
         raise CacnnError(rc, "cacnn_probe_mfma_and_fill")
 
 
-def cacnn_probe_mfma_and_fill_on(compute_units: int, tile: int, lds_reads: int, operands, src, window_bytes: int, sink,
+def cacnn_probe_mfma_and_fill_on(compute_units: int, tile: int, mode: int, operands, src, window_bytes: int, sink,
                                  mfma_iters: int, fill_iters: int, stream=None) -> None:
     """The same on `compute_units` compute units only (one workgroup each, the others idle); tile 0 / 1: the MFMA loop of
-    the kernel with 7 x 1 / 2 x 2 positions per tile; lds_reads = 1: the MFMA wavefronts read their operands from the LDS
-    being filled, as that kernel's multiplying wavefronts do."""
+    the kernel with 7 x 1 / 2 x 2 positions per tile; mode bit 0: the MFMA wavefronts read their operands from the LDS
+    being filled, as that kernel's multiplying wavefronts do; bit 1: a workgroup barrier per iteration (equal counts)."""
     if operands.numel() * operands.element_size() < 16384 or src.numel() * src.element_size() < int(window_bytes) or \
             sink.numel() * sink.element_size() < 65536 * 4:
         raise ValueError("cacnn_probe_mfma_and_fill_on: operands (16 KiB), src (the window) or sink (65536 floats) too short")
-    rc = _lib.cacnn_probe_mfma_and_fill_on(int(compute_units), int(tile), int(lds_reads), _ptr(operands), _ptr(src),
+    rc = _lib.cacnn_probe_mfma_and_fill_on(int(compute_units), int(tile), int(mode), _ptr(operands), _ptr(src),
                                            int(window_bytes), _ptr(sink), int(mfma_iters), int(fill_iters), _stream_handle(stream))
     if rc != 0:
         raise CacnnError(rc, "cacnn_probe_mfma_and_fill_on")

@@ -1374,17 +1374,19 @@ int cacnn_probe_mfma_and_fill(const void* operands, const void* src, size_t wind
                                         fill_iters, hip_stream);
 }
 
-int cacnn_probe_mfma_and_fill_on(int32_t compute_units, int32_t tile, int32_t lds_reads, const void* operands, const void* src,
+int cacnn_probe_mfma_and_fill_on(int32_t compute_units, int32_t tile, int32_t mode, const void* operands, const void* src,
                                  size_t window_bytes, float* sink, int32_t mfma_iters, int32_t fill_iters, void* hip_stream) {
     if (!operands || !src || !sink) return CACNN_ERR_NULL;
-    if (compute_units < 1 || compute_units > kDefaultMachine.num_cu || (lds_reads != 0 && lds_reads != 1) || (tile != 0 && tile != 1))
+    // mode: bit 0 = operands read from LDS, bit 1 = a workgroup barrier per iteration (equal iteration counts only)
+    if (compute_units < 1 || compute_units > kDefaultMachine.num_cu || mode < 0 || mode > 3 || (tile != 0 && tile != 1))
         return CACNN_ERR_INVALID_ARG;
+    if ((mode & 2) && mfma_iters != fill_iters) return CACNN_ERR_INVALID_ARG;
     if (window_bytes < 65536 || window_bytes > (32u << 20) || (window_bytes & (window_bytes - 1)) || mfma_iters < 0 ||
         fill_iters < 0 || mfma_iters > (1 << 20) || fill_iters > (1 << 20) || (mfma_iters == 0 && fill_iters == 0) ||
         reinterpret_cast<uintptr_t>(src) % 16 || reinterpret_cast<uintptr_t>(operands) % 16)
         return CACNN_ERR_INVALID_ARG;
     if (!have_device()) return CACNN_ERR_NO_DEVICE;
-    return launch_mfma_and_fill_probe(tile, operands, src, (uint32_t)window_bytes, mfma_iters, fill_iters, lds_reads, sink, compute_units,
+    return launch_mfma_and_fill_probe(tile, operands, src, (uint32_t)window_bytes, mfma_iters, fill_iters, mode & 1, (mode >> 1) & 1, sink, compute_units,
                                       hip_stream) == 0
                ? CACNN_OK
                : CACNN_ERR_LAUNCH;

@@ -117,7 +117,7 @@ int launch_mfma_probe(int dtype, const void* operands, float* sink, int iters, i
 int launch_copy_probe(const void* src, void* dst, size_t bytes, int grid, void* stream);
 int launch_lds_fill_probe(const void* src, uint32_t window, int iters, float* sink, int grid, void* stream);
 int launch_mfma_and_fill_probe(int tile, const void* operands, const void* src, uint32_t window, int mfma_iters, int fill_iters,
-                               int lds_reads, float* sink, int grid, void* stream);
+                               int lds_reads, int barrier, float* sink, int grid, void* stream);
 
 // Defined in cacnn_kernels.hip.
 int num_variants();

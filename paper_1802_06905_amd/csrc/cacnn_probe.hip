@@ -111,12 +111,15 @@ __global__ void __launch_bounds__(256) lds_fill_kernel(const char* src, uint32_t
 // fragments from the LDS the other waves are filling, with the instructions, the addresses and the bank pattern of the
 // convolution kernel's multiplying waves (16-byte reads of a Filter row, pairs of transposing 8-byte reads of Image rows,
 // laid out as one buffer of that kernel: (TW + 2) x THW x 32 Image rows of 128 bytes, then 64 Filter rows of 13 x 16
-// bytes); still no barrier and no dependence between the two kinds of waves.
+// bytes); still no dependence between the two kinds of waves.
+// barrier = 1 (the host passes it only with mfma_iters == fill_iters, so that all eight waves execute the same number
+// of barriers): once per iteration all eight waves meet at a workgroup barrier, as the kernel's waves do once per unit.
 typedef short pr_s16x4 __attribute__((ext_vector_type(4)));
 #define CACNN_PROBE_LDS(T) __attribute__((address_space(3))) T
 template <int TW, int THW>
 __global__ void __launch_bounds__(512) mfma_and_fill_kernel(const uint32_t* operands, const char* src, uint32_t window,
-                                                            int mfma_iters, int fill_iters, int lds_reads, float* sink) {
+                                                            int mfma_iters, int fill_iters, int lds_reads, int barrier,
+                                                            float* sink) {
     constexpr int NBLK = TW * THW, XS = TW + 2, NX = THW * XS, IMG_BYTES = XS * THW * 32 * 128;
     static_assert(IMG_BYTES + 64 * 13 * 16 <= 50 * 1024 && 3 + NX <= 1024 / 64, "probe geometry: LDS size, operand fragments");
     __shared__ __align__(16) char lds[50 * 1024];
@@ -150,7 +153,10 @@ __global__ void __launch_bounds__(512) mfma_and_fill_kernel(const uint32_t* oper
                         acc[h * TW + w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[r], X[h * XS + w + r], acc[h * TW + w], 0, 0, 0);
         };
         if (!lds_reads) {
-            for (int it = 0; it < 2 * mfma_iters; ++it) mfma_step();
+            for (int it = 0; it < 2 * mfma_iters; ++it) {
+                mfma_step();
+                if (barrier && (it & 1)) __builtin_amdgcn_s_barrier();
+            }
         } else {
             // the multiplying waves' lane offsets (wave = wm + 2 wn; rows of 128 bytes, halves of rows with bit 1 of the
             // channel set exchanged; Filter rows of 13 x 16 bytes behind the Image rows)
@@ -181,6 +187,8 @@ __global__ void __launch_bounds__(512) mfma_and_fill_kernel(const uint32_t* oper
 #pragma unroll
                 for (int x = 0; x < NX; ++x) X[x] = Xn[x];
                 asm volatile("" ::: "memory");      // the LDS changes under the reads: every step reads again
+                // as in the kernel: once per unit, when this step's reads have landed, meet the other waves
+                if (barrier && (it & 1)) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             }
         }
 #pragma unroll
@@ -200,6 +208,8 @@ __global__ void __launch_bounds__(512) mfma_and_fill_kernel(const uint32_t* oper
                                                          (uint32_t)lane * 16u, ((chunk + i) & (chunks - 1)) << 10, 0, 0);
             chunk = (chunk + 48u * 5u + 12u) & (chunks - 1);
             __builtin_amdgcn_s_waitcnt((12 & 15) | ((12 >> 4) << 14) | (7 << 4) | (15 << 8));
+            // (the loads of the iteration before have landed: the kernel's staging waves announce a unit here)
+            if (barrier) __builtin_amdgcn_s_barrier();
         }
         __builtin_amdgcn_s_waitcnt(0);
     }
@@ -208,7 +218,7 @@ __global__ void __launch_bounds__(512) mfma_and_fill_kernel(const uint32_t* oper
 
 template <int TW, int THW>
 static int launch_mfma_and_fill(const void* operands, const void* src, uint32_t window, int mfma_iters, int fill_iters, int lds_reads,
-                                float* sink, int grid, void* stream) {
+                                int barrier, float* sink, int grid, void* stream) {
     // 46 KiB of unused dynamic LDS on top of the kernel's own 50 KiB: no second workgroup fits the compute unit, so a
     // grid below the CU count leaves exactly that many compute units idle
     static bool attr_done = false;
@@ -221,15 +231,16 @@ static int launch_mfma_and_fill(const void* operands, const void* src, uint32_t 
         attr_done = true;
     }
     hipLaunchKernelGGL((mfma_and_fill_kernel<TW, THW>), dim3(grid), dim3(512), 46 * 1024, (hipStream_t)stream,
-                       (const uint32_t*)operands, (const char*)src, window, mfma_iters, fill_iters, lds_reads, sink);
+                       (const uint32_t*)operands, (const char*)src, window, mfma_iters, fill_iters, lds_reads, barrier, sink);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
 // tile: 0 = 64 images x 7 x 1 positions, 1 = 64 images x 2 x 2 positions
 int launch_mfma_and_fill_probe(int tile, const void* operands, const void* src, uint32_t window, int mfma_iters, int fill_iters,
-                               int lds_reads, float* sink, int grid, void* stream) {
-    return tile == 0 ? launch_mfma_and_fill<7, 1>(operands, src, window, mfma_iters, fill_iters, lds_reads, sink, grid, stream)
-                     : launch_mfma_and_fill<2, 2>(operands, src, window, mfma_iters, fill_iters, lds_reads, sink, grid, stream);
+                               int lds_reads, int barrier, float* sink, int grid, void* stream) {
+    if (barrier && mfma_iters != fill_iters) return 1;      // the waves would not meet
+    return tile == 0 ? launch_mfma_and_fill<7, 1>(operands, src, window, mfma_iters, fill_iters, lds_reads, barrier, sink, grid, stream)
+                     : launch_mfma_and_fill<2, 2>(operands, src, window, mfma_iters, fill_iters, lds_reads, barrier, sink, grid, stream);
 }
 
 int launch_lds_fill_probe(const void* src, uint32_t window, int iters, float* sink, int grid, void* stream) {

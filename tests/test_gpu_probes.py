@@ -126,12 +126,13 @@ def test_mfma_and_fill_probe_on_some_compute_units(env):
     # operands read from the LDS: it starts out as copies of the operand words (bf16 ones) and a window of bf16 ones is
     # filled in, so every fragment read is ones and the sums are the register-only figure, with the fill and without
     ones = torch.from_numpy(np.full(1 << 19, np.int32(0x3f803f80), dtype=np.int32)).cuda()
+    # (mode 2 and 3: with a workgroup barrier per iteration, which needs equal iteration counts)
     for tile, blocks in ((0, 7), (1, 4)):
-        for fill in (8, 0):
+        for mode, fill in ((1, 8), (1, 0), (3, 8), (2, 8)):
             sink = torch.zeros(65536, dtype=torch.float32, device="cuda:0")
-            cc.cacnn_probe_mfma_and_fill_on(224, tile, 1, ops, ones, 2 << 20, sink, 8, fill)
+            cc.cacnn_probe_mfma_and_fill_on(224, tile, mode, ops, ones, 2 << 20, sink, 8, fill)
             torch.cuda.synchronize()
             assert torch.all(sink.reshape(256, 256)[:224] == float(blocks * 16 * 3 * 2 * 8 * 16))
-    for tile, reads in ((0, 2), (2, 0), (-1, 1)):
+    for tile, mode, fill in ((0, 4, 1), (2, 0, 1), (-1, 1, 1), (0, 3, 2), (1, 2, 0)):
         with pytest.raises(cc.CacnnError):
-            cc.cacnn_probe_mfma_and_fill_on(224, tile, reads, ops, src, 2 << 20, sink, 1, 1)
+            cc.cacnn_probe_mfma_and_fill_on(224, tile, mode, ops, src, 2 << 20, sink, 1, fill)

@@ -277,7 +277,7 @@ def test_probes_reject_bad_arguments_before_touching_the_gpu():
 
 def test_unit_mix_probe_rejects_bad_arguments_before_touching_the_gpu():
     """cacnn_probe_mfma_and_fill_on through the raw C ABI with made-up (never dereferenced) pointers: NULLs, compute-unit
-    counts outside 1 .. 256, unknown tile and mode, windows that are no power of two or out of range, iteration counts."""
+    counts outside 1 .. 256, unknown tile and mode, a barrier with unequal iteration counts, windows that are no power of two or out of range, iteration counts."""
     lib = ctypes.CDLL(cc.library_path())
     f = lib.cacnn_probe_mfma_and_fill_on
     f.restype = ctypes.c_int
@@ -291,7 +291,8 @@ def test_unit_mix_probe_rejects_bad_arguments_before_touching_the_gpu():
 
     for kw in (dict(ops=None), dict(src=None), dict(sink=None)):
         assert call(**kw) == 1, kw
-    for kw in (dict(cus=0), dict(cus=257), dict(tile=2), dict(tile=-1), dict(reads=2), dict(window=3 << 20), dict(window=1 << 15),
+    for kw in (dict(cus=0), dict(cus=257), dict(tile=2), dict(tile=-1), dict(reads=4), dict(reads=-1), dict(reads=2, mi=1, fi=2),
+               dict(reads=3, mi=5, fi=0), dict(window=3 << 20), dict(window=1 << 15),
                dict(window=64 << 20), dict(mi=-1), dict(mi=0, fi=0), dict(fi=(1 << 20) + 1), dict(ops=4100), dict(src=8200)):
         assert call(**kw) == 2, kw
     import torch
