@@ -571,7 +571,8 @@ def planner_sweep(cc, torch, ci, np, shapes):
         print(f"fit | {family} | {' '.join(f'{c:.4g}' for c in x)} | {float(np.sqrt(np.mean(err ** 2))):.3f} | {len(A)}")
 
 
-# layers that the fixed-geometry kernels added for 1 x 1 filters and for 32-image tiles take (beside the benchmark shapes' own)
+# layers that the fixed-geometry kernels added for 1 x 1 filters, for 32-image tiles and for tiles that overhang Out take
+# (beside the benchmark shapes' own)
 ONE_BY_ONE_SHAPES = [
     ("f32", 8, 256, 256, 14, 14, 1, 1, 1, 1), ("f32", 32, 512, 128, 28, 28, 1, 1, 1, 1), ("f32", 16, 64, 256, 56, 56, 1, 1, 1, 1),
     ("f32", 64, 1024, 256, 14, 14, 1, 1, 1, 1),
@@ -580,13 +581,18 @@ ONE_BY_ONE_SHAPES = [
     # 32 images (or a multiple that is not one of 64): the fixed-geometry bf16 kernels with 32-image tiles take these
     ("bf16", 32, 128, 128, 56, 56, 3, 3, 1, 1), ("bf16", 32, 512, 512, 14, 14, 3, 3, 1, 1), ("bf16", 96, 128, 128, 28, 28, 3, 3, 1, 1),
     ("bf16", 32, 256, 256, 28, 28, 3, 3, 1, 1), ("bf16", 32, 256, 1024, 14, 14, 1, 1, 1, 1),
+    # W, H or K that no tile divides: the bf16 kernels that load the Image straight into LDS mask their Out stores
+    ("bf16", 128, 256, 384, 13, 13, 3, 3, 1, 1), ("bf16", 128, 384, 256, 13, 13, 3, 3, 1, 1), ("bf16", 64, 96, 256, 27, 27, 1, 1, 1, 1),
+    ("bf16", 64, 2048, 1000, 1, 1, 1, 1, 1, 1), ("bf16", 64, 64, 192, 55, 55, 3, 3, 1, 1), ("bf16", 64, 128, 160, 17, 17, 3, 3, 1, 1),
+    ("bf16", 128, 512, 512, 13, 13, 1, 1, 1, 1), ("bf16", 64, 160, 320, 10, 10, 3, 3, 1, 1),
 ]
 
 
 def planner_compare(cc, torch, ci, np):
     """The planner's pick against the fastest of all kernel variants (cacnn_tune) on PLANNER_SHAPES; the planner is the
     one the environment selects (CACNN_PLANNER unset: the calibrated cycle model; lp: the tile sized from the Section 5
-    LP at the gfx950 budget).  One row per shape, then the geometric mean of the ratios."""
+    LP at the gfx950 budget).  One row per shape, then the geometric mean of the ratios.  On ONE_BY_ONE_SHAPES, which the
+    fixed-geometry kernels take, the row also has the fastest of the generic variants."""
     mode = os.environ.get("CACNN_PLANNER", "model")
 
     def timed(fn, n=60, w=10):
@@ -611,11 +617,27 @@ def planner_compare(cc, torch, ci, np):
         t_plan = timed(lambda: cc.cacnn_conv_forward_with_plan(dims, dt, plan, d_img, d_flt, d_out))
         tuned = cc.cacnn_tune(dims, dt, d_img, d_flt, d_out)
         t_tune = timed(lambda: cc.cacnn_conv_forward_with_plan(dims, dt, tuned, d_img, d_flt, d_out))
+        generic = ""
         if sh in PLANNER_SHAPES:
             ratios.append(t_plan / t_tune)                # the summary line is about the generic kernels' cost model
+        else:
+            # what the fixed-geometry kernel is worth on this layer: the fastest of the other variants
+            best = None
+            for vi in range(cc.cacnn_variant_count()):
+                if " fx" in cc.cacnn_variant_name(vi):
+                    continue
+                try:
+                    gplan, _ = cc.cacnn_plan_variant(dims, dt, vi)
+                    t = timed(lambda: cc.cacnn_conv_forward_with_plan(dims, dt, gplan, d_img, d_flt, d_out), n=20, w=3)
+                except cc.CacnnError:
+                    continue
+                if best is None or t < best[0]:
+                    best = (t, vi)
+            if best is not None:
+                generic = f" | fastest generic variant: {cc.cacnn_variant_name(best[1])} {best[0]:.2f} ({best[0] / t_plan:.2f} x the planner's)"
         print(f"{mode} | {dtype} {' '.join(str(v) for v in dims)} | {cc.cacnn_variant_name(plan.variant)} "
               f"[{plan.b_c}, {plan.b_r}, {plan.b_s}] {t_plan:.2f} | {cc.cacnn_variant_name(tuned.variant)} "
-              f"[{tuned.b_c}, {tuned.b_r}, {tuned.b_s}] {t_tune:.2f} | {t_plan / t_tune:.3f}", flush=True)
+              f"[{tuned.b_c}, {tuned.b_r}, {tuned.b_s}] {t_tune:.2f} | {t_plan / t_tune:.3f}{generic}", flush=True)
     gm = float(np.exp(np.mean(np.log(ratios))))
     print(f"{mode}: geometric mean of the ratios {gm:.3f}, worst {max(ratios):.2f}, within 15 % of the fastest on "
           f"{sum(1 for r in ratios if r <= 1.15)} of {len(ratios)}")

@@ -233,8 +233,8 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
         g.lds_bytes = v.fx_lds;
         g.img_items = g.flt_items = 1;
         g.legal = CT == v.fx_ct && bR == v.fx_br && bS == v.fx_bs && g.YS == v.fx_ys && p.sigma_w == v.fx_sw &&
-                  p.sigma_h == v.fx_sh && p.R == bR && p.S % bS == 0 && p.C % CT == 0 && p.B % v.TB == 0 &&
-                  p.W % v.TW == 0 && p.H % v.TH == 0 && p.K % v.KT() == 0 && vec_img;
+                  p.sigma_h == v.fx_sh && p.R == bR && p.S % bS == 0 && p.C % CT == 0 && p.B % v.TB == 0 && vec_img &&
+                  (v.fx_ragged || (p.W % v.TW == 0 && p.H % v.TH == 0 && p.K % v.KT() == 0));
         if (v.fx_whole && (p.S != bS || p.C != CT)) g.legal = false;
         // staged words are addressed by 32-bit byte offsets from the unit's origin
         const double esz = v.dtype == CACNN_F32 ? 4.0 : 2.0;
@@ -453,8 +453,19 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
                 double cost = per_cu * (mc.mfma * t_mfma + mc.stage * t_stage + mc.slice * n_ctiles) +
                               mc.drain * t_out / std::max(1.0, std::min(per_cu, 4.0)) + mc.fixed;
                 // the fixed-geometry kernels run one schedule: priced by what a unit was measured to take
-                if (v.fx_unit_us > 0.f)
-                    cost = (per_cu * n_ctiles * (double)v.fx_unit_us + (double)v.fx_fixed_us) * 2400.0;
+                if (v.fx_unit_us > 0.f) {
+                    double rounds = per_cu;
+                    if (v.fx_calib_cus > 0) {
+                        // the bf16 MFMA rate is the chip's (its power-managed clock), not the compute unit's: measured, a unit
+                        // takes 1.13 to 1.2 times as long on 256 busy compute units as on 224 or 196, and 0.72 to 0.8 times
+                        // on 128; (n / n_calibration)^0.8, not below 0.75, is within a few per cent of those.  Full rounds of
+                        // tiles run on all compute units, the last round on what is left.
+                        auto scale = [&](double busy) { return std::max(0.75, std::pow(busy / (double)v.fx_calib_cus, 0.8)); };
+                        const int64_t full = n_wg / mach.num_cu, rest = n_wg % mach.num_cu;
+                        rounds = (double)full * scale((double)mach.num_cu) + (rest ? scale((double)rest) : 0.0);
+                    }
+                    cost = (rounds * n_ctiles * (double)v.fx_unit_us + (double)v.fx_fixed_us) * 2400.0;
+                }
                 if (best->variant < 0 || cost < best->cost) {
                     best->variant = vi;
                     best->g = g;

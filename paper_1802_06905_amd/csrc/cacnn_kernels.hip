@@ -1793,6 +1793,17 @@ __device__ __forceinline__ void store_block_exact(float* base, int64_t kstride, 
     }
 }
 
+// The same for a block at the edge of Out: only the rows below `rows` (this lane's count of valid output channels from
+// its first row on) are stored.
+__device__ __forceinline__ void store_block_rows(float* base, int64_t kstride, uint32_t lane_off, f32x16& acc, int rows) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int row = (v >> 2) * 8 + (v & 3);
+        if (row < rows) __builtin_nontemporal_store(acc[v], base + (int64_t)row * kstride + lane_off);
+        acc[v] = 0.f;
+    }
+}
+
 __device__ __forceinline__ void lds_done_then_barrier() {
     // every LDS access issued so far has completed; then meet the other waves
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -1894,9 +1905,10 @@ struct Bf16DirectFixed {
     static_assert(BUF_BYTES < 65536 && LDS_BYTES <= 160 * 1024, "direct bf16 geometry: LDS offsets and size");
     static_assert(STEPS == 2 && 2 * LOADS < 64, "direct bf16 geometry: two steps per unit, load counter range");
     static bool matches_host(const KernelArgs& a) {
+        // (W, H and K need not be multiples of the tile: what a tile stages beyond the arrays is zeros or other rows of
+        // the Image, which only reach outputs that are not stored)
         return a.sw == 1 && a.sh == 1 && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
-               a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % TB == 0 && a.W % TW == 0 && a.H % TH == 0 &&
-               a.K % KT == 0 && a.vec_img && a.vec_flt;
+               a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % TB == 0 && a.vec_img && a.vec_flt;
     }
 };
 
@@ -2121,11 +2133,23 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
             --left;
             if (__builtin_expect(--in_tile == 0, 0)) {
                 const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
+                if (tc.k0 + KT <= a.K && tc.w0 + TW <= a.W && tc.h0 + TH <= a.H) {
 #pragma unroll
-                for (int n = 0; n < NBLK; ++n) {
-                    const int hrow = TB == 64 ? n / TW : wn;
-                    float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + tc.h0 + hrow) * a.W + tc.w0 + n % TW) * a.B + tc.b0);
-                    store_block_exact<true>(blk, out_kstride, out_lane, acc[0][n]);
+                    for (int n = 0; n < NBLK; ++n) {
+                        const int hrow = TB == 64 ? n / TW : wn;
+                        float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + tc.h0 + hrow) * a.W + tc.w0 + n % TW) * a.B + tc.b0);
+                        store_block_exact<true>(blk, out_kstride, out_lane, acc[0][n]);
+                    }
+                } else {
+                    // a tile that overhangs Out: the blocks of positions inside, the rows of output channels inside
+                    const int rows = a.K - (tc.k0 + wm * 32 + g * 4);
+#pragma unroll
+                    for (int n = 0; n < NBLK; ++n) {
+                        const int hrow = TB == 64 ? n / TW : wn;
+                        const int w = tc.w0 + n % TW, h = tc.h0 + hrow;
+                        float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + h) * a.W + w) * a.B + tc.b0);
+                        store_block_rows(blk, out_kstride, out_lane, acc[0][n], (w < a.W && h < a.H) ? rows : 0);
+                    }
                 }
                 in_tile = upt;
                 t += gridDim.x;
@@ -2998,10 +3022,10 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
     }
 
 // bf16 with the Image loaded straight into LDS: 64 images, 64 output channels, 32-channel slices of one filter row
-#define CACNN_DIRECT_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                                   \
+#define CACNN_DIRECT_VARIANT(NAME, UNIT_US, FIXED_US, CALIB, TW, TH)                                                 \
     {                                                                                                          \
         {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, TH>::NBLK, 64, TW, TH, 2, 1, Bf16DirectFixed<TW, TH>::MAXF, 1, 3, 1.0f, 32, 3,  \
-         1, Bf16DirectFixed<TW, TH>::YS, 1, 1, Bf16DirectFixed<TW, TH>::LDS_BYTES, UNIT_US, FIXED_US, 0},       \
+         1, Bf16DirectFixed<TW, TH>::YS, 1, 1, Bf16DirectFixed<TW, TH>::LDS_BYTES, UNIT_US, FIXED_US, 0, 1, CALIB},       \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!Bf16DirectFixed<TW, TH>::matches_host(a) || lds != (size_t)Bf16DirectFixed<TW, TH>::LDS_BYTES) return 1; \
@@ -3013,7 +3037,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 #define CACNN_DIRECT_B32_VARIANT(NAME, UNIT_US, FIXED_US, TW, BR)                                               \
     {                                                                                                          \
         {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, 2, BR, 32>::NBLK, 32, TW, 2, 2, 1, Bf16DirectFixed<TW, 2, BR, 32>::MAXF, 1, BR, 1.0f, 32, BR,  \
-         1, Bf16DirectFixed<TW, 2, BR, 32>::YS, 1, 1, Bf16DirectFixed<TW, 2, BR, 32>::LDS_BYTES, UNIT_US, FIXED_US, 0},  \
+         1, Bf16DirectFixed<TW, 2, BR, 32>::YS, 1, 1, Bf16DirectFixed<TW, 2, BR, 32>::LDS_BYTES, UNIT_US, FIXED_US, 0, 1, 256},  \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!Bf16DirectFixed<TW, 2, BR, 32>::matches_host(a) || lds != (size_t)Bf16DirectFixed<TW, 2, BR, 32>::LDS_BYTES) return 1; \
@@ -3025,7 +3049,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 #define CACNN_DIRECT_1X1_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                               \
     {                                                                                                          \
         {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, TH, 1>::NBLK, 64, TW, TH, 2, 1, Bf16DirectFixed<TW, TH, 1>::MAXF, 1, 1, 1.0f, 32, 1,  \
-         1, Bf16DirectFixed<TW, TH, 1>::YS, 1, 1, Bf16DirectFixed<TW, TH, 1>::LDS_BYTES, UNIT_US, FIXED_US, 0}, \
+         1, Bf16DirectFixed<TW, TH, 1>::YS, 1, 1, Bf16DirectFixed<TW, TH, 1>::LDS_BYTES, UNIT_US, FIXED_US, 0, 1, 256}, \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!Bf16DirectFixed<TW, TH, 1>::matches_host(a) || lds != (size_t)Bf16DirectFixed<TW, TH, 1>::LDS_BYTES) return 1; \
@@ -3034,10 +3058,10 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
     }
 
 // bf16 staged through registers with a deep prefetch: 64 images, 64 output channels, 32-channel slices, Image units of BSI filter rows
-#define CACNN_STAGED_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH, BSI)                                              \
+#define CACNN_STAGED_VARIANT(NAME, UNIT_US, FIXED_US, CALIB, TW, TH, BSI)                                            \
     {                                                                                                          \
         {NAME, 1, 2, 2, 1, Bf16StagedFixed<TW, TH, BSI>::NBLK, 64, TW, TH, 2, 1, Bf16StagedFixed<TW, TH, BSI>::MAXF, 1, 3, 1.0f, 32, 3,  \
-         BSI, Bf16StagedFixed<TW, TH, BSI>::YSI, 1, 1, Bf16StagedFixed<TW, TH, BSI>::LDS_BYTES, UNIT_US, FIXED_US, 0},  \
+         BSI, Bf16StagedFixed<TW, TH, BSI>::YSI, 1, 1, Bf16StagedFixed<TW, TH, BSI>::LDS_BYTES, UNIT_US, FIXED_US, 0, 0, CALIB},  \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!Bf16StagedFixed<TW, TH, BSI>::matches_host(a) || lds != (size_t)Bf16StagedFixed<TW, TH, BSI>::LDS_BYTES) return 1; \
@@ -3140,14 +3164,14 @@ static const Variant g_variants[] = {
     CACNN_F32_DIRECT_VARIANT("f32 fxd k64 b8w4h4 w2x2 m1n2 c16r3s3", 4.4f, 3.0f, 4, 4),
     CACNN_F32_DIRECT16_VARIANT("f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r3s3", 4.1f, 2.6f, 2, 7),
     CACNN_F32_DIRECT16_1X1_VARIANT("f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r1s1", 0.50f, 2.6f, 2, 7),
-    CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.0f, 4.5f, 7, 1),
-    CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.62f, 4.2f, 2, 2),
+    CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.0f, 4.5f, 224, 7, 1),
+    CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.62f, 4.2f, 196, 2, 2),
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1", 0.50f, 4.5f, 7, 1),
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1", 0.30f, 4.2f, 2, 2),
     CACNN_DIRECT_B32_VARIANT("bf16 fxd k64 b32w7h2 w2x2 m1n7 c32r3s1", 1.1f, 4.5f, 7, 3),
     CACNN_DIRECT_B32_VARIANT("bf16 fxd k64 b32w7h2 w2x2 m1n7 c32r1s1", 0.6f, 4.5f, 7, 1),
-    CACNN_STAGED_VARIANT("bf16 fxr k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.1f, 4.5f, 7, 1, 1),
-    CACNN_STAGED_VARIANT("bf16 fxr k64 b64w2h2 w2x2 m1n4 c32r3s3", 2.0f, 4.2f, 2, 2, 3),
+    CACNN_STAGED_VARIANT("bf16 fxr k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.1f, 4.5f, 224, 7, 1, 1),
+    CACNN_STAGED_VARIANT("bf16 fxr k64 b64w2h2 w2x2 m1n4 c32r3s3", 2.0f, 4.2f, 196, 2, 2, 3),
     // fixed geometry for the stem-layer shape: 7x7 taps, strides 2, three channels
     {{"f32 fxsd k64 b32w2h2 w2x2 m1n2 c3r7s7 s2", 0, 2, 2, 1, F32StemDirect<2, 2>::NBLK, 32, 2, 2, 2, 1, 1, 1, 0, 1.0f, 3, 7, 7,
       F32StemDirect<2, 2>::YS, 2, 2, F32StemDirect<2, 2>::LDS_BYTES, 5.15f, 4.5f, 1},

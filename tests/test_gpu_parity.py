@@ -67,6 +67,11 @@ RAGGED = [
     ("fx_b32", 96, 64, 128, 7, 6, 3, 3, 1, 1),
     ("fx_b32_1x1", 32, 96, 64, 14, 2, 1, 1, 1, 1),
     ("fx_w2h2", 64, 96, 192, 4, 6, 3, 3, 1, 1),
+    # the bf16 kernels that load the Image straight into LDS mask their Out stores: tiles that overhang Out in w, in h and in
+    # k (the second k-tile has 36 channels: one whole 32-row block, then 4 rows of the lanes' first group and none of the second)
+    ("fx_overhang", 64, 64, 100, 9, 5, 3, 3, 1, 1),
+    ("fx_b32_overhang", 32, 32, 72, 8, 3, 3, 3, 1, 1),
+    ("fx_1x1_overhang", 64, 32, 40, 5, 3, 1, 1, 1, 1),
     ("fx_w4h4", 64, 32, 128, 8, 12, 3, 3, 1, 1),
     # more tiles than workgroups (a workgroup walks several tiles), and a filter taller than the fixed b_s
     ("fx_many_tiles", 64, 32, 128, 24, 24, 3, 3, 1, 1),
@@ -147,7 +152,7 @@ def test_every_variant_runs_on_some_ragged_shape(env, dtype):
     fixed-geometry family) every variant launches at least once, the generic ones with at least two tilings."""
     cc, torch = env
     ran = {}
-    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx_stem")
+    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_overhang", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx_stem")
     for shape in RAGGED:
         if shape[0] in pick:
             run_every_variant(cc, torch, shape, dtype, ran)
@@ -267,6 +272,12 @@ def fixed_geometry_case(name):
     return dims, (ct, br, bs), (tw, th)
 
 
+def overhanging(dims, tw):
+    """The same shape with the second tile along w one column short and eight output channels more than a k-tile."""
+    B, C, K, W, H, R, S, sw, sh = dims
+    return (B, C, K + 8, 2 * tw - 1, H, R, S, sw, sh)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_nonfinite_inputs_stay_local_in_fixed_geometry_kernels(env, dtype):
     """The fixed-geometry kernels pad inside LDS (odd contraction lengths pair the last index with a zero, the stem
@@ -278,8 +289,13 @@ def test_nonfinite_inputs_stay_local_in_fixed_geometry_kernels(env, dtype):
     names = {cc.cacnn_variant_name(i): i for i in variants_for(cc, dtype)}
     fx = [n for n in names if " fx" in n]
     assert fx
-    for name in fx:
+    cases = [(name, False) for name in fx] + [(name, True) for name in fx if name.startswith("bf16 fxd ")]
+    for name, ragged in cases:
         dims, (ct, br, bs), (tw, th) = fixed_geometry_case(name)
+        if ragged:
+            if tw < 2:
+                continue
+            dims = overhanging(dims, tw)       # (the kernels that mask their Out stores: a tile that overhangs Out)
         cfg = ci.custom("inf_fx", *dims, dtype=dtype, dist="normal", seed=29)
         img0, flt = ci.make_inputs(cfg)
         assert np.all(flt != 0)

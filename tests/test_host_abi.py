@@ -381,6 +381,10 @@ def _plan_vs_simulator(dims, dtype):
     same_model = (slices >= 2 and R % plan.b_r == 0 and S % plan.b_s == 0 and
                   (sw <= plan.b_r or plan.b_w == 1) and (sh <= plan.b_s or plan.b_h == 1) and
                   plan.b_r % min(sw, R) == 0 and plan.b_s % min(sh, S) == 0)
+    # a fixed-geometry kernel whose tile overhangs Out stages the tile's whole window (what of it lies inside the Image);
+    # the simulator only the rows that the tile's outputs inside Out touch
+    if " fx" in cc.cacnn_variant_name(plan.variant) and (W % plan.b_w or H % plan.b_h):
+        same_model = False
     return plan, sim, same_model
 
 
