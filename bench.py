@@ -585,6 +585,9 @@ ONE_BY_ONE_SHAPES = [
     ("bf16", 128, 256, 384, 13, 13, 3, 3, 1, 1), ("bf16", 128, 384, 256, 13, 13, 3, 3, 1, 1), ("bf16", 64, 96, 256, 27, 27, 1, 1, 1, 1),
     ("bf16", 64, 2048, 1000, 1, 1, 1, 1, 1, 1), ("bf16", 64, 64, 192, 55, 55, 3, 3, 1, 1), ("bf16", 64, 128, 160, 17, 17, 3, 3, 1, 1),
     ("bf16", 128, 512, 512, 13, 13, 1, 1, 1, 1), ("bf16", 64, 160, 320, 10, 10, 3, 3, 1, 1),
+    # the same for the fp32 kernel with 16 x 16 blocks
+    ("f32", 16, 256, 384, 13, 13, 3, 3, 1, 1), ("f32", 8, 96, 256, 27, 27, 1, 1, 1, 1), ("f32", 32, 128, 160, 17, 17, 3, 3, 1, 1),
+    ("f32", 8, 2048, 1000, 1, 1, 1, 1, 1, 1),
 ]
 
 

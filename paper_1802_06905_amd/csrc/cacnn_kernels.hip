@@ -2650,9 +2650,10 @@ struct F32Direct16 {
     static_assert(FLT_ITEMS % PT == 0 && GROUPS % 2 == 0, "direct fp32 16x16 geometry: whole Filter items, even group count");
     static_assert(IMG_BYTES < 65536 && LDS_BYTES <= 160 * 1024 && 2 * LOADS < 64, "direct fp32 16x16 geometry: LDS offsets, size, load counter");
     static bool matches_host(const KernelArgs& a) {
+        // (W, H and K need not be multiples of the tile: what a tile stages beyond the arrays is zeros or other rows of
+        // the Image, which only reach outputs that are not stored)
         return a.sw == 1 && a.sh == 1 && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
-               a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % TB == 0 && a.W % TW == 0 && a.H % TH == 0 &&
-               a.K % KT == 0 && a.vec_img && a.vec_flt;
+               a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % TB == 0 && a.vec_img && a.vec_flt;
     }
 };
 
@@ -2745,13 +2746,29 @@ __global__ void __launch_bounds__(512) conv_f32_direct16_kernel(const KernelArgs
             --left;
             if (__builtin_expect(--in_tile == 0, 0)) {
                 const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
+                if (tc.k0 + KT <= a.K && tc.w0 + TW <= a.W && tc.h0 + TH <= a.H) {
 #pragma unroll
-                for (int j = 0; j < NBLK; ++j) {
-                    float* const blk = a.out + ((((int64_t)(tc.k0 + wave_id * 16) * a.H + tc.h0 + j) * a.W + tc.w0) * a.B + tc.b0);
+                    for (int j = 0; j < NBLK; ++j) {
+                        float* const blk = a.out + ((((int64_t)(tc.k0 + wave_id * 16) * a.H + tc.h0 + j) * a.W + tc.w0) * a.B + tc.b0);
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        (blk + (int64_t)v * out_kstride)[out_lane] = acc[j][v];
-                        acc[j][v] = 0.f;
+                        for (int v = 0; v < 4; ++v) {
+                            (blk + (int64_t)v * out_kstride)[out_lane] = acc[j][v];
+                            acc[j][v] = 0.f;
+                        }
+                    }
+                } else {
+                    // a tile that overhangs Out: the tile rows inside, this lane's column if it is inside, and of its four
+                    // output channels those inside
+                    const int rows = (tc.w0 + n / TB < a.W) ? a.K - (tc.k0 + wave_id * 16 + q * 4) : 0;
+#pragma unroll
+                    for (int j = 0; j < NBLK; ++j) {
+                        float* const blk = a.out + ((((int64_t)(tc.k0 + wave_id * 16) * a.H + tc.h0 + j) * a.W + tc.w0) * a.B + tc.b0);
+                        const int rows_j = tc.h0 + j < a.H ? rows : 0;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            if (v < rows_j) (blk + (int64_t)v * out_kstride)[out_lane] = acc[j][v];
+                            acc[j][v] = 0.f;
+                        }
                     }
                 }
                 in_tile = upt;
@@ -3085,7 +3102,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 #define CACNN_F32_DIRECT16_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                             \
     {                                                                                                          \
         {NAME, 0, 2, 2, 1, F32Direct16<TW, TH>::NBLK, 8, TW, TH, 2, 1, F32Direct16<TW, TH>::MAXF, 1, -4, 1.0f, 16, 3,    \
-         3, F32Direct16<TW, TH>::YS, 1, 1, F32Direct16<TW, TH>::LDS_BYTES, UNIT_US, FIXED_US, 0},               \
+         3, F32Direct16<TW, TH>::YS, 1, 1, F32Direct16<TW, TH>::LDS_BYTES, UNIT_US, FIXED_US, 0, 1},               \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!F32Direct16<TW, TH>::matches_host(a) || lds != (size_t)F32Direct16<TW, TH>::LDS_BYTES) return 1; \
@@ -3097,7 +3114,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 #define CACNN_F32_DIRECT16_1X1_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                         \
     {                                                                                                          \
         {NAME, 0, 2, 2, 1, F32Direct16<TW, TH, 1>::NBLK, 8, TW, TH, 2, 1, F32Direct16<TW, TH, 1>::MAXF, 1, -4, 1.0f, 16, 1,    \
-         1, F32Direct16<TW, TH, 1>::YS, 1, 1, F32Direct16<TW, TH, 1>::LDS_BYTES, UNIT_US, FIXED_US, 0},         \
+         1, F32Direct16<TW, TH, 1>::YS, 1, 1, F32Direct16<TW, TH, 1>::LDS_BYTES, UNIT_US, FIXED_US, 0, 1},         \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!F32Direct16<TW, TH, 1>::matches_host(a) || lds != (size_t)F32Direct16<TW, TH, 1>::LDS_BYTES) return 1; \

@@ -81,6 +81,10 @@ RAGGED = [
     # c-slices; a taller filter with more tiles than workgroups
     ("fx16_two_each", 16, 32, 128, 4, 14, 3, 3, 1, 1),
     ("fx16_1x1", 8, 48, 64, 4, 14, 1, 1, 1, 1),
+    # the same kernel with tiles that overhang Out in w (one column of the second tile), h (two rows of seven) and k (36
+    # channels in the second k-tile: two waves' sixteen, four of the third wave's first lane group, none of the fourth's)
+    ("fx16_overhang", 16, 32, 100, 3, 9, 3, 3, 1, 1),
+    ("fx16_1x1_overhang", 8, 32, 72, 3, 9, 1, 1, 1, 1),
     ("fx16_many_tiles_s6", 8, 16, 64, 46, 42, 3, 6, 1, 1),
     # the stem-layer kernel: 7x7 taps, strides 2, three channels; more tiles than workgroups and three k-tiles, so a
     # workgroup walks several tiles and restages its Filter tile
@@ -152,7 +156,7 @@ def test_every_variant_runs_on_some_ragged_shape(env, dtype):
     fixed-geometry family) every variant launches at least once, the generic ones with at least two tilings."""
     cc, torch = env
     ran = {}
-    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_overhang", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx_stem")
+    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_overhang", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx16_overhang", "fx_stem")
     for shape in RAGGED:
         if shape[0] in pick:
             run_every_variant(cc, torch, shape, dtype, ran)
@@ -289,7 +293,7 @@ def test_nonfinite_inputs_stay_local_in_fixed_geometry_kernels(env, dtype):
     names = {cc.cacnn_variant_name(i): i for i in variants_for(cc, dtype)}
     fx = [n for n in names if " fx" in n]
     assert fx
-    cases = [(name, False) for name in fx] + [(name, True) for name in fx if name.startswith("bf16 fxd ")]
+    cases = [(name, False) for name in fx] + [(name, True) for name in fx if name.startswith(("bf16 fxd ", "f32 fxd16 "))]
     for name, ragged in cases:
         dims, (ct, br, bs), (tw, th) = fixed_geometry_case(name)
         if ragged:
