@@ -581,10 +581,13 @@ ONE_BY_ONE_SHAPES = [
     # 32 images (or a multiple that is not one of 64): the fixed-geometry bf16 kernels with 32-image tiles take these
     ("bf16", 32, 128, 128, 56, 56, 3, 3, 1, 1), ("bf16", 32, 512, 512, 14, 14, 3, 3, 1, 1), ("bf16", 96, 128, 128, 28, 28, 3, 3, 1, 1),
     ("bf16", 32, 256, 256, 28, 28, 3, 3, 1, 1), ("bf16", 32, 256, 1024, 14, 14, 1, 1, 1, 1),
-    # W, H or K that no tile divides: the bf16 kernels that load the Image straight into LDS mask their Out stores
+    # W, H, K (or B) that no tile divides: the bf16 kernels that load the Image straight into LDS mask their Out stores
     ("bf16", 128, 256, 384, 13, 13, 3, 3, 1, 1), ("bf16", 128, 384, 256, 13, 13, 3, 3, 1, 1), ("bf16", 64, 96, 256, 27, 27, 1, 1, 1, 1),
     ("bf16", 64, 2048, 1000, 1, 1, 1, 1, 1, 1), ("bf16", 64, 64, 192, 55, 55, 3, 3, 1, 1), ("bf16", 64, 128, 160, 17, 17, 3, 3, 1, 1),
     ("bf16", 128, 512, 512, 13, 13, 1, 1, 1, 1), ("bf16", 64, 160, 320, 10, 10, 3, 3, 1, 1),
+    # fewer images than a tile, or a count that no tile divides (multiples of 8)
+    ("bf16", 48, 64, 64, 14, 14, 3, 3, 1, 1), ("bf16", 8, 512, 512, 7, 7, 3, 3, 1, 1),
+    ("bf16", 24, 64, 64, 56, 56, 3, 3, 1, 1), ("bf16", 16, 256, 512, 14, 14, 1, 1, 1, 1),
     # the same for the fp32 kernel with 16 x 16 blocks
     ("f32", 16, 256, 384, 13, 13, 3, 3, 1, 1), ("f32", 8, 96, 256, 27, 27, 1, 1, 1, 1), ("f32", 32, 128, 160, 17, 17, 3, 3, 1, 1),
     ("f32", 8, 2048, 1000, 1, 1, 1, 1, 1, 1),

@@ -233,7 +233,8 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
         g.lds_bytes = v.fx_lds;
         g.img_items = g.flt_items = 1;
         g.legal = CT == v.fx_ct && bR == v.fx_br && bS == v.fx_bs && g.YS == v.fx_ys && p.sigma_w == v.fx_sw &&
-                  p.sigma_h == v.fx_sh && p.R == bR && p.S % bS == 0 && p.C % CT == 0 && p.B % v.TB == 0 && vec_img &&
+                  p.sigma_h == v.fx_sh && p.R == bR && p.S % bS == 0 && p.C % CT == 0 && vec_img &&
+                  (v.fx_ragged == 2 || p.B % v.TB == 0) &&
                   (v.fx_ragged || (p.W % v.TW == 0 && p.H % v.TH == 0 && p.K % v.KT() == 0));
         if (v.fx_whole && (p.S != bS || p.C != CT)) g.legal = false;
         // staged words are addressed by 32-bit byte offsets from the unit's origin

@@ -49,7 +49,7 @@ struct VariantInfo {
     // fixed part of a launch (first loads, last Out tile, dispatch); the planner prices these kernels with them
     float fx_unit_us = 0.f, fx_fixed_us = 0.f;
     int fx_whole = 0;           // 1: with its own LDS layout, the kernel takes a tile's whole contraction as one unit (C == fx_ct, S == fx_bs)
-    int fx_ragged = 0;          // 1: W, H and K need not be multiples of the tile (the kernel masks its Out stores)
+    int fx_ragged = 0;          // 1: W, H and K need not be multiples of the tile (the kernel masks its Out stores); 2: nor B
     int fx_calib_cus = 0;       // > 0 (bf16): the busy compute units fx_unit_us was measured with.  The chip's bf16 MFMA rate is
                                 // power-limited, so a unit takes longer the more compute units work at once
     int KT() const { return WM * MBLK * 32; }

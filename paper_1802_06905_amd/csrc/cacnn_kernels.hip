@@ -1905,10 +1905,11 @@ struct Bf16DirectFixed {
     static_assert(BUF_BYTES < 65536 && LDS_BYTES <= 160 * 1024, "direct bf16 geometry: LDS offsets and size");
     static_assert(STEPS == 2 && 2 * LOADS < 64, "direct bf16 geometry: two steps per unit, load counter range");
     static bool matches_host(const KernelArgs& a) {
-        // (W, H and K need not be multiples of the tile: what a tile stages beyond the arrays is zeros or other rows of
-        // the Image, which only reach outputs that are not stored)
+        // (W, H, K and B need not be multiples of the tile, B only of the 8 images of a 16-byte load: what a tile stages
+        // beyond the arrays or beyond a row's images is zeros or other rows of the Image, which only reach outputs that
+        // are not stored)
         return a.sw == 1 && a.sh == 1 && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
-               a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % TB == 0 && a.vec_img && a.vec_flt;
+               a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % 8 == 0 && a.vec_img && a.vec_flt;
     }
 };
 
@@ -2133,7 +2134,7 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
             --left;
             if (__builtin_expect(--in_tile == 0, 0)) {
                 const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
-                if (tc.k0 + KT <= a.K && tc.w0 + TW <= a.W && tc.h0 + TH <= a.H) {
+                if (tc.k0 + KT <= a.K && tc.w0 + TW <= a.W && tc.h0 + TH <= a.H && tc.b0 + TB <= a.B) {
 #pragma unroll
                     for (int n = 0; n < NBLK; ++n) {
                         const int hrow = TB == 64 ? n / TW : wn;
@@ -2141,8 +2142,9 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
                         store_block_exact<true>(blk, out_kstride, out_lane, acc[0][n]);
                     }
                 } else {
-                    // a tile that overhangs Out: the blocks of positions inside, the rows of output channels inside
-                    const int rows = a.K - (tc.k0 + wm * 32 + g * 4);
+                    // a tile that overhangs Out: the blocks of positions inside, this lane's image if it is inside, the
+                    // rows of output channels inside
+                    const int rows = (tc.b0 + (TB == 64 ? 32 * wn : 0) + j < a.B) ? a.K - (tc.k0 + wm * 32 + g * 4) : 0;
 #pragma unroll
                     for (int n = 0; n < NBLK; ++n) {
                         const int hrow = TB == 64 ? n / TW : wn;
@@ -3042,7 +3044,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 #define CACNN_DIRECT_VARIANT(NAME, UNIT_US, FIXED_US, CALIB, TW, TH)                                                 \
     {                                                                                                          \
         {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, TH>::NBLK, 64, TW, TH, 2, 1, Bf16DirectFixed<TW, TH>::MAXF, 1, 3, 1.0f, 32, 3,  \
-         1, Bf16DirectFixed<TW, TH>::YS, 1, 1, Bf16DirectFixed<TW, TH>::LDS_BYTES, UNIT_US, FIXED_US, 0, 1, CALIB},       \
+         1, Bf16DirectFixed<TW, TH>::YS, 1, 1, Bf16DirectFixed<TW, TH>::LDS_BYTES, UNIT_US, FIXED_US, 0, 2, CALIB},       \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!Bf16DirectFixed<TW, TH>::matches_host(a) || lds != (size_t)Bf16DirectFixed<TW, TH>::LDS_BYTES) return 1; \
@@ -3054,7 +3056,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 #define CACNN_DIRECT_B32_VARIANT(NAME, UNIT_US, FIXED_US, TW, BR)                                               \
     {                                                                                                          \
         {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, 2, BR, 32>::NBLK, 32, TW, 2, 2, 1, Bf16DirectFixed<TW, 2, BR, 32>::MAXF, 1, BR, 1.0f, 32, BR,  \
-         1, Bf16DirectFixed<TW, 2, BR, 32>::YS, 1, 1, Bf16DirectFixed<TW, 2, BR, 32>::LDS_BYTES, UNIT_US, FIXED_US, 0, 1, 256},  \
+         1, Bf16DirectFixed<TW, 2, BR, 32>::YS, 1, 1, Bf16DirectFixed<TW, 2, BR, 32>::LDS_BYTES, UNIT_US, FIXED_US, 0, 2, 256},  \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!Bf16DirectFixed<TW, 2, BR, 32>::matches_host(a) || lds != (size_t)Bf16DirectFixed<TW, 2, BR, 32>::LDS_BYTES) return 1; \
@@ -3066,7 +3068,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 #define CACNN_DIRECT_1X1_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                               \
     {                                                                                                          \
         {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, TH, 1>::NBLK, 64, TW, TH, 2, 1, Bf16DirectFixed<TW, TH, 1>::MAXF, 1, 1, 1.0f, 32, 1,  \
-         1, Bf16DirectFixed<TW, TH, 1>::YS, 1, 1, Bf16DirectFixed<TW, TH, 1>::LDS_BYTES, UNIT_US, FIXED_US, 0, 1, 256}, \
+         1, Bf16DirectFixed<TW, TH, 1>::YS, 1, 1, Bf16DirectFixed<TW, TH, 1>::LDS_BYTES, UNIT_US, FIXED_US, 0, 2, 256}, \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!Bf16DirectFixed<TW, TH, 1>::matches_host(a) || lds != (size_t)Bf16DirectFixed<TW, TH, 1>::LDS_BYTES) return 1; \

@@ -72,6 +72,9 @@ RAGGED = [
     ("fx_overhang", 64, 64, 100, 9, 5, 3, 3, 1, 1),
     ("fx_b32_overhang", 32, 32, 72, 8, 3, 3, 3, 1, 1),
     ("fx_1x1_overhang", 64, 32, 40, 5, 3, 1, 1, 1, 1),
+    # ... and in b: 40 images (a 64-image tile's lanes beyond 40 store nothing; the second 32-image tile holds 8), 8 images
+    ("fx_b_overhang", 40, 32, 72, 9, 3, 3, 3, 1, 1),
+    ("fx_b8_1x1", 8, 32, 64, 7, 2, 1, 1, 1, 1),
     ("fx_w4h4", 64, 32, 128, 8, 12, 3, 3, 1, 1),
     # more tiles than workgroups (a workgroup walks several tiles), and a filter taller than the fixed b_s
     ("fx_many_tiles", 64, 32, 128, 24, 24, 3, 3, 1, 1),
@@ -156,7 +159,7 @@ def test_every_variant_runs_on_some_ragged_shape(env, dtype):
     fixed-geometry family) every variant launches at least once, the generic ones with at least two tilings."""
     cc, torch = env
     ran = {}
-    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_overhang", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx16_overhang", "fx_stem")
+    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_overhang", "fx_b_overhang", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx16_overhang", "fx_stem")
     for shape in RAGGED:
         if shape[0] in pick:
             run_every_variant(cc, torch, shape, dtype, ran)
@@ -276,10 +279,11 @@ def fixed_geometry_case(name):
     return dims, (ct, br, bs), (tw, th)
 
 
-def overhanging(dims, tw):
-    """The same shape with the second tile along w one column short and eight output channels more than a k-tile."""
+def overhanging(dims, tw, fewer_images):
+    """The same shape with the second tile along w one column short, eight output channels more than a k-tile and, for
+    the kernels that take it, eight images fewer than a tile."""
     B, C, K, W, H, R, S, sw, sh = dims
-    return (B, C, K + 8, 2 * tw - 1, H, R, S, sw, sh)
+    return (B - 8 if fewer_images and B > 8 else B, C, K + 8, 2 * tw - 1, H, R, S, sw, sh)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -299,7 +303,8 @@ def test_nonfinite_inputs_stay_local_in_fixed_geometry_kernels(env, dtype):
         if ragged:
             if tw < 2:
                 continue
-            dims = overhanging(dims, tw)       # (the kernels that mask their Out stores: a tile that overhangs Out)
+            # (the kernels that mask their Out stores: a tile that overhangs Out)
+            dims = overhanging(dims, tw, name.startswith("bf16 "))
         cfg = ci.custom("inf_fx", *dims, dtype=dtype, dist="normal", seed=29)
         img0, flt = ci.make_inputs(cfg)
         assert np.all(flt != 0)
