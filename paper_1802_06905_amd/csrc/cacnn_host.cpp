@@ -213,7 +213,9 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
         // Extents first, in 64 bits: a stride can be anything up to 2^31, and everything below is 32-bit arithmetic on
         // products of these.  A tile whose staged Image range or Filter tile cannot fit twice the largest LDS is refused
         // here; past this check every factor and every product of them stays below 2^20.
-        const int64_t XS = p.sigma_w * (int64_t)(v.TW - 1) + bR, YS = p.sigma_h * (int64_t)(v.TH - 1) + bS;
+        // (a 1 x 1 kernel that takes any strides stages the positions its outputs read, not the range between them)
+        const int64_t XS = v.fx_any_stride ? v.TW : p.sigma_w * (int64_t)(v.TW - 1) + bR,
+                      YS = v.fx_any_stride ? v.TH : p.sigma_h * (int64_t)(v.TH - 1) + bS;
         const double esz0 = v.dtype == CACNN_F32 ? 4.0 : 2.0, cap = 2.0 * 160.0 * 1024.0;
         if (XS < 1 || YS < 1 || (double)XS * (double)YS * (double)CT * (double)v.TB * esz0 > cap ||
             (double)v.KT() * (double)bR * (double)bS * (double)CT * esz0 > cap) {
@@ -232,15 +234,17 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
         // a fixed-geometry kernel: its own LDS layout, contraction tile and strides, a shape the tiles divide exactly
         g.lds_bytes = v.fx_lds;
         g.img_items = g.flt_items = 1;
-        g.legal = CT == v.fx_ct && bR == v.fx_br && bS == v.fx_bs && g.YS == v.fx_ys && p.sigma_w == v.fx_sw &&
-                  p.sigma_h == v.fx_sh && p.R == bR && p.S % bS == 0 && p.C % CT == 0 && vec_img &&
+        g.legal = CT == v.fx_ct && bR == v.fx_br && bS == v.fx_bs && g.YS == v.fx_ys &&
+                  (v.fx_any_stride || (p.sigma_w == v.fx_sw && p.sigma_h == v.fx_sh)) && p.R == bR && p.S % bS == 0 &&
+                  p.C % CT == 0 && vec_img &&
                   (v.fx_ragged == 2 || p.B % v.TB == 0) &&
                   (v.fx_ragged || (p.W % v.TW == 0 && p.H % v.TH == 0 && p.K % v.KT() == 0));
         if (v.fx_whole && (p.S != bS || p.C != CT)) g.legal = false;
         // staged words are addressed by 32-bit byte offsets from the unit's origin
         const double esz = v.dtype == CACNN_F32 ? 4.0 : 2.0;
         const double IHd = (double)(p.sigma_h * (p.H - 1) + p.S);
-        if ((double)(g.XS + 1) * IHd * (double)p.C * (double)p.B * esz >= 2147483648.0) g.legal = false;
+        const double reach = v.fx_any_stride ? (double)p.sigma_w * v.TW + 1.0 : (double)(g.XS + 1);
+        if (reach * IHd * (double)p.C * (double)p.B * esz >= 2147483648.0) g.legal = false;
         if ((double)(v.KT() + 1) * (double)p.R * (double)p.S * (double)p.C * esz >= 2147483648.0) g.legal = false;
         return g;
     }
@@ -331,7 +335,8 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
         // staging items are addressed by 32-bit byte offsets from the unit's origin
         const double esz = v.dtype == CACNN_F32 ? 4.0 : 2.0;
         const double IHd = (double)(p.sigma_h * (p.H - 1) + p.S);
-        if ((double)(g.XS + 1) * IHd * (double)p.C * (double)p.B * esz >= 2147483648.0) g.legal = false;
+        const double reach = v.fx_any_stride ? (double)p.sigma_w * v.TW + 1.0 : (double)(g.XS + 1);
+        if (reach * IHd * (double)p.C * (double)p.B * esz >= 2147483648.0) g.legal = false;
         if ((double)(v.KT() + 1) * (double)p.R * (double)p.S * (double)p.C * esz >= 2147483648.0) g.legal = false;
     }
     return g;

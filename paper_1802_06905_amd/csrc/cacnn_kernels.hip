@@ -1908,8 +1908,9 @@ struct Bf16DirectFixed {
         // (W, H, K and B need not be multiples of the tile, B only of the 8 images of a 16-byte load: what a tile stages
         // beyond the arrays or beyond a row's images is zeros or other rows of the Image, which only reach outputs that
         // are not stored)
-        return a.sw == 1 && a.sh == 1 && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
-               a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % 8 == 0 && a.vec_img && a.vec_flt;
+        // (1 x 1 filters: any strides, a tile stages the TW x TH positions its outputs read and nothing between them)
+        return ((BR == 1 && BS == 1) || (a.sw == 1 && a.sh == 1)) && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS &&
+               a.YS == YS && a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % 8 == 0 && a.vec_img && a.vec_flt;
     }
 };
 
@@ -2023,10 +2024,10 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
 #pragma unroll
         for (int i = 0; i < CPW; ++i) {
             if constexpr (TB == 64) {
-                isoff[i] = (uint32_t)(((i / YS) * a.IH + (i % YS)) * a.C + pw * 8) * row_bytes;
+                isoff[i] = (uint32_t)(((i / YS) * a.sw * a.IH + (i % YS) * a.sh) * a.C + pw * 8) * row_bytes;
             } else {
                 const int c = 4 * i + pw, xy = c >> 1;
-                isoff[i] = (uint32_t)(((xy / YS) * a.IH + (xy % YS)) * a.C + 16 * (c & 1)) * row_bytes;
+                isoff[i] = (uint32_t)(((xy / YS) * a.sw * a.IH + (xy % YS) * a.sh) * a.C + 16 * (c & 1)) * row_bytes;
             }
         }
         // Filter: thread (kl = stid / C8, c8 = stid % C8) fetches the 16 bytes of channels 8*c8.. of output channel kl
@@ -2482,15 +2483,16 @@ __device__ __forceinline__ void f32_direct_stage(const KernelArgs& a, CACNN_LDS(
     // Image: lane L of a chunk load fetches 16-byte piece L % 32 (channel (L % 32) / 2, images 4 * (L % 2)..) of
     // position y + L / 32
     const uint32_t row_bytes = (uint32_t)a.B * 4u;
-    const uint32_t ivoff = (uint32_t)(lane >> 5) * (uint32_t)a.C * row_bytes + (uint32_t)((lane & 31) >> 1) * row_bytes +
-                           (uint32_t)(lane & 1) * 16u;
+    // (strides other than 1 only reach here with 1 x 1 filters: the positions a tile stages are then sigma apart)
+    const uint32_t ivoff = (uint32_t)(lane >> 5) * (uint32_t)a.sh * (uint32_t)a.C * row_bytes +
+                           (uint32_t)((lane & 31) >> 1) * row_bytes + (uint32_t)(lane & 1) * 16u;
     uint32_t isoff[CPW], ildst[CPW];
 #pragma unroll
     for (int i = 0; i < CPW; ++i) {
         // the waves that would run out of chunks fetch the last one again (same words to the same place)
         const int ch = min(pw + GEO::PW * i, GEO::CHUNKS - 1);
         const int x = ch / (YS / 2), yy = ch % (YS / 2);
-        isoff[i] = (uint32_t)((x * a.IH + 2 * yy) * a.C) * row_bytes;
+        isoff[i] = (uint32_t)((x * a.sw * a.IH + 2 * yy * a.sh) * a.C) * row_bytes;
         ildst[i] = (uint32_t)(x * XP + yy * 2 * POS);
     }
     // Filter: thread (kl = stid / 4, c4 = stid % 4) fetches the 16 bytes of channels 4*c4.. of output channel kl for
@@ -2654,7 +2656,8 @@ struct F32Direct16 {
     static bool matches_host(const KernelArgs& a) {
         // (W, H and K need not be multiples of the tile: what a tile stages beyond the arrays is zeros or other rows of
         // the Image, which only reach outputs that are not stored)
-        return a.sw == 1 && a.sh == 1 && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
+        // (1 x 1 filters: any strides, a tile stages the TW x TH positions its outputs read and nothing between them)
+        return (BRS == 1 || (a.sw == 1 && a.sh == 1)) && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
                a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % TB == 0 && a.vec_img && a.vec_flt;
     }
 };
@@ -3056,7 +3059,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 #define CACNN_DIRECT_B32_VARIANT(NAME, UNIT_US, FIXED_US, TW, BR)                                               \
     {                                                                                                          \
         {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, 2, BR, 32>::NBLK, 32, TW, 2, 2, 1, Bf16DirectFixed<TW, 2, BR, 32>::MAXF, 1, BR, 1.0f, 32, BR,  \
-         1, Bf16DirectFixed<TW, 2, BR, 32>::YS, 1, 1, Bf16DirectFixed<TW, 2, BR, 32>::LDS_BYTES, UNIT_US, FIXED_US, 0, 2, 256},  \
+         1, Bf16DirectFixed<TW, 2, BR, 32>::YS, 1, 1, Bf16DirectFixed<TW, 2, BR, 32>::LDS_BYTES, UNIT_US, FIXED_US, 0, 2, 256, BR == 1},  \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!Bf16DirectFixed<TW, 2, BR, 32>::matches_host(a) || lds != (size_t)Bf16DirectFixed<TW, 2, BR, 32>::LDS_BYTES) return 1; \
@@ -3068,7 +3071,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 #define CACNN_DIRECT_1X1_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                               \
     {                                                                                                          \
         {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, TH, 1>::NBLK, 64, TW, TH, 2, 1, Bf16DirectFixed<TW, TH, 1>::MAXF, 1, 1, 1.0f, 32, 1,  \
-         1, Bf16DirectFixed<TW, TH, 1>::YS, 1, 1, Bf16DirectFixed<TW, TH, 1>::LDS_BYTES, UNIT_US, FIXED_US, 0, 2, 256}, \
+         1, Bf16DirectFixed<TW, TH, 1>::YS, 1, 1, Bf16DirectFixed<TW, TH, 1>::LDS_BYTES, UNIT_US, FIXED_US, 0, 2, 256, 1}, \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!Bf16DirectFixed<TW, TH, 1>::matches_host(a) || lds != (size_t)Bf16DirectFixed<TW, TH, 1>::LDS_BYTES) return 1; \
@@ -3116,7 +3119,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 #define CACNN_F32_DIRECT16_1X1_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                         \
     {                                                                                                          \
         {NAME, 0, 2, 2, 1, F32Direct16<TW, TH, 1>::NBLK, 8, TW, TH, 2, 1, F32Direct16<TW, TH, 1>::MAXF, 1, -4, 1.0f, 16, 1,    \
-         1, F32Direct16<TW, TH, 1>::YS, 1, 1, F32Direct16<TW, TH, 1>::LDS_BYTES, UNIT_US, FIXED_US, 0, 1},         \
+         1, F32Direct16<TW, TH, 1>::YS, 1, 1, F32Direct16<TW, TH, 1>::LDS_BYTES, UNIT_US, FIXED_US, 0, 1, 0, 1},         \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!F32Direct16<TW, TH, 1>::matches_host(a) || lds != (size_t)F32Direct16<TW, TH, 1>::LDS_BYTES) return 1; \

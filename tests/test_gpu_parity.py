@@ -64,6 +64,9 @@ RAGGED = [
     # shapes the fixed-geometry kernels tile exactly (3x3 taps, unit strides), several tiles and several c-slices
     ("fx_w7", 128, 64, 128, 7, 3, 3, 3, 1, 1),
     ("fx_1x1", 64, 96, 128, 14, 4, 1, 1, 1, 1),
+    # 1 x 1 filters with strides (2, 3) and (2, 2): the tiles stage the positions their outputs read and nothing between
+    ("fx_1x1_strides", 64, 64, 128, 7, 4, 1, 1, 2, 3),
+    ("fx_b32_1x1_strides", 32, 32, 64, 14, 5, 1, 1, 2, 2),
     ("fx_b32", 96, 64, 128, 7, 6, 3, 3, 1, 1),
     ("fx_b32_1x1", 32, 96, 64, 14, 2, 1, 1, 1, 1),
     ("fx_w2h2", 64, 96, 192, 4, 6, 3, 3, 1, 1),
@@ -88,6 +91,7 @@ RAGGED = [
     # channels in the second k-tile: two waves' sixteen, four of the third wave's first lane group, none of the fourth's)
     ("fx16_overhang", 16, 32, 100, 3, 9, 3, 3, 1, 1),
     ("fx16_1x1_overhang", 8, 32, 72, 3, 9, 1, 1, 1, 1),
+    ("fx16_1x1_strides", 8, 32, 64, 4, 9, 1, 1, 2, 3),
     ("fx16_many_tiles_s6", 8, 16, 64, 46, 42, 3, 6, 1, 1),
     # the stem-layer kernel: 7x7 taps, strides 2, three channels; more tiles than workgroups and three k-tiles, so a
     # workgroup walks several tiles and restages its Filter tile
