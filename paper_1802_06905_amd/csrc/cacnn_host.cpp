@@ -844,8 +844,16 @@ int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, c
     // generic kernels' is a model: choose among those first.
     for (int vi = 0; vi < num_variants() && allow_pipelined; ++vi)
         if (variant(vi).info.dtype == dtype && variant(vi).info.fx_ct > 0) evaluate(vi, *p, mach, &best);
-    if (best.variant < 0 || best.n_wg * 8 < mach.num_cu) {
-        const bool use_lp = planner_uses_lp();
+    // ... unless most of its tiles' outputs lie outside Out (fewer images than a tile holds, mostly): then the generic
+    // kernels, which have tiles of 8 and 16 images, compete with it on the estimated time
+    bool mostly_padding = false;
+    if (best.variant >= 0) {
+        const VariantInfo& bv = variant(best.variant).info;
+        const double padded = (double)best.n_wg * bv.KT() * bv.NT();
+        mostly_padding = (double)p->B * p->K * p->W * p->H < 0.5 * padded;
+    }
+    if (best.variant < 0 || best.n_wg * 8 < mach.num_cu || mostly_padding) {
+        const bool use_lp = planner_uses_lp() && !(mostly_padding && best.n_wg * 8 >= mach.num_cu);
         if (use_lp) best = Choice();
         const GpuLpTile lp = solve_gpu_lp(*p, dtype, mach);
         for (int vi = 0; vi < num_variants(); ++vi) {

@@ -1882,13 +1882,17 @@ struct FxWalk {
 // TBP: images per tile, 64 or 32.  With 64 a wave column (wn) takes one half of the images and all TW x TH positions; with
 // 32 a row of the tile is 64 bytes, a column block is all 32 images of one position, the tile is two rows high and wave
 // column wn takes row wn.
-template <int TW, int TH, int BRP = 3, int TBP = 64>
+// SWP: the stride, in both directions, the kernel is compiled for (1; 2 for 3 x 3 filters on tiles of 2 x 2 positions: a
+// tile then stages the 5 columns its two output columns read and, of the rows, the two that the unit's filter row reads).
+template <int TW, int TH, int BRP = 3, int TBP = 64, int SWP = 1>
 struct Bf16DirectFixed {
-    static constexpr int TB = TBP, KT = 64, WM = 2, WN = 2, CT = 32, BS = 1, BR = BRP;
+    static constexpr int TB = TBP, KT = 64, WM = 2, WN = 2, CT = 32, BS = 1, BR = BRP, SW = SWP;
     static constexpr int THW = TBP == 64 ? TH : 1;                  // tile rows one wave works on
     static constexpr int NBLK = TW * THW;                           // column blocks per wave
     static constexpr int C8 = CT / 8, STEPS = BS * (CT / 16);
-    static constexpr int XS = TW + BR - 1, YS = TH - 1 + BS;
+    static constexpr int XS = SWP * (TW - 1) + BR, YS = TH - 1 + BS;  // staged columns; staged rows (one per tile row: BS = 1)
+    static constexpr int YS_HOST = SWP * (TH - 1) + BS;             // the rows between the first and the last of them
+    static_assert(SWP == 1 || (BS == 1 && BRP == 3 && TBP == 64), "direct bf16 geometry: strides with 3 x 3 filters, 64 images");
     static constexpr int ROW = TB * 2;                              // bytes of one (x, y, c) row
     static constexpr int IMG_BYTES = XS * YS * CT * ROW;
     static constexpr int F8 = (BR * BS * C8) | 1;                   // Filter row in 16-byte units, odd: conflict-free
@@ -1909,8 +1913,8 @@ struct Bf16DirectFixed {
         // beyond the arrays or beyond a row's images is zeros or other rows of the Image, which only reach outputs that
         // are not stored)
         // (1 x 1 filters: any strides, a tile stages the TW x TH positions its outputs read and nothing between them)
-        return ((BR == 1 && BS == 1) || (a.sw == 1 && a.sh == 1)) && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS &&
-               a.YS == YS && a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % 8 == 0 && a.vec_img && a.vec_flt;
+        return ((BR == 1 && BS == 1) || (a.sw == SWP && a.sh == SWP)) && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS &&
+               a.YS == YS_HOST && a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % 8 == 0 && a.vec_img && a.vec_flt;
     }
 };
 
@@ -1995,9 +1999,9 @@ __device__ __forceinline__ void load_16_bytes_per_lane_to_lds(__amdgpu_buffer_rs
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (CACNN_LDS(void)*)dst, 16, voff, soff, 0, 0);
 }
 
-template <int TW, int TH, int BRP = 3, int TBP = 64>
+template <int TW, int TH, int BRP = 3, int TBP = 64, int SWP = 1>
 __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs a) {
-    using GEO = Bf16DirectFixed<TW, TH, BRP, TBP>;
+    using GEO = Bf16DirectFixed<TW, TH, BRP, TBP, SWP>;
     constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, BR = GEO::BR, WM = GEO::WM, NBLK = GEO::NBLK;
     constexpr int XS = GEO::XS, YS = GEO::YS, C8 = GEO::C8, F8 = GEO::F8, ROW = GEO::ROW, BUF = GEO::BUF_BYTES;
     constexpr int CTHREADS = GEO::WM * GEO::WN * 64;
@@ -2024,10 +2028,11 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
 #pragma unroll
         for (int i = 0; i < CPW; ++i) {
             if constexpr (TB == 64) {
-                isoff[i] = (uint32_t)(((i / YS) * a.sw * a.IH + (i % YS) * a.sh) * a.C + pw * 8) * row_bytes;
+                // (columns: the staged range is contiguous, except for 1 x 1 filters, where it is the outputs' own columns)
+                isoff[i] = (uint32_t)(((i / YS) * (BR == 1 ? a.sw : 1) * a.IH + (i % YS) * a.sh) * a.C + pw * 8) * row_bytes;
             } else {
                 const int c = 4 * i + pw, xy = c >> 1;
-                isoff[i] = (uint32_t)(((xy / YS) * a.sw * a.IH + (xy % YS) * a.sh) * a.C + 16 * (c & 1)) * row_bytes;
+                isoff[i] = (uint32_t)(((xy / YS) * (BR == 1 ? a.sw : 1) * a.IH + (xy % YS) * a.sh) * a.C + 16 * (c & 1)) * row_bytes;
             }
         }
         // Filter: thread (kl = stid / C8, c8 = stid % C8) fetches the 16 bytes of channels 8*c8.. of output channel kl
@@ -2107,7 +2112,7 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
                 for (int h = 0; h < THW; ++h)
 #pragma unroll
                     for (int w = 0; w < TW; ++w)
-                        acc[0][h * TW + w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[set][r], X[set][h][w + r],
+                        acc[0][h * TW + w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[set][r], X[set][h][SWP * w + r],
                                                                                      acc[0][h * TW + w], 0, 0, 0);
         };
         const int64_t out_kstride = (int64_t)a.H * a.W * a.B;      // floats between output channels
@@ -3055,6 +3060,18 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
+// the same for strides 2
+#define CACNN_DIRECT_S2_VARIANT(NAME, UNIT_US, FIXED_US, CALIB, TW, TH)                                         \
+    {                                                                                                          \
+        {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, TH, 3, 64, 2>::NBLK, 64, TW, TH, 2, 1, Bf16DirectFixed<TW, TH, 3, 64, 2>::MAXF, 1, 3, 1.0f, 32, 3,  \
+         1, Bf16DirectFixed<TW, TH, 3, 64, 2>::YS_HOST, 2, 2, Bf16DirectFixed<TW, TH, 3, 64, 2>::LDS_BYTES, UNIT_US, FIXED_US, 0, 2, CALIB},  \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                if (!Bf16DirectFixed<TW, TH, 3, 64, 2>::matches_host(a) || lds != (size_t)Bf16DirectFixed<TW, TH, 3, 64, 2>::LDS_BYTES) return 1; \
+                return launch_kernel(conv_bf16_direct_kernel<TW, TH, 3, 64, 2>, attr_done, 512, a, grid, lds, stream); \
+            }                                                                                                  \
+    }
+
 // the same with 32 images per tile (two rows of TW positions), for 3 x 3 (BR = 3) or 1 x 1 (BR = 1) filters
 #define CACNN_DIRECT_B32_VARIANT(NAME, UNIT_US, FIXED_US, TW, BR)                                               \
     {                                                                                                          \
@@ -3188,6 +3205,7 @@ static const Variant g_variants[] = {
     CACNN_F32_DIRECT16_1X1_VARIANT("f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r1s1", 0.50f, 2.6f, 2, 7),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.0f, 4.5f, 224, 7, 1),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.62f, 4.2f, 196, 2, 2),
+    CACNN_DIRECT_S2_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1 s2", 0.83f, 4.2f, 196, 2, 2),
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1", 0.50f, 4.5f, 7, 1),
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1", 0.30f, 4.2f, 2, 2),
     CACNN_DIRECT_B32_VARIANT("bf16 fxd k64 b32w7h2 w2x2 m1n7 c32r3s1", 1.1f, 4.5f, 7, 3),

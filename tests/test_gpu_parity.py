@@ -78,6 +78,8 @@ RAGGED = [
     # ... and in b: 40 images (a 64-image tile's lanes beyond 40 store nothing; the second 32-image tile holds 8), 8 images
     ("fx_b_overhang", 40, 32, 72, 9, 3, 3, 3, 1, 1),
     ("fx_b8_1x1", 8, 32, 64, 7, 2, 1, 1, 1, 1),
+    # 3 x 3 filters with strides 2 (the bf16 kernel compiled for them), three tiles along w of which the last overhangs
+    ("fx_s2", 64, 64, 128, 5, 6, 3, 3, 2, 2),
     ("fx_w4h4", 64, 32, 128, 8, 12, 3, 3, 1, 1),
     # more tiles than workgroups (a workgroup walks several tiles), and a filter taller than the fixed b_s
     ("fx_many_tiles", 64, 32, 128, 24, 24, 3, 3, 1, 1),
@@ -114,16 +116,17 @@ FORCED_TILES = {"f32": ((1 << 20, 1 << 20, 1 << 20), (3, 2, 1), (16, 3, 3), (32,
 
 
 def staged_tile_fits(cc, cfg, vi, bc, br, bs):
-    """Whether the Image range a tile of this variant stages for the forced contraction tile can fit the LDS at all
-    (variant names carry the position tile as b<TB>w<TW>h<TH>)."""
+    """Whether the Image range and the Filter tile that a tile of this variant stages for the forced contraction tile can
+    fit the LDS at all (variant names carry the tile as k<KT> b<TB>w<TW>h<TH>)."""
     m = re.search(r" b(\d+)w(\d+)h(\d+)", cc.cacnn_variant_name(vi))
     tb, tw, th = (int(x) for x in m.groups())
+    kt = int(re.search(r" k(\d+) ", cc.cacnn_variant_name(vi)).group(1))
     xs = cfg.sigma_w * (tw - 1) + min(br, cfg.R)
     ys = cfg.sigma_h * (th - 1) + min(bs, cfg.S)
     esz = 4 if cfg.dtype == "f32" else 2
     gran = 1 if cfg.dtype == "f32" else 16         # bf16 c-slices are whole 16-channel MFMA steps
     ct = min(-(-bc // gran) * gran, -(-cfg.C // gran) * gran)
-    return xs * ys * ct * tb * esz <= 160 * 1024
+    return (xs * ys * tb + kt * min(br, cfg.R) * min(bs, cfg.S)) * ct * esz <= 160 * 1024
 
 
 def run_every_variant(cc, torch, shape, dtype, ran):
@@ -163,7 +166,7 @@ def test_every_variant_runs_on_some_ragged_shape(env, dtype):
     fixed-geometry family) every variant launches at least once, the generic ones with at least two tilings."""
     cc, torch = env
     ran = {}
-    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_overhang", "fx_b_overhang", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx16_overhang", "fx_stem")
+    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_overhang", "fx_b_overhang", "fx_s2", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx16_overhang", "fx_stem")
     for shape in RAGGED:
         if shape[0] in pick:
             run_every_variant(cc, torch, shape, dtype, ran)
@@ -192,7 +195,9 @@ def test_direct_kernels_with_one_to_seven_units_per_workgroup(env, dtype):
                 C, S = bc * units, 3          # units c-slices, each with all three filter rows
             else:
                 C, S = bc, units              # one c-slice, units filter rows
-            cfg = ci.custom(f"units{units}", tb, C, 64, tw, th, br, S, 1, 1, dtype=dtype, dist="normal", seed=500 + units)
+            m = re.search(r" s(\d+)$", name)
+            stride = int(m.group(1)) if m else 1           # (a kernel compiled for strides 2 says so at the end of its name)
+            cfg = ci.custom(f"units{units}", tb, C, 64, tw, th, br, S, stride, stride, dtype=dtype, dist="normal", seed=500 + units)
             img, flt = ci.make_inputs(cfg)
             ref, ab = gu.oracle_full(cfg, img, flt)
             plan = cc.Plan()
