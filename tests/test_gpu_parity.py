@@ -40,6 +40,30 @@ def test_benchmark_shape_full_array(env, name):
     say(f"[parity] {name} max rel err {e:.3e}")
 
 
+# layers of ordinary networks that the fixed-geometry kernels only take since they mask their Out stores or take strides:
+# 13 x 13 outputs with 384 output channels, a strided 1 x 1 layer, a 3 x 3 layer with strides 2, fewer images than a tile
+LAYERS = [("bf16", 128, 256, 384, 13, 13, 3, 3, 1, 1), ("bf16", 64, 256, 512, 14, 14, 1, 1, 2, 2),
+          ("bf16", 64, 256, 256, 14, 14, 3, 3, 2, 2), ("bf16", 48, 128, 128, 28, 28, 3, 3, 1, 1),
+          ("f32", 16, 128, 192, 13, 13, 3, 3, 1, 1), ("f32", 8, 256, 512, 14, 14, 1, 1, 2, 2)]
+
+
+@pytest.mark.parametrize("layer", LAYERS, ids=["x".join(str(v) for v in l) for l in LAYERS])
+def test_whole_layers_on_the_fixed_geometry_kernels(env, layer):
+    """Whole layers at ordinary sizes through cacnn_conv_forward: the planner gives them a fixed-geometry kernel, and every
+    output element agrees with the oracle (tiles that overhang Out in w, h, k or b; strided staging)."""
+    cc, torch = env
+    dtype, dims = layer[0], layer[1:]
+    cfg = ci.custom("layer", *dims, dtype=dtype, dist="normal", seed=61)
+    plan = cc.cacnn_tile_plan(cfg.dims, gu.dtype_code(cfg))
+    name = cc.cacnn_variant_name(plan.variant)
+    say(f"[parity] layer {layer} planner's kernel '{name}' grid {plan.grid[0]}")
+    assert " fx" in name, name
+    img, flt = ci.make_inputs(cfg)
+    out = gu.run_gpu(cc, torch, cfg, img, flt)
+    ref, ab = gu.oracle_full(cfg, img, flt)
+    gu.assert_parity(cfg, out, ref, ab, f"layer {layer}")
+
+
 # shapes that span several tiles with ragged tails in every dimension, strides, asymmetric filters
 RAGGED = [
     # name, B, C, K, W, H, R, S, sw, sh
