@@ -15,8 +15,9 @@
 // (RS/sigma_w sigma_h)^(1/2) reuse over matmul that the small-filter bound of Section 4.3 expresses.
 //
 // Kernel families in this file, in order: one tile per workgroup (any shape), pipelined persistent, wave-
-// specialised (staging waves + multiplying waves), and fixed-geometry wave-specialised kernels for 3x3 unit-stride
-// shapes and for the 7x7 stride-2 three-channel stem shape; the variant table at the end lists what is compiled.
+// specialised (staging waves + multiplying waves), and fixed-geometry wave-specialised kernels for 3x3 (strides 1, bf16
+// also 2) and 1x1 (any strides) filters and for the 7x7 stride-2 three-channel stem shape; the variant table at the end
+// lists what is compiled.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <type_traits>
@@ -1809,8 +1810,8 @@ __device__ __forceinline__ void lds_done_then_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// Wave-uniform walk over the units this workgroup stages, for the fixed-geometry kernels (b_r = R, a shape the tiles
-// divide exactly): tiles blockIdx.x, blockIdx.x + gridDim.x, ... of the tile list, and within a tile
+// Wave-uniform walk over the units this workgroup stages, for the fixed-geometry kernels (b_r = R; C a multiple of the
+// c-slice): tiles blockIdx.x, blockIdx.x + gridDim.x, ... of the tile list, and within a tile
 // the contraction slices with c fastest, then s.  Per unit it costs a handful of scalar instructions: the staging
 // waves share the SIMD's issue slots with the MFMA stream and get few of them.
 template <int ESZ, int KT, int TB, int TW, int TH, int CT, int BS>
@@ -3199,7 +3200,7 @@ static const Variant g_variants[] = {
                      conv_f32v4_ws_kernel<2, 2, 1, 2, 32, 2, 2, 3, 10>),
     CACNN_WS_VARIANT(0, "f32 ws4 k64 b16w4h2 w2x2 m1n2", 1.0f, 2, 2, 1, 2, 16, 4, 2, 3, 10, -4,
                      conv_f32v4_ws_kernel<2, 2, 1, 2, 16, 4, 2, 3, 10>),
-    // fixed-geometry kernels (3x3 taps, unit strides, shapes the tiles divide exactly)
+    // fixed-geometry kernels (3x3 and 1x1 taps; the first needs shapes its tiles divide exactly, the others mask their Out stores)
     CACNN_F32_DIRECT_VARIANT("f32 fxd k64 b8w4h4 w2x2 m1n2 c16r3s3", 4.4f, 3.0f, 4, 4),
     CACNN_F32_DIRECT16_VARIANT("f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r3s3", 4.1f, 2.6f, 2, 7),
     CACNN_F32_DIRECT16_1X1_VARIANT("f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r1s1", 0.50f, 2.6f, 2, 7),
