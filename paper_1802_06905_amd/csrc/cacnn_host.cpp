@@ -236,7 +236,7 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
         g.img_items = g.flt_items = 1;
         g.legal = CT == v.fx_ct && bR == v.fx_br && bS == v.fx_bs && g.YS == v.fx_ys &&
                   (v.fx_any_stride || (p.sigma_w == v.fx_sw && p.sigma_h == v.fx_sh)) && p.R == bR && p.S % bS == 0 &&
-                  p.C % CT == 0 && vec_img &&
+                  p.C % CT == (v.fx_tail16 ? 16 : 0) && vec_img &&
                   (v.fx_ragged == 2 || p.B % v.TB == 0) &&
                   (v.fx_ragged || (p.W % v.TW == 0 && p.H % v.TH == 0 && p.K % v.KT() == 0));
         if (v.fx_whole && (p.S != bS || p.C != CT)) g.legal = false;
@@ -417,6 +417,7 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
         if (cts.empty() || cts.back() != ct) cts.push_back(ct);
         if (ct == gran) break;
     }
+    if (v.fx_ct > 0) cts.assign(1, v.fx_ct);      // a fixed-geometry kernel has one c-slice (it may exceed a small C)
     const bool vimg = vec_img_ok(v, p);
     bool found = false;
     const int64_t tiles_k = ceil_div(p.K, v.KT()), tiles_b = ceil_div(p.B, v.TB), tiles_w = ceil_div(p.W, v.TW),
@@ -1100,7 +1101,8 @@ int cacnn_conv_forward_with_plan(const cacnn_problem* problem, int dtype, const 
     if (v.dtype != dtype) return CACNN_ERR_UNSUPPORTED;
     if (plan->b_c < 1 || plan->b_r < 1 || plan->b_s < 1) return CACNN_ERR_INVALID_ARG;
     const int64_t Cpad = round_up(problem->C, v.cgran());
-    const int CT = (int)std::min<int64_t>(round_up(plan->b_c, v.cgran()), Cpad);
+    // (a fixed-geometry kernel's c-slice is its own, also where it exceeds a small C)
+    const int CT = v.fx_ct > 0 && plan->b_c == v.fx_ct ? v.fx_ct : (int)std::min<int64_t>(round_up(plan->b_c, v.cgran()), Cpad);
     const int bR = (int)std::min<int64_t>(plan->b_r, problem->R);
     const int bS = (int)std::min<int64_t>(plan->b_s, problem->S);
     if (plan->xcd_split_k < 0) return CACNN_ERR_INVALID_ARG;

@@ -1909,13 +1909,15 @@ struct Bf16DirectFixed {
     static_assert(FLT_ITEMS % PT == 0, "direct bf16 geometry: whole Filter items per thread");
     static_assert(BUF_BYTES < 65536 && LDS_BYTES <= 160 * 1024, "direct bf16 geometry: LDS offsets and size");
     static_assert(STEPS == 2 && 2 * LOADS < 64, "direct bf16 geometry: two steps per unit, load counter range");
-    static bool matches_host(const KernelArgs& a) {
+    // tail16: the kernel instance whose last c-slice holds 16 channels (C = 16 mod 32) instead of the one for C = 0 mod 32
+    static bool matches_host(const KernelArgs& a, bool tail16 = false) {
+        if (a.C % CT != (tail16 ? 16 : 0)) return false;
         // (W, H, K and B need not be multiples of the tile, B only of the 8 images of a 16-byte load: what a tile stages
         // beyond the arrays or beyond a row's images is zeros or other rows of the Image, which only reach outputs that
         // are not stored)
         // (1 x 1 filters: any strides, a tile stages the TW x TH positions its outputs read and nothing between them)
         return ((BR == 1 && BS == 1) || (a.sw == SWP && a.sh == SWP)) && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS &&
-               a.YS == YS_HOST && a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % 8 == 0 && a.vec_img && a.vec_flt;
+               a.YS == YS_HOST && a.R == BR && a.S % BS == 0 && a.B % 8 == 0 && a.vec_img && a.vec_flt;
     }
 };
 
@@ -2000,7 +2002,12 @@ __device__ __forceinline__ void load_16_bytes_per_lane_to_lds(__amdgpu_buffer_rs
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (CACNN_LDS(void)*)dst, 16, voff, soff, 0, 0);
 }
 
-template <int TW, int TH, int BRP = 3, int TBP = 64, int SWP = 1>
+// T16: C is 16 more than a multiple of the 32-channel slice.  The last c-slice of every filter row is then staged like
+// the others (what it fetches beyond channel C are other rows of the arrays, or zeros beyond their ends), but nothing
+// that was fetched from beyond C is ever read from LDS: for the second 16-channel step of such a unit the multiplying
+// waves take zeros for both operands instead of reading fragments (one loop body for both kinds of unit: two bodies
+// side by side cost the compiler its register allocation).
+template <int TW, int TH, int BRP = 3, int TBP = 64, int SWP = 1, bool T16 = false>
 __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs a) {
     using GEO = Bf16DirectFixed<TW, TH, BRP, TBP, SWP>;
     constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, BR = GEO::BR, WM = GEO::WM, NBLK = GEO::NBLK;
@@ -2012,7 +2019,8 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
     const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
     const int lane = tid & 63;
     // units this workgroup works through: its tiles blockIdx.x, blockIdx.x + gridDim.x, ... times the slices of a tile
-    const int upt = (a.C / CT) * (a.S / BS);
+    const int n_c = (a.C + CT - 1) / CT;            // c-slices (the last one half full in the T16 kernels)
+    const int upt = n_c * (a.S / BS);
     int total = 0;
     for (int t = blockIdx.x; t < a.n_tiles; t += gridDim.x) total += upt;
 
@@ -2120,10 +2128,20 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
         const uint32_t out_lane = (uint32_t)(g * 4) * (uint32_t)out_kstride + (uint32_t)((TB == 64 ? 32 * wn : 0) + j);
         int left = total, in_tile = upt, t = blockIdx.x;
         uint32_t boff = 0;
-        // one unit; MORE: another one follows (its buffer is the next of the three)
-        auto unit = [&](auto more) {
+        // one unit; MORE: another one follows (its buffer is the next of the three); half (T16 kernels): its second
+        // 16-channel step lies beyond C
+        auto unit = [&](auto more, bool half) {
             constexpr bool MORE = decltype(more)::value;
-            load_step(al + boff, xl + boff, 1, 1);
+            if (T16 && half) {
+#pragma unroll
+                for (int r = 0; r < BR; ++r) A[1][r] = bf16x8{};
+#pragma unroll
+                for (int h = 0; h < THW; ++h)
+#pragma unroll
+                    for (int x = 0; x < XS; ++x) X[1][h][x] = bf16x8{};
+            } else {
+                load_step(al + boff, xl + boff, 1, 1);
+            }
             mfma_step(0);
             interleave_front_hint<BR * NBLK, 2 * THW * XS + BR, 2>();
             if constexpr (MORE) {
@@ -2167,8 +2185,14 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
         if (left > 0) {
             lds_done_then_barrier_known();      // unit 0 is staged
             load_step(al, xl, 0, 0);
-            while (left > 1) unit(std::true_type{});
-            unit(std::false_type{});
+            // (T16: c is the fastest index of the walk, so every n_c-th unit is a half one, and so is the last of all)
+            int c_left = n_c;
+            while (left > 1) {
+                const bool half = T16 && --c_left == 0;
+                if (half) c_left = n_c;
+                unit(std::true_type{}, half);
+            }
+            unit(std::false_type{}, T16);
         }
     }
 }
@@ -3061,6 +3085,18 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
+// the same for C = 16 mod 32 (BR = 3 or 1)
+#define CACNN_DIRECT_T16_VARIANT(NAME, UNIT_US, FIXED_US, CALIB, TW, TH, BR)                                    \
+    {                                                                                                          \
+        {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, TH, BR>::NBLK, 64, TW, TH, 2, 1, Bf16DirectFixed<TW, TH, BR>::MAXF, 1, BR, 1.0f, 32, BR,  \
+         1, Bf16DirectFixed<TW, TH, BR>::YS, 1, 1, Bf16DirectFixed<TW, TH, BR>::LDS_BYTES, UNIT_US, FIXED_US, 0, 2, CALIB, BR == 1, 1},  \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                if (!Bf16DirectFixed<TW, TH, BR>::matches_host(a, true) || lds != (size_t)Bf16DirectFixed<TW, TH, BR>::LDS_BYTES) return 1; \
+                return launch_kernel(conv_bf16_direct_kernel<TW, TH, BR, 64, 1, true>, attr_done, 512, a, grid, lds, stream); \
+            }                                                                                                  \
+    }
+
 // the same for strides 2
 #define CACNN_DIRECT_S2_VARIANT(NAME, UNIT_US, FIXED_US, CALIB, TW, TH)                                         \
     {                                                                                                          \
@@ -3207,6 +3243,10 @@ static const Variant g_variants[] = {
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.0f, 4.5f, 224, 7, 1),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.62f, 4.2f, 196, 2, 2),
     CACNN_DIRECT_S2_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1 s2", 0.83f, 4.2f, 196, 2, 2),
+    CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1 t16", 1.0f, 4.5f, 224, 7, 1, 3),
+    CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1 t16", 0.62f, 4.2f, 196, 2, 2, 3),
+    CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1 t16", 0.50f, 4.5f, 256, 7, 1, 1),
+    CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1 t16", 0.30f, 4.2f, 256, 2, 2, 1),
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1", 0.50f, 4.5f, 7, 1),
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1", 0.30f, 4.2f, 2, 2),
     CACNN_DIRECT_B32_VARIANT("bf16 fxd k64 b32w7h2 w2x2 m1n7 c32r3s1", 1.1f, 4.5f, 7, 3),

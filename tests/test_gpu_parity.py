@@ -104,6 +104,11 @@ RAGGED = [
     ("fx_b8_1x1", 8, 32, 64, 7, 2, 1, 1, 1, 1),
     # 3 x 3 filters with strides 2 (the bf16 kernel compiled for them), three tiles along w of which the last overhangs
     ("fx_s2", 64, 64, 128, 5, 6, 3, 3, 2, 2),
+    # C = 16 mod 32: the instances of the bf16 kernels whose last c-slice is half full (48 channels: a whole slice and a half
+    # one per filter row; 16 channels: half slices only), 3 x 3 and 1 x 1
+    ("fx_tail16", 64, 48, 128, 7, 4, 3, 3, 1, 1),
+    ("fx_tail16_only", 64, 16, 64, 4, 4, 3, 3, 1, 1),
+    ("fx_tail16_1x1", 64, 80, 64, 7, 2, 1, 1, 1, 2),
     ("fx_w4h4", 64, 32, 128, 8, 12, 3, 3, 1, 1),
     # more tiles than workgroups (a workgroup walks several tiles), and a filter taller than the fixed b_s
     ("fx_many_tiles", 64, 32, 128, 24, 24, 3, 3, 1, 1),
@@ -190,7 +195,7 @@ def test_every_variant_runs_on_some_ragged_shape(env, dtype):
     fixed-geometry family) every variant launches at least once, the generic ones with at least two tilings."""
     cc, torch = env
     ran = {}
-    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_overhang", "fx_b_overhang", "fx_s2", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx16_overhang", "fx_stem")
+    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_overhang", "fx_b_overhang", "fx_s2", "fx_tail16", "fx_tail16_1x1", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx16_overhang", "fx_stem")
     for shape in RAGGED:
         if shape[0] in pick:
             run_every_variant(cc, torch, shape, dtype, ran)
@@ -217,6 +222,8 @@ def test_direct_kernels_with_one_to_seven_units_per_workgroup(env, dtype):
         for units in range(1, 8):
             if bs == 3:
                 C, S = bc * units, 3          # units c-slices, each with all three filter rows
+            elif name.endswith(" t16"):
+                C, S = bc * units - 16, 1     # units c-slices of one filter row, the last one half full
             else:
                 C, S = bc, units              # one c-slice, units filter rows
             m = re.search(r" s(\d+)$", name)
@@ -307,7 +314,7 @@ def fixed_geometry_case(name):
     ct, br, bs = (int(x) for x in re.search(r" c(\d+)r(\d+)s(\d+)", name).groups())
     m = re.search(r" s(\d+)$", name)
     stride = int(m.group(1)) if m else 1
-    C = ct if " fxsd " in name else 2 * ct
+    C = ct if " fxsd " in name else 2 * ct - 16 if name.endswith(" t16") else 2 * ct
     dims = (tb, C, kt, 2 * tw, 2 * th, br, br, stride, stride)
     return dims, (ct, br, bs), (tw, th)
 
