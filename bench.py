@@ -15,6 +15,7 @@ warm-up launches, then exactly K timed launches between two events on the launch
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -297,9 +298,7 @@ def alternative_variants_us(cc, torch, cfg, buffers, steps, warmup):
         name = cc.cacnn_variant_name(vi)
         if vi == chosen.variant or " fx" not in name or not name.startswith(cfg.dtype + " "):
             continue
-        tile = name.split()[-2 if name.endswith(" s2") else -1]            # c32r3s1
-        ct, rest = tile[1:].split("r")
-        br, bs = rest.split("s")
+        ct, br, bs = re.search(r" c(\d+)r(\d+)s(\d+)", name).groups()       # ... c32r3s1 [s2 | t16]
         plan = cc.cacnn_tile_plan(cfg.dims, dt)
         plan.variant, plan.b_c, plan.b_r, plan.b_s = vi, int(ct), int(br), int(bs)
         plan.xcd_split_k = 0
