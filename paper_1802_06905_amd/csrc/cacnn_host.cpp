@@ -471,7 +471,11 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
                         const int64_t full = n_wg / mach.num_cu, rest = n_wg % mach.num_cu;
                         rounds = (double)full * scale((double)mach.num_cu) + (rest ? scale((double)rest) : 0.0);
                     }
-                    cost = (rounds * n_ctiles * (double)v.fx_unit_us + (double)v.fx_fixed_us) * 2400.0;
+                    // a compute unit that runs several tiles one after the other pays, for each one after the first, the
+                    // empty pipeline at the tile's start and the stores at its end (about 2 us, measured on 1 x 1 layers
+                    // of 1 to 4 units per tile); the first tile's share is in the variant's fixed time
+                    const double tile_us = v.fx_calib_cus > 0 ? 2.0 * (per_cu - 1.0) : 0.0;
+                    cost = (rounds * n_ctiles * (double)v.fx_unit_us + tile_us + (double)v.fx_fixed_us) * 2400.0;
                 }
                 if (best->variant < 0 || cost < best->cost) {
                     best->variant = vi;

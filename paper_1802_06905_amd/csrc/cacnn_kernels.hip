@@ -1885,9 +1885,12 @@ struct FxWalk {
 // column wn takes row wn.
 // SWP: the stride, in both directions, the kernel is compiled for (1; 2 for 3 x 3 filters on tiles of 2 x 2 positions: a
 // tile then stages the 5 columns its two output columns read and, of the rows, the two that the unit's filter row reads).
-template <int TW, int TH, int BRP = 3, int TBP = 64, int SWP = 1>
+// CTP: channels per unit, 32 (two 16-channel steps) or, for 1 x 1 filters, 64 (four steps): a 1 x 1 unit has a third of a
+// 3 x 3 unit's MFMAs, too few to cover the barrier it ends with and the two units that its fetches run ahead.
+template <int TW, int TH, int BRP = 3, int TBP = 64, int SWP = 1, int CTP = 32>
 struct Bf16DirectFixed {
-    static constexpr int TB = TBP, KT = 64, WM = 2, WN = 2, CT = 32, BS = 1, BR = BRP, SW = SWP;
+    static constexpr int TB = TBP, KT = 64, WM = 2, WN = 2, CT = CTP, BS = 1, BR = BRP, SW = SWP;
+    static_assert(CTP == 32 || (CTP == 64 && BRP == 1), "direct bf16 geometry: 64-channel units with 1 x 1 filters");
     static constexpr int THW = TBP == 64 ? TH : 1;                  // tile rows one wave works on
     static constexpr int NBLK = TW * THW;                           // column blocks per wave
     static constexpr int C8 = CT / 8, STEPS = BS * (CT / 16);
@@ -1905,10 +1908,10 @@ struct Bf16DirectFixed {
     static constexpr int LOADS = CPW + MAXF;                        // loads one staging wave issues per unit
     static_assert(TBP == 64 || (TBP == 32 && TH == 2), "direct bf16 geometry: 64 images, or 32 images and two rows");
     static_assert(IMG_BYTES % (1024 * PW) == 0, "direct bf16 geometry: whole chunks per staging wave");
-    static_assert(C8 == PW, "direct bf16 geometry: chunk 4 i + p of a unit is staging wave p's i-th");
+    static_assert(C8 % PW == 0, "direct bf16 geometry: chunk 4 i + p of a unit is staging wave p's i-th");
     static_assert(FLT_ITEMS % PT == 0, "direct bf16 geometry: whole Filter items per thread");
     static_assert(BUF_BYTES < 65536 && LDS_BYTES <= 160 * 1024, "direct bf16 geometry: LDS offsets and size");
-    static_assert(STEPS == 2 && 2 * LOADS < 64, "direct bf16 geometry: two steps per unit, load counter range");
+    static_assert(STEPS % 2 == 0 && 2 * LOADS < 64, "direct bf16 geometry: an even number of steps per unit, load counter range");
     // tail16: the kernel instance whose last c-slice holds 16 channels (C = 16 mod 32) instead of the one for C = 0 mod 32
     static bool matches_host(const KernelArgs& a, bool tail16 = false) {
         if (a.C % CT != (tail16 ? 16 : 0)) return false;
@@ -2007,9 +2010,10 @@ __device__ __forceinline__ void load_16_bytes_per_lane_to_lds(__amdgpu_buffer_rs
 // that was fetched from beyond C is ever read from LDS: for the second 16-channel step of such a unit the multiplying
 // waves take zeros for both operands instead of reading fragments (one loop body for both kinds of unit: two bodies
 // side by side cost the compiler its register allocation).
-template <int TW, int TH, int BRP = 3, int TBP = 64, int SWP = 1, bool T16 = false>
+template <int TW, int TH, int BRP = 3, int TBP = 64, int SWP = 1, bool T16 = false, int CTP = 32>
 __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs a) {
-    using GEO = Bf16DirectFixed<TW, TH, BRP, TBP, SWP>;
+    using GEO = Bf16DirectFixed<TW, TH, BRP, TBP, SWP, CTP>;
+    static_assert(!T16 || CTP == 32, "direct bf16 kernel: the half-full last slice is one of 32 channels");
     constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, BR = GEO::BR, WM = GEO::WM, NBLK = GEO::NBLK;
     constexpr int XS = GEO::XS, YS = GEO::YS, C8 = GEO::C8, F8 = GEO::F8, ROW = GEO::ROW, BUF = GEO::BUF_BYTES;
     constexpr int CTHREADS = GEO::WM * GEO::WN * 64;
@@ -2036,25 +2040,32 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
         uint32_t isoff[CPW];
 #pragma unroll
         for (int i = 0; i < CPW; ++i) {
+            // chunk 4 i + pw of the unit: in LDS order, position by position, a position's channels in chunks of 8 (16) rows
+            const int c = GEO::PW * i + pw;
             if constexpr (TB == 64) {
                 // (columns: the staged range is contiguous, except for 1 x 1 filters, where it is the outputs' own columns)
-                isoff[i] = (uint32_t)(((i / YS) * (BR == 1 ? a.sw : 1) * a.IH + (i % YS) * a.sh) * a.C + pw * 8) * row_bytes;
+                const int xy = c / C8, grp = c % C8;
+                isoff[i] = (uint32_t)(((xy / YS) * (BR == 1 ? a.sw : 1) * a.IH + (xy % YS) * a.sh) * a.C + grp * 8) * row_bytes;
             } else {
-                const int c = 4 * i + pw, xy = c >> 1;
-                isoff[i] = (uint32_t)(((xy / YS) * (BR == 1 ? a.sw : 1) * a.IH + (xy % YS) * a.sh) * a.C + 16 * (c & 1)) * row_bytes;
+                const int xy = c / (CT / 16), grp = c % (CT / 16);
+                isoff[i] = (uint32_t)(((xy / YS) * (BR == 1 ? a.sw : 1) * a.IH + (xy % YS) * a.sh) * a.C + 16 * grp) * row_bytes;
             }
         }
         // Filter: thread (kl = stid / C8, c8 = stid % C8) fetches the 16 bytes of channels 8*c8.. of output channel kl
         // for every tap (r, s) of the unit: one global offset and one LDS address per thread, the tap in the
         // instruction (scalar offset of the load, immediate of the store)
-        static_assert(MAXF == BR * BS && PT == KT * C8, "direct bf16 geometry: one Filter item per thread and tap");
-        const int f_c8 = stid % C8, f_kl = stid / C8;
+        // (64-channel units, 1 x 1 filters only: a second item, 32 channels further on)
+        constexpr int TAPS = BR * BS, GQ = C8 / GEO::PW, FSTEP = GQ > 1 ? GEO::PW * 16 : C8 * 16;   // LDS bytes between items
+        static_assert(MAXF == TAPS * GQ && PT == KT * GEO::PW && (GQ == 1 || TAPS == 1),
+                      "direct bf16 geometry: one Filter item per thread, tap and 32 channels");
+        const int f_c8 = stid % GEO::PW, f_kl = stid / GEO::PW;
         const uint32_t fg0 = ((uint32_t)f_kl * a.R * a.S * a.C + f_c8 * 8) * 2u;
         const uint32_t fl0 = (uint32_t)(uintptr_t)(lds + GEO::IMG_BYTES + (f_kl * F8 + f_c8) * 16);
         const uint32_t fl2 = fl0 + 2 * BUF;
         uint32_t fsoff[MAXF];
 #pragma unroll
-        for (int i = 0; i < MAXF; ++i) fsoff[i] = (uint32_t)((i / BS) * a.S + i % BS) * (uint32_t)a.C * 2u;
+        for (int i = 0; i < MAXF; ++i)
+            fsoff[i] = GQ > 1 ? (uint32_t)i * GEO::PW * 16u : (uint32_t)((i / BS) * a.S + i % BS) * (uint32_t)a.C * 2u;
         FxWalk<2, KT, TB, TW, TH, CT, BS> lu;     // next unit to fetch
         lu.init(a);
         u32x4 freg[2][MAXF];
@@ -2063,7 +2074,7 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
             const __amdgpu_buffer_rsrc_t ri = lu.img(a), rf = lu.flt(a);
 #pragma unroll
             for (int i = 0; i < CPW; ++i)
-                load_16_bytes_per_lane_to_lds(ri, lds + boff_issue + (i * C8 + pw) * 1024, ivoff, isoff[i]);
+                load_16_bytes_per_lane_to_lds(ri, lds + boff_issue + (i * GEO::PW + pw) * 1024, ivoff, isoff[i]);
 #pragma unroll
             for (int i = 0; i < MAXF; ++i) {
                 const uint4 v = buf_load_u4(rf, fg0, fsoff[i]);
@@ -2079,9 +2090,9 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
             // the buffer offset goes into the instruction (the third buffer is beyond the 16-bit field: second base
             // register), chosen by a scalar branch: a vector add here would wait for the vector issue port, which
             // the MFMA stream of the SIMD's other wave hardly ever leaves free
-            if (boff_store == 0) lds_store16_seq<0, C8 * 16>(fl0, freg[set], std::make_index_sequence<MAXF>{});
-            else if (boff_store == BUF) lds_store16_seq<BUF, C8 * 16>(fl0, freg[set], std::make_index_sequence<MAXF>{});
-            else lds_store16_seq<0, C8 * 16>(fl2, freg[set], std::make_index_sequence<MAXF>{});
+            if (boff_store == 0) lds_store16_seq<0, FSTEP>(fl0, freg[set], std::make_index_sequence<MAXF>{});
+            else if (boff_store == BUF) lds_store16_seq<BUF, FSTEP>(fl0, freg[set], std::make_index_sequence<MAXF>{});
+            else lds_store16_seq<0, FSTEP>(fl2, freg[set], std::make_index_sequence<MAXF>{});
             lds_done_then_barrier();
             boff_store = boff_store + BUF == GEO::NBUF * BUF ? 0 : boff_store + BUF;
         };
@@ -2144,6 +2155,13 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
             }
             mfma_step(0);
             interleave_front_hint<BR * NBLK, 2 * THW * XS + BR, 2>();
+            // (units of more than two steps: the steps in between, each read under the MFMAs of the one before)
+#pragma unroll
+            for (int st = 1; st + 1 < GEO::STEPS; ++st) {
+                load_step(al + boff, xl + boff, st + 1, (st + 1) & 1);
+                mfma_step(st & 1);
+                interleave_front_hint<BR * NBLK, 2 * THW * XS + BR, 2>();
+            }
             if constexpr (MORE) {
                 // hand the buffer back once the last fragments have landed, read the next unit's first fragments
                 // under this step's MFMAs
@@ -3085,6 +3103,18 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
+// 1 x 1 filters with 64-channel units
+#define CACNN_DIRECT_1X1_C64_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                           \
+    {                                                                                                          \
+        {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, TH, 1, 64, 1, 64>::NBLK, 64, TW, TH, 2, 1, Bf16DirectFixed<TW, TH, 1, 64, 1, 64>::MAXF, 1, 1, 1.0f, 64, 1,  \
+         1, Bf16DirectFixed<TW, TH, 1, 64, 1, 64>::YS, 1, 1, Bf16DirectFixed<TW, TH, 1, 64, 1, 64>::LDS_BYTES, UNIT_US, FIXED_US, 0, 2, 256, 1},  \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                if (!Bf16DirectFixed<TW, TH, 1, 64, 1, 64>::matches_host(a) || lds != (size_t)Bf16DirectFixed<TW, TH, 1, 64, 1, 64>::LDS_BYTES) return 1; \
+                return launch_kernel(conv_bf16_direct_kernel<TW, TH, 1, 64, 1, false, 64>, attr_done, 512, a, grid, lds, stream); \
+            }                                                                                                  \
+    }
+
 // the same for C = 16 mod 32 (BR = 3 or 1)
 #define CACNN_DIRECT_T16_VARIANT(NAME, UNIT_US, FIXED_US, CALIB, TW, TH, BR)                                    \
     {                                                                                                          \
@@ -3249,6 +3279,7 @@ static const Variant g_variants[] = {
     CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1 t16", 0.30f, 4.2f, 256, 2, 2, 1),
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1", 0.50f, 4.5f, 7, 1),
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1", 0.30f, 4.2f, 2, 2),
+    CACNN_DIRECT_1X1_C64_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c64r1s1", 0.52f, 4.2f, 2, 2),
     CACNN_DIRECT_B32_VARIANT("bf16 fxd k64 b32w7h2 w2x2 m1n7 c32r3s1", 1.1f, 4.5f, 7, 3),
     CACNN_DIRECT_B32_VARIANT("bf16 fxd k64 b32w7h2 w2x2 m1n7 c32r1s1", 0.6f, 4.5f, 7, 1),
     CACNN_STAGED_VARIANT("bf16 fxr k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.1f, 4.5f, 224, 7, 1, 1),

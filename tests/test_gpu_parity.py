@@ -141,7 +141,7 @@ def variants_for(cc, dtype):
 
 # the forced contraction tiles; the last two are the ones the fixed-geometry kernels are compiled for
 FORCED_TILES = {"f32": ((1 << 20, 1 << 20, 1 << 20), (3, 2, 1), (16, 3, 3), (32, 3, 1), (16, 1, 1)),
-                "bf16": ((1 << 20, 1 << 20, 1 << 20), (16, 2, 1), (16, 3, 3), (32, 3, 1), (32, 3, 3), (32, 1, 1))}
+                "bf16": ((1 << 20, 1 << 20, 1 << 20), (16, 2, 1), (16, 3, 3), (32, 3, 1), (32, 3, 3), (32, 1, 1), (64, 1, 1))}
 
 
 def staged_tile_fits(cc, cfg, vi, bc, br, bs):
@@ -195,7 +195,7 @@ def test_every_variant_runs_on_some_ragged_shape(env, dtype):
     fixed-geometry family) every variant launches at least once, the generic ones with at least two tilings."""
     cc, torch = env
     ran = {}
-    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_overhang", "fx_b_overhang", "fx_s2", "fx_tail16", "fx_tail16_1x1", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx16_overhang", "fx_stem")
+    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_1x1_strides", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_overhang", "fx_b_overhang", "fx_s2", "fx_tail16", "fx_tail16_1x1", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx16_overhang", "fx_stem")
     for shape in RAGGED:
         if shape[0] in pick:
             run_every_variant(cc, torch, shape, dtype, ran)
