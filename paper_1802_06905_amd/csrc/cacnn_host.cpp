@@ -235,7 +235,9 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
         g.lds_bytes = v.fx_lds;
         g.img_items = g.flt_items = 1;
         g.legal = CT == v.fx_ct && bR == v.fx_br && bS == v.fx_bs && g.YS == v.fx_ys &&
-                  (v.fx_any_stride || (p.sigma_w == v.fx_sw && p.sigma_h == v.fx_sh)) && p.R == bR && p.S % bS == 0 &&
+                  (v.fx_any_stride || (p.sigma_w == v.fx_sw && p.sigma_h == v.fx_sh)) &&
+                  // (the kernels compiled for 1 x 1 filters take any filter one tap at a time)
+                  (p.R == bR || (v.fx_any_stride && bR == 1)) && p.S % bS == 0 &&
                   p.C % CT == (v.fx_tail16 ? 16 : 0) && vec_img &&
                   (v.fx_ragged == 2 || p.B % v.TB == 0) &&
                   (v.fx_ragged || (p.W % v.TW == 0 && p.H % v.TH == 0 && p.K % v.KT() == 0));
@@ -243,7 +245,7 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
         // staged words are addressed by 32-bit byte offsets from the unit's origin
         const double esz = v.dtype == CACNN_F32 ? 4.0 : 2.0;
         const double IHd = (double)(p.sigma_h * (p.H - 1) + p.S);
-        const double reach = v.fx_any_stride ? (double)p.sigma_w * v.TW + 1.0 : (double)(g.XS + 1);
+        const double reach = v.fx_any_stride ? (double)p.sigma_w * v.TW + (double)p.R : (double)(g.XS + 1);
         if (reach * IHd * (double)p.C * (double)p.B * esz >= 2147483648.0) g.legal = false;
         if ((double)(v.KT() + 1) * (double)p.R * (double)p.S * (double)p.C * esz >= 2147483648.0) g.legal = false;
         return g;
@@ -475,7 +477,10 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
                     // empty pipeline at the tile's start and the stores at its end (about 2 us, measured on 1 x 1 layers
                     // of 1 to 4 units per tile); the first tile's share is in the variant's fixed time
                     const double tile_us = v.fx_calib_cus > 0 ? 2.0 * (per_cu - 1.0) : 0.0;
-                    cost = (rounds * n_ctiles * (double)v.fx_unit_us + tile_us + (double)v.fx_fixed_us) * 2400.0;
+                    // (a bf16 kernel compiled for 1 x 1 filters that walks the taps of a larger filter: its units were
+                    // measured to take 1.1 to 1.17 times a 1 x 1 layer's on 3 x 3 layers with strides 2)
+                    const double taps = v.fx_calib_cus > 0 && v.fx_any_stride && (p.R > 1 || p.S > 1) ? 1.12 : 1.0;
+                    cost = (rounds * n_ctiles * (double)v.fx_unit_us * taps + tile_us + (double)v.fx_fixed_us) * 2400.0;
                 }
                 if (best->variant < 0 || cost < best->cost) {
                     best->variant = vi;
@@ -857,8 +862,11 @@ int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, c
         const double padded = (double)best.n_wg * bv.KT() * bv.NT();
         mostly_padding = (double)p->B * p->K * p->W * p->H < 0.5 * padded;
     }
-    if (best.variant < 0 || best.n_wg * 8 < mach.num_cu || mostly_padding) {
-        const bool use_lp = planner_uses_lp() && !(mostly_padding && best.n_wg * 8 >= mach.num_cu);
+    // ... or it is the fp32 kernel for 1 x 1 filters walking the taps of a larger filter, which re-stages the Image once
+    // per tap: there the generic fp32 kernels, whose model is within 10 % of their measured times, win on some layers
+    const bool f32_taps = best.variant >= 0 && dtype == CACNN_F32 && variant(best.variant).info.fx_any_stride && (p->R > 1 || p->S > 1);
+    if (best.variant < 0 || best.n_wg * 8 < mach.num_cu || mostly_padding || f32_taps) {
+        const bool use_lp = planner_uses_lp() && !((mostly_padding || f32_taps) && best.n_wg * 8 >= mach.num_cu);
         if (use_lp) best = Choice();
         const GpuLpTile lp = solve_gpu_lp(*p, dtype, mach);
         for (int vi = 0; vi < num_variants(); ++vi) {

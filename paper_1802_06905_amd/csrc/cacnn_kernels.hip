@@ -1810,14 +1810,15 @@ __device__ __forceinline__ void lds_done_then_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// Wave-uniform walk over the units this workgroup stages, for the fixed-geometry kernels (b_r = R; C a multiple of the
+// Wave-uniform walk over the units this workgroup stages, for the fixed-geometry kernels (C a multiple of the
 // c-slice): tiles blockIdx.x, blockIdx.x + gridDim.x, ... of the tile list, and within a tile
-// the contraction slices with c fastest, then s.  Per unit it costs a handful of scalar instructions: the staging
-// waves share the SIMD's issue slots with the MFMA stream and get few of them.
+// the contraction slices with c fastest, then s, then r in steps of b_r (one step where b_r = R; the kernels compiled
+// for 1 x 1 filters take any filter one tap at a time this way).  Per unit it costs a handful of scalar instructions:
+// the staging waves share the SIMD's issue slots with the MFMA stream and get few of them.
 template <int ESZ, int KT, int TB, int TW, int TH, int CT, int BS>
 struct FxWalk {
-    int t, s0, c0;
-    int64_t img_org, flt_org;      // byte offsets of the current tile's Image / Filter origin (s0 = c0 = 0)
+    int t, r0, s0, c0;
+    int64_t img_org, flt_org;      // byte offsets of the current tile's Image / Filter origin (r0 = s0 = c0 = 0)
     int64_t img_bytes, flt_bytes;  // array sizes
     __device__ __forceinline__ void set_tile(const KernelArgs& a) {
         const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
@@ -1826,7 +1827,7 @@ struct FxWalk {
     }
     __device__ __forceinline__ void init(const KernelArgs& a) {
         t = blockIdx.x;
-        s0 = c0 = 0;
+        r0 = s0 = c0 = 0;
         img_bytes = (int64_t)a.IW * a.IH * a.C * a.B * ESZ;
         flt_bytes = (int64_t)a.K * a.R * a.S * a.C * ESZ;
         if (t < a.n_tiles) set_tile(a);
@@ -1841,10 +1842,10 @@ struct FxWalk {
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>((const char*)base + off), 0, n, 0x00020000);
     }
     __device__ __forceinline__ __amdgpu_buffer_rsrc_t img(const KernelArgs& a) const {
-        return rsrc(a.image, img_org + (int64_t)((uint32_t)(s0 * a.C + c0) * (uint32_t)a.B) * ESZ, img_bytes);
+        return rsrc(a.image, img_org + (int64_t)((uint32_t)((r0 * a.IH + s0) * a.C + c0) * (uint32_t)a.B) * ESZ, img_bytes);
     }
     __device__ __forceinline__ __amdgpu_buffer_rsrc_t flt(const KernelArgs& a) const {
-        return rsrc(a.filter, flt_org + (int64_t)(s0 * a.C + c0) * ESZ, flt_bytes);
+        return rsrc(a.filter, flt_org + (int64_t)((r0 * a.S + s0) * a.C + c0) * ESZ, flt_bytes);
     }
     __device__ __forceinline__ void next(const KernelArgs& a) {
         c0 += CT;
@@ -1853,8 +1854,12 @@ struct FxWalk {
             s0 += BS;
             if (s0 >= a.S) {
                 s0 = 0;
-                t += gridDim.x;
-                if (t < a.n_tiles) set_tile(a);
+                r0 += a.bR;
+                if (r0 >= a.R) {
+                    r0 = 0;
+                    t += gridDim.x;
+                    if (t < a.n_tiles) set_tile(a);
+                }
             }
         }
     }
@@ -1920,7 +1925,7 @@ struct Bf16DirectFixed {
         // are not stored)
         // (1 x 1 filters: any strides, a tile stages the TW x TH positions its outputs read and nothing between them)
         return ((BR == 1 && BS == 1) || (a.sw == SWP && a.sh == SWP)) && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS &&
-               a.YS == YS_HOST && a.R == BR && a.S % BS == 0 && a.B % 8 == 0 && a.vec_img && a.vec_flt;
+               a.YS == YS_HOST && a.R % BR == 0 && (BR == 1 || a.R == BR) && a.S % BS == 0 && a.B % 8 == 0 && a.vec_img && a.vec_flt;
     }
 };
 
@@ -2024,7 +2029,7 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
     const int lane = tid & 63;
     // units this workgroup works through: its tiles blockIdx.x, blockIdx.x + gridDim.x, ... times the slices of a tile
     const int n_c = (a.C + CT - 1) / CT;            // c-slices (the last one half full in the T16 kernels)
-    const int upt = n_c * (a.S / BS);
+    const int upt = n_c * (a.S / BS) * (a.R / BR);      // (R > b_r only in the kernels for 1 x 1 filters: a unit per tap)
     int total = 0;
     for (int t = blockIdx.x; t < a.n_tiles; t += gridDim.x) total += upt;
 
@@ -2706,7 +2711,7 @@ struct F32Direct16 {
         // the Image, which only reach outputs that are not stored)
         // (1 x 1 filters: any strides, a tile stages the TW x TH positions its outputs read and nothing between them)
         return (BRS == 1 || (a.sw == 1 && a.sh == 1)) && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
-               a.R == BR && a.S % BS == 0 && a.C % CT == 0 && a.B % TB == 0 && a.vec_img && a.vec_flt;
+               a.R % BR == 0 && (BRS == 1 || a.R == BR) && a.S % BS == 0 && a.C % CT == 0 && a.B % TB == 0 && a.vec_img && a.vec_flt;
     }
 };
 
@@ -2721,7 +2726,7 @@ __global__ void __launch_bounds__(512) conv_f32_direct16_kernel(const KernelArgs
     const int tid = threadIdx.x;
     const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
     const int lane = tid & 63;
-    const int upt = (a.C / CT) * (a.S / BS);
+    const int upt = (a.C / CT) * (a.S / BS) * (a.R / GEO::BR);      // (R > b_r only in the kernel for 1 x 1 filters: a unit per tap)
     int total = 0;
     for (int t = blockIdx.x; t < a.n_tiles; t += gridDim.x) total += upt;
 
@@ -3272,16 +3277,16 @@ static const Variant g_variants[] = {
     CACNN_F32_DIRECT16_1X1_VARIANT("f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r1s1", 0.50f, 2.6f, 2, 7),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.0f, 4.5f, 224, 7, 1),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.62f, 4.2f, 196, 2, 2),
-    CACNN_DIRECT_S2_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1 s2", 0.83f, 4.2f, 196, 2, 2),
+    CACNN_DIRECT_S2_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1 s2", 0.85f, 4.2f, 224, 2, 2),
     CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1 t16", 1.0f, 4.5f, 224, 7, 1, 3),
     CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1 t16", 0.62f, 4.2f, 196, 2, 2, 3),
-    CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1 t16", 0.50f, 4.5f, 256, 7, 1, 1),
-    CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1 t16", 0.30f, 4.2f, 256, 2, 2, 1),
-    CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1", 0.50f, 4.5f, 7, 1),
-    CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1", 0.30f, 4.2f, 2, 2),
-    CACNN_DIRECT_1X1_C64_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c64r1s1", 0.52f, 4.2f, 2, 2),
+    CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1 t16", 0.57f, 4.5f, 256, 7, 1, 1),
+    CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1 t16", 0.35f, 4.2f, 256, 2, 2, 1),
+    CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1", 0.57f, 4.5f, 7, 1),
+    CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1", 0.35f, 4.2f, 2, 2),
+    CACNN_DIRECT_1X1_C64_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c64r1s1", 0.61f, 4.2f, 2, 2),
     CACNN_DIRECT_B32_VARIANT("bf16 fxd k64 b32w7h2 w2x2 m1n7 c32r3s1", 1.1f, 4.5f, 7, 3),
-    CACNN_DIRECT_B32_VARIANT("bf16 fxd k64 b32w7h2 w2x2 m1n7 c32r1s1", 0.6f, 4.5f, 7, 1),
+    CACNN_DIRECT_B32_VARIANT("bf16 fxd k64 b32w7h2 w2x2 m1n7 c32r1s1", 0.64f, 4.5f, 7, 1),
     CACNN_STAGED_VARIANT("bf16 fxr k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.1f, 4.5f, 224, 7, 1, 1),
     CACNN_STAGED_VARIANT("bf16 fxr k64 b64w2h2 w2x2 m1n4 c32r3s3", 2.0f, 4.2f, 196, 2, 2, 3),
     // fixed geometry for the stem-layer shape: 7x7 taps, strides 2, three channels

@@ -44,7 +44,10 @@ def test_benchmark_shape_full_array(env, name):
 # 13 x 13 outputs with 384 output channels, a strided 1 x 1 layer, a 3 x 3 layer with strides 2, fewer images than a tile
 LAYERS = [("bf16", 128, 256, 384, 13, 13, 3, 3, 1, 1), ("bf16", 64, 256, 512, 14, 14, 1, 1, 2, 2),
           ("bf16", 64, 256, 256, 14, 14, 3, 3, 2, 2), ("bf16", 48, 128, 128, 28, 28, 3, 3, 1, 1),
-          ("f32", 16, 128, 192, 13, 13, 3, 3, 1, 1), ("f32", 8, 256, 512, 14, 14, 1, 1, 2, 2)]
+          ("f32", 16, 128, 192, 13, 13, 3, 3, 1, 1), ("f32", 8, 256, 512, 14, 14, 1, 1, 2, 2),
+          # filters the kernels compiled for 1 x 1 take one tap at a time: 5 x 5, 1 x 7, fp32 3 x 3 with strides 2
+          ("bf16", 64, 96, 128, 13, 13, 5, 5, 1, 1), ("bf16", 32, 128, 128, 17, 17, 1, 7, 1, 1),
+          ("f32", 16, 64, 128, 14, 14, 3, 3, 2, 2)]
 
 
 @pytest.mark.parametrize("layer", LAYERS, ids=["x".join(str(v) for v in l) for l in LAYERS])
@@ -109,6 +112,10 @@ RAGGED = [
     ("fx_tail16", 64, 48, 128, 7, 4, 3, 3, 1, 1),
     ("fx_tail16_only", 64, 16, 64, 4, 4, 3, 3, 1, 1),
     ("fx_tail16_1x1", 64, 80, 64, 7, 2, 1, 1, 1, 2),
+    # filters other than 1 x 1 on the kernels compiled for 1 x 1 (a unit per tap and c-slice): 5 x 5; 3 x 2 with strides
+    # (2, 3) and C = 16 mod 32
+    ("fx_taps_5x5", 64, 64, 128, 5, 3, 5, 5, 1, 1),
+    ("fx_taps_strides", 64, 48, 64, 5, 4, 3, 2, 2, 3),
     ("fx_w4h4", 64, 32, 128, 8, 12, 3, 3, 1, 1),
     # more tiles than workgroups (a workgroup walks several tiles), and a filter taller than the fixed b_s
     ("fx_many_tiles", 64, 32, 128, 24, 24, 3, 3, 1, 1),
@@ -123,6 +130,7 @@ RAGGED = [
     ("fx16_overhang", 16, 32, 100, 3, 9, 3, 3, 1, 1),
     ("fx16_1x1_overhang", 8, 32, 72, 3, 9, 1, 1, 1, 1),
     ("fx16_1x1_strides", 8, 32, 64, 4, 9, 1, 1, 2, 3),
+    ("fx16_taps", 8, 32, 72, 3, 9, 2, 3, 1, 2),
     ("fx16_many_tiles_s6", 8, 16, 64, 46, 42, 3, 6, 1, 1),
     # the stem-layer kernel: 7x7 taps, strides 2, three channels; more tiles than workgroups and three k-tiles, so a
     # workgroup walks several tiles and restages its Filter tile
