@@ -298,7 +298,7 @@ def alternative_variants_us(cc, torch, cfg, buffers, steps, warmup):
         name = cc.cacnn_variant_name(vi)
         if vi == chosen.variant or " fx" not in name or not name.startswith(cfg.dtype + " "):
             continue
-        ct, br, bs = re.search(r" c(\d+)r(\d+)s(\d+)", name).groups()       # ... c32r3s1 [s2 | t16]
+        ct, br, bs = re.search(r" c(\d+)r(\d+)s(\d+)", name).groups()       # ... c32r3s1 [s2 | t8]
         plan = cc.cacnn_tile_plan(cfg.dims, dt)
         plan.variant, plan.b_c, plan.b_r, plan.b_s = vi, int(ct), int(br), int(bs)
         plan.xcd_split_k = 0
@@ -591,9 +591,10 @@ ONE_BY_ONE_SHAPES = [
     ("bf16", 64, 256, 512, 14, 14, 1, 1, 2, 2), ("bf16", 32, 512, 1024, 7, 7, 1, 1, 2, 2), ("bf16", 128, 64, 128, 28, 28, 1, 1, 2, 2),
     # 3 x 3 filters with strides 2
     ("bf16", 64, 128, 128, 28, 28, 3, 3, 2, 2), ("bf16", 64, 256, 256, 14, 14, 3, 3, 2, 2), ("bf16", 128, 512, 512, 7, 7, 3, 3, 2, 2),
-    # C = 16 mod 32
+    # C a multiple of 8 but not of 32 (the first four: 16 mod 32)
     ("bf16", 128, 80, 192, 28, 28, 3, 3, 1, 1), ("bf16", 64, 144, 288, 14, 14, 1, 1, 1, 1), ("bf16", 64, 48, 128, 56, 56, 3, 3, 1, 1),
-    ("bf16", 64, 16, 64, 112, 112, 3, 3, 1, 1),
+    ("bf16", 64, 16, 64, 112, 112, 3, 3, 1, 1), ("bf16", 64, 40, 120, 28, 28, 1, 1, 1, 1), ("bf16", 64, 120, 40, 28, 28, 1, 1, 1, 1),
+    ("bf16", 64, 24, 72, 56, 56, 3, 3, 1, 1), ("bf16", 128, 72, 72, 28, 28, 3, 3, 1, 1),
     # the same for the fp32 kernel with 16 x 16 blocks
     ("f32", 16, 256, 384, 13, 13, 3, 3, 1, 1), ("f32", 8, 96, 256, 27, 27, 1, 1, 1, 1), ("f32", 32, 128, 160, 17, 17, 3, 3, 1, 1),
     ("f32", 8, 2048, 1000, 1, 1, 1, 1, 1, 1), ("f32", 8, 256, 512, 14, 14, 1, 1, 2, 2), ("f32", 16, 64, 128, 28, 28, 1, 1, 2, 2),

@@ -1841,6 +1841,10 @@ struct FxWalk {
         const int32_t n = (hi | (lo >> 31)) ? 0x7fffffff : (int32_t)lo;
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>((const char*)base + off), 0, n, 0x00020000);
     }
+    // a descriptor of length zero: every load through it is out of range, touches no memory and returns zeros
+    static __device__ __forceinline__ __amdgpu_buffer_rsrc_t empty(const void* base) {
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>((const char*)base), 0, 0, 0x00020000);
+    }
     __device__ __forceinline__ __amdgpu_buffer_rsrc_t img(const KernelArgs& a) const {
         return rsrc(a.image, img_org + (int64_t)((uint32_t)((r0 * a.IH + s0) * a.C + c0) * (uint32_t)a.B) * ESZ, img_bytes);
     }
@@ -1917,9 +1921,9 @@ struct Bf16DirectFixed {
     static_assert(FLT_ITEMS % PT == 0, "direct bf16 geometry: whole Filter items per thread");
     static_assert(BUF_BYTES < 65536 && LDS_BYTES <= 160 * 1024, "direct bf16 geometry: LDS offsets and size");
     static_assert(STEPS % 2 == 0 && 2 * LOADS < 64, "direct bf16 geometry: an even number of steps per unit, load counter range");
-    // tail16: the kernel instance whose last c-slice holds 16 channels (C = 16 mod 32) instead of the one for C = 0 mod 32
-    static bool matches_host(const KernelArgs& a, bool tail16 = false) {
-        if (a.C % CT != (tail16 ? 16 : 0)) return false;
+    // tail8: the kernel instance whose last c-slice is not full (C a multiple of 8, not of 32) instead of the one for C = 0 mod 32
+    static bool matches_host(const KernelArgs& a, bool tail8 = false) {
+        if (tail8 ? (a.C % CT == 0 || a.C % 8 != 0) : a.C % CT != 0) return false;
         // (W, H, K and B need not be multiples of the tile, B only of the 8 images of a 16-byte load: what a tile stages
         // beyond the arrays or beyond a row's images is zeros or other rows of the Image, which only reach outputs that
         // are not stored)
@@ -2010,15 +2014,14 @@ __device__ __forceinline__ void load_16_bytes_per_lane_to_lds(__amdgpu_buffer_rs
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (CACNN_LDS(void)*)dst, 16, voff, soff, 0, 0);
 }
 
-// T16: C is 16 more than a multiple of the 32-channel slice.  The last c-slice of every filter row is then staged like
-// the others (what it fetches beyond channel C are other rows of the arrays, or zeros beyond their ends), but nothing
-// that was fetched from beyond C is ever read from LDS: for the second 16-channel step of such a unit the multiplying
-// waves take zeros for both operands instead of reading fragments (one loop body for both kinds of unit: two bodies
-// side by side cost the compiler its register allocation).
-template <int TW, int TH, int BRP = 3, int TBP = 64, int SWP = 1, bool T16 = false, int CTP = 32>
+// T8: C is a multiple of 8 but not of the 32-channel slice.  The staging waves then fill what lies beyond channel C in the
+// last c-slice of every tap with zeros, for both operands, so the multiplying waves need not know: an 8-channel chunk
+// of the Image beyond C is loaded through a descriptor of length zero (the range check returns zeros, which go to LDS
+// like data), and a thread whose 8 Filter channels lie beyond C loads them from an offset no descriptor covers.
+template <int TW, int TH, int BRP = 3, int TBP = 64, int SWP = 1, bool T8 = false, int CTP = 32>
 __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs a) {
     using GEO = Bf16DirectFixed<TW, TH, BRP, TBP, SWP, CTP>;
-    static_assert(!T16 || CTP == 32, "direct bf16 kernel: the half-full last slice is one of 32 channels");
+    static_assert(!T8 || (CTP == 32 && TBP == 64), "direct bf16 kernel: the partly filled last slice is one of 32 channels of 64 images");
     constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, BR = GEO::BR, WM = GEO::WM, NBLK = GEO::NBLK;
     constexpr int XS = GEO::XS, YS = GEO::YS, C8 = GEO::C8, F8 = GEO::F8, ROW = GEO::ROW, BUF = GEO::BUF_BYTES;
     constexpr int CTHREADS = GEO::WM * GEO::WN * 64;
@@ -2028,7 +2031,7 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
     const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
     const int lane = tid & 63;
     // units this workgroup works through: its tiles blockIdx.x, blockIdx.x + gridDim.x, ... times the slices of a tile
-    const int n_c = (a.C + CT - 1) / CT;            // c-slices (the last one half full in the T16 kernels)
+    const int n_c = (a.C + CT - 1) / CT;            // c-slices (the last one partly filled in the T8 kernels)
     const int upt = n_c * (a.S / BS) * (a.R / BR);      // (R > b_r only in the kernels for 1 x 1 filters: a unit per tap)
     int total = 0;
     for (int t = blockIdx.x; t < a.n_tiles; t += gridDim.x) total += upt;
@@ -2065,6 +2068,9 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
                       "direct bf16 geometry: one Filter item per thread, tap and 32 channels");
         const int f_c8 = stid % GEO::PW, f_kl = stid / GEO::PW;
         const uint32_t fg0 = ((uint32_t)f_kl * a.R * a.S * a.C + f_c8 * 8) * 2u;
+        // (T8: in a c-slice that reaches beyond C, a thread whose channels lie beyond C loads from beyond every descriptor's
+        // range, 2^31 or more with the tap's offset and less than 2^32: zeros)
+        const uint32_t fg0_tail = T8 && f_c8 * 8 >= a.C % CT ? 0x80000000u : fg0;
         const uint32_t fl0 = (uint32_t)(uintptr_t)(lds + GEO::IMG_BYTES + (f_kl * F8 + f_c8) * 16);
         const uint32_t fl2 = fl0 + 2 * BUF;
         uint32_t fsoff[MAXF];
@@ -2076,13 +2082,21 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
         u32x4 freg[2][MAXF];
         int boff_issue = 0, boff_store = 0;       // the buffers the next fetch / the next announced unit use
         auto issue = [&](int set) {
-            const __amdgpu_buffer_rsrc_t ri = lu.img(a), rf = lu.flt(a);
+            const __amdgpu_buffer_rsrc_t rf = lu.flt(a);
+            __amdgpu_buffer_rsrc_t ri = lu.img(a);
+            uint32_t fgo = fg0;
+            if constexpr (T8) {
+                // every chunk of this staging wave holds channels 8 pw .. 8 pw + 7 of the slice (C8 == PW)
+                const int c_left = a.C - lu.c0;
+                if (8 * pw >= c_left) ri = lu.empty(a.image);
+                if (c_left < CT) fgo = fg0_tail;
+            }
 #pragma unroll
             for (int i = 0; i < CPW; ++i)
                 load_16_bytes_per_lane_to_lds(ri, lds + boff_issue + (i * GEO::PW + pw) * 1024, ivoff, isoff[i]);
 #pragma unroll
             for (int i = 0; i < MAXF; ++i) {
-                const uint4 v = buf_load_u4(rf, fg0, fsoff[i]);
+                const uint4 v = buf_load_u4(rf, fgo, fsoff[i]);
                 freg[set][i] = u32x4{v.x, v.y, v.z, v.w};
             }
             lu.next(a);
@@ -2144,20 +2158,10 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
         const uint32_t out_lane = (uint32_t)(g * 4) * (uint32_t)out_kstride + (uint32_t)((TB == 64 ? 32 * wn : 0) + j);
         int left = total, in_tile = upt, t = blockIdx.x;
         uint32_t boff = 0;
-        // one unit; MORE: another one follows (its buffer is the next of the three); half (T16 kernels): its second
-        // 16-channel step lies beyond C
-        auto unit = [&](auto more, bool half) {
+        // one unit; MORE: another one follows (its buffer is the next of the three)
+        auto unit = [&](auto more) {
             constexpr bool MORE = decltype(more)::value;
-            if (T16 && half) {
-#pragma unroll
-                for (int r = 0; r < BR; ++r) A[1][r] = bf16x8{};
-#pragma unroll
-                for (int h = 0; h < THW; ++h)
-#pragma unroll
-                    for (int x = 0; x < XS; ++x) X[1][h][x] = bf16x8{};
-            } else {
-                load_step(al + boff, xl + boff, 1, 1);
-            }
+            load_step(al + boff, xl + boff, 1, 1);
             mfma_step(0);
             interleave_front_hint<BR * NBLK, 2 * THW * XS + BR, 2>();
             // (units of more than two steps: the steps in between, each read under the MFMAs of the one before)
@@ -2208,14 +2212,8 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
         if (left > 0) {
             lds_done_then_barrier_known();      // unit 0 is staged
             load_step(al, xl, 0, 0);
-            // (T16: c is the fastest index of the walk, so every n_c-th unit is a half one, and so is the last of all)
-            int c_left = n_c;
-            while (left > 1) {
-                const bool half = T16 && --c_left == 0;
-                if (half) c_left = n_c;
-                unit(std::true_type{}, half);
-            }
-            unit(std::false_type{}, T16);
+            while (left > 1) unit(std::true_type{});
+            unit(std::false_type{});
         }
     }
 }
@@ -3121,7 +3119,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
     }
 
 // the same for C = 16 mod 32 (BR = 3 or 1)
-#define CACNN_DIRECT_T16_VARIANT(NAME, UNIT_US, FIXED_US, CALIB, TW, TH, BR)                                    \
+#define CACNN_DIRECT_T8_VARIANT(NAME, UNIT_US, FIXED_US, CALIB, TW, TH, BR)                                    \
     {                                                                                                          \
         {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, TH, BR>::NBLK, 64, TW, TH, 2, 1, Bf16DirectFixed<TW, TH, BR>::MAXF, 1, BR, 1.0f, 32, BR,  \
          1, Bf16DirectFixed<TW, TH, BR>::YS, 1, 1, Bf16DirectFixed<TW, TH, BR>::LDS_BYTES, UNIT_US, FIXED_US, 0, 2, CALIB, BR == 1, 1},  \
@@ -3278,10 +3276,10 @@ static const Variant g_variants[] = {
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1", 1.0f, 4.5f, 224, 7, 1),
     CACNN_DIRECT_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1", 0.62f, 4.2f, 196, 2, 2),
     CACNN_DIRECT_S2_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1 s2", 0.85f, 4.2f, 224, 2, 2),
-    CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1 t16", 1.0f, 4.5f, 224, 7, 1, 3),
-    CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1 t16", 0.62f, 4.2f, 196, 2, 2, 3),
-    CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1 t16", 0.57f, 4.5f, 256, 7, 1, 1),
-    CACNN_DIRECT_T16_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1 t16", 0.35f, 4.2f, 256, 2, 2, 1),
+    CACNN_DIRECT_T8_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1 t8", 1.0f, 4.5f, 224, 7, 1, 3),
+    CACNN_DIRECT_T8_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1 t8", 0.62f, 4.2f, 196, 2, 2, 3),
+    CACNN_DIRECT_T8_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1 t8", 0.57f, 4.5f, 256, 7, 1, 1),
+    CACNN_DIRECT_T8_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1 t8", 0.35f, 4.2f, 256, 2, 2, 1),
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1", 0.57f, 4.5f, 7, 1),
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1", 0.35f, 4.2f, 2, 2),
     CACNN_DIRECT_1X1_C64_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c64r1s1", 0.61f, 4.2f, 2, 2),

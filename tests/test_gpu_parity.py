@@ -107,11 +107,14 @@ RAGGED = [
     ("fx_b8_1x1", 8, 32, 64, 7, 2, 1, 1, 1, 1),
     # 3 x 3 filters with strides 2 (the bf16 kernel compiled for them), three tiles along w of which the last overhangs
     ("fx_s2", 64, 64, 128, 5, 6, 3, 3, 2, 2),
-    # C = 16 mod 32: the instances of the bf16 kernels whose last c-slice is half full (48 channels: a whole slice and a half
-    # one per filter row; 16 channels: half slices only), 3 x 3 and 1 x 1
+    # C a multiple of 8 but not of 32: the instances of the bf16 kernels whose last c-slice is partly filled (48 channels: a
+    # whole slice and a half one per filter row; 16 or 8 channels: partly filled slices only; tails of 8 and 24), 3 x 3 and 1 x 1
     ("fx_tail16", 64, 48, 128, 7, 4, 3, 3, 1, 1),
     ("fx_tail16_only", 64, 16, 64, 4, 4, 3, 3, 1, 1),
     ("fx_tail16_1x1", 64, 80, 64, 7, 2, 1, 1, 1, 2),
+    ("fx_tail8", 64, 40, 128, 7, 4, 3, 3, 1, 1),
+    ("fx_tail8_only", 64, 8, 64, 4, 4, 3, 3, 1, 1),
+    ("fx_tail24_1x1", 64, 56, 64, 7, 2, 1, 1, 1, 2),
     # filters other than 1 x 1 on the kernels compiled for 1 x 1 (a unit per tap and c-slice): 5 x 5; 3 x 2 with strides
     # (2, 3) and C = 16 mod 32
     ("fx_taps_5x5", 64, 64, 128, 5, 3, 5, 5, 1, 1),
@@ -230,8 +233,8 @@ def test_direct_kernels_with_one_to_seven_units_per_workgroup(env, dtype):
         for units in range(1, 8):
             if bs == 3:
                 C, S = bc * units, 3          # units c-slices, each with all three filter rows
-            elif name.endswith(" t16"):
-                C, S = bc * units - 16, 1     # units c-slices of one filter row, the last one half full
+            elif name.endswith(" t8"):
+                C, S = bc * units - (8, 16, 24)[units % 3], 1     # units c-slices of one filter row, the last one partly filled
             else:
                 C, S = bc, units              # one c-slice, units filter rows
             m = re.search(r" s(\d+)$", name)
@@ -322,7 +325,7 @@ def fixed_geometry_case(name):
     ct, br, bs = (int(x) for x in re.search(r" c(\d+)r(\d+)s(\d+)", name).groups())
     m = re.search(r" s(\d+)$", name)
     stride = int(m.group(1)) if m else 1
-    C = ct if " fxsd " in name else 2 * ct - 16 if name.endswith(" t16") else 2 * ct
+    C = ct if " fxsd " in name else 2 * ct - 24 if name.endswith(" t8") else 2 * ct
     dims = (tb, C, kt, 2 * tw, 2 * th, br, br, stride, stride)
     return dims, (ct, br, bs), (tw, th)
 
@@ -347,7 +350,7 @@ def test_nonfinite_inputs_stay_local_in_fixed_geometry_kernels(env, dtype):
     assert fx
     cases = [(name, False) for name in fx] + [(name, True) for name in fx if name.startswith(("bf16 fxd ", "f32 fxd16 "))]
     # (the kernels compiled for 1 x 1 filters on a 2 x 3 filter, which they take one tap at a time, with an overhanging tile)
-    cases += [(name, "taps") for name in fx if re.search(r"r1s1( t16)?$", name)]
+    cases += [(name, "taps") for name in fx if re.search(r"r1s1( t8)?$", name)]
     for name, ragged in cases:
         dims, (ct, br, bs), (tw, th) = fixed_geometry_case(name)
         if ragged:
