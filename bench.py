@@ -603,6 +603,9 @@ ONE_BY_ONE_SHAPES = [
     ("bf16", 64, 96, 256, 27, 27, 5, 5, 1, 1), ("bf16", 32, 128, 128, 17, 17, 1, 7, 1, 1), ("bf16", 32, 128, 128, 17, 17, 7, 1, 1, 1),
     ("bf16", 64, 64, 64, 28, 28, 7, 7, 1, 1), ("bf16", 64, 64, 128, 14, 14, 5, 5, 2, 2), ("bf16", 64, 48, 128, 27, 27, 5, 5, 1, 1),
     ("f32", 16, 64, 128, 14, 14, 3, 3, 2, 2), ("f32", 16, 96, 256, 27, 27, 5, 5, 1, 1),
+    # stem layers (7 x 7, strides 2, three channels) that the stem kernel's tile of 32 images x 2 x 2 positions x 64 channels
+    # does not divide
+    ("f32", 16, 3, 64, 112, 112, 7, 7, 2, 2), ("f32", 64, 3, 96, 109, 109, 7, 7, 2, 2),
 ]
 
 

@@ -2872,8 +2872,11 @@ struct F32StemDirect {
     static_assert((TW * TH) % WN == 0 && 2 * CPW < 64, "stem geometry: column blocks per wave, load counter range");
     static_assert(IMG_BYTES < 65536 && LDS_BYTES <= 160 * 1024, "stem geometry: LDS offsets and size");
     static bool matches_host(const KernelArgs& a) {
+        // (W, H, K and B need not be multiples of the tile, B only of the 4 images of a 16-byte load: what a tile stages
+        // beyond the arrays or beyond a row's images is zeros or other rows of the Image, which only reach outputs that
+        // are not stored; Filter rows beyond K are staged as zeros)
         return a.sw == SW && a.sh == SH && a.R == R && a.S == S && a.C == C && a.bR == R && a.bS == S && a.CT == C &&
-               a.B % TB == 0 && a.W % TW == 0 && a.H % TH == 0 && a.K % KT == 0 && a.vec_img;
+               a.B % 4 == 0 && a.vec_img;
     }
 };
 
@@ -2916,12 +2919,13 @@ __global__ void __launch_bounds__(512) conv_f32_stem_direct_kernel(const KernelA
             float* const s_flt = smem_f + GEO::FLT_OFF / 4;
             constexpr int ROW = R * S * C, TOTAL = KT * ROW, BATCH = 8;
             const float* src = (const float*)a.filter + (int64_t)k0 * ROW;
+            const int have = min(KT, a.K - k0) * ROW;      // (a k-tile that overhangs K: the rows beyond it are zeros)
             for (int e0 = 0; e0 < TOTAL; e0 += BATCH * GEO::PT) {
                 float v[BATCH];
 #pragma unroll
                 for (int u = 0; u < BATCH; ++u) {
                     const int e = e0 + u * GEO::PT + stid;
-                    v[u] = e < TOTAL ? src[e] : 0.f;
+                    v[u] = e < have ? src[e] : 0.f;
                 }
 #pragma unroll
                 for (int u = 0; u < BATCH; ++u) {
@@ -3016,10 +3020,21 @@ __global__ void __launch_bounds__(512) conv_f32_stem_direct_kernel(const KernelA
             }
             asm volatile("" ::: "memory");       // keep the reads above where they are
             // Out tile: block n is output column w_l, row h_l; a lane owns image j
+            if (tc.k0 + KT <= a.K && tc.w0 + TW <= a.W && tc.h0 + TH <= a.H && tc.b0 + TB <= a.B) {
 #pragma unroll
-            for (int nb = 0; nb < NBLK; ++nb) {
-                float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + tc.h0 + wn) * a.W + tc.w0 + nb) * a.B + tc.b0);
-                store_block_exact<true>(blk, out_kstride, out_lane, acc[0][nb]);
+                for (int nb = 0; nb < NBLK; ++nb) {
+                    float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + tc.h0 + wn) * a.W + tc.w0 + nb) * a.B + tc.b0);
+                    store_block_exact<true>(blk, out_kstride, out_lane, acc[0][nb]);
+                }
+            } else {
+                // a tile that overhangs Out: the blocks of positions inside, this lane's image if it is inside, the rows
+                // of output channels inside
+                const int rows = (tc.b0 + j < a.B && tc.h0 + wn < a.H) ? a.K - (tc.k0 + wm * 32 + g * 4) : 0;
+#pragma unroll
+                for (int nb = 0; nb < NBLK; ++nb) {
+                    float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + tc.h0 + wn) * a.W + tc.w0 + nb) * a.B + tc.b0);
+                    store_block_rows(blk, out_kstride, out_lane, acc[0][nb], tc.w0 + nb < a.W ? rows : 0);
+                }
             }
             --left;
             t += gridDim.x;
@@ -3289,7 +3304,7 @@ static const Variant g_variants[] = {
     CACNN_STAGED_VARIANT("bf16 fxr k64 b64w2h2 w2x2 m1n4 c32r3s3", 2.0f, 4.2f, 196, 2, 2, 3),
     // fixed geometry for the stem-layer shape: 7x7 taps, strides 2, three channels
     {{"f32 fxsd k64 b32w2h2 w2x2 m1n2 c3r7s7 s2", 0, 2, 2, 1, F32StemDirect<2, 2>::NBLK, 32, 2, 2, 2, 1, 1, 1, 0, 1.0f, 3, 7, 7,
-      F32StemDirect<2, 2>::YS, 2, 2, F32StemDirect<2, 2>::LDS_BYTES, 5.15f, 4.5f, 1},
+      F32StemDirect<2, 2>::YS, 2, 2, F32StemDirect<2, 2>::LDS_BYTES, 5.15f, 4.5f, 1, 2},
      [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {
          static bool attr_done = false;
          if (!F32StemDirect<2, 2>::matches_host(a) || lds != (size_t)F32StemDirect<2, 2>::LDS_BYTES) return 1;

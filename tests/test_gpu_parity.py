@@ -138,6 +138,8 @@ RAGGED = [
     # the stem-layer kernel: 7x7 taps, strides 2, three channels; more tiles than workgroups and three k-tiles, so a
     # workgroup walks several tiles and restages its Filter tile
     ("fx_stem", 32, 3, 192, 28, 16, 7, 7, 2, 2),
+    # ... with tiles that overhang Out in w, h, k (72 channels) and b (24 images)
+    ("fx_stem_overhang", 24, 3, 72, 27, 15, 7, 7, 2, 2),
 ]
 
 def is_pipelined(name):
@@ -348,7 +350,7 @@ def test_nonfinite_inputs_stay_local_in_fixed_geometry_kernels(env, dtype):
     names = {cc.cacnn_variant_name(i): i for i in variants_for(cc, dtype)}
     fx = [n for n in names if " fx" in n]
     assert fx
-    cases = [(name, False) for name in fx] + [(name, True) for name in fx if name.startswith(("bf16 fxd ", "f32 fxd16 "))]
+    cases = [(name, False) for name in fx] + [(name, True) for name in fx if name.startswith(("bf16 fxd ", "f32 fxd16 ", "f32 fxsd "))]
     # (the kernels compiled for 1 x 1 filters on a 2 x 3 filter, which they take one tap at a time, with an overhanging tile)
     cases += [(name, "taps") for name in fx if re.search(r"r1s1( t8)?$", name)]
     for name, ragged in cases:
@@ -357,7 +359,7 @@ def test_nonfinite_inputs_stay_local_in_fixed_geometry_kernels(env, dtype):
             if tw < 2:
                 continue
             # (the kernels that mask their Out stores: a tile that overhangs Out)
-            dims = overhanging(dims, tw, name.startswith("bf16 "))
+            dims = overhanging(dims, tw, name.startswith(("bf16 ", "f32 fxsd ")))
         if ragged == "taps":
             dims = dims[:5] + (2, 3) + dims[7:]
         cfg = ci.custom("inf_fx", *dims, dtype=dtype, dist="normal", seed=29)
