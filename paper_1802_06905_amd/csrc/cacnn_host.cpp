@@ -854,7 +854,7 @@ int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, c
     // generic kernels' is a model: choose among those first.
     for (int vi = 0; vi < num_variants() && allow_pipelined; ++vi)
         if (variant(vi).info.dtype == dtype && variant(vi).info.fx_ct > 0) evaluate(vi, *p, mach, &best);
-    // ... unless most of its tiles' outputs lie outside Out (fewer images than a tile holds, mostly): then the generic
+    // ... unless half or more of its tiles' outputs lie outside Out (fewer images than a tile holds, mostly): then the generic
     // kernels, which have tiles of 8 and 16 images, compete with it on the estimated time
     bool mostly_padding = false;
     if (best.variant >= 0) {
