@@ -2880,7 +2880,9 @@ struct F32StemDirect {
     }
 };
 
-template <int TW, int TH>
+// RAGGED: the instance for shapes whose tiles overhang Out (the other one stores every tile whole: the test at the end of a
+// tile and the second store path beside the first cost it 2.5 % on the benchmark shape)
+template <int TW, int TH, bool RAGGED>
 __global__ void __launch_bounds__(512) conv_f32_stem_direct_kernel(const KernelArgs a) {
     using GEO = F32StemDirect<TW, TH>;
     constexpr int R = GEO::R, S = GEO::S, C = GEO::C, SW = GEO::SW, SH = GEO::SH;
@@ -2919,7 +2921,7 @@ __global__ void __launch_bounds__(512) conv_f32_stem_direct_kernel(const KernelA
             float* const s_flt = smem_f + GEO::FLT_OFF / 4;
             constexpr int ROW = R * S * C, TOTAL = KT * ROW, BATCH = 8;
             const float* src = (const float*)a.filter + (int64_t)k0 * ROW;
-            const int have = min(KT, a.K - k0) * ROW;      // (a k-tile that overhangs K: the rows beyond it are zeros)
+            const int have = RAGGED ? min(KT, a.K - k0) * ROW : TOTAL;      // (a k-tile that overhangs K: the rows beyond it are zeros)
             for (int e0 = 0; e0 < TOTAL; e0 += BATCH * GEO::PT) {
                 float v[BATCH];
 #pragma unroll
@@ -3020,7 +3022,7 @@ __global__ void __launch_bounds__(512) conv_f32_stem_direct_kernel(const KernelA
             }
             asm volatile("" ::: "memory");       // keep the reads above where they are
             // Out tile: block n is output column w_l, row h_l; a lane owns image j
-            if (tc.k0 + KT <= a.K && tc.w0 + TW <= a.W && tc.h0 + TH <= a.H && tc.b0 + TB <= a.B) {
+            if (!RAGGED || (tc.k0 + KT <= a.K && tc.w0 + TW <= a.W && tc.h0 + TH <= a.H && tc.b0 + TB <= a.B)) {
 #pragma unroll
                 for (int nb = 0; nb < NBLK; ++nb) {
                     float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + tc.h0 + wn) * a.W + tc.w0 + nb) * a.B + tc.b0);
@@ -3308,7 +3310,10 @@ static const Variant g_variants[] = {
      [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {
          static bool attr_done = false;
          if (!F32StemDirect<2, 2>::matches_host(a) || lds != (size_t)F32StemDirect<2, 2>::LDS_BYTES) return 1;
-         return launch_kernel(conv_f32_stem_direct_kernel<2, 2>, attr_done, 512, a, grid, lds, stream);
+         static bool attr_done_ragged = false;
+         if (a.B % 32 == 0 && a.W % 2 == 0 && a.H % 2 == 0 && a.K % 64 == 0)
+             return launch_kernel(conv_f32_stem_direct_kernel<2, 2, false>, attr_done, 512, a, grid, lds, stream);
+         return launch_kernel(conv_f32_stem_direct_kernel<2, 2, true>, attr_done_ragged, 512, a, grid, lds, stream);
      }},
     // wave-specialised, bf16
     CACNN_WS_VARIANT(1, "bf16 ws k128 b32w2h2 w2x2 m2n2", 1.05f, 2, 2, 2, 2, 32, 2, 2, 1, 9, 0,
