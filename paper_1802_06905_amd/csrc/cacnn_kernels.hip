@@ -3135,7 +3135,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
-// the same for C = 16 mod 32 (BR = 3 or 1)
+// the same for C a multiple of 8 but not of 32 (BR = 3 or 1): the staging waves zero-fill the last c-slice
 #define CACNN_DIRECT_T8_VARIANT(NAME, UNIT_US, FIXED_US, CALIB, TW, TH, BR)                                    \
     {                                                                                                          \
         {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, TH, BR>::NBLK, 64, TW, TH, 2, 1, Bf16DirectFixed<TW, TH, BR>::MAXF, 1, BR, 1.0f, 32, BR,  \
