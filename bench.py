@@ -606,6 +606,8 @@ ONE_BY_ONE_SHAPES = [
     # stem layers (7 x 7, strides 2, three channels) that the stem kernel's tile of 32 images x 2 x 2 positions x 64 channels
     # does not divide
     ("f32", 16, 3, 64, 112, 112, 7, 7, 2, 2), ("f32", 64, 3, 96, 109, 109, 7, 7, 2, 2),
+    # fp32 with C a multiple of 4 but not of 16
+    ("f32", 16, 24, 96, 56, 56, 3, 3, 1, 1), ("f32", 8, 40, 120, 28, 28, 1, 1, 1, 1), ("f32", 16, 72, 72, 28, 28, 3, 3, 1, 1),
 ]
 
 

@@ -238,7 +238,7 @@ Geometry make_geometry(const VariantInfo& v, const cacnn_problem& p, int CT, int
                   (v.fx_any_stride || (p.sigma_w == v.fx_sw && p.sigma_h == v.fx_sh)) &&
                   // (the kernels compiled for 1 x 1 filters take any filter one tap at a time)
                   (p.R == bR || (v.fx_any_stride && bR == 1)) && p.S % bS == 0 &&
-                  (v.fx_tail8 ? (p.C % CT != 0 && p.C % 8 == 0) : p.C % CT == 0) && vec_img &&
+                  (v.fx_tail8 == 2 ? p.C % 4 == 0 : v.fx_tail8 ? (p.C % CT != 0 && p.C % 8 == 0) : p.C % CT == 0) && vec_img &&
                   (v.fx_ragged == 2 || p.B % v.TB == 0) &&
                   (v.fx_ragged || (p.W % v.TW == 0 && p.H % v.TH == 0 && p.K % v.KT() == 0));
         if (v.fx_whole && (p.S != bS || p.C != CT)) g.legal = false;

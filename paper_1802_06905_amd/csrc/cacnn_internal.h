@@ -53,7 +53,8 @@ struct VariantInfo {
     int fx_calib_cus = 0;       // > 0 (bf16): the busy compute units fx_unit_us was measured with.  The chip's bf16 MFMA rate is
                                 // power-limited, so a unit takes longer the more compute units work at once
     int fx_any_stride = 0;      // 1 (1 x 1 filters): any strides; a tile stages exactly the TW x TH positions its outputs read
-    int fx_tail8 = 0;           // 1: the instance for C a multiple of 8 but not of fx_ct (the last c-slice partly filled); 0: C = 0 mod fx_ct
+    int fx_tail8 = 0;           // 0: C = 0 mod fx_ct; 1: the instance for C a multiple of 8 but not of fx_ct (the last c-slice partly
+                                // filled); 2 (fp32): any C that is a multiple of 4
     int KT() const { return WM * MBLK * 32; }
     int NT() const { return TB * TW * TH; }
     int threads() const { return WM * WN * (pipelined == 2 ? 128 : 64); }

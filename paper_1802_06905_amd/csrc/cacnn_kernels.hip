@@ -2551,6 +2551,13 @@ __device__ __forceinline__ void f32_direct_stage(const KernelArgs& a, CACNN_LDS(
     static_assert(MAXF == BR * BS && PT == KT * (CT / 4), "direct fp32 geometry: one Filter item per thread and tap");
     const int f_c4 = stid % (CT / 4), f_kl = stid / (CT / 4);
     const uint32_t fg0 = ((uint32_t)f_kl * a.R * a.S * a.C + f_c4 * 4) * 4u;
+    // C not a multiple of the c-slice (the 16 x 16-block kernels, C a multiple of 4): in the last c-slice of a tap the lanes
+    // whose channel lies beyond C fetch from beyond every descriptor's range (2^31 or more with the chunk's or the tap's
+    // offset, less than 2^32), so the range check puts zeros into LDS for both operands and the multiplying waves run
+    // the slice like any other
+    const int c_tail = a.C % CT;
+    const uint32_t ivoff_tail = c_tail && (int)((lane & 31) >> 1) >= c_tail ? 0x80000000u : ivoff;
+    const uint32_t fg0_tail = c_tail && f_c4 * 4 >= c_tail ? 0x80000000u : fg0;
     const uint32_t fl0 = (uint32_t)(uintptr_t)(lds + GEO::FLT_OFF + f_kl * FP + f_c4 * 16);
     uint32_t fsoff[MAXF];
 #pragma unroll
@@ -2561,10 +2568,12 @@ __device__ __forceinline__ void f32_direct_stage(const KernelArgs& a, CACNN_LDS(
     int ioff_issue = 0;                       // Image buffer the next fetch goes to
     auto issue = [&](int set) {
         const __amdgpu_buffer_rsrc_t ri = lu.img(a), rf = lu.flt(a);
+        const bool last = lu.c0 + CT > a.C;
+        const uint32_t ivo = last ? ivoff_tail : ivoff, fgo = last ? fg0_tail : fg0;
 #pragma unroll
-        for (int i = 0; i < CPW; ++i) load_16_bytes_per_lane_to_lds(ri, lds + ioff_issue + ildst[i], ivoff, isoff[i]);
+        for (int i = 0; i < CPW; ++i) load_16_bytes_per_lane_to_lds(ri, lds + ioff_issue + ildst[i], ivo, isoff[i]);
 #pragma unroll
-        for (int i = 0; i < MAXF; ++i) freg[set][i] = buf_load_f32x4(rf, fg0, fsoff[i]);
+        for (int i = 0; i < MAXF; ++i) freg[set][i] = buf_load_f32x4(rf, fgo, fsoff[i]);
         lu.next(a);
         ioff_issue = ioff_issue + IBUF == GEO::NBUF_I * IBUF ? 0 : ioff_issue + IBUF;
     };
@@ -2709,7 +2718,7 @@ struct F32Direct16 {
         // the Image, which only reach outputs that are not stored)
         // (1 x 1 filters: any strides, a tile stages the TW x TH positions its outputs read and nothing between them)
         return (BRS == 1 || (a.sw == 1 && a.sh == 1)) && a.CT == CT && a.bS == BS && a.bR == BR && a.XS == XS && a.YS == YS &&
-               a.R % BR == 0 && (BRS == 1 || a.R == BR) && a.S % BS == 0 && a.C % CT == 0 && a.B % TB == 0 && a.vec_img && a.vec_flt;
+               a.R % BR == 0 && (BRS == 1 || a.R == BR) && a.S % BS == 0 && a.C % 4 == 0 && a.B % TB == 0 && a.vec_img && a.vec_flt;
     }
 };
 
@@ -2724,7 +2733,8 @@ __global__ void __launch_bounds__(512) conv_f32_direct16_kernel(const KernelArgs
     const int tid = threadIdx.x;
     const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the role branch is wave-uniform
     const int lane = tid & 63;
-    const int upt = (a.C / CT) * (a.S / BS) * (a.R / GEO::BR);      // (R > b_r only in the kernel for 1 x 1 filters: a unit per tap)
+    // (R > b_r only in the kernel for 1 x 1 filters: a unit per tap; the last c-slice may be partly filled)
+    const int upt = ((a.C + CT - 1) / CT) * (a.S / BS) * (a.R / GEO::BR);
     int total = 0;
     for (int t = blockIdx.x; t < a.n_tiles; t += gridDim.x) total += upt;
 
@@ -3211,7 +3221,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 #define CACNN_F32_DIRECT16_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                             \
     {                                                                                                          \
         {NAME, 0, 2, 2, 1, F32Direct16<TW, TH>::NBLK, 8, TW, TH, 2, 1, F32Direct16<TW, TH>::MAXF, 1, -4, 1.0f, 16, 3,    \
-         3, F32Direct16<TW, TH>::YS, 1, 1, F32Direct16<TW, TH>::LDS_BYTES, UNIT_US, FIXED_US, 0, 1},               \
+         3, F32Direct16<TW, TH>::YS, 1, 1, F32Direct16<TW, TH>::LDS_BYTES, UNIT_US, FIXED_US, 0, 1, 0, 0, 2},               \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!F32Direct16<TW, TH>::matches_host(a) || lds != (size_t)F32Direct16<TW, TH>::LDS_BYTES) return 1; \
@@ -3223,7 +3233,7 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
 #define CACNN_F32_DIRECT16_1X1_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                         \
     {                                                                                                          \
         {NAME, 0, 2, 2, 1, F32Direct16<TW, TH, 1>::NBLK, 8, TW, TH, 2, 1, F32Direct16<TW, TH, 1>::MAXF, 1, -4, 1.0f, 16, 1,    \
-         1, F32Direct16<TW, TH, 1>::YS, 1, 1, F32Direct16<TW, TH, 1>::LDS_BYTES, UNIT_US, FIXED_US, 0, 1, 0, 1},         \
+         1, F32Direct16<TW, TH, 1>::YS, 1, 1, F32Direct16<TW, TH, 1>::LDS_BYTES, UNIT_US, FIXED_US, 0, 1, 0, 1, 2},         \
             [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
                 static bool attr_done = false;                                                                 \
                 if (!F32Direct16<TW, TH, 1>::matches_host(a) || lds != (size_t)F32Direct16<TW, TH, 1>::LDS_BYTES) return 1; \

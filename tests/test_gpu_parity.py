@@ -134,6 +134,10 @@ RAGGED = [
     ("fx16_1x1_overhang", 8, 32, 72, 3, 9, 1, 1, 1, 1),
     ("fx16_1x1_strides", 8, 32, 64, 4, 9, 1, 1, 2, 3),
     ("fx16_taps", 8, 32, 72, 3, 9, 2, 3, 1, 2),
+    # C a multiple of 4 but not of the 16-channel slice: a slice and a half, a quarter slice only, a slice and a quarter with strides
+    ("fx16_tail", 8, 24, 64, 4, 14, 3, 3, 1, 1),
+    ("fx16_tail_only", 8, 4, 64, 4, 7, 3, 3, 1, 1),
+    ("fx16_tail_1x1", 8, 20, 72, 3, 9, 1, 1, 2, 1),
     ("fx16_many_tiles_s6", 8, 16, 64, 46, 42, 3, 6, 1, 1),
     # the stem-layer kernel: 7x7 taps, strides 2, three channels; more tiles than workgroups and three k-tiles, so a
     # workgroup walks several tiles and restages its Filter tile
@@ -235,6 +239,8 @@ def test_direct_kernels_with_one_to_seven_units_per_workgroup(env, dtype):
         for units in range(1, 8):
             if bs == 3:
                 C, S = bc * units, 3          # units c-slices, each with all three filter rows
+                if " fxd16 " in name:
+                    C -= (0, 4, 8, 12)[units % 4]        # (this kernel takes a partly filled last slice)
             elif name.endswith(" t8"):
                 C, S = bc * units - (8, 16, 24)[units % 3], 1     # units c-slices of one filter row, the last one partly filled
             else:
@@ -327,7 +333,7 @@ def fixed_geometry_case(name):
     ct, br, bs = (int(x) for x in re.search(r" c(\d+)r(\d+)s(\d+)", name).groups())
     m = re.search(r" s(\d+)$", name)
     stride = int(m.group(1)) if m else 1
-    C = ct if " fxsd " in name else 2 * ct - 24 if name.endswith(" t8") else 2 * ct
+    C = ct if " fxsd " in name else 2 * ct - 24 if name.endswith(" t8") else 2 * ct - 4 if " fxd16 " in name else 2 * ct
     dims = (tb, C, kt, 2 * tw, 2 * th, br, br, stride, stride)
     return dims, (ct, br, bs), (tw, th)
 
