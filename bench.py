@@ -606,6 +606,11 @@ ONE_BY_ONE_SHAPES = [
     # stem layers (7 x 7, strides 2, three channels) that the stem kernel's tile of 32 images x 2 x 2 positions x 64 channels
     # does not divide
     ("f32", 16, 3, 64, 112, 112, 7, 7, 2, 2), ("f32", 64, 3, 96, 109, 109, 7, 7, 2, 2),
+    # fewer images than a tile together with a K that no tile divides, odd batch sizes (the planner's worst rows are here:
+    # shallow 56 x 56 layers with 40 or 24 images, which are bound by their Out stores and run best on 8-image tiles)
+    ("bf16", 40, 96, 192, 56, 56, 1, 1, 1, 1), ("bf16", 24, 40, 192, 56, 56, 1, 1, 1, 1), ("bf16", 8, 512, 256, 20, 20, 5, 5, 2, 2),
+    ("bf16", 32, 72, 72, 28, 28, 5, 5, 1, 1), ("bf16", 16, 192, 136, 14, 14, 5, 5, 1, 1), ("bf16", 24, 512, 136, 28, 28, 3, 3, 2, 2),
+    ("bf16", 40, 512, 192, 28, 28, 3, 3, 1, 1), ("bf16", 8, 64, 136, 28, 28, 3, 3, 2, 2),
     # fp32 with C a multiple of 4 but not of 16
     ("f32", 16, 24, 96, 56, 56, 3, 3, 1, 1), ("f32", 8, 40, 120, 28, 28, 1, 1, 1, 1), ("f32", 16, 72, 72, 28, 28, 3, 3, 1, 1),
 ]

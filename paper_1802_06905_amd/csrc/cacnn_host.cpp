@@ -450,7 +450,10 @@ bool evaluate(int vi, const cacnn_problem& p, const cacnn_machine& mach, Choice*
                 // linear combination of them plus a constant, with one set of coefficients per kernel family, fitted
                 // (least squares on the relative error) to the measured launch times of every generic variant on 28
                 // calibration layers (bench.py --planner-sweep calibration).
-                const double ksteps = v.dtype != CACNN_F32 ? (double)p.R * p.S * (Cpad / 16)
+                // (a kernel that reuses Image fragments over three taps r runs a last r-slice of fewer taps at the cost of a
+                // whole one)
+                const double r_run = v.reuse_r > 0 ? (double)round_up(p.R, v.reuse_r) : (double)p.R;
+                const double ksteps = v.dtype != CACNN_F32 ? r_run * p.S * (Cpad / 16)
                                       : v.f32v4()          ? (double)p.R * (double)round_up((int64_t)p.S * Cpad, 8) / 2.0
                                                            : (double)p.R * ceil_div((int64_t)p.S * Cpad, 2);
                 const double t_mfma = (v.dtype == CACNN_F32 ? 64.0 : 32.0) * v.MBLK * v.NBLK * ksteps;
@@ -871,6 +874,12 @@ int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, c
     if (best.variant < 0 || best.n_wg * 8 < mach.num_cu || mostly_padding || f32_taps) {
         const bool use_lp = planner_uses_lp() && !((mostly_padding || f32_taps) && best.n_wg * 8 >= mach.num_cu);
         if (use_lp) best = Choice();
+        // a bf16 fixed-geometry kernel that competes is given a head start of a fifth of its time: on such layers its
+        // price was up to a quarter too high and the generic bf16 kernels' up to a quarter too low, and where the pick was
+        // wrong the generic kernel lost up to 1.5 x, the fixed-geometry one 1.1 x
+        const int fx_variant = best.variant;
+        const double fx_cost = best.cost;
+        if (fx_variant >= 0 && dtype != CACNN_F32) best.cost *= 0.8;
         const GpuLpTile lp = solve_gpu_lp(*p, dtype, mach);
         for (int vi = 0; vi < num_variants(); ++vi) {
             if (variant(vi).info.dtype != dtype) continue;
@@ -879,6 +888,7 @@ int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, c
             if (use_lp) evaluate_lp(vi, *p, mach, lp, &best);
             else evaluate(vi, *p, mach, &best);
         }
+        if (best.variant == fx_variant && fx_variant >= 0) best.cost = fx_cost;
     }
     if (best.variant < 0) return CACNN_ERR_INVALID_ARG;  // nothing fits the given LDS size
     return fill_plan(*p, dtype, mach, best, out);

@@ -2195,14 +2195,28 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
                     }
                 } else {
                     // a tile that overhangs Out: the blocks of positions inside, this lane's image if it is inside, the
-                    // rows of output channels inside
-                    const int rows = (tc.b0 + (TB == 64 ? 32 * wn : 0) + j < a.B) ? a.K - (tc.k0 + wm * 32 + g * 4) : 0;
+                    // rows of output channels inside.  (Where all the tile's output channels are inside, which is every
+                    // tile but the last along k, a block is stored whole or not at all: with fewer images than a tile
+                    // holds every tile comes here, and a test per row made such layers half as fast again.)
+                    const bool lane_in = tc.b0 + (TB == 64 ? 32 * wn : 0) + j < a.B;
+                    const bool k_whole = tc.k0 + KT <= a.K;
+                    const int rows = lane_in ? a.K - (tc.k0 + wm * 32 + g * 4) : 0;
 #pragma unroll
                     for (int n = 0; n < NBLK; ++n) {
                         const int hrow = TB == 64 ? n / TW : wn;
                         const int w = tc.w0 + n % TW, h = tc.h0 + hrow;
                         float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + h) * a.W + w) * a.B + tc.b0);
-                        store_block_rows(blk, out_kstride, out_lane, acc[0][n], (w < a.W && h < a.H) ? rows : 0);
+                        const bool blk_in = w < a.W && h < a.H;
+                        if (k_whole) {
+                            if (blk_in && lane_in) {
+                                store_block_exact<true>(blk, out_kstride, out_lane, acc[0][n]);
+                            } else {
+#pragma unroll
+                                for (int v = 0; v < 16; ++v) acc[0][n][v] = 0.f;
+                            }
+                        } else {
+                            store_block_rows(blk, out_kstride, out_lane, acc[0][n], blk_in ? rows : 0);
+                        }
                     }
                 }
                 in_tile = upt;
