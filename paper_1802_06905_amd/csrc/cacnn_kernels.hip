@@ -1093,6 +1093,9 @@ template <int MBLK, int NBLK, int TB, int TW, int TH>
 __device__ __forceinline__ void write_tile(const KernelArgs& a, const TileCoord& tc, f32x16 (&acc)[MBLK][NBLK],
                                            int nblock0, int row0, int j, int q) {
     constexpr int NT = TB * TW * TH;
+    // whole 128-byte lines per half-wave (tiles of 32 or more images, B a multiple of 32): stream them past the caches,
+    // nobody reads them again; otherwise ordinary stores, so that the L2 puts the pieces of a line together
+    const bool stream = TB >= 32 && a.B % 32 == 0;
 #pragma unroll
     for (int n = 0; n < NBLK; ++n) {
         const int nn = (nblock0 + n) * 32 + j;
@@ -1105,8 +1108,7 @@ __device__ __forceinline__ void write_tile(const KernelArgs& a, const TileCoord&
                 const int k = tc.k0 + row0 + m * 32 + (v >> 2) * 8 + q * 4 + (v & 3);
                 if (pos_ok && k < a.K) {
                     float* dst = &a.out[(((int64_t)k * a.H + h) * a.W + w) * a.B + b];
-                    // whole 128-byte lines per half-wave: stream them past the caches, nobody reads them again
-                    if constexpr (TB >= 32) __builtin_nontemporal_store(acc[m][n][v], dst);
+                    if (stream) __builtin_nontemporal_store(acc[m][n][v], dst);
                     else *dst = acc[m][n][v];
                 }
                 acc[m][n][v] = 0.f;
@@ -1795,12 +1797,13 @@ __device__ __forceinline__ void store_block_exact(float* base, int64_t kstride, 
 }
 
 // The same for a block at the edge of Out: only the rows below `rows` (this lane's count of valid output channels from
-// its first row on) are stored.
+// its first row on) are stored.  Ordinary stores: at an edge the pieces of a cache line come from several instructions
+// and waves, and a streaming store of a partial line was measured to cost up to twice the time.
 __device__ __forceinline__ void store_block_rows(float* base, int64_t kstride, uint32_t lane_off, f32x16& acc, int rows) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int row = (v >> 2) * 8 + (v & 3);
-        if (row < rows) __builtin_nontemporal_store(acc[v], base + (int64_t)row * kstride + lane_off);
+        if (row < rows) base[(int64_t)row * kstride + lane_off] = acc[v];
         acc[v] = 0.f;
     }
 }
@@ -2209,7 +2212,11 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
                         const bool blk_in = w < a.W && h < a.H;
                         if (k_whole) {
                             if (blk_in && lane_in) {
-                                store_block_exact<true>(blk, out_kstride, out_lane, acc[0][n]);
+                                // (ordinary stores where the rows of Out are not whole cache lines: the L2 has to put the
+                                // pieces of a line together before it is written back; streamed, such layers took up to
+                                // twice as long)
+                                if (a.B % 32 == 0) store_block_exact<true>(blk, out_kstride, out_lane, acc[0][n]);
+                                else store_block_exact<false>(blk, out_kstride, out_lane, acc[0][n]);
                             } else {
 #pragma unroll
                                 for (int v = 0; v < 16; ++v) acc[0][n][v] = 0.f;
