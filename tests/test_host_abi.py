@@ -567,3 +567,53 @@ def test_lp_tile_at_l2_and_cache_model_agree_on_the_channel_groups():
         admissible = [a for a in (1, 2, 4, 8) if tiles_k % a == 0]
         from_lp = min(admissible, key=lambda a: abs(math.log(a / want)))
         assert from_lp == l2.a_k, (name, want, l2.a_k)
+
+
+def test_which_shapes_the_fixed_geometry_kernels_accept():
+    """The host's legality rules for the kernels that load the Image straight into LDS, without a GPU: channel counts (bf16:
+    multiples of 32, or of 8 on the instances whose last c-slice is zero-filled; fp32: multiples of 4), filters other than
+    the one a kernel is compiled for (only the 1 x 1 instances walk taps), strides, image counts."""
+    names = {cc.cacnn_variant_name(i): i for i in range(cc.cacnn_variant_count())}
+
+    def accepts(name, dims, dt):
+        try:
+            plan, _ = cc.cacnn_plan_variant(dims, dt, names[name])
+        except cc.CacnnError:
+            return False
+        assert plan.variant == names[name]
+        return True
+
+    w7 = "bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r3s1"
+    assert accepts(w7, (64, 64, 64, 14, 14, 3, 3, 1, 1), 1)
+    assert not accepts(w7, (64, 48, 64, 14, 14, 3, 3, 1, 1), 1)           # C = 16 mod 32: the t8 instance's
+    assert accepts(w7 + " t8", (64, 48, 64, 14, 14, 3, 3, 1, 1), 1)
+    assert accepts(w7 + " t8", (64, 8, 64, 14, 14, 3, 3, 1, 1), 1)
+    assert not accepts(w7 + " t8", (64, 64, 64, 14, 14, 3, 3, 1, 1), 1)   # ... and not the other way round
+    assert not accepts(w7 + " t8", (64, 44, 64, 14, 14, 3, 3, 1, 1), 1)   # 16-byte Filter loads need C % 8 == 0
+    assert not accepts(w7, (64, 64, 64, 14, 14, 3, 3, 2, 2), 1)           # compiled for strides 1
+    assert not accepts(w7, (64, 64, 64, 14, 14, 5, 5, 1, 1), 1)           # compiled for 3 taps along w
+    assert not accepts(w7, (60, 64, 64, 14, 14, 3, 3, 1, 1), 1)           # 16-byte Image loads need B % 8 == 0
+    assert accepts(w7, (40, 64, 100, 13, 9, 3, 3, 1, 1), 1)               # overhang in b, k, w, h
+    one = "bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1"
+    assert accepts(one, (64, 64, 64, 14, 14, 1, 1, 3, 2), 1)              # 1 x 1: any strides
+    assert accepts(one, (64, 64, 64, 14, 14, 5, 7, 2, 1), 1)              # ... and any filter, a tap at a time
+    assert not accepts("bf16 fxd k64 b64w2h2 w2x2 m1n4 c64r1s1", (64, 96, 64, 14, 14, 1, 1, 1, 1), 1)   # 64-channel units
+    assert accepts("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1 s2", (64, 64, 64, 14, 14, 3, 3, 2, 2), 1)
+    assert not accepts("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1 s2", (64, 64, 64, 14, 14, 3, 3, 2, 1), 1)
+    f16 = "f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r3s3"
+    assert accepts(f16, (8, 64, 64, 14, 14, 3, 3, 1, 1), 0)
+    assert accepts(f16, (8, 20, 70, 13, 9, 3, 3, 1, 1), 0)                # C a multiple of 4, overhang in k, w, h
+    assert not accepts(f16, (8, 18, 64, 14, 14, 3, 3, 1, 1), 0)
+    assert not accepts(f16, (12, 64, 64, 14, 14, 3, 3, 1, 1), 0)          # whole 8-image tiles
+    assert not accepts(f16, (8, 64, 64, 14, 14, 5, 5, 1, 1), 0)
+    assert accepts("f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r1s1", (8, 64, 64, 14, 14, 5, 5, 2, 3), 0)
+    stem = "f32 fxsd k64 b32w2h2 w2x2 m1n2 c3r7s7 s2"
+    assert accepts(stem, (32, 3, 64, 112, 112, 7, 7, 2, 2), 0)
+    assert accepts(stem, (20, 3, 72, 27, 15, 7, 7, 2, 2), 0)              # overhang in b, k, w, h
+    assert not accepts(stem, (32, 4, 64, 112, 112, 7, 7, 2, 2), 0)
+    assert not accepts(stem, (32, 3, 64, 112, 112, 7, 7, 1, 1), 0)
+    assert not accepts(stem, (30, 3, 64, 112, 112, 7, 7, 2, 2), 0)        # 16-byte Image loads need B % 4 == 0
+    # and the planner hands such layers to them
+    for dims, dt in (((64, 96, 128, 13, 13, 5, 5, 1, 1), 1), ((64, 40, 120, 28, 28, 3, 3, 1, 1), 1),
+                     ((16, 24, 96, 56, 56, 3, 3, 1, 1), 0), ((64, 3, 96, 109, 109, 7, 7, 2, 2), 0)):
+        assert " fx" in cc.cacnn_variant_name(cc.cacnn_tile_plan(dims, dt).variant), dims
