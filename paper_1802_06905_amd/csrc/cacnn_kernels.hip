@@ -2197,7 +2197,9 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
             --left;
             if (__builtin_expect(--in_tile == 0, 0)) {
                 const TileCoord tc = decode_tile_index(a, t, KT, TB, TW, TH);
-                if (tc.k0 + KT <= a.K && tc.w0 + TW <= a.W && tc.h0 + TH <= a.H && tc.b0 + TB <= a.B) {
+                // (B not a multiple of 32: the rows of Out are not whole cache lines, and every tile takes the path with
+                // ordinary stores)
+                if (tc.k0 + KT <= a.K && tc.w0 + TW <= a.W && tc.h0 + TH <= a.H && tc.b0 + TB <= a.B && a.B % 32 == 0) {
 #pragma unroll
                     for (int n = 0; n < NBLK; ++n) {
                         const int hrow = TB == 64 ? n / TW : wn;
@@ -3061,7 +3063,7 @@ __global__ void __launch_bounds__(512) conv_f32_stem_direct_kernel(const KernelA
             }
             asm volatile("" ::: "memory");       // keep the reads above where they are
             // Out tile: block n is output column w_l, row h_l; a lane owns image j
-            if (!RAGGED || (tc.k0 + KT <= a.K && tc.w0 + TW <= a.W && tc.h0 + TH <= a.H && tc.b0 + TB <= a.B)) {
+            if (!RAGGED || (tc.k0 + KT <= a.K && tc.w0 + TW <= a.W && tc.h0 + TH <= a.H && tc.b0 + TB <= a.B && a.B % 32 == 0)) {
 #pragma unroll
                 for (int nb = 0; nb < NBLK; ++nb) {
                     float* const blk = a.out + ((((int64_t)(tc.k0 + wm * 32) * a.H + tc.h0 + wn) * a.W + tc.w0 + nb) * a.B + tc.b0);
