@@ -2025,7 +2025,7 @@ __device__ __forceinline__ void load_16_bytes_per_lane_to_lds(__amdgpu_buffer_rs
 template <int TW, int TH, int BRP = 3, int TBP = 64, int SWP = 1, bool T8 = false, int CTP = 32>
 __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs a) {
     using GEO = Bf16DirectFixed<TW, TH, BRP, TBP, SWP, CTP>;
-    static_assert(!T8 || CTP == 32, "direct bf16 kernel: the partly filled last slice is one of 32 channels");
+    static_assert(!T8 || CTP == 32 || TBP == 64, "direct bf16 kernel: a partly filled last slice of 64 channels with 64 images only");
     constexpr int TB = GEO::TB, KT = GEO::KT, CT = GEO::CT, BS = GEO::BS, BR = GEO::BR, WM = GEO::WM, NBLK = GEO::NBLK;
     constexpr int XS = GEO::XS, YS = GEO::YS, C8 = GEO::C8, F8 = GEO::F8, ROW = GEO::ROW, BUF = GEO::BUF_BYTES;
     constexpr int CTHREADS = GEO::WM * GEO::WN * 64;
@@ -2075,6 +2075,8 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
         // (T8: in a c-slice that reaches beyond C, a thread whose channels lie beyond C loads from beyond every descriptor's
         // range, 2^31 or more with the tap's offset and less than 2^32: zeros)
         const uint32_t fg0_tail = T8 && f_c8 * 8 >= a.C % CT ? 0x80000000u : fg0;
+        // (64-channel units: the thread's second item lies 32 channels further on)
+        const uint32_t fg0_tail2 = T8 && f_c8 * 8 + 32 >= a.C % CT ? 0x80000000u : fg0;
         // (32 images: chunk 4 i + pw is half pw % 2 of a position, lane L has its channel 16 (pw % 2) + L / 4)
         const uint32_t ivoff_tail = T8 && TB == 32 && 16 * (pw & 1) + (lane >> 2) >= a.C % CT ? 0x80000000u : ivoff;
         const uint32_t fl0 = (uint32_t)(uintptr_t)(lds + GEO::IMG_BYTES + (f_kl * F8 + f_c8) * 16);
@@ -2090,24 +2092,28 @@ __global__ void __launch_bounds__(512) conv_bf16_direct_kernel(const KernelArgs 
         auto issue = [&](int set) {
             const __amdgpu_buffer_rsrc_t rf = lu.flt(a);
             __amdgpu_buffer_rsrc_t ri = lu.img(a);
-            uint32_t fgo = fg0;
+            __amdgpu_buffer_rsrc_t ri2 = ri;          // 64-channel units: for the chunks of channels 8 pw + 32 ..
+            uint32_t fgo = fg0, fgo2 = fg0;
             uint32_t ivo = ivoff;
             if constexpr (T8) {
                 const int c_left = a.C - lu.c0;
                 if constexpr (TB == 64) {
-                    // every chunk of this staging wave holds channels 8 pw .. 8 pw + 7 of the slice (C8 == PW)
+                    // every chunk of this staging wave holds channels 8 pw .. 8 pw + 7 of the slice (32-channel units,
+                    // C8 == PW), or those and channels 8 pw + 32 .. in turns (64-channel units)
                     if (8 * pw >= c_left) ri = lu.empty(a.image);
+                    if (8 * pw + 32 >= c_left) ri2 = lu.empty(a.image);
                 } else {
                     if (c_left < CT) ivo = ivoff_tail;
                 }
-                if (c_left < CT) fgo = fg0_tail;
+                if (c_left < CT) fgo = fg0_tail, fgo2 = fg0_tail2;
             }
 #pragma unroll
             for (int i = 0; i < CPW; ++i)
-                load_16_bytes_per_lane_to_lds(ri, lds + boff_issue + (i * GEO::PW + pw) * 1024, ivo, isoff[i]);
+                load_16_bytes_per_lane_to_lds(C8 > GEO::PW && (i & 1) ? ri2 : ri, lds + boff_issue + (i * GEO::PW + pw) * 1024, ivo,
+                                              isoff[i]);
 #pragma unroll
             for (int i = 0; i < MAXF; ++i) {
-                const uint4 v = buf_load_u4(rf, fgo, fsoff[i]);
+                const uint4 v = buf_load_u4(rf, GQ > 1 && i == 1 ? fgo2 : fgo, fsoff[i]);
                 freg[set][i] = u32x4{v.x, v.y, v.z, v.w};
             }
             lu.next(a);
@@ -3176,6 +3182,18 @@ static int launch_kernel(KernelT kernel, bool& attr_done, int threads, const Ker
             }                                                                                                  \
     }
 
+// ... and for C a multiple of 8 but not of 64
+#define CACNN_DIRECT_1X1_C64_T8_VARIANT(NAME, UNIT_US, FIXED_US, TW, TH)                                        \
+    {                                                                                                          \
+        {NAME, 1, 2, 2, 1, Bf16DirectFixed<TW, TH, 1, 64, 1, 64>::NBLK, 64, TW, TH, 2, 1, Bf16DirectFixed<TW, TH, 1, 64, 1, 64>::MAXF, 1, 1, 1.0f, 64, 1,  \
+         1, Bf16DirectFixed<TW, TH, 1, 64, 1, 64>::YS, 1, 1, Bf16DirectFixed<TW, TH, 1, 64, 1, 64>::LDS_BYTES, UNIT_US, FIXED_US, 0, 2, 256, 1, 1},  \
+            [](const KernelArgs& a, int grid, size_t lds, void* stream) -> int {                               \
+                static bool attr_done = false;                                                                 \
+                if (!Bf16DirectFixed<TW, TH, 1, 64, 1, 64>::matches_host(a, true) || lds != (size_t)Bf16DirectFixed<TW, TH, 1, 64, 1, 64>::LDS_BYTES) return 1; \
+                return launch_kernel(conv_bf16_direct_kernel<TW, TH, 1, 64, 1, true, 64>, attr_done, 512, a, grid, lds, stream); \
+            }                                                                                                  \
+    }
+
 // the same for C a multiple of 8 but not of 32 (BR = 3 or 1): the staging waves zero-fill the last c-slice
 #define CACNN_DIRECT_T8_VARIANT(NAME, UNIT_US, FIXED_US, CALIB, TW, TH, BR)                                    \
     {                                                                                                          \
@@ -3353,6 +3371,7 @@ static const Variant g_variants[] = {
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w7h1 w2x2 m1n7 c32r1s1", 0.57f, 4.5f, 7, 1),
     CACNN_DIRECT_1X1_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r1s1", 0.35f, 4.2f, 2, 2),
     CACNN_DIRECT_1X1_C64_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c64r1s1", 0.61f, 4.2f, 2, 2),
+    CACNN_DIRECT_1X1_C64_T8_VARIANT("bf16 fxd k64 b64w2h2 w2x2 m1n4 c64r1s1 t8", 0.61f, 4.2f, 2, 2),
     CACNN_DIRECT_B32_VARIANT("bf16 fxd k64 b32w7h2 w2x2 m1n7 c32r3s1", 1.1f, 4.5f, 7, 3),
     CACNN_DIRECT_B32_VARIANT("bf16 fxd k64 b32w7h2 w2x2 m1n7 c32r1s1", 0.64f, 4.5f, 7, 1),
     CACNN_DIRECT_B32_T8_VARIANT("bf16 fxd k64 b32w7h2 w2x2 m1n7 c32r3s1 t8", 1.1f, 4.5f, 7, 3),

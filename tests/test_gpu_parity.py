@@ -118,6 +118,10 @@ RAGGED = [
     # ... and on tiles of 32 images (a chunk holds 16 channels: tails of 8 and 24 end inside one)
     ("fx_b32_tail", 32, 40, 72, 8, 3, 3, 3, 1, 1),
     ("fx_b32_tail_1x1", 96, 24, 64, 14, 2, 1, 1, 1, 1),
+    # ... and on 64-channel units (tails of 32, 8 and 56 channels; the last with a 3 x 1 filter, a tap at a time)
+    ("fx_c64_tail", 64, 96, 64, 4, 4, 1, 1, 1, 1),
+    ("fx_c64_tail8", 64, 72, 64, 4, 2, 1, 1, 2, 1),
+    ("fx_c64_tail56", 64, 120, 72, 3, 2, 3, 1, 1, 1),
     # filters other than 1 x 1 on the kernels compiled for 1 x 1 (a unit per tap and c-slice): 5 x 5; 3 x 2 with strides
     # (2, 3) and C = 16 mod 32
     ("fx_taps_5x5", 64, 64, 128, 5, 3, 5, 5, 1, 1),
@@ -215,7 +219,7 @@ def test_every_variant_runs_on_some_ragged_shape(env, dtype):
     fixed-geometry family) every variant launches at least once, the generic ones with at least two tilings."""
     cc, torch = env
     ran = {}
-    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_1x1_strides", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_overhang", "fx_b_overhang", "fx_s2", "fx_tail16", "fx_tail16_1x1", "fx_b32_tail", "fx_b32_tail_1x1", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx16_overhang", "fx_stem")
+    pick = ("ragged_all", "pipe_friendly", "pipe_b8", "fx_w7", "fx_1x1", "fx_1x1_strides", "fx_b32", "fx_b32_1x1", "fx_w2h2", "fx_overhang", "fx_b_overhang", "fx_s2", "fx_tail16", "fx_tail16_1x1", "fx_b32_tail", "fx_b32_tail_1x1", "fx_c64_tail", "fx_w4h4", "fx16_two_each", "fx16_1x1", "fx16_overhang", "fx_stem")
     for shape in RAGGED:
         if shape[0] in pick:
             run_every_variant(cc, torch, shape, dtype, ran)

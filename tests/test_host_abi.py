@@ -598,6 +598,7 @@ def test_which_shapes_the_fixed_geometry_kernels_accept():
     assert accepts(one, (64, 64, 64, 14, 14, 1, 1, 3, 2), 1)              # 1 x 1: any strides
     assert accepts(one, (64, 64, 64, 14, 14, 5, 7, 2, 1), 1)              # ... and any filter, a tap at a time
     assert not accepts("bf16 fxd k64 b64w2h2 w2x2 m1n4 c64r1s1", (64, 96, 64, 14, 14, 1, 1, 1, 1), 1)   # 64-channel units
+    assert accepts("bf16 fxd k64 b64w2h2 w2x2 m1n4 c64r1s1 t8", (64, 96, 64, 14, 14, 1, 1, 1, 1), 1)
     assert accepts("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1 s2", (64, 64, 64, 14, 14, 3, 3, 2, 2), 1)
     assert not accepts("bf16 fxd k64 b64w2h2 w2x2 m1n4 c32r3s1 s2", (64, 64, 64, 14, 14, 3, 3, 2, 1), 1)
     f16 = "f32 fxd16 k64 b8w2h7 w4x1 m1n7 c16r3s3"
