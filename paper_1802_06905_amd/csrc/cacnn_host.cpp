@@ -874,12 +874,12 @@ int plan_impl(const cacnn_problem* p, int dtype, const cacnn_machine* machine, c
     if (best.variant < 0 || best.n_wg * 8 < mach.num_cu || mostly_padding || f32_taps) {
         const bool use_lp = planner_uses_lp() && !((mostly_padding || f32_taps) && best.n_wg * 8 >= mach.num_cu);
         if (use_lp) best = Choice();
-        // a bf16 fixed-geometry kernel that competes is given a head start of a fifth of its time: on such layers its
+        // a bf16 fixed-geometry kernel that competes is given a head start of a quarter of its time: on such layers its
         // price was up to a quarter too high and the generic bf16 kernels' up to a quarter too low, and where the pick was
-        // wrong the generic kernel lost up to 1.5 x, the fixed-geometry one 1.1 x
+        // wrong the generic kernel lost up to 1.5 x, the fixed-geometry one 1.15 x
         const int fx_variant = best.variant;
         const double fx_cost = best.cost;
-        if (fx_variant >= 0 && dtype != CACNN_F32) best.cost *= 0.8;
+        if (fx_variant >= 0 && dtype != CACNN_F32) best.cost *= 0.75;
         const GpuLpTile lp = solve_gpu_lp(*p, dtype, mach);
         for (int vi = 0; vi < num_variants(); ++vi) {
             if (variant(vi).info.dtype != dtype) continue;
