@@ -616,11 +616,30 @@ ONE_BY_ONE_SHAPES = [
 ]
 
 
-def planner_compare(cc, torch, ci, np):
+def padded_shapes():
+    """36 seeded random bf16 layers on which a 64- or 32-image tile is partly empty: 8 to 40 images, output-channel
+    counts that no k-tile divides among them, 1 x 1 to 1 x 7 filters, strides 1 and 2."""
+    import random
+    rng = random.Random(5)
+    shapes = []
+    while len(shapes) < 36:
+        B = rng.choice([8, 16, 24, 32, 40])
+        C = rng.choice([32, 40, 64, 72, 96, 128, 192, 256, 512])
+        K = rng.choice([40, 64, 72, 96, 136, 192, 256, 512])
+        W = rng.choice([7, 14, 20, 28, 56])
+        R, S = rng.choice([(1, 1), (3, 3), (3, 3), (5, 5), (1, 7)])
+        st = rng.choice([1, 1, 2])
+        if 3e8 < B * C * K * W * W * R * S < 4e10:
+            shapes.append(("bf16", B, C, K, W, W, R, S, st, st))
+    return shapes
+
+
+def planner_compare(cc, torch, ci, np, padded=False):
     """The planner's pick against the fastest of all kernel variants (cacnn_tune) on PLANNER_SHAPES; the planner is the
     one the environment selects (CACNN_PLANNER unset: the calibrated cycle model; lp: the tile sized from the Section 5
     LP at the gfx950 budget).  One row per shape, then the geometric mean of the ratios.  On ONE_BY_ONE_SHAPES, which the
-    fixed-geometry kernels take, the row also has the fastest of the generic variants."""
+    fixed-geometry kernels take, the row also has the fastest of the generic variants.  padded: on padded_shapes()
+    instead, the summary over all of them."""
     mode = os.environ.get("CACNN_PLANNER", "model")
 
     def timed(fn, n=60, w=10):
@@ -636,7 +655,7 @@ def planner_compare(cc, torch, ci, np):
 
     ratios = []
     print("mode | dtype B C K W H R S sw sh | planner's variant [b_c b_r b_s] us | fastest variant [b_c b_r b_s] us | ratio")
-    for sh in PLANNER_SHAPES + ONE_BY_ONE_SHAPES:
+    for sh in (padded_shapes() if padded else PLANNER_SHAPES + ONE_BY_ONE_SHAPES):
         dtype, dims = sh[0], sh[1:]
         cfg = ci.custom("cmp", *dims, dtype=dtype, dist="normal", seed=3)
         _, _, d_img, d_flt, d_out = upload_config(torch, ci, np, cfg)
@@ -650,6 +669,8 @@ def planner_compare(cc, torch, ci, np):
             t_plan += 0.5 * timed(lambda: cc.cacnn_conv_forward_with_plan(dims, dt, plan, d_img, d_flt, d_out), n=30)
             t_tune += 0.5 * timed(lambda: cc.cacnn_conv_forward_with_plan(dims, dt, tuned, d_img, d_flt, d_out), n=30)
         generic = ""
+        if padded:
+            ratios.append(t_plan / t_tune)
         if sh in PLANNER_SHAPES:
             ratios.append(t_plan / t_tune)                # the summary line is about the generic kernels' cost model
         else:
@@ -702,6 +723,9 @@ def main():
     ap.add_argument("--planner-sweep", choices=["calibration", "test"], default=None,
                     help="time every kernel variant on the calibration layers (or on the --planner-compare layers) and print "
                          "the cost model's estimate next to each; no JSON line")
+    ap.add_argument("--planner-compare-padded", action="store_true",
+                    help="the same comparison on 36 seeded random bf16 layers with 8 to 40 images and output-channel counts "
+                         "that no tile divides; no JSON line")
     ap.add_argument("--planner-compare", action="store_true",
                     help="time the planner's pick against cacnn_tune's on sixteen mid-size and ragged layers and print a "
                          "table (the planner is the one CACNN_PLANNER selects); no JSON line")
@@ -725,8 +749,8 @@ def main():
     if args.planner_sweep:
         planner_sweep(cc, torch, ci, np, {"calibration": CALIBRATION_SHAPES, "test": PLANNER_SHAPES}[args.planner_sweep])
         return
-    if args.planner_compare:
-        planner_compare(cc, torch, ci, np)
+    if args.planner_compare or args.planner_compare_padded:
+        planner_compare(cc, torch, ci, np, padded=args.planner_compare_padded)
         return
     if args.workload == "p1":
         pcfg = ci.POOL_CONFIGS["p1"]
